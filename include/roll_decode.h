@@ -1,0 +1,255 @@
+/*
+ * roll_decode.h - C ABI of the rollout decode step for MI355X (gfx950).
+ *
+ * One decode step of an LLM rollout worker over a ragged, continuously
+ * refilled batch: paged grouped-query decode attention over per-sequence
+ * KV lengths, then temperature / top-p sampling that records the log-prob
+ * of the sampled token under the distribution it was drawn from.
+ *
+ * Where this sits in ROLL Flash (arXiv 2510.11345): Section 4.2 describes
+ * the serving worker's event loop, whose "step-wise inference" service
+ * advances the engine by one decode step over the running batch and whose
+ * ADD / ABORT commands make requests join and leave that batch at step
+ * granularity; Section 1 states that decoding is memory-bandwidth bound
+ * and that response lengths are long-tailed; Section 5.1 (queue
+ * scheduling) hands a freed slot the next prompt at once; Appendix A.1
+ * fixes the sampling parameters (temperature, top_p, top_k off, one beam)
+ * and uses the engine's token probability as the denominator of the
+ * truncated importance weight.  The paper treats the engine step as a
+ * black box; the definitions below are the standard ones it relies on.
+ *
+ * Conventions
+ *   - Every pointer is tagged HOST or DEVICE.  DEVICE pointers belong to
+ *     the one visible GPU; the caller owns them and the stream.
+ *   - Calls that take a stream enqueue work on it (a hipStream_t passed as
+ *     void*, NULL = the default stream) and return without waiting for it.
+ *   - Return value: ROLL_OK (0) or a negative roll_status.  On error no
+ *     output buffer has been written and no allocator state has changed.
+ *     roll_last_error() returns a thread-local description.
+ *   - bf16 = upper 16 bits of an IEEE-754 binary32, stored as uint16.
+ *
+ * KV page layout (both pools hold num_pages pages of page_size tokens for
+ * num_kv_heads heads of head_dim elements, bf16).  The layouts are chosen
+ * so that the matrix-core operands of the attention kernel are 16-byte
+ * contiguous per lane; the writer (roll_kv_append_tokens) pays the
+ * transposition once, the reader (every later decode step) never does.
+ *   K:  k_pages[page][h][d / 8][t][d % 8]     shape [N, Hkv, D/8, P, 8]
+ *   V:  v_pages[page][h][t / 8][d][t % 8]     shape [N, Hkv, P/8, D, 8]
+ * with t the token's position inside the page, d the head-dim index.
+ */
+#ifndef ROLL_DECODE_H
+#define ROLL_DECODE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum roll_status {
+    ROLL_OK = 0,
+    ROLL_ERR_INVALID_ARG = -1,  /* NULL / misaligned pointer, bad shape or parameter */
+    ROLL_ERR_NO_PAGES = -2,     /* free list cannot cover the request; state unchanged */
+    ROLL_ERR_SLOT_EMPTY = -3,   /* release of a slot that holds no sequence */
+    ROLL_ERR_SLOT_RANGE = -4,   /* slot index outside [0, num_slots) */
+    ROLL_ERR_SEQ_TOO_LONG = -5, /* sequence would need more than max_pages_per_seq pages */
+    ROLL_ERR_WORKSPACE = -6,    /* workspace NULL, misaligned or too small */
+    ROLL_ERR_HIP = -7           /* a HIP runtime call failed (message has the HIP error) */
+} roll_status;
+
+typedef enum roll_dtype { ROLL_BF16 = 0, ROLL_F32 = 1 } roll_dtype;
+
+/* HOST. Thread-local text of the last error on this thread ("" if none). */
+const char* roll_last_error(void);
+
+/* HOST. Library version, e.g. "0.1". */
+const char* roll_version(void);
+
+/* ------------------------------------------------------------------ */
+/* Page-table KV-cache allocator (Section 4.2: ADD enqueues a request, */
+/* ABORT or completion reclaims it; Section 5.1: a freed slot is given */
+/* the next prompt immediately).                                       */
+/* ------------------------------------------------------------------ */
+
+typedef struct roll_kv_pool roll_kv_pool;
+
+typedef struct roll_kv_config {
+    int32_t num_pages;          /* physical pages in each of k_pages / v_pages */
+    int32_t page_size;          /* tokens per page: 16, 32 or 64 */
+    int32_t num_slots;          /* rows of the running batch (B) */
+    int32_t max_pages_per_seq;  /* row length of page_table */
+} roll_kv_config;
+
+/*
+ * Create a pool.  The authoritative state (free-page stack, per-slot page
+ * lists and lengths) lives in host memory owned by the pool.
+ *   page_table_dev  DEVICE int32 [num_slots, max_pages_per_seq], borrowed for
+ *                   the pool's lifetime; the pool fills it with -1 on the
+ *                   first roll_kv_commit and keeps it in step afterwards.
+ *   seq_lens_dev    DEVICE int32 [num_slots], borrowed likewise.
+ * Both may be NULL together: the pool is then host-only (allocator logic,
+ * schedulers, tests) and roll_kv_commit is an error.
+ * Free pages are handed out as a LIFO stack whose initial pop order is
+ * 0, 1, 2, ...; no result of the decode step depends on that order.
+ */
+int roll_kv_pool_create(roll_kv_pool** pool, const roll_kv_config* cfg,
+                        int32_t* page_table_dev, int32_t* seq_lens_dev);
+int roll_kv_pool_destroy(roll_kv_pool* pool);
+
+/*
+ * HOST state only.  Grow slot's sequence by n_tokens (>= 1), taking pages
+ * from the free stack when a page boundary is crossed.  A slot with length
+ * 0 becomes live (ADD / refill).  All-or-nothing: on ROLL_ERR_NO_PAGES or
+ * ROLL_ERR_SEQ_TOO_LONG nothing has changed.
+ */
+int roll_kv_alloc(roll_kv_pool* pool, int32_t slot, int32_t n_tokens);
+
+/*
+ * HOST state only.  Finish or ABORT: every page of the slot goes back on
+ * the free stack and its length becomes 0 (the KV of an aborted request is
+ * discarded and recomputed later, Section 4.2).  ROLL_ERR_SLOT_EMPTY if the
+ * slot holds nothing.
+ */
+int roll_kv_release(roll_kv_pool* pool, int32_t slot);
+
+/*
+ * Publish every change made since the last commit to page_table_dev and
+ * seq_lens_dev, as one small host-to-device copy plus one scatter kernel
+ * enqueued on stream.  Does not wait for the stream.  Work enqueued on the
+ * same stream afterwards sees the new tables.
+ */
+int roll_kv_commit(roll_kv_pool* pool, void* stream);
+
+/* HOST introspection. */
+int roll_kv_free_pages(const roll_kv_pool* pool);               /* count, or < 0 */
+int roll_kv_seq_len(const roll_kv_pool* pool, int32_t slot);    /* tokens, or < 0 */
+/* Copies up to cap page ids of the slot to pages_out (HOST); returns the
+ * number of pages the slot owns, or < 0. */
+int roll_kv_slot_pages(const roll_kv_pool* pool, int32_t slot,
+                       int32_t* pages_out, int32_t cap);
+
+/*
+ * Write the K/V vectors of n_tokens tokens into the paged pools in the page
+ * layout given at the top of this header.  Token i goes to position
+ * positions[i] of the sequence in slot slots[i]; the page is looked up in
+ * page_table on the device, so a roll_kv_commit covering that position must
+ * precede this call on the same stream.  The decode step appends one token
+ * per live row (positions[i] = seq_len - 1); a refilled prompt writes all
+ * its tokens with one call.
+ *   k_new, v_new   DEVICE bf16 [n_tokens, num_kv_heads, head_dim], row-major
+ *   slots          DEVICE int32 [n_tokens]
+ *   positions      DEVICE int32 [n_tokens]   (entries < 0 are skipped)
+ *   k_pages,v_pages DEVICE bf16 pools
+ *   page_table     DEVICE int32 [num_slots, max_pages_per_seq]
+ */
+int roll_kv_append_tokens(const void* k_new, const void* v_new,
+                          const int32_t* slots, const int32_t* positions,
+                          int32_t n_tokens, void* k_pages, void* v_pages,
+                          const int32_t* page_table, int32_t max_pages_per_seq,
+                          int32_t num_pages, int32_t page_size,
+                          int32_t num_kv_heads, int32_t head_dim, void* stream);
+
+/* ------------------------------------------------------------------ */
+/* Paged GQA decode attention (the bandwidth-bound part of the step,   */
+/* Section 1).  For every row b with L = seq_lens[b] >= 1 and query    */
+/* head h (KV head h / (Hq/Hkv)):                                      */
+/*   s_j = scale * <q[b,h,:], K_j>,  p = softmax_j(s),  j in [0, L)    */
+/*   out[b,h,:] = sum_j p_j V_j                                        */
+/* seq_lens counts the token being decoded: its K/V is appended before */
+/* the call, so no mask is needed.  Rows with L == 0 give zeros.       */
+/* ------------------------------------------------------------------ */
+
+typedef struct roll_attn_desc {
+    int32_t batch;              /* B rows of q / page_table / seq_lens / out */
+    int32_t num_q_heads;        /* Hq */
+    int32_t num_kv_heads;       /* Hkv; Hq % Hkv == 0 and Hq / Hkv <= 16 */
+    int32_t head_dim;           /* D: 64 or 128 */
+    int32_t page_size;          /* P: 16, 32 or 64 */
+    int32_t max_pages_per_seq;  /* row length of page_table */
+    int32_t num_pages;          /* pages in each pool (bounds the page ids) */
+    int32_t out_dtype;          /* ROLL_BF16 or ROLL_F32 */
+    float softmax_scale;        /* 0 => 1 / sqrt(D) */
+    int32_t chunk_tokens;       /* split-K chunk; 0 => library default; multiple of 128 */
+    int64_t max_total_tokens;   /* upper bound on sum of seq_lens; 0 => B * max_pages * P */
+    void* ev_main_begin;        /* optional hipEvent_t recorded before / after the    */
+    void* ev_main_end;          /* split-K attention kernel (profiling); NULL = none  */
+} roll_attn_desc;
+
+/* HOST. Bytes of DEVICE workspace roll_decode_attn needs for this desc. */
+size_t roll_decode_attn_workspace_bytes(const roll_attn_desc* desc);
+
+/*
+ *   q           DEVICE bf16 [B, Hq, D]
+ *   k_pages     DEVICE bf16 [num_pages, Hkv, D/8, P, 8]
+ *   v_pages     DEVICE bf16 [num_pages, Hkv, P/8, D, 8]
+ *   page_table  DEVICE int32 [B, max_pages_per_seq]; entries past a row's
+ *               last page are never read
+ *   seq_lens    DEVICE int32 [B]; values outside [0, max_pages*P] are
+ *               clamped into that range
+ *   out         DEVICE [B, Hq, D] of out_dtype
+ *   workspace   DEVICE, 256-byte aligned, >= roll_decode_attn_workspace_bytes
+ * All pointers 16-byte aligned.  Enqueues three kernels on stream: work-list
+ * build, split-K partial attention, merge.  Two calls that share a workspace
+ * must be ordered on one stream.
+ */
+int roll_decode_attn(const void* q, const void* k_pages, const void* v_pages,
+                     const int32_t* page_table, const int32_t* seq_lens,
+                     void* out, const roll_attn_desc* desc,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------ */
+/* Sampling with log-prob recording (Appendix A.1).  Per row r:        */
+/*   z_i = logits[r,i] / temperature                                   */
+/*   kept = all i                       if top_p >= 1                  */
+/*        = { i : logits[r,i] >= x_cut } otherwise, x_cut = the first  */
+/*          value, going down the distinct logit values, at which the  */
+/*          mass of softmax(z) on values >= it reaches top_p           */
+/*   u_i  = uniform from Philox4x32-10, key = philox_seed,             */
+/*          counter = (i >> 2, row_id, step_lo, step_hi), word i & 3,  */
+/*          u = ((word >> 9) + 0.5) * 2^-23                            */
+/*   token   = argmax_{i in kept} z_i - log(-log u_i)   (lowest i wins */
+/*             exact ties)                                             */
+/*   logprob = z_token - log sum_{i in kept} exp(z_i)                  */
+/* At temperature 1 and top_p 1 (the setting the paper enforces) the   */
+/* log-prob is log_softmax(logits)[token], the behaviour-policy        */
+/* probability that the truncated importance weight divides by.        */
+/* ------------------------------------------------------------------ */
+
+typedef struct roll_sample_desc {
+    int32_t batch;          /* B rows */
+    int32_t vocab;          /* V */
+    int64_t row_stride;     /* elements between rows of logits (>= V) */
+    int32_t logits_dtype;   /* ROLL_BF16 or ROLL_F32 */
+    int32_t reserved;
+    const int32_t* row_ids; /* DEVICE int32 [B] Philox row ids, or NULL for 0..B-1 */
+} roll_sample_desc;
+
+size_t roll_sample_logprob_workspace_bytes(const roll_sample_desc* desc);
+
+/*
+ *   logits       DEVICE [B, row_stride] bf16 or fp32, 16-byte aligned rows
+ *   temperature  > 0
+ *   top_p        in (0, 1]
+ *   tokens_out   DEVICE int32 [B]
+ *   logprob_out  DEVICE fp32 [B]
+ */
+int roll_sample_logprob(const void* logits, float temperature, float top_p,
+                        uint64_t philox_seed, uint64_t step,
+                        int32_t* tokens_out, float* logprob_out,
+                        const roll_sample_desc* desc,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------ */
+/* Profiling helpers: HIP events the benchmark hands to roll_attn_desc. */
+/* ------------------------------------------------------------------ */
+int roll_prof_event_create(void** event);
+int roll_prof_event_destroy(void* event);
+int roll_prof_event_record(void* event, void* stream);
+/* Waits for end, then writes the milliseconds between the two events. */
+int roll_prof_event_elapsed_ms(void* begin, void* end, float* ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ROLL_DECODE_H */
