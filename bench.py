@@ -1,0 +1,158 @@
+#!/usr/bin/env python3
+"""Benchmark of the rollout decode step on one MI355X.
+
+One step = the whole hot path over one batch: allocator (+1 token per row, one commit),
+K/V append, paged GQA decode attention (work list, split-K partial, merge) and
+temperature / top-p sampling with log-prob recording.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c2] [--chunk C]
+"""
+from __future__ import annotations
+
+import argparse
+import glob
+import json
+import os
+import re
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published peak
+
+
+def profiled_traffic(workload: str):
+    """HBM bytes per launch measured with rocprofv3 --pmc, if a summary under profiles/ states it
+    as a line `traffic_bytes_per_launch[<workload>]: <number>`."""
+    pat = re.compile(r"traffic_bytes_per_launch\[" + re.escape(workload) + r"\]:\s*([0-9.eE+]+)")
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.txt")) +
+                       glob.glob(os.path.join(ROOT, "profiles", "*.md"))):
+        m = pat.search(open(path).read())
+        if m:
+            return float(m.group(1))
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="c2", choices=["c2", "c3", "c5"])
+    ap.add_argument("--chunk", type=int, default=0, help="split-K chunk tokens (0 = library default)")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--oracle-rows", type=int, default=16)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU: rollout decode is data-parallel over sequences with "
+              "no exchange between GPUs, so --gpus N > 1 is not implemented; run with --gpus 1.",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2510_11345_amd import binding as rb
+    from paper_2510_11345_amd import workloads as wl
+    from paper_2510_11345_amd.harness import DecodeBatch
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    rb.lib()  # fail loudly if the HIP library is missing
+    cfg = wl.CONFIGS[args.config]
+    K, W = args.steps, args.warmup
+    lengths = wl.draw_lengths(cfg.lengths, cfg.batch, args.seed, cfg.max_len).astype(np.int64)
+    # seq_lens count the token being decoded: start one short, every step appends one token
+    batch = DecodeBatch(cfg, args.seed, lengths - 1, headroom_tokens=K + W + 2,
+                        chunk_tokens=args.chunk, profile_events=False)
+    logits = wl.make_logits(cfg, args.seed, "cuda")
+    torch.cuda.synchronize()
+
+    step_index = 0
+    for _ in range(W):
+        batch.step(logits, step_index)
+        step_index += 1
+    torch.cuda.synchronize()
+    batch.ev_spare = [(rb.ProfEvent(), rb.ProfEvent()) for _ in range(K)]
+    batch.profile_events = True
+    t0 = time.perf_counter()
+    for _ in range(K):
+        batch.step(logits, step_index)
+        step_index += 1
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    batch.profile_events = False
+
+    ms_per_step = (t1 - t0) * 1e3 / K
+    beta = cfg.kv_bytes_per_token
+    kern_ms = [a.elapsed_ms(b) for a, b, _ in batch.ev_pairs]
+    kv_bytes = [beta * tot for _, _, tot in batch.ev_pairs]
+    avg_kern_ms = float(np.mean(kern_ms))
+    avg_kv_bytes = float(np.mean(kv_bytes))
+    achieved = avg_kv_bytes / (avg_kern_ms * 1e-3) / 1e9
+    workload = (f"{cfg.name}: B={cfg.batch} Hq={cfg.num_q_heads} Hkv={cfg.num_kv_heads} D={cfg.head_dim} "
+                f"P={cfg.page_size} lengths={cfg.lengths} V={cfg.vocab} T={cfg.temperature} top_p={cfg.top_p}")
+
+    result = {
+        "metric": "decode tokens/s (one attention layer + sampling per step)",
+        "value": cfg.batch / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": workload, "seed": args.seed, "sum_seq_lens": int(batch.total_tokens()),
+                   "chunk_tokens": args.chunk or "default"},
+        "kv_read_GBps": achieved,
+        "kv_read_frac_of_peak": achieved / HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "attn_partial", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": profiled_traffic(cfg.name),
+                     "algorithmic_bytes_per_launch": avg_kv_bytes, "avg_launch_ms": avg_kern_ms},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        n = min(args.oracle_rows, cfg.batch)
+        rows = [int(r) for r in np.linspace(0, cfg.batch - 1, n).round().astype(int)]
+        rows = sorted(set(rows))
+        q, k, v, table, lens = batch.gather_rows(rows)
+        last_step = step_index - 1
+        gpu_out = batch.out[torch.tensor(rows, device="cuda")].double().cpu().numpy()
+        gpu_tok = batch.tokens.cpu().numpy()[rows]
+        gpu_lp = batch.logprob.double().cpu().numpy()[rows]
+        lg_host = wl.logits_numpy(logits[torch.tensor(rows, device="cuda")])
+        c0 = time.perf_counter()
+        ref_out, threads = oracle.decode_attn(q, k, v, table, lens, cfg.num_q_heads, cfg.num_kv_heads,
+                                              cfg.head_dim, cfg.page_size, return_threads=True)
+        c1 = time.perf_counter()
+        ref = oracle.sample_logprob(lg_host, cfg.temperature, cfg.top_p, args.seed, last_step, row_ids=rows)
+        c2 = time.perf_counter()
+        mism = int((gpu_tok != ref["tokens"]).sum())
+        result["cpu_baseline"] = {
+            "value": len(rows) / (c2 - c0), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{len(rows)} of {cfg.batch} rows (evenly spaced), {int(lens.sum())} KV tokens: "
+                      f"attention {c1 - c0:.2f} s + sampling {c2 - c1:.2f} s",
+        }
+        result["parity_on_sample"] = {
+            "attn_max_abs_err_bf16_out": float(np.abs(gpu_out - ref_out).max()),
+            "logprob_max_abs_err": float(np.abs(gpu_lp - ref["logprob"])[gpu_tok == ref["tokens"]].max())
+            if mism < len(rows) else None,
+            "token_mismatches": mism,
+            "near_ties_below_1e-5": int((ref["gap"] < 1e-5).sum()),
+        }
+    batch.close()
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -106,6 +106,15 @@ int roll_kv_pool_destroy(roll_kv_pool* pool);
 int roll_kv_alloc(roll_kv_pool* pool, int32_t slot, int32_t n_tokens);
 
 /*
+ * HOST state only.  roll_kv_alloc for count distinct slots in one call (the
+ * per-step "every live row grows by one token").  slots and n_tokens are HOST
+ * arrays of count entries.  All-or-nothing over the whole batch: on any error
+ * (a repeated slot is ROLL_ERR_INVALID_ARG) nothing has changed.
+ */
+int roll_kv_alloc_batch(roll_kv_pool* pool, const int32_t* slots,
+                        const int32_t* n_tokens, int32_t count);
+
+/*
  * HOST state only.  Finish or ABORT: every page of the slot goes back on
  * the free stack and its length becomes 0 (the KV of an aborted request is
  * discarded and recomputed later, Section 4.2).  ROLL_ERR_SLOT_EMPTY if the
@@ -138,13 +147,16 @@ int roll_kv_slot_pages(const roll_kv_pool* pool, int32_t slot,
  * per live row (positions[i] = seq_len - 1); a refilled prompt writes all
  * its tokens with one call.
  *   k_new, v_new   DEVICE bf16 [n_tokens, num_kv_heads, head_dim], row-major
- *   slots          DEVICE int32 [n_tokens]
- *   positions      DEVICE int32 [n_tokens]   (entries < 0 are skipped)
+ *   slots          DEVICE int32 [n_tokens], or NULL for slot i = i
+ *   positions      DEVICE int32 [n_tokens] (entries < 0 are skipped), or NULL
+ *                  for "the last token of the slot": seq_lens[slot] - 1
+ *   seq_lens       DEVICE int32 [num_slots]; read only when positions is NULL
  *   k_pages,v_pages DEVICE bf16 pools
  *   page_table     DEVICE int32 [num_slots, max_pages_per_seq]
  */
 int roll_kv_append_tokens(const void* k_new, const void* v_new,
                           const int32_t* slots, const int32_t* positions,
+                          const int32_t* seq_lens,
                           int32_t n_tokens, void* k_pages, void* v_pages,
                           const int32_t* page_table, int32_t max_pages_per_seq,
                           int32_t num_pages, int32_t page_size,

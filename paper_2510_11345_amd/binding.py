@@ -1,0 +1,286 @@
+"""ctypes binding of libroll_decode.so: same names as the C ABI, marshalling only.
+
+Every function takes torch tensors that already live on the GPU (PyTorch is
+used for device memory and streams only), passes their pointers and the
+current stream to the library and raises ``RollError`` on a non-zero status.
+There is no fallback: if the library is missing or a kernel cannot run, the
+call fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libroll_decode.so")
+
+ROLL_BF16, ROLL_F32 = 0, 1
+
+EXPORTS = [
+    "roll_last_error", "roll_version",
+    "roll_kv_pool_create", "roll_kv_pool_destroy", "roll_kv_alloc", "roll_kv_alloc_batch", "roll_kv_release",
+    "roll_kv_commit", "roll_kv_free_pages", "roll_kv_seq_len", "roll_kv_slot_pages",
+    "roll_kv_append_tokens",
+    "roll_decode_attn_workspace_bytes", "roll_decode_attn",
+    "roll_sample_logprob_workspace_bytes", "roll_sample_logprob",
+    "roll_prof_event_create", "roll_prof_event_destroy", "roll_prof_event_record",
+    "roll_prof_event_elapsed_ms",
+]
+
+
+class RollError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"roll status {status}: {message}")
+        self.status = status
+
+
+class KvConfig(C.Structure):
+    _fields_ = [("num_pages", C.c_int32), ("page_size", C.c_int32), ("num_slots", C.c_int32),
+                ("max_pages_per_seq", C.c_int32)]
+
+
+class AttnDesc(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("page_size", C.c_int32), ("max_pages_per_seq", C.c_int32),
+                ("num_pages", C.c_int32), ("out_dtype", C.c_int32), ("softmax_scale", C.c_float),
+                ("chunk_tokens", C.c_int32), ("max_total_tokens", C.c_int64),
+                ("ev_main_begin", C.c_void_p), ("ev_main_end", C.c_void_p)]
+
+
+class SampleDesc(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("vocab", C.c_int32), ("row_stride", C.c_int64),
+                ("logits_dtype", C.c_int32), ("reserved", C.c_int32), ("row_ids", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    """Load the built library (build it first with ``python -m paper_2510_11345_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: run `python -m paper_2510_11345_amd.build` "
+                "(or __graft_entry__.build()) first")
+        L = C.CDLL(LIB_PATH)
+        L.roll_last_error.restype = C.c_char_p
+        L.roll_version.restype = C.c_char_p
+        L.roll_decode_attn_workspace_bytes.restype = C.c_size_t
+        L.roll_decode_attn_workspace_bytes.argtypes = [C.POINTER(AttnDesc)]
+        L.roll_sample_logprob_workspace_bytes.restype = C.c_size_t
+        L.roll_sample_logprob_workspace_bytes.argtypes = [C.POINTER(SampleDesc)]
+        L.roll_kv_pool_create.argtypes = [C.POINTER(C.c_void_p), C.POINTER(KvConfig), C.c_void_p, C.c_void_p]
+        L.roll_kv_pool_destroy.argtypes = [C.c_void_p]
+        L.roll_kv_alloc.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+        L.roll_kv_alloc_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]
+        L.roll_kv_release.argtypes = [C.c_void_p, C.c_int32]
+        L.roll_kv_commit.argtypes = [C.c_void_p, C.c_void_p]
+        L.roll_kv_free_pages.argtypes = [C.c_void_p]
+        L.roll_kv_seq_len.argtypes = [C.c_void_p, C.c_int32]
+        L.roll_kv_slot_pages.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_int32]
+        L.roll_kv_append_tokens.argtypes = [C.c_void_p] * 5 + [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p] + \
+            [C.c_int32] * 5 + [C.c_void_p]
+        L.roll_decode_attn.argtypes = [C.c_void_p] * 6 + [C.POINTER(AttnDesc), C.c_void_p, C.c_size_t, C.c_void_p]
+        L.roll_sample_logprob.argtypes = [C.c_void_p, C.c_float, C.c_float, C.c_uint64, C.c_uint64,
+                                          C.c_void_p, C.c_void_p, C.POINTER(SampleDesc), C.c_void_p,
+                                          C.c_size_t, C.c_void_p]
+        L.roll_prof_event_create.argtypes = [C.POINTER(C.c_void_p)]
+        L.roll_prof_event_destroy.argtypes = [C.c_void_p]
+        L.roll_prof_event_record.argtypes = [C.c_void_p, C.c_void_p]
+        L.roll_prof_event_elapsed_ms.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_float)]
+        _lib = L
+    return _lib
+
+
+def _check(status: int) -> int:
+    if status < 0:
+        raise RollError(status, lib().roll_last_error().decode())
+    return status
+
+
+def _stream() -> Optional[int]:
+    if not torch.cuda.is_available():  # host-only use (allocator logic); GPU calls fail in the library
+        return None
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: Optional[torch.Tensor], dtype=None) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("expected a CUDA (ROCm) tensor")
+    if not t.is_contiguous():
+        raise ValueError("expected a contiguous tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"expected dtype {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def roll_version() -> str:
+    return lib().roll_version().decode()
+
+
+# ----------------------------------------------------------------------------
+# allocator
+# ----------------------------------------------------------------------------
+class KvPool:
+    """Owner of a roll_kv_pool handle.  page_table / seq_lens are device int32 tensors
+    (or both None for a host-only pool)."""
+
+    def __init__(self, num_pages: int, page_size: int, num_slots: int, max_pages_per_seq: int,
+                 page_table: Optional[torch.Tensor] = None, seq_lens: Optional[torch.Tensor] = None):
+        self.cfg = KvConfig(num_pages, page_size, num_slots, max_pages_per_seq)
+        self.page_table, self.seq_lens = page_table, seq_lens
+        if page_table is not None:
+            assert tuple(page_table.shape) == (num_slots, max_pages_per_seq)
+            assert tuple(seq_lens.shape) == (num_slots,)
+        self._h = C.c_void_p()
+        _check(lib().roll_kv_pool_create(C.byref(self._h), C.byref(self.cfg),
+                                         _dev(page_table, torch.int32), _dev(seq_lens, torch.int32)))
+
+    def close(self):
+        if self._h:
+            _check(lib().roll_kv_pool_destroy(self._h))
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def roll_kv_alloc(pool: KvPool, slot: int, n_tokens: int) -> None:
+    _check(lib().roll_kv_alloc(pool._h, slot, n_tokens))
+
+
+def roll_kv_alloc_batch(pool: KvPool, slots, n_tokens) -> None:
+    """slots, n_tokens: host int32 numpy arrays of equal length."""
+    import numpy as np
+    slots = np.ascontiguousarray(slots, dtype=np.int32)
+    n_tokens = np.ascontiguousarray(n_tokens, dtype=np.int32)
+    assert slots.shape == n_tokens.shape and slots.ndim == 1
+    _check(lib().roll_kv_alloc_batch(pool._h, slots.ctypes.data, n_tokens.ctypes.data, len(slots)))
+
+
+def roll_kv_release(pool: KvPool, slot: int) -> None:
+    _check(lib().roll_kv_release(pool._h, slot))
+
+
+def roll_kv_commit(pool: KvPool) -> None:
+    _check(lib().roll_kv_commit(pool._h, _stream()))
+
+
+def roll_kv_free_pages(pool: KvPool) -> int:
+    return _check(lib().roll_kv_free_pages(pool._h))
+
+
+def roll_kv_seq_len(pool: KvPool, slot: int) -> int:
+    return _check(lib().roll_kv_seq_len(pool._h, slot))
+
+
+def roll_kv_slot_pages(pool: KvPool, slot: int) -> list:
+    n = _check(lib().roll_kv_slot_pages(pool._h, slot, None, 0))
+    buf = (C.c_int32 * max(n, 1))()
+    _check(lib().roll_kv_slot_pages(pool._h, slot, buf, n))
+    return list(buf[:n])
+
+
+def roll_kv_append_tokens(k_new, v_new, slots, positions, seq_lens, k_pages, v_pages, page_table,
+                          page_size: int) -> None:
+    """slots None: token i belongs to slot i; positions None: last token of the slot."""
+    n, Hkv, D = k_new.shape
+    _check(lib().roll_kv_append_tokens(
+        _dev(k_new, torch.bfloat16), _dev(v_new, torch.bfloat16), _dev(slots, torch.int32),
+        _dev(positions, torch.int32), _dev(seq_lens, torch.int32), n,
+        _dev(k_pages, torch.bfloat16), _dev(v_pages, torch.bfloat16),
+        _dev(page_table, torch.int32), page_table.shape[1], k_pages.shape[0], page_size, Hkv, D,
+        _stream()))
+
+
+# ----------------------------------------------------------------------------
+# attention
+# ----------------------------------------------------------------------------
+def attn_desc(q, k_pages, page_table, page_size, out_dtype=torch.bfloat16, softmax_scale=0.0,
+              chunk_tokens=0, max_total_tokens=0, ev_begin=None, ev_end=None) -> AttnDesc:
+    B, Hq, D = q.shape
+    return AttnDesc(B, Hq, k_pages.shape[1], D, page_size, page_table.shape[1], k_pages.shape[0],
+                    ROLL_F32 if out_dtype == torch.float32 else ROLL_BF16, softmax_scale,
+                    chunk_tokens, max_total_tokens, ev_begin, ev_end)
+
+
+def roll_decode_attn_workspace_bytes(desc: AttnDesc) -> int:
+    n = lib().roll_decode_attn_workspace_bytes(C.byref(desc))
+    if n == 0:
+        raise RollError(-1, lib().roll_last_error().decode())
+    return n
+
+
+def roll_decode_attn(q, k_pages, v_pages, page_table, seq_lens, out, desc: AttnDesc,
+                     workspace: torch.Tensor) -> None:
+    _check(lib().roll_decode_attn(
+        _dev(q, torch.bfloat16), _dev(k_pages, torch.bfloat16), _dev(v_pages, torch.bfloat16),
+        _dev(page_table, torch.int32), _dev(seq_lens, torch.int32), _dev(out), C.byref(desc),
+        _dev(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+# ----------------------------------------------------------------------------
+# sampling
+# ----------------------------------------------------------------------------
+def sample_desc(logits, row_ids=None) -> SampleDesc:
+    B, V = logits.shape
+    dt = ROLL_BF16 if logits.dtype == torch.bfloat16 else ROLL_F32
+    if logits.dtype not in (torch.bfloat16, torch.float32):
+        raise ValueError("logits must be bf16 or fp32")
+    if logits.stride(1) != 1:
+        raise ValueError("logits rows must be dense")
+    return SampleDesc(B, V, logits.stride(0), dt, 0, _dev(row_ids, torch.int32))
+
+
+def roll_sample_logprob_workspace_bytes(desc: SampleDesc) -> int:
+    n = lib().roll_sample_logprob_workspace_bytes(C.byref(desc))
+    if n == 0:
+        raise RollError(-1, lib().roll_last_error().decode())
+    return n
+
+
+def roll_sample_logprob(logits, temperature, top_p, philox_seed, step, tokens_out, logprob_out,
+                        desc: SampleDesc, workspace: Optional[torch.Tensor] = None) -> None:
+    if not logits.is_cuda:
+        raise ValueError("expected a CUDA (ROCm) tensor")
+    _check(lib().roll_sample_logprob(
+        logits.data_ptr(), temperature, top_p, philox_seed, step, _dev(tokens_out, torch.int32),
+        _dev(logprob_out, torch.float32), C.byref(desc), _dev(workspace),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream()))
+
+
+# ----------------------------------------------------------------------------
+# profiling events
+# ----------------------------------------------------------------------------
+class ProfEvent:
+    def __init__(self):
+        self._h = C.c_void_p()
+        _check(lib().roll_prof_event_create(C.byref(self._h)))
+
+    @property
+    def handle(self):
+        return self._h
+
+    def record(self):
+        _check(lib().roll_prof_event_record(self._h, _stream()))
+
+    def elapsed_ms(self, end: "ProfEvent") -> float:
+        ms = C.c_float()
+        _check(lib().roll_prof_event_elapsed_ms(self._h, end._h, C.byref(ms)))
+        return ms.value
+
+    def __del__(self):
+        try:
+            if self._h:
+                lib().roll_prof_event_destroy(self._h)
+        except Exception:
+            pass

@@ -1,0 +1,476 @@
+// Temperature / top-p sampling with log-prob recording for gfx950.
+//
+// ROLL Flash (arXiv 2510.11345) Appendix A.1: rollout samples with a given
+// temperature and top_p (top_k off, one beam) and the engine's probability of
+// the sampled token is the denominator of the truncated importance weight, so
+// the step must return, next to each token, its log-prob under the
+// distribution it was actually drawn from.
+//
+// One workgroup of 1024 threads per row.
+//   top_p == 1: ONE sweep over the row computes the online (max, sum-exp) for
+//     the log-sum-exp and runs the Gumbel-max race.
+//   top_p <  1: sweep 1 finds max z; a radix select over the order-preserving
+//     integer key of the logit (10 bits per level: 2 levels for bf16, 4 for
+//     fp32) finds the cut value x_cut, each level being one sweep that adds
+//     exp(z - max) in 2^-40 fixed point (integer adds commute, so the cut does
+//     not depend on thread timing) into an LDS histogram followed by a
+//     block-wide suffix scan; the last sweep runs the race over logits >= x_cut.
+//
+// The Gumbel-max race is exact and cheap: g(u) = -log(-log u) <= -log(1 - u)
+// because -log u >= 1 - u, so an entry can only win if z + (-log(1 - u)) reaches
+// the best exact value seen so far by its wave.  That test costs one hardware
+// log2 per entry; the few entries that pass are evaluated in fp64 (division by
+// the temperature and both logs), which is the arithmetic the definition is
+// stated in.  The running best is shared across the wave whenever it moves.
+#include <cfloat>
+#include <cmath>
+
+#include "common.h"
+
+namespace {
+
+constexpr int kThreads = 1024;
+constexpr int kWavesPerBlock = kThreads / 64;
+constexpr int kRadixBits = 10;
+constexpr int kBins = 1 << kRadixBits;
+constexpr float kLog2e = 1.44269504088896340736f;
+constexpr float kLn2 = 0.69314718055994530942f;
+
+struct SampleParams {
+    int32_t V;
+    int64_t row_stride;
+    float inv_t;
+    double temperature;
+    float top_p;
+    uint32_t seed_lo, seed_hi, step_lo, step_hi;
+};
+
+// ---- Philox4x32-10 (Salmon et al., SC'11) ----------------------------------
+struct Philox4 { uint32_t w[4]; };
+
+__device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                 uint32_t k0, uint32_t k1) {
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        const uint32_t hi_a = __umulhi(0xD2511F53u, c0), lo_a = 0xD2511F53u * c0;
+        const uint32_t hi_b = __umulhi(0xCD9E8D57u, c2), lo_b = 0xCD9E8D57u * c2;
+        const uint32_t n0 = hi_b ^ c1 ^ k0;
+        const uint32_t n2 = hi_a ^ c3 ^ k1;
+        c0 = n0; c1 = lo_b; c2 = n2; c3 = lo_a;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return Philox4{{c0, c1, c2, c3}};
+}
+
+// ---- element access ---------------------------------------------------------
+template <typename T> struct Elem;
+template <> struct Elem<uint16_t> {  // bf16 bit patterns
+    static constexpr int kVec = 8;
+    static constexpr int kKeyBits = 16;
+    __device__ static float widen(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+    __device__ static void unpack(const uint4& v, float (&x)[8]) {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            x[2 * j] = __uint_as_float(w[j] << 16);
+            x[2 * j + 1] = __uint_as_float(w[j] & 0xFFFF0000u);
+        }
+    }
+};
+template <> struct Elem<float> {
+    static constexpr int kVec = 4;
+    static constexpr int kKeyBits = 32;
+    __device__ static float widen(float f) { return f; }
+    __device__ static void unpack(const uint4& v, float (&x)[4]) {
+        x[0] = __uint_as_float(v.x); x[1] = __uint_as_float(v.y);
+        x[2] = __uint_as_float(v.z); x[3] = __uint_as_float(v.w);
+    }
+};
+
+// Order-preserving key: larger float <=> larger unsigned key (-0 < +0, harmless).
+__device__ __forceinline__ uint32_t order_key(float x) {
+    const uint32_t b = __float_as_uint(x);
+    return b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+}
+__device__ __forceinline__ float key_to_float(uint32_t k) {
+    const uint32_t b = (k >> 31) ? (k ^ 0x80000000u) : ~k;
+    return __uint_as_float(b);
+}
+
+// Calls f.run<N>(i0, x, active) for every aligned vector of the row and f.run<1> for the
+// tail.  Every lane of the workgroup makes the same number of calls (inactive ones carry
+// active == false), so the bodies may use wave-wide operations.
+template <typename T, typename F>
+__device__ __forceinline__ void sweep(const T* __restrict__ row, int32_t V, F& f) {
+    constexpr int N = Elem<T>::kVec;
+    const int32_t nvec = V / N;
+    const uint4* __restrict__ row16 = (const uint4*)row;
+    for (int32_t base = 0; base < nvec; base += kThreads) {
+        const int32_t vi = base + (int32_t)threadIdx.x;
+        const bool active = vi < nvec;
+        float x[N];
+        if (active) {
+            Elem<T>::unpack(row16[vi], x);
+        } else {
+#pragma unroll
+            for (int j = 0; j < N; ++j) x[j] = 0.f;
+        }
+        f.template run<N>(vi * N, x, active);
+    }
+    if (nvec * N < V) {
+        const int32_t i = nvec * N + (int32_t)threadIdx.x;
+        const bool active = i < V;
+        float x[1] = {active ? Elem<T>::widen(row[i]) : 0.f};
+        f.template run<1>(i, x, active);
+    }
+}
+
+// ---- block reductions -------------------------------------------------------
+__device__ __forceinline__ double shfl_xor_f64(double v, int mask) {
+    uint64_t b = __builtin_bit_cast(uint64_t, v);
+    uint32_t lo = __shfl_xor((uint32_t)b, mask), hi = __shfl_xor((uint32_t)(b >> 32), mask);
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+__device__ __forceinline__ uint64_t shfl_up_u64(uint64_t v, int delta) {
+    uint32_t lo = __shfl_up((uint32_t)v, delta), hi = __shfl_up((uint32_t)(v >> 32), delta);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// ---- sweep bodies -----------------------------------------------------------
+struct MaxSum {  // online max and sum of exp in log2 units
+    float inv_t;
+    float m = -INFINITY, s = 0.f;
+    template <int N> __device__ __forceinline__ void run(int32_t, const float (&x)[N], bool active) {
+        if (!active) return;
+#pragma unroll
+        for (int j = 0; j < N; ++j) add(x[j] * inv_t);
+    }
+    __device__ __forceinline__ void add(float z) {
+        if (z > m) {
+            s = s * __builtin_amdgcn_exp2f((m - z) * kLog2e) + 1.f;
+            m = z;
+        } else if (z > -INFINITY) {
+            s += __builtin_amdgcn_exp2f((z - m) * kLog2e);
+        }
+    }
+};
+
+struct Race {  // Gumbel-max with the exact filter described at the top of the file
+    const SampleParams& p;
+    uint32_t row_id;
+    float x_cut;           // entries below it are not kept (-inf when top_p == 1)
+    double best = -INFINITY;
+    int32_t best_i = 0x7FFFFFFF;
+    float thr = -INFINITY;  // wave-uniform: (float) of the wave's best exact value, rounded down
+
+    __device__ __forceinline__ void exact(int32_t i, float x, uint32_t word) {
+        const double u = ((double)(word >> 9) + 0.5) * 0x1p-23;
+        const double y = (double)x / p.temperature - log(-log(u));
+        if (y > best || (y == best && i < best_i)) {
+            best = y;
+            best_i = i;
+        }
+    }
+    __device__ __forceinline__ void share() {
+        double b = best;
+#pragma unroll
+        for (int mask = 1; mask < 64; mask <<= 1) b = fmax(b, shfl_xor_f64(b, mask));
+        float t = (float)b;
+        if ((double)t > b) t = nextafterf(t, -INFINITY);
+        thr = t;
+    }
+    template <int N> __device__ __forceinline__ void run(int32_t i0, const float (&x)[N], bool active) {
+        uint32_t words[N];
+        if (N == 1) {
+            const Philox4 r = philox4x32_10((uint32_t)i0 >> 2, row_id, p.step_lo, p.step_hi, p.seed_lo, p.seed_hi);
+            words[0] = r.w[i0 & 3];
+        } else {
+#pragma unroll
+            for (int b4 = 0; b4 < N / 4; ++b4) {
+                const Philox4 r = philox4x32_10(((uint32_t)i0 >> 2) + b4, row_id, p.step_lo, p.step_hi, p.seed_lo, p.seed_hi);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) words[4 * b4 + j] = r.w[j];
+            }
+        }
+        uint32_t pass = 0;
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            const float z = x[j] * p.inv_t;
+            // 1 - u is exact in fp32; -log(1 - u) bounds the Gumbel variate from above.
+            const float one_minus_u = 1.0f - ((float)(words[j] >> 9) + 0.5f) * 0x1p-23f;
+            const float g_ub = -__builtin_amdgcn_logf(one_minus_u) * kLn2;
+            const float slack = 3e-5f + 2e-6f * fabsf(z);
+            if (active && x[j] >= x_cut && z + g_ub + slack >= thr) pass |= 1u << j;
+        }
+        if (__any(pass != 0)) {
+#pragma unroll
+            for (int j = 0; j < N; ++j)
+                if (pass & (1u << j)) exact(i0 + j, x[j], words[j]);
+            share();
+        }
+    }
+};
+
+template <int SHIFT, int BITS>
+struct Histogram {  // adds exp(z - m) in 2^-40 fixed point to the bin of the key's digit
+    float inv_t, m;
+    uint32_t prefix;  // the key's bits above SHIFT + BITS must equal this
+    unsigned long long* hist;
+    template <int N> __device__ __forceinline__ void run(int32_t, const float (&x)[N], bool active) {
+        if (!active) return;
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            const uint32_t key = order_key(x[j]);
+            if (SHIFT + BITS < 32 && (key >> ((SHIFT + BITS) & 31)) != prefix) continue;
+            const float w = __builtin_amdgcn_exp2f((x[j] * inv_t - m) * kLog2e);
+            const unsigned long long fx = (unsigned long long)((double)w * 0x1p40);
+            if (fx) atomicAdd(&hist[(key >> SHIFT) & ((1u << BITS) - 1u)], fx);
+        }
+    }
+};
+
+struct MaxSumAndRace {  // the single sweep of the top_p == 1 path
+    MaxSum& a;
+    Race& b;
+    template <int N> __device__ __forceinline__ void run(int32_t i0, const float (&x)[N], bool active) {
+        a.template run<N>(i0, x, active);
+        b.template run<N>(i0, x, active);
+    }
+};
+
+struct Select {
+    uint32_t prefix;            // key bits selected so far (right-aligned)
+    unsigned long long above;   // fixed-point mass of keys strictly above the prefix range
+};
+
+// hist holds kBins bins; thread t owns bin (kBins - 1 - t) so that a forward inclusive scan over
+// threads is a suffix sum over bins.  Picks the highest bin at which above + suffix >= target.
+__device__ void scan_select(unsigned long long* hist, unsigned long long* s_wave, Select* s_sel,
+                            unsigned long long target, int bits) {
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int nb = 1 << bits;
+    const int bin = nb - 1 - tid;
+    const unsigned long long mine = (tid < nb) ? hist[bin] : 0ull;
+    unsigned long long incl = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const unsigned long long v = shfl_up_u64(incl, d);
+        if (lane >= d) incl += v;
+    }
+    if (lane == 63) s_wave[wave] = incl;
+    __syncthreads();
+    unsigned long long base = s_sel->above;
+    for (int w = 0; w < wave; ++w) base += s_wave[w];
+    incl += base;
+    const unsigned long long excl = incl - mine;
+    __syncthreads();
+    if (tid < nb && excl < target && incl >= target) {
+        s_sel->prefix = (s_sel->prefix << bits) | (uint32_t)bin;
+        s_sel->above = excl;
+    }
+    __syncthreads();
+}
+
+// One radix level: histogram of the digit at SHIFT (BITS wide) over the entries whose higher
+// key bits equal the prefix chosen so far, then the suffix scan that picks the next digit.
+template <typename T, int SHIFT, int BITS, bool FIRST>
+__device__ void radix_level(const T* __restrict__ row, const SampleParams& p, float M,
+                            unsigned long long* s_hist, unsigned long long* s_wave, Select* s_sel,
+                            unsigned long long& target) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = tid; i < kBins; i += kThreads) s_hist[i] = 0ull;
+    __syncthreads();
+    Histogram<SHIFT, BITS> h{p.inv_t, M, s_sel->prefix, s_hist};
+    sweep<T>(row, p.V, h);
+    __syncthreads();
+    if (FIRST) {  // total mass -> target = ceil(top_p * total)
+        unsigned long long incl = 0;
+        for (int i = tid; i < kBins; i += kThreads) incl += s_hist[i];
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const unsigned long long v = shfl_up_u64(incl, d);
+            if (lane >= d) incl += v;
+        }
+        if (lane == 63) s_wave[wave] = incl;
+        __syncthreads();
+        unsigned long long total = 0;
+        for (int w = 0; w < kWavesPerBlock; ++w) total += s_wave[w];
+        target = (unsigned long long)ceil((double)p.top_p * (double)total);
+        if (target < 1) target = 1;
+        if (target > total) target = total;
+        __syncthreads();
+    }
+    scan_select(s_hist, s_wave, s_sel, target, BITS);
+}
+
+template <typename T, bool TOPP>
+__global__ __launch_bounds__(kThreads) void sample_rows(const T* __restrict__ logits,
+                                                         const int32_t* __restrict__ row_ids,
+                                                         int32_t* __restrict__ tokens_out,
+                                                         float* __restrict__ logprob_out, SampleParams p) {
+    __shared__ unsigned long long s_hist[TOPP ? kBins : 1];
+    __shared__ unsigned long long s_wave[kWavesPerBlock];
+    __shared__ Select s_sel;
+    __shared__ float s_m[kWavesPerBlock];
+    __shared__ double s_s[kWavesPerBlock];
+    __shared__ double s_best[kWavesPerBlock];
+    __shared__ int32_t s_besti[kWavesPerBlock];
+    __shared__ float s_xcut;
+    __shared__ double s_lse;
+
+    const int32_t r = blockIdx.x;
+    const T* __restrict__ row = logits + (int64_t)r * p.row_stride;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t row_id = row_ids ? (uint32_t)row_ids[r] : (uint32_t)r;
+
+    MaxSum ms{p.inv_t};
+    Race race{p, row_id, -INFINITY};
+
+    if (!TOPP) {
+        // One sweep: online log-sum-exp and the race together.
+        MaxSumAndRace both{ms, race};
+        sweep<T>(row, p.V, both);
+    } else {
+        sweep<T>(row, p.V, ms);
+    }
+
+    // Block max and sum (sum only used when top_p == 1).
+    {
+        float m = ms.m;
+#pragma unroll
+        for (int mask = 1; mask < 64; mask <<= 1) m = fmaxf(m, __shfl_xor(m, mask));
+        double s = (double)ms.s * (double)__builtin_amdgcn_exp2f((ms.m - m) * kLog2e);
+        if (ms.s == 0.f) s = 0.0;
+#pragma unroll
+        for (int mask = 1; mask < 64; mask <<= 1) s += shfl_xor_f64(s, mask);
+        if (lane == 0) { s_m[wave] = m; s_s[wave] = s; }
+        __syncthreads();
+        if (tid == 0) {
+            float M = s_m[0];
+            for (int w = 1; w < kWavesPerBlock; ++w) M = fmaxf(M, s_m[w]);
+            double S = 0.0;
+            for (int w = 0; w < kWavesPerBlock; ++w)
+                S += s_s[w] * exp2((double)(s_m[w] - M) * (double)kLog2e);
+            s_m[0] = M;
+            s_lse = (double)M + log(S);
+            s_sel.prefix = 0;
+            s_sel.above = 0;
+        }
+        __syncthreads();
+    }
+
+    if (TOPP) {
+        const float M = s_m[0];
+        constexpr int kKeyBits = Elem<T>::kKeyBits;
+        unsigned long long target = 0;
+        // Levels from the most significant digit down; the last level may be narrower.
+        if (kKeyBits == 16) {
+            radix_level<T, 22, 10, true>(row, p, M, s_hist, s_wave, &s_sel, target);
+            radix_level<T, 16, 6, false>(row, p, M, s_hist, s_wave, &s_sel, target);
+        } else {
+            radix_level<T, 22, 10, true>(row, p, M, s_hist, s_wave, &s_sel, target);
+            radix_level<T, 12, 10, false>(row, p, M, s_hist, s_wave, &s_sel, target);
+            radix_level<T, 2, 10, false>(row, p, M, s_hist, s_wave, &s_sel, target);
+            radix_level<T, 0, 2, false>(row, p, M, s_hist, s_wave, &s_sel, target);
+        }
+        if (tid == 0) {
+            // s_sel.prefix is now the full key of the cut value; the kept mass is everything
+            // above it plus the cut value's own class.
+            const uint32_t key = s_sel.prefix << (32 - kKeyBits) | (kKeyBits == 16 ? ((s_sel.prefix >> 15) ? 0u : 0xFFFFu) : 0u);
+            s_xcut = key_to_float(key);
+        }
+        __syncthreads();
+        // Kept mass: one more histogram-free reduction is avoided by re-reading the last level:
+        // bins >= the selected digit of the last level, plus `above`.
+        if (tid == 0) {
+            constexpr int last_bits = kKeyBits == 16 ? 6 : 2;
+            const uint32_t digit = s_sel.prefix & ((1u << last_bits) - 1u);
+            const unsigned long long kept = s_sel.above + s_hist[digit];
+            s_lse = (double)M + log((double)kept * 0x1p-40);
+        }
+        __syncthreads();
+        race.x_cut = s_xcut;
+        sweep<T>(row, p.V, race);
+    }
+
+    // Block arg-max of the exact perturbed values (lowest index on ties).
+    {
+        double b = race.best;
+        int32_t bi = race.best_i;
+#pragma unroll
+        for (int mask = 1; mask < 64; mask <<= 1) {
+            const double ob = shfl_xor_f64(b, mask);
+            const int32_t oi = __shfl_xor(bi, mask);
+            if (ob > b || (ob == b && oi < bi)) { b = ob; bi = oi; }
+        }
+        if (lane == 0) { s_best[wave] = b; s_besti[wave] = bi; }
+        __syncthreads();
+        if (tid == 0) {
+            for (int w = 1; w < kWavesPerBlock; ++w)
+                if (s_best[w] > b || (s_best[w] == b && s_besti[w] < bi)) { b = s_best[w]; bi = s_besti[w]; }
+            if ((uint32_t)bi >= (uint32_t)p.V) {  // no finite entry in the row
+                tokens_out[r] = 0;
+                logprob_out[r] = NAN;
+            } else {
+                tokens_out[r] = bi;
+                const double z = (double)Elem<T>::widen(row[bi]) / p.temperature;
+                logprob_out[r] = (float)(z - s_lse);
+            }
+        }
+    }
+}
+
+int validate(const roll_sample_desc* d) {
+    if (!d) return roll::fail(ROLL_ERR_INVALID_ARG, "desc is NULL");
+    if (d->batch <= 0 || d->vocab <= 0) return roll::fail(ROLL_ERR_INVALID_ARG, "batch and vocab must be > 0");
+    if (d->row_stride < d->vocab) return roll::fail(ROLL_ERR_INVALID_ARG, "row_stride < vocab");
+    if (d->logits_dtype != ROLL_BF16 && d->logits_dtype != ROLL_F32) return roll::fail(ROLL_ERR_INVALID_ARG, "logits_dtype must be ROLL_BF16 or ROLL_F32");
+    const int64_t elem = d->logits_dtype == ROLL_BF16 ? 2 : 4;
+    if ((d->row_stride * elem) % 16 != 0) return roll::fail(ROLL_ERR_INVALID_ARG, "rows must start 16-byte aligned (row_stride * element size %% 16 == 0)");
+    return ROLL_OK;
+}
+
+}  // namespace
+
+extern "C" size_t roll_sample_logprob_workspace_bytes(const roll_sample_desc* d) {
+    if (validate(d) != ROLL_OK) return 0;
+    return 256;  // reserved; the current kernels keep all intermediate state on chip
+}
+
+extern "C" int roll_sample_logprob(const void* logits, float temperature, float top_p,
+                                   uint64_t philox_seed, uint64_t step, int32_t* tokens_out,
+                                   float* logprob_out, const roll_sample_desc* d, void* workspace,
+                                   size_t workspace_bytes, void* stream_v) {
+    int rc = validate(d);
+    if (rc != ROLL_OK) return rc;
+    if (!logits || !tokens_out || !logprob_out) return roll::fail(ROLL_ERR_INVALID_ARG, "NULL pointer argument");
+    if (!roll::aligned(logits, 16)) return roll::fail(ROLL_ERR_INVALID_ARG, "logits must be 16-byte aligned");
+    if (!(temperature > 0.f) || std::isinf(temperature)) return roll::fail(ROLL_ERR_INVALID_ARG, "temperature must be finite and > 0");
+    if (!(top_p > 0.f) || top_p > 1.f) return roll::fail(ROLL_ERR_INVALID_ARG, "top_p must be in (0, 1]");
+    (void)workspace;
+    (void)workspace_bytes;
+    hipStream_t stream = (hipStream_t)stream_v;
+    SampleParams p{};
+    p.V = d->vocab;
+    p.row_stride = d->row_stride;
+    p.inv_t = 1.0f / temperature;
+    p.temperature = (double)temperature;
+    p.top_p = top_p;
+    p.seed_lo = (uint32_t)philox_seed;
+    p.seed_hi = (uint32_t)(philox_seed >> 32);
+    p.step_lo = (uint32_t)step;
+    p.step_hi = (uint32_t)(step >> 32);
+    const bool topp = top_p < 1.0f;
+    const dim3 grid(d->batch), block(kThreads);
+    if (d->logits_dtype == ROLL_BF16) {
+        if (topp) sample_rows<uint16_t, true><<<grid, block, 0, stream>>>((const uint16_t*)logits, d->row_ids, tokens_out, logprob_out, p);
+        else sample_rows<uint16_t, false><<<grid, block, 0, stream>>>((const uint16_t*)logits, d->row_ids, tokens_out, logprob_out, p);
+    } else {
+        if (topp) sample_rows<float, true><<<grid, block, 0, stream>>>((const float*)logits, d->row_ids, tokens_out, logprob_out, p);
+        else sample_rows<float, false><<<grid, block, 0, stream>>>((const float*)logits, d->row_ids, tokens_out, logprob_out, p);
+    }
+    ROLL_HIP_CHECK(hipGetLastError());
+    return ROLL_OK;
+}

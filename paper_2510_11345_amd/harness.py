@@ -1,0 +1,136 @@
+"""Device-side state of a running decode batch, built through the C ABI.
+
+Plumbing shared by the benchmark, the smoke check and the end-to-end tests:
+it owns the torch tensors (device memory only), drives the allocator and
+calls the library once per step.  No arithmetic of the decode step is here.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as rb
+from . import workloads as wl
+
+
+class DecodeBatch:
+    """A batch of `cfg.batch` slots whose KV lives in paged pools.
+
+    The pools are filled with i.i.d. N(0,1) bf16 once (a slot's "history" is
+    whatever its pages hold); lengths are grown through roll_kv_alloc_batch in
+    page-sized rounds over all rows, so that the physical pages of different
+    rows interleave the way they do in a long-running continuous batch.
+    """
+
+    def __init__(self, cfg: wl.DecodeConfig, seed: int, lengths: np.ndarray, headroom_tokens: int = 0,
+                 out_dtype=torch.bfloat16, chunk_tokens: int = 0, device: str = "cuda",
+                 spare_pages: int = 64, max_len: int | None = None, fill_pools: bool = True,
+                 profile_events: bool = False):
+        self.cfg, self.seed, self.device = cfg, seed, device
+        B, P = cfg.batch, cfg.page_size
+        Hq, Hkv, D = cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim
+        lengths = np.asarray(lengths, dtype=np.int64)
+        assert len(lengths) == B
+        cap = int(max(int(lengths.max()) + headroom_tokens, 1)) if max_len is None else int(max_len)
+        self.max_pages = (cap + P - 1) // P
+        need = int(((np.minimum(lengths + headroom_tokens, cap) + P - 1) // P).sum())
+        self.num_pages = need + spare_pages
+        self.page_table = torch.empty((B, self.max_pages), dtype=torch.int32, device=device)
+        self.seq_lens = torch.zeros((B,), dtype=torch.int32, device=device)
+        self.pool = rb.KvPool(self.num_pages, P, B, self.max_pages, self.page_table, self.seq_lens)
+        if fill_pools:
+            self.k_pages = wl.randn_bf16((self.num_pages, Hkv, D // 8, P, 8), seed, 2, device)
+            self.v_pages = wl.randn_bf16((self.num_pages, Hkv, P // 8, D, 8), seed, 3, device)
+        else:
+            self.k_pages = torch.zeros((self.num_pages, Hkv, D // 8, P, 8), dtype=torch.bfloat16, device=device)
+            self.v_pages = torch.zeros((self.num_pages, Hkv, P // 8, D, 8), dtype=torch.bfloat16, device=device)
+        self.q = wl.randn_bf16((B, Hq, D), seed, 1, device)
+        self.k_new = wl.randn_bf16((B, Hkv, D), seed, 5, device)
+        self.v_new = wl.randn_bf16((B, Hkv, D), seed, 6, device)
+        self.out = torch.zeros((B, Hq, D), dtype=out_dtype, device=device)
+        self.tokens = torch.zeros((B,), dtype=torch.int32, device=device)
+        self.logprob = torch.zeros((B,), dtype=torch.float32, device=device)
+        self.lengths = np.zeros(B, dtype=np.int64)
+        self.all_slots = np.arange(B, dtype=np.int32)
+        self.ones = np.ones(B, dtype=np.int32)
+        self.ev_pairs = []   # (begin, end, sum of seq_lens) per profiled step
+        self.ev_spare = []   # pre-created event pairs, so that none is created inside a timed loop
+        self.profile_events = profile_events
+        self.chunk_tokens = chunk_tokens
+        self.out_dtype = out_dtype
+        self._desc_total = -1
+        self._ws = None
+        self.grow_to(lengths)
+
+    # -- allocator ------------------------------------------------------------
+    def grow_to(self, target: np.ndarray) -> None:
+        """Grow every row to its target length, one page-sized round over all rows at a time."""
+        target = np.asarray(target, dtype=np.int64)
+        P = self.cfg.page_size
+        while True:
+            todo = np.flatnonzero(self.lengths < target)
+            if len(todo) == 0:
+                break
+            n = np.minimum(target[todo] - self.lengths[todo], P).astype(np.int32)
+            rb.roll_kv_alloc_batch(self.pool, todo.astype(np.int32), n)
+            self.lengths[todo] += n
+        rb.roll_kv_commit(self.pool)
+
+    def total_tokens(self) -> int:
+        return int(self.lengths.sum())
+
+    # -- one decode step --------------------------------------------------------
+    def _attn_desc(self):
+        # the bound only has to hold for the calls made with this descriptor
+        bound = self.total_tokens() + 64 * self.cfg.batch
+        if self._ws is None or bound > self._desc_total:
+            self._desc_total = bound + 4096 * self.cfg.batch
+            self.desc = rb.attn_desc(self.q, self.k_pages, self.page_table, self.cfg.page_size,
+                                     self.out_dtype, 0.0, self.chunk_tokens, self._desc_total)
+            nbytes = rb.roll_decode_attn_workspace_bytes(self.desc)
+            self._ws = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        return self.desc
+
+    def step(self, logits: torch.Tensor, step_index: int, temperature=None, top_p=None,
+             grow: bool = True) -> None:
+        """alloc (+1 token per row) -> commit -> append K/V -> attention -> sample."""
+        cfg = self.cfg
+        if grow:
+            rb.roll_kv_alloc_batch(self.pool, self.all_slots, self.ones)
+            self.lengths += 1
+            rb.roll_kv_commit(self.pool)
+            rb.roll_kv_append_tokens(self.k_new, self.v_new, None, None, self.seq_lens, self.k_pages,
+                                     self.v_pages, self.page_table, cfg.page_size)
+        desc = self._attn_desc()
+        if self.profile_events:
+            e0, e1 = self.ev_spare.pop() if self.ev_spare else (rb.ProfEvent(), rb.ProfEvent())
+            desc.ev_main_begin, desc.ev_main_end = e0.handle.value, e1.handle.value
+            self.ev_pairs.append((e0, e1, self.total_tokens()))
+        rb.roll_decode_attn(self.q, self.k_pages, self.v_pages, self.page_table, self.seq_lens, self.out,
+                            desc, self._ws)
+        if self.profile_events:
+            desc.ev_main_begin, desc.ev_main_end = None, None
+        sdesc = rb.sample_desc(logits)
+        rb.roll_sample_logprob(logits, cfg.temperature if temperature is None else temperature,
+                               cfg.top_p if top_p is None else top_p, self.seed, step_index,
+                               self.tokens, self.logprob, sdesc, None)
+
+    # -- host copies for the oracle --------------------------------------------
+    def gather_rows(self, rows):
+        """Host copy of the listed rows: compact pools holding only their pages and a remapped
+        page table; returns (q_bits, k_bits, v_bits, page_table, seq_lens) over len(rows) rows."""
+        P = self.cfg.page_size
+        pages, table = [], np.full((len(rows), self.max_pages), -1, dtype=np.int32)
+        for i, r in enumerate(rows):
+            pr = rb.roll_kv_slot_pages(self.pool, int(r))
+            table[i, :len(pr)] = np.arange(len(pages), len(pages) + len(pr))
+            pages.extend(pr)
+        idx = torch.tensor(pages, dtype=torch.int64, device=self.device)
+        k = wl.bits(self.k_pages.index_select(0, idx)).reshape(-1)
+        v = wl.bits(self.v_pages.index_select(0, idx)).reshape(-1)
+        q = wl.bits(self.q[torch.tensor(list(rows), device=self.device)])
+        lens = self.lengths[list(rows)].astype(np.int32)
+        return q, k, v, table, lens
+
+    def close(self):
+        self.pool.close()

@@ -1,0 +1,80 @@
+"""Shared plumbing of the GPU parity tests: upload seeded inputs, call the C ABI through the
+binding, fetch results.  No arithmetic of the decode step lives here."""
+import numpy as np
+import torch
+
+from paper_2510_11345_amd import binding as rb
+from paper_2510_11345_amd import workloads as wl
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def run_attn(inp, cfg, out_dtype=torch.float32, chunk_tokens=0, softmax_scale=0.0,
+             max_total_tokens=0, seq_lens=None):
+    """inp: dict from workloads.make_attn_inputs (cpu or cuda tensors). Returns out on host (float64)."""
+    dev = "cuda"
+    q = inp["q"].to(dev)
+    k_pages = inp["k_pages"].to(dev)
+    v_pages = inp["v_pages"].to(dev)
+    table = torch.from_numpy(np.ascontiguousarray(inp["page_table"])).to(dev)
+    lens = torch.from_numpy(np.ascontiguousarray(inp["seq_lens"] if seq_lens is None else seq_lens)).to(dev)
+    B, Hq, D = q.shape
+    out = torch.full((B, Hq, D), float("nan"), dtype=out_dtype, device=dev)
+    desc = rb.attn_desc(q, k_pages, table, cfg.page_size, out_dtype, softmax_scale, chunk_tokens,
+                        max_total_tokens)
+    ws = torch.empty(rb.roll_decode_attn_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+    rb.roll_decode_attn(q, k_pages, v_pages, table, lens, out, desc, ws)
+    torch.cuda.synchronize()
+    return out.double().cpu().numpy()
+
+
+def oracle_attn(inp, cfg, rows=None, scale=None, seq_lens=None):
+    import oracle
+    return oracle.decode_attn(wl.bits(inp["q"]), wl.bits(inp["k_pages"]).reshape(-1),
+                              wl.bits(inp["v_pages"]).reshape(-1), inp["page_table"],
+                              inp["seq_lens"] if seq_lens is None else seq_lens,
+                              cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.page_size,
+                              scale=scale, rows=rows)
+
+
+def run_sample(logits, T, top_p, seed, step, row_ids=None):
+    dev = "cuda"
+    lg = logits if logits.is_cuda else logits.to(dev)
+    B = lg.shape[0]
+    tokens = torch.full((B,), -7, dtype=torch.int32, device=dev)
+    lp = torch.full((B,), float("nan"), dtype=torch.float32, device=dev)
+    rid = None if row_ids is None else torch.tensor(row_ids, dtype=torch.int32, device=dev)
+    desc = rb.sample_desc(lg, rid)
+    ws = torch.empty(rb.roll_sample_logprob_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+    rb.roll_sample_logprob(lg, T, top_p, seed, step, tokens, lp, desc, ws)
+    torch.cuda.synchronize()
+    return tokens.cpu().numpy(), lp.double().cpu().numpy()
+
+
+def compare_sampling(logits, T, top_p, seed, step, row_ids=None, lp_tol=1e-3):
+    """Runs both sides; returns (n_mismatch_excused_tie, n_mismatch_excused_band). Asserts the bar:
+    token ids identical unless the oracle's top-two gap is below 1e-5 or a token lies in the
+    top-p boundary band; log-probs within lp_tol wherever the tokens agree."""
+    import oracle
+    tok, lp = run_sample(logits, T, top_p, seed, step, row_ids)
+    ref = oracle.sample_logprob(wl.logits_numpy(logits), T, top_p, seed, step, row_ids=row_ids)
+    x = wl.logits_numpy(logits)
+    if x.dtype == np.uint16:
+        x = (x.astype(np.uint32) << 16).view(np.float32)
+    ties = band = 0
+    for r in range(len(tok)):
+        if tok[r] == ref["tokens"][r]:
+            assert abs(lp[r] - ref["logprob"][r]) <= lp_tol, (r, lp[r], ref["logprob"][r])
+            continue
+        in_band = lambda t: ref["x_cut_plus"][r] <= x[r, t] < ref["x_cut_minus"][r]
+        if ref["gap"][r] < 1e-5:
+            ties += 1
+        elif 0 <= tok[r] < x.shape[1] and (in_band(tok[r]) or in_band(ref["tokens"][r])):
+            band += 1
+        else:
+            raise AssertionError(f"row {r}: token {tok[r]} != oracle {ref['tokens'][r]} "
+                                 f"(gap {ref['gap'][r]:.3e})")
+    say(f"    sampling parity: {len(tok)} rows, near-tie mismatches {ties}, boundary-band mismatches {band}")
+    return ties, band

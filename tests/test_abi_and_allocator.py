@@ -1,0 +1,149 @@
+"""CPU-only checks: the C-ABI library loads and exports what the header declares, argument
+validation rejects bad input before anything touches a GPU, and the host allocator logic
+(host-only pool) keeps its invariants."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2510_11345_amd import binding as rb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "roll_decode.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(roll_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = rb.lib()
+    syms = declared_symbols()
+    assert len(syms) >= 18
+    for s in syms:
+        assert hasattr(L, s), f"{s} declared in roll_decode.h but not exported"
+    assert sorted(rb.EXPORTS) == syms  # the binding covers the same set
+    assert rb.roll_version()
+
+
+def host_pool(num_pages=64, P=16, slots=4, max_pages=8):
+    return rb.KvPool(num_pages, P, slots, max_pages)
+
+
+def owned(pool, slots):
+    return [rb.roll_kv_slot_pages(pool, s) for s in range(slots)]
+
+
+def check_conservation(pool, slots, num_pages):
+    pages = [p for lst in owned(pool, slots) for p in lst]
+    assert len(pages) == len(set(pages)), "a page is owned twice"
+    assert all(0 <= p < num_pages for p in pages)
+    assert rb.roll_kv_free_pages(pool) + len(pages) == num_pages
+
+
+def test_alloc_grows_by_pages_and_conserves():
+    pool = host_pool()
+    rb.roll_kv_alloc(pool, 0, 1)
+    assert rb.roll_kv_seq_len(pool, 0) == 1 and rb.roll_kv_slot_pages(pool, 0) == [0]
+    rb.roll_kv_alloc(pool, 0, 15)          # fills the page, no new one
+    assert rb.roll_kv_slot_pages(pool, 0) == [0]
+    rb.roll_kv_alloc(pool, 0, 1)           # crosses the boundary
+    assert rb.roll_kv_slot_pages(pool, 0) == [0, 1] and rb.roll_kv_seq_len(pool, 0) == 17
+    rb.roll_kv_alloc(pool, 2, 40)
+    assert rb.roll_kv_slot_pages(pool, 2) == [2, 3, 4]
+    check_conservation(pool, 4, 64)
+
+
+def test_release_returns_everything_and_refill_reuses():
+    pool = host_pool()
+    rb.roll_kv_alloc(pool, 1, 100)
+    before = rb.roll_kv_slot_pages(pool, 1)
+    assert rb.roll_kv_free_pages(pool) == 64 - 7
+    rb.roll_kv_release(pool, 1)            # finish or ABORT
+    assert rb.roll_kv_free_pages(pool) == 64 and rb.roll_kv_seq_len(pool, 1) == 0
+    rb.roll_kv_alloc(pool, 3, 100)         # the refill gets the same pages back
+    assert rb.roll_kv_slot_pages(pool, 3) == before
+    with pytest.raises(rb.RollError) as e:
+        rb.roll_kv_release(pool, 1)        # double release
+    assert e.value.status == -3
+
+
+def test_errors_leave_state_unchanged():
+    pool = host_pool(num_pages=10, max_pages=8)
+    rb.roll_kv_alloc(pool, 0, 5 * 16)
+    snap = (owned(pool, 4), rb.roll_kv_free_pages(pool))
+    with pytest.raises(rb.RollError) as e:
+        rb.roll_kv_alloc(pool, 1, 6 * 16)  # needs 6, 5 free
+    assert e.value.status == -2
+    with pytest.raises(rb.RollError) as e:
+        rb.roll_kv_alloc(pool, 0, 4 * 16)  # would need 9 > max_pages_per_seq
+    assert e.value.status == -5
+    with pytest.raises(rb.RollError) as e:
+        rb.roll_kv_alloc(pool, 4, 1)
+    assert e.value.status == -4
+    with pytest.raises(rb.RollError) as e:
+        rb.roll_kv_alloc(pool, 0, 0)
+    assert e.value.status == -1
+    with pytest.raises(rb.RollError) as e:
+        rb.roll_kv_commit(pool)            # host-only pool
+    assert e.value.status == -1
+    assert (owned(pool, 4), rb.roll_kv_free_pages(pool)) == snap
+    assert "host-only" in rb.lib().roll_last_error().decode()
+
+
+def test_random_alloc_release_keeps_invariants():
+    rng = np.random.default_rng(0)
+    slots, num_pages = 16, 300
+    pool = host_pool(num_pages=num_pages, slots=slots, max_pages=40)
+    lens = [0] * slots
+    for _ in range(3000):
+        s = int(rng.integers(slots))
+        if lens[s] and rng.random() < 0.15:
+            rb.roll_kv_release(pool, s); lens[s] = 0
+        else:
+            n = int(rng.integers(1, 50))
+            try:
+                rb.roll_kv_alloc(pool, s, n); lens[s] += n
+            except rb.RollError as e:
+                assert e.status in (-2, -5)
+        assert rb.roll_kv_seq_len(pool, s) == lens[s]
+    check_conservation(pool, slots, num_pages)
+    for s in range(slots):
+        assert len(rb.roll_kv_slot_pages(pool, s)) == (lens[s] + 15) // 16
+
+
+def test_bad_pool_config_is_rejected():
+    for args in [(0, 16, 4, 8), (64, 8, 4, 8), (64, 16, 0, 8), (64, 16, 4, 0)]:
+        with pytest.raises(rb.RollError):
+            rb.KvPool(*args)
+
+
+def test_attention_and_sampling_reject_bad_descriptors_on_the_host():
+    L = rb.lib()
+    good = rb.AttnDesc(4, 8, 2, 64, 16, 8, 32, rb.ROLL_BF16, 0.0, 0, 0, None, None)
+    assert L.roll_decode_attn_workspace_bytes(C.byref(good)) > 0
+    for field, val in [("head_dim", 96), ("num_kv_heads", 3), ("page_size", 8), ("chunk_tokens", 100),
+                       ("batch", 0), ("out_dtype", 7), ("num_q_heads", 64)]:
+        d = rb.AttnDesc(4, 8, 2, 64, 16, 8, 32, rb.ROLL_BF16, 0.0, 0, 0, None, None)
+        if field == "num_q_heads":
+            d.num_kv_heads = 2  # group of 32 > 16
+        setattr(d, field, val)
+        assert L.roll_decode_attn_workspace_bytes(C.byref(d)) == 0
+        assert L.roll_decode_attn(16, 16, 16, 16, 16, 16, C.byref(d), 256, 1 << 30, None) == -1
+    # NULL / misaligned pointers and a short workspace never reach a kernel launch
+    assert L.roll_decode_attn(None, 16, 16, 16, 16, 16, C.byref(good), 256, 1 << 30, None) == -1
+    assert L.roll_decode_attn(8, 16, 16, 16, 16, 16, C.byref(good), 256, 1 << 30, None) == -1
+    assert L.roll_decode_attn(16, 16, 16, 16, 16, 16, C.byref(good), 256, 8, None) == -6
+    assert L.roll_decode_attn(16, 16, 16, 16, 16, 16, C.byref(good), None, 1 << 30, None) == -6
+    sd = rb.SampleDesc(2, 4096, 4096, rb.ROLL_F32, 0, None)
+    assert L.roll_sample_logprob_workspace_bytes(C.byref(sd)) > 0
+    for T, p in [(0.0, 1.0), (-1.0, 1.0), (1.0, 0.0), (1.0, 1.5), (float("nan"), 1.0), (1.0, float("nan"))]:
+        assert L.roll_sample_logprob(16, T, p, 0, 0, 16, 16, C.byref(sd), None, 0, None) == -1
+    bad = rb.SampleDesc(2, 4096, 4095, rb.ROLL_F32, 0, None)
+    assert L.roll_sample_logprob(16, 1.0, 1.0, 0, 0, 16, 16, C.byref(bad), None, 0, None) == -1
+    bad = rb.SampleDesc(2, 4097, 4097, rb.ROLL_BF16, 0, None)  # rows would not be 16-byte aligned
+    assert L.roll_sample_logprob(16, 1.0, 1.0, 0, 0, 16, 16, C.byref(bad), None, 0, None) == -1
+    assert L.roll_sample_logprob(None, 1.0, 1.0, 0, 0, 16, 16, C.byref(sd), None, 0, None) == -1

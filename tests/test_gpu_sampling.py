@@ -1,0 +1,87 @@
+"""GPU parity of roll_sample_logprob against the fp64 oracle (needs an MI355X)."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2510_11345_amd import workloads as wl
+from gpu_helpers import compare_sampling, run_sample, say
+
+pytestmark = pytest.mark.gpu
+
+
+def test_config1_exact():
+    cfg = wl.CONFIGS["c1"]
+    say("  sample case c1: fp32 N(0,1) V=4096 B=8 T=1 p=1 seed 0")
+    lg = wl.make_logits(cfg, 0)
+    for step in range(4):
+        compare_sampling(lg, 1.0, 1.0, seed=0, step=step)
+
+
+@pytest.mark.parametrize("name,T,p", [("c2", 1.0, 1.0), ("c3", 0.7, 0.95), ("c5", 1.0, 0.99)])
+def test_full_vocab_reduced_batch(name, T, p):
+    cfg = wl.CONFIGS[name]
+    say(f"  sample case {name}: {cfg.logits_dtype} {cfg.logits} V={cfg.vocab} B=12 T={T} p={p}")
+    lg = wl.make_logits(cfg, 1, batch=12)
+    compare_sampling(lg, T, p, seed=42, step=3)
+
+
+@pytest.mark.parametrize("dtype,V,stride", [("bf16", 1001, 1008), ("f32", 4099, 4100), ("bf16", 5, 8),
+                                            ("f32", 3, 4), ("bf16", 8200, 8200), ("f32", 70001, 70004)])
+@pytest.mark.parametrize("T,p", [(1.0, 1.0), (0.8, 0.9)])
+def test_odd_vocab_sizes_and_strides(dtype, V, stride, T, p):
+    say(f"  sample case odd: {dtype} V={V} stride={stride} T={T} p={p}")
+    cfg = dataclasses.replace(wl.CONFIGS["c2"], vocab=stride, logits_dtype=dtype)
+    lg = wl.make_logits(cfg, 2, batch=5).cuda()[:, :V]   # a strided view: rows dense, stride > V
+    assert lg.stride(0) == stride and lg.is_cuda
+    compare_sampling(lg, T, p, seed=7, step=11)
+
+
+def test_row_ids_and_step_define_the_draw():
+    cfg = dataclasses.replace(wl.CONFIGS["c2"], vocab=4096)
+    lg = wl.make_logits(cfg, 3, batch=6)
+    t0, l0 = run_sample(lg, 1.0, 1.0, 5, 9)
+    perm = [4, 2, 0, 5, 1, 3]
+    t1, l1 = run_sample(lg[perm].contiguous(), 1.0, 1.0, 5, 9, row_ids=perm)
+    assert np.array_equal(t1, t0[perm]) and np.array_equal(l1, l0[perm])
+    t2, _ = run_sample(lg, 1.0, 1.0, 5, 10)
+    t3, _ = run_sample(lg, 1.0, 1.0, 6, 9)
+    assert not np.array_equal(t2, t0) and not np.array_equal(t3, t0)
+    compare_sampling(lg[perm].contiguous(), 1.0, 1.0, 5, 9, row_ids=perm)
+    compare_sampling(lg, 1.3, 0.7, (1 << 40) + 17, (1 << 33) + 5)   # 64-bit seed and step
+
+
+def test_masked_and_dominant_entries():
+    cfg = dataclasses.replace(wl.CONFIGS["c2"], vocab=2048)
+    lg = wl.make_logits(cfg, 4, batch=4).float()
+    lg[0, 100:] = float("-inf")           # only the first 100 entries can be drawn
+    lg[1, 777] = 60.0                     # one entry holds all the mass
+    lg[2, :] = 0.5                        # uniform
+    lg = lg.to(torch.bfloat16)
+    for T, p in [(1.0, 1.0), (1.0, 0.9), (0.5, 0.3)]:
+        tok, lp = run_sample(lg, T, p, 1, 2)
+        assert tok[0] < 100 and tok[1] == 777 and abs(lp[1]) < 1e-6
+        assert abs(lp[2] + np.log(2048)) < 1e-3
+        compare_sampling(lg, T, p, 1, 2)
+
+
+def test_tiny_top_p_keeps_the_top_class():
+    cfg = dataclasses.replace(wl.CONFIGS["c2"], vocab=4096)
+    lg = wl.make_logits(cfg, 5, batch=8)
+    tok, lp = run_sample(lg, 1.0, 1e-6, 3, 0)
+    x = lg.float().numpy()
+    for r in range(8):
+        assert x[r, tok[r]] == x[r].max()
+    compare_sampling(lg, 1.0, 1e-6, 3, 0)
+
+
+def test_many_steps_small_vocab_all_tokens_match():
+    # the sampler as a whole: every draw of a long run equals the oracle's draw
+    cfg = dataclasses.replace(wl.CONFIGS["c1"], vocab=16)
+    lg = (wl.make_logits(cfg, 6, batch=64) * 1.5).contiguous()
+    ties = 0
+    for step in range(40):
+        t, _ = compare_sampling(lg, 0.9, 0.95, seed=99, step=step)
+        ties += t
+    assert ties <= 2
