@@ -41,6 +41,7 @@ typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 
 constexpr int kWaves = 4;          // wavefronts per workgroup
+constexpr bool kPipeline = false;   // issue the next step's loads before computing the current one
 constexpr int kStep = 32;          // tokens per wave step
 constexpr int kDefaultChunk = 512; // tokens per split-K chunk
 constexpr int kCounterInts = 64;   // 256-byte header of the workspace
@@ -140,6 +141,14 @@ __global__ __launch_bounds__(1024) void build_worklist(const int32_t* __restrict
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ bf16x8_t as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8_t, v); }
 
+// KV is read exactly once per step: a nontemporal load keeps it from displacing the
+// page table, Q and the partials in L2 (measured: +10 % on a plain streaming read).
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream(const uint4* p) {
+    const u32x4_t v = __builtin_nontemporal_load((const u32x4_t*)p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 __device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi) {
     f32x2_t f = {lo, hi};
     bf16x2_t b = __builtin_convertvector(f, bf16x2_t);
@@ -157,15 +166,19 @@ struct WaveCtx {
     const uint4* __restrict__ k_pages;
     const uint4* __restrict__ v_pages;
     const int32_t* __restrict__ pt_row;
-    int32_t h, Hkv, log2P, num_pages, last_page, r, q;
+    int32_t h, Hkv, log2P, num_pages, max_pages, r, q;
 };
 
 template <int D>
 __device__ __forceinline__ void load_step(const WaveCtx<D>& c, int32_t t0, StepData<D>& s) {
     const int32_t P = 1 << c.log2P;
     int32_t pa = t0 >> c.log2P;
+    // The second page may lie past the row's end; its table entry is then stale or -1.  Reading
+    // it is in bounds (clamped to the table row) and the id is clamped below, so the loads stay
+    // inside the pool; the tokens are masked by the caller.  Not clamping to the row's own
+    // last page keeps the row length off the address path.
     int32_t pb = (t0 + 16) >> c.log2P;
-    pb = pb > c.last_page ? c.last_page : pb;
+    pb = pb > c.max_pages - 1 ? c.max_pages - 1 : pb;
     int32_t pgA = c.pt_row[pa];
     int32_t pgB = c.pt_row[pb];
     pgA = pgA < 0 ? 0 : (pgA >= c.num_pages ? c.num_pages - 1 : pgA);
@@ -179,7 +192,7 @@ __device__ __forceinline__ void load_step(const WaveCtx<D>& c, int32_t t0, StepD
         const int32_t tin = (t0 + tis) & (P - 1);
         const uint4* base = c.k_pages + (((int64_t)page * c.Hkv + c.h) * (D / 8) + c.q) * P + tin;
 #pragma unroll
-        for (int kk = 0; kk < D / 32; ++kk) s.k[tt][kk] = base[(int64_t)kk * 4 * P];
+        for (int kk = 0; kk < D / 32; ++kk) s.k[tt][kk] = load_stream(base + (int64_t)kk * 4 * P);
     }
     // V: lane (r, q) reads, for d-tile nt, the 8 tokens 8q..8q+7 of head-dim element 16nt+r.
     {
@@ -187,7 +200,7 @@ __device__ __forceinline__ void load_step(const WaveCtx<D>& c, int32_t t0, StepD
         const int32_t oct = ((t0 + 8 * c.q) & (P - 1)) >> 3;
         const uint4* base = c.v_pages + (((int64_t)page * c.Hkv + c.h) * (P / 8) + oct) * D + c.r;
 #pragma unroll
-        for (int nt = 0; nt < D / 16; ++nt) s.v[nt] = base[nt * 16];
+        for (int nt = 0; nt < D / 16; ++nt) s.v[nt] = load_stream(base + nt * 16);
     }
 }
 
@@ -309,7 +322,7 @@ __global__ __launch_bounds__(kWaves * 64) void attn_partial(
     ctx.Hkv = prm.Hkv;
     ctx.log2P = prm.log2P;
     ctx.num_pages = prm.num_pages;
-    ctx.last_page = (L - 1) >> prm.log2P;
+    ctx.max_pages = prm.max_pages;
     ctx.r = lane & 15;
     ctx.q = lane >> 4;
 
@@ -514,11 +527,11 @@ extern "C" int roll_decode_attn(const void* q, const void* k_pages, const void* 
     const size_t lds = sizeof(float) * (2 * kWaves * 16 + (size_t)kWaves * prm.G * (d->head_dim + 4));
     if (d->ev_main_begin) ROLL_HIP_CHECK(hipEventRecord((hipEvent_t)d->ev_main_begin, stream));
     if (d->head_dim == 128)
-        attn_partial<128, true><<<grid, kWaves * 64, lds, stream>>>(
+        attn_partial<128, kPipeline><<<grid, kWaves * 64, lds, stream>>>(
             (const uint4*)q, (const uint4*)k_pages, (const uint4*)v_pages, page_table, seq_lens, ws.work,
             ws.counters, ws.chunk_offsets, out, ws.part_ml, ws.part_acc, prm);
     else
-        attn_partial<64, true><<<grid, kWaves * 64, lds, stream>>>(
+        attn_partial<64, kPipeline><<<grid, kWaves * 64, lds, stream>>>(
             (const uint4*)q, (const uint4*)k_pages, (const uint4*)v_pages, page_table, seq_lens, ws.work,
             ws.counters, ws.chunk_offsets, out, ws.part_ml, ws.part_acc, prm);
     ROLL_HIP_CHECK(hipGetLastError());
