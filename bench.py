@@ -5,7 +5,7 @@ One step = the whole hot path over one batch: allocator (+1 token per row, one c
 K/V append, paged GQA decode attention (work list, split-K partial, merge) and
 temperature / top-p sampling with log-prob recording.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c2] [--chunk C]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c2]
 """
 from __future__ import annotations
 
@@ -43,7 +43,6 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="c2", choices=["c2", "c3", "c5"])
-    ap.add_argument("--chunk", type=int, default=0, help="split-K chunk tokens (0 = library default)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--oracle-rows", type=int, default=16)
@@ -68,7 +67,7 @@ def main():
     lengths = wl.draw_lengths(cfg.lengths, cfg.batch, args.seed, cfg.max_len).astype(np.int64)
     # seq_lens count the token being decoded: start one short, every step appends one token
     batch = DecodeBatch(cfg, args.seed, lengths - 1, headroom_tokens=K + W + 2,
-                        chunk_tokens=args.chunk, profile_events=False)
+                        profile_events=False)
     logits = wl.make_logits(cfg, args.seed, "cuda")
     torch.cuda.synchronize()
 
@@ -110,11 +109,10 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": workload, "seed": args.seed, "sum_seq_lens": int(batch.total_tokens()),
-                   "chunk_tokens": args.chunk or "default"},
+        "config": {"workload": workload, "seed": args.seed, "sum_seq_lens": int(batch.total_tokens())},
         "kv_read_GBps": achieved,
         "kv_read_frac_of_peak": achieved / HBM_PEAK_GBS,
-        "roofline": {"bound": "hbm", "kernel": "attn_partial", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "attn_stream", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": profiled_traffic(cfg.name),
                      "algorithmic_bytes_per_launch": avg_kv_bytes, "avg_launch_ms": avg_kern_ms},

@@ -173,7 +173,7 @@ int roll_kv_append_tokens(const void* k_new, const void* v_new,
 /* ------------------------------------------------------------------ */
 
 typedef struct roll_attn_desc {
-    int32_t batch;              /* B rows of q / page_table / seq_lens / out */
+    int32_t batch;              /* B rows of q / page_table / seq_lens / out; <= 8192 */
     int32_t num_q_heads;        /* Hq */
     int32_t num_kv_heads;       /* Hkv; Hq % Hkv == 0 and Hq / Hkv <= 16 */
     int32_t head_dim;           /* D: 64 or 128 */
@@ -182,10 +182,9 @@ typedef struct roll_attn_desc {
     int32_t num_pages;          /* pages in each pool (bounds the page ids) */
     int32_t out_dtype;          /* ROLL_BF16 or ROLL_F32 */
     float softmax_scale;        /* 0 => 1 / sqrt(D) */
-    int32_t chunk_tokens;       /* split-K chunk; 0 => library default; multiple of 128 */
-    int64_t max_total_tokens;   /* upper bound on sum of seq_lens; 0 => B * max_pages * P */
+    int32_t reserved;           /* must be 0 */
     void* ev_main_begin;        /* optional hipEvent_t recorded before / after the    */
-    void* ev_main_end;          /* split-K attention kernel (profiling); NULL = none  */
+    void* ev_main_end;          /* stream-K attention kernel (profiling); NULL = none */
 } roll_attn_desc;
 
 /* HOST. Bytes of DEVICE workspace roll_decode_attn needs for this desc. */
@@ -201,9 +200,10 @@ size_t roll_decode_attn_workspace_bytes(const roll_attn_desc* desc);
  *               clamped into that range
  *   out         DEVICE [B, Hq, D] of out_dtype
  *   workspace   DEVICE, 256-byte aligned, >= roll_decode_attn_workspace_bytes
- * All pointers 16-byte aligned.  Enqueues three kernels on stream: work-list
- * build, split-K partial attention, merge.  Two calls that share a workspace
- * must be ordered on one stream.
+ * All pointers 16-byte aligned.  Enqueues two kernels on stream: the persistent
+ * stream-K attention kernel and the merge of rows that were cut across waves.
+ * The workspace size does not depend on the sequence lengths.  Two calls that
+ * share a workspace must be ordered on one stream.
  */
 int roll_decode_attn(const void* q, const void* k_pages, const void* v_pages,
                      const int32_t* page_table, const int32_t* seq_lens,

@@ -46,7 +46,7 @@ class AttnDesc(C.Structure):
     _fields_ = [("batch", C.c_int32), ("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("page_size", C.c_int32), ("max_pages_per_seq", C.c_int32),
                 ("num_pages", C.c_int32), ("out_dtype", C.c_int32), ("softmax_scale", C.c_float),
-                ("chunk_tokens", C.c_int32), ("max_total_tokens", C.c_int64),
+                ("reserved", C.c_int32),
                 ("ev_main_begin", C.c_void_p), ("ev_main_end", C.c_void_p)]
 
 
@@ -206,11 +206,11 @@ def roll_kv_append_tokens(k_new, v_new, slots, positions, seq_lens, k_pages, v_p
 # attention
 # ----------------------------------------------------------------------------
 def attn_desc(q, k_pages, page_table, page_size, out_dtype=torch.bfloat16, softmax_scale=0.0,
-              chunk_tokens=0, max_total_tokens=0, ev_begin=None, ev_end=None) -> AttnDesc:
+              ev_begin=None, ev_end=None) -> AttnDesc:
     B, Hq, D = q.shape
     return AttnDesc(B, Hq, k_pages.shape[1], D, page_size, page_table.shape[1], k_pages.shape[0],
                     ROLL_F32 if out_dtype == torch.float32 else ROLL_BF16, softmax_scale,
-                    chunk_tokens, max_total_tokens, ev_begin, ev_end)
+                    0, ev_begin, ev_end)
 
 
 def roll_decode_attn_workspace_bytes(desc: AttnDesc) -> int:

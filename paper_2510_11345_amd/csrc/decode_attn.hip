@@ -1,6 +1,5 @@
-// Paged GQA decode attention for gfx950: work-list build, split-K partial
-// attention on the matrix cores, LDS-staged merge across the waves of a
-// workgroup, and a second-stage merge across chunks.
+// Paged GQA decode attention for gfx950: one persistent stream-K kernel on the
+// matrix cores plus a small merge of the pieces of rows that were cut.
 //
 // ROLL Flash (arXiv 2510.11345) Section 1: decoding is memory-bandwidth bound
 // and response lengths are long-tailed; Section 4.2: one step over the whole
@@ -8,16 +7,24 @@
 // stream each live KV byte exactly once at HBM speed while rows of very
 // different lengths share the chip evenly.
 //
-// Work decomposition.  Row b with L_b tokens is cut into ceil(L_b / C) chunks
-// of C tokens; one workgroup of kWaves wavefronts handles one (row, chunk, KV
-// head) unit, wave w taking the 32-token steps w, w + kWaves, ...  All G = Hq /
-// Hkv query heads that share the KV head ride in one MFMA tile, so a KV byte
-// is fetched once and used G times.
+// Work decomposition (split-K over the flattened batch).  Row b with L_b tokens
+// is ceil(L_b / 32) steps of 32 tokens for each KV head; the (row, KV head)
+// streams are laid end to end, S steps in all, and persistent wavefront w of W
+// takes the steps [w S / W, (w + 1) S / W).  Every wave therefore reads the same
+// number of bytes whatever the length mix, a row longer than a wave's share is
+// cut across neighbouring waves, and at most the first and the last stream of a
+// wave are pieces; a wave writes a complete stream straight to `out` and a piece
+// (running max, sum, un-normalised output) to its two slots of the workspace.
+// The row prefix sums that locate a wave's first step are rebuilt in LDS by
+// every workgroup (a few microseconds, no separate launch, no dependent
+// global loads on the way to the first KV byte).  All G = Hq / Hkv query heads
+// that share the KV head ride in one MFMA tile, so a KV byte is fetched once and
+// used G times.
 //
 // Per 32-token step and wave (lane = 16 * q + r):
 //   S^T[tok][g]  = K[tok][:] . Q[g][:]      2 tiles x (D/32) v_mfma_f32_16x16x32_bf16,
 //                  K rows as the A operand (16 bytes per lane straight from the page),
-//                  Q as the B operand (held in registers for the whole unit);
+//                  Q as the B operand (held in registers for the whole stream);
 //   online softmax per head g = r over the 8 scores a lane owns (tokens 8q..8q+7),
 //                  one cross-lane max over q per step;
 //   O^T[d][g]   += V^T[d][tok] . P^T[tok][g]  (D/16) x 2 MFMAs, V octets as the A operand,
@@ -30,6 +37,7 @@
 // long as K rows and V octets agree: tile tt, row 4*q'+i  <->  token 8*q' + 4*tt + i.
 #include <cfloat>
 #include <cmath>
+#include <mutex>
 
 #include "common.h"
 
@@ -40,109 +48,57 @@ typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
 typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 
-constexpr int kWaves = 4;          // wavefronts per workgroup
-constexpr bool kPipeline = false;   // issue the next step's loads before computing the current one
+constexpr int kGroupWaves = 4;     // wavefronts per workgroup (they only share the LDS prefix)
 constexpr int kStep = 32;          // tokens per wave step
-constexpr int kDefaultChunk = 512; // tokens per split-K chunk
-constexpr int kCounterInts = 64;   // 256-byte header of the workspace
+constexpr int kMinSteps = 4;       // do not spread a small batch thinner than this per wave
+constexpr int kMaxBatch = 8192;    // rows whose prefix sums fit the LDS budget
 
 struct AttnParams {
     int32_t B, Hq, Hkv, G;
     int32_t log2P, max_pages, num_pages;
-    int32_t chunk_tokens, max_len;
-    int32_t max_chunks;  // capacity of the work list and of the partial buffers
+    int32_t max_len;
+    int32_t W;        // persistent waves launched
     int32_t out_f32;
     float scale_log2e;
 };
 
 struct Workspace {
-    int32_t* counters;       // [0] = number of chunks
-    int32_t* chunk_offsets;  // [B + 1] exclusive prefix of chunks per row
-    int2* work;              // [max_chunks] (row, chunk index in row)
-    float2* part_ml;         // [max_chunks * Hq] (max in log2 units, sum)
-    float* part_acc;         // [max_chunks * Hq * D] un-normalised output
+    int32_t* row_off;  // [B + 1] exclusive prefix of steps per row (written by workgroup 0)
+    float2* part_ml;   // [2 W * G] (max in log2 units, sum) of a piece
+    float* part_acc;   // [2 W * G * D] un-normalised output of a piece
     size_t bytes;
-    int64_t max_chunks;
 };
 
 __host__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-__host__ Workspace carve(void* base, int32_t B, int32_t Hq, int32_t D, int32_t chunk, int64_t max_len,
-                         int64_t max_total) {
+__host__ Workspace carve(void* base, int32_t B, int32_t G, int32_t D, int32_t W) {
     Workspace w{};
-    const int64_t per_row = (max_len + chunk - 1) / chunk;
-    int64_t max_chunks = (int64_t)B * per_row;
-    if (max_total > 0) max_chunks = std::min<int64_t>(max_chunks, max_total / chunk + B);
-    if (max_chunks < 1) max_chunks = 1;
-    w.max_chunks = max_chunks;
     size_t off = 0;
     char* p = (char*)base;
-    w.counters = (int32_t*)(p + off);       off = align_up(off + sizeof(int32_t) * kCounterInts, 256);
-    w.chunk_offsets = (int32_t*)(p + off);  off = align_up(off + sizeof(int32_t) * ((size_t)B + 1), 256);
-    w.work = (int2*)(p + off);              off = align_up(off + sizeof(int2) * (size_t)max_chunks, 256);
-    w.part_ml = (float2*)(p + off);         off = align_up(off + sizeof(float2) * (size_t)max_chunks * Hq, 256);
-    w.part_acc = (float*)(p + off);         off = align_up(off + sizeof(float) * (size_t)max_chunks * Hq * D, 256);
+    w.row_off = (int32_t*)(p + off);  off = align_up(off + sizeof(int32_t) * ((size_t)B + 1), 256);
+    w.part_ml = (float2*)(p + off);   off = align_up(off + sizeof(float2) * 2 * (size_t)W * G, 256);
+    w.part_acc = (float*)(p + off);   off = align_up(off + sizeof(float) * 2 * (size_t)W * G * D, 256);
     w.bytes = off;
     return w;
 }
 
-// ---------------------------------------------------------------------------
-// Work list: chunks per row, exclusive prefix sum, flat (row, chunk) list.
-// One workgroup; rows are scanned in tiles of blockDim.x.
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void build_worklist(const int32_t* __restrict__ seq_lens,
-                                                        int32_t B, int32_t chunk, int32_t max_len,
-                                                        int64_t max_chunks,
-                                                        int32_t* __restrict__ counters,
-                                                        int32_t* __restrict__ chunk_offsets,
-                                                        int2* __restrict__ work) {
-    __shared__ int32_t s_scan[1024];
-    __shared__ int32_t s_carry;
-    const int tid = threadIdx.x;
-    if (tid == 0) s_carry = 0;
-    __syncthreads();
-    for (int32_t base = 0; base < B; base += blockDim.x) {
-        const int32_t b = base + tid;
-        int32_t n = 0;
-        if (b < B) {
-            int32_t L = seq_lens[b];
-            L = L < 0 ? 0 : (L > max_len ? max_len : L);
-            n = (L + chunk - 1) / chunk;
-        }
-        s_scan[tid] = n;
-        __syncthreads();
-        for (int off = 1; off < (int)blockDim.x; off <<= 1) {
-            int32_t v = tid >= off ? s_scan[tid - off] : 0;
-            __syncthreads();
-            s_scan[tid] += v;
-            __syncthreads();
-        }
-        const int32_t carry = s_carry;
-        const int32_t incl = s_scan[tid] + carry;
-        const int32_t excl = incl - n;
-        if (b < B) {
-            chunk_offsets[b] = excl;
-            for (int32_t c = 0; c < n; ++c)
-                if ((int64_t)excl + c < max_chunks) work[excl + c] = make_int2(b, c);
-        }
-        __syncthreads();
-        if (tid == (int)blockDim.x - 1) s_carry = incl;
-        __syncthreads();
+// How the S steps are dealt to waves; shared by the attention and the merge kernel.
+struct Deal {
+    int64_t S;   // total steps over all (row, KV head) streams
+    int32_t W;   // waves that take part
+    __device__ Deal(int64_t steps, int32_t launched) : S(steps) {
+        const int64_t want = (steps + kMinSteps - 1) / kMinSteps;
+        W = (int32_t)(want < 1 ? 1 : (want < launched ? want : launched));
     }
-    if (tid == 0) {
-        const int32_t total = s_carry;
-        chunk_offsets[B] = total;
-        counters[0] = (int64_t)total < max_chunks ? total : (int32_t)max_chunks;
-    }
-}
+    __device__ int64_t first_step(int32_t w) const { return (int64_t)w * S / W; }
+    // the wave whose range holds step i
+    __device__ int32_t owner(int64_t i) const { return (int32_t)(((i + 1) * W + S - 1) / S - 1); }
+};
 
-// ---------------------------------------------------------------------------
-// Split-K partial attention.
-// ---------------------------------------------------------------------------
 __device__ __forceinline__ bf16x8_t as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8_t, v); }
 
 // KV is read exactly once per step: a nontemporal load keeps it from displacing the
-// page table, Q and the partials in L2 (measured: +10 % on a plain streaming read).
+// page table, Q and the pieces in L2 (measured: +10 % on a plain streaming read).
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 load_stream(const uint4* p) {
     const u32x4_t v = __builtin_nontemporal_load((const u32x4_t*)p);
@@ -288,175 +244,243 @@ __device__ __forceinline__ void compute_step(const WaveCtx<D>& c, const bf16x8_t
     }
 }
 
-template <int D, bool PIPE>
-__global__ __launch_bounds__(kWaves * 64) void attn_partial(
+
+// Steps per row into LDS as an exclusive prefix, clamped lengths beside it.
+// pre has B + 1 entries, len has B.  All threads of the workgroup take part.
+__device__ void build_row_prefix(const int32_t* __restrict__ seq_lens, int32_t B, int32_t max_len,
+                                 int32_t* pre, int32_t* len, int32_t* s_wave_tot) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nthreads = blockDim.x, nwaves = nthreads >> 6;
+    int32_t carry = 0;
+    for (int32_t base = 0; base < B; base += nthreads) {
+        const int32_t b = base + tid;
+        int32_t L = 0;
+        if (b < B) {
+            L = seq_lens[b];
+            L = L < 0 ? 0 : (L > max_len ? max_len : L);
+            len[b] = L;
+        }
+        const int32_t n = (L + kStep - 1) / kStep;
+        int32_t incl = n;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int32_t v = __shfl_up(incl, d);
+            if (lane >= d) incl += v;
+        }
+        if (lane == 63) s_wave_tot[wave] = incl;
+        __syncthreads();
+        int32_t before = carry;
+        for (int w = 0; w < wave; ++w) before += s_wave_tot[w];
+        int32_t tile_total = 0;
+        for (int w = 0; w < nwaves; ++w) tile_total += s_wave_tot[w];
+        if (b < B) pre[b] = before + incl - n;
+        carry += tile_total;
+        __syncthreads();
+    }
+    if (tid == 0) pre[B] = carry;
+    __syncthreads();
+}
+
+template <int D>
+__global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
     const uint4* __restrict__ q16, const uint4* __restrict__ k_pages, const uint4* __restrict__ v_pages,
     const int32_t* __restrict__ page_table, const int32_t* __restrict__ seq_lens,
-    const int2* __restrict__ work, const int32_t* __restrict__ counters,
-    const int32_t* __restrict__ chunk_offsets, void* __restrict__ out, float2* __restrict__ part_ml,
+    void* __restrict__ out, int32_t* __restrict__ row_off, float2* __restrict__ part_ml,
     float* __restrict__ part_acc, AttnParams prm) {
-    extern __shared__ float smem[];
-    const int32_t total_units = counters[0] * prm.Hkv;
-    const int32_t unit = blockIdx.x;
-    if (unit >= total_units) return;
-    const int2 entry = work[unit / prm.Hkv];
-    const int32_t h = unit % prm.Hkv;
-    const int32_t b = entry.x, ci = entry.y;
-    int32_t L = seq_lens[b];
-    L = L < 0 ? 0 : (L > prm.max_len ? prm.max_len : L);
-    const int32_t start = ci * prm.chunk_tokens;
-    const int32_t end = min(L, start + prm.chunk_tokens);
-    const int32_t n_steps = (end - start + kStep - 1) / kStep;
-    const int32_t row_chunk0 = chunk_offsets[b];
-    const int32_t n_chunks = chunk_offsets[b + 1] - row_chunk0;
+    extern __shared__ int32_t lds[];
+    int32_t* pre = lds;                  // [B + 1]
+    int32_t* len = lds + prm.B + 1;      // [B]
+    __shared__ int32_t s_wave_tot[kGroupWaves];
+    build_row_prefix(seq_lens, prm.B, prm.max_len, pre, len, s_wave_tot);
+    if (blockIdx.x == 0)
+        for (int32_t i = threadIdx.x; i <= prm.B; i += blockDim.x) row_off[i] = pre[i];
 
     const int32_t lane = threadIdx.x & 63;
-    const int32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int32_t G = prm.G;
+    const int32_t w = blockIdx.x * kGroupWaves + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int32_t G = prm.G, Hkv = prm.Hkv;
+    const Deal deal((int64_t)pre[prm.B] * Hkv, prm.W);
+    if (w >= deal.W) return;
+    int64_t item = deal.first_step(w);
+    int32_t todo = (int32_t)(deal.first_step(w + 1) - item);
+    if (todo <= 0) return;
+
+    // Locate the first stream: the last row b with Hkv * pre[b] <= item (such a row is not empty).
+    int32_t b;
+    {
+        int32_t lo = 0, hi = prm.B;  // invariant: Hkv*pre[lo] <= item < Hkv*pre[hi]
+        while (hi - lo > 1) {
+            const int32_t mid = (lo + hi) >> 1;
+            if ((int64_t)pre[mid] * Hkv <= item) lo = mid; else hi = mid;
+        }
+        b = lo;
+    }
+    int32_t n_b = pre[b + 1] - pre[b];
+    const int32_t rem = (int32_t)(item - (int64_t)pre[b] * Hkv);
+    int32_t h = rem / n_b;
+    int32_t s = rem % n_b;
 
     WaveCtx<D> ctx;
     ctx.k_pages = k_pages;
     ctx.v_pages = v_pages;
-    ctx.pt_row = page_table + (int64_t)b * prm.max_pages;
-    ctx.h = h;
-    ctx.Hkv = prm.Hkv;
+    ctx.Hkv = Hkv;
     ctx.log2P = prm.log2P;
     ctx.num_pages = prm.num_pages;
     ctx.max_pages = prm.max_pages;
     ctx.r = lane & 15;
     ctx.q = lane >> 4;
 
-    // Q as the B operand: lane (r, q) holds head r, head-dim 32kk + 8q .. + 7; zero for r >= G.
-    bf16x8_t qf[D / 32];
-    {
-        const uint4 zero = make_uint4(0, 0, 0, 0);
-        const uint4* qrow = q16 + ((int64_t)b * prm.Hq + (int64_t)h * G + ctx.r) * (D / 8) + ctx.q;
-#pragma unroll
-        for (int kk = 0; kk < D / 32; ++kk) qf[kk] = as_bf16x8(ctx.r < G ? qrow[kk * 4] : zero);
-    }
+    bool first_stream = true;
+    while (todo > 0) {
+        const int32_t L = len[b];
+        const int32_t cnt = min(todo, n_b - s);
+        ctx.pt_row = page_table + (int64_t)b * prm.max_pages;
+        ctx.h = h;
 
-    WaveAcc<D> acc;
+        // Q as the B operand: lane (r, q) holds head r, head-dim 32kk + 8q .. + 7; zero for r >= G.
+        bf16x8_t qf[D / 32];
+        {
+            const uint4 zero = make_uint4(0, 0, 0, 0);
+            const uint4* qrow = q16 + ((int64_t)b * prm.Hq + (int64_t)h * G + ctx.r) * (D / 8) + ctx.q;
 #pragma unroll
-    for (int nt = 0; nt < D / 16; ++nt) acc.o[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    acc.m = -INFINITY;
-    acc.l = 0.f;
+            for (int kk = 0; kk < D / 32; ++kk) qf[kk] = as_bf16x8(ctx.r < G ? qrow[kk * 4] : zero);
+        }
+        WaveAcc<D> acc;
+#pragma unroll
+        for (int nt = 0; nt < D / 16; ++nt) acc.o[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        acc.m = -INFINITY;
+        acc.l = 0.f;
 
-    if (PIPE) {
-        StepData<D> s0, s1;
-        int32_t s = wave;
-        if (s < n_steps) {
-            load_step<D>(ctx, start + s * kStep, s0);
-            for (;;) {
-                const int32_t sn = s + kWaves;
-                const bool has1 = sn < n_steps;
-                if (has1) load_step<D>(ctx, start + sn * kStep, s1);
-                compute_step<D>(ctx, qf, s0, start + s * kStep, end, prm.scale_log2e, acc);
-                if (!has1) break;
-                s = sn + kWaves;
-                const bool has0 = s < n_steps;
-                if (has0) load_step<D>(ctx, start + s * kStep, s0);
-                compute_step<D>(ctx, qf, s1, start + sn * kStep, end, prm.scale_log2e, acc);
-                if (!has0) break;
+        for (int32_t i = s; i < s + cnt; ++i) {
+            StepData<D> sd;
+            load_step<D>(ctx, i * kStep, sd);
+            compute_step<D>(ctx, qf, sd, i * kStep, L, prm.scale_log2e, acc);
+        }
+
+        // Finish the per-head sum across the four q-groups of the wave.
+        acc.l += __shfl_xor(acc.l, 16);
+        acc.l += __shfl_xor(acc.l, 32);
+
+        if (ctx.r < G) {
+            const int32_t head = h * G + ctx.r;
+            if (cnt == n_b) {  // the whole stream: normalise and write the result
+                const float inv = 1.0f / acc.l;
+                const int64_t idx = ((int64_t)b * prm.Hq + head) * D + 4 * ctx.q;
+#pragma unroll
+                for (int nt = 0; nt < D / 16; ++nt) {
+                    const f32x4_t o = acc.o[nt] * inv;
+                    if (prm.out_f32) {
+                        *(f32x4_t*)((float*)out + idx + 16 * nt) = o;
+                    } else {
+                        uint2 pk;
+                        pk.x = pack_bf16_rne(o[0], o[1]);
+                        pk.y = pack_bf16_rne(o[2], o[3]);
+                        *(uint2*)((__bf16*)out + idx + 16 * nt) = pk;
+                    }
+                }
+            } else {           // a piece: slot 2w for the wave's first stream, 2w + 1 otherwise
+                const int64_t slot = ((int64_t)2 * w + (first_stream ? 0 : 1)) * G + ctx.r;
+                if (ctx.q == 0) part_ml[slot] = make_float2(acc.m, acc.l);
+                float* dst = part_acc + slot * D + 4 * ctx.q;
+#pragma unroll
+                for (int nt = 0; nt < D / 16; ++nt) *(f32x4_t*)(dst + 16 * nt) = acc.o[nt];
             }
         }
-    } else {
-        for (int32_t s = wave; s < n_steps; s += kWaves) {
-            StepData<D> sd;
-            load_step<D>(ctx, start + s * kStep, sd);
-            compute_step<D>(ctx, qf, sd, start + s * kStep, end, prm.scale_log2e, acc);
-        }
-    }
 
-    // Finish the per-head sum across the four q-groups of the wave.
-    acc.l += __shfl_xor(acc.l, 16);
-    acc.l += __shfl_xor(acc.l, 32);
-
-    // LDS-staged merge across the waves of the workgroup.
-    const int32_t ldo = D + 4;                           // padded row of the O staging tile
-    float* s_m = smem;                                   // [kWaves][16]
-    float* s_l = smem + kWaves * 16;                     // [kWaves][16]
-    float* s_o = smem + 2 * kWaves * 16;                 // [kWaves][G][ldo]
-    if (ctx.q == 0) {
-        s_m[wave * 16 + ctx.r] = acc.m;
-        s_l[wave * 16 + ctx.r] = acc.l;
-    }
-    if (ctx.r < G) {
-        float* dst = s_o + ((int64_t)(wave * G + ctx.r)) * ldo + 4 * ctx.q;
-#pragma unroll
-        for (int nt = 0; nt < D / 16; ++nt) *(f32x4_t*)(dst + 16 * nt) = acc.o[nt];
-    }
-    __syncthreads();
-
-    const int32_t chunk_global = row_chunk0 + ci;
-    for (int32_t e = threadIdx.x; e < G * D; e += kWaves * 64) {
-        const int32_t g = e / D, d = e % D;
-        float M = s_m[g];
-#pragma unroll
-        for (int w = 1; w < kWaves; ++w) M = fmaxf(M, s_m[w * 16 + g]);
-        float lsum = 0.f, o = 0.f;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            const float wgt = __builtin_amdgcn_exp2f(s_m[w * 16 + g] - M);  // 0 for an idle wave
-            lsum += s_l[w * 16 + g] * wgt;
-            o += s_o[(w * G + g) * ldo + d] * wgt;
-        }
-        const int32_t head = h * G + g;
-        if (n_chunks == 1) {
-            const float val = o / lsum;
-            const int64_t idx = ((int64_t)b * prm.Hq + head) * D + d;
-            if (prm.out_f32) ((float*)out)[idx] = val;
-            else ((__bf16*)out)[idx] = (__bf16)val;
-        } else {
-            const int64_t ph = (int64_t)chunk_global * prm.Hq + head;
-            part_acc[ph * D + d] = o;
-            if (d == 0) part_ml[ph] = make_float2(M, lsum);
+        todo -= cnt;
+        first_stream = false;
+        s = 0;
+        if (todo > 0) {  // next stream: next KV head, or the next row that has tokens
+            if (++h == Hkv) {
+                h = 0;
+                do { ++b; } while (b < prm.B - 1 && pre[b + 1] == pre[b]);
+                n_b = pre[b + 1] - pre[b];
+            }
         }
     }
 }
 
 // ---------------------------------------------------------------------------
-// Second-stage merge across the chunks of a row; also zero-fills empty rows.
-// One workgroup per (row, KV head); a thread owns (head, d) outputs.
+// Merge of the pieces of every (row, KV head) stream that was cut across waves;
+// also zero-fills empty rows.  One workgroup per stream; the piece weights are
+// staged in LDS, then a thread owns (head, d) outputs.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void attn_merge(const int32_t* __restrict__ seq_lens,
-                                                   const int32_t* __restrict__ chunk_offsets,
+__global__ __launch_bounds__(256) void attn_merge(const int32_t* __restrict__ row_off,
                                                    const float2* __restrict__ part_ml,
                                                    const float* __restrict__ part_acc,
                                                    void* __restrict__ out, int32_t D, AttnParams prm) {
+    __shared__ float s_max[16], s_inv[16];  // per head: max over pieces, 1 / normalising sum
     const int32_t b = blockIdx.x / prm.Hkv;
     const int32_t h = blockIdx.x % prm.Hkv;
-    const int32_t c0 = chunk_offsets[b];
-    const int32_t n_all = chunk_offsets[b + 1] - c0;
-    if (n_all == 1) return;
-    // Chunks past the capacity were never computed (the caller's max_total_tokens was too low).
-    const int32_t n = c0 + n_all <= prm.max_chunks ? n_all : (c0 < prm.max_chunks ? prm.max_chunks - c0 : 0);
     const int32_t G = prm.G;
-    for (int32_t e = threadIdx.x; e < G * D; e += blockDim.x) {
-        const int32_t g = e / D, d = e % D;
-        const int32_t head = h * G + g;
-        float val = 0.f;
-        if (n > 1) {
-            float M = -INFINITY;
-            for (int32_t c = 0; c < n; ++c) M = fmaxf(M, part_ml[(int64_t)(c0 + c) * prm.Hq + head].x);
-            float lsum = 0.f, o = 0.f;
-            for (int32_t c = 0; c < n; ++c) {
-                const int64_t ph = (int64_t)(c0 + c) * prm.Hq + head;
-                const float2 ml = part_ml[ph];
-                const float wgt = __builtin_amdgcn_exp2f(ml.x - M);
-                lsum += ml.y * wgt;
-                o += part_acc[ph * D + d] * wgt;
-            }
-            val = o / lsum;
+    const int32_t n_b = row_off[b + 1] - row_off[b];
+    const int64_t base_out = ((int64_t)b * prm.Hq + (int64_t)h * G) * D;
+    if (n_b == 0) {
+        for (int32_t e = threadIdx.x; e < G * D; e += blockDim.x) {
+            if (prm.out_f32) ((float*)out)[base_out + e] = 0.f;
+            else ((__bf16*)out)[base_out + e] = (__bf16)0.f;
         }
-        const int64_t idx = ((int64_t)b * prm.Hq + head) * D + d;
-        if (prm.out_f32) ((float*)out)[idx] = val;
-        else ((__bf16*)out)[idx] = (__bf16)val;
+        return;
+    }
+    const Deal deal((int64_t)row_off[prm.B] * prm.Hkv, prm.W);
+    const int64_t g0 = (int64_t)row_off[b] * prm.Hkv + (int64_t)h * n_b;
+    const int32_t w0 = deal.owner(g0), w1 = deal.owner(g0 + n_b - 1);
+    if (w0 == w1) return;  // written whole by its wave
+    const int32_t pieces = w1 - w0 + 1;
+    // slot of piece p (wave w0 + p): the wave's first stream (2w) unless w0 entered it mid-range
+    const int32_t slot0 = 2 * w0 + (deal.first_step(w0) == g0 ? 0 : 1);
+    auto slot_of = [&](int32_t p) -> int64_t { return p == 0 ? slot0 : 2 * (w0 + p); };
+
+    for (int32_t g = threadIdx.x; g < G; g += blockDim.x) {
+        float M = -INFINITY;
+        for (int32_t p = 0; p < pieces; ++p) M = fmaxf(M, part_ml[slot_of(p) * G + g].x);
+        float lsum = 0.f;
+        for (int32_t p = 0; p < pieces; ++p) {
+            const float2 ml = part_ml[slot_of(p) * G + g];
+            lsum += ml.y * __builtin_amdgcn_exp2f(ml.x - M);
+        }
+        s_max[g] = M;
+        s_inv[g] = 1.0f / lsum;
+    }
+    __syncthreads();
+    // A thread owns 4 consecutive head-dim outputs of one head.
+    for (int32_t e4 = threadIdx.x; e4 < G * D / 4; e4 += blockDim.x) {
+        const int32_t g = (e4 * 4) / D;
+        const float M = s_max[g], inv = s_inv[g];
+        f32x4_t o = {0.f, 0.f, 0.f, 0.f};
+        int32_t p = 0;
+        for (; p + 4 <= pieces; p += 4) {
+            f32x4_t v[4];
+            float wgt[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t slot = slot_of(p + u);
+                v[u] = *(const f32x4_t*)(part_acc + slot * G * D + (int64_t)e4 * 4);
+                wgt[u] = part_ml[slot * G + g].x;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) o += v[u] * __builtin_amdgcn_exp2f(wgt[u] - M);
+        }
+        for (; p < pieces; ++p) {
+            const int64_t slot = slot_of(p);
+            const f32x4_t v = *(const f32x4_t*)(part_acc + slot * G * D + (int64_t)e4 * 4);
+            o += v * __builtin_amdgcn_exp2f(part_ml[slot * G + g].x - M);
+        }
+        o *= inv;
+        const int64_t idx = base_out + (int64_t)e4 * 4;
+        if (prm.out_f32) {
+            *(f32x4_t*)((float*)out + idx) = o;
+        } else {
+            uint2 pk;
+            pk.x = pack_bf16_rne(o[0], o[1]);
+            pk.y = pack_bf16_rne(o[2], o[3]);
+            *(uint2*)((__bf16*)out + idx) = pk;
+        }
     }
 }
 
 int validate(const roll_attn_desc* d) {
     if (!d) return roll::fail(ROLL_ERR_INVALID_ARG, "desc is NULL");
-    if (d->batch <= 0) return roll::fail(ROLL_ERR_INVALID_ARG, "batch must be > 0");
+    if (d->batch <= 0 || d->batch > kMaxBatch) return roll::fail(ROLL_ERR_INVALID_ARG, "batch must be in [1, %d]", kMaxBatch);
     if (d->num_q_heads <= 0 || d->num_kv_heads <= 0 || d->num_q_heads % d->num_kv_heads != 0)
         return roll::fail(ROLL_ERR_INVALID_ARG, "num_q_heads must be a positive multiple of num_kv_heads");
     if (d->num_q_heads / d->num_kv_heads > 16)
@@ -465,23 +489,47 @@ int validate(const roll_attn_desc* d) {
     if (d->page_size != 16 && d->page_size != 32 && d->page_size != 64)
         return roll::fail(ROLL_ERR_INVALID_ARG, "page_size must be 16, 32 or 64");
     if (d->max_pages_per_seq <= 0 || d->num_pages <= 0) return roll::fail(ROLL_ERR_INVALID_ARG, "max_pages_per_seq and num_pages must be > 0");
-    if ((int64_t)d->max_pages_per_seq * d->page_size > (1 << 30))
-        return roll::fail(ROLL_ERR_INVALID_ARG, "max_pages_per_seq * page_size above 2^30 tokens");
+    if ((int64_t)d->max_pages_per_seq * d->page_size > (1 << 24))
+        return roll::fail(ROLL_ERR_INVALID_ARG, "max_pages_per_seq * page_size above 2^24 tokens");
     if (d->out_dtype != ROLL_BF16 && d->out_dtype != ROLL_F32) return roll::fail(ROLL_ERR_INVALID_ARG, "out_dtype must be ROLL_BF16 or ROLL_F32");
-    if (d->chunk_tokens < 0 || d->chunk_tokens % (kWaves * kStep) != 0)
-        return roll::fail(ROLL_ERR_INVALID_ARG, "chunk_tokens must be 0 or a multiple of %d", kWaves * kStep);
     if (!(d->softmax_scale >= 0.f) || std::isinf(d->softmax_scale)) return roll::fail(ROLL_ERR_INVALID_ARG, "softmax_scale must be finite and >= 0");
-    if (d->max_total_tokens < 0) return roll::fail(ROLL_ERR_INVALID_ARG, "max_total_tokens < 0");
     return ROLL_OK;
 }
+
+// Persistent waves to launch: what the device holds at once for this kernel.
+int persistent_waves(int head_dim, size_t lds_bytes, int32_t* waves_out) {
+    static std::mutex mu;
+    static int cached[2] = {0, 0};
+    std::lock_guard<std::mutex> lock(mu);
+    int& c = cached[head_dim == 128];
+    if (c > 0) {
+        *waves_out = c;
+        return ROLL_OK;
+    }
+    int dev = 0;
+    ROLL_HIP_CHECK(hipGetDevice(&dev));
+    hipDeviceProp_t prop;
+    ROLL_HIP_CHECK(hipGetDeviceProperties(&prop, dev));
+    int groups = 0;
+    if (head_dim == 128)
+        ROLL_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&groups, attn_stream<128>, kGroupWaves * 64, lds_bytes));
+    else
+        ROLL_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&groups, attn_stream<64>, kGroupWaves * 64, lds_bytes));
+    if (groups < 1) groups = 1;
+    c = groups * kGroupWaves * prop.multiProcessorCount;
+    *waves_out = c;
+    return ROLL_OK;
+}
+
+// Upper bound used to size the workspace without touching the device: 16 waves on each of
+// 256 compute units (a gfx950 device has no more).
+constexpr int32_t kMaxPersistentWaves = 16 * 256;
 
 }  // namespace
 
 extern "C" size_t roll_decode_attn_workspace_bytes(const roll_attn_desc* d) {
     if (validate(d) != ROLL_OK) return 0;
-    const int32_t chunk = d->chunk_tokens ? d->chunk_tokens : kDefaultChunk;
-    return carve(nullptr, d->batch, d->num_q_heads, d->head_dim, chunk,
-                 (int64_t)d->max_pages_per_seq * d->page_size, d->max_total_tokens).bytes;
+    return carve(nullptr, d->batch, d->num_q_heads / d->num_kv_heads, d->head_dim, kMaxPersistentWaves).bytes;
 }
 
 extern "C" int roll_decode_attn(const void* q, const void* k_pages, const void* v_pages,
@@ -495,50 +543,49 @@ extern "C" int roll_decode_attn(const void* q, const void* k_pages, const void* 
     if (!roll::aligned(q, 16) || !roll::aligned(k_pages, 16) || !roll::aligned(v_pages, 16) || !roll::aligned(out, 16) ||
         !roll::aligned(page_table, 4) || !roll::aligned(seq_lens, 4))
         return roll::fail(ROLL_ERR_INVALID_ARG, "q, k_pages, v_pages, out must be 16-byte aligned");
-    const int32_t chunk = d->chunk_tokens ? d->chunk_tokens : kDefaultChunk;
-    const int64_t max_len = (int64_t)d->max_pages_per_seq * d->page_size;
+    const int32_t G = d->num_q_heads / d->num_kv_heads;
     if (!workspace || !roll::aligned(workspace, 256)) return roll::fail(ROLL_ERR_WORKSPACE, "workspace NULL or not 256-byte aligned");
-    Workspace ws = carve(workspace, d->batch, d->num_q_heads, d->head_dim, chunk, max_len, d->max_total_tokens);
+    Workspace ws = carve(workspace, d->batch, G, d->head_dim, kMaxPersistentWaves);
     if (workspace_bytes < ws.bytes)
         return roll::fail(ROLL_ERR_WORKSPACE, "workspace too small: %zu < %zu bytes", workspace_bytes, ws.bytes);
-    if (ws.max_chunks * d->num_kv_heads * 2 > INT32_MAX) return roll::fail(ROLL_ERR_INVALID_ARG, "too many work units");
+
+    const size_t lds = sizeof(int32_t) * (2 * (size_t)d->batch + 1);
+    int32_t W = 0;
+    rc = persistent_waves(d->head_dim, lds, &W);
+    if (rc != ROLL_OK) return rc;
+    if (W > kMaxPersistentWaves) W = kMaxPersistentWaves;
+    W = W / kGroupWaves * kGroupWaves;
 
     hipStream_t stream = (hipStream_t)stream_v;
     AttnParams prm{};
     prm.B = d->batch;
     prm.Hq = d->num_q_heads;
     prm.Hkv = d->num_kv_heads;
-    prm.G = d->num_q_heads / d->num_kv_heads;
+    prm.G = G;
     prm.log2P = d->page_size == 16 ? 4 : (d->page_size == 32 ? 5 : 6);
     prm.max_pages = d->max_pages_per_seq;
     prm.num_pages = d->num_pages;
-    prm.chunk_tokens = chunk;
-    prm.max_len = (int32_t)max_len;
-    prm.max_chunks = (int32_t)ws.max_chunks;
+    prm.max_len = (int32_t)((int64_t)d->max_pages_per_seq * d->page_size);
+    prm.W = W;
     prm.out_f32 = d->out_dtype == ROLL_F32;
     const float scale = d->softmax_scale > 0.f ? d->softmax_scale : 1.0f / sqrtf((float)d->head_dim);
     prm.scale_log2e = scale * 1.44269504088896340736f;
 
-    build_worklist<<<1, 1024, 0, stream>>>(seq_lens, d->batch, chunk, prm.max_len, ws.max_chunks,
-                                           ws.counters, ws.chunk_offsets, ws.work);
-    ROLL_HIP_CHECK(hipGetLastError());
-
-    const unsigned grid = (unsigned)(ws.max_chunks * d->num_kv_heads);
-    const size_t lds = sizeof(float) * (2 * kWaves * 16 + (size_t)kWaves * prm.G * (d->head_dim + 4));
+    const unsigned grid = (unsigned)(W / kGroupWaves);
     if (d->ev_main_begin) ROLL_HIP_CHECK(hipEventRecord((hipEvent_t)d->ev_main_begin, stream));
     if (d->head_dim == 128)
-        attn_partial<128, kPipeline><<<grid, kWaves * 64, lds, stream>>>(
-            (const uint4*)q, (const uint4*)k_pages, (const uint4*)v_pages, page_table, seq_lens, ws.work,
-            ws.counters, ws.chunk_offsets, out, ws.part_ml, ws.part_acc, prm);
+        attn_stream<128><<<grid, kGroupWaves * 64, lds, stream>>>(
+            (const uint4*)q, (const uint4*)k_pages, (const uint4*)v_pages, page_table, seq_lens, out,
+            ws.row_off, ws.part_ml, ws.part_acc, prm);
     else
-        attn_partial<64, kPipeline><<<grid, kWaves * 64, lds, stream>>>(
-            (const uint4*)q, (const uint4*)k_pages, (const uint4*)v_pages, page_table, seq_lens, ws.work,
-            ws.counters, ws.chunk_offsets, out, ws.part_ml, ws.part_acc, prm);
+        attn_stream<64><<<grid, kGroupWaves * 64, lds, stream>>>(
+            (const uint4*)q, (const uint4*)k_pages, (const uint4*)v_pages, page_table, seq_lens, out,
+            ws.row_off, ws.part_ml, ws.part_acc, prm);
     ROLL_HIP_CHECK(hipGetLastError());
     if (d->ev_main_end) ROLL_HIP_CHECK(hipEventRecord((hipEvent_t)d->ev_main_end, stream));
 
-    attn_merge<<<d->batch * d->num_kv_heads, 256, 0, stream>>>(seq_lens, ws.chunk_offsets, ws.part_ml,
-                                                              ws.part_acc, out, d->head_dim, prm);
+    attn_merge<<<d->batch * d->num_kv_heads, 256, 0, stream>>>(ws.row_off, ws.part_ml, ws.part_acc, out,
+                                                              d->head_dim, prm);
     ROLL_HIP_CHECK(hipGetLastError());
     return ROLL_OK;
 }

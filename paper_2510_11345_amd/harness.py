@@ -23,7 +23,7 @@ class DecodeBatch:
     """
 
     def __init__(self, cfg: wl.DecodeConfig, seed: int, lengths: np.ndarray, headroom_tokens: int = 0,
-                 out_dtype=torch.bfloat16, chunk_tokens: int = 0, device: str = "cuda",
+                 out_dtype=torch.bfloat16, device: str = "cuda",
                  spare_pages: int = 64, max_len: int | None = None, fill_pools: bool = True,
                  profile_events: bool = False):
         self.cfg, self.seed, self.device = cfg, seed, device
@@ -56,10 +56,10 @@ class DecodeBatch:
         self.ev_pairs = []   # (begin, end, sum of seq_lens) per profiled step
         self.ev_spare = []   # pre-created event pairs, so that none is created inside a timed loop
         self.profile_events = profile_events
-        self.chunk_tokens = chunk_tokens
         self.out_dtype = out_dtype
-        self._desc_total = -1
-        self._ws = None
+        self.desc = rb.attn_desc(self.q, self.k_pages, self.page_table, P, out_dtype)
+        self._ws = torch.empty(rb.roll_decode_attn_workspace_bytes(self.desc), dtype=torch.uint8,
+                               device=device)
         self.grow_to(lengths)
 
     # -- allocator ------------------------------------------------------------
@@ -80,17 +80,6 @@ class DecodeBatch:
         return int(self.lengths.sum())
 
     # -- one decode step --------------------------------------------------------
-    def _attn_desc(self):
-        # the bound only has to hold for the calls made with this descriptor
-        bound = self.total_tokens() + 64 * self.cfg.batch
-        if self._ws is None or bound > self._desc_total:
-            self._desc_total = bound + 4096 * self.cfg.batch
-            self.desc = rb.attn_desc(self.q, self.k_pages, self.page_table, self.cfg.page_size,
-                                     self.out_dtype, 0.0, self.chunk_tokens, self._desc_total)
-            nbytes = rb.roll_decode_attn_workspace_bytes(self.desc)
-            self._ws = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
-        return self.desc
-
     def step(self, logits: torch.Tensor, step_index: int, temperature=None, top_p=None,
              grow: bool = True) -> None:
         """alloc (+1 token per row) -> commit -> append K/V -> attention -> sample."""
@@ -101,7 +90,7 @@ class DecodeBatch:
             rb.roll_kv_commit(self.pool)
             rb.roll_kv_append_tokens(self.k_new, self.v_new, None, None, self.seq_lens, self.k_pages,
                                      self.v_pages, self.page_table, cfg.page_size)
-        desc = self._attn_desc()
+        desc = self.desc
         if self.profile_events:
             e0, e1 = self.ev_spare.pop() if self.ev_spare else (rb.ProfEvent(), rb.ProfEvent())
             desc.ev_main_begin, desc.ev_main_end = e0.handle.value, e1.handle.value

@@ -11,8 +11,7 @@ def say(msg):
     print(msg, flush=True)
 
 
-def run_attn(inp, cfg, out_dtype=torch.float32, chunk_tokens=0, softmax_scale=0.0,
-             max_total_tokens=0, seq_lens=None):
+def run_attn(inp, cfg, out_dtype=torch.float32, softmax_scale=0.0, seq_lens=None):
     """inp: dict from workloads.make_attn_inputs (cpu or cuda tensors). Returns out on host (float64)."""
     dev = "cuda"
     q = inp["q"].to(dev)
@@ -22,8 +21,7 @@ def run_attn(inp, cfg, out_dtype=torch.float32, chunk_tokens=0, softmax_scale=0.
     lens = torch.from_numpy(np.ascontiguousarray(inp["seq_lens"] if seq_lens is None else seq_lens)).to(dev)
     B, Hq, D = q.shape
     out = torch.full((B, Hq, D), float("nan"), dtype=out_dtype, device=dev)
-    desc = rb.attn_desc(q, k_pages, table, cfg.page_size, out_dtype, softmax_scale, chunk_tokens,
-                        max_total_tokens)
+    desc = rb.attn_desc(q, k_pages, table, cfg.page_size, out_dtype, softmax_scale)
     ws = torch.empty(rb.roll_decode_attn_workspace_bytes(desc), dtype=torch.uint8, device=dev)
     rb.roll_decode_attn(q, k_pages, v_pages, table, lens, out, desc, ws)
     torch.cuda.synchronize()

@@ -123,11 +123,11 @@ def test_bad_pool_config_is_rejected():
 
 def test_attention_and_sampling_reject_bad_descriptors_on_the_host():
     L = rb.lib()
-    good = rb.AttnDesc(4, 8, 2, 64, 16, 8, 32, rb.ROLL_BF16, 0.0, 0, 0, None, None)
+    good = rb.AttnDesc(4, 8, 2, 64, 16, 8, 32, rb.ROLL_BF16, 0.0, 0, None, None)
     assert L.roll_decode_attn_workspace_bytes(C.byref(good)) > 0
-    for field, val in [("head_dim", 96), ("num_kv_heads", 3), ("page_size", 8), ("chunk_tokens", 100),
+    for field, val in [("head_dim", 96), ("num_kv_heads", 3), ("page_size", 8), ("batch", 8193),
                        ("batch", 0), ("out_dtype", 7), ("num_q_heads", 64)]:
-        d = rb.AttnDesc(4, 8, 2, 64, 16, 8, 32, rb.ROLL_BF16, 0.0, 0, 0, None, None)
+        d = rb.AttnDesc(4, 8, 2, 64, 16, 8, 32, rb.ROLL_BF16, 0.0, 0, None, None)
         if field == "num_q_heads":
             d.num_kv_heads = 2  # group of 32 > 16
         setattr(d, field, val)

@@ -17,17 +17,17 @@ EDGE_LENGTHS = [1, 2, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 511, 51
                 1025, 1537, 2048, 2049]
 
 
-def check(cfg, lengths, seed, chunk_tokens=0, bf16_too=True, scale=0.0):
+def check(cfg, lengths, seed, bf16_too=True, scale=0.0):
     say(f"  attn case {cfg.name} B={len(lengths)} Hq={cfg.num_q_heads} Hkv={cfg.num_kv_heads} "
-        f"D={cfg.head_dim} P={cfg.page_size} chunk={chunk_tokens} seed={seed} maxL={max(lengths)}")
+        f"D={cfg.head_dim} P={cfg.page_size} seed={seed} maxL={max(lengths)}")
     inp = wl.make_attn_inputs(cfg, seed, "cpu", lengths=np.asarray(lengths, np.int32))
     ref = oracle_attn(inp, cfg, scale=scale if scale else None)
-    got = run_attn(inp, cfg, torch.float32, chunk_tokens, softmax_scale=scale)
+    got = run_attn(inp, cfg, torch.float32, softmax_scale=scale)
     err = np.abs(got - ref).max()
     say(f"    fp32 out: max abs err {err:.3e}")
     assert np.isfinite(got).all() and err <= TOL_F32
     if bf16_too:
-        got16 = run_attn(inp, cfg, torch.bfloat16, chunk_tokens, softmax_scale=scale)
+        got16 = run_attn(inp, cfg, torch.bfloat16, softmax_scale=scale)
         err16 = np.abs(got16 - ref).max()
         say(f"    bf16 out: max abs err {err16:.3e}")
         assert np.isfinite(got16).all() and err16 <= TOL_BF16
@@ -39,10 +39,23 @@ def test_config1_exact_shape():
     check(cfg, wl.draw_lengths(cfg.lengths, cfg.batch, 0), seed=0)
 
 
-@pytest.mark.parametrize("chunk", [0, 128, 256, 1024])
-def test_7b_shape_edge_lengths(chunk):
+def test_7b_shape_edge_lengths():
     cfg = wl.CONFIGS["c2"]
-    check(cfg, EDGE_LENGTHS, seed=1, chunk_tokens=chunk, bf16_too=(chunk == 0))
+    check(cfg, EDGE_LENGTHS, seed=1)
+
+
+@pytest.mark.parametrize("lengths", [[40000], [3, 30000, 5], [1] * 40, [33] * 300, [20000, 20000, 1, 0, 7]])
+def test_rows_cut_across_many_waves_and_tiny_batches(lengths):
+    # one row longer than all the others together is spread over hundreds of waves; a batch of
+    # one-token rows leaves most waves idle; both ends of the work dealing
+    cfg = wl.CONFIGS["c2"]
+    lens = np.asarray(lengths, np.int32)
+    inp = wl.make_attn_inputs(cfg, 11, "cpu", lengths=np.maximum(lens, 1))
+    ref = oracle_attn(inp, cfg, seq_lens=lens)
+    got = run_attn(inp, cfg, torch.float32, seq_lens=lens)
+    err = np.abs(got - ref).max()
+    say(f"  attn cut-rows case {lengths[:5]}... max abs err {err:.3e}")
+    assert np.isfinite(got).all() and err <= TOL_F32
 
 
 def test_7b_shape_lognormal_lengths():
