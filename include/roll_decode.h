@@ -31,11 +31,19 @@
  * KV page layout (both pools hold num_pages pages of page_size tokens for
  * num_kv_heads heads of head_dim elements, bf16).  The layouts are chosen
  * so that the matrix-core operands of the attention kernel are 16-byte
- * contiguous per lane; the writer (roll_kv_append_tokens) pays the
- * transposition once, the reader (every later decode step) never does.
- *   K:  k_pages[page][h][d / 8][t][d % 8]     shape [N, Hkv, D/8, P, 8]
- *   V:  v_pages[page][h][t / 8][d][t % 8]     shape [N, Hkv, P/8, D, 8]
- * with t the token's position inside the page, d the head-dim index.
+ * contiguous per lane and every load instruction of a wave covers whole
+ * 128-byte lines; the writer (roll_kv_append_tokens) pays the transposition
+ * once, the reader (every later decode step) never does.
+ *   K:  k_pages[page][h][d / 8][kpos(t)][d % 8]   shape [N, Hkv, D/8, P, 8]
+ *   V:  v_pages[page][h][t / 8][d][t % 8]         shape [N, Hkv, P/8, D, 8]
+ * with t the token's position inside the page, d the head-dim index, and
+ * kpos a fixed permutation of the token order inside blocks of W = min(P, 32)
+ * tokens: for t = W * blk + u,
+ *   kpos(t) = W * blk + (u & 3) + 4 * (u >> 3) + (W / 2) * ((u >> 2) & 1)
+ * i.e. of every 8 consecutive tokens the first four go to the first half of
+ * the block and the last four to the second half.  (The score tile of the
+ * attention kernel hands each lane four consecutive tokens of either half;
+ * with this order the K rows of one tile are contiguous in memory.)
  */
 #ifndef ROLL_DECODE_H
 #define ROLL_DECODE_H

@@ -47,6 +47,8 @@ def lib():
         L.oracle_v_index.restype = C.c_int64
         for f in (L.oracle_k_index, L.oracle_v_index):
             f.argtypes = [C.c_int64] + [C.c_int] * 6
+        L.oracle_k_slot.restype = C.c_int
+        L.oracle_k_slot.argtypes = [C.c_int, C.c_int]
         L.oracle_top_p_cut.restype = C.c_double
         L.oracle_top_p_cut.argtypes = [C.POINTER(C.c_double), C.c_int, C.c_double, C.c_double]
         L.oracle_decode_attn.restype = C.c_int
@@ -65,6 +67,10 @@ def philox4x32_10(ctr, key):
 
 def uniform(seed, step, row_id, i):
     return float(lib().oracle_uniform(int(seed), int(step), int(row_id), int(i)))
+
+
+def k_slot(t, P):
+    return int(lib().oracle_k_slot(t, P))
 
 
 def k_index(page, h, t, d, Hkv, D, P):

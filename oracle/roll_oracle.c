@@ -104,12 +104,27 @@ double oracle_uniform(uint64_t seed, uint64_t step, uint32_t row_id, uint32_t i)
 
 /* ------------------------------------------------------------------ */
 /* Paged KV cache: index formulas of the two page layouts              */
-/*   K: [page][h][d / 8][t][d % 8]     V: [page][h][t / 8][d][t % 8]   */
+/*   K: [page][h][d / 8][kpos(t)][d % 8]   V: [page][h][t / 8][d][t % 8] */
 /* ------------------------------------------------------------------ */
+
+/*
+ * Slot of token t inside a K block row.  Tokens are taken in blocks of
+ * width = min(P, 32); inside a block, every run of 8 tokens is split: its
+ * first four go to the first half of the block, its last four to the second
+ * half, runs kept in order.
+ */
+int oracle_k_slot(int t, int P)
+{
+    int width = P < 32 ? P : 32;
+    int block = t / width, u = t % width;
+    int run = u / 8, in_run = u % 8;
+    int half = in_run / 4, quad_pos = in_run % 4;
+    return block * width + half * (width / 2) + run * 4 + quad_pos;
+}
 
 int64_t oracle_k_index(int64_t page, int h, int t, int d, int Hkv, int D, int P)
 {
-    return ((((page * Hkv + h) * (D / 8) + d / 8) * P + t) * 8) + d % 8;
+    return ((((page * Hkv + h) * (D / 8) + d / 8) * P + oracle_k_slot(t, P)) * 8) + d % 8;
 }
 
 int64_t oracle_v_index(int64_t page, int h, int t, int d, int Hkv, int D, int P)

@@ -140,16 +140,21 @@ __device__ __forceinline__ void load_step(const WaveCtx<D>& c, int32_t t0, StepD
     pgA = pgA < 0 ? 0 : (pgA >= c.num_pages ? c.num_pages - 1 : pgA);
     pgB = pgB < 0 ? 0 : (pgB >= c.num_pages ? c.num_pages - 1 : pgB);
     // K: lane (r, q) reads, for tile tt and k-block kk, 8 head-dim elements 32kk+8q.. of
-    // token 8*(r>>2) + 4*tt + (r&3).
+    // token 8*(r>>2) + 4*tt + (r&3) of the step.  In the page's permuted token order that
+    // token sits at slot (r & 7) + 8 tt of page r >> 3 when P == 16, and at slot r + 16 tt of
+    // the step's 32-slot block otherwise: the 16 rows of a tile are contiguous, so one load
+    // instruction covers whole 128-byte lines.
+    const uint4* kbase[2];
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
-        const int32_t tis = 8 * (c.r >> 2) + 4 * tt + (c.r & 3);
-        const int32_t page = tis >= 16 ? pgB : pgA;
-        const int32_t tin = (t0 + tis) & (P - 1);
-        const uint4* base = c.k_pages + (((int64_t)page * c.Hkv + c.h) * (D / 8) + c.q) * P + tin;
-#pragma unroll
-        for (int kk = 0; kk < D / 32; ++kk) s.k[tt][kk] = load_stream(base + (int64_t)kk * 4 * P);
+        const int32_t page = (P == 16 && c.r >= 8) ? pgB : pgA;
+        const int32_t slot = P == 16 ? (c.r & 7) + 8 * tt : (t0 & (P - 1)) + c.r + 16 * tt;
+        kbase[tt] = c.k_pages + (((int64_t)page * c.Hkv + c.h) * (D / 8) + c.q) * P + slot;
     }
+#pragma unroll
+    for (int kk = 0; kk < D / 32; ++kk)
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) s.k[tt][kk] = load_stream(kbase[tt] + (int64_t)kk * 4 * P);
     // V: lane (r, q) reads, for d-tile nt, the 8 tokens 8q..8q+7 of head-dim element 16nt+r.
     {
         const int32_t page = c.q >= 2 ? pgB : pgA;

@@ -52,7 +52,7 @@ __global__ void apply_updates(const int32_t* __restrict__ stage, int32_t* __rest
 }
 
 // One thread per (token, kv head, 8-element slice of head_dim).
-//   K page layout [page][h][d/8][t][d%8]: the slice is one 16-byte store.
+//   K page layout [page][h][d/8][kpos(t)][d%8]: the slice is one 16-byte store.
 //   V page layout [page][h][t/8][d][t%8]: the slice is 8 two-byte stores, 16 bytes apart.
 __global__ void append_tokens(const uint4* __restrict__ k_new, const uint4* __restrict__ v_new,
                               const int32_t* __restrict__ slots, const int32_t* __restrict__ positions,
@@ -77,7 +77,12 @@ __global__ void append_tokens(const uint4* __restrict__ k_new, const uint4* __re
     const int32_t t = pos % P;
     const uint4 kv = k_new[item];
     const uint4 vv = v_new[item];
-    k_pages[(((int64_t)page * Hkv + h) * d8n + c) * P + t] = kv;
+    // kpos: inside blocks of min(P, 32) tokens, the low quad of every 8 tokens goes to the
+    // first half of the block and the high quad to the second half.
+    const int32_t width = P < 32 ? P : 32;
+    const int32_t u = t & (width - 1);
+    const int32_t kpos = (t - u) + (u & 3) + 4 * (u >> 3) + (width >> 1) * ((u >> 2) & 1);
+    k_pages[(((int64_t)page * Hkv + h) * d8n + c) * P + kpos] = kv;
     uint16_t* vdst = v_pages + ((((int64_t)page * Hkv + h) * (P / 8) + t / 8) * D + c * 8) * 8 + t % 8;
     const uint32_t w[4] = {vv.x, vv.y, vv.z, vv.w};
 #pragma unroll

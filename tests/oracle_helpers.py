@@ -15,6 +15,15 @@ def from_bf16_bits(b):
     return (b.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
 
 
+def k_slot_bits(t, P):
+    """Third, bit-level statement of the K token permutation: inside blocks of min(P, 32)
+    tokens, bit 2 of the in-block index moves to the top and the bits above it shift down."""
+    nbits = 4 if P == 16 else 5
+    u, blk = t & ((1 << nbits) - 1), t >> nbits
+    low, b2, high = u & 3, (u >> 2) & 1, u >> 3
+    return (blk << nbits) | (b2 << (nbits - 1)) | (high << 2) | low
+
+
 def build_paged(K, V, lens, P, rng=None, spare=2):
     """K, V: float arrays [B, Lmax, Hkv, D] (logical).  Returns bf16-bit pools in the
     oracle's page layouts with a (optionally shuffled) page table, plus the rounded

@@ -6,6 +6,7 @@ import pytest
 import torch
 
 from paper_2510_11345_amd import workloads as wl
+import oracle
 from gpu_helpers import oracle_attn, run_attn, say
 
 pytestmark = pytest.mark.gpu
@@ -113,7 +114,7 @@ def test_garbage_past_the_length_is_never_used():
     for page in range(inp["num_pages"]):
         for t in range(P):
             if not used[page, t]:
-                k[page, :, :, t, :] = nan           # [N, Hkv, D/8, P, 8]
+                k[page, :, :, oracle.k_slot(t, P), :] = nan   # [N, Hkv, D/8, P (permuted), 8]
                 v[page, :, t // 8, :, t % 8] = nan  # [N, Hkv, P/8, D, 8]
     got = run_attn(inp, cfg, torch.float32)
     assert np.isfinite(got).all()

@@ -8,7 +8,7 @@ import pytest
 import scipy.special
 
 import oracle
-from oracle_helpers import build_paged, from_bf16_bits, to_bf16_bits
+from oracle_helpers import build_paged, from_bf16_bits, k_slot_bits, to_bf16_bits
 
 
 def rand_case(rng, B=3, Hq=8, Hkv=2, D=64, P=16, Lmax=70, lens=None):
@@ -29,13 +29,24 @@ def run(Q, K, V, lens, P, rng=None, scale=None):
     return out, from_bf16_bits(qb), Kr, Vr, (qb, kp, vp, table)
 
 
-def test_layout_index_formulas():
-    # K: [page][h][d/8][t][d%8]; V: [page][h][t/8][d][t%8] -- check against numpy reshapes
-    Hkv, D, P, N = 2, 64, 16, 3
+@pytest.mark.parametrize("P", [16, 32, 64])
+def test_layout_index_formulas(P):
+    # K: [page][h][d/8][kpos(t)][d%8]; V: [page][h][t/8][d][t%8] -- check against numpy reshapes
+    Hkv, D, N = 2, 64, 3
     k = np.arange(N * Hkv * D * P).reshape(N, Hkv, D // 8, P, 8)
     v = np.arange(N * Hkv * D * P).reshape(N, Hkv, P // 8, D, 8)
-    for (pg, h, t, d) in [(0, 0, 0, 0), (2, 1, 15, 63), (1, 0, 9, 17), (1, 1, 7, 8)]:
-        assert oracle.k_index(pg, h, t, d, Hkv, D, P) == k[pg, h, d // 8, t, d % 8]
+    slots = [oracle.k_slot(t, P) for t in range(P)]
+    assert sorted(slots) == list(range(P))                       # a permutation of the page
+    assert slots == [k_slot_bits(t, P) for t in range(P)]
+    # the first four of every eight tokens fill the first half of each block, in order
+    W = min(P, 32)
+    first_half = [t for t in range(W) if t % 8 < 4]
+    assert [slots[t] for t in first_half] == list(range(W // 2))
+    assert [slots[t] for t in range(W) if t % 8 >= 4] == list(range(W // 2, W))
+    if P == 64:
+        assert slots[32:] == [32 + s for s in slots[:32]]
+    for (pg, h, t, d) in [(0, 0, 0, 0), (2, 1, P - 1, 63), (1, 0, 9, 17), (1, 1, 7, 8), (0, 1, 12, 5)]:
+        assert oracle.k_index(pg, h, t, d, Hkv, D, P) == k[pg, h, d // 8, slots[t], d % 8]
         assert oracle.v_index(pg, h, t, d, Hkv, D, P) == v[pg, h, t // 8, d, t % 8]
 
 
