@@ -16,12 +16,15 @@
 //     not depend on thread timing) into an LDS histogram followed by a
 //     block-wide suffix scan; the last sweep runs the race over logits >= x_cut.
 //
-// The Gumbel-max race is exact and cheap: g(u) = -log(-log u) <= -log(1 - u)
-// because -log u >= 1 - u, so an entry can only win if z + (-log(1 - u)) reaches
-// the best exact value seen so far by its wave.  That test costs one hardware
-// log2 per entry; the few entries that pass are evaluated in fp64 (division by
-// the temperature and both logs), which is the arithmetic the definition is
-// stated in.  The running best is shared across the wave whenever it moves.
+// The Gumbel-max race is exact and cheap.  With g(u) = -log(-log u) and
+// -log u >= 1 - u, an entry can only win if  1 - u <= exp(z - best), best being
+// the largest exact perturbed logit seen so far by its wave.  exp(z - ref) is
+// needed for the log-sum-exp anyway, so the test costs one multiply and one
+// compare per entry on top of the Philox draw; the few entries that pass are
+// evaluated in fp64 (division by the temperature and both logs), the arithmetic
+// the definition is stated in.  The running best is shared across the wave
+// whenever it moves.  The integer multiplies of Philox are the bulk of the
+// arithmetic: each round is two 32x32->64 products (v_mad_u64_u32).
 #include <cfloat>
 #include <cmath>
 
@@ -33,13 +36,12 @@ constexpr int kThreads = 1024;
 constexpr int kWavesPerBlock = kThreads / 64;
 constexpr int kRadixBits = 10;
 constexpr int kBins = 1 << kRadixBits;
-constexpr float kLog2e = 1.44269504088896340736f;
-constexpr float kLn2 = 0.69314718055994530942f;
+constexpr double kLog2ed = 1.44269504088896340736;
 
 struct SampleParams {
     int32_t V;
     int64_t row_stride;
-    float inv_t;
+    float k2;  // log2(e) / temperature: z in log2 units is x * k2
     double temperature;
     float top_p;
     uint32_t seed_lo, seed_hi, step_lo, step_hi;
@@ -52,11 +54,11 @@ __device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint3
                                                  uint32_t k0, uint32_t k1) {
 #pragma unroll
     for (int round = 0; round < 10; ++round) {
-        const uint32_t hi_a = __umulhi(0xD2511F53u, c0), lo_a = 0xD2511F53u * c0;
-        const uint32_t hi_b = __umulhi(0xCD9E8D57u, c2), lo_b = 0xCD9E8D57u * c2;
-        const uint32_t n0 = hi_b ^ c1 ^ k0;
-        const uint32_t n2 = hi_a ^ c3 ^ k1;
-        c0 = n0; c1 = lo_b; c2 = n2; c3 = lo_a;
+        const uint64_t pa = (uint64_t)0xD2511F53u * c0;
+        const uint64_t pb = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(pb >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(pa >> 32) ^ c3 ^ k1;
+        c0 = n0; c1 = (uint32_t)pb; c2 = n2; c3 = (uint32_t)pa;
         k0 += 0x9E3779B9u;
         k1 += 0xBB67AE85u;
     }
@@ -100,23 +102,24 @@ __device__ __forceinline__ float key_to_float(uint32_t k) {
 
 // Calls f.run<N>(i0, x, active) for every aligned vector of the row and f.run<1> for the
 // tail.  Every lane of the workgroup makes the same number of calls (inactive ones carry
-// active == false), so the bodies may use wave-wide operations.
+// active == false), so the bodies may use wave-wide operations.  The next vector is
+// requested before the current one is processed.
 template <typename T, typename F>
 __device__ __forceinline__ void sweep(const T* __restrict__ row, int32_t V, F& f) {
     constexpr int N = Elem<T>::kVec;
     const int32_t nvec = V / N;
     const uint4* __restrict__ row16 = (const uint4*)row;
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+    int32_t vi = (int32_t)threadIdx.x;
+    uint4 cur = vi < nvec ? row16[vi] : zero;
     for (int32_t base = 0; base < nvec; base += kThreads) {
-        const int32_t vi = base + (int32_t)threadIdx.x;
-        const bool active = vi < nvec;
+        const int32_t vn = vi + kThreads;
+        const uint4 nxt = vn < nvec ? row16[vn] : zero;
         float x[N];
-        if (active) {
-            Elem<T>::unpack(row16[vi], x);
-        } else {
-#pragma unroll
-            for (int j = 0; j < N; ++j) x[j] = 0.f;
-        }
-        f.template run<N>(vi * N, x, active);
+        Elem<T>::unpack(cur, x);
+        f.template run<N>(vi * N, x, vi < nvec);
+        cur = nxt;
+        vi = vn;
     }
     if (nvec * N < V) {
         const int32_t i = nvec * N + (int32_t)threadIdx.x;
@@ -126,7 +129,7 @@ __device__ __forceinline__ void sweep(const T* __restrict__ row, int32_t V, F& f
     }
 }
 
-// ---- block reductions -------------------------------------------------------
+// ---- cross-lane helpers -------------------------------------------------------
 __device__ __forceinline__ double shfl_xor_f64(double v, int mask) {
     uint64_t b = __builtin_bit_cast(uint64_t, v);
     uint32_t lo = __shfl_xor((uint32_t)b, mask), hi = __shfl_xor((uint32_t)(b >> 32), mask);
@@ -138,31 +141,31 @@ __device__ __forceinline__ uint64_t shfl_up_u64(uint64_t v, int delta) {
 }
 
 // ---- sweep bodies -----------------------------------------------------------
-struct MaxSum {  // online max and sum of exp in log2 units
-    float inv_t;
-    float m = -INFINITY, s = 0.f;
+struct MaxOnly {  // per-thread max of the raw logits
+    float xm = -FLT_MAX;
     template <int N> __device__ __forceinline__ void run(int32_t, const float (&x)[N], bool active) {
         if (!active) return;
 #pragma unroll
-        for (int j = 0; j < N; ++j) add(x[j] * inv_t);
-    }
-    __device__ __forceinline__ void add(float z) {
-        if (z > m) {
-            s = s * __builtin_amdgcn_exp2f((m - z) * kLog2e) + 1.f;
-            m = z;
-        } else if (z > -INFINITY) {
-            s += __builtin_amdgcn_exp2f((z - m) * kLog2e);
-        }
+        for (int j = 0; j < N; ++j) xm = fmaxf(xm, x[j]);
     }
 };
 
-struct Race {  // Gumbel-max with the exact filter described at the top of the file
+// Gumbel-max race with the exact filter described at the top of the file.  With LSE the
+// per-thread reference logit follows the thread's running max and s accumulates
+// sum exp2((x - xref) k2); without it the reference is fixed (the row max) and only the
+// race runs.
+template <bool LSE>
+struct Race {
     const SampleParams& p;
     uint32_t row_id;
-    float x_cut;           // entries below it are not kept (-inf when top_p == 1)
-    double best = -INFINITY;
+    float x_cut;             // entries below it are not kept (-inf when top_p == 1)
+    float xref;              // reference logit of the exponentials: the running max of this
+                             // thread's raw logits (LSE) or the row max (otherwise)
+    float s = 0.f;           // sum of exp2((x - xref) k2) over this thread's entries (LSE only)
+    double best = -INFINITY; // best exact perturbed logit of this lane, natural-log units
     int32_t best_i = 0x7FFFFFFF;
-    float thr = -INFINITY;  // wave-uniform: (float) of the wave's best exact value, rounded down
+    float thr2 = -INFINITY;  // wave-uniform lower bound of the wave's best, log2 units
+    float c = INFINITY;      // exp2(xref k2 - thr2) with a safety factor
 
     __device__ __forceinline__ void exact(int32_t i, float x, uint32_t word) {
         const double u = ((double)(word >> 9) + 0.5) * 0x1p-23;
@@ -176,10 +179,12 @@ struct Race {  // Gumbel-max with the exact filter described at the top of the f
         double b = best;
 #pragma unroll
         for (int mask = 1; mask < 64; mask <<= 1) b = fmax(b, shfl_xor_f64(b, mask));
-        float t = (float)b;
-        if ((double)t > b) t = nextafterf(t, -INFINITY);
-        thr = t;
+        float t = (float)(b * kLog2ed);
+        if ((double)t > b * kLog2ed) t = nextafterf(t, -INFINITY);
+        thr2 = nextafterf(t, -INFINITY);
     }
+    __device__ __forceinline__ void refresh_c() { c = __builtin_amdgcn_exp2f(xref * p.k2 - thr2) * 1.0001f; }
+
     template <int N> __device__ __forceinline__ void run(int32_t i0, const float (&x)[N], bool active) {
         uint32_t words[N];
         if (N == 1) {
@@ -193,28 +198,42 @@ struct Race {  // Gumbel-max with the exact filter described at the top of the f
                 for (int j = 0; j < 4; ++j) words[4 * b4 + j] = r.w[j];
             }
         }
+        float xa[N];
+#pragma unroll
+        for (int j = 0; j < N; ++j) xa[j] = active ? x[j] : -INFINITY;
+        if (LSE) {  // move the reference to the running max, branch-free
+            float vmax = xa[0];
+#pragma unroll
+            for (int j = 1; j < N; ++j) vmax = fmaxf(vmax, xa[j]);
+            const float x_new = fmaxf(xref, vmax);
+            s *= __builtin_amdgcn_exp2f((xref - x_new) * p.k2);
+            xref = x_new;
+            refresh_c();
+        }
         uint32_t pass = 0;
 #pragma unroll
         for (int j = 0; j < N; ++j) {
-            const float z = x[j] * p.inv_t;
-            // 1 - u is exact in fp32; -log(1 - u) bounds the Gumbel variate from above.
-            const float one_minus_u = 1.0f - ((float)(words[j] >> 9) + 0.5f) * 0x1p-23f;
-            const float g_ub = -__builtin_amdgcn_logf(one_minus_u) * kLn2;
-            const float slack = 3e-5f + 2e-6f * fabsf(z);
-            if (active && x[j] >= x_cut && z + g_ub + slack >= thr) pass |= 1u << j;
+            // exponent relative to the reference: the difference of two logits is (nearly)
+            // exact, so entries close to the max keep full relative accuracy
+            const float e = __builtin_amdgcn_exp2f((xa[j] - xref) * p.k2);  // 0 for -inf entries
+            if (LSE) s += e;
+            // 1 - u = ((2^23 - 1 - k) + 0.5) 2^-23, exact in fp32
+            const float one_minus_u = ((float)((~words[j]) >> 9) + 0.5f) * 0x1p-23f;
+            if (one_minus_u <= e * c && x[j] >= x_cut) pass |= 1u << j;
         }
         if (__any(pass != 0)) {
 #pragma unroll
             for (int j = 0; j < N; ++j)
                 if (pass & (1u << j)) exact(i0 + j, x[j], words[j]);
             share();
+            refresh_c();
         }
     }
 };
 
 template <int SHIFT, int BITS>
-struct Histogram {  // adds exp(z - m) in 2^-40 fixed point to the bin of the key's digit
-    float inv_t, m;
+struct Histogram {  // adds exp(z - max) in 2^-40 fixed point to the bin of the key's digit
+    float k2, xmax;
     uint32_t prefix;  // the key's bits above SHIFT + BITS must equal this
     unsigned long long* hist;
     template <int N> __device__ __forceinline__ void run(int32_t, const float (&x)[N], bool active) {
@@ -223,19 +242,10 @@ struct Histogram {  // adds exp(z - m) in 2^-40 fixed point to the bin of the ke
         for (int j = 0; j < N; ++j) {
             const uint32_t key = order_key(x[j]);
             if (SHIFT + BITS < 32 && (key >> ((SHIFT + BITS) & 31)) != prefix) continue;
-            const float w = __builtin_amdgcn_exp2f((x[j] * inv_t - m) * kLog2e);
+            const float w = __builtin_amdgcn_exp2f((x[j] - xmax) * k2);
             const unsigned long long fx = (unsigned long long)((double)w * 0x1p40);
             if (fx) atomicAdd(&hist[(key >> SHIFT) & ((1u << BITS) - 1u)], fx);
         }
-    }
-};
-
-struct MaxSumAndRace {  // the single sweep of the top_p == 1 path
-    MaxSum& a;
-    Race& b;
-    template <int N> __device__ __forceinline__ void run(int32_t i0, const float (&x)[N], bool active) {
-        a.template run<N>(i0, x, active);
-        b.template run<N>(i0, x, active);
     }
 };
 
@@ -276,13 +286,13 @@ __device__ void scan_select(unsigned long long* hist, unsigned long long* s_wave
 // One radix level: histogram of the digit at SHIFT (BITS wide) over the entries whose higher
 // key bits equal the prefix chosen so far, then the suffix scan that picks the next digit.
 template <typename T, int SHIFT, int BITS, bool FIRST>
-__device__ void radix_level(const T* __restrict__ row, const SampleParams& p, float M,
+__device__ void radix_level(const T* __restrict__ row, const SampleParams& p, float xmax,
                             unsigned long long* s_hist, unsigned long long* s_wave, Select* s_sel,
                             unsigned long long& target) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     for (int i = tid; i < kBins; i += kThreads) s_hist[i] = 0ull;
     __syncthreads();
-    Histogram<SHIFT, BITS> h{p.inv_t, M, s_sel->prefix, s_hist};
+    Histogram<SHIFT, BITS> h{p.k2, xmax, s_sel->prefix, s_hist};
     sweep<T>(row, p.V, h);
     __syncthreads();
     if (FIRST) {  // total mass -> target = ceil(top_p * total)
@@ -325,24 +335,19 @@ __global__ __launch_bounds__(kThreads) void sample_rows(const T* __restrict__ lo
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t row_id = row_ids ? (uint32_t)row_ids[r] : (uint32_t)r;
 
-    MaxSum ms{p.inv_t};
-    Race race{p, row_id, -INFINITY};
+    Race<true> race{p, row_id, -INFINITY, -FLT_MAX};
+    MaxOnly mo;
+    if (!TOPP) sweep<T>(row, p.V, race);  // one sweep: online log-sum-exp and the race together
+    else sweep<T>(row, p.V, mo);
 
-    if (!TOPP) {
-        // One sweep: online log-sum-exp and the race together.
-        MaxSumAndRace both{ms, race};
-        sweep<T>(row, p.V, both);
-    } else {
-        sweep<T>(row, p.V, ms);
-    }
-
-    // Block max and sum (sum only used when top_p == 1).
+    // Block max of the raw logits and, for top_p == 1, the log-sum-exp.  The sums are taken
+    // relative to fl(xmax * k2); the exact xmax / T is added back in fp64 at the end.
     {
-        float m = ms.m;
+        const float mine = TOPP ? mo.xm : race.xref;
+        float m = mine;
 #pragma unroll
         for (int mask = 1; mask < 64; mask <<= 1) m = fmaxf(m, __shfl_xor(m, mask));
-        double s = (double)ms.s * (double)__builtin_amdgcn_exp2f((ms.m - m) * kLog2e);
-        if (ms.s == 0.f) s = 0.0;
+        double s = TOPP ? 0.0 : (double)race.s * (double)__builtin_amdgcn_exp2f((mine - m) * p.k2);
 #pragma unroll
         for (int mask = 1; mask < 64; mask <<= 1) s += shfl_xor_f64(s, mask);
         if (lane == 0) { s_m[wave] = m; s_s[wave] = s; }
@@ -352,53 +357,54 @@ __global__ __launch_bounds__(kThreads) void sample_rows(const T* __restrict__ lo
             for (int w = 1; w < kWavesPerBlock; ++w) M = fmaxf(M, s_m[w]);
             double S = 0.0;
             for (int w = 0; w < kWavesPerBlock; ++w)
-                S += s_s[w] * exp2((double)(s_m[w] - M) * (double)kLog2e);
+                S += s_s[w] * (double)__builtin_amdgcn_exp2f((s_m[w] - M) * p.k2);
             s_m[0] = M;
-            s_lse = (double)M + log(S);
+            s_lse = (double)M / p.temperature + log(S);
             s_sel.prefix = 0;
             s_sel.above = 0;
         }
         __syncthreads();
     }
 
+    Race<false> race_kept{p, row_id, -INFINITY, 0.f};
     if (TOPP) {
-        const float M = s_m[0];
+        const float xM = s_m[0];
         constexpr int kKeyBits = Elem<T>::kKeyBits;
         unsigned long long target = 0;
         // Levels from the most significant digit down; the last level may be narrower.
         if (kKeyBits == 16) {
-            radix_level<T, 22, 10, true>(row, p, M, s_hist, s_wave, &s_sel, target);
-            radix_level<T, 16, 6, false>(row, p, M, s_hist, s_wave, &s_sel, target);
+            radix_level<T, 22, 10, true>(row, p, xM, s_hist, s_wave, &s_sel, target);
+            radix_level<T, 16, 6, false>(row, p, xM, s_hist, s_wave, &s_sel, target);
         } else {
-            radix_level<T, 22, 10, true>(row, p, M, s_hist, s_wave, &s_sel, target);
-            radix_level<T, 12, 10, false>(row, p, M, s_hist, s_wave, &s_sel, target);
-            radix_level<T, 2, 10, false>(row, p, M, s_hist, s_wave, &s_sel, target);
-            radix_level<T, 0, 2, false>(row, p, M, s_hist, s_wave, &s_sel, target);
+            radix_level<T, 22, 10, true>(row, p, xM, s_hist, s_wave, &s_sel, target);
+            radix_level<T, 12, 10, false>(row, p, xM, s_hist, s_wave, &s_sel, target);
+            radix_level<T, 2, 10, false>(row, p, xM, s_hist, s_wave, &s_sel, target);
+            radix_level<T, 0, 2, false>(row, p, xM, s_hist, s_wave, &s_sel, target);
         }
         if (tid == 0) {
-            // s_sel.prefix is now the full key of the cut value; the kept mass is everything
-            // above it plus the cut value's own class.
-            const uint32_t key = s_sel.prefix << (32 - kKeyBits) | (kKeyBits == 16 ? ((s_sel.prefix >> 15) ? 0u : 0xFFFFu) : 0u);
+            // s_sel.prefix is now the key of the cut value (its upper 16 bits for bf16, whose
+            // lower key bits are all ones for negative values and zero otherwise).  The kept
+            // mass is everything above the cut plus the cut value's own class, which is the
+            // selected bin of the last level.
+            const uint32_t key = (s_sel.prefix << (32 - kKeyBits)) |
+                                 (kKeyBits == 16 ? ((s_sel.prefix >> 15) ? 0u : 0xFFFFu) : 0u);
             s_xcut = key_to_float(key);
-        }
-        __syncthreads();
-        // Kept mass: one more histogram-free reduction is avoided by re-reading the last level:
-        // bins >= the selected digit of the last level, plus `above`.
-        if (tid == 0) {
             constexpr int last_bits = kKeyBits == 16 ? 6 : 2;
             const uint32_t digit = s_sel.prefix & ((1u << last_bits) - 1u);
             const unsigned long long kept = s_sel.above + s_hist[digit];
-            s_lse = (double)M + log((double)kept * 0x1p-40);
+            s_lse = (double)xM / p.temperature + log((double)kept * 0x1p-40);
         }
         __syncthreads();
-        race.x_cut = s_xcut;
-        sweep<T>(row, p.V, race);
+        race_kept.x_cut = s_xcut;
+        race_kept.xref = xM;
+        race_kept.refresh_c();
+        sweep<T>(row, p.V, race_kept);
     }
 
     // Block arg-max of the exact perturbed values (lowest index on ties).
     {
-        double b = race.best;
-        int32_t bi = race.best_i;
+        double b = TOPP ? race_kept.best : race.best;
+        int32_t bi = TOPP ? race_kept.best_i : race.best_i;
 #pragma unroll
         for (int mask = 1; mask < 64; mask <<= 1) {
             const double ob = shfl_xor_f64(b, mask);
@@ -455,7 +461,7 @@ extern "C" int roll_sample_logprob(const void* logits, float temperature, float 
     SampleParams p{};
     p.V = d->vocab;
     p.row_stride = d->row_stride;
-    p.inv_t = 1.0f / temperature;
+    p.k2 = (float)(1.44269504088896340736 / (double)temperature);
     p.temperature = (double)temperature;
     p.top_p = top_p;
     p.seed_lo = (uint32_t)philox_seed;
