@@ -181,7 +181,7 @@ int roll_kv_append_tokens(const void* k_new, const void* v_new,
 /* ------------------------------------------------------------------ */
 
 typedef struct roll_attn_desc {
-    int32_t batch;              /* B rows of q / page_table / seq_lens / out; <= 8192 */
+    int32_t batch;              /* B rows of q / page_table / seq_lens / out; <= 8192, B * Hkv <= 65536 */
     int32_t num_q_heads;        /* Hq */
     int32_t num_kv_heads;       /* Hkv; Hq % Hkv == 0 and Hq / Hkv <= 16 */
     int32_t head_dim;           /* D: 64 or 128 */
@@ -199,6 +199,15 @@ typedef struct roll_attn_desc {
 size_t roll_decode_attn_workspace_bytes(const roll_attn_desc* desc);
 
 /*
+ * Prepare a workspace: enqueues a kernel on stream that zeroes the arrival
+ * counters at its start.  Call once after allocating the buffer (and again if
+ * anything else has written to it, or after a call that failed on the
+ * device); every roll_decode_attn leaves the counters zero again.  A
+ * workspace prepared once serves any later desc it is large enough for.
+ */
+int roll_decode_attn_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  *   q           DEVICE bf16 [B, Hq, D]
  *   k_pages     DEVICE bf16 [num_pages, Hkv, D/8, P, 8]
  *   v_pages     DEVICE bf16 [num_pages, Hkv, P/8, D, 8]
@@ -207,9 +216,10 @@ size_t roll_decode_attn_workspace_bytes(const roll_attn_desc* desc);
  *   seq_lens    DEVICE int32 [B]; values outside [0, max_pages*P] are
  *               clamped into that range
  *   out         DEVICE [B, Hq, D] of out_dtype
- *   workspace   DEVICE, 256-byte aligned, >= roll_decode_attn_workspace_bytes
- * All pointers 16-byte aligned.  Enqueues two kernels on stream: the persistent
- * stream-K attention kernel and the merge of rows that were cut across waves.
+ *   workspace   DEVICE, 256-byte aligned, >= roll_decode_attn_workspace_bytes,
+ *               prepared with roll_decode_attn_workspace_init
+ * All pointers 16-byte aligned.  Enqueues one kernel on stream: the persistent
+ * stream-K attention kernel, which also merges the rows it cut across waves.
  * The workspace size does not depend on the sequence lengths.  Two calls that
  * share a workspace must be ordered on one stream.
  */

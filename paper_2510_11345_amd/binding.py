@@ -24,7 +24,7 @@ EXPORTS = [
     "roll_kv_pool_create", "roll_kv_pool_destroy", "roll_kv_alloc", "roll_kv_alloc_batch", "roll_kv_release",
     "roll_kv_commit", "roll_kv_free_pages", "roll_kv_seq_len", "roll_kv_slot_pages",
     "roll_kv_append_tokens",
-    "roll_decode_attn_workspace_bytes", "roll_decode_attn",
+    "roll_decode_attn_workspace_bytes", "roll_decode_attn_workspace_init", "roll_decode_attn",
     "roll_sample_logprob_workspace_bytes", "roll_sample_logprob",
     "roll_prof_event_create", "roll_prof_event_destroy", "roll_prof_event_record",
     "roll_prof_event_elapsed_ms",
@@ -84,6 +84,7 @@ def lib():
         L.roll_kv_slot_pages.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_int32]
         L.roll_kv_append_tokens.argtypes = [C.c_void_p] * 5 + [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p] + \
             [C.c_int32] * 5 + [C.c_void_p]
+        L.roll_decode_attn_workspace_init.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
         L.roll_decode_attn.argtypes = [C.c_void_p] * 6 + [C.POINTER(AttnDesc), C.c_void_p, C.c_size_t, C.c_void_p]
         L.roll_sample_logprob.argtypes = [C.c_void_p, C.c_float, C.c_float, C.c_uint64, C.c_uint64,
                                           C.c_void_p, C.c_void_p, C.POINTER(SampleDesc), C.c_void_p,
@@ -218,6 +219,18 @@ def roll_decode_attn_workspace_bytes(desc: AttnDesc) -> int:
     if n == 0:
         raise RollError(-1, lib().roll_last_error().decode())
     return n
+
+
+def roll_decode_attn_workspace_init(workspace: torch.Tensor) -> None:
+    _check(lib().roll_decode_attn_workspace_init(_dev(workspace), workspace.numel() * workspace.element_size(),
+                                                 _stream()))
+
+
+def new_attn_workspace(desc: AttnDesc, device="cuda") -> torch.Tensor:
+    """Allocate and prepare a workspace for desc."""
+    ws = torch.empty(roll_decode_attn_workspace_bytes(desc), dtype=torch.uint8, device=device)
+    roll_decode_attn_workspace_init(ws)
+    return ws
 
 
 def roll_decode_attn(q, k_pages, v_pages, page_table, seq_lens, out, desc: AttnDesc,

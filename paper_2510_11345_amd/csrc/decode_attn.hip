@@ -1,5 +1,5 @@
-// Paged GQA decode attention for gfx950: one persistent stream-K kernel on the
-// matrix cores plus a small merge of the pieces of rows that were cut.
+// Paged GQA decode attention for gfx950: ONE persistent stream-K kernel on the
+// matrix cores; rows that were cut across waves are merged inside it.
 //
 // ROLL Flash (arXiv 2510.11345) Section 1: decoding is memory-bandwidth bound
 // and response lengths are long-tailed; Section 4.2: one step over the whole
@@ -15,6 +15,9 @@
 // cut across neighbouring waves, and at most the first and the last stream of a
 // wave are pieces; a wave writes a complete stream straight to `out` and a piece
 // (running max, sum, un-normalised output) to its two slots of the workspace.
+// Pieces are merged by whichever wave delivers the last one (an arrival counter
+// per group of 16 neighbouring pieces, then one per stream when a stream has
+// more than 16): no wave ever waits for another, so there is nothing to hang.
 // The row prefix sums that locate a wave's first step are rebuilt in LDS by
 // every workgroup (a few microseconds, no separate launch, no dependent
 // global loads on the way to the first KV byte).  All G = Hq / Hkv query heads
@@ -52,6 +55,11 @@ constexpr int kGroupWaves = 4;     // wavefronts per workgroup (they only share 
 constexpr int kStep = 32;          // tokens per wave step
 constexpr int kMinSteps = 4;       // do not spread a small batch thinner than this per wave
 constexpr int kMaxBatch = 8192;    // rows whose prefix sums fit the LDS budget
+constexpr int kMaxStreams = 65536; // batch * num_kv_heads: one arrival counter each
+constexpr int kMergeGroup = 16;    // pieces merged by one wave at the first level
+// Upper bound of persistent waves, used to size the workspace without touching the device:
+// 16 waves on each of 256 compute units (a gfx950 device has no more).
+constexpr int32_t kMaxPersistentWaves = 16 * 256;
 
 struct AttnParams {
     int32_t B, Hq, Hkv, G;
@@ -63,23 +71,39 @@ struct AttnParams {
 };
 
 struct Workspace {
-    int32_t* row_off;  // [B + 1] exclusive prefix of steps per row (written by workgroup 0)
-    float2* part_ml;   // [2 W * G] (max in log2 units, sum) of a piece
+    // zero between calls (roll_decode_attn_workspace_init, then every merger resets its counter)
+    int32_t* group_arrivals;   // [2 W] indexed by the slot of the first piece of a group
+    int32_t* stream_arrivals;  // [kMaxStreams] indexed by row * Hkv + kv head
+    // scratch
+    float2* part_ml;   // [2 W * G] (max in log2 units, sum) of a piece: slots 2w, 2w + 1 of wave w
     float* part_acc;   // [2 W * G * D] un-normalised output of a piece
+    float2* group_ml;  // [2 W * G] merged group of pieces, at the slot of the group's first piece
+    float* group_acc;  // [2 W * G * D]
+    size_t header_bytes;
     size_t bytes;
 };
 
 __host__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-__host__ Workspace carve(void* base, int32_t B, int32_t G, int32_t D, int32_t W) {
+__host__ Workspace carve(void* base, int32_t G, int32_t D) {
     Workspace w{};
+    const size_t W = kMaxPersistentWaves;
     size_t off = 0;
     char* p = (char*)base;
-    w.row_off = (int32_t*)(p + off);  off = align_up(off + sizeof(int32_t) * ((size_t)B + 1), 256);
-    w.part_ml = (float2*)(p + off);   off = align_up(off + sizeof(float2) * 2 * (size_t)W * G, 256);
-    w.part_acc = (float*)(p + off);   off = align_up(off + sizeof(float) * 2 * (size_t)W * G * D, 256);
+    w.group_arrivals = (int32_t*)(p + off);   off = align_up(off + sizeof(int32_t) * 2 * W, 256);
+    w.stream_arrivals = (int32_t*)(p + off);  off = align_up(off + sizeof(int32_t) * kMaxStreams, 256);
+    w.header_bytes = off;
+    w.part_ml = (float2*)(p + off);           off = align_up(off + sizeof(float2) * 2 * W * G, 256);
+    w.part_acc = (float*)(p + off);           off = align_up(off + sizeof(float) * 2 * W * G * D, 256);
+    w.group_ml = (float2*)(p + off);          off = align_up(off + sizeof(float2) * 2 * W * G, 256);
+    w.group_acc = (float*)(p + off);          off = align_up(off + sizeof(float) * 2 * W * G * D, 256);
     w.bytes = off;
     return w;
+}
+
+__global__ void zero_words(uint32_t* dst, size_t n) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = 0u;
 }
 
 // How the S steps are dealt to waves; shared by the attention and the merge kernel.
@@ -125,9 +149,9 @@ struct WaveCtx {
     int32_t h, Hkv, log2P, num_pages, max_pages, r, q;
 };
 
+// Physical pages of the (up to) two pages a 32-token step touches.
 template <int D>
-__device__ __forceinline__ void load_step(const WaveCtx<D>& c, int32_t t0, StepData<D>& s) {
-    const int32_t P = 1 << c.log2P;
+__device__ __forceinline__ void step_pages(const WaveCtx<D>& c, int32_t t0, int32_t& pgA, int32_t& pgB) {
     int32_t pa = t0 >> c.log2P;
     // The second page may lie past the row's end; its table entry is then stale or -1.  Reading
     // it is in bounds (clamped to the table row) and the id is clamped below, so the loads stay
@@ -135,15 +159,22 @@ __device__ __forceinline__ void load_step(const WaveCtx<D>& c, int32_t t0, StepD
     // last page keeps the row length off the address path.
     int32_t pb = (t0 + 16) >> c.log2P;
     pb = pb > c.max_pages - 1 ? c.max_pages - 1 : pb;
-    int32_t pgA = c.pt_row[pa];
-    int32_t pgB = c.pt_row[pb];
+    pgA = c.pt_row[pa];
+    pgB = c.pt_row[pb];
     pgA = pgA < 0 ? 0 : (pgA >= c.num_pages ? c.num_pages - 1 : pgA);
     pgB = pgB < 0 ? 0 : (pgB >= c.num_pages ? c.num_pages - 1 : pgB);
-    // K: lane (r, q) reads, for tile tt and k-block kk, 8 head-dim elements 32kk+8q.. of
-    // token 8*(r>>2) + 4*tt + (r&3) of the step.  In the page's permuted token order that
-    // token sits at slot (r & 7) + 8 tt of page r >> 3 when P == 16, and at slot r + 16 tt of
-    // the step's 32-slot block otherwise: the 16 rows of a tile are contiguous, so one load
-    // instruction covers whole 128-byte lines.
+}
+
+// K: lane (r, q) reads, for tile tt and k-block kk, 8 head-dim elements 32kk+8q.. of
+// token 8*(r>>2) + 4*tt + (r&3) of the step.  In the page's permuted token order that
+// token sits at slot (r & 7) + 8 tt of page r >> 3 when P == 16, and at slot r + 16 tt of
+// the step's 32-slot block otherwise: the 16 rows of a tile are contiguous, so one load
+// instruction covers whole 128-byte lines.
+template <int D>
+__device__ __forceinline__ void load_k(const WaveCtx<D>& c, int32_t t0, StepData<D>& s) {
+    const int32_t P = 1 << c.log2P;
+    int32_t pgA, pgB;
+    step_pages<D>(c, t0, pgA, pgB);
     const uint4* kbase[2];
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
@@ -155,14 +186,19 @@ __device__ __forceinline__ void load_step(const WaveCtx<D>& c, int32_t t0, StepD
     for (int kk = 0; kk < D / 32; ++kk)
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) s.k[tt][kk] = load_stream(kbase[tt] + (int64_t)kk * 4 * P);
-    // V: lane (r, q) reads, for d-tile nt, the 8 tokens 8q..8q+7 of head-dim element 16nt+r.
-    {
-        const int32_t page = c.q >= 2 ? pgB : pgA;
-        const int32_t oct = ((t0 + 8 * c.q) & (P - 1)) >> 3;
-        const uint4* base = c.v_pages + (((int64_t)page * c.Hkv + c.h) * (P / 8) + oct) * D + c.r;
+}
+
+// V: lane (r, q) reads, for d-tile nt, the 8 tokens 8q..8q+7 of head-dim element 16nt+r.
+template <int D>
+__device__ __forceinline__ void load_v(const WaveCtx<D>& c, int32_t t0, StepData<D>& s) {
+    const int32_t P = 1 << c.log2P;
+    int32_t pgA, pgB;
+    step_pages<D>(c, t0, pgA, pgB);
+    const int32_t page = c.q >= 2 ? pgB : pgA;
+    const int32_t oct = ((t0 + 8 * c.q) & (P - 1)) >> 3;
+    const uint4* base = c.v_pages + (((int64_t)page * c.Hkv + c.h) * (P / 8) + oct) * D + c.r;
 #pragma unroll
-        for (int nt = 0; nt < D / 16; ++nt) s.v[nt] = load_stream(base + nt * 16);
-    }
+    for (int nt = 0; nt < D / 16; ++nt) s.v[nt] = load_stream(base + nt * 16);
 }
 
 template <int D>
@@ -172,10 +208,12 @@ struct WaveAcc {
     float l;            // this lane's share of the running sum of head r
 };
 
+// Scores of the step's 32 tokens for head r, in log2 units; the 8 a lane owns are tokens
+// t0 + 8q + j.  Tokens at or past `end` get -inf.  Consumes the K registers.
 template <int D>
-__device__ __forceinline__ void compute_step(const WaveCtx<D>& c, const bf16x8_t (&qf)[D / 32],
-                                             StepData<D>& s, int32_t t0, int32_t end,
-                                             float scale_log2e, WaveAcc<D>& a) {
+__device__ __forceinline__ void score_step(const WaveCtx<D>& c, const bf16x8_t (&qf)[D / 32],
+                                           const StepData<D>& s, int32_t t0, int32_t end,
+                                           float scale_log2e, float (&sv)[8]) {
     f32x4_t sc[2];
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
@@ -185,18 +223,24 @@ __device__ __forceinline__ void compute_step(const WaveCtx<D>& c, const bf16x8_t
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(s.k[tt][kk]), qf[kk], acc, 0, 0, 0);
         sc[tt] = acc;
     }
-    float sv[8];
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
         for (int i = 0; i < 4; ++i) sv[4 * tt + i] = sc[tt][i] * scale_log2e;
-
-    if (t0 + kStep > end) {  // ragged tail of the row: mask scores and zero the V octets
+    if (t0 + kStep > end) {  // ragged tail of the row
         const int32_t first = t0 + 8 * c.q;
 #pragma unroll
         for (int j = 0; j < 8; ++j)
             if (first + j >= end) sv[j] = -INFINITY;
-        const int32_t nvalid = end - first;
+    }
+}
+
+// Online softmax update with the step's scores and O^T += V^T P^T.  Consumes the V registers.
+template <int D>
+__device__ __forceinline__ void accumulate_step(const WaveCtx<D>& c, const float (&sv)[8], StepData<D>& s,
+                                                int32_t t0, int32_t end, WaveAcc<D>& a) {
+    if (t0 + kStep > end) {  // ragged tail: zero the V octets of tokens that do not exist
+        const int32_t nvalid = end - (t0 + 8 * c.q);
 #pragma unroll
         for (int nt = 0; nt < D / 16; ++nt) {
             uint32_t w[4] = {s.v[nt].x, s.v[nt].y, s.v[nt].z, s.v[nt].w};
@@ -249,7 +293,6 @@ __device__ __forceinline__ void compute_step(const WaveCtx<D>& c, const bf16x8_t
     }
 }
 
-
 // Steps per row into LDS as an exclusive prefix, clamped lengths beside it.
 // pre has B + 1 entries, len has B.  All threads of the workgroup take part.
 __device__ void build_row_prefix(const int32_t* __restrict__ seq_lens, int32_t B, int32_t max_len,
@@ -286,23 +329,126 @@ __device__ void build_row_prefix(const int32_t* __restrict__ seq_lens, int32_t B
     __syncthreads();
 }
 
+// Write one head-dim quad row of a finished stream: normalise by the sum and store.
+template <int D>
+__device__ __forceinline__ void store_result(const WaveAcc<D>& a, void* __restrict__ out, int64_t idx,
+                                             int32_t out_f32) {
+    const float inv = 1.0f / a.l;
+#pragma unroll
+    for (int nt = 0; nt < D / 16; ++nt) {
+        const f32x4_t o = a.o[nt] * inv;
+        if (out_f32) {
+            *(f32x4_t*)((float*)out + idx + 16 * nt) = o;
+        } else {
+            uint2 pk;
+            pk.x = pack_bf16_rne(o[0], o[1]);
+            pk.y = pack_bf16_rne(o[2], o[3]);
+            *(uint2*)((__bf16*)out + idx + 16 * nt) = pk;
+        }
+    }
+}
+
+// Pieces travel between waves on different XCDs (each with its own L2) inside one kernel.
+// They are written and read with relaxed device-scope atomic 8-byte accesses, which are
+// coherent across the XCDs by themselves; the handshake is a device-scope atomic counter.
+// That keeps the whole-L2 write-back / invalidate of a device-scope fence out of a kernel
+// whose L2s are busy streaming KV.
+__device__ __forceinline__ void coherent_store2(float* p, float a, float b) {
+    const uint64_t bits = (uint64_t)__float_as_uint(a) | ((uint64_t)__float_as_uint(b) << 32);
+    __hip_atomic_store((uint64_t*)p, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ f32x2_t coherent_load2(const float* p) {
+    const uint64_t bits = __hip_atomic_load((const uint64_t*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return f32x2_t{__uint_as_float((uint32_t)bits), __uint_as_float((uint32_t)(bits >> 32))};
+}
+
+// Store a piece (un-normalised) at `slot` of a piece array; lane (r, q) owns head r, quads 4q.
+template <int D>
+__device__ __forceinline__ void store_piece(const WaveAcc<D>& a, float2* ml, float* acc, int64_t slot,
+                                            int32_t G, int32_t r, int32_t q) {
+    const int64_t row = slot * G + r;
+    if (q == 0) coherent_store2((float*)(ml + row), a.m, a.l);
+    float* dst = acc + row * D + 4 * q;
+#pragma unroll
+    for (int nt = 0; nt < D / 16; ++nt) {
+        coherent_store2(dst + 16 * nt, a.o[nt][0], a.o[nt][1]);
+        coherent_store2(dst + 16 * nt + 2, a.o[nt][2], a.o[nt][3]);
+    }
+}
+
+// Log-sum-exp merge of n pieces whose slots are slot_of(0..n-1); result stays un-normalised.
+template <int D, typename SlotFn>
+__device__ __forceinline__ void merge_pieces(WaveAcc<D>& out_acc, const float2* ml, const float* acc,
+                                             int32_t n, SlotFn slot_of, int32_t G, int32_t r, int32_t q) {
+    float M = -INFINITY;
+    for (int32_t i = 0; i < n; ++i) {
+        const f32x2_t m_l = coherent_load2((const float*)(ml + slot_of(i) * G + r));
+        M = fmaxf(M, m_l[0]);
+    }
+    float lsum = 0.f;
+    f32x4_t o[D / 16];
+#pragma unroll
+    for (int nt = 0; nt < D / 16; ++nt) o[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 2
+    for (int32_t i = 0; i < n; ++i) {
+        const int64_t row = slot_of(i) * G + r;
+        const f32x2_t m_l = coherent_load2((const float*)(ml + row));
+        const float wgt = __builtin_amdgcn_exp2f(m_l[0] - M);
+        lsum += m_l[1] * wgt;
+        const float* src = acc + row * D + 4 * q;
+#pragma unroll
+        for (int nt = 0; nt < D / 16; ++nt) {
+            const f32x2_t lo = coherent_load2(src + 16 * nt), hi = coherent_load2(src + 16 * nt + 2);
+            o[nt] += f32x4_t{lo[0], lo[1], hi[0], hi[1]} * wgt;
+        }
+    }
+    out_acc.m = M;
+    out_acc.l = lsum;
+#pragma unroll
+    for (int nt = 0; nt < D / 16; ++nt) out_acc.o[nt] = o[nt];
+}
+
+// One arrival at a counter; returns true in every lane of the wave that arrived last.
+// The wave first waits until its own piece stores have completed (they bypass the caches, so
+// completed means visible to every XCD), then bumps the counter with a device-scope atomic.
+// The last arriver resets the counter for the next call; nobody else touches it any more.
+__device__ __forceinline__ bool arrive_last(int32_t* counter, int32_t expected, int32_t lane) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    int32_t old = 0;
+    if (lane == 0) old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    old = __builtin_amdgcn_readfirstlane(old);
+    asm volatile("" ::: "memory");
+    if (old != expected - 1) return false;
+    if (lane == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return true;
+}
+
 template <int D>
 __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
     const uint4* __restrict__ q16, const uint4* __restrict__ k_pages, const uint4* __restrict__ v_pages,
     const int32_t* __restrict__ page_table, const int32_t* __restrict__ seq_lens,
-    void* __restrict__ out, int32_t* __restrict__ row_off, float2* __restrict__ part_ml,
-    float* __restrict__ part_acc, AttnParams prm) {
+    void* __restrict__ out, int32_t* group_arrivals, int32_t* stream_arrivals, float2* part_ml,
+    float* part_acc, float2* group_ml, float* group_acc, AttnParams prm) {
     extern __shared__ int32_t lds[];
     int32_t* pre = lds;                  // [B + 1]
     int32_t* len = lds + prm.B + 1;      // [B]
     __shared__ int32_t s_wave_tot[kGroupWaves];
     build_row_prefix(seq_lens, prm.B, prm.max_len, pre, len, s_wave_tot);
-    if (blockIdx.x == 0)
-        for (int32_t i = threadIdx.x; i <= prm.B; i += blockDim.x) row_off[i] = pre[i];
 
     const int32_t lane = threadIdx.x & 63;
     const int32_t w = blockIdx.x * kGroupWaves + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int32_t G = prm.G, Hkv = prm.Hkv;
+
+    // Rows without tokens give zeros; wave w of the launch clears rows w, w + W, ...
+    for (int32_t b = w; b < prm.B; b += prm.W) {
+        if (len[b] != 0) continue;
+        const int64_t base = (int64_t)b * prm.Hq * D;
+        for (int32_t e = lane * 4; e < prm.Hq * D; e += 256) {
+            if (prm.out_f32) *(f32x4_t*)((float*)out + base + e) = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            else *(uint2*)((__bf16*)out + base + e) = make_uint2(0u, 0u);
+        }
+    }
+
     const Deal deal((int64_t)pre[prm.B] * Hkv, prm.W);
     if (w >= deal.W) return;
     int64_t item = deal.first_step(w);
@@ -333,6 +479,7 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
     ctx.max_pages = prm.max_pages;
     ctx.r = lane & 15;
     ctx.q = lane >> 4;
+    const int32_t rr = ctx.r < G ? ctx.r : 0;  // lanes of the padding heads shadow head 0, store nothing
 
     bool first_stream = true;
     while (todo > 0) {
@@ -355,39 +502,61 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
         acc.m = -INFINITY;
         acc.l = 0.f;
 
+        // All 16 loads of a step are issued together and the wave then waits for them; the other
+        // wave on the SIMD streams meanwhile.  (Requesting the next step's K and V into the
+        // registers as soon as the MFMAs free them was measured and gave nothing: in steady state
+        // the kernel is bound by the memory system, not by bytes in flight per wave.)
         for (int32_t i = s; i < s + cnt; ++i) {
             StepData<D> sd;
-            load_step<D>(ctx, i * kStep, sd);
-            compute_step<D>(ctx, qf, sd, i * kStep, L, prm.scale_log2e, acc);
+            load_k<D>(ctx, i * kStep, sd);
+            load_v<D>(ctx, i * kStep, sd);
+            float sv[8];
+            score_step<D>(ctx, qf, sd, i * kStep, L, prm.scale_log2e, sv);
+            accumulate_step<D>(ctx, sv, sd, i * kStep, L, acc);
         }
 
         // Finish the per-head sum across the four q-groups of the wave.
         acc.l += __shfl_xor(acc.l, 16);
         acc.l += __shfl_xor(acc.l, 32);
 
-        if (ctx.r < G) {
-            const int32_t head = h * G + ctx.r;
-            if (cnt == n_b) {  // the whole stream: normalise and write the result
-                const float inv = 1.0f / acc.l;
-                const int64_t idx = ((int64_t)b * prm.Hq + head) * D + 4 * ctx.q;
-#pragma unroll
-                for (int nt = 0; nt < D / 16; ++nt) {
-                    const f32x4_t o = acc.o[nt] * inv;
-                    if (prm.out_f32) {
-                        *(f32x4_t*)((float*)out + idx + 16 * nt) = o;
-                    } else {
-                        uint2 pk;
-                        pk.x = pack_bf16_rne(o[0], o[1]);
-                        pk.y = pack_bf16_rne(o[2], o[3]);
-                        *(uint2*)((__bf16*)out + idx + 16 * nt) = pk;
+        const int64_t out_idx = ((int64_t)b * prm.Hq + (int64_t)h * G + rr) * D + 4 * ctx.q;
+        if (cnt == n_b) {  // the whole stream: normalise and write the result
+            if (ctx.r < G) store_result<D>(acc, out, out_idx, prm.out_f32);
+        } else {
+            // A piece of a stream that spans the waves w0..w1.  Piece i comes from wave w0 + i and
+            // sits in that wave's slot 2(w0 + i), except that w0 uses its second slot when the
+            // stream is not the first one it touched.
+            const int64_t g0 = (int64_t)pre[b] * Hkv + (int64_t)h * n_b;
+            const int32_t w0 = deal.owner(g0), w1 = deal.owner(g0 + n_b - 1);
+            const int32_t pieces = w1 - w0 + 1;
+            const int64_t slot0 = 2 * (int64_t)w0 + (deal.first_step(w0) == g0 ? 0 : 1);
+            const int64_t my_slot = 2 * (int64_t)w + (first_stream ? 0 : 1);
+            if (ctx.r < G) store_piece<D>(acc, part_ml, part_acc, my_slot, G, ctx.r, ctx.q);
+
+            const int32_t gid = (w - w0) / kMergeGroup;
+            const int32_t gfirst = gid * kMergeGroup;               // first piece of my group
+            const int32_t gsize = min(kMergeGroup, pieces - gfirst);
+            const int32_t ngroups = (pieces + kMergeGroup - 1) / kMergeGroup;
+            // Slots are unique per piece, so the slot of a group's first piece names the group
+            // (a wave can end one stream and begin the next: wave numbers alone would collide).
+            auto piece_slot = [&](int32_t pi) -> int64_t { return pi == 0 ? slot0 : 2 * (int64_t)(w0 + pi); };
+            const int64_t group_slot = piece_slot(gfirst);
+            if (arrive_last(group_arrivals + group_slot, gsize, lane)) {
+                WaveAcc<D> grp;
+                merge_pieces<D>(grp, part_ml, part_acc, gsize,
+                                [&](int32_t i) -> int64_t { return piece_slot(gfirst + i); }, G, rr, ctx.q);
+                if (ngroups == 1) {
+                    if (ctx.r < G) store_result<D>(grp, out, out_idx, prm.out_f32);
+                } else {
+                    if (ctx.r < G) store_piece<D>(grp, group_ml, group_acc, group_slot, G, ctx.r, ctx.q);
+                    if (arrive_last(stream_arrivals + b * Hkv + h, ngroups, lane)) {
+                        WaveAcc<D> all;
+                        merge_pieces<D>(all, group_ml, group_acc, ngroups,
+                                        [&](int32_t j) -> int64_t { return piece_slot(j * kMergeGroup); }, G,
+                                        rr, ctx.q);
+                        if (ctx.r < G) store_result<D>(all, out, out_idx, prm.out_f32);
                     }
                 }
-            } else {           // a piece: slot 2w for the wave's first stream, 2w + 1 otherwise
-                const int64_t slot = ((int64_t)2 * w + (first_stream ? 0 : 1)) * G + ctx.r;
-                if (ctx.q == 0) part_ml[slot] = make_float2(acc.m, acc.l);
-                float* dst = part_acc + slot * D + 4 * ctx.q;
-#pragma unroll
-                for (int nt = 0; nt < D / 16; ++nt) *(f32x4_t*)(dst + 16 * nt) = acc.o[nt];
             }
         }
 
@@ -404,85 +573,6 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
     }
 }
 
-// ---------------------------------------------------------------------------
-// Merge of the pieces of every (row, KV head) stream that was cut across waves;
-// also zero-fills empty rows.  One workgroup per stream; the piece weights are
-// staged in LDS, then a thread owns (head, d) outputs.
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void attn_merge(const int32_t* __restrict__ row_off,
-                                                   const float2* __restrict__ part_ml,
-                                                   const float* __restrict__ part_acc,
-                                                   void* __restrict__ out, int32_t D, AttnParams prm) {
-    __shared__ float s_max[16], s_inv[16];  // per head: max over pieces, 1 / normalising sum
-    const int32_t b = blockIdx.x / prm.Hkv;
-    const int32_t h = blockIdx.x % prm.Hkv;
-    const int32_t G = prm.G;
-    const int32_t n_b = row_off[b + 1] - row_off[b];
-    const int64_t base_out = ((int64_t)b * prm.Hq + (int64_t)h * G) * D;
-    if (n_b == 0) {
-        for (int32_t e = threadIdx.x; e < G * D; e += blockDim.x) {
-            if (prm.out_f32) ((float*)out)[base_out + e] = 0.f;
-            else ((__bf16*)out)[base_out + e] = (__bf16)0.f;
-        }
-        return;
-    }
-    const Deal deal((int64_t)row_off[prm.B] * prm.Hkv, prm.W);
-    const int64_t g0 = (int64_t)row_off[b] * prm.Hkv + (int64_t)h * n_b;
-    const int32_t w0 = deal.owner(g0), w1 = deal.owner(g0 + n_b - 1);
-    if (w0 == w1) return;  // written whole by its wave
-    const int32_t pieces = w1 - w0 + 1;
-    // slot of piece p (wave w0 + p): the wave's first stream (2w) unless w0 entered it mid-range
-    const int32_t slot0 = 2 * w0 + (deal.first_step(w0) == g0 ? 0 : 1);
-    auto slot_of = [&](int32_t p) -> int64_t { return p == 0 ? slot0 : 2 * (w0 + p); };
-
-    for (int32_t g = threadIdx.x; g < G; g += blockDim.x) {
-        float M = -INFINITY;
-        for (int32_t p = 0; p < pieces; ++p) M = fmaxf(M, part_ml[slot_of(p) * G + g].x);
-        float lsum = 0.f;
-        for (int32_t p = 0; p < pieces; ++p) {
-            const float2 ml = part_ml[slot_of(p) * G + g];
-            lsum += ml.y * __builtin_amdgcn_exp2f(ml.x - M);
-        }
-        s_max[g] = M;
-        s_inv[g] = 1.0f / lsum;
-    }
-    __syncthreads();
-    // A thread owns 4 consecutive head-dim outputs of one head.
-    for (int32_t e4 = threadIdx.x; e4 < G * D / 4; e4 += blockDim.x) {
-        const int32_t g = (e4 * 4) / D;
-        const float M = s_max[g], inv = s_inv[g];
-        f32x4_t o = {0.f, 0.f, 0.f, 0.f};
-        int32_t p = 0;
-        for (; p + 4 <= pieces; p += 4) {
-            f32x4_t v[4];
-            float wgt[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int64_t slot = slot_of(p + u);
-                v[u] = *(const f32x4_t*)(part_acc + slot * G * D + (int64_t)e4 * 4);
-                wgt[u] = part_ml[slot * G + g].x;
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) o += v[u] * __builtin_amdgcn_exp2f(wgt[u] - M);
-        }
-        for (; p < pieces; ++p) {
-            const int64_t slot = slot_of(p);
-            const f32x4_t v = *(const f32x4_t*)(part_acc + slot * G * D + (int64_t)e4 * 4);
-            o += v * __builtin_amdgcn_exp2f(part_ml[slot * G + g].x - M);
-        }
-        o *= inv;
-        const int64_t idx = base_out + (int64_t)e4 * 4;
-        if (prm.out_f32) {
-            *(f32x4_t*)((float*)out + idx) = o;
-        } else {
-            uint2 pk;
-            pk.x = pack_bf16_rne(o[0], o[1]);
-            pk.y = pack_bf16_rne(o[2], o[3]);
-            *(uint2*)((__bf16*)out + idx) = pk;
-        }
-    }
-}
-
 int validate(const roll_attn_desc* d) {
     if (!d) return roll::fail(ROLL_ERR_INVALID_ARG, "desc is NULL");
     if (d->batch <= 0 || d->batch > kMaxBatch) return roll::fail(ROLL_ERR_INVALID_ARG, "batch must be in [1, %d]", kMaxBatch);
@@ -490,6 +580,8 @@ int validate(const roll_attn_desc* d) {
         return roll::fail(ROLL_ERR_INVALID_ARG, "num_q_heads must be a positive multiple of num_kv_heads");
     if (d->num_q_heads / d->num_kv_heads > 16)
         return roll::fail(ROLL_ERR_INVALID_ARG, "GQA group size above 16 is not supported");
+    if ((int64_t)d->batch * d->num_kv_heads > kMaxStreams)
+        return roll::fail(ROLL_ERR_INVALID_ARG, "batch * num_kv_heads above %d", kMaxStreams);
     if (d->head_dim != 64 && d->head_dim != 128) return roll::fail(ROLL_ERR_INVALID_ARG, "head_dim must be 64 or 128");
     if (d->page_size != 16 && d->page_size != 32 && d->page_size != 64)
         return roll::fail(ROLL_ERR_INVALID_ARG, "page_size must be 16, 32 or 64");
@@ -526,15 +618,22 @@ int persistent_waves(int head_dim, size_t lds_bytes, int32_t* waves_out) {
     return ROLL_OK;
 }
 
-// Upper bound used to size the workspace without touching the device: 16 waves on each of
-// 256 compute units (a gfx950 device has no more).
-constexpr int32_t kMaxPersistentWaves = 16 * 256;
-
 }  // namespace
 
 extern "C" size_t roll_decode_attn_workspace_bytes(const roll_attn_desc* d) {
     if (validate(d) != ROLL_OK) return 0;
-    return carve(nullptr, d->batch, d->num_q_heads / d->num_kv_heads, d->head_dim, kMaxPersistentWaves).bytes;
+    return carve(nullptr, d->num_q_heads / d->num_kv_heads, d->head_dim).bytes;
+}
+
+extern "C" int roll_decode_attn_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
+    const Workspace ws = carve(workspace, 1, 64);
+    if (!workspace || !roll::aligned(workspace, 256)) return roll::fail(ROLL_ERR_WORKSPACE, "workspace NULL or not 256-byte aligned");
+    if (workspace_bytes < ws.header_bytes)
+        return roll::fail(ROLL_ERR_WORKSPACE, "workspace too small: %zu < %zu bytes", workspace_bytes, ws.header_bytes);
+    const size_t words = ws.header_bytes / 4;
+    zero_words<<<(unsigned)((words + 255) / 256), 256, 0, (hipStream_t)stream>>>((uint32_t*)workspace, words);
+    ROLL_HIP_CHECK(hipGetLastError());
+    return ROLL_OK;
 }
 
 extern "C" int roll_decode_attn(const void* q, const void* k_pages, const void* v_pages,
@@ -550,7 +649,7 @@ extern "C" int roll_decode_attn(const void* q, const void* k_pages, const void* 
         return roll::fail(ROLL_ERR_INVALID_ARG, "q, k_pages, v_pages, out must be 16-byte aligned");
     const int32_t G = d->num_q_heads / d->num_kv_heads;
     if (!workspace || !roll::aligned(workspace, 256)) return roll::fail(ROLL_ERR_WORKSPACE, "workspace NULL or not 256-byte aligned");
-    Workspace ws = carve(workspace, d->batch, G, d->head_dim, kMaxPersistentWaves);
+    Workspace ws = carve(workspace, G, d->head_dim);
     if (workspace_bytes < ws.bytes)
         return roll::fail(ROLL_ERR_WORKSPACE, "workspace too small: %zu < %zu bytes", workspace_bytes, ws.bytes);
 
@@ -581,16 +680,12 @@ extern "C" int roll_decode_attn(const void* q, const void* k_pages, const void* 
     if (d->head_dim == 128)
         attn_stream<128><<<grid, kGroupWaves * 64, lds, stream>>>(
             (const uint4*)q, (const uint4*)k_pages, (const uint4*)v_pages, page_table, seq_lens, out,
-            ws.row_off, ws.part_ml, ws.part_acc, prm);
+            ws.group_arrivals, ws.stream_arrivals, ws.part_ml, ws.part_acc, ws.group_ml, ws.group_acc, prm);
     else
         attn_stream<64><<<grid, kGroupWaves * 64, lds, stream>>>(
             (const uint4*)q, (const uint4*)k_pages, (const uint4*)v_pages, page_table, seq_lens, out,
-            ws.row_off, ws.part_ml, ws.part_acc, prm);
+            ws.group_arrivals, ws.stream_arrivals, ws.part_ml, ws.part_acc, ws.group_ml, ws.group_acc, prm);
     ROLL_HIP_CHECK(hipGetLastError());
     if (d->ev_main_end) ROLL_HIP_CHECK(hipEventRecord((hipEvent_t)d->ev_main_end, stream));
-
-    attn_merge<<<d->batch * d->num_kv_heads, 256, 0, stream>>>(ws.row_off, ws.part_ml, ws.part_acc, out,
-                                                              d->head_dim, prm);
-    ROLL_HIP_CHECK(hipGetLastError());
     return ROLL_OK;
 }

@@ -58,8 +58,7 @@ class DecodeBatch:
         self.profile_events = profile_events
         self.out_dtype = out_dtype
         self.desc = rb.attn_desc(self.q, self.k_pages, self.page_table, P, out_dtype)
-        self._ws = torch.empty(rb.roll_decode_attn_workspace_bytes(self.desc), dtype=torch.uint8,
-                               device=device)
+        self._ws = rb.new_attn_workspace(self.desc, device)
         self.grow_to(lengths)
 
     # -- allocator ------------------------------------------------------------

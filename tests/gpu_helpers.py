@@ -22,7 +22,7 @@ def run_attn(inp, cfg, out_dtype=torch.float32, softmax_scale=0.0, seq_lens=None
     B, Hq, D = q.shape
     out = torch.full((B, Hq, D), float("nan"), dtype=out_dtype, device=dev)
     desc = rb.attn_desc(q, k_pages, table, cfg.page_size, out_dtype, softmax_scale)
-    ws = torch.empty(rb.roll_decode_attn_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+    ws = rb.new_attn_workspace(desc, dev)
     rb.roll_decode_attn(q, k_pages, v_pages, table, lens, out, desc, ws)
     torch.cuda.synchronize()
     return out.double().cpu().numpy()
