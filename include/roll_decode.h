@@ -138,6 +138,19 @@ int roll_kv_release(roll_kv_pool* pool, int32_t slot);
  */
 int roll_kv_commit(roll_kv_pool* pool, void* stream);
 
+/*
+ * roll_kv_commit and, in the same kernel launch, the K/V append of a decode
+ * step: the vectors k_new[slot], v_new[slot] are written at the last position
+ * (seq_len - 1) of every slot that holds a sequence; empty slots are skipped.
+ * The target page of each slot is taken from the pool's host state, so the
+ * write does not depend on the device tables being published first.
+ *   k_new, v_new    DEVICE bf16 [num_slots, num_kv_heads, head_dim], row-major
+ *   k_pages,v_pages DEVICE bf16 pools of cfg.num_pages pages
+ */
+int roll_kv_commit_append(roll_kv_pool* pool, const void* k_new, const void* v_new,
+                          void* k_pages, void* v_pages, int32_t num_kv_heads,
+                          int32_t head_dim, void* stream);
+
 /* HOST introspection. */
 int roll_kv_free_pages(const roll_kv_pool* pool);               /* count, or < 0 */
 int roll_kv_seq_len(const roll_kv_pool* pool, int32_t slot);    /* tokens, or < 0 */

@@ -22,7 +22,7 @@ ROLL_BF16, ROLL_F32 = 0, 1
 EXPORTS = [
     "roll_last_error", "roll_version",
     "roll_kv_pool_create", "roll_kv_pool_destroy", "roll_kv_alloc", "roll_kv_alloc_batch", "roll_kv_release",
-    "roll_kv_commit", "roll_kv_free_pages", "roll_kv_seq_len", "roll_kv_slot_pages",
+    "roll_kv_commit", "roll_kv_commit_append", "roll_kv_free_pages", "roll_kv_seq_len", "roll_kv_slot_pages",
     "roll_kv_append_tokens",
     "roll_decode_attn_workspace_bytes", "roll_decode_attn_workspace_init", "roll_decode_attn",
     "roll_sample_logprob_workspace_bytes", "roll_sample_logprob",
@@ -79,6 +79,7 @@ def lib():
         L.roll_kv_alloc_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]
         L.roll_kv_release.argtypes = [C.c_void_p, C.c_int32]
         L.roll_kv_commit.argtypes = [C.c_void_p, C.c_void_p]
+        L.roll_kv_commit_append.argtypes = [C.c_void_p] * 5 + [C.c_int32, C.c_int32, C.c_void_p]
         L.roll_kv_free_pages.argtypes = [C.c_void_p]
         L.roll_kv_seq_len.argtypes = [C.c_void_p, C.c_int32]
         L.roll_kv_slot_pages.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_int32]
@@ -174,6 +175,15 @@ def roll_kv_release(pool: KvPool, slot: int) -> None:
 
 def roll_kv_commit(pool: KvPool) -> None:
     _check(lib().roll_kv_commit(pool._h, _stream()))
+
+
+def roll_kv_commit_append(pool: KvPool, k_new, v_new, k_pages, v_pages) -> None:
+    """Publish the tables and write k_new[slot], v_new[slot] at position seq_len - 1 of every live slot."""
+    n, Hkv, D = k_new.shape
+    assert n == pool.cfg.num_slots and tuple(v_new.shape) == (n, Hkv, D)
+    _check(lib().roll_kv_commit_append(pool._h, _dev(k_new, torch.bfloat16), _dev(v_new, torch.bfloat16),
+                                       _dev(k_pages, torch.bfloat16), _dev(v_pages, torch.bfloat16), Hkv, D,
+                                       _stream()))
 
 
 def roll_kv_free_pages(pool: KvPool) -> int:

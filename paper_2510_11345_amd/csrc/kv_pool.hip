@@ -27,7 +27,7 @@ constexpr int kRing = 8;
 constexpr int kStageDeltas = 8192;  // (index, value) pairs per staging block
 
 struct Stage {
-    int32_t* host = nullptr;  // pinned; [num_slots lengths][2 * kStageDeltas deltas]
+    int32_t* host = nullptr;  // pinned; [num_slots lengths][num_slots append targets][2 * kStageDeltas deltas]
     int32_t* dev = nullptr;   // the same block as seen from the GPU
     hipEvent_t consumed = nullptr;
     bool in_flight = false;
@@ -38,29 +38,63 @@ __global__ void fill_i32(int32_t* dst, int64_t n, int32_t value) {
     if (i < n) dst[i] = value;
 }
 
-// stage = [lengths (num_slots, only if copy_lens)][pairs]; one thread per entry.
+// Store 8 consecutive head-dim elements of one token's K and V into the two page layouts.
+//   K page layout [page][h][d/8][kpos(t)][d%8]: the slice is one 16-byte store.
+//   V page layout [page][h][t/8][d][t%8]: the slice is 8 two-byte stores, 16 bytes apart.
+__device__ __forceinline__ void store_kv_slice(uint4 kv, uint4 vv, uint4* __restrict__ k_pages,
+                                               uint16_t* __restrict__ v_pages, int32_t page, int32_t t,
+                                               int32_t h, int32_t c, int32_t P, int32_t Hkv, int32_t D) {
+    // kpos: inside blocks of min(P, 32) tokens, the low quad of every 8 tokens goes to the
+    // first half of the block and the high quad to the second half.
+    const int32_t width = P < 32 ? P : 32;
+    const int32_t u = t & (width - 1);
+    const int32_t kpos = (t - u) + (u & 3) + 4 * (u >> 3) + (width >> 1) * ((u >> 2) & 1);
+    k_pages[(((int64_t)page * Hkv + h) * (D / 8) + c) * P + kpos] = kv;
+    uint16_t* vdst = v_pages + ((((int64_t)page * Hkv + h) * (P / 8) + t / 8) * D + c * 8) * 8 + t % 8;
+    const uint32_t w[4] = {vv.x, vv.y, vv.z, vv.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        vdst[(2 * j) * 8] = (uint16_t)(w[j] & 0xFFFFu);
+        vdst[(2 * j + 1) * 8] = (uint16_t)(w[j] >> 16);
+    }
+}
+
+// stage = [lengths (num_slots)][append targets (num_slots)][pairs]; one thread per entry.
+// With k_new set, the same launch also writes the newest token of every slot whose target
+// (page * P + position in page, computed on the host from the same state) is >= 0.
 __global__ void apply_updates(const int32_t* __restrict__ stage, int32_t* __restrict__ page_table,
                               int32_t* __restrict__ seq_lens, int32_t num_slots, int32_t copy_lens,
-                              int32_t n_delta, int64_t table_elems) {
-    int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+                              int32_t n_delta, int64_t table_elems, const uint4* __restrict__ k_new,
+                              const uint4* __restrict__ v_new, uint4* __restrict__ k_pages,
+                              uint16_t* __restrict__ v_pages, int32_t num_pages, int32_t P, int32_t Hkv,
+                              int32_t D) {
+    const int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (copy_lens && i < num_slots) seq_lens[i] = stage[i];
     if (i < n_delta) {
-        int32_t idx = stage[num_slots + 2 * i];
-        int32_t val = stage[num_slots + 2 * i + 1];
+        const int32_t idx = stage[2 * num_slots + 2 * i];
+        const int32_t val = stage[2 * num_slots + 2 * i + 1];
         if (idx >= 0 && idx < table_elems) page_table[idx] = val;
+    }
+    if (k_new) {
+        const int32_t d8n = D / 8;
+        const int32_t items = num_slots * Hkv * d8n;
+        if (i < items) {
+            const int32_t c = i % d8n, h = (i / d8n) % Hkv, slot = i / (d8n * Hkv);
+            const int32_t target = stage[num_slots + slot];
+            if (target >= 0 && target / P < num_pages)
+                store_kv_slice(k_new[i], v_new[i], k_pages, v_pages, target / P, target % P, h, c, P, Hkv, D);
+        }
     }
 }
 
 // One thread per (token, kv head, 8-element slice of head_dim).
-//   K page layout [page][h][d/8][kpos(t)][d%8]: the slice is one 16-byte store.
-//   V page layout [page][h][t/8][d][t%8]: the slice is 8 two-byte stores, 16 bytes apart.
 __global__ void append_tokens(const uint4* __restrict__ k_new, const uint4* __restrict__ v_new,
                               const int32_t* __restrict__ slots, const int32_t* __restrict__ positions,
-                              const int32_t* __restrict__ seq_lens, int64_t n_items, uint4* __restrict__ k_pages,
-                              uint16_t* __restrict__ v_pages, const int32_t* __restrict__ page_table,
-                              int32_t max_pages, int32_t num_pages, int32_t P, int32_t Hkv,
-                              int32_t D) {
-    int64_t item = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+                              const int32_t* __restrict__ seq_lens, int64_t n_items,
+                              uint4* __restrict__ k_pages, uint16_t* __restrict__ v_pages,
+                              const int32_t* __restrict__ page_table, int32_t max_pages,
+                              int32_t num_pages, int32_t P, int32_t Hkv, int32_t D) {
+    const int64_t item = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (item >= n_items) return;
     const int32_t d8n = D / 8;
     const int32_t c = (int32_t)(item % d8n);
@@ -74,22 +108,7 @@ __global__ void append_tokens(const uint4* __restrict__ k_new, const uint4* __re
     if (pidx >= max_pages) return;
     const int32_t page = page_table[(int64_t)slot * max_pages + pidx];
     if (page < 0 || page >= num_pages) return;
-    const int32_t t = pos % P;
-    const uint4 kv = k_new[item];
-    const uint4 vv = v_new[item];
-    // kpos: inside blocks of min(P, 32) tokens, the low quad of every 8 tokens goes to the
-    // first half of the block and the high quad to the second half.
-    const int32_t width = P < 32 ? P : 32;
-    const int32_t u = t & (width - 1);
-    const int32_t kpos = (t - u) + (u & 3) + 4 * (u >> 3) + (width >> 1) * ((u >> 2) & 1);
-    k_pages[(((int64_t)page * Hkv + h) * d8n + c) * P + kpos] = kv;
-    uint16_t* vdst = v_pages + ((((int64_t)page * Hkv + h) * (P / 8) + t / 8) * D + c * 8) * 8 + t % 8;
-    const uint32_t w[4] = {vv.x, vv.y, vv.z, vv.w};
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        vdst[(2 * j) * 8] = (uint16_t)(w[j] & 0xFFFFu);
-        vdst[(2 * j + 1) * 8] = (uint16_t)(w[j] >> 16);
-    }
+    store_kv_slice(k_new[item], v_new[item], k_pages, v_pages, page, pos % P, h, c, P, Hkv, D);
 }
 
 }  // namespace
@@ -249,7 +268,7 @@ static int acquire_stage(roll_kv_pool* pool, Stage** out) {
     Stage& s = pool->ring[pool->ring_next];
     pool->ring_next = (pool->ring_next + 1) % kRing;
     if (!s.host) {
-        const size_t bytes = sizeof(int32_t) * ((size_t)pool->cfg.num_slots + 2 * (size_t)kStageDeltas);
+        const size_t bytes = sizeof(int32_t) * (2 * (size_t)pool->cfg.num_slots + 2 * (size_t)kStageDeltas);
         ROLL_HIP_CHECK(hipHostMalloc((void**)&s.host, bytes, hipHostMallocDefault));
         ROLL_HIP_CHECK(hipHostGetDevicePointer((void**)&s.dev, s.host, 0));
         ROLL_HIP_CHECK(hipEventCreateWithFlags(&s.consumed, hipEventDisableTiming));
@@ -262,7 +281,15 @@ static int acquire_stage(roll_kv_pool* pool, Stage** out) {
     return ROLL_OK;
 }
 
-extern "C" int roll_kv_commit(roll_kv_pool* pool, void* stream_v) {
+struct AppendArgs {
+    const uint4* k_new = nullptr;
+    const uint4* v_new = nullptr;
+    uint4* k_pages = nullptr;
+    uint16_t* v_pages = nullptr;
+    int32_t Hkv = 0, D = 0;
+};
+
+static int commit_impl(roll_kv_pool* pool, void* stream_v, const AppendArgs& ap) {
     if (!pool) return roll::fail(ROLL_ERR_INVALID_ARG, "pool is NULL");
     if (!pool->page_table_dev) return roll::fail(ROLL_ERR_INVALID_ARG, "host-only pool has no device tables to commit to");
     hipStream_t stream = (hipStream_t)stream_v;
@@ -305,13 +332,26 @@ extern "C" int roll_kv_commit(roll_kv_pool* pool, void* stream_v) {
         const int32_t batch = (int32_t)std::min<size_t>(kStageDeltas, n_pairs - done);
         // Lengths go with the last block so that they never run ahead of their pages.
         const bool last = done + batch >= n_pairs;
+        const bool append = last && ap.k_new != nullptr;
         if (last) std::memcpy(s->host, pool->slot_len.data(), sizeof(int32_t) * c.num_slots);
+        if (append) {  // where the newest token of each live slot goes: page * P + position in page
+            int32_t* target = s->host + c.num_slots;
+            for (int32_t slot = 0; slot < c.num_slots; ++slot) {
+                const int32_t len = pool->slot_len[slot];
+                target[slot] = len > 0 ? pool->slot_pages[(size_t)slot * c.max_pages_per_seq + (len - 1) / c.page_size] * c.page_size +
+                                             (len - 1) % c.page_size
+                                       : -1;
+            }
+        }
         if (batch > 0)
-            std::memcpy(s->host + c.num_slots, pool->pending.data() + 2 * done, sizeof(int32_t) * 2 * batch);
+            std::memcpy(s->host + 2 * c.num_slots, pool->pending.data() + 2 * done, sizeof(int32_t) * 2 * batch);
         const int threads = 256;
-        const int32_t n = std::max(last ? c.num_slots : 0, batch);
+        int32_t n = std::max(last ? c.num_slots : 0, batch);
+        if (append) n = std::max(n, c.num_slots * ap.Hkv * (ap.D / 8));
         apply_updates<<<(n + threads - 1) / threads, threads, 0, stream>>>(
-            s->dev, pool->page_table_dev, pool->seq_lens_dev, c.num_slots, last ? 1 : 0, batch, table_elems);
+            s->dev, pool->page_table_dev, pool->seq_lens_dev, c.num_slots, last ? 1 : 0, batch, table_elems,
+            append ? ap.k_new : nullptr, ap.v_new, ap.k_pages, ap.v_pages, c.num_pages, c.page_size, ap.Hkv,
+            ap.D);
         ROLL_HIP_CHECK(hipGetLastError());
         ROLL_HIP_CHECK(hipEventRecord(s->consumed, stream));
         s->in_flight = true;
@@ -320,6 +360,26 @@ extern "C" int roll_kv_commit(roll_kv_pool* pool, void* stream_v) {
     }
     pool->pending.clear();
     return ROLL_OK;
+}
+
+extern "C" int roll_kv_commit(roll_kv_pool* pool, void* stream) { return commit_impl(pool, stream, AppendArgs{}); }
+
+extern "C" int roll_kv_commit_append(roll_kv_pool* pool, const void* k_new, const void* v_new, void* k_pages,
+                                     void* v_pages, int32_t num_kv_heads, int32_t head_dim, void* stream) {
+    if (!k_new || !v_new || !k_pages || !v_pages) return roll::fail(ROLL_ERR_INVALID_ARG, "NULL pointer argument");
+    if (!roll::aligned(k_new, 16) || !roll::aligned(v_new, 16) || !roll::aligned(k_pages, 16) || !roll::aligned(v_pages, 16))
+        return roll::fail(ROLL_ERR_INVALID_ARG, "k_new, v_new, k_pages, v_pages must be 16-byte aligned");
+    if (head_dim <= 0 || head_dim % 8 != 0 || num_kv_heads <= 0) return roll::fail(ROLL_ERR_INVALID_ARG, "bad shape");
+    if (pool && (int64_t)pool->cfg.num_pages * pool->cfg.page_size > INT32_MAX)
+        return roll::fail(ROLL_ERR_INVALID_ARG, "pool above 2^31 tokens");
+    AppendArgs ap;
+    ap.k_new = (const uint4*)k_new;
+    ap.v_new = (const uint4*)v_new;
+    ap.k_pages = (uint4*)k_pages;
+    ap.v_pages = (uint16_t*)v_pages;
+    ap.Hkv = num_kv_heads;
+    ap.D = head_dim;
+    return commit_impl(pool, stream, ap);
 }
 
 extern "C" int roll_kv_append_tokens(const void* k_new, const void* v_new, const int32_t* slots,

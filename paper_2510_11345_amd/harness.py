@@ -81,14 +81,12 @@ class DecodeBatch:
     # -- one decode step --------------------------------------------------------
     def step(self, logits: torch.Tensor, step_index: int, temperature=None, top_p=None,
              grow: bool = True) -> None:
-        """alloc (+1 token per row) -> commit -> append K/V -> attention -> sample."""
+        """alloc (+1 token per row) -> commit + append K/V (one launch) -> attention -> sample."""
         cfg = self.cfg
         if grow:
             rb.roll_kv_alloc_batch(self.pool, self.all_slots, self.ones)
             self.lengths += 1
-            rb.roll_kv_commit(self.pool)
-            rb.roll_kv_append_tokens(self.k_new, self.v_new, None, None, self.seq_lens, self.k_pages,
-                                     self.v_pages, self.page_table, cfg.page_size)
+            rb.roll_kv_commit_append(self.pool, self.k_new, self.v_new, self.k_pages, self.v_pages)
         desc = self.desc
         if self.profile_events:
             e0, e1 = self.ev_spare.pop() if self.ev_spare else (rb.ProfEvent(), rb.ProfEvent())

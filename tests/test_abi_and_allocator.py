@@ -147,3 +147,21 @@ def test_attention_and_sampling_reject_bad_descriptors_on_the_host():
     bad = rb.SampleDesc(2, 4097, 4097, rb.ROLL_BF16, 0, None)  # rows would not be 16-byte aligned
     assert L.roll_sample_logprob(16, 1.0, 1.0, 0, 0, 16, 16, C.byref(bad), None, 0, None) == -1
     assert L.roll_sample_logprob(None, 1.0, 1.0, 0, 0, 16, 16, C.byref(sd), None, 0, None) == -1
+
+
+def test_alloc_batch_is_all_or_nothing():
+    pool = host_pool(num_pages=10, slots=4, max_pages=8)
+    rb.roll_kv_alloc_batch(pool, np.array([0, 2], np.int32), np.array([20, 1], np.int32))
+    assert rb.roll_kv_seq_len(pool, 0) == 20 and rb.roll_kv_seq_len(pool, 2) == 1
+    snap = (owned(pool, 4), rb.roll_kv_free_pages(pool))
+    for slots, n, status in [([0, 0], [1, 1], -1),          # repeated slot
+                             ([1, 3], [5 * 16, 4 * 16], -2),  # 9 pages needed, 7 free
+                             ([1, 0], [1, 8 * 16], -5),       # slot 0 would exceed max_pages
+                             ([1, 7], [1, 1], -4),
+                             ([1, 3], [1, 0], -1)]:
+        with pytest.raises(rb.RollError) as e:
+            rb.roll_kv_alloc_batch(pool, np.array(slots, np.int32), np.array(n, np.int32))
+        assert e.value.status == status
+        assert (owned(pool, 4), rb.roll_kv_free_pages(pool)) == snap
+    rb.roll_kv_alloc_batch(pool, np.array([], np.int32), np.array([], np.int32))
+    check_conservation(pool, 4, 10)

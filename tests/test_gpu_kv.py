@@ -89,3 +89,39 @@ def test_append_tokens_writes_the_documented_layouts(Hkv, D, P):
     assert np.array_equal(wl.bits(k_pages).reshape(-1), ek)
     assert np.array_equal(wl.bits(v_pages).reshape(-1), ev)
     pool.close()
+
+
+@pytest.mark.parametrize("Hkv,D,P", [(4, 128, 16), (8, 128, 32)])
+def test_commit_append_publishes_and_writes_in_one_launch(Hkv, D, P):
+    say(f"  commit_append case Hkv={Hkv} D={D} P={P}")
+    slots, max_pages = 6, 5
+    num_pages = slots * max_pages
+    pool, table, lens = make_pool(num_pages, P, slots, max_pages)
+    k_pages = torch.zeros((num_pages, Hkv, D // 8, P, 8), dtype=torch.bfloat16, device="cuda")
+    v_pages = torch.zeros((num_pages, Hkv, P // 8, D, 8), dtype=torch.bfloat16, device="cuda")
+    ek = np.zeros(num_pages * Hkv * D * P, np.uint16)
+    ev = np.zeros_like(ek)
+    L = [P - 1, 0, 2 * P, 5, 0, 3 * P + 7]           # slots 1 and 4 stay empty
+    for s, l in enumerate(L):
+        if l:
+            rb.roll_kv_alloc(pool, s, l)
+    live = np.array([s for s, l in enumerate(L) if l], np.int32)
+    for step in range(3):                            # crosses a page boundary for slots 0 and 2
+        rb.roll_kv_alloc_batch(pool, live, np.ones(len(live), np.int32))
+        k_new = wl.randn_bf16((slots, Hkv, D), 2, 60 + step)
+        v_new = wl.randn_bf16((slots, Hkv, D), 2, 70 + step)
+        rb.roll_kv_commit_append(pool, k_new.cuda(), v_new.cuda(), k_pages, v_pages)
+        kb, vb = wl.bits(k_new), wl.bits(v_new)
+        for s in live:
+            pos = rb.roll_kv_seq_len(pool, int(s)) - 1
+            page = rb.roll_kv_slot_pages(pool, int(s))[pos // P]
+            oracle.kv_store(ek, ev, page, pos % P, kb[s], vb[s], Hkv, D, P)
+    torch.cuda.synchronize()
+    assert np.array_equal(wl.bits(k_pages).reshape(-1), ek)
+    assert np.array_equal(wl.bits(v_pages).reshape(-1), ev)
+    t, l = table.cpu().numpy(), lens.cpu().numpy()
+    assert list(l) == [x + 3 if x else 0 for x in L]
+    for s in range(slots):
+        pages = rb.roll_kv_slot_pages(pool, s)
+        assert list(t[s, :len(pages)]) == pages
+    pool.close()
