@@ -25,15 +25,20 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0  # MI355X published peak
 
 
-def profiled_traffic(workload: str):
-    """HBM bytes per launch measured with rocprofv3 --pmc, if a summary under profiles/ states it
-    as a line `traffic_bytes_per_launch[<workload>]: <number>`."""
-    pat = re.compile(r"traffic_bytes_per_launch\[" + re.escape(workload) + r"\]:\s*([0-9.eE+]+)")
+def profiled_traffic(workload: str, algorithmic_bytes: float):
+    """HBM bytes per launch of the attention kernel from the rocprofv3 --pmc summary under
+    profiles/ (lines `traffic_bytes_per_launch[<workload>]` and `algorithmic_bytes_in_that_run[...]`),
+    scaled from the profiled run's algorithmic bytes to this run's.  None if no summary covers
+    the workload."""
+    key = re.escape(workload)
+    pat_t = re.compile(r"traffic_bytes_per_launch\[" + key + r"\]:\s*([0-9.eE+]+)")
+    pat_a = re.compile(r"algorithmic_bytes_in_that_run\[" + key + r"\]:\s*([0-9.eE+]+)")
     for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.txt")) +
                        glob.glob(os.path.join(ROOT, "profiles", "*.md"))):
-        m = pat.search(open(path).read())
-        if m:
-            return float(m.group(1))
+        text = open(path).read()
+        mt, ma = pat_t.search(text), pat_a.search(text)
+        if mt and ma:
+            return float(mt.group(1)) * algorithmic_bytes / float(ma.group(1))
     return None
 
 
@@ -45,7 +50,9 @@ def main():
     ap.add_argument("--config", default="c2", choices=["c2", "c3", "c5"])
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--oracle-rows", type=int, default=16)
+    ap.add_argument("--oracle-rows", type=int, default=0, help="rows timed on the CPU oracle (0 = the whole batch)")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="only run one plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU: rollout decode is data-parallel over sequences with "
@@ -62,6 +69,15 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     rb.lib()  # fail loudly if the HIP library is missing
+    if args.pmc_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_calibration": "one device copy", "bytes_read": src.numel() * 4,
+                          "bytes_written": dst.numel() * 4}))
+        return
     cfg = wl.CONFIGS[args.config]
     K, W = args.steps, args.warmup
     lengths = wl.draw_lengths(cfg.lengths, cfg.batch, args.seed, cfg.max_len).astype(np.int64)
@@ -114,13 +130,13 @@ def main():
         "kv_read_frac_of_peak": achieved / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "kernel": "attn_stream", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": profiled_traffic(cfg.name),
+                     "traffic": profiled_traffic(cfg.name, avg_kv_bytes),
                      "algorithmic_bytes_per_launch": avg_kv_bytes, "avg_launch_ms": avg_kern_ms},
     }
 
     if not args.no_cpu_baseline:
         import oracle
-        n = min(args.oracle_rows, cfg.batch)
+        n = cfg.batch if args.oracle_rows <= 0 else min(args.oracle_rows, cfg.batch)
         rows = [int(r) for r in np.linspace(0, cfg.batch - 1, n).round().astype(int)]
         rows = sorted(set(rows))
         q, k, v, table, lens = batch.gather_rows(rows)
