@@ -25,7 +25,7 @@ class DecodeBatch:
     def __init__(self, cfg: wl.DecodeConfig, seed: int, lengths: np.ndarray, headroom_tokens: int = 0,
                  out_dtype=torch.bfloat16, device: str = "cuda",
                  spare_pages: int = 64, max_len: int | None = None, fill_pools: bool = True,
-                 profile_events: bool = False):
+                 profile_events: bool = False, num_pages: int | None = None):
         self.cfg, self.seed, self.device = cfg, seed, device
         B, P = cfg.batch, cfg.page_size
         Hq, Hkv, D = cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim
@@ -34,7 +34,7 @@ class DecodeBatch:
         cap = int(max(int(lengths.max()) + headroom_tokens, 1)) if max_len is None else int(max_len)
         self.max_pages = (cap + P - 1) // P
         need = int(((np.minimum(lengths + headroom_tokens, cap) + P - 1) // P).sum())
-        self.num_pages = need + spare_pages
+        self.num_pages = need + spare_pages if num_pages is None else int(num_pages)
         self.page_table = torch.empty((B, self.max_pages), dtype=torch.int32, device=device)
         self.seq_lens = torch.zeros((B,), dtype=torch.int32, device=device)
         self.pool = rb.KvPool(self.num_pages, P, B, self.max_pages, self.page_table, self.seq_lens)
@@ -120,3 +120,64 @@ class DecodeBatch:
 
     def close(self):
         self.pool.close()
+
+
+class RefillLoop:
+    """Queue-scheduled continuous refill on top of a DecodeBatch: every slot holds a request with
+    a pre-drawn target length; a slot whose request has finished is released and at once given
+    the next prompt of the queue, whose K/V (synthetic, seeded by the request id) is written into
+    freshly allocated pages; then every slot decodes one token."""
+
+    def __init__(self, cfg: wl.DecodeConfig, plan: wl.RefillPlan, seed: int, max_len: int,
+                 out_dtype=torch.bfloat16, device: str = "cuda"):
+        self.cfg, self.plan, self.seed, self.device = cfg, plan, seed, device
+        B = cfg.batch
+        self.request = np.arange(B, dtype=np.int64)          # request id held by each slot
+        self.generated = plan.start_generated[:B].astype(np.int64).copy()
+        self.next_request = B
+        start_len = plan.prompt_len[:B].astype(np.int64) + self.generated
+        # the pool can hold every slot at max_len, so a refill never runs out of pages
+        total_pages = B * ((max_len + cfg.page_size - 1) // cfg.page_size)
+        self.batch = DecodeBatch(cfg, seed, start_len, out_dtype=out_dtype, device=device,
+                                 max_len=max_len, fill_pools=True, num_pages=total_pages)
+        self.refills = 0
+        self.refill_log = []  # (step, slot, request)
+
+    def _prompt_kv(self, request: int, n: int):
+        cfg = self.cfg
+        k = wl.randn_bf16((n, cfg.num_kv_heads, cfg.head_dim), self.seed, 1000 + 2 * request, self.device)
+        v = wl.randn_bf16((n, cfg.num_kv_heads, cfg.head_dim), self.seed, 1001 + 2 * request, self.device)
+        return k, v
+
+    def step(self, logits: torch.Tensor, step_index: int) -> list:
+        """One scheduler tick + one decode step.  Returns the slots refilled at this step."""
+        b, plan, cfg = self.batch, self.plan, self.cfg
+        done = np.flatnonzero(self.generated >= plan.target_len[self.request])
+        refilled = []
+        for slot in done:
+            if self.next_request >= len(plan.prompt_len):
+                raise RuntimeError("prompt queue exhausted")
+            rb.roll_kv_release(b.pool, int(slot))
+            req = self.next_request
+            self.next_request += 1
+            n = int(plan.prompt_len[req])
+            rb.roll_kv_alloc(b.pool, int(slot), n)
+            self.request[slot], self.generated[slot] = req, 0
+            b.lengths[slot] = n
+            refilled.append((int(slot), req, n))
+        if refilled:
+            rb.roll_kv_commit(b.pool)   # the prompt writer looks its pages up on the device
+            for slot, req, n in refilled:
+                k, v = self._prompt_kv(req, n)
+                slots = torch.full((n,), slot, dtype=torch.int32, device=self.device)
+                pos = torch.arange(n, dtype=torch.int32, device=self.device)
+                rb.roll_kv_append_tokens(k, v, slots, pos, None, b.k_pages, b.v_pages, b.page_table,
+                                         cfg.page_size)
+                self.refill_log.append((step_index, slot, req))
+            self.refills += len(refilled)
+        b.step(logits, step_index)      # +1 token per slot, commit + append, attention, sampling
+        self.generated += 1
+        return [r[0] for r in refilled]
+
+    def close(self):
+        self.batch.close()

@@ -202,11 +202,16 @@ class RefillPlan:
     start_generated: np.ndarray  # tokens already generated by the initial occupants
 
 
-def draw_refill_plan(num_slots: int, num_requests: int, seed: int) -> RefillPlan:
+def draw_refill_plan(num_slots: int, num_requests: int, seed: int, prompt_range=(128, 1024),
+                     target_median: float = 1500.0, target_clip=(16, 16384)) -> RefillPlan:
+    """Prompt queue of the continuous-refill workload: request i has a prompt of prompt_len[i]
+    tokens and finishes after target_len[i] generated tokens.  The first num_slots requests
+    occupy the slots at step 0 and have already generated start_generated[i] < target_len[i]
+    tokens, so that finishes are spread over the run instead of bunched at its start."""
     rng = np.random.default_rng([seed, 0x52454649])
-    prompt = rng.integers(128, 1025, size=num_requests).astype(np.int32)
-    target = np.clip(np.rint(np.exp(rng.normal(math.log(1500.0), 1.0, size=num_requests))),
-                     16, 16384).astype(np.int32)
+    prompt = rng.integers(prompt_range[0], prompt_range[1] + 1, size=num_requests).astype(np.int32)
+    target = np.clip(np.rint(np.exp(rng.normal(math.log(target_median), 1.0, size=num_requests))),
+                     target_clip[0], target_clip[1]).astype(np.int32)
     start = np.zeros(num_requests, dtype=np.int32)
     start[:num_slots] = (rng.random(num_slots) * target[:num_slots]).astype(np.int32)
     return RefillPlan(prompt, target, start)

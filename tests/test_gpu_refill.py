@@ -1,0 +1,82 @@
+"""Queue-scheduled continuous refill through the C ABI (needs an MI355X): slots finish by
+pre-drawn target length, are released and refilled from a prompt queue, and every step's
+sampling (and a subset of steps' attention) is checked against the oracle."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2510_11345_amd import binding as rb
+from paper_2510_11345_amd import workloads as wl
+from paper_2510_11345_amd.harness import RefillLoop
+from gpu_helpers import say
+
+pytestmark = pytest.mark.gpu
+
+
+def test_refill_loop_reduced():
+    # config 4 at reduced size: 24 slots, 7B-class heads, 48 steps, short targets so that
+    # about one slot finishes per step
+    cfg = dataclasses.replace(wl.CONFIGS["c4"], batch=24, vocab=8192)
+    steps = 48
+    plan = wl.draw_refill_plan(cfg.batch, cfg.batch + 200, seed=3, prompt_range=(5, 90),
+                               target_median=30.0, target_clip=(2, 400))
+    loop = RefillLoop(cfg, plan, seed=3, max_len=90 + 400 + steps + 2, out_dtype=torch.float32)
+    b = loop.batch
+    total_pages = b.num_pages
+    attn_checked = 0
+    for step in range(steps):
+        logits = wl.make_logits(cfg, 3, "cuda", salt=100 + step)
+        refilled = loop.step(logits, step)
+        torch.cuda.synchronize()
+        # allocator invariants after every tick
+        owned = sum(len(rb.roll_kv_slot_pages(b.pool, s)) for s in range(cfg.batch))
+        assert owned + rb.roll_kv_free_pages(b.pool) == total_pages
+        assert np.array_equal(b.seq_lens.cpu().numpy(), b.lengths.astype(np.int32))
+        # sampling parity every step (row id = slot, step = decode step)
+        ref = oracle.sample_logprob(wl.logits_numpy(logits), cfg.temperature, cfg.top_p, 3, step)
+        tok, lp = b.tokens.cpu().numpy(), b.logprob.double().cpu().numpy()
+        bad = [r for r in range(cfg.batch) if tok[r] != ref["tokens"][r] and ref["gap"][r] >= 1e-5]
+        assert not bad, (step, bad)
+        same = tok == ref["tokens"]
+        assert np.abs(lp - ref["logprob"])[same].max() <= 1e-3
+        # attention parity on the first and last step, every 8th, and right after a refill
+        if step in (0, steps - 1) or step % 8 == 0 or refilled:
+            rows = list(range(cfg.batch))
+            q, k, v, table, lens = b.gather_rows(rows)
+            want = oracle.decode_attn(q, k, v, table, lens, cfg.num_q_heads, cfg.num_kv_heads,
+                                      cfg.head_dim, cfg.page_size)
+            err = np.abs(b.out.double().cpu().numpy() - want).max()
+            assert err <= 1e-4, (step, err)
+            attn_checked += 1
+    say(f"  refill loop: {steps} steps, {loop.refills} refills, attention checked on {attn_checked} steps, "
+        f"free pages at the end {rb.roll_kv_free_pages(b.pool)}")
+    assert loop.refills >= 10
+    loop.close()
+
+
+def test_abort_mid_sequence_then_refill():
+    # ABORT = release of a live slot; its pages go back and the next prompt reuses them
+    cfg = dataclasses.replace(wl.CONFIGS["c4"], batch=4, vocab=4096)
+    plan = wl.draw_refill_plan(4, 12, seed=5, prompt_range=(20, 40), target_median=1000.0,
+                               target_clip=(900, 1000))
+    loop = RefillLoop(cfg, plan, seed=5, max_len=1100, out_dtype=torch.float32)
+    b = loop.batch
+    logits = wl.make_logits(cfg, 5, "cuda")
+    loop.step(logits, 0)
+    free_before = rb.roll_kv_free_pages(b.pool)
+    pages = rb.roll_kv_slot_pages(b.pool, 2)
+    loop.generated[2] = 10**9            # force slot 2 to be reclaimed at the next tick
+    refilled = loop.step(logits, 1)
+    assert refilled == [2]
+    new_pages = rb.roll_kv_slot_pages(b.pool, 2)
+    assert set(new_pages) <= set(pages) or len(new_pages) <= len(pages)
+    assert rb.roll_kv_free_pages(b.pool) >= free_before
+    torch.cuda.synchronize()
+    q, k, v, table, lens = b.gather_rows([0, 1, 2, 3])
+    want = oracle.decode_attn(q, k, v, table, lens, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim,
+                              cfg.page_size)
+    assert np.abs(b.out.double().cpu().numpy() - want).max() <= 1e-4
+    loop.close()
