@@ -1,0 +1,60 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times (needs an
+MI355X): one decode step of c2, c3 and c5 through the harness; attention on sampled rows (the
+shortest, the longest, and rows spread over the batch), sampling on sampled rows."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2510_11345_amd import workloads as wl
+from paper_2510_11345_amd.harness import DecodeBatch
+from gpu_helpers import say
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("name", ["c2", "c3", "c5"])
+def test_full_size_step_matches_oracle_on_sampled_rows(name):
+    cfg = wl.CONFIGS[name]
+    lengths = wl.draw_lengths(cfg.lengths, cfg.batch, 0, cfg.max_len).astype(np.int64)
+    say(f"  full-size case {name}: B={cfg.batch} sum L={int(lengths.sum())} max L={int(lengths.max())}")
+    batch = DecodeBatch(cfg, 0, lengths - 1, headroom_tokens=4)
+    logits = wl.make_logits(cfg, 0, "cuda")
+    batch.step(logits, 0)
+    torch.cuda.synchronize()
+    assert np.array_equal(batch.lengths, lengths)
+    order = np.argsort(lengths)
+    rows = sorted(set([int(order[0]), int(order[1]), int(order[-1]), int(order[-2]), int(order[len(order) // 2])] +
+                      [int(r) for r in np.linspace(0, cfg.batch - 1, 7).round()]))
+    q, k, v, table, lens = batch.gather_rows(rows)
+    want = oracle.decode_attn(q, k, v, table, lens, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim,
+                              cfg.page_size)
+    got = batch.out[torch.tensor(rows, device="cuda")].double().cpu().numpy()
+    err = np.abs(got - want).max()
+    say(f"    attention on {len(rows)} rows (lengths {sorted(int(x) for x in lens)[:3]}..{int(lens.max())}): "
+        f"max abs err {err:.3e} (bf16 out)")
+    assert np.isfinite(got).all() and err <= 2e-2
+    # every finite-length row must have produced output (no row silently skipped by the dealing)
+    assert bool((batch.out.float().abs().sum(dim=(1, 2)) > 0).all())
+
+    srows = rows[:8]
+    ref = oracle.sample_logprob(wl.logits_numpy(logits[torch.tensor(srows, device="cuda")]), cfg.temperature,
+                                cfg.top_p, 0, 0, row_ids=srows)
+    tok = batch.tokens.cpu().numpy()[srows]
+    lp = batch.logprob.double().cpu().numpy()[srows]
+    x = logits[torch.tensor(srows, device="cuda")].float().cpu().numpy()
+    ties = band = 0
+    for i in range(len(srows)):
+        if tok[i] == ref["tokens"][i]:
+            assert abs(lp[i] - ref["logprob"][i]) <= 1e-3
+        elif ref["gap"][i] < 1e-5:
+            ties += 1
+        else:
+            in_band = lambda t: ref["x_cut_plus"][i] <= x[i, t] < ref["x_cut_minus"][i]
+            assert in_band(tok[i]) or in_band(ref["tokens"][i]), (srows[i], tok[i], ref["tokens"][i])
+            band += 1
+    say(f"    sampling on {len(srows)} rows: near-tie mismatches {ties}, boundary-band mismatches {band}")
+    # all tokens in range for the whole batch
+    all_tok = batch.tokens.cpu().numpy()
+    assert ((all_tok >= 0) & (all_tok < cfg.vocab)).all()
+    batch.close()
