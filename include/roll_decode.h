@@ -266,6 +266,11 @@ typedef struct roll_sample_desc {
     int32_t logits_dtype;   /* ROLL_BF16 or ROLL_F32 */
     int32_t reserved;
     const int32_t* row_ids; /* DEVICE int32 [B] Philox row ids, or NULL for 0..B-1 */
+    float* raw_logprob_out; /* DEVICE fp32 [B] or NULL: log_softmax(logits)[token] at temperature 1
+                             * with no truncation, for the token that was drawn.  Appendix A.1 forces
+                             * temperature 1 and top_p 1 because an engine returns one distribution
+                             * only; with both values recorded any sampling setting keeps the raw
+                             * probability available to the trainer. */
 } roll_sample_desc;
 
 size_t roll_sample_logprob_workspace_bytes(const roll_sample_desc* desc);

@@ -137,20 +137,21 @@ def _logits_args(logits):
 
 def sample_logprob(logits, temperature, top_p, seed, step, row_ids=None, band=1e-5,
                    n_threads=0):
-    """Returns dict(tokens, logprob, gap, kept, x_cut, x_cut_minus, x_cut_plus, threads)."""
+    """Returns dict(tokens, logprob, raw_logprob, gap, kept, x_cut, x_cut_minus, x_cut_plus, threads)."""
     dt, B, V, stride = _logits_args(logits)
     tokens = np.zeros(B, np.int32)
     kept = np.zeros(B, np.int32)
-    lp, gap, xc, xm, xp = (np.zeros(B, np.float64) for _ in range(5))
+    lp, gap, xc, xm, xp, raw = (np.zeros(B, np.float64) for _ in range(6))
     rid = None if row_ids is None else np.ascontiguousarray(row_ids, dtype=np.int32)
     used = lib().oracle_sample_logprob(
         C.c_void_p(logits.ctypes.data), C.c_int(dt), C.c_int(B), C.c_int(V), C.c_int64(stride),
         C.c_double(float(np.float32(temperature))), C.c_double(float(np.float32(top_p))),
         C.c_uint64(seed), C.c_uint64(step), _p(rid, C.c_int32), C.c_double(band),
         _p(tokens, C.c_int32), _p(lp, C.c_double), _p(gap, C.c_double), _p(kept, C.c_int32),
-        _p(xc, C.c_double), _p(xm, C.c_double), _p(xp, C.c_double), C.c_int(n_threads))
-    return dict(tokens=tokens, logprob=lp, gap=gap, kept=kept, x_cut=xc, x_cut_minus=xm,
-                x_cut_plus=xp, threads=used)
+        _p(xc, C.c_double), _p(xm, C.c_double), _p(xp, C.c_double), _p(raw, C.c_double),
+        C.c_int(n_threads))
+    return dict(tokens=tokens, logprob=lp, raw_logprob=raw, gap=gap, kept=kept, x_cut=xc,
+                x_cut_minus=xm, x_cut_plus=xp, threads=used)
 
 
 def top_p_cut(x, temperature, top_p):

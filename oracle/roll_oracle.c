@@ -298,7 +298,7 @@ double oracle_top_p_cut(const double* x, int V, double T, double top_p)
 static void sample_row(const void* row, int dtype, int V, double T, double top_p,
                        uint64_t seed, uint64_t step, uint32_t row_id, double band,
                        int32_t* token, double* logprob, double* gap, int32_t* kept_count,
-                       double* x_cut, double* x_cut_minus, double* x_cut_plus)
+                       double* x_cut, double* x_cut_minus, double* x_cut_plus, double* raw_logprob)
 {
     double* x = (double*)malloc(sizeof(double) * (size_t)V);
     for (int i = 0; i < V; ++i) x[i] = logit_to_double(row, dtype, i);
@@ -338,6 +338,15 @@ static void sample_row(const void* row, int dtype, int V, double T, double top_p
     }
     *token = arg;
     *logprob = x[arg] / T - lse;
+    if (raw_logprob) {
+        /* log-prob of the same token under the untouched distribution softmax(x): temperature 1,
+         * no truncation (what a training engine recomputes from the raw logits) */
+        double xm = -INFINITY, sum = 0.0;
+        for (int i = 0; i < V; ++i)
+            if (x[i] > xm) xm = x[i];
+        for (int i = 0; i < V; ++i) sum += exp(x[i] - xm);
+        *raw_logprob = x[arg] - (xm + log(sum));
+    }
     if (gap) *gap = best - second;
     if (kept_count) *kept_count = kept;
     free(x);
@@ -353,7 +362,7 @@ int oracle_sample_logprob(const void* logits, int dtype, int B, int V, int64_t r
                           const int32_t* row_ids, double band,
                           int32_t* tokens, double* logprob, double* gap, int32_t* kept_count,
                           double* x_cut, double* x_cut_minus, double* x_cut_plus,
-                          int n_threads)
+                          double* raw_logprob, int n_threads)
 {
     int used = 1;
 #ifdef _OPENMP
@@ -368,7 +377,8 @@ int oracle_sample_logprob(const void* logits, int dtype, int B, int V, int64_t r
         sample_row(row, dtype, V, temperature, top_p, seed, step, rid, band,
                    &tokens[r], &logprob[r], gap ? &gap[r] : NULL,
                    kept_count ? &kept_count[r] : NULL, x_cut ? &x_cut[r] : NULL,
-                   x_cut_minus ? &x_cut_minus[r] : NULL, x_cut_plus ? &x_cut_plus[r] : NULL);
+                   x_cut_minus ? &x_cut_minus[r] : NULL, x_cut_plus ? &x_cut_plus[r] : NULL,
+                   raw_logprob ? &raw_logprob[r] : NULL);
     }
     return used;
 }
@@ -404,7 +414,7 @@ void oracle_sample_counts(const void* row, int dtype, int V, double T, double to
         int32_t tok;
         double lp;
         sample_row(row, dtype, V, T, top_p, seed, step0 + (uint64_t)s, row_id, 0.0,
-                   &tok, &lp, NULL, NULL, NULL, NULL, NULL);
+                   &tok, &lp, NULL, NULL, NULL, NULL, NULL, NULL);
         counts[tok] += 1;
     }
 }

@@ -52,7 +52,8 @@ class AttnDesc(C.Structure):
 
 class SampleDesc(C.Structure):
     _fields_ = [("batch", C.c_int32), ("vocab", C.c_int32), ("row_stride", C.c_int64),
-                ("logits_dtype", C.c_int32), ("reserved", C.c_int32), ("row_ids", C.c_void_p)]
+                ("logits_dtype", C.c_int32), ("reserved", C.c_int32), ("row_ids", C.c_void_p),
+                ("raw_logprob_out", C.c_void_p)]
 
 
 _lib = None
@@ -254,14 +255,15 @@ def roll_decode_attn(q, k_pages, v_pages, page_table, seq_lens, out, desc: AttnD
 # ----------------------------------------------------------------------------
 # sampling
 # ----------------------------------------------------------------------------
-def sample_desc(logits, row_ids=None) -> SampleDesc:
+def sample_desc(logits, row_ids=None, raw_logprob_out=None) -> SampleDesc:
     B, V = logits.shape
     dt = ROLL_BF16 if logits.dtype == torch.bfloat16 else ROLL_F32
     if logits.dtype not in (torch.bfloat16, torch.float32):
         raise ValueError("logits must be bf16 or fp32")
     if logits.stride(1) != 1:
         raise ValueError("logits rows must be dense")
-    return SampleDesc(B, V, logits.stride(0), dt, 0, _dev(row_ids, torch.int32))
+    return SampleDesc(B, V, logits.stride(0), dt, 0, _dev(row_ids, torch.int32),
+                      _dev(raw_logprob_out, torch.float32))
 
 
 def roll_sample_logprob_workspace_bytes(desc: SampleDesc) -> int:

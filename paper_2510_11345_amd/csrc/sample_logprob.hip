@@ -10,11 +10,12 @@
 //   top_p == 1: ONE sweep over the row computes the online (max, sum-exp) for
 //     the log-sum-exp and runs the Gumbel-max race.
 //   top_p <  1: sweep 1 finds max z; a radix select over the order-preserving
-//     integer key of the logit (10 bits per level: 2 levels for bf16, 4 for
+//     integer key of the logit (one byte per level: 2 levels for bf16, 4 for
 //     fp32) finds the cut value x_cut, each level being one sweep that adds
 //     exp(z - max) in 2^-40 fixed point (integer adds commute, so the cut does
-//     not depend on thread timing) into an LDS histogram followed by a
-//     block-wide suffix scan; the last sweep runs the race over logits >= x_cut.
+//     not depend on thread timing) into an LDS histogram (16 copies per bin so
+//     that hot bins do not serialise the wave) followed by a block-wide suffix
+//     scan; the last sweep runs the race over logits >= x_cut.
 //
 // The Gumbel-max race is exact and cheap.  With g(u) = -log(-log u) and
 // -log u >= 1 - u, an entry can only win if  1 - u <= exp(z - best), best being
@@ -34,9 +35,12 @@ namespace {
 
 constexpr int kThreads = 1024;
 constexpr int kWavesPerBlock = kThreads / 64;
-constexpr int kRadixBits = 10;
+constexpr int kRadixBits = 8;              // one byte of the key per radix level
 constexpr int kBins = 1 << kRadixBits;
+constexpr int kCopies = 16;                // copies of every bin, picked by lane % 16, so that lanes
+                                           // adding to one hot bin land on different LDS banks
 constexpr double kLog2ed = 1.44269504088896340736;
+constexpr float kLog2e = 1.44269504088896340736f;
 
 struct SampleParams {
     int32_t V;
@@ -141,12 +145,22 @@ __device__ __forceinline__ uint64_t shfl_up_u64(uint64_t v, int delta) {
 }
 
 // ---- sweep bodies -----------------------------------------------------------
-struct MaxOnly {  // per-thread max of the raw logits
+template <bool RAW>
+struct MaxOnly {  // per-thread max of the raw logits; with RAW also sum exp(x - xm) (online)
     float xm = -FLT_MAX;
+    float s_raw = 0.f;
     template <int N> __device__ __forceinline__ void run(int32_t, const float (&x)[N], bool active) {
         if (!active) return;
+        float vmax = x[0];
 #pragma unroll
-        for (int j = 0; j < N; ++j) xm = fmaxf(xm, x[j]);
+        for (int j = 1; j < N; ++j) vmax = fmaxf(vmax, x[j]);
+        const float x_new = fmaxf(xm, vmax);
+        if (RAW) {
+            s_raw *= __builtin_amdgcn_exp2f((xm - x_new) * kLog2e);
+#pragma unroll
+            for (int j = 0; j < N; ++j) s_raw += __builtin_amdgcn_exp2f((x[j] - x_new) * kLog2e);
+        }
+        xm = x_new;
     }
 };
 
@@ -154,7 +168,7 @@ struct MaxOnly {  // per-thread max of the raw logits
 // per-thread reference logit follows the thread's running max and s accumulates
 // sum exp2((x - xref) k2); without it the reference is fixed (the row max) and only the
 // race runs.
-template <bool LSE>
+template <bool LSE, bool RAW>
 struct Race {
     const SampleParams& p;
     uint32_t row_id;
@@ -162,6 +176,7 @@ struct Race {
     float xref;              // reference logit of the exponentials: the running max of this
                              // thread's raw logits (LSE) or the row max (otherwise)
     float s = 0.f;           // sum of exp2((x - xref) k2) over this thread's entries (LSE only)
+    float s_raw = 0.f;       // the same at temperature 1 (LSE and RAW only)
     double best = -INFINITY; // best exact perturbed logit of this lane, natural-log units
     int32_t best_i = 0x7FFFFFFF;
     float thr2 = -INFINITY;  // wave-uniform lower bound of the wave's best, log2 units
@@ -207,6 +222,11 @@ struct Race {
             for (int j = 1; j < N; ++j) vmax = fmaxf(vmax, xa[j]);
             const float x_new = fmaxf(xref, vmax);
             s *= __builtin_amdgcn_exp2f((xref - x_new) * p.k2);
+            if (RAW) {
+                s_raw *= __builtin_amdgcn_exp2f((xref - x_new) * kLog2e);
+#pragma unroll
+                for (int j = 0; j < N; ++j) s_raw += __builtin_amdgcn_exp2f((xa[j] - x_new) * kLog2e);
+            }
             xref = x_new;
             refresh_c();
         }
@@ -231,20 +251,29 @@ struct Race {
     }
 };
 
-template <int SHIFT, int BITS>
+// w in [0, 1] as 2^-40 fixed point, truncated: the integer and the fractional part of
+// w * 2^20 are both exact in fp32, so no 64-bit float conversion is needed.
+__device__ __forceinline__ unsigned long long to_fixed40(float w) {
+    const float f = w * 0x1p20f;
+    const uint32_t a = (uint32_t)f;
+    const uint32_t b = (uint32_t)((f - (float)a) * 0x1p20f);
+    return ((unsigned long long)a << 20) | b;
+}
+
+template <int SHIFT>
 struct Histogram {  // adds exp(z - max) in 2^-40 fixed point to the bin of the key's digit
     float k2, xmax;
-    uint32_t prefix;  // the key's bits above SHIFT + BITS must equal this
-    unsigned long long* hist;
+    uint32_t prefix;  // the key's bits above SHIFT + kRadixBits must equal this
+    unsigned long long* hist;  // [kBins][kCopies]
+    uint32_t copy;             // this lane's copy
     template <int N> __device__ __forceinline__ void run(int32_t, const float (&x)[N], bool active) {
         if (!active) return;
 #pragma unroll
         for (int j = 0; j < N; ++j) {
             const uint32_t key = order_key(x[j]);
-            if (SHIFT + BITS < 32 && (key >> ((SHIFT + BITS) & 31)) != prefix) continue;
-            const float w = __builtin_amdgcn_exp2f((x[j] - xmax) * k2);
-            const unsigned long long fx = (unsigned long long)((double)w * 0x1p40);
-            if (fx) atomicAdd(&hist[(key >> SHIFT) & ((1u << BITS) - 1u)], fx);
+            if (SHIFT + kRadixBits < 32 && (key >> ((SHIFT + kRadixBits) & 31)) != prefix) continue;
+            const unsigned long long fx = to_fixed40(__builtin_amdgcn_exp2f((x[j] - xmax) * k2));
+            if (fx) atomicAdd(&hist[((key >> SHIFT) & (kBins - 1u)) * kCopies + copy], fx);
         }
     }
 };
@@ -254,15 +283,15 @@ struct Select {
     unsigned long long above;   // fixed-point mass of keys strictly above the prefix range
 };
 
-// hist holds kBins bins; thread t owns bin (kBins - 1 - t) so that a forward inclusive scan over
-// threads is a suffix sum over bins.  Picks the highest bin at which above + suffix >= target.
-__device__ void scan_select(unsigned long long* hist, unsigned long long* s_wave, Select* s_sel,
-                            unsigned long long target, int bits) {
+// tot holds kBins bin totals; thread t owns bin (kBins - 1 - t) so that a forward inclusive scan
+// over threads is a suffix sum over bins.  Picks the highest bin at which above + suffix >= target.
+__device__ void scan_select(const unsigned long long* tot, unsigned long long* s_wave, Select* s_sel,
+                            unsigned long long target) {
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int nb = 1 << bits;
+    const int nb = kBins, bits = kRadixBits;
     const int bin = nb - 1 - tid;
-    const unsigned long long mine = (tid < nb) ? hist[bin] : 0ull;
+    const unsigned long long mine = (tid < nb) ? tot[bin] : 0ull;
     unsigned long long incl = mine;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
@@ -285,19 +314,26 @@ __device__ void scan_select(unsigned long long* hist, unsigned long long* s_wave
 
 // One radix level: histogram of the digit at SHIFT (BITS wide) over the entries whose higher
 // key bits equal the prefix chosen so far, then the suffix scan that picks the next digit.
-template <typename T, int SHIFT, int BITS, bool FIRST>
+template <typename T, int SHIFT, bool FIRST>
 __device__ void radix_level(const T* __restrict__ row, const SampleParams& p, float xmax,
-                            unsigned long long* s_hist, unsigned long long* s_wave, Select* s_sel,
-                            unsigned long long& target) {
+                            unsigned long long* s_hist, unsigned long long* s_tot,
+                            unsigned long long* s_wave, Select* s_sel, unsigned long long& target) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int i = tid; i < kBins; i += kThreads) s_hist[i] = 0ull;
+    for (int i = tid; i < kBins * kCopies; i += kThreads) s_hist[i] = 0ull;
     __syncthreads();
-    Histogram<SHIFT, BITS> h{p.k2, xmax, s_sel->prefix, s_hist};
+    Histogram<SHIFT> h{p.k2, xmax, s_sel->prefix, s_hist, (uint32_t)(lane & (kCopies - 1))};
     sweep<T>(row, p.V, h);
+    __syncthreads();
+    if (tid < kBins) {  // fold the copies of my bin
+        unsigned long long t = 0;
+#pragma unroll
+        for (int c = 0; c < kCopies; ++c) t += s_hist[tid * kCopies + ((c + tid) & (kCopies - 1))];
+        s_tot[tid] = t;
+    }
     __syncthreads();
     if (FIRST) {  // total mass -> target = ceil(top_p * total)
         unsigned long long incl = 0;
-        for (int i = tid; i < kBins; i += kThreads) incl += s_hist[i];
+        for (int i = tid; i < kBins; i += kThreads) incl += s_tot[i];
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
             const unsigned long long v = shfl_up_u64(incl, d);
@@ -312,15 +348,19 @@ __device__ void radix_level(const T* __restrict__ row, const SampleParams& p, fl
         if (target > total) target = total;
         __syncthreads();
     }
-    scan_select(s_hist, s_wave, s_sel, target, BITS);
+    scan_select(s_tot, s_wave, s_sel, target);
 }
 
-template <typename T, bool TOPP>
+// RAW: also accumulate sum exp(x - max) at temperature 1 for raw_logprob_out (needed only when
+// the sampled distribution differs from the raw one).
+template <typename T, bool TOPP, bool RAW>
 __global__ __launch_bounds__(kThreads) void sample_rows(const T* __restrict__ logits,
                                                          const int32_t* __restrict__ row_ids,
                                                          int32_t* __restrict__ tokens_out,
-                                                         float* __restrict__ logprob_out, SampleParams p) {
-    __shared__ unsigned long long s_hist[TOPP ? kBins : 1];
+                                                         float* __restrict__ logprob_out,
+                                                         float* __restrict__ raw_logprob_out, SampleParams p) {
+    __shared__ unsigned long long s_hist[TOPP ? kBins * kCopies : 1];
+    __shared__ unsigned long long s_tot[TOPP ? kBins : 1];
     __shared__ unsigned long long s_wave[kWavesPerBlock];
     __shared__ Select s_sel;
     __shared__ float s_m[kWavesPerBlock];
@@ -329,14 +369,16 @@ __global__ __launch_bounds__(kThreads) void sample_rows(const T* __restrict__ lo
     __shared__ int32_t s_besti[kWavesPerBlock];
     __shared__ float s_xcut;
     __shared__ double s_lse;
+    __shared__ double s_sraw[kWavesPerBlock];
+    __shared__ double s_raw_lse;
 
     const int32_t r = blockIdx.x;
     const T* __restrict__ row = logits + (int64_t)r * p.row_stride;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t row_id = row_ids ? (uint32_t)row_ids[r] : (uint32_t)r;
 
-    Race<true> race{p, row_id, -INFINITY, -FLT_MAX};
-    MaxOnly mo;
+    Race<true, RAW> race{p, row_id, -INFINITY, -FLT_MAX};
+    MaxOnly<RAW> mo;
     if (!TOPP) sweep<T>(row, p.V, race);  // one sweep: online log-sum-exp and the race together
     else sweep<T>(row, p.V, mo);
 
@@ -348,38 +390,42 @@ __global__ __launch_bounds__(kThreads) void sample_rows(const T* __restrict__ lo
 #pragma unroll
         for (int mask = 1; mask < 64; mask <<= 1) m = fmaxf(m, __shfl_xor(m, mask));
         double s = TOPP ? 0.0 : (double)race.s * (double)__builtin_amdgcn_exp2f((mine - m) * p.k2);
+        double sr = (double)(TOPP ? mo.s_raw : race.s_raw) * (double)__builtin_amdgcn_exp2f((mine - m) * kLog2e);
 #pragma unroll
-        for (int mask = 1; mask < 64; mask <<= 1) s += shfl_xor_f64(s, mask);
-        if (lane == 0) { s_m[wave] = m; s_s[wave] = s; }
+        for (int mask = 1; mask < 64; mask <<= 1) {
+            s += shfl_xor_f64(s, mask);
+            sr += shfl_xor_f64(sr, mask);
+        }
+        if (lane == 0) { s_m[wave] = m; s_s[wave] = s; s_sraw[wave] = sr; }
         __syncthreads();
         if (tid == 0) {
             float M = s_m[0];
             for (int w = 1; w < kWavesPerBlock; ++w) M = fmaxf(M, s_m[w]);
-            double S = 0.0;
-            for (int w = 0; w < kWavesPerBlock; ++w)
+            double S = 0.0, SR = 0.0;
+            for (int w = 0; w < kWavesPerBlock; ++w) {
                 S += s_s[w] * (double)__builtin_amdgcn_exp2f((s_m[w] - M) * p.k2);
+                SR += s_sraw[w] * (double)__builtin_amdgcn_exp2f((s_m[w] - M) * kLog2e);
+            }
             s_m[0] = M;
             s_lse = (double)M / p.temperature + log(S);
+            s_raw_lse = (double)M + log(SR);
             s_sel.prefix = 0;
             s_sel.above = 0;
         }
         __syncthreads();
     }
 
-    Race<false> race_kept{p, row_id, -INFINITY, 0.f};
+    Race<false, false> race_kept{p, row_id, -INFINITY, 0.f};
     if (TOPP) {
         const float xM = s_m[0];
         constexpr int kKeyBits = Elem<T>::kKeyBits;
         unsigned long long target = 0;
         // Levels from the most significant digit down; the last level may be narrower.
-        if (kKeyBits == 16) {
-            radix_level<T, 22, 10, true>(row, p, xM, s_hist, s_wave, &s_sel, target);
-            radix_level<T, 16, 6, false>(row, p, xM, s_hist, s_wave, &s_sel, target);
-        } else {
-            radix_level<T, 22, 10, true>(row, p, xM, s_hist, s_wave, &s_sel, target);
-            radix_level<T, 12, 10, false>(row, p, xM, s_hist, s_wave, &s_sel, target);
-            radix_level<T, 2, 10, false>(row, p, xM, s_hist, s_wave, &s_sel, target);
-            radix_level<T, 0, 2, false>(row, p, xM, s_hist, s_wave, &s_sel, target);
+        radix_level<T, 24, true>(row, p, xM, s_hist, s_tot, s_wave, &s_sel, target);
+        radix_level<T, 16, false>(row, p, xM, s_hist, s_tot, s_wave, &s_sel, target);
+        if (kKeyBits == 32) {
+            radix_level<T, 8, false>(row, p, xM, s_hist, s_tot, s_wave, &s_sel, target);
+            radix_level<T, 0, false>(row, p, xM, s_hist, s_tot, s_wave, &s_sel, target);
         }
         if (tid == 0) {
             // s_sel.prefix is now the key of the cut value (its upper 16 bits for bf16, whose
@@ -389,9 +435,8 @@ __global__ __launch_bounds__(kThreads) void sample_rows(const T* __restrict__ lo
             const uint32_t key = (s_sel.prefix << (32 - kKeyBits)) |
                                  (kKeyBits == 16 ? ((s_sel.prefix >> 15) ? 0u : 0xFFFFu) : 0u);
             s_xcut = key_to_float(key);
-            constexpr int last_bits = kKeyBits == 16 ? 6 : 2;
-            const uint32_t digit = s_sel.prefix & ((1u << last_bits) - 1u);
-            const unsigned long long kept = s_sel.above + s_hist[digit];
+            const uint32_t digit = s_sel.prefix & (kBins - 1u);
+            const unsigned long long kept = s_sel.above + s_tot[digit];
             s_lse = (double)xM / p.temperature + log((double)kept * 0x1p-40);
         }
         __syncthreads();
@@ -419,10 +464,14 @@ __global__ __launch_bounds__(kThreads) void sample_rows(const T* __restrict__ lo
             if ((uint32_t)bi >= (uint32_t)p.V) {  // no finite entry in the row
                 tokens_out[r] = 0;
                 logprob_out[r] = NAN;
+                if (raw_logprob_out) raw_logprob_out[r] = NAN;
             } else {
                 tokens_out[r] = bi;
-                const double z = (double)Elem<T>::widen(row[bi]) / p.temperature;
-                logprob_out[r] = (float)(z - s_lse);
+                const double x = (double)Elem<T>::widen(row[bi]);
+                const float lp = (float)(x / p.temperature - s_lse);
+                logprob_out[r] = lp;
+                // without an extra sum the sampled distribution is the raw one (T = 1, top_p = 1)
+                if (raw_logprob_out) raw_logprob_out[r] = RAW ? (float)(x - s_raw_lse) : lp;
             }
         }
     }
@@ -469,14 +518,24 @@ extern "C" int roll_sample_logprob(const void* logits, float temperature, float 
     p.step_lo = (uint32_t)step;
     p.step_hi = (uint32_t)(step >> 32);
     const bool topp = top_p < 1.0f;
+    float* raw = d->raw_logprob_out;
+    const bool raw_sum = raw != nullptr && (topp || temperature != 1.0f);
     const dim3 grid(d->batch), block(kThreads);
-    if (d->logits_dtype == ROLL_BF16) {
-        if (topp) sample_rows<uint16_t, true><<<grid, block, 0, stream>>>((const uint16_t*)logits, d->row_ids, tokens_out, logprob_out, p);
-        else sample_rows<uint16_t, false><<<grid, block, 0, stream>>>((const uint16_t*)logits, d->row_ids, tokens_out, logprob_out, p);
-    } else {
-        if (topp) sample_rows<float, true><<<grid, block, 0, stream>>>((const float*)logits, d->row_ids, tokens_out, logprob_out, p);
-        else sample_rows<float, false><<<grid, block, 0, stream>>>((const float*)logits, d->row_ids, tokens_out, logprob_out, p);
+    const int variant = (d->logits_dtype == ROLL_BF16 ? 0 : 4) + (topp ? 2 : 0) + (raw_sum ? 1 : 0);
+#define ROLL_LAUNCH_SAMPLE(T, TOPP, RAW)                                                            \
+    sample_rows<T, TOPP, RAW><<<grid, block, 0, stream>>>((const T*)logits, d->row_ids, tokens_out, \
+                                                          logprob_out, raw, p)
+    switch (variant) {
+        case 0: ROLL_LAUNCH_SAMPLE(uint16_t, false, false); break;
+        case 1: ROLL_LAUNCH_SAMPLE(uint16_t, false, true); break;
+        case 2: ROLL_LAUNCH_SAMPLE(uint16_t, true, false); break;
+        case 3: ROLL_LAUNCH_SAMPLE(uint16_t, true, true); break;
+        case 4: ROLL_LAUNCH_SAMPLE(float, false, false); break;
+        case 5: ROLL_LAUNCH_SAMPLE(float, false, true); break;
+        case 6: ROLL_LAUNCH_SAMPLE(float, true, false); break;
+        default: ROLL_LAUNCH_SAMPLE(float, true, true); break;
     }
+#undef ROLL_LAUNCH_SAMPLE
     ROLL_HIP_CHECK(hipGetLastError());
     return ROLL_OK;
 }

@@ -37,17 +37,20 @@ def oracle_attn(inp, cfg, rows=None, scale=None, seq_lens=None):
                               scale=scale, rows=rows)
 
 
-def run_sample(logits, T, top_p, seed, step, row_ids=None):
+def run_sample(logits, T, top_p, seed, step, row_ids=None, want_raw=False):
     dev = "cuda"
     lg = logits if logits.is_cuda else logits.to(dev)
     B = lg.shape[0]
     tokens = torch.full((B,), -7, dtype=torch.int32, device=dev)
     lp = torch.full((B,), float("nan"), dtype=torch.float32, device=dev)
     rid = None if row_ids is None else torch.tensor(row_ids, dtype=torch.int32, device=dev)
-    desc = rb.sample_desc(lg, rid)
+    raw = torch.full((B,), float("nan"), dtype=torch.float32, device=dev) if want_raw else None
+    desc = rb.sample_desc(lg, rid, raw)
     ws = torch.empty(rb.roll_sample_logprob_workspace_bytes(desc), dtype=torch.uint8, device=dev)
     rb.roll_sample_logprob(lg, T, top_p, seed, step, tokens, lp, desc, ws)
     torch.cuda.synchronize()
+    if want_raw:
+        return tokens.cpu().numpy(), lp.double().cpu().numpy(), raw.double().cpu().numpy()
     return tokens.cpu().numpy(), lp.double().cpu().numpy()
 
 
@@ -56,7 +59,9 @@ def compare_sampling(logits, T, top_p, seed, step, row_ids=None, lp_tol=1e-3):
     token ids identical unless the oracle's top-two gap is below 1e-5 or a token lies in the
     top-p boundary band; log-probs within lp_tol wherever the tokens agree."""
     import oracle
-    tok, lp = run_sample(logits, T, top_p, seed, step, row_ids)
+    tok, lp, raw = run_sample(logits, T, top_p, seed, step, row_ids, want_raw=True)
+    tok2, lp2 = run_sample(logits, T, top_p, seed, step, row_ids)        # without the raw output
+    assert np.array_equal(tok, tok2) and np.array_equal(lp, lp2)
     ref = oracle.sample_logprob(wl.logits_numpy(logits), T, top_p, seed, step, row_ids=row_ids)
     x = wl.logits_numpy(logits)
     if x.dtype == np.uint16:
@@ -65,6 +70,7 @@ def compare_sampling(logits, T, top_p, seed, step, row_ids=None, lp_tol=1e-3):
     for r in range(len(tok)):
         if tok[r] == ref["tokens"][r]:
             assert abs(lp[r] - ref["logprob"][r]) <= lp_tol, (r, lp[r], ref["logprob"][r])
+            assert abs(raw[r] - ref["raw_logprob"][r]) <= lp_tol, (r, raw[r], ref["raw_logprob"][r])
             continue
         in_band = lambda t: ref["x_cut_plus"][r] <= x[r, t] < ref["x_cut_minus"][r]
         if ref["gap"][r] < 1e-5:

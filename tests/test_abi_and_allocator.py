@@ -138,13 +138,13 @@ def test_attention_and_sampling_reject_bad_descriptors_on_the_host():
     assert L.roll_decode_attn(8, 16, 16, 16, 16, 16, C.byref(good), 256, 1 << 30, None) == -1
     assert L.roll_decode_attn(16, 16, 16, 16, 16, 16, C.byref(good), 256, 8, None) == -6
     assert L.roll_decode_attn(16, 16, 16, 16, 16, 16, C.byref(good), None, 1 << 30, None) == -6
-    sd = rb.SampleDesc(2, 4096, 4096, rb.ROLL_F32, 0, None)
+    sd = rb.SampleDesc(2, 4096, 4096, rb.ROLL_F32, 0, None, None)
     assert L.roll_sample_logprob_workspace_bytes(C.byref(sd)) > 0
     for T, p in [(0.0, 1.0), (-1.0, 1.0), (1.0, 0.0), (1.0, 1.5), (float("nan"), 1.0), (1.0, float("nan"))]:
         assert L.roll_sample_logprob(16, T, p, 0, 0, 16, 16, C.byref(sd), None, 0, None) == -1
-    bad = rb.SampleDesc(2, 4096, 4095, rb.ROLL_F32, 0, None)
+    bad = rb.SampleDesc(2, 4096, 4095, rb.ROLL_F32, 0, None, None)
     assert L.roll_sample_logprob(16, 1.0, 1.0, 0, 0, 16, 16, C.byref(bad), None, 0, None) == -1
-    bad = rb.SampleDesc(2, 4097, 4097, rb.ROLL_BF16, 0, None)  # rows would not be 16-byte aligned
+    bad = rb.SampleDesc(2, 4097, 4097, rb.ROLL_BF16, 0, None, None)  # rows would not be 16-byte aligned
     assert L.roll_sample_logprob(16, 1.0, 1.0, 0, 0, 16, 16, C.byref(bad), None, 0, None) == -1
     assert L.roll_sample_logprob(None, 1.0, 1.0, 0, 0, 16, 16, C.byref(sd), None, 0, None) == -1
 

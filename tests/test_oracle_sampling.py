@@ -37,6 +37,20 @@ def test_logprob_bf16_logits_and_temperature():
         assert abs(r["logprob"][b] - ref[b, r["tokens"][b]]) < 1e-12
 
 
+def test_raw_logprob_is_library_log_softmax_whatever_the_sampling_setting():
+    rng = np.random.default_rng(11)
+    xb = to_bf16_bits(rng.standard_normal((5, 700)) * 2)
+    ref = scipy.special.log_softmax(from_bf16_bits(xb), axis=1)
+    for T, p in [(1.0, 1.0), (0.7, 0.95), (1.4, 0.5)]:
+        r = oracle.sample_logprob(xb, T, p, seed=2, step=1)
+        for b in range(5):
+            assert abs(r["raw_logprob"][b] - ref[b, r["tokens"][b]]) < 1e-12
+        if T == 1.0 and p == 1.0:
+            np.testing.assert_allclose(r["raw_logprob"], r["logprob"], atol=1e-12)
+        else:
+            assert not np.allclose(r["raw_logprob"], r["logprob"])
+
+
 def test_uniform_logits_give_minus_log_V():
     x = np.full((2, 300), 1.25, dtype=np.float32)
     r = oracle.sample_logprob(x, 1.0, 1.0, seed=0, step=0)
