@@ -53,6 +53,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 
 constexpr int kGroupWaves = 4;     // wavefronts per workgroup (they only share the LDS prefix)
 constexpr int kStep = 32;          // tokens per wave step
+constexpr bool kDoubleBuffer = false;  // keep the next step's loads in flight while computing
 constexpr int kMinSteps = 4;       // do not spread a small batch thinner than this per wave
 constexpr int kMaxBatch = 8192;    // rows whose prefix sums fit the LDS budget
 constexpr int kMaxStreams = 65536; // batch * num_kv_heads: one arrival counter each
@@ -502,17 +503,43 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
         acc.m = -INFINITY;
         acc.l = 0.f;
 
-        // All 16 loads of a step are issued together and the wave then waits for them; the other
-        // wave on the SIMD streams meanwhile.  (Requesting the next step's K and V into the
-        // registers as soon as the MFMAs free them was measured and gave nothing: in steady state
-        // the kernel is bound by the memory system, not by bytes in flight per wave.)
-        for (int32_t i = s; i < s + cnt; ++i) {
-            StepData<D> sd;
-            load_k<D>(ctx, i * kStep, sd);
-            load_v<D>(ctx, i * kStep, sd);
-            float sv[8];
-            score_step<D>(ctx, qf, sd, i * kStep, L, prm.scale_log2e, sv);
-            accumulate_step<D>(ctx, sv, sd, i * kStep, L, acc);
+        if (kDoubleBuffer) {
+            // Two register sets: the loads of step i + 1 are in flight while step i is computed.
+            StepData<D> s0, s1;
+            const int32_t end_step = s + cnt;
+            int32_t i = s;
+            load_k<D>(ctx, i * kStep, s0);
+            load_v<D>(ctx, i * kStep, s0);
+            for (;;) {
+                float sv[8];
+                const bool more1 = i + 1 < end_step;
+                if (more1) {
+                    load_k<D>(ctx, (i + 1) * kStep, s1);
+                    load_v<D>(ctx, (i + 1) * kStep, s1);
+                }
+                score_step<D>(ctx, qf, s0, i * kStep, L, prm.scale_log2e, sv);
+                accumulate_step<D>(ctx, sv, s0, i * kStep, L, acc);
+                if (!more1) break;
+                ++i;
+                const bool more0 = i + 1 < end_step;
+                if (more0) {
+                    load_k<D>(ctx, (i + 1) * kStep, s0);
+                    load_v<D>(ctx, (i + 1) * kStep, s0);
+                }
+                score_step<D>(ctx, qf, s1, i * kStep, L, prm.scale_log2e, sv);
+                accumulate_step<D>(ctx, sv, s1, i * kStep, L, acc);
+                if (!more0) break;
+                ++i;
+            }
+        } else {
+            for (int32_t i = s; i < s + cnt; ++i) {
+                StepData<D> sd;
+                load_k<D>(ctx, i * kStep, sd);
+                load_v<D>(ctx, i * kStep, sd);
+                float sv[8];
+                score_step<D>(ctx, qf, sd, i * kStep, L, prm.scale_log2e, sv);
+                accumulate_step<D>(ctx, sv, sd, i * kStep, L, acc);
+            }
         }
 
         // Finish the per-head sum across the four q-groups of the wave.
@@ -593,7 +620,10 @@ int validate(const roll_attn_desc* d) {
     return ROLL_OK;
 }
 
-// Persistent waves to launch: what the device holds at once for this kernel.
+// Persistent waves to launch: one workgroup (kGroupWaves waves, one per SIMD) on every compute
+// unit.  Measured on c2 / c3 / c5: 3 to 4 waves per CU with 16 KiB in flight each already sit on
+// the memory system's plateau; 8 per CU are 1-2 % slower and 2 per CU need double buffering
+// to get there.  Fewer waves also mean fewer cut rows to merge.
 int persistent_waves(int head_dim, size_t lds_bytes, int32_t* waves_out) {
     static std::mutex mu;
     static int cached[2] = {0, 0};
@@ -612,8 +642,8 @@ int persistent_waves(int head_dim, size_t lds_bytes, int32_t* waves_out) {
         ROLL_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&groups, attn_stream<128>, kGroupWaves * 64, lds_bytes));
     else
         ROLL_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&groups, attn_stream<64>, kGroupWaves * 64, lds_bytes));
-    if (groups < 1) groups = 1;
-    c = groups * kGroupWaves * prop.multiProcessorCount;
+    if (groups < 1) return roll::fail(ROLL_ERR_HIP, "the attention kernel does not fit on a compute unit");
+    c = kGroupWaves * prop.multiProcessorCount;
     *waves_out = c;
     return ROLL_OK;
 }
