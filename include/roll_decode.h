@@ -289,6 +289,48 @@ int roll_sample_logprob(const void* logits, float temperature, float top_p,
                         void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------ */
+/* Consumer of logprob_out: the off-policy objectives of Section 3.2   */
+/* and the truncated importance weight of Appendix A.1, per token of a */
+/* batch of ragged responses.  With r = pi_theta / pi_old (pi_old = the */
+/* rollout's recorded probability), R the learning signal (reward or    */
+/* advantage) and clip(x, lo, hi):                                      */
+/*   PPO            min(R r, R clip(r, 1 - eps_low, 1 + eps_high))      */
+/*   DECOUPLED_PPO  min(R r, R (pi_prox / pi_old)                       */
+/*                          clip(pi_theta / pi_prox, 1 - eps_low, 1 + eps_high)) */
+/*   TIS            sg(clip(r, 0, c)) R log pi_theta                    */
+/*   CISPO          sg(clip(r, 1 - eps_low, 1 + eps_high)) R log pi_theta */
+/*   TOPR           (R > 0 ? 1 : sg(clip(r, 0, c))) R log pi_theta      */
+/* sg() terms carry no derivative.                                      */
+/* ------------------------------------------------------------------ */
+
+typedef enum roll_loss_kind {
+    ROLL_LOSS_PPO = 0, ROLL_LOSS_DECOUPLED_PPO = 1, ROLL_LOSS_TIS = 2, ROLL_LOSS_CISPO = 3, ROLL_LOSS_TOPR = 4
+} roll_loss_kind;
+
+typedef struct roll_loss_desc {
+    int32_t kind;      /* roll_loss_kind */
+    int32_t num_seqs;  /* responses in the batch */
+    float eps_low;     /* lower clip offset (PPO, Decoupled PPO, CISPO) */
+    float eps_high;    /* upper clip offset */
+    float c;           /* truncation threshold (TIS, TOPR, is_weight_out) */
+} roll_loss_desc;
+
+/*
+ * All pointers DEVICE.  Tokens of response s are seq_offsets[s] .. seq_offsets[s+1]-1.
+ *   logp_theta, logp_old, signal  fp32 [T]; logp_prox fp32 [T] (Decoupled PPO only, else NULL)
+ *   seq_offsets    int64 [num_seqs + 1], non-decreasing
+ *   value_out      fp32 [T] or NULL: the objective per token
+ *   grad_out       fp32 [T] or NULL: its derivative with respect to log pi_theta
+ *   is_weight_out  fp32 [T] or NULL: min(pi_theta / pi_old, c)
+ *   seq_mean_out   fp32 [num_seqs]: (1/|o|) sum_t value (0 for an empty response)
+ *   batch_mean_out fp32 [1]: mean of seq_mean_out over the non-empty responses
+ */
+int roll_policy_loss(const float* logp_theta, const float* logp_old, const float* logp_prox,
+                     const float* signal, const int64_t* seq_offsets, float* value_out,
+                     float* grad_out, float* is_weight_out, float* seq_mean_out,
+                     float* batch_mean_out, const roll_loss_desc* desc, void* stream);
+
+/* ------------------------------------------------------------------ */
 /* Profiling helpers: HIP events the benchmark hands to roll_attn_desc. */
 /* ------------------------------------------------------------------ */
 int roll_prof_event_create(void** event);

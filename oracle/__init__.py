@@ -184,3 +184,25 @@ def sample_counts(row, temperature, top_p, seed, step0, n_draws, row_id=0):
                                C.c_uint64(step0), C.c_int64(n_draws), C.c_uint32(row_id),
                                _p(counts, C.c_int64))
     return counts
+
+
+LOSS_KINDS = {"ppo": 0, "decoupled_ppo": 1, "tis": 2, "cispo": 3, "topr": 4}
+
+
+def policy_loss(kind, logp_theta, logp_old, logp_prox, signal, offsets, eps_lo=0.2, eps_hi=0.2, c=5.0):
+    """Off-policy objectives over ragged responses.  Arrays are float32 [T]; offsets int64 [n_seq+1].
+    Returns dict(value, grad, is_weight [T], seq_mean [n_seq], batch_mean)."""
+    lt = np.ascontiguousarray(logp_theta, np.float32)
+    lo = np.ascontiguousarray(logp_old, np.float32)
+    lp = None if logp_prox is None else np.ascontiguousarray(logp_prox, np.float32)
+    R = np.ascontiguousarray(signal, np.float32)
+    off = np.ascontiguousarray(offsets, np.int64)
+    T, n = len(lt), len(off) - 1
+    value, grad, w = (np.zeros(T, np.float64) for _ in range(3))
+    seq_mean = np.zeros(n, np.float64)
+    bm = C.c_double()
+    lib().oracle_policy_loss(C.c_int(LOSS_KINDS[kind]), _p(lt, C.c_float), _p(lo, C.c_float), _p(lp, C.c_float),
+                             _p(R, C.c_float), _p(off, C.c_int64), C.c_int(n), C.c_double(eps_lo),
+                             C.c_double(eps_hi), C.c_double(c), _p(value, C.c_double), _p(grad, C.c_double),
+                             _p(w, C.c_double), _p(seq_mean, C.c_double), C.byref(bm))
+    return dict(value=value, grad=grad, is_weight=w, seq_mean=seq_mean, batch_mean=bm.value)

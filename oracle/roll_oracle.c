@@ -418,3 +418,90 @@ void oracle_sample_counts(const void* row, int dtype, int V, double T, double to
         counts[tok] += 1;
     }
 }
+
+/* ------------------------------------------------------------------ */
+/* Consumer of the recorded log-probs: off-policy objectives           */
+/* ------------------------------------------------------------------ */
+
+#define ORACLE_LOSS_PPO 0
+#define ORACLE_LOSS_DECOUPLED_PPO 1
+#define ORACLE_LOSS_TIS 2
+#define ORACLE_LOSS_CISPO 3
+#define ORACLE_LOSS_TOPR 4
+
+static double clip_d(double x, double lo, double hi) { return x < lo ? lo : (x > hi ? hi : x); }
+
+/*
+ * Per-token value of the five objectives of Section 3.2 ("Loss Objective for
+ * Off-policy Algorithms") and its derivative with respect to log pi_theta,
+ * with pi_old the rollout engine's recorded probability.  lt, lo, lp are the
+ * log-probs of the token under pi_theta, pi_old, pi_prox; R is the learning
+ * signal (reward or advantage).  (x)^a_b in the paper is clip(x, b, a).
+ *   PPO            min(R r, R clip(r, 1 - eps_lo, 1 + eps_hi)),           r = pi_theta / pi_old
+ *   Decoupled PPO  min(R r, R (pi_prox / pi_old) clip(pi_theta / pi_prox, 1 - eps_lo, 1 + eps_hi))
+ *   Truncated IS   sg(clip(r, 0, c)) R log pi_theta
+ *   CISPO          sg(clip(r, 1 - eps_lo, 1 + eps_hi)) R log pi_theta
+ *   TOPR           (1[T+] + 1[T-] sg(clip(r, 0, c))) R log pi_theta
+ * Readings: the symmetric eps of PPO is given as the pair (eps_lo, eps_hi) so
+ * that CISPO's asymmetric interval uses the same parameters; a trajectory is
+ * in T+ when its signal is > 0 (the paper says "high-return / correct"); sg()
+ * terms contribute no derivative; at a clip corner the derivative of the
+ * clipped branch is taken as 0 and min() prefers the first argument on ties.
+ * is_weight = min(r, c): the truncated importance weight of Appendix A.1.
+ */
+void oracle_policy_loss_token(int kind, double lt, double lo, double lp, double R, double eps_lo,
+                              double eps_hi, double c, double* value, double* dvalue_dlt,
+                              double* is_weight)
+{
+    double r = exp(lt - lo);
+    double v = 0.0, g = 0.0;
+    if (kind == ORACLE_LOSS_PPO) {
+        double a = R * r, b = R * clip_d(r, 1.0 - eps_lo, 1.0 + eps_hi);
+        int inside = r > 1.0 - eps_lo && r < 1.0 + eps_hi;
+        if (a <= b) { v = a; g = R * r; } else { v = b; g = inside ? R * r : 0.0; }
+    } else if (kind == ORACLE_LOSS_DECOUPLED_PPO) {
+        double rp = exp(lt - lp), w = exp(lp - lo);
+        double a = R * r, b = R * w * clip_d(rp, 1.0 - eps_lo, 1.0 + eps_hi);
+        int inside = rp > 1.0 - eps_lo && rp < 1.0 + eps_hi;
+        if (a <= b) { v = a; g = R * r; } else { v = b; g = inside ? R * w * rp : 0.0; }
+    } else if (kind == ORACLE_LOSS_TIS) {
+        double w = clip_d(r, 0.0, c);
+        v = w * R * lt; g = w * R;
+    } else if (kind == ORACLE_LOSS_CISPO) {
+        double w = clip_d(r, 1.0 - eps_lo, 1.0 + eps_hi);
+        v = w * R * lt; g = w * R;
+    } else { /* TOPR */
+        double w = R > 0.0 ? 1.0 : clip_d(r, 0.0, c);
+        v = w * R * lt; g = w * R;
+    }
+    *value = v;
+    *dvalue_dlt = g;
+    *is_weight = r < c ? r : c;
+}
+
+/*
+ * Whole batch of ragged responses: tokens of sequence s are offsets[s] ..
+ * offsets[s+1]-1.  seq_mean[s] = (1/|o_s|) sum_t value (0 for an empty
+ * sequence); batch_mean = mean of seq_mean over the non-empty sequences (the
+ * E over trajectories with the 1/|o| sum over tokens of the PPO objective).
+ */
+void oracle_policy_loss(int kind, const float* lt, const float* lo, const float* lp, const float* R,
+                        const int64_t* offsets, int n_seq, double eps_lo, double eps_hi, double c,
+                        double* value, double* grad, double* is_weight, double* seq_mean,
+                        double* batch_mean)
+{
+    double total = 0.0;
+    int live = 0;
+    for (int s = 0; s < n_seq; ++s) {
+        double acc = 0.0;
+        for (int64_t i = offsets[s]; i < offsets[s + 1]; ++i) {
+            oracle_policy_loss_token(kind, (double)lt[i], (double)lo[i], lp ? (double)lp[i] : (double)lo[i],
+                                     (double)R[i], eps_lo, eps_hi, c, &value[i], &grad[i], &is_weight[i]);
+            acc += value[i];
+        }
+        int64_t n = offsets[s + 1] - offsets[s];
+        seq_mean[s] = n > 0 ? acc / (double)n : 0.0;
+        if (n > 0) { total += seq_mean[s]; ++live; }
+    }
+    *batch_mean = live ? total / live : 0.0;
+}

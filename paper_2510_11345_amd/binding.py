@@ -25,7 +25,7 @@ EXPORTS = [
     "roll_kv_commit", "roll_kv_commit_append", "roll_kv_free_pages", "roll_kv_seq_len", "roll_kv_slot_pages",
     "roll_kv_append_tokens",
     "roll_decode_attn_workspace_bytes", "roll_decode_attn_workspace_init", "roll_decode_attn",
-    "roll_sample_logprob_workspace_bytes", "roll_sample_logprob",
+    "roll_sample_logprob_workspace_bytes", "roll_sample_logprob", "roll_policy_loss",
     "roll_prof_event_create", "roll_prof_event_destroy", "roll_prof_event_record",
     "roll_prof_event_elapsed_ms",
 ]
@@ -48,6 +48,14 @@ class AttnDesc(C.Structure):
                 ("num_pages", C.c_int32), ("out_dtype", C.c_int32), ("softmax_scale", C.c_float),
                 ("reserved", C.c_int32),
                 ("ev_main_begin", C.c_void_p), ("ev_main_end", C.c_void_p)]
+
+
+class LossDesc(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("num_seqs", C.c_int32), ("eps_low", C.c_float), ("eps_high", C.c_float),
+                ("c", C.c_float)]
+
+
+LOSS_KINDS = {"ppo": 0, "decoupled_ppo": 1, "tis": 2, "cispo": 3, "topr": 4}
 
 
 class SampleDesc(C.Structure):
@@ -91,6 +99,7 @@ def lib():
         L.roll_sample_logprob.argtypes = [C.c_void_p, C.c_float, C.c_float, C.c_uint64, C.c_uint64,
                                           C.c_void_p, C.c_void_p, C.POINTER(SampleDesc), C.c_void_p,
                                           C.c_size_t, C.c_void_p]
+        L.roll_policy_loss.argtypes = [C.c_void_p] * 10 + [C.POINTER(LossDesc), C.c_void_p]
         L.roll_prof_event_create.argtypes = [C.POINTER(C.c_void_p)]
         L.roll_prof_event_destroy.argtypes = [C.c_void_p]
         L.roll_prof_event_record.argtypes = [C.c_void_p, C.c_void_p]
@@ -281,6 +290,19 @@ def roll_sample_logprob(logits, temperature, top_p, philox_seed, step, tokens_ou
         logits.data_ptr(), temperature, top_p, philox_seed, step, _dev(tokens_out, torch.int32),
         _dev(logprob_out, torch.float32), C.byref(desc), _dev(workspace),
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream()))
+
+
+# ----------------------------------------------------------------------------
+# consumer of the log-probs
+# ----------------------------------------------------------------------------
+def roll_policy_loss(kind, logp_theta, logp_old, logp_prox, signal, seq_offsets, value_out, grad_out,
+                     is_weight_out, seq_mean_out, batch_mean_out, eps_low=0.2, eps_high=0.2, c=5.0) -> None:
+    desc = LossDesc(LOSS_KINDS[kind], seq_offsets.numel() - 1, eps_low, eps_high, c)
+    _check(lib().roll_policy_loss(
+        _dev(logp_theta, torch.float32), _dev(logp_old, torch.float32), _dev(logp_prox, torch.float32),
+        _dev(signal, torch.float32), _dev(seq_offsets, torch.int64), _dev(value_out, torch.float32),
+        _dev(grad_out, torch.float32), _dev(is_weight_out, torch.float32), _dev(seq_mean_out, torch.float32),
+        _dev(batch_mean_out, torch.float32), C.byref(desc), _stream()))
 
 
 # ----------------------------------------------------------------------------

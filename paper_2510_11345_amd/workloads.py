@@ -215,3 +215,34 @@ def draw_refill_plan(num_slots: int, num_requests: int, seed: int, prompt_range=
     start = np.zeros(num_requests, dtype=np.int32)
     start[:num_slots] = (rng.random(num_slots) * target[:num_slots]).astype(np.int32)
     return RefillPlan(prompt, target, start)
+
+
+# --------------------------------------------------------------------------
+# A rollout batch as the trainer sees it: ragged responses with recorded log-probs
+# --------------------------------------------------------------------------
+
+def make_policy_batch(num_seqs: int, seed: int, length_law: str = "lognormal_2048", max_len: int = 16384,
+                      group: int = 8, drift: float = 0.3, device="cpu"):
+    """Ragged responses (lengths from a long-tailed law, a few empty), per-token log-probs of the
+    rollout policy (negative, a few nats), of the current and proximal policies (the rollout's plus
+    Gaussian drift, i.e. stale by a few policy versions), and a per-response learning signal
+    normalised within groups of `group` responses (GRPO-style advantage), broadcast to tokens.
+    Returns dict of torch tensors: logp_old, logp_theta, logp_prox, signal [T] fp32; offsets int64."""
+    rng = np.random.default_rng([seed, 0x504F4C])
+    lens = draw_lengths(length_law, num_seqs, seed, max_len).astype(np.int64)
+    lens[rng.integers(0, num_seqs, size=max(1, num_seqs // 64))] = 0
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    T = int(offsets[-1])
+    g = _gen(seed, 77, "cpu")
+    lo = -(torch.randn(T, generator=g).abs() * 1.5 + 0.01)
+    lt = lo + torch.randn(T, generator=g) * drift
+    lp = lo + torch.randn(T, generator=g) * (0.5 * drift)
+    reward = rng.random(num_seqs) < 0.4                      # verifiable reward: right or wrong
+    adv = np.zeros(num_seqs, np.float32)
+    for s0 in range(0, num_seqs, group):
+        r = reward[s0:s0 + group].astype(np.float32)
+        adv[s0:s0 + group] = (r - r.mean()) / (r.std() + 1e-6)
+    signal = torch.from_numpy(np.repeat(adv, lens))
+    out = dict(logp_old=lo.float(), logp_theta=lt.float(), logp_prox=lp.float(), signal=signal.float(),
+               offsets=torch.from_numpy(offsets))
+    return {k: v.to(device) for k, v in out.items()}
