@@ -42,6 +42,42 @@ def profiled_traffic(workload: str, algorithmic_bytes: float):
     return None
 
 
+def policy_loss_bench(args, torch, rb, wl):
+    """Tokens/s of roll_policy_loss on a rollout-sized ragged batch (512 responses, lognormal lengths),
+    one launch pair per objective; HBM roofline on the bytes a token moves."""
+    b = {k: v.cuda() for k, v in wl.make_policy_batch(512, args.seed).items()}
+    T, n = b["logp_old"].numel(), b["offsets"].numel() - 1
+    value, grad, w = (torch.empty(T, device="cuda") for _ in range(3))
+    seq_mean, batch_mean = torch.empty(n, device="cuda"), torch.empty(1, device="cuda")
+    res = {}
+    for kind in ["ppo", "decoupled_ppo", "tis", "cispo", "topr"]:
+        prox = b["logp_prox"] if kind == "decoupled_ppo" else None
+        call = lambda: rb.roll_policy_loss(kind, b["logp_theta"], b["logp_old"], prox, b["signal"], b["offsets"],
+                                           value, grad, w, seq_mean, batch_mean)
+        for _ in range(args.warmup):
+            call()
+        e0, e1 = rb.ProfEvent(), rb.ProfEvent()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_ms(e1) / args.steps
+        nbytes = T * (4 * (3 + (1 if prox is not None else 0)) + 12)
+        res[kind] = {"ms": ms, "tokens_per_s": T / (ms * 1e-3), "GBps": nbytes / (ms * 1e-3) / 1e9}
+    best = res["ppo"]
+    print(json.dumps({"metric": "policy-loss tokens/s (value, derivative, IS weight, ragged means)",
+                      "value": best["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+                      "warmup": args.warmup, "ms_per_step": best["ms"], "higher_is_better": True,
+                      "dtype": "f64 arithmetic on f32 data", "data": "synthetic",
+                      "config": {"workload": f"512 ragged responses, {T} tokens, lognormal(2048) lengths"},
+                      "roofline": {"bound": "hbm", "kernel": "policy_loss_rows", "achieved": best["GBps"],
+                                   "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": best["GBps"] / HBM_PEAK_GBS,
+                                   "traffic": None},
+                      "per_objective": res}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -52,6 +88,8 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--oracle-rows", type=int, default=0, help="rows timed on the CPU oracle (0 = the whole batch)")
+    ap.add_argument("--policy-loss", action="store_true",
+                    help="measure roll_policy_loss (the consumer of logprob_out) instead of the decode step")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="only run one plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -78,6 +116,9 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"pmc_calibration": "one device copy", "bytes_read": src.numel() * 4,
                           "bytes_written": dst.numel() * 4}))
+        return
+    if args.policy_loss:
+        policy_loss_bench(args, torch, rb, wl)
         return
     cfg = wl.CONFIGS[args.config]
     K, W = args.steps, args.warmup
