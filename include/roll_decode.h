@@ -63,7 +63,9 @@ typedef enum roll_status {
     ROLL_ERR_SLOT_RANGE = -4,   /* slot index outside [0, num_slots) */
     ROLL_ERR_SEQ_TOO_LONG = -5, /* sequence would need more than max_pages_per_seq pages */
     ROLL_ERR_WORKSPACE = -6,    /* workspace NULL, misaligned or too small */
-    ROLL_ERR_HIP = -7           /* a HIP runtime call failed (message has the HIP error) */
+    ROLL_ERR_HIP = -7,          /* a HIP runtime call failed (message has the HIP error) */
+    ROLL_ERR_BUFFER_FULL = -8,  /* SampleBuffer: (1 + alpha) * batch samples are outstanding */
+    ROLL_ERR_WOULD_BLOCK = -9   /* SampleBuffer: the call must wait for generation to finish */
 } roll_status;
 
 typedef enum roll_dtype { ROLL_BF16 = 0, ROLL_F32 = 1 } roll_dtype;
@@ -329,6 +331,43 @@ int roll_policy_loss(const float* logp_theta, const float* logp_old, const float
                      const float* signal, const int64_t* seq_offsets, float* value_out,
                      float* grad_out, float* is_weight_out, float* seq_mean_out,
                      float* batch_mean_out, const roll_loss_desc* desc, void* stream);
+
+/* ------------------------------------------------------------------ */
+/* SampleBuffer with the asynchronous ratio (Section 4.3), HOST only.  */
+/* alpha = largest allowed gap between the current policy version n and */
+/* the version that initiated a sample.  A sample is outstanding from   */
+/* begin until a batch takes it; one batch is taken per version.        */
+/* Guarantees, for any interleaving of the calls: at most               */
+/* floor((1 + alpha) * batch) samples outstanding;                      */
+/* every sample taken at version n was initiated at a version >= n -    */
+/* alpha; every sample begun is eventually taken (none is dropped).     */
+/* Not thread-safe: one controller thread calls it.                     */
+/* ------------------------------------------------------------------ */
+
+typedef struct roll_sample_buffer roll_sample_buffer;
+
+int roll_sample_buffer_create(roll_sample_buffer** buffer, int32_t batch_size, double alpha);
+int roll_sample_buffer_destroy(roll_sample_buffer* buffer);
+/* Start generating a new sample under the current version.  ROLL_ERR_BUFFER_FULL when the
+ * earliest batch that could take it lies more than alpha versions ahead (with alpha = 0:
+ * while the trainer runs, or once a batch worth of samples is outstanding). */
+int roll_sample_buffer_begin(roll_sample_buffer* buffer, int64_t* ticket, int64_t* init_version);
+/* Generation finished; payload is the caller's handle of the trajectory. */
+int roll_sample_buffer_complete(roll_sample_buffer* buffer, int64_t ticket, uint64_t payload);
+/* ABORT (Section 4.2): the running request is interrupted and reclaimed; it stays outstanding
+ * with its initiating version and is resumed later, possibly under a newer policy. */
+int roll_sample_buffer_abort(roll_sample_buffer* buffer, int64_t ticket);
+int roll_sample_buffer_resume(roll_sample_buffer* buffer, int64_t ticket, int64_t* version_now);
+/* One training batch: batch_size samples, those that cannot wait another version first, then
+ * the oldest.  ROLL_ERR_WOULD_BLOCK if fewer are complete or a due sample is still generating.
+ * tickets / init_versions / payloads: HOST arrays of batch_size entries (the last two may be NULL). */
+int roll_sample_buffer_take_batch(roll_sample_buffer* buffer, int64_t* tickets, int64_t* init_versions,
+                                  uint64_t* payloads);
+/* After the train step: n -> n + 1.  ROLL_ERR_WOULD_BLOCK while a sample would become too old. */
+int roll_sample_buffer_advance_version(roll_sample_buffer* buffer);
+int64_t roll_sample_buffer_version(const roll_sample_buffer* buffer);
+int64_t roll_sample_buffer_outstanding(const roll_sample_buffer* buffer);
+int64_t roll_sample_buffer_capacity(const roll_sample_buffer* buffer);
 
 /* ------------------------------------------------------------------ */
 /* Profiling helpers: HIP events the benchmark hands to roll_attn_desc. */

@@ -26,6 +26,10 @@ EXPORTS = [
     "roll_kv_append_tokens",
     "roll_decode_attn_workspace_bytes", "roll_decode_attn_workspace_init", "roll_decode_attn",
     "roll_sample_logprob_workspace_bytes", "roll_sample_logprob", "roll_policy_loss",
+    "roll_sample_buffer_create", "roll_sample_buffer_destroy", "roll_sample_buffer_begin",
+    "roll_sample_buffer_complete", "roll_sample_buffer_abort", "roll_sample_buffer_resume",
+    "roll_sample_buffer_take_batch", "roll_sample_buffer_advance_version", "roll_sample_buffer_version",
+    "roll_sample_buffer_outstanding", "roll_sample_buffer_capacity",
     "roll_prof_event_create", "roll_prof_event_destroy", "roll_prof_event_record",
     "roll_prof_event_elapsed_ms",
 ]
@@ -100,6 +104,17 @@ def lib():
                                           C.c_void_p, C.c_void_p, C.POINTER(SampleDesc), C.c_void_p,
                                           C.c_size_t, C.c_void_p]
         L.roll_policy_loss.argtypes = [C.c_void_p] * 10 + [C.POINTER(LossDesc), C.c_void_p]
+        L.roll_sample_buffer_create.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.c_double]
+        L.roll_sample_buffer_destroy.argtypes = [C.c_void_p]
+        L.roll_sample_buffer_begin.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+        L.roll_sample_buffer_complete.argtypes = [C.c_void_p, C.c_int64, C.c_uint64]
+        L.roll_sample_buffer_abort.argtypes = [C.c_void_p, C.c_int64]
+        L.roll_sample_buffer_resume.argtypes = [C.c_void_p, C.c_int64, C.POINTER(C.c_int64)]
+        L.roll_sample_buffer_take_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.roll_sample_buffer_advance_version.argtypes = [C.c_void_p]
+        for f in (L.roll_sample_buffer_version, L.roll_sample_buffer_outstanding, L.roll_sample_buffer_capacity):
+            f.argtypes = [C.c_void_p]
+            f.restype = C.c_int64
         L.roll_prof_event_create.argtypes = [C.POINTER(C.c_void_p)]
         L.roll_prof_event_destroy.argtypes = [C.c_void_p]
         L.roll_prof_event_record.argtypes = [C.c_void_p, C.c_void_p]
@@ -303,6 +318,64 @@ def roll_policy_loss(kind, logp_theta, logp_old, logp_prox, signal, seq_offsets,
         _dev(signal, torch.float32), _dev(seq_offsets, torch.int64), _dev(value_out, torch.float32),
         _dev(grad_out, torch.float32), _dev(is_weight_out, torch.float32), _dev(seq_mean_out, torch.float32),
         _dev(batch_mean_out, torch.float32), C.byref(desc), _stream()))
+
+
+# ----------------------------------------------------------------------------
+# SampleBuffer (host only)
+# ----------------------------------------------------------------------------
+class SampleBuffer:
+    def __init__(self, batch_size: int, alpha: float):
+        self.batch_size = batch_size
+        self._h = C.c_void_p()
+        _check(lib().roll_sample_buffer_create(C.byref(self._h), batch_size, alpha))
+
+    def begin(self):
+        """(ticket, init_version), or None when the buffer is at capacity."""
+        t, v = C.c_int64(), C.c_int64()
+        st = lib().roll_sample_buffer_begin(self._h, C.byref(t), C.byref(v))
+        if st == -8:
+            return None
+        _check(st)
+        return t.value, v.value
+
+    def complete(self, ticket: int, payload: int = 0):
+        _check(lib().roll_sample_buffer_complete(self._h, ticket, payload))
+
+    def abort(self, ticket: int):
+        _check(lib().roll_sample_buffer_abort(self._h, ticket))
+
+    def resume(self, ticket: int) -> int:
+        v = C.c_int64()
+        _check(lib().roll_sample_buffer_resume(self._h, ticket, C.byref(v)))
+        return v.value
+
+    def take_batch(self):
+        """List of (ticket, init_version, payload), or None when the trainer has to wait."""
+        n = self.batch_size
+        t, v, p = (C.c_int64 * n)(), (C.c_int64 * n)(), (C.c_uint64 * n)()
+        st = lib().roll_sample_buffer_take_batch(self._h, t, v, p)
+        if st == -9:
+            return None
+        _check(st)
+        return list(zip(t, v, p))
+
+    def advance_version(self) -> bool:
+        st = lib().roll_sample_buffer_advance_version(self._h)
+        if st == -9:
+            return False
+        _check(st)
+        return True
+
+    version = property(lambda self: lib().roll_sample_buffer_version(self._h))
+    outstanding = property(lambda self: lib().roll_sample_buffer_outstanding(self._h))
+    capacity = property(lambda self: lib().roll_sample_buffer_capacity(self._h))
+
+    def __del__(self):
+        try:
+            if self._h:
+                lib().roll_sample_buffer_destroy(self._h)
+        except Exception:
+            pass
 
 
 # ----------------------------------------------------------------------------
