@@ -21,8 +21,7 @@
  *     sampling, log-prob of the drawn token under the sampled distribution,
  *   - Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11) as the counter-based
  *     generator.
- * Readings taken where the paper is silent are listed in the design notes
- * of the repository and repeated at each function.
+ * Readings taken where the paper is silent are stated at each function.
  *
  * Parity pins (tests/test_oracle_*.py): Philox against the published
  * known-answer vectors and an independent big-integer implementation;
@@ -30,7 +29,9 @@
  * page permutation, GQA sharing, split/merge, dense library softmax(QK^T)V
  * and two-key closed form; sampling against library log_softmax, uniform
  * logits, shift and scale invariance, brute-force subset enumeration of the
- * top-p set, chi-square of sampled frequencies on tiny vocabularies.
+ * top-p set, chi-square of sampled frequencies on tiny vocabularies; the
+ * off-policy objectives against hand-computed values, the reductions between
+ * them that the paper's description implies, and a numerical derivative.
  * End-to-end numbers: parity unpinned against the paper (it prints no
  * worked numeric example for this path).
  */

@@ -1,4 +1,4 @@
-"""Parity at the benchmark's full sizes, in the launch configuration bench.py times (needs an
+"""Parity at the full sizes of the benchmark configurations, in the launch configuration bench.py times (needs an
 MI355X): one decode step of c2, c3 and c5 through the harness; attention on sampled rows (the
 shortest, the longest, and rows spread over the batch), sampling on sampled rows."""
 import numpy as np
