@@ -160,6 +160,9 @@ int roll_kv_seq_len(const roll_kv_pool* pool, int32_t slot);    /* tokens, or < 
  * number of pages the slot owns, or < 0. */
 int roll_kv_slot_pages(const roll_kv_pool* pool, int32_t slot,
                        int32_t* pages_out, int32_t cap);
+/* Decode steps that roll_decode_step_attn published in its single launch
+ * (the others took the two-launch route), or < 0. */
+int64_t roll_kv_fused_steps(const roll_kv_pool* pool);
 
 /*
  * Write the K/V vectors of n_tokens tokens into the paged pools in the page
@@ -242,6 +245,29 @@ int roll_decode_attn(const void* q, const void* k_pages, const void* v_pages,
                      const int32_t* page_table, const int32_t* seq_lens,
                      void* out, const roll_attn_desc* desc,
                      void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * One launch for the memory-side of a decode step (Section 4.2, the engine's
+ * step over the whole running batch): what roll_kv_commit_append followed by
+ * roll_decode_attn on the pool's own device tables would do.  Publishes the
+ * allocator changes made since the last commit, writes the newest token of
+ * every live slot (k_new / v_new, DEVICE bf16 [num_slots, Hkv, D]) into the
+ * pages, and attends over all tokens including that one, which is taken from
+ * k_new / v_new directly.
+ *   pool        created with device tables; desc->batch, page_size,
+ *               max_pages_per_seq and num_pages must equal the pool's
+ *   k_pages, v_pages  DEVICE, written (one token per live slot) and read
+ *   q, out, desc, workspace  as for roll_decode_attn
+ * The single launch applies when the changes since the last commit are exactly
+ * one decode step: every live slot grew by one token, empty slots stayed
+ * empty, and at most 128 slots started a new page.  Anything else (refills,
+ * releases, the first use of a pool) is still handled, by the two launches
+ * named above, with the same results.  HOST-side effects are those of
+ * roll_kv_commit.  Errors as for the two calls it replaces.
+ */
+int roll_decode_step_attn(roll_kv_pool* pool, const void* k_new, const void* v_new, const void* q,
+                          void* k_pages, void* v_pages, void* out, const roll_attn_desc* desc,
+                          void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------ */
 /* Sampling with log-prob recording (Appendix A.1).  Per row r:        */

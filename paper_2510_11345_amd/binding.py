@@ -23,8 +23,10 @@ EXPORTS = [
     "roll_last_error", "roll_version",
     "roll_kv_pool_create", "roll_kv_pool_destroy", "roll_kv_alloc", "roll_kv_alloc_batch", "roll_kv_release",
     "roll_kv_commit", "roll_kv_commit_append", "roll_kv_free_pages", "roll_kv_seq_len", "roll_kv_slot_pages",
+    "roll_kv_fused_steps",
     "roll_kv_append_tokens",
     "roll_decode_attn_workspace_bytes", "roll_decode_attn_workspace_init", "roll_decode_attn",
+    "roll_decode_step_attn",
     "roll_sample_logprob_workspace_bytes", "roll_sample_logprob", "roll_policy_loss",
     "roll_sample_buffer_create", "roll_sample_buffer_destroy", "roll_sample_buffer_begin",
     "roll_sample_buffer_complete", "roll_sample_buffer_abort", "roll_sample_buffer_resume",
@@ -94,12 +96,15 @@ def lib():
         L.roll_kv_commit.argtypes = [C.c_void_p, C.c_void_p]
         L.roll_kv_commit_append.argtypes = [C.c_void_p] * 5 + [C.c_int32, C.c_int32, C.c_void_p]
         L.roll_kv_free_pages.argtypes = [C.c_void_p]
+        L.roll_kv_fused_steps.argtypes = [C.c_void_p]
+        L.roll_kv_fused_steps.restype = C.c_int64
         L.roll_kv_seq_len.argtypes = [C.c_void_p, C.c_int32]
         L.roll_kv_slot_pages.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_int32]
         L.roll_kv_append_tokens.argtypes = [C.c_void_p] * 5 + [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p] + \
             [C.c_int32] * 5 + [C.c_void_p]
         L.roll_decode_attn_workspace_init.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
         L.roll_decode_attn.argtypes = [C.c_void_p] * 6 + [C.POINTER(AttnDesc), C.c_void_p, C.c_size_t, C.c_void_p]
+        L.roll_decode_step_attn.argtypes = [C.c_void_p] * 7 + [C.POINTER(AttnDesc), C.c_void_p, C.c_size_t, C.c_void_p]
         L.roll_sample_logprob.argtypes = [C.c_void_p, C.c_float, C.c_float, C.c_uint64, C.c_uint64,
                                           C.c_void_p, C.c_void_p, C.POINTER(SampleDesc), C.c_void_p,
                                           C.c_size_t, C.c_void_p]
@@ -211,6 +216,10 @@ def roll_kv_commit_append(pool: KvPool, k_new, v_new, k_pages, v_pages) -> None:
                                        _stream()))
 
 
+def roll_kv_fused_steps(pool: KvPool) -> int:
+    return _check(lib().roll_kv_fused_steps(pool._h))
+
+
 def roll_kv_free_pages(pool: KvPool) -> int:
     return _check(lib().roll_kv_free_pages(pool._h))
 
@@ -273,6 +282,14 @@ def roll_decode_attn(q, k_pages, v_pages, page_table, seq_lens, out, desc: AttnD
     _check(lib().roll_decode_attn(
         _dev(q, torch.bfloat16), _dev(k_pages, torch.bfloat16), _dev(v_pages, torch.bfloat16),
         _dev(page_table, torch.int32), _dev(seq_lens, torch.int32), _dev(out), C.byref(desc),
+        _dev(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def roll_decode_step_attn(pool: "KvPool", k_new, v_new, q, k_pages, v_pages, out, desc: AttnDesc,
+                          workspace: torch.Tensor) -> None:
+    _check(lib().roll_decode_step_attn(
+        pool._h, _dev(k_new, torch.bfloat16), _dev(v_new, torch.bfloat16), _dev(q, torch.bfloat16),
+        _dev(k_pages, torch.bfloat16), _dev(v_pages, torch.bfloat16), _dev(out), C.byref(desc),
         _dev(workspace), workspace.numel() * workspace.element_size(), _stream()))
 
 

@@ -42,7 +42,11 @@
 #include <cmath>
 #include <mutex>
 
+#include <type_traits>
+
 #include "common.h"
+#include "kv_layout.h"
+#include "kv_pool_internal.h"
 
 namespace {
 
@@ -73,6 +77,7 @@ struct AttnParams {
 
 struct Workspace {
     // zero between calls (roll_decode_attn_workspace_init, then every merger resets its counter)
+    int32_t* grid_arrivals;    // [1] workgroups of a fused step that have read the old lengths
     int32_t* group_arrivals;   // [2 W] indexed by the slot of the first piece of a group
     int32_t* stream_arrivals;  // [kMaxStreams] indexed by row * Hkv + kv head
     // scratch
@@ -91,6 +96,7 @@ __host__ Workspace carve(void* base, int32_t G, int32_t D) {
     const size_t W = kMaxPersistentWaves;
     size_t off = 0;
     char* p = (char*)base;
+    w.grid_arrivals = (int32_t*)(p + off);    off = align_up(off + sizeof(int32_t), 256);
     w.group_arrivals = (int32_t*)(p + off);   off = align_up(off + sizeof(int32_t) * 2 * W, 256);
     w.stream_arrivals = (int32_t*)(p + off);  off = align_up(off + sizeof(int32_t) * kMaxStreams, 256);
     w.header_bytes = off;
@@ -148,10 +154,29 @@ struct WaveCtx {
     const uint4* __restrict__ v_pages;
     const int32_t* __restrict__ pt_row;
     int32_t h, Hkv, log2P, num_pages, max_pages, r, q;
+    // Fused step only: the stream's newest token is not in the pages yet; its K row, V row,
+    // position, page index and physical page.
+    const uint4* __restrict__ k_new_row;
+    const uint16_t* __restrict__ v_new_row;
+    int32_t new_tok, new_pi, new_page;
 };
 
+// Extra kernel arguments of the fused step (allocator commit + K/V append + attention).
+struct FusedArgs {
+    int32_t n_delta;
+    int32_t slot[roll::kMaxFusedDeltas];  // slot that was given a fresh page for its newest token
+    int32_t page[roll::kMaxFusedDeltas];
+    const uint4* k_new;                   // [B, Hkv, D] bf16: the newest token of every slot
+    const uint4* v_new;
+    int32_t* page_table_w;
+    int32_t* seq_lens_w;
+    int32_t* grid_arrivals;
+};
+struct NoFusedArgs {};
+
 // Physical pages of the (up to) two pages a 32-token step touches.
-template <int D>
+// NEWEST: the step holds the stream's newest token in a fused launch.
+template <int D, bool NEWEST>
 __device__ __forceinline__ void step_pages(const WaveCtx<D>& c, int32_t t0, int32_t& pgA, int32_t& pgB) {
     int32_t pa = t0 >> c.log2P;
     // The second page may lie past the row's end; its table entry is then stale or -1.  Reading
@@ -164,6 +189,10 @@ __device__ __forceinline__ void step_pages(const WaveCtx<D>& c, int32_t t0, int3
     pgB = c.pt_row[pb];
     pgA = pgA < 0 ? 0 : (pgA >= c.num_pages ? c.num_pages - 1 : pgA);
     pgB = pgB < 0 ? 0 : (pgB >= c.num_pages ? c.num_pages - 1 : pgB);
+    if (NEWEST) {  // the table entry of the newest token's page may not be written yet
+        if (pa == c.new_pi) pgA = c.new_page;
+        if (pb == c.new_pi) pgB = c.new_page;
+    }
 }
 
 // K: lane (r, q) reads, for tile tt and k-block kk, 8 head-dim elements 32kk+8q.. of
@@ -171,35 +200,62 @@ __device__ __forceinline__ void step_pages(const WaveCtx<D>& c, int32_t t0, int3
 // token sits at slot (r & 7) + 8 tt of page r >> 3 when P == 16, and at slot r + 16 tt of
 // the step's 32-slot block otherwise: the 16 rows of a tile are contiguous, so one load
 // instruction covers whole 128-byte lines.
-template <int D>
+// With NEWEST the lane that owns the newest token reads its row from k_new instead.
+template <int D, bool NEWEST>
 __device__ __forceinline__ void load_k(const WaveCtx<D>& c, int32_t t0, StepData<D>& s) {
     const int32_t P = 1 << c.log2P;
     int32_t pgA, pgB;
-    step_pages<D>(c, t0, pgA, pgB);
+    step_pages<D, NEWEST>(c, t0, pgA, pgB);
     const uint4* kbase[2];
+    bool fresh[2] = {false, false};
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
         const int32_t page = (P == 16 && c.r >= 8) ? pgB : pgA;
         const int32_t slot = P == 16 ? (c.r & 7) + 8 * tt : (t0 & (P - 1)) + c.r + 16 * tt;
         kbase[tt] = c.k_pages + (((int64_t)page * c.Hkv + c.h) * (D / 8) + c.q) * P + slot;
+        if (NEWEST) fresh[tt] = t0 + 8 * (c.r >> 2) + 4 * tt + (c.r & 3) == c.new_tok;
     }
 #pragma unroll
     for (int kk = 0; kk < D / 32; ++kk)
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt) s.k[tt][kk] = load_stream(kbase[tt] + (int64_t)kk * 4 * P);
+        for (int tt = 0; tt < 2; ++tt) {
+            const uint4* src = kbase[tt] + (int64_t)kk * 4 * P;
+            if (NEWEST && fresh[tt]) src = c.k_new_row + c.q + kk * 4;
+            s.k[tt][kk] = load_stream(src);
+        }
 }
 
 // V: lane (r, q) reads, for d-tile nt, the 8 tokens 8q..8q+7 of head-dim element 16nt+r.
-template <int D>
+template <int D, bool NEWEST>
 __device__ __forceinline__ void load_v(const WaveCtx<D>& c, int32_t t0, StepData<D>& s) {
     const int32_t P = 1 << c.log2P;
     int32_t pgA, pgB;
-    step_pages<D>(c, t0, pgA, pgB);
+    step_pages<D, NEWEST>(c, t0, pgA, pgB);
     const int32_t page = c.q >= 2 ? pgB : pgA;
     const int32_t oct = ((t0 + 8 * c.q) & (P - 1)) >> 3;
     const uint4* base = c.v_pages + (((int64_t)page * c.Hkv + c.h) * (P / 8) + oct) * D + c.r;
 #pragma unroll
     for (int nt = 0; nt < D / 16; ++nt) s.v[nt] = load_stream(base + nt * 16);
+}
+
+// Fused launch, the step that holds a stream's newest token: the sixteen lanes of the token's
+// octet put the token's element (fresh[nt] = v_new[16nt + r], fetched when the stream began)
+// into the octets they have just read.
+template <int D>
+__device__ __forceinline__ void patch_newest_v(const WaveCtx<D>& c, int32_t t0, const uint32_t (&fresh)[D / 16],
+                                               StepData<D>& s) {
+    const int32_t j = c.new_tok - (t0 + 8 * c.q);
+    if (j < 0 || j >= 8) return;
+#pragma unroll
+    for (int nt = 0; nt < D / 16; ++nt) {
+        uint32_t w[4] = {s.v[nt].x, s.v[nt].y, s.v[nt].z, s.v[nt].w};
+#pragma unroll
+        for (int k2 = 0; k2 < 4; ++k2) {
+            if (j == 2 * k2) w[k2] = (w[k2] & 0xFFFF0000u) | fresh[nt];
+            if (j == 2 * k2 + 1) w[k2] = (w[k2] & 0x0000FFFFu) | (fresh[nt] << 16);
+        }
+        s.v[nt] = make_uint4(w[0], w[1], w[2], w[3]);
+    }
 }
 
 template <int D>
@@ -237,10 +293,11 @@ __device__ __forceinline__ void score_step(const WaveCtx<D>& c, const bf16x8_t (
 }
 
 // Online softmax update with the step's scores and O^T += V^T P^T.  Consumes the V registers.
-template <int D>
+// NEWEST: the step ends the row even when it is full (its newest token came from v_new).
+template <int D, bool NEWEST>
 __device__ __forceinline__ void accumulate_step(const WaveCtx<D>& c, const float (&sv)[8], StepData<D>& s,
                                                 int32_t t0, int32_t end, WaveAcc<D>& a) {
-    if (t0 + kStep > end) {  // ragged tail: zero the V octets of tokens that do not exist
+    if (NEWEST || t0 + kStep > end) {  // ragged tail: zero the V octets of tokens that do not exist
         const int32_t nvalid = end - (t0 + 8 * c.q);
 #pragma unroll
         for (int nt = 0; nt < D / 16; ++nt) {
@@ -296,7 +353,9 @@ __device__ __forceinline__ void accumulate_step(const WaveCtx<D>& c, const float
 
 // Steps per row into LDS as an exclusive prefix, clamped lengths beside it.
 // pre has B + 1 entries, len has B.  All threads of the workgroup take part.
-__device__ void build_row_prefix(const int32_t* __restrict__ seq_lens, int32_t B, int32_t max_len,
+// With grow, every row that holds tokens counts one more than the stored length (the token
+// appended by the same launch).
+__device__ void build_row_prefix(const int32_t* seq_lens, int32_t B, int32_t max_len, bool grow,
                                  int32_t* pre, int32_t* len, int32_t* s_wave_tot) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nthreads = blockDim.x, nwaves = nthreads >> 6;
@@ -306,6 +365,7 @@ __device__ void build_row_prefix(const int32_t* __restrict__ seq_lens, int32_t B
         int32_t L = 0;
         if (b < B) {
             L = seq_lens[b];
+            if (grow && L > 0) ++L;
             L = L < 0 ? 0 : (L > max_len ? max_len : L);
             len[b] = L;
         }
@@ -424,21 +484,53 @@ __device__ __forceinline__ bool arrive_last(int32_t* counter, int32_t expected, 
     return true;
 }
 
-template <int D>
+// Physical page of the newest token (position L - 1) of `slot`: from the deltas when that
+// token opened a page, else from the slot's page-table row.
+__device__ __forceinline__ int32_t newest_page(const FusedArgs& fa, const int32_t* pt_row, int32_t slot,
+                                               int32_t L, int32_t log2P, int32_t num_pages) {
+    int32_t page = -1;
+    if (((L - 1) & ((1 << log2P) - 1)) == 0)
+        for (int32_t i = 0; i < fa.n_delta; ++i)
+            if (fa.slot[i] == slot) page = fa.page[i];
+    if (page < 0) page = pt_row[(L - 1) >> log2P];
+    return page < 0 ? 0 : (page >= num_pages ? num_pages - 1 : page);
+}
+
+// FUSED: the launch is a whole decode step after the allocator's bookkeeping.  Lengths on the
+// device are those before the step (every live row grows by one), the page-table deltas come as
+// kernel arguments, and the newest token's K/V come from fa.k_new / fa.v_new.  The step that
+// holds a stream's newest token runs as code of its own after the stream's loop: it takes that
+// token's K row and V elements from k_new / v_new and its page from the arguments, so nothing in
+// the launch reads what the launch writes.  The wave that ran that step writes the token into
+// the pages once its attention work is done; workgroup 0 publishes the deltas; the lengths are
+// written by the workgroup that is last to finish, when every workgroup has read the old ones.
+// page_table and seq_lens stay __restrict__ although the launch writes both arrays through other
+// pointers: no value it uses is read from an entry it writes.
+template <int D, bool FUSED>
 __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
-    const uint4* __restrict__ q16, const uint4* __restrict__ k_pages, const uint4* __restrict__ v_pages,
+    const uint4* __restrict__ q16, const uint4* k_pages, const uint4* v_pages,
     const int32_t* __restrict__ page_table, const int32_t* __restrict__ seq_lens,
     void* __restrict__ out, int32_t* group_arrivals, int32_t* stream_arrivals, float2* part_ml,
-    float* part_acc, float2* group_ml, float* group_acc, AttnParams prm) {
+    float* part_acc, float2* group_ml, float* group_acc, AttnParams prm,
+    const typename std::conditional<FUSED, FusedArgs, NoFusedArgs>::type fa) {
     extern __shared__ int32_t lds[];
     int32_t* pre = lds;                  // [B + 1]
     int32_t* len = lds + prm.B + 1;      // [B]
     __shared__ int32_t s_wave_tot[kGroupWaves];
-    build_row_prefix(seq_lens, prm.B, prm.max_len, pre, len, s_wave_tot);
+    build_row_prefix(seq_lens, prm.B, prm.max_len, FUSED, pre, len, s_wave_tot);
 
     const int32_t lane = threadIdx.x & 63;
     const int32_t w = blockIdx.x * kGroupWaves + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int32_t G = prm.G, Hkv = prm.Hkv;
+
+    if constexpr (FUSED) {
+        if (blockIdx.x == 0)
+            for (int32_t i = threadIdx.x; i < fa.n_delta; i += blockDim.x) {
+                const int32_t slot = fa.slot[i];
+                if (slot >= 0 && slot < prm.B && len[slot] > 0)
+                    fa.page_table_w[(int64_t)slot * prm.max_pages + ((len[slot] - 1) >> prm.log2P)] = fa.page[i];
+            }
+    }
 
     // Rows without tokens give zeros; wave w of the launch clears rows w, w + W, ...
     for (int32_t b = w; b < prm.B; b += prm.W) {
@@ -451,10 +543,11 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
     }
 
     const Deal deal((int64_t)pre[prm.B] * Hkv, prm.W);
-    if (w >= deal.W) return;
+    do {  // one pass; a wave without work leaves it early
+    if (w >= deal.W) break;
     int64_t item = deal.first_step(w);
     int32_t todo = (int32_t)(deal.first_step(w + 1) - item);
-    if (todo <= 0) return;
+    if (todo <= 0) break;
 
     // Locate the first stream: the last row b with Hkv * pre[b] <= item (such a row is not empty).
     int32_t b;
@@ -482,12 +575,29 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
     ctx.q = lane >> 4;
     const int32_t rr = ctx.r < G ? ctx.r : 0;  // lanes of the padding heads shadow head 0, store nothing
 
+    const int32_t b_first = b, h_first = h, s_first = s, n_first = n_b, todo_first = todo;
+
     bool first_stream = true;
     while (todo > 0) {
         const int32_t L = len[b];
         const int32_t cnt = min(todo, n_b - s);
         ctx.pt_row = page_table + (int64_t)b * prm.max_pages;
         ctx.h = h;
+        if constexpr (FUSED) {
+            ctx.k_new_row = fa.k_new + ((int64_t)b * Hkv + h) * (D / 8);
+            ctx.v_new_row = (const uint16_t*)fa.v_new + ((int64_t)b * Hkv + h) * D;
+            ctx.new_tok = L - 1;
+            ctx.new_pi = (L - 1) >> prm.log2P;
+            ctx.new_page = s + cnt == n_b ? newest_page(fa, ctx.pt_row, b, L, prm.log2P, prm.num_pages) : 0;
+        }
+        // The newest token's V elements this lane may need, fetched ahead of the stream's loads.
+        uint32_t v_fresh[D / 16];
+        if constexpr (FUSED) {
+            if (s + cnt == n_b) {
+#pragma unroll
+                for (int nt = 0; nt < D / 16; ++nt) v_fresh[nt] = ctx.v_new_row[16 * nt + ctx.r];
+            }
+        }
 
         // Q as the B operand: lane (r, q) holds head r, head-dim 32kk + 8q .. + 7; zero for r >= G.
         bf16x8_t qf[D / 32];
@@ -503,43 +613,58 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
         acc.m = -INFINITY;
         acc.l = 0.f;
 
+        // In a fused launch the step that holds the stream's newest token runs as code of its
+        // own after the loop, so that the loop is the same as in a plain launch.
+        const bool has_newest = FUSED && s + cnt == n_b;
+        const int32_t loop_end = s + cnt - (has_newest ? 1 : 0);
         if (kDoubleBuffer) {
             // Two register sets: the loads of step i + 1 are in flight while step i is computed.
             StepData<D> s0, s1;
-            const int32_t end_step = s + cnt;
             int32_t i = s;
-            load_k<D>(ctx, i * kStep, s0);
-            load_v<D>(ctx, i * kStep, s0);
-            for (;;) {
-                float sv[8];
-                const bool more1 = i + 1 < end_step;
-                if (more1) {
-                    load_k<D>(ctx, (i + 1) * kStep, s1);
-                    load_v<D>(ctx, (i + 1) * kStep, s1);
+            if (i < loop_end) {
+                load_k<D, false>(ctx, i * kStep, s0);
+                load_v<D, false>(ctx, i * kStep, s0);
+                for (;;) {
+                    float sv[8];
+                    const bool more1 = i + 1 < loop_end;
+                    if (more1) {
+                        load_k<D, false>(ctx, (i + 1) * kStep, s1);
+                        load_v<D, false>(ctx, (i + 1) * kStep, s1);
+                    }
+                    score_step<D>(ctx, qf, s0, i * kStep, L, prm.scale_log2e, sv);
+                    accumulate_step<D, false>(ctx, sv, s0, i * kStep, L, acc);
+                    if (!more1) break;
+                    ++i;
+                    const bool more0 = i + 1 < loop_end;
+                    if (more0) {
+                        load_k<D, false>(ctx, (i + 1) * kStep, s0);
+                        load_v<D, false>(ctx, (i + 1) * kStep, s0);
+                    }
+                    score_step<D>(ctx, qf, s1, i * kStep, L, prm.scale_log2e, sv);
+                    accumulate_step<D, false>(ctx, sv, s1, i * kStep, L, acc);
+                    if (!more0) break;
+                    ++i;
                 }
-                score_step<D>(ctx, qf, s0, i * kStep, L, prm.scale_log2e, sv);
-                accumulate_step<D>(ctx, sv, s0, i * kStep, L, acc);
-                if (!more1) break;
-                ++i;
-                const bool more0 = i + 1 < end_step;
-                if (more0) {
-                    load_k<D>(ctx, (i + 1) * kStep, s0);
-                    load_v<D>(ctx, (i + 1) * kStep, s0);
-                }
-                score_step<D>(ctx, qf, s1, i * kStep, L, prm.scale_log2e, sv);
-                accumulate_step<D>(ctx, sv, s1, i * kStep, L, acc);
-                if (!more0) break;
-                ++i;
             }
         } else {
-            for (int32_t i = s; i < s + cnt; ++i) {
+            for (int32_t i = s; i < loop_end; ++i) {
                 StepData<D> sd;
-                load_k<D>(ctx, i * kStep, sd);
-                load_v<D>(ctx, i * kStep, sd);
+                load_k<D, false>(ctx, i * kStep, sd);
+                load_v<D, false>(ctx, i * kStep, sd);
                 float sv[8];
                 score_step<D>(ctx, qf, sd, i * kStep, L, prm.scale_log2e, sv);
-                accumulate_step<D>(ctx, sv, sd, i * kStep, L, acc);
+                accumulate_step<D, false>(ctx, sv, sd, i * kStep, L, acc);
             }
+        }
+        if (has_newest) {
+            const int32_t t0 = loop_end * kStep;
+            StepData<D> sd;
+            load_k<D, FUSED>(ctx, t0, sd);
+            load_v<D, FUSED>(ctx, t0, sd);
+            float sv[8];
+            score_step<D>(ctx, qf, sd, t0, L, prm.scale_log2e, sv);
+            patch_newest_v<D>(ctx, t0, v_fresh, sd);
+            accumulate_step<D, FUSED>(ctx, sv, sd, t0, L, acc);
         }
 
         // Finish the per-head sum across the four q-groups of the wave.
@@ -598,6 +723,45 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
             }
         }
     }
+
+    if constexpr (FUSED) {
+        // Append pass, after the wave's attention work so that nothing waits for these stores:
+        // the wave that owned a stream's last step writes that stream's newest token (the K and
+        // V row of one KV head) into the pages.
+        const int32_t P = 1 << prm.log2P;
+        int32_t ab = b_first, ah = h_first, as = s_first, an = n_first, atodo = todo_first;
+        while (atodo > 0) {
+            const int32_t cnt = min(atodo, an - as);
+            if (as + cnt == an) {
+                const int32_t L = len[ab];
+                const int32_t page = newest_page(fa, page_table + (int64_t)ab * prm.max_pages, ab, L, prm.log2P, prm.num_pages);
+                const int32_t pos = (L - 1) & (P - 1);
+                const int64_t row = (int64_t)ab * Hkv + ah;
+                if (lane < D / 8)
+                    ((uint4*)k_pages)[(((int64_t)page * Hkv + ah) * (D / 8) + lane) * P + roll::k_slot(pos, P)] =
+                        fa.k_new[row * (D / 8) + lane];
+                uint16_t* vdst = (uint16_t*)v_pages + ((((int64_t)page * Hkv + ah) * (P / 8) + pos / 8) * D) * 8 + pos % 8;
+                const uint16_t* vsrc = (const uint16_t*)fa.v_new + row * D;
+#pragma unroll
+                for (int e = 0; e < D / 64; ++e) vdst[(int64_t)(lane + 64 * e) * 8] = vsrc[lane + 64 * e];
+            }
+            atodo -= cnt;
+            as = 0;
+            if (atodo > 0 && ++ah == Hkv) {
+                ah = 0;
+                do { ++ab; } while (ab < prm.B - 1 && pre[ab + 1] == pre[ab]);
+                an = pre[ab + 1] - pre[ab];
+            }
+        }
+    }
+    } while (false);
+
+    if constexpr (FUSED) {
+        // Every workgroup has read the old lengths long ago; the last one to get here writes the
+        // new ones.  At the end of the wave's work the atomic's round trip delays nothing.
+        if (threadIdx.x < 64 && arrive_last(fa.grid_arrivals, (int32_t)gridDim.x, lane))
+            for (int32_t i = lane; i < prm.B; i += 64) fa.seq_lens_w[i] = len[i];
+    }
 }
 
 int validate(const roll_attn_desc* d) {
@@ -639,9 +803,9 @@ int persistent_waves(int head_dim, size_t lds_bytes, int32_t* waves_out) {
     ROLL_HIP_CHECK(hipGetDeviceProperties(&prop, dev));
     int groups = 0;
     if (head_dim == 128)
-        ROLL_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&groups, attn_stream<128>, kGroupWaves * 64, lds_bytes));
+        ROLL_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&groups, attn_stream<128, false>, kGroupWaves * 64, lds_bytes));
     else
-        ROLL_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&groups, attn_stream<64>, kGroupWaves * 64, lds_bytes));
+        ROLL_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&groups, attn_stream<64, false>, kGroupWaves * 64, lds_bytes));
     if (groups < 1) return roll::fail(ROLL_ERR_HIP, "the attention kernel does not fit on a compute unit");
     c = kGroupWaves * prop.multiProcessorCount;
     *waves_out = c;
@@ -666,12 +830,12 @@ extern "C" int roll_decode_attn_workspace_init(void* workspace, size_t workspace
     return ROLL_OK;
 }
 
-extern "C" int roll_decode_attn(const void* q, const void* k_pages, const void* v_pages,
-                                const int32_t* page_table, const int32_t* seq_lens, void* out,
-                                const roll_attn_desc* d, void* workspace, size_t workspace_bytes,
-                                void* stream_v) {
-    int rc = validate(d);
-    if (rc != ROLL_OK) return rc;
+namespace {
+
+// Argument checks and the launch shared by the plain and the fused entry point.
+int launch_attn(const void* q, const void* k_pages, const void* v_pages, const int32_t* page_table,
+                const int32_t* seq_lens, void* out, const roll_attn_desc* d, void* workspace,
+                size_t workspace_bytes, hipStream_t stream, FusedArgs* fused) {
     if (!q || !k_pages || !v_pages || !page_table || !seq_lens || !out)
         return roll::fail(ROLL_ERR_INVALID_ARG, "NULL pointer argument");
     if (!roll::aligned(q, 16) || !roll::aligned(k_pages, 16) || !roll::aligned(v_pages, 16) || !roll::aligned(out, 16) ||
@@ -685,12 +849,11 @@ extern "C" int roll_decode_attn(const void* q, const void* k_pages, const void* 
 
     const size_t lds = sizeof(int32_t) * (2 * (size_t)d->batch + 1);
     int32_t W = 0;
-    rc = persistent_waves(d->head_dim, lds, &W);
+    int rc = persistent_waves(d->head_dim, lds, &W);
     if (rc != ROLL_OK) return rc;
     if (W > kMaxPersistentWaves) W = kMaxPersistentWaves;
     W = W / kGroupWaves * kGroupWaves;
 
-    hipStream_t stream = (hipStream_t)stream_v;
     AttnParams prm{};
     prm.B = d->batch;
     prm.Hq = d->num_q_heads;
@@ -707,15 +870,74 @@ extern "C" int roll_decode_attn(const void* q, const void* k_pages, const void* 
 
     const unsigned grid = (unsigned)(W / kGroupWaves);
     if (d->ev_main_begin) ROLL_HIP_CHECK(hipEventRecord((hipEvent_t)d->ev_main_begin, stream));
-    if (d->head_dim == 128)
-        attn_stream<128><<<grid, kGroupWaves * 64, lds, stream>>>(
-            (const uint4*)q, (const uint4*)k_pages, (const uint4*)v_pages, page_table, seq_lens, out,
-            ws.group_arrivals, ws.stream_arrivals, ws.part_ml, ws.part_acc, ws.group_ml, ws.group_acc, prm);
-    else
-        attn_stream<64><<<grid, kGroupWaves * 64, lds, stream>>>(
-            (const uint4*)q, (const uint4*)k_pages, (const uint4*)v_pages, page_table, seq_lens, out,
-            ws.group_arrivals, ws.stream_arrivals, ws.part_ml, ws.part_acc, ws.group_ml, ws.group_acc, prm);
+#define ROLL_LAUNCH_ATTN(DIM, FUSED, EXTRA)                                                                   \
+    attn_stream<DIM, FUSED><<<grid, kGroupWaves * 64, lds, stream>>>(                                        \
+        (const uint4*)q, (const uint4*)k_pages, (const uint4*)v_pages, page_table, seq_lens, out,             \
+        ws.group_arrivals, ws.stream_arrivals, ws.part_ml, ws.part_acc, ws.group_ml, ws.group_acc, prm, EXTRA)
+    if (fused) {
+        fused->grid_arrivals = ws.grid_arrivals;
+        if (d->head_dim == 128) ROLL_LAUNCH_ATTN(128, true, *fused);
+        else ROLL_LAUNCH_ATTN(64, true, *fused);
+    } else {
+        if (d->head_dim == 128) ROLL_LAUNCH_ATTN(128, false, NoFusedArgs{});
+        else ROLL_LAUNCH_ATTN(64, false, NoFusedArgs{});
+    }
+#undef ROLL_LAUNCH_ATTN
     ROLL_HIP_CHECK(hipGetLastError());
     if (d->ev_main_end) ROLL_HIP_CHECK(hipEventRecord((hipEvent_t)d->ev_main_end, stream));
+    return ROLL_OK;
+}
+
+}  // namespace
+
+extern "C" int roll_decode_attn(const void* q, const void* k_pages, const void* v_pages,
+                                const int32_t* page_table, const int32_t* seq_lens, void* out,
+                                const roll_attn_desc* d, void* workspace, size_t workspace_bytes,
+                                void* stream_v) {
+    int rc = validate(d);
+    if (rc != ROLL_OK) return rc;
+    return launch_attn(q, k_pages, v_pages, page_table, seq_lens, out, d, workspace, workspace_bytes,
+                       (hipStream_t)stream_v, nullptr);
+}
+
+extern "C" int roll_decode_step_attn(roll_kv_pool* pool, const void* k_new, const void* v_new, const void* q,
+                                     void* k_pages, void* v_pages, void* out, const roll_attn_desc* d,
+                                     void* workspace, size_t workspace_bytes, void* stream_v) {
+    int rc = validate(d);
+    if (rc != ROLL_OK) return rc;
+    if (!pool || !k_new || !v_new) return roll::fail(ROLL_ERR_INVALID_ARG, "NULL pointer argument");
+    if (!roll::aligned(k_new, 16) || !roll::aligned(v_new, 16))
+        return roll::fail(ROLL_ERR_INVALID_ARG, "k_new, v_new must be 16-byte aligned");
+    hipStream_t stream = (hipStream_t)stream_v;
+    roll::FusedPlan plan;
+    rc = roll::plan_fused_step(pool, stream, &plan);
+    if (rc != ROLL_OK) return rc;
+    if (plan.num_slots != d->batch || plan.page_size != d->page_size || plan.max_pages != d->max_pages_per_seq ||
+        plan.num_pages != d->num_pages)
+        return roll::fail(ROLL_ERR_INVALID_ARG, "desc does not match the pool (slots %d, page size %d, max pages %d, pages %d)",
+                          plan.num_slots, plan.page_size, plan.max_pages, plan.num_pages);
+    if (!plan.fusable) {
+        // Not a plain decode step since the last commit (refills, first use, many new pages):
+        // publish through the allocator's own kernel, then attend.
+        rc = roll_kv_commit_append(pool, k_new, v_new, k_pages, v_pages, d->num_kv_heads, d->head_dim, stream_v);
+        if (rc != ROLL_OK) return rc;
+        return launch_attn(q, k_pages, v_pages, plan.page_table_dev, plan.seq_lens_dev, out, d, workspace,
+                           workspace_bytes, stream, nullptr);
+    }
+    FusedArgs fa;
+    fa.n_delta = plan.n_delta;
+    for (int32_t i = 0; i < plan.n_delta; ++i) {
+        fa.slot[i] = plan.slot[i];
+        fa.page[i] = plan.page[i];
+    }
+    fa.k_new = (const uint4*)k_new;
+    fa.v_new = (const uint4*)v_new;
+    fa.page_table_w = plan.page_table_dev;
+    fa.seq_lens_w = plan.seq_lens_dev;
+    fa.grid_arrivals = nullptr;
+    rc = launch_attn(q, k_pages, v_pages, plan.page_table_dev, plan.seq_lens_dev, out, d, workspace,
+                     workspace_bytes, stream, &fa);
+    if (rc != ROLL_OK) return rc;
+    roll::finish_fused_step(pool);
     return ROLL_OK;
 }

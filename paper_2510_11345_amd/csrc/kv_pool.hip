@@ -20,6 +20,8 @@
 #include <vector>
 
 #include "common.h"
+#include "kv_layout.h"
+#include "kv_pool_internal.h"
 
 namespace {
 
@@ -36,27 +38,6 @@ struct Stage {
 __global__ void fill_i32(int32_t* dst, int64_t n, int32_t value) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) dst[i] = value;
-}
-
-// Store 8 consecutive head-dim elements of one token's K and V into the two page layouts.
-//   K page layout [page][h][d/8][kpos(t)][d%8]: the slice is one 16-byte store.
-//   V page layout [page][h][t/8][d][t%8]: the slice is 8 two-byte stores, 16 bytes apart.
-__device__ __forceinline__ void store_kv_slice(uint4 kv, uint4 vv, uint4* __restrict__ k_pages,
-                                               uint16_t* __restrict__ v_pages, int32_t page, int32_t t,
-                                               int32_t h, int32_t c, int32_t P, int32_t Hkv, int32_t D) {
-    // kpos: inside blocks of min(P, 32) tokens, the low quad of every 8 tokens goes to the
-    // first half of the block and the high quad to the second half.
-    const int32_t width = P < 32 ? P : 32;
-    const int32_t u = t & (width - 1);
-    const int32_t kpos = (t - u) + (u & 3) + 4 * (u >> 3) + (width >> 1) * ((u >> 2) & 1);
-    k_pages[(((int64_t)page * Hkv + h) * (D / 8) + c) * P + kpos] = kv;
-    uint16_t* vdst = v_pages + ((((int64_t)page * Hkv + h) * (P / 8) + t / 8) * D + c * 8) * 8 + t % 8;
-    const uint32_t w[4] = {vv.x, vv.y, vv.z, vv.w};
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        vdst[(2 * j) * 8] = (uint16_t)(w[j] & 0xFFFFu);
-        vdst[(2 * j + 1) * 8] = (uint16_t)(w[j] >> 16);
-    }
 }
 
 // stage = [lengths (num_slots)][append targets (num_slots)][pairs]; one thread per entry.
@@ -82,7 +63,7 @@ __global__ void apply_updates(const int32_t* __restrict__ stage, int32_t* __rest
             const int32_t c = i % d8n, h = (i / d8n) % Hkv, slot = i / (d8n * Hkv);
             const int32_t target = stage[num_slots + slot];
             if (target >= 0 && target / P < num_pages)
-                store_kv_slice(k_new[i], v_new[i], k_pages, v_pages, target / P, target % P, h, c, P, Hkv, D);
+                roll::store_kv_slice(k_new[i], v_new[i], k_pages, v_pages, target / P, target % P, h, c, P, Hkv, D);
         }
     }
 }
@@ -108,7 +89,7 @@ __global__ void append_tokens(const uint4* __restrict__ k_new, const uint4* __re
     if (pidx >= max_pages) return;
     const int32_t page = page_table[(int64_t)slot * max_pages + pidx];
     if (page < 0 || page >= num_pages) return;
-    store_kv_slice(k_new[item], v_new[item], k_pages, v_pages, page, pos % P, h, c, P, Hkv, D);
+    roll::store_kv_slice(k_new[item], v_new[item], k_pages, v_pages, page, pos % P, h, c, P, Hkv, D);
 }
 
 }  // namespace
@@ -126,6 +107,10 @@ struct roll_kv_pool {
     int32_t* page_table_dev = nullptr;
     int32_t* seq_lens_dev = nullptr;
     bool device_tables_initialised = false;
+    // Lengths as the device holds them after the last commit (valid once one has happened).
+    std::vector<int32_t> committed_len;
+    bool committed_len_valid = false;
+    int64_t fused_steps = 0;
     Stage ring[kRing];
     int ring_next = 0;
 };
@@ -289,10 +274,21 @@ struct AppendArgs {
     int32_t Hkv = 0, D = 0;
 };
 
-static int commit_impl(roll_kv_pool* pool, void* stream_v, const AppendArgs& ap) {
+// Where the newest token of each live slot goes: page * P + position in page, -1 for an empty slot.
+static void fill_append_targets(const roll_kv_pool* pool, int32_t* target) {
+    const roll_kv_config& c = pool->cfg;
+    for (int32_t slot = 0; slot < c.num_slots; ++slot) {
+        const int32_t len = pool->slot_len[slot];
+        target[slot] = len > 0 ? pool->slot_pages[(size_t)slot * c.max_pages_per_seq + (len - 1) / c.page_size] * c.page_size +
+                                     (len - 1) % c.page_size
+                               : -1;
+    }
+}
+
+// First-use fill of the device table and de-duplication of the pending deltas.
+static int prepare_commit(roll_kv_pool* pool, hipStream_t stream) {
     if (!pool) return roll::fail(ROLL_ERR_INVALID_ARG, "pool is NULL");
     if (!pool->page_table_dev) return roll::fail(ROLL_ERR_INVALID_ARG, "host-only pool has no device tables to commit to");
-    hipStream_t stream = (hipStream_t)stream_v;
     const roll_kv_config& c = pool->cfg;
     const int64_t table_elems = (int64_t)c.num_slots * c.max_pages_per_seq;
     if (!pool->device_tables_initialised) {
@@ -322,6 +318,15 @@ static int commit_impl(roll_kv_pool* pool, void* stream_v, const AppendArgs& ap)
         }
         pd.erase(pd.begin(), pd.begin() + (std::ptrdiff_t)w);
     }
+    return ROLL_OK;
+}
+
+static int commit_impl(roll_kv_pool* pool, void* stream_v, const AppendArgs& ap) {
+    hipStream_t stream = (hipStream_t)stream_v;
+    int rc0 = prepare_commit(pool, stream);
+    if (rc0 != ROLL_OK) return rc0;
+    const roll_kv_config& c = pool->cfg;
+    const int64_t table_elems = (int64_t)c.num_slots * c.max_pages_per_seq;
     const size_t n_pairs = pool->pending.size() / 2;
     size_t done = 0;
     bool first = true;
@@ -334,15 +339,7 @@ static int commit_impl(roll_kv_pool* pool, void* stream_v, const AppendArgs& ap)
         const bool last = done + batch >= n_pairs;
         const bool append = last && ap.k_new != nullptr;
         if (last) std::memcpy(s->host, pool->slot_len.data(), sizeof(int32_t) * c.num_slots);
-        if (append) {  // where the newest token of each live slot goes: page * P + position in page
-            int32_t* target = s->host + c.num_slots;
-            for (int32_t slot = 0; slot < c.num_slots; ++slot) {
-                const int32_t len = pool->slot_len[slot];
-                target[slot] = len > 0 ? pool->slot_pages[(size_t)slot * c.max_pages_per_seq + (len - 1) / c.page_size] * c.page_size +
-                                             (len - 1) % c.page_size
-                                       : -1;
-            }
-        }
+        if (append) fill_append_targets(pool, s->host + c.num_slots);
         if (batch > 0)
             std::memcpy(s->host + 2 * c.num_slots, pool->pending.data() + 2 * done, sizeof(int32_t) * 2 * batch);
         const int threads = 256;
@@ -359,10 +356,54 @@ static int commit_impl(roll_kv_pool* pool, void* stream_v, const AppendArgs& ap)
         first = false;
     }
     pool->pending.clear();
+    pool->committed_len = pool->slot_len;
+    pool->committed_len_valid = true;
     return ROLL_OK;
 }
 
 extern "C" int roll_kv_commit(roll_kv_pool* pool, void* stream) { return commit_impl(pool, stream, AppendArgs{}); }
+
+int roll::plan_fused_step(roll_kv_pool* pool, hipStream_t stream, roll::FusedPlan* plan) {
+    int rc = prepare_commit(pool, stream);
+    if (rc != ROLL_OK) return rc;
+    const roll_kv_config& c = pool->cfg;
+    plan->num_slots = c.num_slots;
+    plan->max_pages = c.max_pages_per_seq;
+    plan->num_pages = c.num_pages;
+    plan->page_size = c.page_size;
+    plan->page_table_dev = pool->page_table_dev;
+    plan->seq_lens_dev = pool->seq_lens_dev;
+    plan->n_delta = 0;
+    plan->fusable = 0;
+    const size_t n_pairs = pool->pending.size() / 2;
+    if (!pool->committed_len_valid || n_pairs > (size_t)roll::kMaxFusedDeltas) return ROLL_OK;
+    for (int32_t slot = 0; slot < c.num_slots; ++slot) {
+        const int32_t was = pool->committed_len[slot];
+        if (pool->slot_len[slot] != was + (was > 0 ? 1 : 0)) return ROLL_OK;
+    }
+    for (size_t i = 0; i < n_pairs; ++i) {
+        const int32_t idx = pool->pending[2 * i], slot = idx / c.max_pages_per_seq;
+        const int32_t len = pool->slot_len[slot];
+        if (len <= 0 || idx != slot * c.max_pages_per_seq + (len - 1) / c.page_size || (len - 1) % c.page_size != 0)
+            return ROLL_OK;
+        plan->slot[i] = slot;
+        plan->page[i] = pool->pending[2 * i + 1];
+    }
+    plan->n_delta = (int32_t)n_pairs;
+    plan->fusable = 1;
+    return ROLL_OK;
+}
+
+void roll::finish_fused_step(roll_kv_pool* pool) {
+    pool->pending.clear();
+    pool->committed_len = pool->slot_len;
+    ++pool->fused_steps;
+}
+
+extern "C" int64_t roll_kv_fused_steps(const roll_kv_pool* pool) {
+    if (!pool) return roll::fail(ROLL_ERR_INVALID_ARG, "pool is NULL");
+    return pool->fused_steps;
+}
 
 extern "C" int roll_kv_commit_append(roll_kv_pool* pool, const void* k_new, const void* v_new, void* k_pages,
                                      void* v_pages, int32_t num_kv_heads, int32_t head_dim, void* stream) {

@@ -25,7 +25,7 @@ class DecodeBatch:
     def __init__(self, cfg: wl.DecodeConfig, seed: int, lengths: np.ndarray, headroom_tokens: int = 0,
                  out_dtype=torch.bfloat16, device: str = "cuda",
                  spare_pages: int = 64, max_len: int | None = None, fill_pools: bool = True,
-                 profile_events: bool = False, num_pages: int | None = None):
+                 profile_events: bool = False, num_pages: int | None = None, fused: bool = True):
         self.cfg, self.seed, self.device = cfg, seed, device
         B, P = cfg.batch, cfg.page_size
         Hq, Hkv, D = cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim
@@ -56,6 +56,7 @@ class DecodeBatch:
         self.ev_pairs = []   # (begin, end, sum of seq_lens) per profiled step
         self.ev_spare = []   # pre-created event pairs, so that none is created inside a timed loop
         self.profile_events = profile_events
+        self.fused = fused
         self.out_dtype = out_dtype
         self.desc = rb.attn_desc(self.q, self.k_pages, self.page_table, P, out_dtype)
         self._ws = rb.new_attn_workspace(self.desc, device)
@@ -81,19 +82,26 @@ class DecodeBatch:
     # -- one decode step --------------------------------------------------------
     def step(self, logits: torch.Tensor, step_index: int, temperature=None, top_p=None,
              grow: bool = True) -> None:
-        """alloc (+1 token per row) -> commit + append K/V (one launch) -> attention -> sample."""
+        """alloc (+1 token per row) -> commit + append K/V + attention (one launch when self.fused,
+        else two) -> sample."""
         cfg = self.cfg
+        fused = grow and self.fused
         if grow:
             rb.roll_kv_alloc_batch(self.pool, self.all_slots, self.ones)
             self.lengths += 1
-            rb.roll_kv_commit_append(self.pool, self.k_new, self.v_new, self.k_pages, self.v_pages)
+            if not fused:
+                rb.roll_kv_commit_append(self.pool, self.k_new, self.v_new, self.k_pages, self.v_pages)
         desc = self.desc
         if self.profile_events:
             e0, e1 = self.ev_spare.pop() if self.ev_spare else (rb.ProfEvent(), rb.ProfEvent())
             desc.ev_main_begin, desc.ev_main_end = e0.handle.value, e1.handle.value
             self.ev_pairs.append((e0, e1, self.total_tokens()))
-        rb.roll_decode_attn(self.q, self.k_pages, self.v_pages, self.page_table, self.seq_lens, self.out,
-                            desc, self._ws)
+        if fused:
+            rb.roll_decode_step_attn(self.pool, self.k_new, self.v_new, self.q, self.k_pages, self.v_pages,
+                                     self.out, desc, self._ws)
+        else:
+            rb.roll_decode_attn(self.q, self.k_pages, self.v_pages, self.page_table, self.seq_lens, self.out,
+                                desc, self._ws)
         if self.profile_events:
             desc.ev_main_begin, desc.ev_main_end = None, None
         sdesc = rb.sample_desc(logits)
