@@ -52,6 +52,7 @@ def lib():
         L.oracle_top_p_cut.restype = C.c_double
         L.oracle_top_p_cut.argtypes = [C.POINTER(C.c_double), C.c_int, C.c_double, C.c_double]
         L.oracle_decode_attn.restype = C.c_int
+        L.oracle_prefill_attn.restype = C.c_int
         L.oracle_sample_logprob.restype = C.c_int
         _lib = L
     return _lib
@@ -122,6 +123,30 @@ def decode_attn(q, k_pages, v_pages, page_table, seq_lens, Hq, Hkv, D, P, scale=
         C.c_int(page_table.shape[1]), C.c_double(scale), _p(r, C.c_int32),
         C.c_int(0 if r is None else len(r)), C.c_int(n_threads))
     return (out, used) if return_threads else out
+
+
+def prefill_attn(q, k_new, v_new, chunk_slot, chunk_start, chunk_offset, k_pages, v_pages, page_table,
+                 Hq, Hkv, D, P, scale=None, n_threads=0):
+    """Chunked prefill: writes the chunk tokens' K/V into k_pages / v_pages IN PLACE (uint16 pools)
+    and returns out[T, Hq, D] fp64, token (c, j) attending over positions 0 .. chunk_start[c] + j
+    of slot chunk_slot[c].  q uint16 [T, Hq, D]; k_new, v_new uint16 [T, Hkv, D]."""
+    for a in (q, k_new, v_new, k_pages, v_pages):
+        assert a.dtype == np.uint16 and a.flags.c_contiguous
+    cs = np.ascontiguousarray(chunk_slot, dtype=np.int32)
+    st = np.ascontiguousarray(chunk_start, dtype=np.int32)
+    off = np.ascontiguousarray(chunk_offset, dtype=np.int32)
+    page_table = np.ascontiguousarray(page_table, dtype=np.int32)
+    n_chunks, T = len(cs), int(off[-1])
+    assert len(st) == n_chunks and len(off) == n_chunks + 1 and q.shape[0] == T
+    scale = 1.0 / np.sqrt(D) if scale is None else scale
+    out = np.zeros((T, Hq, D), dtype=np.float64)
+    lib().oracle_prefill_attn(
+        _p(q, C.c_uint16), _p(k_new, C.c_uint16), _p(v_new, C.c_uint16), _p(cs, C.c_int32),
+        _p(st, C.c_int32), _p(off, C.c_int32), C.c_int(n_chunks), _p(k_pages, C.c_uint16),
+        _p(v_pages, C.c_uint16), _p(page_table, C.c_int32), _p(out, C.c_double), C.c_int(Hq),
+        C.c_int(Hkv), C.c_int(D), C.c_int(P), C.c_int(page_table.shape[1]), C.c_double(scale),
+        C.c_int(n_threads))
+    return out
 
 
 def _logits_args(logits):

@@ -234,6 +234,80 @@ int oracle_decode_attn(const uint16_t* q, const uint16_t* k_pages, const uint16_
 }
 
 /* ------------------------------------------------------------------ */
+/* Chunked prefill                                                     */
+/* ------------------------------------------------------------------ */
+
+/*
+ * The prefill step of the engine loop (Section 4.2: a request that joins the
+ * running batch is first prefilled, then decoded step by step), taken in
+ * chunks.  Chunk c holds the n_c = chunk_offset[c+1] - chunk_offset[c]
+ * consecutive tokens of slot chunk_slot[c] at positions chunk_start[c] + j;
+ * the slot's page-table row already maps those positions.
+ *   1. every chunk token's K and V ([Hkv, D] bf16 each) go into the pages at
+ *      the token's position;
+ *   2. token (c, j) attends causally over its slot's positions
+ *      0 .. chunk_start[c] + j:  out = sum_i softmax_i(scale <q, K_i>) V_i.
+ * q, out are [T, Hq, D] and k_new, v_new [T, Hkv, D] with T = chunk_offset[C];
+ * query head h uses KV head h / (Hq / Hkv).  Everything in fp64.
+ * Readings: Q and K arrive position-encoded; plain causal mask, nothing else.
+ * Returns the number of threads used.
+ */
+int oracle_prefill_attn(const uint16_t* q, const uint16_t* k_new, const uint16_t* v_new,
+                        const int32_t* chunk_slot, const int32_t* chunk_start,
+                        const int32_t* chunk_offset, int C, uint16_t* k_pages, uint16_t* v_pages,
+                        const int32_t* page_table, double* out, int Hq, int Hkv, int D, int P,
+                        int max_pages, double scale, int n_threads)
+{
+    int used = 1;
+#ifdef _OPENMP
+    if (n_threads > 0) omp_set_num_threads(n_threads);
+    used = omp_get_max_threads();
+#endif
+    /* step 1, in token order */
+    for (int c = 0; c < C; ++c)
+        for (int t = chunk_offset[c]; t < chunk_offset[c + 1]; ++t) {
+            int pos = chunk_start[c] + (t - chunk_offset[c]);
+            int64_t page = page_table[(int64_t)chunk_slot[c] * max_pages + pos / P];
+            oracle_kv_store(k_pages, v_pages, page, pos % P, k_new + (int64_t)t * Hkv * D,
+                            v_new + (int64_t)t * Hkv * D, Hkv, D, P);
+        }
+    /* step 2: tokens and heads are independent */
+    const int group = Hq / Hkv;
+    for (int c = 0; c < C; ++c) {
+        const int32_t* pt = page_table + (int64_t)chunk_slot[c] * max_pages;
+        const int t_begin = chunk_offset[c], n_tok = chunk_offset[c + 1] - chunk_offset[c];
+        const int64_t units = (int64_t)n_tok * Hq;
+#pragma omp parallel for schedule(dynamic, 1)
+        for (int64_t u = 0; u < units; ++u) {
+            const int t = t_begin + (int)(u / Hq), h = (int)(u % Hq), kvh = h / group;
+            const int last = chunk_start[c] + (t - t_begin); /* newest position the token sees */
+            const uint16_t* qv = q + ((int64_t)t * Hq + h) * D;
+            double* o = out + ((int64_t)t * Hq + h) * D;
+            double* sc = (double*)malloc(sizeof(double) * (size_t)(last + 1));
+            double mx = -INFINITY;
+            for (int i = 0; i <= last; ++i) {
+                double dot = 0.0;
+                for (int d = 0; d < D; ++d)
+                    dot += bf16_to_double(qv[d]) *
+                           bf16_to_double(k_pages[oracle_k_index(pt[i / P], kvh, i % P, d, Hkv, D, P)]);
+                sc[i] = dot * scale;
+                if (sc[i] > mx) mx = sc[i];
+            }
+            double z = 0.0;
+            for (int i = 0; i <= last; ++i) z += exp(sc[i] - mx);
+            for (int d = 0; d < D; ++d) o[d] = 0.0;
+            for (int i = 0; i <= last; ++i) {
+                double wgt = exp(sc[i] - mx) / z;
+                for (int d = 0; d < D; ++d)
+                    o[d] += wgt * bf16_to_double(v_pages[oracle_v_index(pt[i / P], kvh, i % P, d, Hkv, D, P)]);
+            }
+            free(sc);
+        }
+    }
+    return used;
+}
+
+/* ------------------------------------------------------------------ */
 /* Sampling                                                            */
 /* ------------------------------------------------------------------ */
 
