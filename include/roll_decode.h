@@ -270,6 +270,55 @@ int roll_decode_step_attn(roll_kv_pool* pool, const void* k_new, const void* v_n
                           void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------ */
+/* Chunked prefill attention into pages (Section 4.2: a request that   */
+/* joins the running batch, or a slot refilled by queue scheduling,    */
+/* Section 5.1.1, is prefilled before it is decoded step by step).     */
+/* Chunk c is the n_c = chunk_offset[c+1] - chunk_offset[c] consecutive */
+/* tokens of slot chunk_slot[c] at positions chunk_start[c] + j.       */
+/*   1. every chunk token's K/V is written into the slot's pages;      */
+/*   2. token (c, j) attends causally over its slot's positions        */
+/*      0 .. chunk_start[c] + j (tokens cached before the chunk and    */
+/*      the chunk itself): out = softmax(scale * q K^T) V.             */
+/* ------------------------------------------------------------------ */
+typedef struct roll_prefill_desc {
+    int32_t num_chunks;         /* C >= 0                                 */
+    int32_t num_tokens;         /* T = chunk_offset[C] >= 0               */
+    int32_t num_q_heads;        /* Hq, multiple of num_kv_heads, G <= 16  */
+    int32_t num_kv_heads;       /* Hkv                                    */
+    int32_t head_dim;           /* D: 64 or 128                           */
+    int32_t page_size;          /* P: 16, 32 or 64                        */
+    int32_t max_pages_per_seq;  /* row stride of page_table               */
+    int32_t num_pages;          /* pages in the pools                     */
+    int32_t num_slots;          /* rows of page_table                     */
+    int32_t out_dtype;          /* ROLL_BF16 or ROLL_F32                  */
+    float   softmax_scale;      /* 0 = 1/sqrt(head_dim)                   */
+    int32_t reserved;           /* must be 0                              */
+} roll_prefill_desc;
+
+/*
+ *   q                DEVICE bf16 [T, Hq, D], chunks back to back
+ *   k_new, v_new     DEVICE bf16 [T, Hkv, D]
+ *   chunk_slot       DEVICE int32 [C]
+ *   chunk_start      DEVICE int32 [C]  tokens the slot holds before the chunk
+ *   chunk_offset     DEVICE int32 [C + 1], non-decreasing, chunk_offset[0] = 0
+ *   k_pages, v_pages DEVICE bf16 pools in the layouts of roll_decode_attn; written
+ *   page_table       DEVICE int32 [num_slots, max_pages_per_seq]; must already map
+ *                    every position of every chunk (roll_kv_alloc + roll_kv_commit)
+ *   out              DEVICE [T, Hq, D] of out_dtype
+ * q, k_new, v_new, the pools and out 16-byte aligned.  Chunks of one call must
+ * not overlap in (slot, position); several chunks of one slot are fine.  A
+ * chunk whose slot or positions are out of range is skipped (nothing written
+ * for it, its rows of out unspecified).  Enqueues two kernels on stream: the
+ * writer of the chunk tokens, then the attention.  The device sequence lengths
+ * of the allocator are not read: the chunk arrays say how far each token sees.
+ */
+int roll_prefill_attn(const void* q, const void* k_new, const void* v_new,
+                      const int32_t* chunk_slot, const int32_t* chunk_start,
+                      const int32_t* chunk_offset, void* k_pages, void* v_pages,
+                      const int32_t* page_table, void* out,
+                      const roll_prefill_desc* desc, void* stream);
+
+/* ------------------------------------------------------------------ */
 /* Sampling with log-prob recording (Appendix A.1).  Per row r:        */
 /*   z_i = logits[r,i] / temperature                                   */
 /*   kept = all i                       if top_p >= 1                  */

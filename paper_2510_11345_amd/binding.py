@@ -26,7 +26,7 @@ EXPORTS = [
     "roll_kv_fused_steps",
     "roll_kv_append_tokens",
     "roll_decode_attn_workspace_bytes", "roll_decode_attn_workspace_init", "roll_decode_attn",
-    "roll_decode_step_attn",
+    "roll_decode_step_attn", "roll_prefill_attn",
     "roll_sample_logprob_workspace_bytes", "roll_sample_logprob", "roll_policy_loss",
     "roll_sample_buffer_create", "roll_sample_buffer_destroy", "roll_sample_buffer_begin",
     "roll_sample_buffer_complete", "roll_sample_buffer_abort", "roll_sample_buffer_resume",
@@ -62,6 +62,13 @@ class LossDesc(C.Structure):
 
 
 LOSS_KINDS = {"ppo": 0, "decoupled_ppo": 1, "tis": 2, "cispo": 3, "topr": 4}
+
+
+class PrefillDesc(C.Structure):
+    _fields_ = [("num_chunks", C.c_int32), ("num_tokens", C.c_int32), ("num_q_heads", C.c_int32),
+                ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("page_size", C.c_int32),
+                ("max_pages_per_seq", C.c_int32), ("num_pages", C.c_int32), ("num_slots", C.c_int32),
+                ("out_dtype", C.c_int32), ("softmax_scale", C.c_float), ("reserved", C.c_int32)]
 
 
 class SampleDesc(C.Structure):
@@ -105,6 +112,7 @@ def lib():
         L.roll_decode_attn_workspace_init.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
         L.roll_decode_attn.argtypes = [C.c_void_p] * 6 + [C.POINTER(AttnDesc), C.c_void_p, C.c_size_t, C.c_void_p]
         L.roll_decode_step_attn.argtypes = [C.c_void_p] * 7 + [C.POINTER(AttnDesc), C.c_void_p, C.c_size_t, C.c_void_p]
+        L.roll_prefill_attn.argtypes = [C.c_void_p] * 10 + [C.POINTER(PrefillDesc), C.c_void_p]
         L.roll_sample_logprob.argtypes = [C.c_void_p, C.c_float, C.c_float, C.c_uint64, C.c_uint64,
                                           C.c_void_p, C.c_void_p, C.POINTER(SampleDesc), C.c_void_p,
                                           C.c_size_t, C.c_void_p]
@@ -291,6 +299,27 @@ def roll_decode_step_attn(pool: "KvPool", k_new, v_new, q, k_pages, v_pages, out
         pool._h, _dev(k_new, torch.bfloat16), _dev(v_new, torch.bfloat16), _dev(q, torch.bfloat16),
         _dev(k_pages, torch.bfloat16), _dev(v_pages, torch.bfloat16), _dev(out), C.byref(desc),
         _dev(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def roll_prefill_attn(q, k_new, v_new, chunk_slot, chunk_start, chunk_offset, k_pages, v_pages, page_table,
+                      out, page_size: int, softmax_scale: float = 0.0) -> None:
+    """Chunked prefill: K/V of the chunk tokens into the pages, then causal attention per token."""
+    T, Hq, D = q.shape
+    Hkv = k_new.shape[1]
+    n_chunks = chunk_slot.shape[0]
+    assert tuple(k_new.shape) == (T, Hkv, D) and tuple(v_new.shape) == (T, Hkv, D)
+    assert tuple(out.shape) == (T, Hq, D) and chunk_start.shape[0] == n_chunks
+    assert chunk_offset.shape[0] == n_chunks + 1
+    if out.dtype not in (torch.bfloat16, torch.float32):
+        raise TypeError("out must be bfloat16 or float32")
+    desc = PrefillDesc(n_chunks, T, Hq, Hkv, D, page_size, page_table.shape[1], k_pages.shape[0],
+                       page_table.shape[0], ROLL_BF16 if out.dtype == torch.bfloat16 else ROLL_F32,
+                       softmax_scale, 0)
+    _check(lib().roll_prefill_attn(
+        _dev(q, torch.bfloat16), _dev(k_new, torch.bfloat16), _dev(v_new, torch.bfloat16),
+        _dev(chunk_slot, torch.int32), _dev(chunk_start, torch.int32), _dev(chunk_offset, torch.int32),
+        _dev(k_pages, torch.bfloat16), _dev(v_pages, torch.bfloat16), _dev(page_table, torch.int32),
+        _dev(out), C.byref(desc), _stream()))
 
 
 # ----------------------------------------------------------------------------

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libroll_decode.so")
-SOURCES = ["api.hip", "kv_pool.hip", "decode_attn.hip", "sample_logprob.hip", "policy_loss.hip",
+SOURCES = ["api.hip", "kv_pool.hip", "decode_attn.hip", "prefill_attn.hip", "sample_logprob.hip", "policy_loss.hip",
            "sample_buffer.hip"]
 
 

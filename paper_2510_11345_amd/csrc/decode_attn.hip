@@ -24,39 +24,24 @@
 // that share the KV head ride in one MFMA tile, so a KV byte is fetched once and
 // used G times.
 //
-// Per 32-token step and wave (lane = 16 * q + r):
-//   S^T[tok][g]  = K[tok][:] . Q[g][:]      2 tiles x (D/32) v_mfma_f32_16x16x32_bf16,
-//                  K rows as the A operand (16 bytes per lane straight from the page),
-//                  Q as the B operand (held in registers for the whole stream);
-//   online softmax per head g = r over the 8 scores a lane owns (tokens 8q..8q+7),
-//                  one cross-lane max over q per step;
-//   O^T[d][g]   += V^T[d][tok] . P^T[tok][g]  (D/16) x 2 MFMAs, V octets as the A operand,
-//                  P split into a bf16 high part and a bf16 remainder as two B operands so
-//                  that the probabilities keep ~16 mantissa bits (the fp32-output tolerance
-//                  does not survive an 8-bit P).
-// The accumulator layout of S^T (a lane owns 4 consecutive token rows of a tile for one
-// head) is exactly the B-operand layout of the PV product once the two S tiles are laid
-// side by side, so P never moves between lanes.  Which 8 tokens a lane owns is free as
-// long as K rows and V octets agree: tile tt, row 4*q'+i  <->  token 8*q' + 4*tt + i.
+// The per-step arithmetic (S^T = K Q^T, online softmax, O^T += V^T P^T on the matrix cores) is
+// shared with the prefill kernel and described where it is defined.
 #include <cfloat>
 #include <cmath>
 #include <mutex>
 
 #include <type_traits>
 
+#include "attn_core.h"
 #include "common.h"
 #include "kv_layout.h"
 #include "kv_pool_internal.h"
 
 namespace {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
-typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
-typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2_t;
-typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+using namespace roll::attn;
 
 constexpr int kGroupWaves = 4;     // wavefronts per workgroup (they only share the LDS prefix)
-constexpr int kStep = 32;          // tokens per wave step
 constexpr bool kDoubleBuffer = false;  // keep the next step's loads in flight while computing
 constexpr int kMinSteps = 4;       // do not spread a small batch thinner than this per wave
 constexpr int kMaxBatch = 8192;    // rows whose prefix sums fit the LDS budget
@@ -126,8 +111,6 @@ struct Deal {
     __device__ int32_t owner(int64_t i) const { return (int32_t)(((i + 1) * W + S - 1) / S - 1); }
 };
 
-__device__ __forceinline__ bf16x8_t as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8_t, v); }
-
 // KV is read exactly once per step: a nontemporal load keeps it from displacing the
 // page table, Q and the pieces in L2 (measured: +10 % on a plain streaming read).
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
@@ -135,18 +118,6 @@ __device__ __forceinline__ uint4 load_stream(const uint4* p) {
     const u32x4_t v = __builtin_nontemporal_load((const u32x4_t*)p);
     return make_uint4(v.x, v.y, v.z, v.w);
 }
-
-__device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi) {
-    f32x2_t f = {lo, hi};
-    bf16x2_t b = __builtin_convertvector(f, bf16x2_t);
-    return __builtin_bit_cast(uint32_t, b);
-}
-
-template <int D>
-struct StepData {
-    uint4 k[2][D / 32];
-    uint4 v[D / 16];
-};
 
 template <int D>
 struct WaveCtx {
@@ -258,32 +229,13 @@ __device__ __forceinline__ void patch_newest_v(const WaveCtx<D>& c, int32_t t0, 
     }
 }
 
-template <int D>
-struct WaveAcc {
-    f32x4_t o[D / 16];  // O^T tiles: lane (r, q) holds head r, head-dim 16nt + 4q + i
-    float m;            // running max of head r, log2 units
-    float l;            // this lane's share of the running sum of head r
-};
-
 // Scores of the step's 32 tokens for head r, in log2 units; the 8 a lane owns are tokens
-// t0 + 8q + j.  Tokens at or past `end` get -inf.  Consumes the K registers.
+// t0 + 8q + j.  Tokens at or past `end` get -inf.
 template <int D>
 __device__ __forceinline__ void score_step(const WaveCtx<D>& c, const bf16x8_t (&qf)[D / 32],
                                            const StepData<D>& s, int32_t t0, int32_t end,
                                            float scale_log2e, float (&sv)[8]) {
-    f32x4_t sc[2];
-#pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
-        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kk = 0; kk < D / 32; ++kk)
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(s.k[tt][kk]), qf[kk], acc, 0, 0, 0);
-        sc[tt] = acc;
-    }
-#pragma unroll
-    for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) sv[4 * tt + i] = sc[tt][i] * scale_log2e;
+    qk_scores<D>(qf, s, scale_log2e, sv);
     if (t0 + kStep > end) {  // ragged tail of the row
         const int32_t first = t0 + 8 * c.q;
 #pragma unroll
@@ -294,61 +246,12 @@ __device__ __forceinline__ void score_step(const WaveCtx<D>& c, const bf16x8_t (
 
 // Online softmax update with the step's scores and O^T += V^T P^T.  Consumes the V registers.
 // NEWEST: the step ends the row even when it is full (its newest token came from v_new).
+// The running max stays finite: every processed step has a valid token.
 template <int D, bool NEWEST>
 __device__ __forceinline__ void accumulate_step(const WaveCtx<D>& c, const float (&sv)[8], StepData<D>& s,
                                                 int32_t t0, int32_t end, WaveAcc<D>& a) {
-    if (NEWEST || t0 + kStep > end) {  // ragged tail: zero the V octets of tokens that do not exist
-        const int32_t nvalid = end - (t0 + 8 * c.q);
-#pragma unroll
-        for (int nt = 0; nt < D / 16; ++nt) {
-            uint32_t w[4] = {s.v[nt].x, s.v[nt].y, s.v[nt].z, s.v[nt].w};
-#pragma unroll
-            for (int k2 = 0; k2 < 4; ++k2) {
-                const uint32_t keep = (2 * k2 < nvalid ? 0x0000FFFFu : 0u) | (2 * k2 + 1 < nvalid ? 0xFFFF0000u : 0u);
-                w[k2] &= keep;
-            }
-            s.v[nt] = make_uint4(w[0], w[1], w[2], w[3]);
-        }
-    }
-
-    float mx = sv[0];
-#pragma unroll
-    for (int j = 1; j < 8; ++j) mx = fmaxf(mx, sv[j]);
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(a.m, mx);   // finite: every processed step has a valid token
-    const float alpha = __builtin_amdgcn_exp2f(a.m - m_new);
-    a.m = m_new;
-    float p[8];
-    float psum = 0.f;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        p[j] = __builtin_amdgcn_exp2f(sv[j] - m_new);
-        psum += p[j];
-    }
-    a.l = a.l * alpha + psum;
-
-    uint32_t hi[4], lo[4];
-#pragma unroll
-    for (int k2 = 0; k2 < 4; ++k2) {
-        hi[k2] = pack_bf16_rne(p[2 * k2], p[2 * k2 + 1]);
-        const float r0 = p[2 * k2] - __uint_as_float(hi[k2] << 16);
-        const float r1 = p[2 * k2 + 1] - __uint_as_float(hi[k2] & 0xFFFF0000u);
-        lo[k2] = pack_bf16_rne(r0, r1);
-    }
-    const bf16x8_t p_hi = as_bf16x8(make_uint4(hi[0], hi[1], hi[2], hi[3]));
-    const bf16x8_t p_lo = as_bf16x8(make_uint4(lo[0], lo[1], lo[2], lo[3]));
-
-    if (__any(alpha != 1.0f)) {
-#pragma unroll
-        for (int nt = 0; nt < D / 16; ++nt) a.o[nt] *= alpha;
-    }
-#pragma unroll
-    for (int nt = 0; nt < D / 16; ++nt) {
-        const bf16x8_t vf = as_bf16x8(s.v[nt]);
-        a.o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, p_hi, a.o[nt], 0, 0, 0);
-        a.o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, p_lo, a.o[nt], 0, 0, 0);
-    }
+    if (NEWEST || t0 + kStep > end) mask_v_tail<D>(s, end - (t0 + 8 * c.q));  // ragged tail
+    softmax_pv<D>(sv, s, a);
 }
 
 // Steps per row into LDS as an exclusive prefix, clamped lengths beside it.
@@ -388,25 +291,6 @@ __device__ void build_row_prefix(const int32_t* seq_lens, int32_t B, int32_t max
     }
     if (tid == 0) pre[B] = carry;
     __syncthreads();
-}
-
-// Write one head-dim quad row of a finished stream: normalise by the sum and store.
-template <int D>
-__device__ __forceinline__ void store_result(const WaveAcc<D>& a, void* __restrict__ out, int64_t idx,
-                                             int32_t out_f32) {
-    const float inv = 1.0f / a.l;
-#pragma unroll
-    for (int nt = 0; nt < D / 16; ++nt) {
-        const f32x4_t o = a.o[nt] * inv;
-        if (out_f32) {
-            *(f32x4_t*)((float*)out + idx + 16 * nt) = o;
-        } else {
-            uint2 pk;
-            pk.x = pack_bf16_rne(o[0], o[1]);
-            pk.y = pack_bf16_rne(o[2], o[3]);
-            *(uint2*)((__bf16*)out + idx + 16 * nt) = pk;
-        }
-    }
 }
 
 // Pieces travel between waves on different XCDs (each with its own L2) inside one kernel.

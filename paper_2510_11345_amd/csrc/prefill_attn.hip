@@ -1,0 +1,324 @@
+// Chunked prefill attention into pages for gfx950.
+//
+// ROLL Flash (arXiv 2510.11345) Section 4.2: a request that joins the running batch (ADD, or a
+// slot refilled by queue scheduling, Section 5.1.1) is prefilled before it is decoded step by
+// step.  A chunk is a run of consecutive prompt tokens of one slot.  The entry point first
+// writes the chunk tokens' K/V into the slot's pages (one small launch), then every chunk token
+// attends causally over its slot's tokens 0 .. its own position, read from the pages in the
+// two layouts the decode kernel streams.
+//
+// Unlike decoding this is a dense contraction: 16 query tokens of one head share every K/V
+// byte, and the G query heads of a KV head share it again.  One workgroup therefore takes
+// (chunk, block of 16 query tokens, KV head); wave g of it owns query head g of the group and
+// holds the 16 query tokens as the 16 columns of the MFMA tiles.  Each 32-token step of K and
+// V is copied once per workgroup from the pages into LDS, verbatim (the page layouts are
+// already the A-operand layouts: consecutive lanes read consecutive 16-byte pieces, so the LDS
+// reads are conflict free), double buffered with the global loads of the next step in flight
+// during the MFMAs of the current one.  The per-step arithmetic is the decode kernel's; only
+// the mask differs (column r sees tokens up to the position of query token r).
+#include <cmath>
+
+#include "attn_core.h"
+#include "common.h"
+#include "kv_layout.h"
+
+namespace {
+
+using namespace roll::attn;
+
+constexpr int kQBlock = 16;       // query tokens per workgroup = columns of an MFMA tile
+constexpr int kMinWaves = 4;      // workgroups have at least this many waves to copy K/V with
+constexpr int kCopies = 4;        // 16-byte pieces a thread copies per step at most
+
+struct PrefillParams {
+    int32_t C, T, Hq, Hkv, G;
+    int32_t log2P, max_pages, num_pages, num_slots;
+    int32_t out_f32;
+    float scale_log2e;
+};
+
+// The chunk that holds token t: the last c with chunk_offset[c] <= t.
+__device__ __forceinline__ int32_t chunk_of_token(const int32_t* __restrict__ chunk_offset, int32_t C, int32_t t) {
+    int32_t lo = 0, hi = C;
+    while (hi - lo > 1) {
+        const int32_t mid = (lo + hi) >> 1;
+        if (chunk_offset[mid] <= t) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// One thread per (token, KV head, 8 head-dim elements).  Tokens whose slot, position or page
+// is out of range are skipped.
+__global__ void append_chunks(const uint4* __restrict__ k_new, const uint4* __restrict__ v_new,
+                              const int32_t* __restrict__ chunk_slot, const int32_t* __restrict__ chunk_start,
+                              const int32_t* __restrict__ chunk_offset, uint4* __restrict__ k_pages,
+                              uint16_t* __restrict__ v_pages, const int32_t* __restrict__ page_table,
+                              PrefillParams prm, int32_t D) {
+    const int32_t d8n = D / 8, per_tok = prm.Hkv * d8n;
+    const int64_t item = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (item >= (int64_t)prm.T * per_tok) return;
+    const int32_t t = (int32_t)(item / per_tok), rem = (int32_t)(item - (int64_t)t * per_tok);
+    const int32_t c = chunk_of_token(chunk_offset, prm.C, t);
+    const int32_t slot = chunk_slot[c], pos = chunk_start[c] + (t - chunk_offset[c]);
+    const int32_t P = 1 << prm.log2P;
+    if (slot < 0 || slot >= prm.num_slots || pos < 0 || (pos >> prm.log2P) >= prm.max_pages) return;
+    const int32_t page = page_table[(int64_t)slot * prm.max_pages + (pos >> prm.log2P)];
+    if (page < 0 || page >= prm.num_pages) return;
+    roll::store_kv_slice(k_new[item], v_new[item], k_pages, v_pages, page, pos & (P - 1), rem / d8n, rem % d8n, P,
+                         prm.Hkv, D);
+}
+
+// The (up to) kCopies 16-byte pieces of a step's K and V tiles that one thread copies.
+// LDS tile (uint4 units): K [D/8][32 token slots of the step], then V [4 octets][D].
+template <int D>
+struct CopyPlan {
+    static constexpr int kTile = D * 8;   // uint4 per step: (D/8) * 32 + 4 * D
+};
+
+template <int D>
+__device__ __forceinline__ void fetch_step(uint4 (&reg)[kCopies], const uint4* __restrict__ k_pages,
+                                           const uint4* __restrict__ v_pages, const int32_t* __restrict__ pt_row,
+                                           int32_t h, int32_t t0, int32_t log2P, int32_t max_pages,
+                                           int32_t num_pages, int32_t Hkv) {
+    const int32_t P = 1 << log2P;
+    int32_t pa = t0 >> log2P, pb = (t0 + 16) >> log2P;
+    pb = pb > max_pages - 1 ? max_pages - 1 : pb;   // a second page past the row's end is masked later
+    int32_t pgA = pt_row[pa], pgB = pt_row[pb];
+    pgA = pgA < 0 ? 0 : (pgA >= num_pages ? num_pages - 1 : pgA);
+    pgB = pgB < 0 ? 0 : (pgB >= num_pages ? num_pages - 1 : pgB);
+#pragma unroll
+    for (int i = 0; i < kCopies; ++i) {
+        // a thread with nothing left to copy in this round re-reads the tile's last piece
+        const int32_t want = threadIdx.x + i * blockDim.x;
+        const int32_t idx = want < CopyPlan<D>::kTile ? want : CopyPlan<D>::kTile - 1;
+        const uint4* src;
+        if (idx < (D / 8) * 32) {
+            const int32_t d8 = idx >> 5, s32 = idx & 31;
+            const int32_t page = (P == 16 && s32 >= 16) ? pgB : pgA;
+            const int32_t slot = P == 16 ? (s32 & 15) : (t0 & (P - 1)) + s32;
+            src = k_pages + (((int64_t)page * Hkv + h) * (D / 8) + d8) * P + slot;
+        } else {
+            const int32_t j = idx - (D / 8) * 32, oct = j / D, d = j - oct * D;
+            const int32_t page = (P == 16 && oct >= 2) ? pgB : pgA;
+            const int32_t oct_in_page = ((t0 + 8 * oct) & (P - 1)) >> 3;
+            src = v_pages + (((int64_t)page * Hkv + h) * (P / 8) + oct_in_page) * D + d;
+        }
+        reg[i] = *src;
+    }
+}
+
+template <int D>
+__device__ __forceinline__ void stash_step(const uint4 (&reg)[kCopies], uint4* tile) {
+#pragma unroll
+    for (int i = 0; i < kCopies; ++i) {
+        const int32_t idx = threadIdx.x + i * blockDim.x;
+        if (idx < CopyPlan<D>::kTile) tile[idx] = reg[i];
+    }
+}
+
+// MAXW: most waves a workgroup of this instance may have (the register budget follows from it).
+template <int D, int MAXW>
+__global__ __launch_bounds__(64 * MAXW) void prefill_attn(
+    const uint4* __restrict__ q16, const uint4* __restrict__ k_pages, const uint4* __restrict__ v_pages,
+    const int32_t* __restrict__ page_table, const int32_t* __restrict__ chunk_slot,
+    const int32_t* __restrict__ chunk_start, const int32_t* __restrict__ chunk_offset,
+    void* __restrict__ out, PrefillParams prm) {
+    extern __shared__ uint4 tiles[];   // two step tiles
+    __shared__ int32_t s_chunk, s_qb, s_found;
+
+    // Which (chunk, query block) is this workgroup's?  Blocks are numbered chunk after chunk;
+    // the workgroups take them from the last one down, so that within a prompt the blocks
+    // with the longest prefixes start first.  Wave 0 counts the blocks of 64 chunks at a time.
+    const int32_t h = blockIdx.x % prm.Hkv;
+    const int32_t wanted_from_end = blockIdx.x / prm.Hkv;
+    const int32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (wave == 0) {
+        int32_t total = 0;
+        for (int32_t base = 0; base < prm.C; base += 64) {
+            const int32_t c = base + lane;
+            const int32_t n = c < prm.C ? chunk_offset[c + 1] - chunk_offset[c] : 0;
+            int32_t incl = (n + kQBlock - 1) / kQBlock;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int32_t v = __shfl_up(incl, d);
+                if (lane >= d) incl += v;
+            }
+            total += __shfl(incl, 63);
+        }
+        const int32_t wanted = total - 1 - wanted_from_end;
+        if (lane == 0) s_found = 0;
+        int32_t carry = 0;
+        for (int32_t base = 0; base < prm.C && wanted >= 0; base += 64) {
+            const int32_t c = base + lane;
+            const int32_t n = c < prm.C ? chunk_offset[c + 1] - chunk_offset[c] : 0;
+            const int32_t nb = (n + kQBlock - 1) / kQBlock;
+            int32_t incl = nb;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int32_t v = __shfl_up(incl, d);
+                if (lane >= d) incl += v;
+            }
+            const int32_t first = carry + incl - nb;
+            if (wanted >= first && wanted < first + nb) {
+                s_chunk = c;
+                s_qb = wanted - first;
+                s_found = 1;
+            }
+            carry += __shfl(incl, 63);
+        }
+    }
+    __syncthreads();
+    if (!s_found) return;
+    const int32_t c = s_chunk, qb = s_qb;
+
+    const int32_t slot = chunk_slot[c];
+    const int32_t n_c = chunk_offset[c + 1] - chunk_offset[c];
+    const int32_t tq0 = chunk_offset[c] + kQBlock * qb;       // first query token of the block
+    const int32_t pos0 = chunk_start[c] + kQBlock * qb;       // its position in the slot
+    const int32_t nq = min(kQBlock, n_c - kQBlock * qb);      // query tokens in the block
+    if (slot < 0 || slot >= prm.num_slots || pos0 < 0) return;
+    int32_t kv_end = pos0 + nq;                               // tokens the last query sees
+    const int32_t cap = prm.max_pages << prm.log2P;
+    kv_end = kv_end > cap ? cap : kv_end;
+    const int32_t n_steps = (kv_end + kStep - 1) / kStep;
+    const int32_t* pt_row = page_table + (int64_t)slot * prm.max_pages;
+    const int32_t P = 1 << prm.log2P;
+
+    const int32_t r = lane & 15, q = lane >> 4;
+    const bool computes = wave < prm.G;                       // the other waves only copy
+    const int32_t col = r < nq ? r : nq - 1;                  // padding columns shadow the last query
+    const int32_t pq = pos0 + col;                            // newest position column r sees
+    bf16x8_t qf[D / 32];
+    WaveAcc<D> acc;
+    if (computes) {
+        const uint4* qrow = q16 + ((int64_t)(tq0 + col) * prm.Hq + (int64_t)h * prm.G + wave) * (D / 8) + q;
+#pragma unroll
+        for (int kk = 0; kk < D / 32; ++kk) qf[kk] = as_bf16x8(qrow[kk * 4]);
+    }
+#pragma unroll
+    for (int nt = 0; nt < D / 16; ++nt) acc.o[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    acc.m = -INFINITY;
+    acc.l = 0.f;
+
+    uint4 cp[kCopies];
+    fetch_step<D>(cp, k_pages, v_pages, pt_row, h, 0, prm.log2P, prm.max_pages, prm.num_pages, prm.Hkv);
+    stash_step<D>(cp, tiles);
+    __syncthreads();
+    for (int32_t s = 0; s < n_steps; ++s) {
+        const int32_t t0 = s * kStep;
+        const bool more = s + 1 < n_steps;
+        // (the last step fetches itself again rather than branching around the loads)
+        fetch_step<D>(cp, k_pages, v_pages, pt_row, h, more ? t0 + kStep : t0, prm.log2P, prm.max_pages, prm.num_pages, prm.Hkv);
+        if (computes) {
+            const uint4* kt = tiles + (s & 1) * CopyPlan<D>::kTile;
+            const uint4* vt = kt + (D / 8) * 32;
+            StepData<D> sd;
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt) {
+                const int32_t s32 = P == 16 ? 16 * (r >> 3) + (r & 7) + 8 * tt : r + 16 * tt;
+#pragma unroll
+                for (int kk = 0; kk < D / 32; ++kk) sd.k[tt][kk] = kt[(4 * kk + q) * 32 + s32];
+            }
+#pragma unroll
+            for (int nt = 0; nt < D / 16; ++nt) sd.v[nt] = vt[q * D + 16 * nt + r];
+            float sv[8];
+            qk_scores<D>(qf, sd, prm.scale_log2e, sv);
+            if (t0 + kStep - 1 > pos0) {   // the step reaches past the first query's position: causal mask
+                const int32_t first = t0 + 8 * q;
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (first + j > pq) sv[j] = -INFINITY;
+            }
+            if (t0 + kStep > kv_end) mask_v_tail<D>(sd, kv_end - (t0 + 8 * q));
+            softmax_pv<D>(sv, sd, acc);   // token 0 is visible to every column, so the max is finite
+        }
+        if (more) stash_step<D>(cp, tiles + ((s + 1) & 1) * CopyPlan<D>::kTile);
+        __syncthreads();
+    }
+
+    if (!computes) return;
+    acc.l += __shfl_xor(acc.l, 16);
+    acc.l += __shfl_xor(acc.l, 32);
+    if (r < nq) {
+        const int64_t idx = ((int64_t)(tq0 + r) * prm.Hq + (int64_t)h * prm.G + wave) * D + 4 * q;
+        store_result<D>(acc, out, idx, prm.out_f32);
+    }
+}
+
+int validate(const roll_prefill_desc* d) {
+    if (!d) return roll::fail(ROLL_ERR_INVALID_ARG, "desc is NULL");
+    if (d->num_chunks < 0 || d->num_tokens < 0) return roll::fail(ROLL_ERR_INVALID_ARG, "num_chunks and num_tokens must be >= 0");
+    if (d->num_q_heads <= 0 || d->num_kv_heads <= 0 || d->num_q_heads % d->num_kv_heads != 0)
+        return roll::fail(ROLL_ERR_INVALID_ARG, "num_q_heads must be a positive multiple of num_kv_heads");
+    if (d->num_q_heads / d->num_kv_heads > 16)
+        return roll::fail(ROLL_ERR_INVALID_ARG, "GQA group size above 16 is not supported");
+    if (d->head_dim != 64 && d->head_dim != 128) return roll::fail(ROLL_ERR_INVALID_ARG, "head_dim must be 64 or 128");
+    if (d->page_size != 16 && d->page_size != 32 && d->page_size != 64)
+        return roll::fail(ROLL_ERR_INVALID_ARG, "page_size must be 16, 32 or 64");
+    if (d->max_pages_per_seq <= 0 || d->num_pages <= 0 || d->num_slots <= 0)
+        return roll::fail(ROLL_ERR_INVALID_ARG, "max_pages_per_seq, num_pages and num_slots must be > 0");
+    if ((int64_t)d->max_pages_per_seq * d->page_size > (1 << 24))
+        return roll::fail(ROLL_ERR_INVALID_ARG, "max_pages_per_seq * page_size above 2^24 tokens");
+    if ((int64_t)d->num_pages * d->page_size > INT32_MAX) return roll::fail(ROLL_ERR_INVALID_ARG, "pool above 2^31 tokens");
+    if ((int64_t)d->num_tokens * d->num_q_heads * d->head_dim > ((int64_t)1 << 40))
+        return roll::fail(ROLL_ERR_INVALID_ARG, "num_tokens too large");
+    if (d->out_dtype != ROLL_BF16 && d->out_dtype != ROLL_F32) return roll::fail(ROLL_ERR_INVALID_ARG, "out_dtype must be ROLL_BF16 or ROLL_F32");
+    if (!(d->softmax_scale >= 0.f) || std::isinf(d->softmax_scale)) return roll::fail(ROLL_ERR_INVALID_ARG, "softmax_scale must be finite and >= 0");
+    return ROLL_OK;
+}
+
+}  // namespace
+
+extern "C" int roll_prefill_attn(const void* q, const void* k_new, const void* v_new, const int32_t* chunk_slot,
+                                 const int32_t* chunk_start, const int32_t* chunk_offset, void* k_pages,
+                                 void* v_pages, const int32_t* page_table, void* out, const roll_prefill_desc* d,
+                                 void* stream_v) {
+    int rc = validate(d);
+    if (rc != ROLL_OK) return rc;
+    if (d->num_chunks == 0 || d->num_tokens == 0) return ROLL_OK;
+    if (!q || !k_new || !v_new || !chunk_slot || !chunk_start || !chunk_offset || !k_pages || !v_pages || !page_table || !out)
+        return roll::fail(ROLL_ERR_INVALID_ARG, "NULL pointer argument");
+    if (!roll::aligned(q, 16) || !roll::aligned(k_new, 16) || !roll::aligned(v_new, 16) || !roll::aligned(k_pages, 16) ||
+        !roll::aligned(v_pages, 16) || !roll::aligned(out, 16))
+        return roll::fail(ROLL_ERR_INVALID_ARG, "q, k_new, v_new, k_pages, v_pages, out must be 16-byte aligned");
+    hipStream_t stream = (hipStream_t)stream_v;
+    PrefillParams prm{};
+    prm.C = d->num_chunks;
+    prm.T = d->num_tokens;
+    prm.Hq = d->num_q_heads;
+    prm.Hkv = d->num_kv_heads;
+    prm.G = d->num_q_heads / d->num_kv_heads;
+    prm.log2P = d->page_size == 16 ? 4 : (d->page_size == 32 ? 5 : 6);
+    prm.max_pages = d->max_pages_per_seq;
+    prm.num_pages = d->num_pages;
+    prm.num_slots = d->num_slots;
+    prm.out_f32 = d->out_dtype == ROLL_F32;
+    const float scale = d->softmax_scale > 0.f ? d->softmax_scale : 1.0f / sqrtf((float)d->head_dim);
+    prm.scale_log2e = scale * 1.44269504088896340736f;
+
+    const int64_t items = (int64_t)prm.T * prm.Hkv * (d->head_dim / 8);
+    append_chunks<<<(unsigned)((items + 255) / 256), 256, 0, stream>>>(
+        (const uint4*)k_new, (const uint4*)v_new, chunk_slot, chunk_start, chunk_offset, (uint4*)k_pages,
+        (uint16_t*)v_pages, page_table, prm, d->head_dim);
+    ROLL_HIP_CHECK(hipGetLastError());
+
+    // At most ceil(T / 16) + C query blocks (each chunk ends with at most one partial block).
+    const int64_t blocks_bound = ((int64_t)prm.T + kQBlock - 1) / kQBlock + prm.C;
+    const int64_t grid = blocks_bound * prm.Hkv;
+    if (grid > INT32_MAX) return roll::fail(ROLL_ERR_INVALID_ARG, "too many query blocks");
+    const int threads = 64 * (prm.G > kMinWaves ? prm.G : kMinWaves);
+#define ROLL_LAUNCH_PREFILL(DIM, MAXW)                                                                        \
+    prefill_attn<DIM, MAXW><<<(unsigned)grid, threads, 2 * sizeof(uint4) * CopyPlan<DIM>::kTile, stream>>>(     \
+        (const uint4*)q, (const uint4*)k_pages, (const uint4*)v_pages, page_table, chunk_slot, chunk_start,    \
+        chunk_offset, out, prm)
+    if (d->head_dim == 128) {
+        if (prm.G <= 8) ROLL_LAUNCH_PREFILL(128, 8);
+        else ROLL_LAUNCH_PREFILL(128, 16);
+    } else {
+        if (prm.G <= 8) ROLL_LAUNCH_PREFILL(64, 8);
+        else ROLL_LAUNCH_PREFILL(64, 16);
+    }
+#undef ROLL_LAUNCH_PREFILL
+    ROLL_HIP_CHECK(hipGetLastError());
+    return ROLL_OK;
+}
