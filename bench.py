@@ -78,6 +78,77 @@ def policy_loss_bench(args, torch, rb, wl):
                       "per_objective": res}), flush=True)
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix-core peak
+
+
+def prefill_bench(args, torch, rb, wl):
+    """Tokens/s of roll_prefill_attn on prompts with the 7B-class head shape of c2 / c4.  Two
+    workloads: the refill queue's prompt lengths (128..1024, 64 prompts in one call) and long
+    prompts (8 x 8192, prefilled in chunks of 2048).  Matrix-core roofline on the algorithmic
+    flops of causal attention: 4 D Hq per (query, visible key) pair."""
+    import numpy as np
+    cfg = wl.CONFIGS["c2"]
+    Hq, Hkv, D, P = cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.page_size
+    rng = np.random.default_rng([args.seed, 0x505245])
+    res = {}
+    for name, lens, chunk in [("refill_prompts_64x128..1024", rng.integers(128, 1025, size=64), None),
+                              ("long_prompts_8x8192_chunks_of_2048", np.full(8, 8192), 2048)]:
+        n_slots, cap = len(lens), int(lens.max())
+        max_pages = (cap + P - 1) // P
+        num_pages = n_slots * max_pages + 8
+        page_table = torch.empty((n_slots, max_pages), dtype=torch.int32, device="cuda")
+        seq_lens = torch.zeros((n_slots,), dtype=torch.int32, device="cuda")
+        pool = rb.KvPool(num_pages, P, n_slots, max_pages, page_table, seq_lens)
+        for s_, n in enumerate(lens):
+            rb.roll_kv_alloc(pool, s_, int(n))
+        rb.roll_kv_commit(pool)
+        k_pages = torch.zeros((num_pages, Hkv, D // 8, P, 8), dtype=torch.bfloat16, device="cuda")
+        v_pages = torch.zeros((num_pages, Hkv, P // 8, D, 8), dtype=torch.bfloat16, device="cuda")
+        # calls: one per chunk round; every call holds one chunk per prompt that still has tokens
+        calls = []
+        step = int(lens.max()) if chunk is None else chunk
+        for start in range(0, int(lens.max()), step):
+            ch = [(s_, start, int(min(step, n - start))) for s_, n in enumerate(lens) if n > start]
+            T = sum(c[2] for c in ch)
+            off = np.concatenate([[0], np.cumsum([c[2] for c in ch])]).astype(np.int32)
+            calls.append(dict(
+                q=wl.randn_bf16((T, Hq, D), args.seed, 40 + start, "cuda"),
+                k=wl.randn_bf16((T, Hkv, D), args.seed, 41 + start, "cuda"),
+                v=wl.randn_bf16((T, Hkv, D), args.seed, 42 + start, "cuda"),
+                slot=torch.tensor([c[0] for c in ch], dtype=torch.int32, device="cuda"),
+                start=torch.tensor([c[1] for c in ch], dtype=torch.int32, device="cuda"),
+                off=torch.from_numpy(off).cuda(),
+                out=torch.empty((T, Hq, D), dtype=torch.bfloat16, device="cuda"),
+                pairs=sum(n * st + n * (n + 1) // 2 for _, st, n in ch), T=T))
+        run = lambda: [rb.roll_prefill_attn(c["q"], c["k"], c["v"], c["slot"], c["start"], c["off"], k_pages, v_pages,
+                                            page_table, c["out"], P) for c in calls]
+        for _ in range(args.warmup):
+            run()
+        e0, e1 = rb.ProfEvent(), rb.ProfEvent()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_ms(e1) / args.steps
+        tokens, pairs = sum(c["T"] for c in calls), sum(c["pairs"] for c in calls)
+        flops = 4.0 * D * Hq * pairs
+        res[name] = {"ms": ms, "tokens": tokens, "launch_pairs": len(calls), "tokens_per_s": tokens / (ms * 1e-3),
+                     "TFLOPs": flops / (ms * 1e-3) / 1e12}
+        pool.close()
+    head = res["long_prompts_8x8192_chunks_of_2048"]
+    print(json.dumps({"metric": "prefill tokens/s (one attention layer, K/V written into pages)",
+                      "value": head["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+                      "warmup": args.warmup, "ms_per_step": head["ms"], "higher_is_better": True,
+                      "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": f"8 prompts x 8192 tokens in chunks of 2048, Hq={Hq} Hkv={Hkv} D={D} P={P}"},
+                      "roofline": {"bound": "mfma", "kernel": "prefill_attn", "achieved": head["TFLOPs"],
+                                   "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                   "frac": head["TFLOPs"] / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+                      "per_workload": res}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -90,6 +161,8 @@ def main():
     ap.add_argument("--oracle-rows", type=int, default=0, help="rows timed on the CPU oracle (0 = the whole batch)")
     ap.add_argument("--policy-loss", action="store_true",
                     help="measure roll_policy_loss (the consumer of logprob_out) instead of the decode step")
+    ap.add_argument("--prefill", action="store_true",
+                    help="measure roll_prefill_attn (chunked prefill into pages) instead of the decode step")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="only run one plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -119,6 +192,9 @@ def main():
         return
     if args.policy_loss:
         policy_loss_bench(args, torch, rb, wl)
+        return
+    if args.prefill:
+        prefill_bench(args, torch, rb, wl)
         return
     cfg = wl.CONFIGS[args.config]
     K, W = args.steps, args.warmup
@@ -156,7 +232,7 @@ def main():
     if cfg.name == "c4":
         extra = {"refills_in_timed_steps": loop.refills - refills_before,
                  "free_pages_at_end": rb.roll_kv_free_pages(batch.pool),
-                 "note": "refill (release, alloc, prompt K/V write) is inside the timed steps"}
+                 "note": "refill (release, alloc, chunked prefill of the new prompts into pages) is inside the timed steps"}
 
     ms_per_step = (t1 - t0) * 1e3 / K
     beta = cfg.kv_bytes_per_token

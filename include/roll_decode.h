@@ -341,13 +341,18 @@ typedef struct roll_sample_desc {
     int32_t vocab;          /* V */
     int64_t row_stride;     /* elements between rows of logits (>= V) */
     int32_t logits_dtype;   /* ROLL_BF16 or ROLL_F32 */
-    int32_t reserved;
+    int32_t policy_version; /* version n of the weights that produced these logits */
     const int32_t* row_ids; /* DEVICE int32 [B] Philox row ids, or NULL for 0..B-1 */
     float* raw_logprob_out; /* DEVICE fp32 [B] or NULL: log_softmax(logits)[token] at temperature 1
                              * with no truncation, for the token that was drawn.  Appendix A.1 forces
                              * temperature 1 and top_p 1 because an engine returns one distribution
                              * only; with both values recorded any sampling setting keeps the raw
                              * probability available to the trainer. */
+    int32_t* policy_version_out; /* DEVICE int32 [B] or NULL: policy_version, written beside every
+                             * log-prob.  A trajectory that was aborted and resumed (Section 4.2) holds
+                             * tokens of several policy versions; the per-token tag tells the trainer
+                             * which pi_old each recorded log-prob belongs to, and the oldest tag of a
+                             * sample is what the asynchronous-ratio freshness rule bounds. */
 } roll_sample_desc;
 
 size_t roll_sample_logprob_workspace_bytes(const roll_sample_desc* desc);

@@ -73,8 +73,8 @@ class PrefillDesc(C.Structure):
 
 class SampleDesc(C.Structure):
     _fields_ = [("batch", C.c_int32), ("vocab", C.c_int32), ("row_stride", C.c_int64),
-                ("logits_dtype", C.c_int32), ("reserved", C.c_int32), ("row_ids", C.c_void_p),
-                ("raw_logprob_out", C.c_void_p)]
+                ("logits_dtype", C.c_int32), ("policy_version", C.c_int32), ("row_ids", C.c_void_p),
+                ("raw_logprob_out", C.c_void_p), ("policy_version_out", C.c_void_p)]
 
 
 _lib = None
@@ -325,15 +325,16 @@ def roll_prefill_attn(q, k_new, v_new, chunk_slot, chunk_start, chunk_offset, k_
 # ----------------------------------------------------------------------------
 # sampling
 # ----------------------------------------------------------------------------
-def sample_desc(logits, row_ids=None, raw_logprob_out=None) -> SampleDesc:
+def sample_desc(logits, row_ids=None, raw_logprob_out=None, policy_version: int = 0,
+                policy_version_out=None) -> SampleDesc:
     B, V = logits.shape
     dt = ROLL_BF16 if logits.dtype == torch.bfloat16 else ROLL_F32
     if logits.dtype not in (torch.bfloat16, torch.float32):
         raise ValueError("logits must be bf16 or fp32")
     if logits.stride(1) != 1:
         raise ValueError("logits rows must be dense")
-    return SampleDesc(B, V, logits.stride(0), dt, 0, _dev(row_ids, torch.int32),
-                      _dev(raw_logprob_out, torch.float32))
+    return SampleDesc(B, V, logits.stride(0), dt, policy_version, _dev(row_ids, torch.int32),
+                      _dev(raw_logprob_out, torch.float32), _dev(policy_version_out, torch.int32))
 
 
 def roll_sample_logprob_workspace_bytes(desc: SampleDesc) -> int:

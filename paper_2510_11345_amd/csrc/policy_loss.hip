@@ -19,7 +19,8 @@
 
 namespace {
 
-constexpr int kLossThreads = 256;
+constexpr int kLossThreads = 1024;
+constexpr int kUnroll = 4;        // tokens per thread and round
 
 struct LossParams {
     int32_t kind;
@@ -57,14 +58,31 @@ __global__ __launch_bounds__(kLossThreads) void policy_loss_rows(
     const int32_t s = blockIdx.x;
     const int64_t begin = offsets[s], end = offsets[s + 1];
     double acc = 0.0;
-    for (int64_t i = begin + threadIdx.x; i < end; i += kLossThreads) {
-        double v, g, w;
-        const double lold = (double)lo[i];
-        loss_token(p, (double)lt[i], lold, lp ? (double)lp[i] : lold, (double)R[i], v, g, w);
-        if (value) value[i] = (float)v;
-        if (grad) grad[i] = (float)g;
-        if (is_weight) is_weight[i] = (float)w;
-        acc += v;
+    // kUnroll tokens per thread and round, all loads of a round issued before the arithmetic:
+    // the longest response of a long-tailed batch is one workgroup's work, so its time is set
+    // by how many bytes that workgroup keeps in flight.
+    for (int64_t base = begin + threadIdx.x; base < end; base += (int64_t)kLossThreads * kUnroll) {
+        float a_t[kUnroll], a_o[kUnroll], a_p[kUnroll], a_r[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t i = base + (int64_t)u * kLossThreads;
+            const bool in = i < end;
+            a_t[u] = in ? lt[i] : 0.f;
+            a_o[u] = in ? lo[i] : 0.f;
+            a_p[u] = in && lp ? lp[i] : a_o[u];
+            a_r[u] = in ? R[i] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t i = base + (int64_t)u * kLossThreads;
+            if (i >= end) continue;
+            double v, g, w;
+            loss_token(p, (double)a_t[u], (double)a_o[u], (double)a_p[u], (double)a_r[u], v, g, w);
+            if (value) value[i] = (float)v;
+            if (grad) grad[i] = (float)g;
+            if (is_weight) is_weight[i] = (float)w;
+            acc += v;
+        }
     }
     s_part[threadIdx.x] = acc;
     __syncthreads();

@@ -49,6 +49,8 @@ struct SampleParams {
     double temperature;
     float top_p;
     uint32_t seed_lo, seed_hi, step_lo, step_hi;
+    int32_t policy_version;
+    int32_t* policy_version_out;  // [B] or NULL: the version tag recorded beside every log-prob
 };
 
 // ---- Philox4x32-10 (Salmon et al., SC'11) ----------------------------------
@@ -461,6 +463,7 @@ __global__ __launch_bounds__(kThreads) void sample_rows(const T* __restrict__ lo
         if (tid == 0) {
             for (int w = 1; w < kWavesPerBlock; ++w)
                 if (s_best[w] > b || (s_best[w] == b && s_besti[w] < bi)) { b = s_best[w]; bi = s_besti[w]; }
+            if (p.policy_version_out) p.policy_version_out[r] = p.policy_version;
             if ((uint32_t)bi >= (uint32_t)p.V) {  // no finite entry in the row
                 tokens_out[r] = 0;
                 logprob_out[r] = NAN;
@@ -517,6 +520,8 @@ extern "C" int roll_sample_logprob(const void* logits, float temperature, float 
     p.seed_hi = (uint32_t)(philox_seed >> 32);
     p.step_lo = (uint32_t)step;
     p.step_hi = (uint32_t)(step >> 32);
+    p.policy_version = d->policy_version;
+    p.policy_version_out = d->policy_version_out;
     const bool topp = top_p < 1.0f;
     float* raw = d->raw_logprob_out;
     const bool raw_sum = raw != nullptr && (topp || temperature != 1.0f);

@@ -133,12 +133,19 @@ class DecodeBatch:
 class RefillLoop:
     """Queue-scheduled continuous refill on top of a DecodeBatch: every slot holds a request with
     a pre-drawn target length; a slot whose request has finished is released and at once given
-    the next prompt of the queue, whose K/V (synthetic, seeded by the request id) is written into
-    freshly allocated pages; then every slot decodes one token."""
+    the next prompt of the queue, which is prefilled into freshly allocated pages (all prompts
+    of a tick in one roll_prefill_attn call; with prefill=False only their K/V is written);
+    then every slot decodes one token.  Prompt Q/K/V are slices of a seeded random bank."""
 
     def __init__(self, cfg: wl.DecodeConfig, plan: wl.RefillPlan, seed: int, max_len: int,
-                 out_dtype=torch.bfloat16, device: str = "cuda"):
+                 out_dtype=torch.bfloat16, device: str = "cuda", prefill: bool = True):
         self.cfg, self.plan, self.seed, self.device = cfg, plan, seed, device
+        self.prefill = prefill
+        self.bank_tokens = int(plan.prompt_len.max()) + 4096
+        self.bank_q = wl.randn_bf16((self.bank_tokens, cfg.num_q_heads, cfg.head_dim), seed, 1000, device)
+        self.bank_k = wl.randn_bf16((self.bank_tokens, cfg.num_kv_heads, cfg.head_dim), seed, 1001, device)
+        self.bank_v = wl.randn_bf16((self.bank_tokens, cfg.num_kv_heads, cfg.head_dim), seed, 1002, device)
+        self.last_prefill = None   # (q, out, [(slot, n, first token)]) of the latest tick with refills
         B = cfg.batch
         self.request = np.arange(B, dtype=np.int64)          # request id held by each slot
         self.generated = plan.start_generated[:B].astype(np.int64).copy()
@@ -151,11 +158,10 @@ class RefillLoop:
         self.refills = 0
         self.refill_log = []  # (step, slot, request)
 
-    def _prompt_kv(self, request: int, n: int):
-        cfg = self.cfg
-        k = wl.randn_bf16((n, cfg.num_kv_heads, cfg.head_dim), self.seed, 1000 + 2 * request, self.device)
-        v = wl.randn_bf16((n, cfg.num_kv_heads, cfg.head_dim), self.seed, 1001 + 2 * request, self.device)
-        return k, v
+    def _prompt(self, request: int, n: int):
+        """Q, K, V of a request's prompt: n consecutive tokens of the bank."""
+        o = (request * 977) % (self.bank_tokens - n)
+        return self.bank_q[o:o + n], self.bank_k[o:o + n], self.bank_v[o:o + n]
 
     def step(self, logits: torch.Tensor, step_index: int) -> list:
         """One scheduler tick + one decode step.  Returns the slots refilled at this step."""
@@ -175,12 +181,24 @@ class RefillLoop:
             refilled.append((int(slot), req, n))
         if refilled:
             rb.roll_kv_commit(b.pool)   # the prompt writer looks its pages up on the device
-            for slot, req, n in refilled:
-                k, v = self._prompt_kv(req, n)
-                slots = torch.full((n,), slot, dtype=torch.int32, device=self.device)
-                pos = torch.arange(n, dtype=torch.int32, device=self.device)
+            parts = [self._prompt(req, n) for _, req, n in refilled]
+            q, k, v = (torch.cat([p[i] for p in parts]) for i in range(3))
+            lens = [n for _, _, n in refilled]
+            first = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+            if self.prefill:
+                out = torch.empty((q.shape[0], cfg.num_q_heads, cfg.head_dim), dtype=b.out_dtype, device=self.device)
+                # through pinned memory, so that the copy is asynchronous and the host keeps running ahead
+                meta = torch.tensor([[r[0] for r in refilled] + [0], [0] * (len(refilled) + 1), first.tolist()],
+                                    dtype=torch.int32).pin_memory().to(self.device, non_blocking=True)
+                rb.roll_prefill_attn(q, k, v, meta[0, :-1], meta[1, :-1], meta[2], b.k_pages, b.v_pages,
+                                     b.page_table, out, cfg.page_size)
+                self.last_prefill = (q, out, [(r[0], r[2], int(f)) for r, f in zip(refilled, first)])
+            else:
+                slots = torch.from_numpy(np.repeat([r[0] for r in refilled], lens).astype(np.int32)).pin_memory().to(self.device, non_blocking=True)
+                pos = torch.from_numpy(np.concatenate([np.arange(n) for n in lens]).astype(np.int32)).pin_memory().to(self.device, non_blocking=True)
                 rb.roll_kv_append_tokens(k, v, slots, pos, None, b.k_pages, b.v_pages, b.page_table,
                                          cfg.page_size)
+            for slot, req, _ in refilled:
                 self.refill_log.append((step_index, slot, req))
             self.refills += len(refilled)
         b.step(logits, step_index)      # +1 token per slot, commit + append, attention, sampling

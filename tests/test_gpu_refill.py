@@ -26,7 +26,7 @@ def test_refill_loop_reduced():
     loop = RefillLoop(cfg, plan, seed=3, max_len=90 + 400 + steps + 2, out_dtype=torch.float32)
     b = loop.batch
     total_pages = b.num_pages
-    attn_checked = 0
+    attn_checked = prefill_checked = 0
     for step in range(steps):
         logits = wl.make_logits(cfg, 3, "cuda", salt=100 + step)
         refilled = loop.step(logits, step)
@@ -42,6 +42,19 @@ def test_refill_loop_reduced():
         assert not bad, (step, bad)
         same = tok == ref["tokens"]
         assert np.abs(lp - ref["logprob"])[same].max() <= 1e-3
+        # the prefill of the refilled prompts: its output for the last prompt token is a decode
+        # step over the prompt (the pages are read back after the step; the token appended by
+        # the step lies beyond the prompt's length)
+        if refilled:
+            qp, outp, meta = loop.last_prefill
+            assert [m[0] for m in meta] == refilled
+            _, kq, vq, tq, _ = b.gather_rows(refilled)
+            last = [m[2] + m[1] - 1 for m in meta]
+            want_p = oracle.decode_attn(wl.bits(qp[last]), kq, vq, tq, np.array([m[1] for m in meta], np.int32),
+                                        cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.page_size)
+            err_p = np.abs(outp[last].double().cpu().numpy() - want_p).max()
+            assert err_p <= 1e-4, (step, err_p)
+            prefill_checked += len(refilled)
         # attention parity on the first and last step, every 8th, and right after a refill
         if step in (0, steps - 1) or step % 8 == 0 or refilled:
             rows = list(range(cfg.batch))
@@ -52,7 +65,7 @@ def test_refill_loop_reduced():
             assert err <= 1e-4, (step, err)
             attn_checked += 1
     say(f"  refill loop: {steps} steps, {loop.refills} refills, attention checked on {attn_checked} steps, "
-        f"free pages at the end {rb.roll_kv_free_pages(b.pool)}")
+        f"free pages at the end {rb.roll_kv_free_pages(b.pool)}, prefills checked {prefill_checked}")
     assert loop.refills >= 10
     loop.close()
 

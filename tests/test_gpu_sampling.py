@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 import torch
 
+from paper_2510_11345_amd import binding as rb
 from paper_2510_11345_amd import workloads as wl
 from gpu_helpers import compare_sampling, run_sample, say
 
@@ -85,3 +86,24 @@ def test_many_steps_small_vocab_all_tokens_match():
         t, _ = compare_sampling(lg, 0.9, 0.95, seed=99, step=step)
         ties += t
     assert ties <= 2
+
+
+def test_policy_version_tag_is_recorded_beside_the_logprob():
+    # a trajectory that is generated under version 3, aborted, and resumed under version 5
+    # carries both tags token by token; tokens and log-probs do not depend on the tag output
+    cfg = dataclasses.replace(wl.CONFIGS["c1"], batch=6, vocab=5000)
+    logits = wl.make_logits(cfg, 9, "cuda")
+    steps, B = 4, cfg.batch
+    tags = torch.full((steps, B), -1, dtype=torch.int32, device="cuda")
+    toks = torch.zeros((steps, B), dtype=torch.int32, device="cuda")
+    lps = torch.zeros((steps, B), dtype=torch.float32, device="cuda")
+    for step in range(steps):
+        version = 3 if step < 2 else 5
+        desc = rb.sample_desc(logits, policy_version=version, policy_version_out=tags[step])
+        rb.roll_sample_logprob(logits, 1.0, 1.0, 9, step, toks[step], lps[step], desc, None)
+    torch.cuda.synchronize()
+    assert tags.cpu().tolist() == [[3] * B, [3] * B, [5] * B, [5] * B]
+    for step in range(steps):
+        t, lp = run_sample(logits, 1.0, 1.0, 9, step)
+        assert np.array_equal(t, toks[step].cpu().numpy())
+        assert np.array_equal(lp, lps[step].double().cpu().numpy())
