@@ -91,8 +91,9 @@ __device__ __forceinline__ void mask_v_tail(StepData<D>& s, int32_t nvalid) {
 }
 
 // Online softmax update with the step's scores (-inf = masked; the running max must be finite
-// afterwards) and O^T += V^T P^T.
-template <int D>
+// afterwards) and O^T += V^T P^T.  SPLIT: P as a bf16 high part plus a bf16 remainder (two
+// MFMAs per tile); without it P is rounded to bf16 once, which is enough for a bf16 result.
+template <int D, bool SPLIT = true>
 __device__ __forceinline__ void softmax_pv(const float (&sv)[8], const StepData<D>& s, WaveAcc<D>& a) {
     float mx = sv[0];
 #pragma unroll
@@ -115,9 +116,13 @@ __device__ __forceinline__ void softmax_pv(const float (&sv)[8], const StepData<
 #pragma unroll
     for (int k2 = 0; k2 < 4; ++k2) {
         hi[k2] = pack_bf16_rne(p[2 * k2], p[2 * k2 + 1]);
-        const float r0 = p[2 * k2] - __uint_as_float(hi[k2] << 16);
-        const float r1 = p[2 * k2 + 1] - __uint_as_float(hi[k2] & 0xFFFF0000u);
-        lo[k2] = pack_bf16_rne(r0, r1);
+        if (SPLIT) {
+            const float r0 = p[2 * k2] - __uint_as_float(hi[k2] << 16);
+            const float r1 = p[2 * k2 + 1] - __uint_as_float(hi[k2] & 0xFFFF0000u);
+            lo[k2] = pack_bf16_rne(r0, r1);
+        } else {
+            lo[k2] = 0u;
+        }
     }
     const bf16x8_t p_hi = as_bf16x8(make_uint4(hi[0], hi[1], hi[2], hi[3]));
     const bf16x8_t p_lo = as_bf16x8(make_uint4(lo[0], lo[1], lo[2], lo[3]));
@@ -130,7 +135,7 @@ __device__ __forceinline__ void softmax_pv(const float (&sv)[8], const StepData<
     for (int nt = 0; nt < D / 16; ++nt) {
         const bf16x8_t vf = as_bf16x8(s.v[nt]);
         a.o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, p_hi, a.o[nt], 0, 0, 0);
-        a.o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, p_lo, a.o[nt], 0, 0, 0);
+        if (SPLIT) a.o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, p_lo, a.o[nt], 0, 0, 0);
     }
 }
 

@@ -7,10 +7,10 @@
 // attends causally over its slot's tokens 0 .. its own position, read from the pages in the
 // two layouts the decode kernel streams.
 //
-// Unlike decoding this is a dense contraction: 16 query tokens of one head share every K/V
+// Unlike decoding this is a dense contraction: the query tokens of one head share every K/V
 // byte, and the G query heads of a KV head share it again.  One workgroup therefore takes
-// (chunk, block of 16 query tokens, KV head); wave g of it owns query head g of the group and
-// holds the 16 query tokens as the 16 columns of the MFMA tiles.  Each 32-token step of K and
+// (chunk, block of 32 query tokens, KV head); wave g of it owns query head g of the group and
+// holds the query tokens as the columns of two MFMA tiles.  Each 32-token step of K and
 // V is copied once per workgroup from the pages into LDS, verbatim (the page layouts are
 // already the A-operand layouts: consecutive lanes read consecutive 16-byte pieces, so the LDS
 // reads are conflict free), double buffered with the global loads of the next step in flight
@@ -26,7 +26,7 @@ namespace {
 
 using namespace roll::attn;
 
-constexpr int kQBlock = 16;       // query tokens per workgroup = columns of an MFMA tile
+constexpr int kTile = 16;         // query tokens per MFMA column tile
 constexpr int kMinWaves = 4;      // workgroups have at least this many waves to copy K/V with
 constexpr int kCopies = 4;        // 16-byte pieces a thread copies per step at most
 
@@ -72,7 +72,7 @@ __global__ void append_chunks(const uint4* __restrict__ k_new, const uint4* __re
 // LDS tile (uint4 units): K [D/8][32 token slots of the step], then V [4 octets][D].
 template <int D>
 struct CopyPlan {
-    static constexpr int kTile = D * 8;   // uint4 per step: (D/8) * 32 + 4 * D
+    static constexpr int kPieces = D * 8;   // uint4 per step: (D/8) * 32 + 4 * D
 };
 
 template <int D>
@@ -90,7 +90,7 @@ __device__ __forceinline__ void fetch_step(uint4 (&reg)[kCopies], const uint4* _
     for (int i = 0; i < kCopies; ++i) {
         // a thread with nothing left to copy in this round re-reads the tile's last piece
         const int32_t want = threadIdx.x + i * blockDim.x;
-        const int32_t idx = want < CopyPlan<D>::kTile ? want : CopyPlan<D>::kTile - 1;
+        const int32_t idx = want < CopyPlan<D>::kPieces ? want : CopyPlan<D>::kPieces - 1;
         const uint4* src;
         if (idx < (D / 8) * 32) {
             const int32_t d8 = idx >> 5, s32 = idx & 31;
@@ -112,12 +112,14 @@ __device__ __forceinline__ void stash_step(const uint4 (&reg)[kCopies], uint4* t
 #pragma unroll
     for (int i = 0; i < kCopies; ++i) {
         const int32_t idx = threadIdx.x + i * blockDim.x;
-        if (idx < CopyPlan<D>::kTile) tile[idx] = reg[i];
+        if (idx < CopyPlan<D>::kPieces) tile[idx] = reg[i];
     }
 }
 
 // MAXW: most waves a workgroup of this instance may have (the register budget follows from it).
-template <int D, int MAXW>
+// QT: column tiles (16 query tokens each) per wave; every K/V piece read from LDS is used for all
+// of them.  F32OUT: fp32 result, P split in two bf16 parts; else bf16 result, P rounded once.
+template <int D, int MAXW, int QT, bool F32OUT>
 __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     const uint4* __restrict__ q16, const uint4* __restrict__ k_pages, const uint4* __restrict__ v_pages,
     const int32_t* __restrict__ page_table, const int32_t* __restrict__ chunk_slot,
@@ -129,6 +131,7 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     // Which (chunk, query block) is this workgroup's?  Blocks are numbered chunk after chunk;
     // the workgroups take them from the last one down, so that within a prompt the blocks
     // with the longest prefixes start first.  Wave 0 counts the blocks of 64 chunks at a time.
+    constexpr int kQBlock = kTile * QT;   // query tokens per workgroup
     const int32_t h = blockIdx.x % prm.Hkv;
     const int32_t wanted_from_end = blockIdx.x / prm.Hkv;
     const int32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -186,19 +189,23 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
 
     const int32_t r = lane & 15, q = lane >> 4;
     const bool computes = wave < prm.G;                       // the other waves only copy
-    const int32_t col = r < nq ? r : nq - 1;                  // padding columns shadow the last query
-    const int32_t pq = pos0 + col;                            // newest position column r sees
-    bf16x8_t qf[D / 32];
-    WaveAcc<D> acc;
-    if (computes) {
-        const uint4* qrow = q16 + ((int64_t)(tq0 + col) * prm.Hq + (int64_t)h * prm.G + wave) * (D / 8) + q;
+    int32_t pq[QT];                                           // newest position column r of tile c sees
+    bf16x8_t qf[QT][D / 32];
+    WaveAcc<D> acc[QT];
 #pragma unroll
-        for (int kk = 0; kk < D / 32; ++kk) qf[kk] = as_bf16x8(qrow[kk * 4]);
+    for (int c = 0; c < QT; ++c) {
+        const int32_t col = kTile * c + r < nq ? kTile * c + r : nq - 1;   // padding columns shadow the last query
+        pq[c] = pos0 + col;
+        if (computes) {
+            const uint4* qrow = q16 + ((int64_t)(tq0 + col) * prm.Hq + (int64_t)h * prm.G + wave) * (D / 8) + q;
+#pragma unroll
+            for (int kk = 0; kk < D / 32; ++kk) qf[c][kk] = as_bf16x8(qrow[kk * 4]);
+        }
+#pragma unroll
+        for (int nt = 0; nt < D / 16; ++nt) acc[c].o[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        acc[c].m = -INFINITY;
+        acc[c].l = 0.f;
     }
-#pragma unroll
-    for (int nt = 0; nt < D / 16; ++nt) acc.o[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    acc.m = -INFINITY;
-    acc.l = 0.f;
 
     uint4 cp[kCopies];
     fetch_step<D>(cp, k_pages, v_pages, pt_row, h, 0, prm.log2P, prm.max_pages, prm.num_pages, prm.Hkv);
@@ -210,7 +217,7 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
         // (the last step fetches itself again rather than branching around the loads)
         fetch_step<D>(cp, k_pages, v_pages, pt_row, h, more ? t0 + kStep : t0, prm.log2P, prm.max_pages, prm.num_pages, prm.Hkv);
         if (computes) {
-            const uint4* kt = tiles + (s & 1) * CopyPlan<D>::kTile;
+            const uint4* kt = tiles + (s & 1) * CopyPlan<D>::kPieces;
             const uint4* vt = kt + (D / 8) * 32;
             StepData<D> sd;
 #pragma unroll
@@ -221,27 +228,33 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
             }
 #pragma unroll
             for (int nt = 0; nt < D / 16; ++nt) sd.v[nt] = vt[q * D + 16 * nt + r];
-            float sv[8];
-            qk_scores<D>(qf, sd, prm.scale_log2e, sv);
-            if (t0 + kStep - 1 > pos0) {   // the step reaches past the first query's position: causal mask
-                const int32_t first = t0 + 8 * q;
-#pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    if (first + j > pq) sv[j] = -INFINITY;
-            }
             if (t0 + kStep > kv_end) mask_v_tail<D>(sd, kv_end - (t0 + 8 * q));
-            softmax_pv<D>(sv, sd, acc);   // token 0 is visible to every column, so the max is finite
+#pragma unroll
+            for (int c = 0; c < QT; ++c) {
+                float sv[8];
+                qk_scores<D>(qf[c], sd, prm.scale_log2e, sv);
+                if (t0 + kStep - 1 > pos0) {   // the step reaches past the first query's position: causal mask
+                    const int32_t first = t0 + 8 * q;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (first + j > pq[c]) sv[j] = -INFINITY;
+                }
+                softmax_pv<D, F32OUT>(sv, sd, acc[c]);   // token 0 is visible to every column: the max is finite
+            }
         }
-        if (more) stash_step<D>(cp, tiles + ((s + 1) & 1) * CopyPlan<D>::kTile);
+        if (more) stash_step<D>(cp, tiles + ((s + 1) & 1) * CopyPlan<D>::kPieces);
         __syncthreads();
     }
 
     if (!computes) return;
-    acc.l += __shfl_xor(acc.l, 16);
-    acc.l += __shfl_xor(acc.l, 32);
-    if (r < nq) {
-        const int64_t idx = ((int64_t)(tq0 + r) * prm.Hq + (int64_t)h * prm.G + wave) * D + 4 * q;
-        store_result<D>(acc, out, idx, prm.out_f32);
+#pragma unroll
+    for (int c = 0; c < QT; ++c) {
+        acc[c].l += __shfl_xor(acc[c].l, 16);
+        acc[c].l += __shfl_xor(acc[c].l, 32);
+        if (kTile * c + r < nq) {
+            const int64_t idx = ((int64_t)(tq0 + kTile * c + r) * prm.Hq + (int64_t)h * prm.G + wave) * D + 4 * q;
+            store_result<D>(acc[c], out, idx, F32OUT);
+        }
     }
 }
 
@@ -302,22 +315,32 @@ extern "C" int roll_prefill_attn(const void* q, const void* k_new, const void* v
         (uint16_t*)v_pages, page_table, prm, d->head_dim);
     ROLL_HIP_CHECK(hipGetLastError());
 
-    // At most ceil(T / 16) + C query blocks (each chunk ends with at most one partial block).
-    const int64_t blocks_bound = ((int64_t)prm.T + kQBlock - 1) / kQBlock + prm.C;
+    // Groups of up to 8 query heads keep two column tiles (32 query tokens) per wave; larger
+    // groups have half the register budget per wave and keep one.
+    const int qt = prm.G <= 8 ? 2 : 1;
+    const int q_block = kTile * qt;
+    // At most ceil(T / q_block) + C query blocks (each chunk ends with at most one partial block).
+    const int64_t blocks_bound = ((int64_t)prm.T + q_block - 1) / q_block + prm.C;
     const int64_t grid = blocks_bound * prm.Hkv;
     if (grid > INT32_MAX) return roll::fail(ROLL_ERR_INVALID_ARG, "too many query blocks");
     const int threads = 64 * (prm.G > kMinWaves ? prm.G : kMinWaves);
-#define ROLL_LAUNCH_PREFILL(DIM, MAXW)                                                                        \
-    prefill_attn<DIM, MAXW><<<(unsigned)grid, threads, 2 * sizeof(uint4) * CopyPlan<DIM>::kTile, stream>>>(     \
+#define ROLL_LAUNCH_PREFILL(DIM, MAXW, QT, F32)                                                                \
+    prefill_attn<DIM, MAXW, QT, F32><<<(unsigned)grid, threads, 2 * sizeof(uint4) * CopyPlan<DIM>::kPieces, stream>>>( \
         (const uint4*)q, (const uint4*)k_pages, (const uint4*)v_pages, page_table, chunk_slot, chunk_start,    \
         chunk_offset, out, prm)
-    if (d->head_dim == 128) {
-        if (prm.G <= 8) ROLL_LAUNCH_PREFILL(128, 8);
-        else ROLL_LAUNCH_PREFILL(128, 16);
-    } else {
-        if (prm.G <= 8) ROLL_LAUNCH_PREFILL(64, 8);
-        else ROLL_LAUNCH_PREFILL(64, 16);
-    }
+#define ROLL_LAUNCH_PREFILL_DIM(DIM)                                   \
+    do {                                                               \
+        if (prm.G <= 8) {                                              \
+            if (prm.out_f32) ROLL_LAUNCH_PREFILL(DIM, 8, 2, true);     \
+            else ROLL_LAUNCH_PREFILL(DIM, 8, 2, false);                \
+        } else {                                                       \
+            if (prm.out_f32) ROLL_LAUNCH_PREFILL(DIM, 16, 1, true);    \
+            else ROLL_LAUNCH_PREFILL(DIM, 16, 1, false);               \
+        }                                                              \
+    } while (0)
+    if (d->head_dim == 128) ROLL_LAUNCH_PREFILL_DIM(128);
+    else ROLL_LAUNCH_PREFILL_DIM(64);
+#undef ROLL_LAUNCH_PREFILL_DIM
 #undef ROLL_LAUNCH_PREFILL
     ROLL_HIP_CHECK(hipGetLastError());
     return ROLL_OK;
