@@ -146,6 +146,12 @@ class RefillLoop:
         self.bank_k = wl.randn_bf16((self.bank_tokens, cfg.num_kv_heads, cfg.head_dim), seed, 1001, device)
         self.bank_v = wl.randn_bf16((self.bank_tokens, cfg.num_kv_heads, cfg.head_dim), seed, 1002, device)
         self.last_prefill = None   # (q, out, [(slot, n, first token)]) of the latest tick with refills
+        # chunk arrays travel through a small ring of pinned buffers (asynchronous copies, so the
+        # host keeps running ahead of the GPU; an event per buffer guards its reuse)
+        self._ring = [dict(host=torch.zeros((3, cfg.batch + 1), dtype=torch.int32).pin_memory(),
+                           dev=torch.zeros((3, cfg.batch + 1), dtype=torch.int32, device=device), ev=None)
+                      for _ in range(8)]
+        self._ring_next = 0
         B = cfg.batch
         self.request = np.arange(B, dtype=np.int64)          # request id held by each slot
         self.generated = plan.start_generated[:B].astype(np.int64).copy()
@@ -187,11 +193,20 @@ class RefillLoop:
             first = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
             if self.prefill:
                 out = torch.empty((q.shape[0], cfg.num_q_heads, cfg.head_dim), dtype=b.out_dtype, device=self.device)
-                # through pinned memory, so that the copy is asynchronous and the host keeps running ahead
-                meta = torch.tensor([[r[0] for r in refilled] + [0], [0] * (len(refilled) + 1), first.tolist()],
-                                    dtype=torch.int32).pin_memory().to(self.device, non_blocking=True)
-                rb.roll_prefill_attn(q, k, v, meta[0, :-1], meta[1, :-1], meta[2], b.k_pages, b.v_pages,
-                                     b.page_table, out, cfg.page_size)
+                slot_ = self._ring[self._ring_next]
+                self._ring_next = (self._ring_next + 1) % len(self._ring)
+                if slot_["ev"] is not None:
+                    slot_["ev"].synchronize()
+                n_ch = len(refilled)
+                slot_["host"][0, :n_ch] = torch.tensor([r[0] for r in refilled], dtype=torch.int32)
+                slot_["host"][1, :n_ch] = 0
+                slot_["host"][2, :n_ch + 1] = torch.from_numpy(first)
+                meta = slot_["dev"]
+                meta.copy_(slot_["host"], non_blocking=True)
+                rb.roll_prefill_attn(q, k, v, meta[0, :n_ch], meta[1, :n_ch], meta[2, :n_ch + 1], b.k_pages,
+                                     b.v_pages, b.page_table, out, cfg.page_size)
+                slot_["ev"] = torch.cuda.Event()
+                slot_["ev"].record()
                 self.last_prefill = (q, out, [(r[0], r[2], int(f)) for r, f in zip(refilled, first)])
             else:
                 slots = torch.from_numpy(np.repeat([r[0] for r in refilled], lens).astype(np.int32)).pin_memory().to(self.device, non_blocking=True)
