@@ -808,7 +808,7 @@ extern "C" int roll_decode_step_attn(roll_kv_pool* pool, const void* k_new, cons
         return launch_attn(q, k_pages, v_pages, plan.page_table_dev, plan.seq_lens_dev, out, d, workspace,
                            workspace_bytes, stream, nullptr);
     }
-    FusedArgs fa;
+    FusedArgs fa{};
     fa.n_delta = plan.n_delta;
     for (int32_t i = 0; i < plan.n_delta; ++i) {
         fa.slot[i] = plan.slot[i];

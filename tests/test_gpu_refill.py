@@ -10,7 +10,7 @@ import torch
 import oracle
 from paper_2510_11345_amd import binding as rb
 from paper_2510_11345_amd import workloads as wl
-from paper_2510_11345_amd.harness import RefillLoop
+from paper_2510_11345_amd.harness import DecodeBatch, RefillLoop
 from gpu_helpers import say
 
 pytestmark = pytest.mark.gpu
@@ -93,3 +93,72 @@ def test_abort_mid_sequence_then_refill():
                               cfg.page_size)
     assert np.abs(b.out.double().cpu().numpy() - want).max() <= 1e-4
     loop.close()
+
+
+def test_random_release_refill_schedule():
+    # slots come and go at random (releases without refill leave empty slots in the batch, prompts of
+    # awkward lengths, several events per tick): the device tables must follow the host state at
+    # every step, whichever route (one launch or two) the step takes
+    rng = np.random.default_rng(17)
+    cfg = dataclasses.replace(wl.CONFIGS["c4"], batch=12, vocab=2048)
+    P, B, steps = cfg.page_size, cfg.batch, 90
+    start = rng.integers(1, 70, size=B)
+    b = DecodeBatch(cfg, 17, start, max_len=400, out_dtype=torch.float32, num_pages=B * 26)
+    logits = wl.make_logits(cfg, 17, "cuda")
+    live = np.ones(B, dtype=bool)
+    bank_q = wl.randn_bf16((256, cfg.num_q_heads, cfg.head_dim), 17, 70, "cuda")
+    bank_k = wl.randn_bf16((256, cfg.num_kv_heads, cfg.head_dim), 17, 71, "cuda")
+    bank_v = wl.randn_bf16((256, cfg.num_kv_heads, cfg.head_dim), 17, 72, "cuda")
+    checked = 0
+    for step in range(steps):
+        changed = False
+        for slot in np.flatnonzero(live):
+            if rng.random() < 0.06 or b.lengths[slot] > 300:
+                rb.roll_kv_release(b.pool, int(slot))
+                b.lengths[slot] = 0
+                live[slot] = False
+                changed = True
+        chunks = []
+        for slot in np.flatnonzero(~live):
+            if rng.random() < 0.3:
+                n = int(rng.choice([1, P - 1, P, P + 1, 2 * P, 37, 95]))
+                rb.roll_kv_alloc(b.pool, int(slot), n)
+                b.lengths[slot] = n
+                live[slot] = True
+                chunks.append((int(slot), n))
+                changed = True
+        if chunks:
+            rb.roll_kv_commit(b.pool)
+            T = sum(n for _, n in chunks)
+            off = np.concatenate([[0], np.cumsum([n for _, n in chunks])]).astype(np.int32)
+            out = torch.empty((T, cfg.num_q_heads, cfg.head_dim), dtype=torch.float32, device="cuda")
+            rb.roll_prefill_attn(bank_q[:T], bank_k[:T], bank_v[:T],
+                                 torch.tensor([s for s, _ in chunks], dtype=torch.int32, device="cuda"),
+                                 torch.zeros(len(chunks), dtype=torch.int32, device="cuda"),
+                                 torch.from_numpy(off).cuda(), b.k_pages, b.v_pages, b.page_table, out, P)
+        elif changed and rng.random() < 0.5:
+            rb.roll_kv_commit(b.pool)       # sometimes the release is published before the step
+        # one decode step over the live slots only
+        slots = np.flatnonzero(live).astype(np.int32)
+        if len(slots):
+            rb.roll_kv_alloc_batch(b.pool, slots, np.ones(len(slots), dtype=np.int32))
+            b.lengths[slots] += 1
+        rb.roll_decode_step_attn(b.pool, b.k_new, b.v_new, b.q, b.k_pages, b.v_pages, b.out, b.desc, b._ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(b.seq_lens.cpu().numpy(), b.lengths.astype(np.int32)), step
+        table = b.page_table.cpu().numpy()
+        for slot in range(B):
+            pages = rb.roll_kv_slot_pages(b.pool, slot)
+            assert list(table[slot, :len(pages)]) == pages, (step, slot)
+        owned = sum(len(rb.roll_kv_slot_pages(b.pool, s)) for s in range(B))
+        assert owned + rb.roll_kv_free_pages(b.pool) == b.num_pages
+        if step % 6 == 0 or step == steps - 1 or chunks:
+            q, k, v, tb, lens = b.gather_rows(list(range(B)))
+            want = oracle.decode_attn(q, k, v, tb, lens, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, P)
+            err = np.abs(b.out.double().cpu().numpy() - want).max()
+            assert err <= 1e-4, (step, err)
+            checked += 1
+    fused = rb.roll_kv_fused_steps(b.pool)
+    say(f"  random schedule: {steps} steps, {fused} in one launch, attention checked on {checked}")
+    assert 10 <= fused < steps
+    b.close()
