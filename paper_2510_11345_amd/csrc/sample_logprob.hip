@@ -268,15 +268,23 @@ struct Histogram {  // adds exp(z - max) in 2^-40 fixed point to the bin of the 
     uint32_t prefix;  // the key's bits above SHIFT + kRadixBits must equal this
     unsigned long long* hist;  // [kBins][kCopies]
     uint32_t copy;             // this lane's copy
+    // Straight-line code: an entry outside the prefix (or of an inactive lane) adds zero to the
+    // bin of its own digit instead of branching around the add; the branches cost more than the
+    // adds they saved.
     template <int N> __device__ __forceinline__ void run(int32_t, const float (&x)[N], bool active) {
-        if (!active) return;
+        unsigned long long fx[N];
+        uint32_t slot[N];
 #pragma unroll
         for (int j = 0; j < N; ++j) {
             const uint32_t key = order_key(x[j]);
-            if (SHIFT + kRadixBits < 32 && (key >> ((SHIFT + kRadixBits) & 31)) != prefix) continue;
-            const unsigned long long fx = to_fixed40(__builtin_amdgcn_exp2f((x[j] - xmax) * k2));
-            if (fx) atomicAdd(&hist[((key >> SHIFT) & (kBins - 1u)) * kCopies + copy], fx);
+            bool in = active;
+            if (SHIFT + kRadixBits < 32) in = in && (key >> ((SHIFT + kRadixBits) & 31)) == prefix;
+            const float w = __builtin_amdgcn_exp2f((x[j] - xmax) * k2);
+            fx[j] = to_fixed40(in ? w : 0.f);
+            slot[j] = ((key >> SHIFT) & (kBins - 1u)) * kCopies + copy;
         }
+#pragma unroll
+        for (int j = 0; j < N; ++j) atomicAdd(&hist[slot[j]], fx[j]);
     }
 };
 
