@@ -54,11 +54,29 @@ struct WaveAcc {
     float l;            // this lane's share of the running sum of column r
 };
 
-// Scores of the step's 32 tokens for column r, in log2 units; the 8 a lane owns are the
-// step's tokens 8q + j.  No masking.
+// Maximum / sum over the four lanes that share a column (lanes r, r + 16, r + 32, r + 48), in
+// every one of them.  v_permlane16_swap exchanges the odd 16-lane rows of its first operand
+// with the even rows of its second, v_permlane32_swap the upper half of the first with the
+// lower half of the second; with the same value in both operands the two results of a swap
+// are the value of the lane itself and that of its partner (in either order), so combining
+// them is the xor-16 (xor-32) step of a butterfly, without a trip through LDS.
+__device__ __forceinline__ float max_over_q(float v) {
+    const auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    const auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float sum_over_q(float v) {
+    const auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    const auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
+// Raw scores q . k of the step's 32 tokens for column r; the 8 a lane owns are the step's
+// tokens 8q + j.  No scaling, no masking.
 template <int D>
-__device__ __forceinline__ void qk_scores(const bf16x8_t (&qf)[D / 32], const StepData<D>& s, float scale_log2e,
-                                          float (&sv)[8]) {
+__device__ __forceinline__ void qk_scores(const bf16x8_t (&qf)[D / 32], const StepData<D>& s, float (&sv)[8]) {
     f32x4_t sc[2];
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
@@ -71,7 +89,7 @@ __device__ __forceinline__ void qk_scores(const bf16x8_t (&qf)[D / 32], const St
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) sv[4 * tt + i] = sc[tt][i] * scale_log2e;
+        for (int i = 0; i < 4; ++i) sv[4 * tt + i] = sc[tt][i];
 }
 
 // Zero the V elements of this lane's tokens nvalid, nvalid + 1, .. 7 (tokens that do not exist
@@ -90,16 +108,17 @@ __device__ __forceinline__ void mask_v_tail(StepData<D>& s, int32_t nvalid) {
     }
 }
 
-// Online softmax update with the step's scores (-inf = masked; the running max must be finite
-// afterwards) and O^T += V^T P^T.  SPLIT: P as a bf16 high part plus a bf16 remainder (two
+// Online softmax update with the step's raw scores (-inf = masked; the running max must be
+// finite afterwards) and O^T += V^T P^T.  scale_log2e = softmax scale * log2(e) > 0 is applied
+// inside the exponent's fused multiply-add; the running max is kept in log2 units.  SPLIT: P as a bf16 high part plus a bf16 remainder (two
 // MFMAs per tile); without it P is rounded to bf16 once, which is enough for a bf16 result.
 template <int D, bool SPLIT = true>
-__device__ __forceinline__ void softmax_pv(const float (&sv)[8], const StepData<D>& s, WaveAcc<D>& a) {
+__device__ __forceinline__ void softmax_pv(const float (&sv)[8], const StepData<D>& s, float scale_log2e,
+                                           WaveAcc<D>& a) {
     float mx = sv[0];
 #pragma unroll
     for (int j = 1; j < 8; ++j) mx = fmaxf(mx, sv[j]);
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    mx = max_over_q(mx) * scale_log2e;
     const float m_new = fmaxf(a.m, mx);
     const float alpha = __builtin_amdgcn_exp2f(a.m - m_new);
     a.m = m_new;
@@ -107,7 +126,7 @@ __device__ __forceinline__ void softmax_pv(const float (&sv)[8], const StepData<
     float psum = 0.f;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        p[j] = __builtin_amdgcn_exp2f(sv[j] - m_new);
+        p[j] = __builtin_amdgcn_exp2f(fmaf(sv[j], scale_log2e, -m_new));
         psum += p[j];
     }
     a.l = a.l * alpha + psum;

@@ -229,13 +229,12 @@ __device__ __forceinline__ void patch_newest_v(const WaveCtx<D>& c, int32_t t0, 
     }
 }
 
-// Scores of the step's 32 tokens for head r, in log2 units; the 8 a lane owns are tokens
-// t0 + 8q + j.  Tokens at or past `end` get -inf.
+// Raw scores of the step's 32 tokens for head r; the 8 a lane owns are tokens t0 + 8q + j.
+// Tokens at or past `end` get -inf.
 template <int D>
 __device__ __forceinline__ void score_step(const WaveCtx<D>& c, const bf16x8_t (&qf)[D / 32],
-                                           const StepData<D>& s, int32_t t0, int32_t end,
-                                           float scale_log2e, float (&sv)[8]) {
-    qk_scores<D>(qf, s, scale_log2e, sv);
+                                           const StepData<D>& s, int32_t t0, int32_t end, float (&sv)[8]) {
+    qk_scores<D>(qf, s, sv);
     if (t0 + kStep > end) {  // ragged tail of the row
         const int32_t first = t0 + 8 * c.q;
 #pragma unroll
@@ -249,9 +248,9 @@ __device__ __forceinline__ void score_step(const WaveCtx<D>& c, const bf16x8_t (
 // The running max stays finite: every processed step has a valid token.
 template <int D, bool NEWEST>
 __device__ __forceinline__ void accumulate_step(const WaveCtx<D>& c, const float (&sv)[8], StepData<D>& s,
-                                                int32_t t0, int32_t end, WaveAcc<D>& a) {
+                                                int32_t t0, int32_t end, float scale_log2e, WaveAcc<D>& a) {
     if (NEWEST || t0 + kStep > end) mask_v_tail<D>(s, end - (t0 + 8 * c.q));  // ragged tail
-    softmax_pv<D>(sv, s, a);
+    softmax_pv<D>(sv, s, scale_log2e, a);
 }
 
 // Steps per row into LDS as an exclusive prefix, clamped lengths beside it.
@@ -515,8 +514,8 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
                         load_k<D, false>(ctx, (i + 1) * kStep, s1);
                         load_v<D, false>(ctx, (i + 1) * kStep, s1);
                     }
-                    score_step<D>(ctx, qf, s0, i * kStep, L, prm.scale_log2e, sv);
-                    accumulate_step<D, false>(ctx, sv, s0, i * kStep, L, acc);
+                    score_step<D>(ctx, qf, s0, i * kStep, L, sv);
+                    accumulate_step<D, false>(ctx, sv, s0, i * kStep, L, prm.scale_log2e, acc);
                     if (!more1) break;
                     ++i;
                     const bool more0 = i + 1 < loop_end;
@@ -524,8 +523,8 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
                         load_k<D, false>(ctx, (i + 1) * kStep, s0);
                         load_v<D, false>(ctx, (i + 1) * kStep, s0);
                     }
-                    score_step<D>(ctx, qf, s1, i * kStep, L, prm.scale_log2e, sv);
-                    accumulate_step<D, false>(ctx, sv, s1, i * kStep, L, acc);
+                    score_step<D>(ctx, qf, s1, i * kStep, L, sv);
+                    accumulate_step<D, false>(ctx, sv, s1, i * kStep, L, prm.scale_log2e, acc);
                     if (!more0) break;
                     ++i;
                 }
@@ -536,8 +535,8 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
                 load_k<D, false>(ctx, i * kStep, sd);
                 load_v<D, false>(ctx, i * kStep, sd);
                 float sv[8];
-                score_step<D>(ctx, qf, sd, i * kStep, L, prm.scale_log2e, sv);
-                accumulate_step<D, false>(ctx, sv, sd, i * kStep, L, acc);
+                score_step<D>(ctx, qf, sd, i * kStep, L, sv);
+                accumulate_step<D, false>(ctx, sv, sd, i * kStep, L, prm.scale_log2e, acc);
             }
         }
         if (has_newest) {
@@ -546,14 +545,13 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
             load_k<D, FUSED>(ctx, t0, sd);
             load_v<D, FUSED>(ctx, t0, sd);
             float sv[8];
-            score_step<D>(ctx, qf, sd, t0, L, prm.scale_log2e, sv);
+            score_step<D>(ctx, qf, sd, t0, L, sv);
             patch_newest_v<D>(ctx, t0, v_fresh, sd);
-            accumulate_step<D, FUSED>(ctx, sv, sd, t0, L, acc);
+            accumulate_step<D, FUSED>(ctx, sv, sd, t0, L, prm.scale_log2e, acc);
         }
 
         // Finish the per-head sum across the four q-groups of the wave.
-        acc.l += __shfl_xor(acc.l, 16);
-        acc.l += __shfl_xor(acc.l, 32);
+        acc.l = sum_over_q(acc.l);
 
         const int64_t out_idx = ((int64_t)b * prm.Hq + (int64_t)h * G + rr) * D + 4 * ctx.q;
         if (cnt == n_b) {  // the whole stream: normalise and write the result

@@ -13,10 +13,11 @@
 // holds the query tokens as the columns of two MFMA tiles.  Each 32-token step of K and
 // V is copied once per workgroup from the pages into LDS, verbatim (the page layouts are
 // already the A-operand layouts: consecutive lanes read consecutive 16-byte pieces, so the LDS
-// reads are conflict free), double buffered with the global loads of the next step in flight
-// during the MFMAs of the current one.  The per-step arithmetic is the decode kernel's; only
+// reads are conflict free) with global_load_lds, double buffered: the copy of the next step is
+// in flight during the MFMAs of the current one.  The per-step arithmetic is the decode kernel's; only
 // the mask differs (column r sees tokens up to the position of query token r).
 #include <cmath>
+#include <type_traits>
 
 #include "attn_core.h"
 #include "common.h"
@@ -27,8 +28,10 @@ namespace {
 using namespace roll::attn;
 
 constexpr int kTile = 16;         // query tokens per MFMA column tile
-constexpr int kMinWaves = 4;      // workgroups have at least this many waves to copy K/V with
-constexpr int kCopies = 4;        // 16-byte pieces a thread copies per step at most
+constexpr int kCopyWaves = 8;     // the first 8 waves of a workgroup copy K/V (workgroups have at least 8)
+constexpr int kCopyThreads = 64 * kCopyWaves;
+constexpr int kTiles = 4;         // LDS ring: the step in use and three steps of copies in flight
+constexpr int kAhead = kTiles - 1;
 
 struct PrefillParams {
     int32_t C, T, Hq, Hkv, G;
@@ -68,29 +71,39 @@ __global__ void append_chunks(const uint4* __restrict__ k_new, const uint4* __re
                          prm.Hkv, D);
 }
 
-// The (up to) kCopies 16-byte pieces of a step's K and V tiles that one thread copies.
-// LDS tile (uint4 units): K [D/8][32 token slots of the step], then V [4 octets][D].
+// LDS tile of one step (uint4 units): K [D/8][32 token slots of the step], then V [4 octets][D].
+// Each of the kCopyThreads copying threads moves kPerThread 16-byte pieces per step, the same
+// number in every copying wave, so that a wave can wait for "all but the youngest n steps" of
+// its copies with one s_waitcnt vmcnt.
 template <int D>
 struct CopyPlan {
-    static constexpr int kPieces = D * 8;   // uint4 per step: (D/8) * 32 + 4 * D
+    static constexpr int kPieces = D * 8;   // (D/8) * 32 + 4 * D
+    static constexpr int kPerThread = kPieces / kCopyThreads;
+    static_assert(kPieces % kCopyThreads == 0, "pieces must divide evenly over the copying threads");
 };
 
+// Copies one step's K and V from the pages into an LDS tile with global_load_lds_dwordx4:
+// each lane's 16 bytes go straight from memory to tile[wave-uniform base + lane] without
+// passing through registers, asynchronously (the wave waits on vmcnt before the barrier that
+// publishes the tile).  Called by all threads; the first kCopyThreads do the work.  pt_row
+// must be wave-uniform so that the page ids come through the scalar cache and do not share
+// the counter of the copies.
 template <int D>
-__device__ __forceinline__ void fetch_step(uint4 (&reg)[kCopies], const uint4* __restrict__ k_pages,
-                                           const uint4* __restrict__ v_pages, const int32_t* __restrict__ pt_row,
-                                           int32_t h, int32_t t0, int32_t log2P, int32_t max_pages,
-                                           int32_t num_pages, int32_t Hkv) {
+__device__ __forceinline__ void copy_step(uint4* tile, const uint4* __restrict__ k_pages,
+                                          const uint4* __restrict__ v_pages, const int32_t* __restrict__ pt_row,
+                                          int32_t h, int32_t t0, int32_t log2P, int32_t max_pages,
+                                          int32_t num_pages, int32_t Hkv) {
     const int32_t P = 1 << log2P;
     int32_t pa = t0 >> log2P, pb = (t0 + 16) >> log2P;
     pb = pb > max_pages - 1 ? max_pages - 1 : pb;   // a second page past the row's end is masked later
     int32_t pgA = pt_row[pa], pgB = pt_row[pb];
     pgA = pgA < 0 ? 0 : (pgA >= num_pages ? num_pages - 1 : pgA);
     pgB = pgB < 0 ? 0 : (pgB >= num_pages ? num_pages - 1 : pgB);
+    if (threadIdx.x >= kCopyThreads) return;
+    const int32_t wave_base = (int32_t)(threadIdx.x & ~63u);
 #pragma unroll
-    for (int i = 0; i < kCopies; ++i) {
-        // a thread with nothing left to copy in this round re-reads the tile's last piece
-        const int32_t want = threadIdx.x + i * blockDim.x;
-        const int32_t idx = want < CopyPlan<D>::kPieces ? want : CopyPlan<D>::kPieces - 1;
+    for (int i = 0; i < CopyPlan<D>::kPerThread; ++i) {
+        const int32_t idx = threadIdx.x + i * kCopyThreads;
         const uint4* src;
         if (idx < (D / 8) * 32) {
             const int32_t d8 = idx >> 5, s32 = idx & 31;
@@ -103,17 +116,20 @@ __device__ __forceinline__ void fetch_step(uint4 (&reg)[kCopies], const uint4* _
             const int32_t oct_in_page = ((t0 + 8 * oct) & (P - 1)) >> 3;
             src = v_pages + (((int64_t)page * Hkv + h) * (P / 8) + oct_in_page) * D + d;
         }
-        reg[i] = *src;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                         (__attribute__((address_space(3))) void*)(tile + i * kCopyThreads + wave_base),
+                                         16, 0, 0);
     }
 }
 
-template <int D>
-__device__ __forceinline__ void stash_step(const uint4 (&reg)[kCopies], uint4* tile) {
-#pragma unroll
-    for (int i = 0; i < kCopies; ++i) {
-        const int32_t idx = threadIdx.x + i * blockDim.x;
-        if (idx < CopyPlan<D>::kPieces) tile[idx] = reg[i];
-    }
+// All of this wave's copies have landed in LDS except those of the youngest STEPS steps, and
+// its own LDS reads have returned.  (s_waitcnt immediate of gfx9: vmcnt in bits 3:0 and 15:14,
+// expcnt 6:4 left at its maximum, lgkmcnt 11:8 = 0.)
+template <int D, int STEPS>
+__device__ __forceinline__ void copies_landed_but() {
+    constexpr int n = STEPS * CopyPlan<D>::kPerThread;
+    static_assert(n < 64, "vmcnt field");
+    __builtin_amdgcn_s_waitcnt((n & 0xF) | ((n >> 4) << 14) | (7 << 4));
 }
 
 // MAXW: most waves a workgroup of this instance may have (the register budget follows from it).
@@ -125,7 +141,9 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     const int32_t* __restrict__ page_table, const int32_t* __restrict__ chunk_slot,
     const int32_t* __restrict__ chunk_start, const int32_t* __restrict__ chunk_offset,
     void* __restrict__ out, PrefillParams prm) {
-    extern __shared__ uint4 tiles[];   // two step tiles
+    static_assert(kTiles == 4 && kAhead == 3, "the step loop is written out for four tiles");
+    __shared__ uint4 tile0[CopyPlan<D>::kPieces], tile1[CopyPlan<D>::kPieces], tile2[CopyPlan<D>::kPieces],
+        tile3[CopyPlan<D>::kPieces];
     __shared__ int32_t s_chunk, s_qb, s_found;
 
     // Which (chunk, query block) is this workgroup's?  Blocks are numbered chunk after chunk;
@@ -172,7 +190,8 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     }
     __syncthreads();
     if (!s_found) return;
-    const int32_t c = s_chunk, qb = s_qb;
+    // (wave-uniform by construction; saying so keeps everything derived from them in scalar registers)
+    const int32_t c = __builtin_amdgcn_readfirstlane(s_chunk), qb = __builtin_amdgcn_readfirstlane(s_qb);
 
     const int32_t slot = chunk_slot[c];
     const int32_t n_c = chunk_offset[c + 1] - chunk_offset[c];
@@ -207,19 +226,33 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
         acc[c].l = 0.f;
     }
 
-    uint4 cp[kCopies];
-    fetch_step<D>(cp, k_pages, v_pages, pt_row, h, 0, prm.log2P, prm.max_pages, prm.num_pages, prm.Hkv);
-    stash_step<D>(cp, tiles);
-    __syncthreads();
-    for (int32_t s = 0; s < n_steps; ++s) {
+    // A ring of kTiles LDS tiles: while step s is computed the copies of steps s + 1 .. s + kAhead
+    // are in flight (one step ahead is not enough: a copy takes longer than a step's arithmetic).
+    // Copies are issued for steps past the last one too (clamped to it), so that every wave always
+    // has the same number in flight and one wait count fits all.  The tiles are separate arrays
+    // and the loop is unrolled over them, so that each LDS access names its array: the compiler
+    // then orders an LDS read only after the copies into the same tile, not after all of them.
+    const int32_t last_t0 = (n_steps - 1) * kStep;
+    auto tile = [&](auto I) -> uint4* {
+        if constexpr (decltype(I)::value == 0) return tile0;
+        else if constexpr (decltype(I)::value == 1) return tile1;
+        else if constexpr (decltype(I)::value == 2) return tile2;
+        else return tile3;
+    };
+    auto copy_to = [&](auto I, int32_t t0) {
+        copy_step<D>(tile(I), k_pages, v_pages, pt_row, h, min(t0, last_t0), prm.log2P, prm.max_pages,
+                     prm.num_pages, prm.Hkv);
+    };
+    // One step: operands of step s from tile I into registers, start the copy of step s + kAhead
+    // into the tile that step s - 1 used (every wave has passed the barrier since), arithmetic,
+    // then wait until this wave's copies of step s + 1 have landed and meet the other waves.
+    auto step = [&](auto I, int32_t s) {
+        constexpr int kI = decltype(I)::value;
         const int32_t t0 = s * kStep;
-        const bool more = s + 1 < n_steps;
-        // (the last step fetches itself again rather than branching around the loads)
-        fetch_step<D>(cp, k_pages, v_pages, pt_row, h, more ? t0 + kStep : t0, prm.log2P, prm.max_pages, prm.num_pages, prm.Hkv);
+        StepData<D> sd;
         if (computes) {
-            const uint4* kt = tiles + (s & 1) * CopyPlan<D>::kPieces;
+            const uint4* kt = tile(I);
             const uint4* vt = kt + (D / 8) * 32;
-            StepData<D> sd;
 #pragma unroll
             for (int tt = 0; tt < 2; ++tt) {
                 const int32_t s32 = P == 16 ? 16 * (r >> 3) + (r & 7) + 8 * tt : r + 16 * tt;
@@ -228,29 +261,47 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
             }
 #pragma unroll
             for (int nt = 0; nt < D / 16; ++nt) sd.v[nt] = vt[q * D + 16 * nt + r];
+        }
+        copy_to(std::integral_constant<int, (kI + kAhead) % kTiles>{}, t0 + kAhead * kStep);
+        if (computes) {
             if (t0 + kStep > kv_end) mask_v_tail<D>(sd, kv_end - (t0 + 8 * q));
+            // Scores of all column tiles first, then softmax and PV tile by tile: the vector work
+            // of one tile's softmax then runs while the matrix cores finish the other tile's
+            // products.
+            float sv[QT][8];
+#pragma unroll
+            for (int c = 0; c < QT; ++c) qk_scores<D>(qf[c], sd, sv[c]);
 #pragma unroll
             for (int c = 0; c < QT; ++c) {
-                float sv[8];
-                qk_scores<D>(qf[c], sd, prm.scale_log2e, sv);
                 if (t0 + kStep - 1 > pos0) {   // the step reaches past the first query's position: causal mask
                     const int32_t first = t0 + 8 * q;
 #pragma unroll
                     for (int j = 0; j < 8; ++j)
-                        if (first + j > pq[c]) sv[j] = -INFINITY;
+                        if (first + j > pq[c]) sv[c][j] = -INFINITY;
                 }
-                softmax_pv<D, F32OUT>(sv, sd, acc[c]);   // token 0 is visible to every column: the max is finite
+                softmax_pv<D, F32OUT>(sv[c], sd, prm.scale_log2e, acc[c]);   // token 0 is visible to every column: the max is finite
             }
         }
-        if (more) stash_step<D>(cp, tiles + ((s + 1) & 1) * CopyPlan<D>::kPieces);
-        __syncthreads();
+        copies_landed_but<D, kAhead - 1>();   // step s + 1 has landed
+        __builtin_amdgcn_s_barrier();
+    };
+
+    copy_to(std::integral_constant<int, 0>{}, 0);
+    copy_to(std::integral_constant<int, 1>{}, kStep);
+    copy_to(std::integral_constant<int, 2>{}, 2 * kStep);
+    copies_landed_but<D, kAhead - 1>();
+    __builtin_amdgcn_s_barrier();
+    for (int32_t s = 0; s < n_steps; s += kTiles) {   // n_steps is the same for the whole workgroup
+        step(std::integral_constant<int, 0>{}, s);
+        if (s + 1 < n_steps) step(std::integral_constant<int, 1>{}, s + 1);
+        if (s + 2 < n_steps) step(std::integral_constant<int, 2>{}, s + 2);
+        if (s + 3 < n_steps) step(std::integral_constant<int, 3>{}, s + 3);
     }
 
     if (!computes) return;
 #pragma unroll
     for (int c = 0; c < QT; ++c) {
-        acc[c].l += __shfl_xor(acc[c].l, 16);
-        acc[c].l += __shfl_xor(acc[c].l, 32);
+        acc[c].l = sum_over_q(acc[c].l);
         if (kTile * c + r < nq) {
             const int64_t idx = ((int64_t)(tq0 + kTile * c + r) * prm.Hq + (int64_t)h * prm.G + wave) * D + 4 * q;
             store_result<D>(acc[c], out, idx, F32OUT);
@@ -323,9 +374,9 @@ extern "C" int roll_prefill_attn(const void* q, const void* k_new, const void* v
     const int64_t blocks_bound = ((int64_t)prm.T + q_block - 1) / q_block + prm.C;
     const int64_t grid = blocks_bound * prm.Hkv;
     if (grid > INT32_MAX) return roll::fail(ROLL_ERR_INVALID_ARG, "too many query blocks");
-    const int threads = 64 * (prm.G > kMinWaves ? prm.G : kMinWaves);
+    const int threads = 64 * (prm.G > kCopyWaves ? prm.G : kCopyWaves);
 #define ROLL_LAUNCH_PREFILL(DIM, MAXW, QT, F32)                                                                \
-    prefill_attn<DIM, MAXW, QT, F32><<<(unsigned)grid, threads, 2 * sizeof(uint4) * CopyPlan<DIM>::kPieces, stream>>>( \
+    prefill_attn<DIM, MAXW, QT, F32><<<(unsigned)grid, threads, 0, stream>>>( \
         (const uint4*)q, (const uint4*)k_pages, (const uint4*)v_pages, page_table, chunk_slot, chunk_start,    \
         chunk_offset, out, prm)
 #define ROLL_LAUNCH_PREFILL_DIM(DIM)                                   \
