@@ -243,22 +243,27 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
         copy_step<D>(tile(I), k_pages, v_pages, pt_row, h, min(t0, last_t0), prm.log2P, prm.max_pages,
                      prm.num_pages, prm.Hkv);
     };
-    // One step: operands of step s from tile I into registers, start the copy of step s + kAhead
-    // into the tile that step s - 1 used (every wave has passed the barrier since), arithmetic,
-    // then wait until this wave's copies of step s + 1 have landed and meet the other waves.
+    StepData<D> sd;   // K of the step about to be computed is read one step early (see below)
+    auto read_k = [&](auto I) {
+        const uint4* kt = tile(I);
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+            const int32_t s32 = P == 16 ? 16 * (r >> 3) + (r & 7) + 8 * tt : r + 16 * tt;
+#pragma unroll
+            for (int kk = 0; kk < D / 32; ++kk) sd.k[tt][kk] = kt[(4 * kk + q) * 32 + s32];
+        }
+    };
+    // One step.  V of step s from tile I into registers (K is there already), start the copy of
+    // step s + kAhead into the tile that step s - 1 used (every wave has passed the barrier
+    // since), scores; the K registers are free now and take K of step s + 1 from the next tile
+    // while softmax and PV run (all waves would otherwise read LDS at the same moment after every
+    // barrier, with the matrix cores idle); then wait until this wave's copies of steps s + 1 and
+    // s + 2 have landed and meet the other waves.
     auto step = [&](auto I, int32_t s) {
         constexpr int kI = decltype(I)::value;
         const int32_t t0 = s * kStep;
-        StepData<D> sd;
         if (computes) {
-            const uint4* kt = tile(I);
-            const uint4* vt = kt + (D / 8) * 32;
-#pragma unroll
-            for (int tt = 0; tt < 2; ++tt) {
-                const int32_t s32 = P == 16 ? 16 * (r >> 3) + (r & 7) + 8 * tt : r + 16 * tt;
-#pragma unroll
-                for (int kk = 0; kk < D / 32; ++kk) sd.k[tt][kk] = kt[(4 * kk + q) * 32 + s32];
-            }
+            const uint4* vt = tile(I) + (D / 8) * 32;
 #pragma unroll
             for (int nt = 0; nt < D / 16; ++nt) sd.v[nt] = vt[q * D + 16 * nt + r];
         }
@@ -271,6 +276,7 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
             float sv[QT][8];
 #pragma unroll
             for (int c = 0; c < QT; ++c) qk_scores<D>(qf[c], sd, sv[c]);
+            read_k(std::integral_constant<int, (kI + 1) % kTiles>{});
 #pragma unroll
             for (int c = 0; c < QT; ++c) {
                 if (t0 + kStep - 1 > pos0) {   // the step reaches past the first query's position: causal mask
@@ -282,15 +288,16 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
                 softmax_pv<D, F32OUT>(sv[c], sd, prm.scale_log2e, acc[c]);   // token 0 is visible to every column: the max is finite
             }
         }
-        copies_landed_but<D, kAhead - 1>();   // step s + 1 has landed
+        copies_landed_but<D, kAhead - 2>();   // steps s + 1 and s + 2 have landed
         __builtin_amdgcn_s_barrier();
     };
 
     copy_to(std::integral_constant<int, 0>{}, 0);
     copy_to(std::integral_constant<int, 1>{}, kStep);
     copy_to(std::integral_constant<int, 2>{}, 2 * kStep);
-    copies_landed_but<D, kAhead - 1>();
+    copies_landed_but<D, kAhead - 2>();
     __builtin_amdgcn_s_barrier();
+    if (computes) read_k(std::integral_constant<int, 0>{});
     for (int32_t s = 0; s < n_steps; s += kTiles) {   // n_steps is the same for the whole workgroup
         step(std::integral_constant<int, 0>{}, s);
         if (s + 1 < n_steps) step(std::integral_constant<int, 1>{}, s + 1);
