@@ -112,16 +112,24 @@ __device__ __forceinline__ void mask_v_tail(StepData<D>& s, int32_t nvalid) {
 // finite afterwards) and O^T += V^T P^T.  scale_log2e = softmax scale * log2(e) > 0 is applied
 // inside the exponent's fused multiply-add; the running max is kept in log2 units.  SPLIT: P as a bf16 high part plus a bf16 remainder (two
 // MFMAs per tile); without it P is rounded to bf16 once, which is enough for a bf16 result.
-template <int D, bool SPLIT = true>
-__device__ __forceinline__ void softmax_pv(const float (&sv)[8], const StepData<D>& s, float scale_log2e,
-                                           WaveAcc<D>& a) {
+// The probabilities of one step as the B operands of the PV product, and the factor by which
+// the running sums shrink.
+struct StepProbs {
+    bf16x8_t hi, lo;   // lo is unused without SPLIT
+    float alpha;
+};
+
+// First half of the update: running max and sum, probabilities.  Straight-line code.
+template <bool SPLIT>
+__device__ __forceinline__ StepProbs softmax_probs(const float (&sv)[8], float scale_log2e, float& m, float& l) {
     float mx = sv[0];
 #pragma unroll
     for (int j = 1; j < 8; ++j) mx = fmaxf(mx, sv[j]);
     mx = max_over_q(mx) * scale_log2e;
-    const float m_new = fmaxf(a.m, mx);
-    const float alpha = __builtin_amdgcn_exp2f(a.m - m_new);
-    a.m = m_new;
+    const float m_new = fmaxf(m, mx);
+    StepProbs out;
+    out.alpha = __builtin_amdgcn_exp2f(m - m_new);
+    m = m_new;
     float p[8];
     float psum = 0.f;
 #pragma unroll
@@ -129,7 +137,7 @@ __device__ __forceinline__ void softmax_pv(const float (&sv)[8], const StepData<
         p[j] = __builtin_amdgcn_exp2f(fmaf(sv[j], scale_log2e, -m_new));
         psum += p[j];
     }
-    a.l = a.l * alpha + psum;
+    l = l * out.alpha + psum;
 
     uint32_t hi[4], lo[4];
 #pragma unroll
@@ -143,19 +151,33 @@ __device__ __forceinline__ void softmax_pv(const float (&sv)[8], const StepData<
             lo[k2] = 0u;
         }
     }
-    const bf16x8_t p_hi = as_bf16x8(make_uint4(hi[0], hi[1], hi[2], hi[3]));
-    const bf16x8_t p_lo = as_bf16x8(make_uint4(lo[0], lo[1], lo[2], lo[3]));
+    out.hi = as_bf16x8(make_uint4(hi[0], hi[1], hi[2], hi[3]));
+    out.lo = as_bf16x8(make_uint4(lo[0], lo[1], lo[2], lo[3]));
+    return out;
+}
 
-    if (__any(alpha != 1.0f)) {
+// Second half: O^T = alpha O^T (skipped by the caller's test when no lane needs it) + V^T P^T.
+template <int D>
+__device__ __forceinline__ void rescale(WaveAcc<D>& a, float alpha) {
 #pragma unroll
-        for (int nt = 0; nt < D / 16; ++nt) a.o[nt] *= alpha;
-    }
+    for (int nt = 0; nt < D / 16; ++nt) a.o[nt] *= alpha;
+}
+template <int D, bool SPLIT>
+__device__ __forceinline__ void pv_accumulate(const StepData<D>& s, const StepProbs& pr, WaveAcc<D>& a) {
 #pragma unroll
     for (int nt = 0; nt < D / 16; ++nt) {
         const bf16x8_t vf = as_bf16x8(s.v[nt]);
-        a.o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, p_hi, a.o[nt], 0, 0, 0);
-        if (SPLIT) a.o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, p_lo, a.o[nt], 0, 0, 0);
+        a.o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pr.hi, a.o[nt], 0, 0, 0);
+        if (SPLIT) a.o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pr.lo, a.o[nt], 0, 0, 0);
     }
+}
+
+template <int D, bool SPLIT = true>
+__device__ __forceinline__ void softmax_pv(const float (&sv)[8], const StepData<D>& s, float scale_log2e,
+                                           WaveAcc<D>& a) {
+    const StepProbs pr = softmax_probs<SPLIT>(sv, scale_log2e, a.m, a.l);
+    if (__any(pr.alpha != 1.0f)) rescale<D>(a, pr.alpha);
+    pv_accumulate<D, SPLIT>(s, pr, a);
 }
 
 // Write one head-dim quad row of a finished column: normalise by the sum and store at

@@ -11,9 +11,9 @@
 // byte, and the G query heads of a KV head share it again.  One workgroup therefore takes
 // (chunk, block of 32 query tokens, KV head); wave g of it owns query head g of the group and
 // holds the query tokens as the columns of two MFMA tiles.  Each 32-token step of K and
-// V is copied once per workgroup from the pages into LDS, verbatim (the page layouts are
-// already the A-operand layouts: consecutive lanes read consecutive 16-byte pieces, so the LDS
-// reads are conflict free) with global_load_lds, double buffered: the copy of the next step is
+// V is copied once per workgroup from the pages into LDS in 16-byte pieces (the page layouts
+// are already the A-operand layouts; the pieces are ordered so that consecutive lanes read
+// consecutive pieces and the LDS reads are conflict free) with global_load_lds, double buffered: the copy of the next step is
 // in flight during the MFMAs of the current one.  The per-step arithmetic is the decode kernel's; only
 // the mask differs (column r sees tokens up to the position of query token r).
 #include <cmath>
@@ -106,7 +106,12 @@ __device__ __forceinline__ void copy_step(uint4* tile, const uint4* __restrict__
         const int32_t idx = threadIdx.x + i * kCopyThreads;
         const uint4* src;
         if (idx < (D / 8) * 32) {
-            const int32_t d8 = idx >> 5, s32 = idx & 31;
+            // LDS order of the 32 token slots of a K row: the 16 slots that the lanes r = 0..15 of
+            // MFMA tile tt read sit next to each other at 16 tt + r (256 contiguous bytes, all 64
+            // banks once).  With 16-token pages those are the slots 8 tt .. 8 tt + 7 of the step's
+            // first page and of its second page; with larger pages the page order is that order.
+            const int32_t d8 = idx >> 5, pos = idx & 31;
+            const int32_t s32 = P == 16 ? 16 * ((pos >> 3) & 1) + (pos & 7) + 8 * (pos >> 4) : pos;
             const int32_t page = (P == 16 && s32 >= 16) ? pgB : pgA;
             const int32_t slot = P == 16 ? (s32 & 15) : (t0 & (P - 1)) + s32;
             src = k_pages + (((int64_t)page * Hkv + h) * (D / 8) + d8) * P + slot;
@@ -247,11 +252,9 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     auto read_k = [&](auto I) {
         const uint4* kt = tile(I);
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-            const int32_t s32 = P == 16 ? 16 * (r >> 3) + (r & 7) + 8 * tt : r + 16 * tt;
+        for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-            for (int kk = 0; kk < D / 32; ++kk) sd.k[tt][kk] = kt[(4 * kk + q) * 32 + s32];
-        }
+            for (int kk = 0; kk < D / 32; ++kk) sd.k[tt][kk] = kt[(4 * kk + q) * 32 + 16 * tt + r];
     };
     // One step.  V of step s from tile I into registers (K is there already), start the copy of
     // step s + kAhead into the tile that step s - 1 used (every wave has passed the barrier
@@ -277,16 +280,30 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
 #pragma unroll
             for (int c = 0; c < QT; ++c) qk_scores<D>(qf[c], sd, sv[c]);
             read_k(std::integral_constant<int, (kI + 1) % kTiles>{});
+            if (t0 + kStep - 1 > pos0) {   // the step reaches past the first query's position: causal mask
+                const int32_t first = t0 + 8 * q;
 #pragma unroll
-            for (int c = 0; c < QT; ++c) {
-                if (t0 + kStep - 1 > pos0) {   // the step reaches past the first query's position: causal mask
-                    const int32_t first = t0 + 8 * q;
+                for (int c = 0; c < QT; ++c)
 #pragma unroll
                     for (int j = 0; j < 8; ++j)
                         if (first + j > pq[c]) sv[c][j] = -INFINITY;
-                }
-                softmax_pv<D, F32OUT>(sv[c], sd, prm.scale_log2e, acc[c]);   // token 0 is visible to every column: the max is finite
             }
+            // The softmax of all column tiles as one stretch of straight-line code (independent
+            // dependency chains for the scheduler to interleave), one test for the rare rescale,
+            // then all PV products.  Token 0 is visible to every column, so the max is finite.
+            StepProbs pr[QT];
+            bool shrink = false;
+#pragma unroll
+            for (int c = 0; c < QT; ++c) {
+                pr[c] = softmax_probs<F32OUT>(sv[c], prm.scale_log2e, acc[c].m, acc[c].l);
+                shrink = shrink || pr[c].alpha != 1.0f;
+            }
+            if (__any(shrink)) {
+#pragma unroll
+                for (int c = 0; c < QT; ++c) rescale<D>(acc[c], pr[c].alpha);
+            }
+#pragma unroll
+            for (int c = 0; c < QT; ++c) pv_accumulate<D, F32OUT>(sd, pr[c], acc[c]);
         }
         copies_landed_but<D, kAhead - 2>();   // steps s + 1 and s + 2 have landed
         __builtin_amdgcn_s_barrier();
