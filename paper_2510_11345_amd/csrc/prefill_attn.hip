@@ -85,20 +85,27 @@ struct CopyPlan {
 // Copies one step's K and V from the pages into an LDS tile with global_load_lds_dwordx4:
 // each lane's 16 bytes go straight from memory to tile[wave-uniform base + lane] without
 // passing through registers, asynchronously (the wave waits on vmcnt before the barrier that
-// publishes the tile).  Called by all threads; the first kCopyThreads do the work.  pt_row
-// must be wave-uniform so that the page ids come through the scalar cache and do not share
-// the counter of the copies.
-template <int D>
-__device__ __forceinline__ void copy_step(uint4* tile, const uint4* __restrict__ k_pages,
-                                          const uint4* __restrict__ v_pages, const int32_t* __restrict__ pt_row,
-                                          int32_t h, int32_t t0, int32_t log2P, int32_t max_pages,
-                                          int32_t num_pages, int32_t Hkv) {
-    const int32_t P = 1 << log2P;
+// publishes the tile).  Called by all threads; the first kCopyThreads do the work.
+struct StepPages { int32_t a, b; };   // physical pages of the (up to) two pages a step touches
+
+// pt_row must be wave-uniform so that the page ids come through the scalar cache and do not
+// share the counter of the copies.  Ids are clamped into the pool.
+__device__ __forceinline__ StepPages step_page_ids(const int32_t* __restrict__ pt_row, int32_t t0, int32_t log2P,
+                                                   int32_t max_pages, int32_t num_pages) {
     int32_t pa = t0 >> log2P, pb = (t0 + 16) >> log2P;
     pb = pb > max_pages - 1 ? max_pages - 1 : pb;   // a second page past the row's end is masked later
     int32_t pgA = pt_row[pa], pgB = pt_row[pb];
     pgA = pgA < 0 ? 0 : (pgA >= num_pages ? num_pages - 1 : pgA);
     pgB = pgB < 0 ? 0 : (pgB >= num_pages ? num_pages - 1 : pgB);
+    return StepPages{pgA, pgB};
+}
+
+template <int D>
+__device__ __forceinline__ void copy_step(uint4* tile, const uint4* __restrict__ k_pages,
+                                          const uint4* __restrict__ v_pages, StepPages pg, int32_t h, int32_t t0,
+                                          int32_t log2P, int32_t Hkv) {
+    const int32_t P = 1 << log2P;
+    const int32_t pgA = pg.a, pgB = pg.b;
     if (threadIdx.x >= kCopyThreads) return;
     const int32_t wave_base = (int32_t)(threadIdx.x & ~63u);
 #pragma unroll
@@ -244,10 +251,13 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
         else if constexpr (decltype(I)::value == 2) return tile2;
         else return tile3;
     };
-    auto copy_to = [&](auto I, int32_t t0) {
-        copy_step<D>(tile(I), k_pages, v_pages, pt_row, h, min(t0, last_t0), prm.log2P, prm.max_pages,
-                     prm.num_pages, prm.Hkv);
+    auto pages_of = [&](int32_t t0) {
+        return step_page_ids(pt_row, min(t0, last_t0), prm.log2P, prm.max_pages, prm.num_pages);
     };
+    auto copy_to = [&](auto I, int32_t t0, StepPages pg) {
+        copy_step<D>(tile(I), k_pages, v_pages, pg, h, min(t0, last_t0), prm.log2P, prm.Hkv);
+    };
+    StepPages pg_next;   // page ids of the next copy, fetched one step early: the copy never waits for them
     StepData<D> sd;   // K of the step about to be computed is read one step early (see below)
     auto read_k = [&](auto I) {
         const uint4* kt = tile(I);
@@ -270,7 +280,8 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
 #pragma unroll
             for (int nt = 0; nt < D / 16; ++nt) sd.v[nt] = vt[q * D + 16 * nt + r];
         }
-        copy_to(std::integral_constant<int, (kI + kAhead) % kTiles>{}, t0 + kAhead * kStep);
+        copy_to(std::integral_constant<int, (kI + kAhead) % kTiles>{}, t0 + kAhead * kStep, pg_next);
+        pg_next = pages_of(t0 + (kAhead + 1) * kStep);
         if (computes) {
             if (t0 + kStep > kv_end) mask_v_tail<D>(sd, kv_end - (t0 + 8 * q));
             // Scores of all column tiles first, then softmax and PV tile by tile: the vector work
@@ -309,9 +320,10 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
         __builtin_amdgcn_s_barrier();
     };
 
-    copy_to(std::integral_constant<int, 0>{}, 0);
-    copy_to(std::integral_constant<int, 1>{}, kStep);
-    copy_to(std::integral_constant<int, 2>{}, 2 * kStep);
+    copy_to(std::integral_constant<int, 0>{}, 0, pages_of(0));
+    copy_to(std::integral_constant<int, 1>{}, kStep, pages_of(kStep));
+    copy_to(std::integral_constant<int, 2>{}, 2 * kStep, pages_of(2 * kStep));
+    pg_next = pages_of(kAhead * kStep);
     copies_landed_but<D, kAhead - 2>();
     __builtin_amdgcn_s_barrier();
     if (computes) read_k(std::integral_constant<int, 0>{});
