@@ -156,6 +156,59 @@ __device__ __forceinline__ StepProbs softmax_probs(const float (&sv)[8], float s
     return out;
 }
 
+// The update with a lazily moved reference, for kernels bound by vector work: as long as no
+// score of the step exceeds the running reference a.m by more than kLazyBits (log2 units) the
+// reference stays, no maximum is taken and nothing is rescaled; probabilities may then be as
+// large as 2^kLazyBits, which neither bf16 nor the fp32 sums mind, and the final division by
+// l makes the result the same.  When some lane of the wave does exceed it (always in a row's
+// first step, where a.m is -inf), the reference moves to the exact running maximum, the sums are
+// rescaled, and the exponents are taken again: at most one such round per call.
+constexpr float kLazyBits = 8.0f;
+template <int D, bool SPLIT>
+__device__ __forceinline__ StepProbs softmax_probs_lazy(const float (&sv)[8], float scale_log2e, WaveAcc<D>& a) {
+    float t[8];
+#pragma unroll
+    for (int round = 0; round < 2; ++round) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) t[j] = fmaf(sv[j], scale_log2e, -a.m);
+        const float top = fmaxf(fmaxf(fmaxf(t[0], t[1]), fmaxf(t[2], t[3])), fmaxf(fmaxf(t[4], t[5]), fmaxf(t[6], t[7])));
+        if (round == 1 || !__any(!(top <= kLazyBits))) break;
+        float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+        mx = max_over_q(mx) * scale_log2e;
+        const float m_new = fmaxf(a.m, mx);
+        const float alpha = __builtin_amdgcn_exp2f(a.m - m_new);
+        a.m = m_new;
+        a.l *= alpha;
+#pragma unroll
+        for (int nt = 0; nt < D / 16; ++nt) a.o[nt] *= alpha;
+    }
+    float p[8];
+    float psum = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        p[j] = __builtin_amdgcn_exp2f(t[j]);
+        psum += p[j];
+    }
+    a.l += psum;
+    StepProbs out;
+    uint32_t hi[4], lo[4];
+#pragma unroll
+    for (int k2 = 0; k2 < 4; ++k2) {
+        hi[k2] = pack_bf16_rne(p[2 * k2], p[2 * k2 + 1]);
+        if (SPLIT) {
+            const float r0 = p[2 * k2] - __uint_as_float(hi[k2] << 16);
+            const float r1 = p[2 * k2 + 1] - __uint_as_float(hi[k2] & 0xFFFF0000u);
+            lo[k2] = pack_bf16_rne(r0, r1);
+        } else {
+            lo[k2] = 0u;
+        }
+    }
+    out.hi = as_bf16x8(make_uint4(hi[0], hi[1], hi[2], hi[3]));
+    out.lo = as_bf16x8(make_uint4(lo[0], lo[1], lo[2], lo[3]));
+    out.alpha = 1.0f;
+    return out;
+}
+
 // Second half: O^T = alpha O^T (skipped by the caller's test when no lane needs it) + V^T P^T.
 template <int D>
 __device__ __forceinline__ void rescale(WaveAcc<D>& a, float alpha) {

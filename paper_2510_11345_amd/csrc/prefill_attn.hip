@@ -303,16 +303,8 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
             // dependency chains for the scheduler to interleave), one test for the rare rescale,
             // then all PV products.  Token 0 is visible to every column, so the max is finite.
             StepProbs pr[QT];
-            bool shrink = false;
 #pragma unroll
-            for (int c = 0; c < QT; ++c) {
-                pr[c] = softmax_probs<F32OUT>(sv[c], prm.scale_log2e, acc[c].m, acc[c].l);
-                shrink = shrink || pr[c].alpha != 1.0f;
-            }
-            if (__any(shrink)) {
-#pragma unroll
-                for (int c = 0; c < QT; ++c) rescale<D>(acc[c], pr[c].alpha);
-            }
+            for (int c = 0; c < QT; ++c) pr[c] = softmax_probs_lazy<D, F32OUT>(sv[c], prm.scale_log2e, acc[c]);
 #pragma unroll
             for (int c = 0; c < QT; ++c) pv_accumulate<D, F32OUT>(sd, pr[c], acc[c]);
         }
