@@ -10,12 +10,14 @@
 // Unlike decoding this is a dense contraction: the query tokens of one head share every K/V
 // byte, and the G query heads of a KV head share it again.  One workgroup therefore takes
 // (chunk, block of 32 query tokens, KV head); wave g of it owns query head g of the group and
-// holds the query tokens as the columns of two MFMA tiles.  Each 32-token step of K and
-// V is copied once per workgroup from the pages into LDS in 16-byte pieces (the page layouts
-// are already the A-operand layouts; the pieces are ordered so that consecutive lanes read
-// consecutive pieces and the LDS reads are conflict free) with global_load_lds, double buffered: the copy of the next step is
-// in flight during the MFMAs of the current one.  The per-step arithmetic is the decode kernel's; only
-// the mask differs (column r sees tokens up to the position of query token r).
+// holds the query tokens as the columns of two MFMA tiles.  Each 32-token step of K and V is
+// copied once per workgroup from the pages into LDS in 16-byte pieces with global_load_lds (the
+// page layouts are already the A-operand layouts; the pieces are ordered so that consecutive
+// lanes read consecutive pieces and the LDS reads are conflict free), into a ring of tiles with
+// the copies of several steps in flight.  The per-step arithmetic is the decode kernel's with two
+// differences: the mask is per column (column r sees tokens up to the position of query token r),
+// and the softmax reference moves lazily, because here the vector work of the softmax, not
+// memory, is what the matrix cores wait for.
 #include <cmath>
 #include <type_traits>
 
