@@ -52,25 +52,86 @@ __device__ __forceinline__ int32_t chunk_of_token(const int32_t* __restrict__ ch
     return lo;
 }
 
-// One thread per (token, KV head, 8 head-dim elements).  Tokens whose slot, position or page
-// is out of range are skipped.
-__global__ void append_chunks(const uint4* __restrict__ k_new, const uint4* __restrict__ v_new,
-                              const int32_t* __restrict__ chunk_slot, const int32_t* __restrict__ chunk_start,
-                              const int32_t* __restrict__ chunk_offset, uint4* __restrict__ k_pages,
-                              uint16_t* __restrict__ v_pages, const int32_t* __restrict__ page_table,
-                              PrefillParams prm, int32_t D) {
-    const int32_t d8n = D / 8, per_tok = prm.Hkv * d8n;
-    const int64_t item = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (item >= (int64_t)prm.T * per_tok) return;
-    const int32_t t = (int32_t)(item / per_tok), rem = (int32_t)(item - (int64_t)t * per_tok);
-    const int32_t c = chunk_of_token(chunk_offset, prm.C, t);
-    const int32_t slot = chunk_slot[c], pos = chunk_start[c] + (t - chunk_offset[c]);
+// Writes the chunk tokens' K and V into the pages.  Tokens whose slot, position or page is out
+// of range are skipped.  The first k_blocks workgroups write K: one thread per (token, KV head,
+// 8 head-dim elements), a 16-byte store each.  The others write V, whose layout keeps 8
+// consecutive positions of one head-dim element together: one wave per (octet of positions of
+// a chunk, KV head) gathers the (up to) 8 tokens' elements row by row and stores 16 bytes per
+// head-dim element; an octet that the chunk covers only in part is written element by element
+// so that the positions outside the chunk keep what they hold.
+__global__ __launch_bounds__(256) void append_chunks(
+    const uint4* __restrict__ k_new, const uint16_t* __restrict__ v_new, const int32_t* __restrict__ chunk_slot,
+    const int32_t* __restrict__ chunk_start, const int32_t* __restrict__ chunk_offset, uint4* __restrict__ k_pages,
+    uint4* __restrict__ v_pages, const int32_t* __restrict__ page_table, PrefillParams prm, int32_t D,
+    int32_t k_blocks) {
     const int32_t P = 1 << prm.log2P;
-    if (slot < 0 || slot >= prm.num_slots || pos < 0 || (pos >> prm.log2P) >= prm.max_pages) return;
-    const int32_t page = page_table[(int64_t)slot * prm.max_pages + (pos >> prm.log2P)];
+    if ((int32_t)blockIdx.x < k_blocks) {
+        const int32_t d8n = D / 8, per_tok = prm.Hkv * d8n;
+        const int64_t item = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+        if (item >= (int64_t)prm.T * per_tok) return;
+        const int32_t t = (int32_t)(item / per_tok), rem = (int32_t)(item - (int64_t)t * per_tok);
+        const int32_t c = chunk_of_token(chunk_offset, prm.C, t);
+        const int32_t slot = chunk_slot[c], pos = chunk_start[c] + (t - chunk_offset[c]);
+        if (slot < 0 || slot >= prm.num_slots || pos < 0 || (pos >> prm.log2P) >= prm.max_pages) return;
+        const int32_t page = page_table[(int64_t)slot * prm.max_pages + (pos >> prm.log2P)];
+        if (page < 0 || page >= prm.num_pages) return;
+        k_pages[(((int64_t)page * prm.Hkv + rem / d8n) * d8n + rem % d8n) * P + roll::k_slot(pos & (P - 1), P)] = k_new[item];
+        return;
+    }
+    // V: which (chunk, octet of it) is this wave's?  Octets are numbered chunk after chunk; the
+    // wave counts those of 64 chunks at a time.
+    const int32_t lane = threadIdx.x & 63;
+    const int32_t wave_ordinal = ((int32_t)blockIdx.x - k_blocks) * (int32_t)(blockDim.x >> 6) + (int32_t)(threadIdx.x >> 6);
+    const int32_t waves_per_unit = D / 64;   // a wave covers 64 head-dim elements
+    const int32_t unit = wave_ordinal / waves_per_unit, d = (wave_ordinal % waves_per_unit) * 64 + lane;
+    const int32_t wanted = unit / prm.Hkv, h = unit % prm.Hkv;
+    int32_t c = -1, k = 0, carry = 0;
+    for (int32_t base = 0; base < prm.C && c < 0; base += 64) {
+        const int32_t cc = base + lane;
+        int32_t n_oct = 0;
+        if (cc < prm.C) {
+            const int32_t n = chunk_offset[cc + 1] - chunk_offset[cc], st = chunk_start[cc];
+            if (n > 0 && st >= 0) n_oct = ((st + n + 7) >> 3) - (st >> 3);
+        }
+        int32_t incl = n_oct;
+#pragma unroll
+        for (int dd = 1; dd < 64; dd <<= 1) {
+            const int32_t v = __shfl_up(incl, dd);
+            if (lane >= dd) incl += v;
+        }
+        const int32_t first = carry + incl - n_oct;
+        const uint64_t hit = __ballot(wanted >= first && wanted < first + n_oct);
+        if (hit) {
+            const int32_t src = __ffsll((unsigned long long)hit) - 1;
+            c = base + src;
+            k = wanted - __shfl(first, src);
+        }
+        carry += __shfl(incl, 63);
+    }
+    if (c < 0) return;   // past the last octet
+    const int32_t slot = chunk_slot[c], start = chunk_start[c], n = chunk_offset[c + 1] - chunk_offset[c];
+    const int32_t pos0 = ((start >> 3) + k) << 3;
+    const int32_t lo = pos0 > start ? pos0 : start, hi = pos0 + 8 < start + n ? pos0 + 8 : start + n;
+    if (slot < 0 || slot >= prm.num_slots || (pos0 >> prm.log2P) >= prm.max_pages) return;
+    const int32_t page = page_table[(int64_t)slot * prm.max_pages + (pos0 >> prm.log2P)];
     if (page < 0 || page >= prm.num_pages) return;
-    roll::store_kv_slice(k_new[item], v_new[item], k_pages, v_pages, page, pos & (P - 1), rem / d8n, rem % d8n, P,
-                         prm.Hkv, D);
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+    for (int32_t pos = lo; pos < hi; ++pos) {
+        const int64_t t = (int64_t)chunk_offset[c] + (pos - start);
+        const uint32_t val = v_new[(t * prm.Hkv + h) * D + d];
+        const int32_t j = pos - pos0;
+        w[j >> 1] |= val << ((j & 1) * 16);
+    }
+    uint4* dst = v_pages + (((int64_t)page * prm.Hkv + h) * (P / 8) + ((pos0 & (P - 1)) >> 3)) * D + d;
+    if (hi - lo == 8) {
+        *dst = make_uint4(w[0], w[1], w[2], w[3]);
+    } else {
+        uint16_t* dst16 = (uint16_t*)dst;
+        for (int32_t pos = lo; pos < hi; ++pos) {
+            const int32_t j = pos - pos0;
+            dst16[j] = (uint16_t)(w[j >> 1] >> ((j & 1) * 16));
+        }
+    }
 }
 
 // LDS tile of one step (uint4 units): K [D/8][32 token slots of the step], then V [4 octets][D].
@@ -218,7 +279,6 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     kv_end = kv_end > cap ? cap : kv_end;
     const int32_t n_steps = (kv_end + kStep - 1) / kStep;
     const int32_t* pt_row = page_table + (int64_t)slot * prm.max_pages;
-    const int32_t P = 1 << prm.log2P;
 
     const int32_t r = lane & 15, q = lane >> 4;
     const bool computes = wave < prm.G;                       // the other waves only copy
@@ -390,10 +450,16 @@ extern "C" int roll_prefill_attn(const void* q, const void* k_new, const void* v
     const float scale = d->softmax_scale > 0.f ? d->softmax_scale : 1.0f / sqrtf((float)d->head_dim);
     prm.scale_log2e = scale * 1.44269504088896340736f;
 
-    const int64_t items = (int64_t)prm.T * prm.Hkv * (d->head_dim / 8);
-    append_chunks<<<(unsigned)((items + 255) / 256), 256, 0, stream>>>(
-        (const uint4*)k_new, (const uint4*)v_new, chunk_slot, chunk_start, chunk_offset, (uint4*)k_pages,
-        (uint16_t*)v_pages, page_table, prm, d->head_dim);
+    const int64_t k_items = (int64_t)prm.T * prm.Hkv * (d->head_dim / 8);
+    const int64_t k_blocks = (k_items + 255) / 256;
+    // at most T / 8 + 2 C octets of positions (a chunk may begin and end inside one); one wave per
+    // octet, KV head and 64 head-dim elements, four waves per workgroup
+    const int64_t v_waves = (((int64_t)prm.T + 7) / 8 + 2 * (int64_t)prm.C) * prm.Hkv * (d->head_dim / 64);
+    const int64_t v_blocks = (v_waves + 3) / 4;
+    if (k_blocks + v_blocks > INT32_MAX) return roll::fail(ROLL_ERR_INVALID_ARG, "too many tokens");
+    append_chunks<<<(unsigned)(k_blocks + v_blocks), 256, 0, stream>>>(
+        (const uint4*)k_new, (const uint16_t*)v_new, chunk_slot, chunk_start, chunk_offset, (uint4*)k_pages,
+        (uint4*)v_pages, page_table, prm, d->head_dim, (int32_t)k_blocks);
     ROLL_HIP_CHECK(hipGetLastError());
 
     // Groups of up to 8 query heads keep two column tiles (32 query tokens) per wave; larger
