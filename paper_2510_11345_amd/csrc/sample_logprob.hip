@@ -62,8 +62,9 @@ __device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint3
     for (int round = 0; round < 10; ++round) {
         const uint64_t pa = (uint64_t)0xD2511F53u * c0;
         const uint64_t pb = (uint64_t)0xCD9E8D57u * c2;
-        const uint32_t n0 = (uint32_t)(pb >> 32) ^ c1 ^ k0;
-        const uint32_t n2 = (uint32_t)(pa >> 32) ^ c3 ^ k1;
+        // a ^ b ^ c in one instruction (v_bitop3_b32, truth table 0x96)
+        const uint32_t n0 = __builtin_amdgcn_bitop3_b32((uint32_t)(pb >> 32), c1, k0, 0x96);
+        const uint32_t n2 = __builtin_amdgcn_bitop3_b32((uint32_t)(pa >> 32), c3, k1, 0x96);
         c0 = n0; c1 = (uint32_t)pb; c2 = n2; c3 = (uint32_t)pa;
         k0 += 0x9E3779B9u;
         k1 += 0xBB67AE85u;
@@ -76,6 +77,7 @@ template <typename T> struct Elem;
 template <> struct Elem<uint16_t> {  // bf16 bit patterns
     static constexpr int kVec = 8;
     static constexpr int kKeyBits = 16;
+    __device__ static uint4 minus_inf_vector() { return make_uint4(0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u); }
     __device__ static float widen(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
     __device__ static void unpack(const uint4& v, float (&x)[8]) {
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
@@ -89,6 +91,7 @@ template <> struct Elem<uint16_t> {  // bf16 bit patterns
 template <> struct Elem<float> {
     static constexpr int kVec = 4;
     static constexpr int kKeyBits = 32;
+    __device__ static uint4 minus_inf_vector() { return make_uint4(0xFF800000u, 0xFF800000u, 0xFF800000u, 0xFF800000u); }
     __device__ static float widen(float f) { return f; }
     __device__ static void unpack(const uint4& v, float (&x)[4]) {
         x[0] = __uint_as_float(v.x); x[1] = __uint_as_float(v.y);
@@ -108,14 +111,14 @@ __device__ __forceinline__ float key_to_float(uint32_t k) {
 
 // Calls f.run<N>(i0, x, active) for every aligned vector of the row and f.run<1> for the
 // tail.  Every lane of the workgroup makes the same number of calls (inactive ones carry
-// active == false), so the bodies may use wave-wide operations.  The next vector is
-// requested before the current one is processed.
+// active == false and logits of -inf), so the bodies may use wave-wide operations.  The next
+// vector is requested before the current one is processed.
 template <typename T, typename F>
 __device__ __forceinline__ void sweep(const T* __restrict__ row, int32_t V, F& f) {
     constexpr int N = Elem<T>::kVec;
     const int32_t nvec = V / N;
     const uint4* __restrict__ row16 = (const uint4*)row;
-    const uint4 zero = make_uint4(0, 0, 0, 0);
+    const uint4 zero = Elem<T>::minus_inf_vector();
     int32_t vi = (int32_t)threadIdx.x;
     uint4 cur = vi < nvec ? row16[vi] : zero;
     for (int32_t base = 0; base < nvec; base += kThreads) {
@@ -130,7 +133,7 @@ __device__ __forceinline__ void sweep(const T* __restrict__ row, int32_t V, F& f
     if (nvec * N < V) {
         const int32_t i = nvec * N + (int32_t)threadIdx.x;
         const bool active = i < V;
-        float x[1] = {active ? Elem<T>::widen(row[i]) : 0.f};
+        float x[1] = {active ? Elem<T>::widen(row[i]) : -INFINITY};
         f.template run<1>(i, x, active);
     }
 }
@@ -170,7 +173,8 @@ struct MaxOnly {  // per-thread max of the raw logits; with RAW also sum exp(x -
 // per-thread reference logit follows the thread's running max and s accumulates
 // sum exp2((x - xref) k2); without it the reference is fixed (the row max) and only the
 // race runs.
-template <bool LSE, bool RAW>
+// CUT: entries below x_cut are not kept (the top-p pass); without it every entry is.
+template <bool LSE, bool RAW, bool CUT>
 struct Race {
     const SampleParams& p;
     uint32_t row_id;
@@ -215,22 +219,24 @@ struct Race {
                 for (int j = 0; j < 4; ++j) words[4 * b4 + j] = r.w[j];
             }
         }
-        float xa[N];
-#pragma unroll
-        for (int j = 0; j < N; ++j) xa[j] = active ? x[j] : -INFINITY;
-        if (LSE) {  // move the reference to the running max, branch-free
+        (void)active;  // an inactive lane's logits are -inf: they add nothing and cannot pass
+        const float (&xa)[N] = x;
+        if (LSE) {  // move the reference to the running max when some lane's max grew (rare after
+                    // the first vectors; the sums are rescaled only then)
             float vmax = xa[0];
 #pragma unroll
             for (int j = 1; j < N; ++j) vmax = fmaxf(vmax, xa[j]);
-            const float x_new = fmaxf(xref, vmax);
-            s *= __builtin_amdgcn_exp2f((xref - x_new) * p.k2);
-            if (RAW) {
-                s_raw *= __builtin_amdgcn_exp2f((xref - x_new) * kLog2e);
-#pragma unroll
-                for (int j = 0; j < N; ++j) s_raw += __builtin_amdgcn_exp2f((xa[j] - x_new) * kLog2e);
+            if (__any(vmax > xref)) {
+                const float x_new = fmaxf(xref, vmax);
+                s *= __builtin_amdgcn_exp2f((xref - x_new) * p.k2);
+                if (RAW) s_raw *= __builtin_amdgcn_exp2f((xref - x_new) * kLog2e);
+                xref = x_new;
+                refresh_c();
             }
-            xref = x_new;
-            refresh_c();
+            if (RAW) {
+#pragma unroll
+                for (int j = 0; j < N; ++j) s_raw += __builtin_amdgcn_exp2f((xa[j] - xref) * kLog2e);
+            }
         }
         uint32_t pass = 0;
 #pragma unroll
@@ -241,7 +247,7 @@ struct Race {
             if (LSE) s += e;
             // 1 - u = ((2^23 - 1 - k) + 0.5) 2^-23, exact in fp32
             const float one_minus_u = ((float)((~words[j]) >> 9) + 0.5f) * 0x1p-23f;
-            if (one_minus_u <= e * c && x[j] >= x_cut) pass |= 1u << j;
+            if (one_minus_u <= e * c && (!CUT || x[j] >= x_cut)) pass |= 1u << j;
         }
         if (__any(pass != 0)) {
 #pragma unroll
@@ -387,7 +393,7 @@ __global__ __launch_bounds__(kThreads) void sample_rows(const T* __restrict__ lo
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t row_id = row_ids ? (uint32_t)row_ids[r] : (uint32_t)r;
 
-    Race<true, RAW> race{p, row_id, -INFINITY, -FLT_MAX};
+    Race<true, RAW, false> race{p, row_id, -INFINITY, -FLT_MAX};
     MaxOnly<RAW> mo;
     if (!TOPP) sweep<T>(row, p.V, race);  // one sweep: online log-sum-exp and the race together
     else sweep<T>(row, p.V, mo);
@@ -425,7 +431,7 @@ __global__ __launch_bounds__(kThreads) void sample_rows(const T* __restrict__ lo
         __syncthreads();
     }
 
-    Race<false, false> race_kept{p, row_id, -INFINITY, 0.f};
+    Race<false, false, true> race_kept{p, row_id, -INFINITY, 0.f};
     if (TOPP) {
         const float xM = s_m[0];
         constexpr int kKeyBits = Elem<T>::kKeyBits;
