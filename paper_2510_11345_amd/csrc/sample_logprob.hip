@@ -186,7 +186,7 @@ struct Race {
     double best = -INFINITY; // best exact perturbed logit of this lane, natural-log units
     int32_t best_i = 0x7FFFFFFF;
     float thr2 = -INFINITY;  // wave-uniform lower bound of the wave's best, log2 units
-    float c = INFINITY;      // exp2(xref k2 - thr2) with a safety factor
+    float c = INFINITY;      // 2^23 exp2(xref k2 - thr2) with a safety factor
 
     __device__ __forceinline__ void exact(int32_t i, float x, uint32_t word) {
         const double u = ((double)(word >> 9) + 0.5) * 0x1p-23;
@@ -204,7 +204,7 @@ struct Race {
         if ((double)t > b * kLog2ed) t = nextafterf(t, -INFINITY);
         thr2 = nextafterf(t, -INFINITY);
     }
-    __device__ __forceinline__ void refresh_c() { c = __builtin_amdgcn_exp2f(xref * p.k2 - thr2) * 1.0001f; }
+    __device__ __forceinline__ void refresh_c() { c = __builtin_amdgcn_exp2f(xref * p.k2 - thr2) * (1.0001f * 0x1p23f); }
 
     template <int N> __device__ __forceinline__ void run(int32_t i0, const float (&x)[N], bool active) {
         uint32_t words[N];
@@ -238,21 +238,26 @@ struct Race {
                 for (int j = 0; j < N; ++j) s_raw += __builtin_amdgcn_exp2f((xa[j] - xref) * kLog2e);
             }
         }
-        uint32_t pass = 0;
+        bool pass[N];
+        bool any_pass = false;
 #pragma unroll
         for (int j = 0; j < N; ++j) {
             // exponent relative to the reference: the difference of two logits is (nearly)
             // exact, so entries close to the max keep full relative accuracy
             const float e = __builtin_amdgcn_exp2f((xa[j] - xref) * p.k2);  // 0 for -inf entries
             if (LSE) s += e;
-            // 1 - u = ((2^23 - 1 - k) + 0.5) 2^-23, exact in fp32
-            const float one_minus_u = ((float)((~words[j]) >> 9) + 0.5f) * 0x1p-23f;
-            if (one_minus_u <= e * c && (!CUT || x[j] >= x_cut)) pass |= 1u << j;
+            // With k = word >> 9, 1 - u = (2^23 - 1 - k + 0.5) 2^-23, so 1 - u <= e exp2(..) reads
+            // k >= 2^23 - 0.5 - e c.  The right side is formed one lower, 2^23 - 1.5 - e c (fp32
+            // rounds it by at most 0.25 there), so the test can only let an extra entry through,
+            // never hold a winner back.  e = 0 with c = inf gives NaN: no pass, as it must be.
+            const float kf = (float)(words[j] >> 9);
+            pass[j] = kf >= fmaf(-e, c, 8388606.5f) && (!CUT || x[j] >= x_cut);
+            any_pass = any_pass || pass[j];
         }
-        if (__any(pass != 0)) {
+        if (__any(any_pass)) {
 #pragma unroll
             for (int j = 0; j < N; ++j)
-                if (pass & (1u << j)) exact(i0 + j, x[j], words[j]);
+                if (pass[j]) exact(i0 + j, x[j], words[j]);
             share();
             refresh_c();
         }
