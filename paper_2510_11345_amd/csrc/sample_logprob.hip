@@ -169,6 +169,11 @@ struct MaxOnly {  // per-thread max of the raw logits; with RAW also sum exp(x -
     }
 };
 
+// The exponentials of a sum are exp2(fma(x, k2, nk)) with nk = -fl(xref k2): relative to
+// 2^(-nk) exactly, whatever rounding nk itself carries.  Kept finite so that -inf entries
+// give exp2(-inf) = 0 and not inf - inf.
+__device__ __forceinline__ float ref_offset(float xref, float k2) { return fminf(-xref * k2, FLT_MAX); }
+
 // Gumbel-max race with the exact filter described at the top of the file.  With LSE the
 // per-thread reference logit follows the thread's running max and s accumulates
 // sum exp2((x - xref) k2); without it the reference is fixed (the row max) and only the
@@ -185,8 +190,17 @@ struct Race {
     float s_raw = 0.f;       // the same at temperature 1 (LSE and RAW only)
     double best = -INFINITY; // best exact perturbed logit of this lane, natural-log units
     int32_t best_i = 0x7FFFFFFF;
-    float thr2 = -INFINITY;  // wave-uniform lower bound of the wave's best, log2 units
-    float c = INFINITY;      // 2^23 exp2(xref k2 - thr2) with a safety factor
+    uint32_t* block_thr_key; // LDS: order_key of the largest threshold any wave of the workgroup published
+    float thr2 = -INFINITY;  // lower bound of the row's best perturbed logit, log2 units: the largest
+                             // exact value this wave has seen, or one another wave published
+    uint32_t thr_key = order_key(-INFINITY);
+    float nk = 0.f;          // -xref k2 (finite): exponents are formed as fma(x, k2, nk)
+    float c = INFINITY;      // 2^32 exp2(-nk - thr2) with a safety factor
+
+    __device__ __forceinline__ void set_ref(float x_new) {
+        xref = x_new;
+        nk = ref_offset(x_new, p.k2);
+    }
 
     __device__ __forceinline__ void exact(int32_t i, float x, uint32_t word) {
         const double u = ((double)(word >> 9) + 0.5) * 0x1p-23;
@@ -202,11 +216,25 @@ struct Race {
         for (int mask = 1; mask < 64; mask <<= 1) b = fmax(b, shfl_xor_f64(b, mask));
         float t = (float)(b * kLog2ed);
         if ((double)t > b * kLog2ed) t = nextafterf(t, -INFINITY);
-        thr2 = nextafterf(t, -INFINITY);
+        t = nextafterf(t, -INFINITY);
+        // publish it and take what the other waves have published: any wave's best bounds the
+        // row's best from below.  Which threshold a wave happens to see only decides how many
+        // entries it evaluates exactly, never the result.
+        uint32_t k = order_key(t);
+        uint32_t seen = 0;
+        if ((threadIdx.x & 63) == 0) seen = atomicMax(block_thr_key, k);
+        seen = __builtin_amdgcn_readfirstlane(seen);
+        k = seen > k ? seen : k;
+        if (k > thr_key) {
+            thr_key = k;
+            thr2 = key_to_float(k);
+        }
     }
-    __device__ __forceinline__ void refresh_c() { c = __builtin_amdgcn_exp2f(xref * p.k2 - thr2) * (1.0001f * 0x1p23f); }
+    __device__ __forceinline__ void refresh_c() { c = __builtin_amdgcn_exp2f(-nk - thr2) * (1.0001f * 0x1p32f); }
 
     template <int N> __device__ __forceinline__ void run(int32_t i0, const float (&x)[N], bool active) {
+        // requested here, used after the random words are drawn
+        const uint32_t block_key = __hip_atomic_load(block_thr_key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         uint32_t words[N];
         if (N == 1) {
             const Philox4 r = philox4x32_10((uint32_t)i0 >> 2, row_id, p.step_lo, p.step_hi, p.seed_lo, p.seed_hi);
@@ -230,7 +258,7 @@ struct Race {
                 const float x_new = fmaxf(xref, vmax);
                 s *= __builtin_amdgcn_exp2f((xref - x_new) * p.k2);
                 if (RAW) s_raw *= __builtin_amdgcn_exp2f((xref - x_new) * kLog2e);
-                xref = x_new;
+                set_ref(x_new);
                 refresh_c();
             }
             if (RAW) {
@@ -238,20 +266,39 @@ struct Race {
                 for (int j = 0; j < N; ++j) s_raw += __builtin_amdgcn_exp2f((xa[j] - xref) * kLog2e);
             }
         }
+        if (block_key > thr_key) {  // another wave has found a better candidate
+            thr_key = block_key;
+            thr2 = key_to_float(block_key);
+            refresh_c();
+        }
+        bool seeded = false;
+        const bool seed0 = x[0] > -INFINITY && (!CUT || x[0] >= x_cut);
+        if (__any(thr2 == -INFINITY && seed0)) {
+            // Nothing bounds the best yet, so every kept entry would pass: evaluate the first
+            // entry of every lane that keeps it, and filter the rest of the vector against the
+            // best of those.
+            if (seed0) exact(i0, x[0], words[0]);
+            share();
+            refresh_c();
+            seeded = true;
+        }
         bool pass[N];
         bool any_pass = false;
 #pragma unroll
         for (int j = 0; j < N; ++j) {
-            // exponent relative to the reference: the difference of two logits is (nearly)
-            // exact, so entries close to the max keep full relative accuracy
-            const float e = __builtin_amdgcn_exp2f((xa[j] - xref) * p.k2);  // 0 for -inf entries
+            // The exponent keeps full relative accuracy near the reference: the product is not
+            // rounded before nk is added.  -inf entries give 0.
+            const float e = __builtin_amdgcn_exp2f(fmaf(xa[j], p.k2, nk));
             if (LSE) s += e;
             // With k = word >> 9, 1 - u = (2^23 - 1 - k + 0.5) 2^-23, so 1 - u <= e exp2(..) reads
-            // k >= 2^23 - 0.5 - e c.  The right side is formed one lower, 2^23 - 1.5 - e c (fp32
-            // rounds it by at most 0.25 there), so the test can only let an extra entry through,
-            // never hold a winner back.  e = 0 with c = inf gives NaN: no pass, as it must be.
-            const float kf = (float)(words[j] >> 9);
-            pass[j] = kf >= fmaf(-e, c, 8388606.5f) && (!CUT || x[j] >= x_cut);
+            // k >= 2^23 - 0.5 - e exp2(..) 2^23.  Both sides are taken times 2^9: the whole word
+            // converted to fp32 (rounded to nearest) is at least k 2^9, and the right side is
+            // formed one unit of k lower, (2^23 - 1.5) 2^9 - e c (fp32 rounds that by at most a
+            // quarter unit), so the test can only let an extra entry through, never hold a winner
+            // back.  e = 0 (an entry more than 126 binary orders below a logit of the same row,
+            // which the 28 orders a draw can add never make up) with c = inf gives NaN: no pass.
+            pass[j] = (float)words[j] >= fmaf(-e, c, 8388606.5f * 512.f) && (!CUT || x[j] >= x_cut);
+            if (j == 0) pass[j] = pass[j] && !seeded;
             any_pass = any_pass || pass[j];
         }
         if (__any(any_pass)) {
@@ -392,25 +439,32 @@ __global__ __launch_bounds__(kThreads) void sample_rows(const T* __restrict__ lo
     __shared__ double s_lse;
     __shared__ double s_sraw[kWavesPerBlock];
     __shared__ double s_raw_lse;
+    __shared__ uint32_t s_thr_key;
 
     const int32_t r = blockIdx.x;
     const T* __restrict__ row = logits + (int64_t)r * p.row_stride;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t row_id = row_ids ? (uint32_t)row_ids[r] : (uint32_t)r;
 
+    if (threadIdx.x == 0) s_thr_key = order_key(-INFINITY);
+    __syncthreads();
     Race<true, RAW, false> race{p, row_id, -INFINITY, -FLT_MAX};
+    race.block_thr_key = &s_thr_key;
+    race.set_ref(-FLT_MAX);
     MaxOnly<RAW> mo;
     if (!TOPP) sweep<T>(row, p.V, race);  // one sweep: online log-sum-exp and the race together
     else sweep<T>(row, p.V, mo);
 
-    // Block max of the raw logits and, for top_p == 1, the log-sum-exp.  The sums are taken
-    // relative to fl(xmax * k2); the exact xmax / T is added back in fp64 at the end.
+    // Block max of the raw logits and, for top_p == 1, the log-sum-exp in log2 units of the
+    // logits times k2: a lane's sum is relative to 2^(-nk) of its own reference, the block's to
+    // that of the row max, and the sampled token's log-prob is taken with the same k2, so the
+    // rounding of k2 and of nk cancels (a row with all its mass on one entry gives 0).
     {
         const float mine = TOPP ? mo.xm : race.xref;
         float m = mine;
 #pragma unroll
         for (int mask = 1; mask < 64; mask <<= 1) m = fmaxf(m, __shfl_xor(m, mask));
-        double s = TOPP ? 0.0 : (double)race.s * (double)__builtin_amdgcn_exp2f((mine - m) * p.k2);
+        double s = TOPP ? 0.0 : (double)race.s * (double)__builtin_amdgcn_exp2f(ref_offset(m, p.k2) - race.nk);
         double sr = (double)(TOPP ? mo.s_raw : race.s_raw) * (double)__builtin_amdgcn_exp2f((mine - m) * kLog2e);
 #pragma unroll
         for (int mask = 1; mask < 64; mask <<= 1) {
@@ -424,11 +478,11 @@ __global__ __launch_bounds__(kThreads) void sample_rows(const T* __restrict__ lo
             for (int w = 1; w < kWavesPerBlock; ++w) M = fmaxf(M, s_m[w]);
             double S = 0.0, SR = 0.0;
             for (int w = 0; w < kWavesPerBlock; ++w) {
-                S += s_s[w] * (double)__builtin_amdgcn_exp2f((s_m[w] - M) * p.k2);
+                S += s_s[w] * (double)__builtin_amdgcn_exp2f(ref_offset(M, p.k2) - ref_offset(s_m[w], p.k2));
                 SR += s_sraw[w] * (double)__builtin_amdgcn_exp2f((s_m[w] - M) * kLog2e);
             }
             s_m[0] = M;
-            s_lse = (double)M / p.temperature + log(S);
+            s_lse = (log2(S) - (double)ref_offset(M, p.k2)) / kLog2ed;
             s_raw_lse = (double)M + log(SR);
             s_sel.prefix = 0;
             s_sel.above = 0;
@@ -461,8 +515,9 @@ __global__ __launch_bounds__(kThreads) void sample_rows(const T* __restrict__ lo
             s_lse = (double)xM / p.temperature + log((double)kept * 0x1p-40);
         }
         __syncthreads();
+        race_kept.block_thr_key = &s_thr_key;  // still -inf: no race has run in this launch
         race_kept.x_cut = s_xcut;
-        race_kept.xref = xM;
+        race_kept.set_ref(xM);
         race_kept.refresh_c();
         sweep<T>(row, p.V, race_kept);
     }
@@ -490,7 +545,8 @@ __global__ __launch_bounds__(kThreads) void sample_rows(const T* __restrict__ lo
             } else {
                 tokens_out[r] = bi;
                 const double x = (double)Elem<T>::widen(row[bi]);
-                const float lp = (float)(x / p.temperature - s_lse);
+                const double z = TOPP ? x / p.temperature : x * (double)p.k2 / kLog2ed;
+                const float lp = (float)(z - s_lse);
                 logprob_out[r] = lp;
                 // without an extra sum the sampled distribution is the raw one (T = 1, top_p = 1)
                 if (raw_logprob_out) raw_logprob_out[r] = RAW ? (float)(x - s_raw_lse) : lp;
