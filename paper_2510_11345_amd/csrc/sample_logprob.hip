@@ -99,9 +99,10 @@ template <> struct Elem<float> {
     }
 };
 
-// Order-preserving key: larger float <=> larger unsigned key (-0 < +0, harmless).
+// Order-preserving key: larger float <=> larger unsigned key.  Adding +0 turns -0 into +0, so
+// that the two zeros, equal as values, are one class of the cut.
 __device__ __forceinline__ uint32_t order_key(float x) {
-    const uint32_t b = __float_as_uint(x);
+    const uint32_t b = __float_as_uint(x + 0.0f);
     return b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u);
 }
 __device__ __forceinline__ float key_to_float(uint32_t k) {
@@ -143,6 +144,10 @@ __device__ __forceinline__ double shfl_xor_f64(double v, int mask) {
     uint64_t b = __builtin_bit_cast(uint64_t, v);
     uint32_t lo = __shfl_xor((uint32_t)b, mask), hi = __shfl_xor((uint32_t)(b >> 32), mask);
     return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int mask) {
+    uint32_t lo = __shfl_xor((uint32_t)v, mask), hi = __shfl_xor((uint32_t)(v >> 32), mask);
+    return ((uint64_t)hi << 32) | lo;
 }
 __device__ __forceinline__ uint64_t shfl_up_u64(uint64_t v, int delta) {
     uint32_t lo = __shfl_up((uint32_t)v, delta), hi = __shfl_up((uint32_t)(v >> 32), delta);
@@ -233,6 +238,12 @@ struct Race {
     __device__ __forceinline__ void refresh_c() { c = __builtin_amdgcn_exp2f(-nk - thr2) * (1.0001f * 0x1p32f); }
 
     template <int N> __device__ __forceinline__ void run(int32_t i0, const float (&x)[N], bool active) {
+        if (CUT) {  // a vector without a kept entry in any lane needs no random numbers
+            bool kept = false;
+#pragma unroll
+            for (int j = 0; j < N; ++j) kept = kept || x[j] >= x_cut;
+            if (!__any(kept)) return;
+        }
         // requested here, used after the random words are drawn
         const uint32_t block_key = __hip_atomic_load(block_thr_key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         uint32_t words[N];
@@ -311,6 +322,80 @@ struct Race {
     }
 };
 
+// The race over the kept entries only.  A Philox block serves four consecutive entries, and below
+// the cut lies most of the row, so the blocks that hold a kept entry are first gathered, by wave,
+// into a queue in LDS (block number and its four logits), and the race runs on 64 gathered blocks
+// at a time, one per lane: random numbers are drawn only for blocks that need them.  A wave
+// whose first vector has a kept entry in more than half of its blocks (a cut deep in the row)
+// skips the queue and races on the vectors as they come.
+constexpr int kQueueCap = 128;  // >= 63 left over + 64 pushed; a power of two
+constexpr int kQueueBytesPerWave = kQueueCap * (4 * 4 + 4);
+
+template <typename RaceT>
+struct CompactRace {
+    RaceT& race;
+    float* qx;       // [kQueueCap][4] this wave's queue: the logits of a block
+    uint32_t* qblk;  // [kQueueCap] and its number (entry index / 4)
+    uint32_t head = 0, tail = 0;  // wave-uniform; positions are taken modulo kQueueCap
+    int mode = 0;                 // wave-uniform: 0 undecided, 1 through the queue, 2 direct
+
+    __device__ __forceinline__ void drain(uint32_t n) {
+        const uint32_t lane = threadIdx.x & 63;
+        const uint32_t slot = (tail + lane) & (kQueueCap - 1);
+        const bool valid = lane < n;
+        __builtin_amdgcn_wave_barrier();
+        const float4 v = *(const float4*)(qx + slot * 4);
+        const uint32_t blk = qblk[slot];
+        __builtin_amdgcn_wave_barrier();
+        tail += n;
+        const float x4[4] = {valid ? v.x : -INFINITY, valid ? v.y : -INFINITY, valid ? v.z : -INFINITY,
+                             valid ? v.w : -INFINITY};
+        race.template run<4>((int32_t)((valid ? blk : 0u) * 4u), x4, valid);
+    }
+    __device__ __forceinline__ void push(uint32_t blk, float x0, float x1, float x2, float x3) {
+        const float cut = race.x_cut;
+        const bool need = x0 >= cut || x1 >= cut || x2 >= cut || x3 >= cut;
+        const unsigned long long mask = __ballot(need);
+        if (mask == 0) return;
+        const uint32_t pos = head + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                              __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+        if (need) {
+            const uint32_t slot = pos & (kQueueCap - 1);
+            *(float4*)(qx + slot * 4) = make_float4(x0, x1, x2, x3);
+            qblk[slot] = blk;
+        }
+        head += (uint32_t)__popcll(mask);
+        if (head - tail >= 64) drain(64);
+    }
+    template <int N> __device__ __forceinline__ void run(int32_t i0, const float (&x)[N], bool active) {
+        if (N > 1 && mode == 0) {
+            const float cut = race.x_cut;
+            int needed = 0;
+#pragma unroll
+            for (int b = 0; b < N / 4; ++b)
+                needed += __popcll(__ballot(x[4 * b] >= cut || x[4 * b + 1] >= cut || x[4 * b + 2] >= cut ||
+                                            x[4 * b + 3] >= cut));
+            mode = needed > 32 * (N / 4) ? 2 : 1;
+        }
+        if (N > 1 && mode == 2) {
+            race.template run<N>(i0, x, active);
+            return;
+        }
+        if (N == 1) {  // the row's tail: one entry of its block per lane
+            const int w = i0 & 3;
+            push((uint32_t)i0 >> 2, w == 0 ? x[0] : -INFINITY, w == 1 ? x[0] : -INFINITY,
+                 w == 2 ? x[0] : -INFINITY, w == 3 ? x[0] : -INFINITY);
+        } else {
+#pragma unroll
+            for (int b = 0; b < N / 4; ++b)
+                push(((uint32_t)i0 >> 2) + b, x[4 * b], x[4 * b + 1], x[4 * b + 2], x[4 * b + 3]);
+        }
+    }
+    __device__ __forceinline__ void finish() {
+        if (head != tail) drain(head - tail);
+    }
+};
+
 // w in [0, 1] as 2^-40 fixed point, truncated: the integer and the fractional part of
 // w * 2^20 are both exact in fp32, so no 64-bit float conversion is needed.
 __device__ __forceinline__ unsigned long long to_fixed40(float w) {
@@ -322,7 +407,7 @@ __device__ __forceinline__ unsigned long long to_fixed40(float w) {
 
 template <int SHIFT>
 struct Histogram {  // adds exp(z - max) in 2^-40 fixed point to the bin of the key's digit
-    float k2, xmax;
+    float k2, nk;   // nk = ref_offset(row max)
     uint32_t prefix;  // the key's bits above SHIFT + kRadixBits must equal this
     unsigned long long* hist;  // [kBins][kCopies]
     uint32_t copy;             // this lane's copy
@@ -337,7 +422,7 @@ struct Histogram {  // adds exp(z - max) in 2^-40 fixed point to the bin of the 
             const uint32_t key = order_key(x[j]);
             bool in = active;
             if (SHIFT + kRadixBits < 32) in = in && (key >> ((SHIFT + kRadixBits) & 31)) == prefix;
-            const float w = __builtin_amdgcn_exp2f((x[j] - xmax) * k2);
+            const float w = __builtin_amdgcn_exp2f(fmaf(x[j], k2, nk));
             fx[j] = to_fixed40(in ? w : 0.f);
             slot[j] = ((key >> SHIFT) & (kBins - 1u)) * kCopies + copy;
         }
@@ -349,17 +434,18 @@ struct Histogram {  // adds exp(z - max) in 2^-40 fixed point to the bin of the 
 struct Select {
     uint32_t prefix;            // key bits selected so far (right-aligned)
     unsigned long long above;   // fixed-point mass of keys strictly above the prefix range
+    unsigned long long kept;    // above + the mass of the selected range itself
+    int32_t found;              // the last selection reached its target
 };
 
-// tot holds kBins bin totals; thread t owns bin (kBins - 1 - t) so that a forward inclusive scan
-// over threads is a suffix sum over bins.  Picks the highest bin at which above + suffix >= target.
-__device__ void scan_select(const unsigned long long* tot, unsigned long long* s_wave, Select* s_sel,
-                            unsigned long long target) {
+// Threads hold the masses of key ranges in descending key order (thread 0 the highest; threads
+// with no range pass 0).  Picks the first thread at which above + running sum >= target and
+// records its prefix; found stays 0 if the target is not reached.
+__device__ void scan_select(unsigned long long mine, uint32_t my_prefix, unsigned long long* s_wave,
+                            Select* s_sel, unsigned long long target) {
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int nb = kBins, bits = kRadixBits;
-    const int bin = nb - 1 - tid;
-    const unsigned long long mine = (tid < nb) ? tot[bin] : 0ull;
+    if (tid == 0) s_sel->found = 0;
     unsigned long long incl = mine;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
@@ -373,23 +459,49 @@ __device__ void scan_select(const unsigned long long* tot, unsigned long long* s
     incl += base;
     const unsigned long long excl = incl - mine;
     __syncthreads();
-    if (tid < nb && excl < target && incl >= target) {
-        s_sel->prefix = (s_sel->prefix << bits) | (uint32_t)bin;
+    if (excl < target && incl >= target) {
+        s_sel->prefix = my_prefix;
         s_sel->above = excl;
+        s_sel->kept = incl;
+        s_sel->found = 1;
     }
     __syncthreads();
+}
+
+// Sum over the workgroup of one value per thread (every thread gets it).
+__device__ unsigned long long block_sum_u64(unsigned long long v, unsigned long long* s_wave) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const unsigned long long o = shfl_up_u64(v, d);
+        if (lane >= d) v += o;
+    }
+    if (lane == 63) s_wave[wave] = v;
+    __syncthreads();
+    unsigned long long total = 0;
+    for (int w = 0; w < kWavesPerBlock; ++w) total += s_wave[w];
+    __syncthreads();
+    return total;
+}
+
+__device__ __forceinline__ unsigned long long top_p_target(float top_p, unsigned long long total) {
+    unsigned long long target = (unsigned long long)ceil((double)top_p * (double)total);
+    if (target < 1) target = 1;
+    if (target > total) target = total;
+    return target;
 }
 
 // One radix level: histogram of the digit at SHIFT (BITS wide) over the entries whose higher
 // key bits equal the prefix chosen so far, then the suffix scan that picks the next digit.
 template <typename T, int SHIFT, bool FIRST>
-__device__ void radix_level(const T* __restrict__ row, const SampleParams& p, float xmax,
+__device__ void radix_level(const T* __restrict__ row, const SampleParams& p, float nk,
                             unsigned long long* s_hist, unsigned long long* s_tot,
                             unsigned long long* s_wave, Select* s_sel, unsigned long long& target) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
     for (int i = tid; i < kBins * kCopies; i += kThreads) s_hist[i] = 0ull;
     __syncthreads();
-    Histogram<SHIFT> h{p.k2, xmax, s_sel->prefix, s_hist, (uint32_t)(lane & (kCopies - 1))};
+    const uint32_t prefix = s_sel->prefix;
+    Histogram<SHIFT> h{p.k2, nk, prefix, s_hist, (uint32_t)(lane & (kCopies - 1))};
     sweep<T>(row, p.V, h);
     __syncthreads();
     if (tid < kBins) {  // fold the copies of my bin
@@ -399,24 +511,88 @@ __device__ void radix_level(const T* __restrict__ row, const SampleParams& p, fl
         s_tot[tid] = t;
     }
     __syncthreads();
-    if (FIRST) {  // total mass -> target = ceil(top_p * total)
-        unsigned long long incl = 0;
-        for (int i = tid; i < kBins; i += kThreads) incl += s_tot[i];
+    if (FIRST)  // total mass -> target = ceil(top_p * total)
+        target = top_p_target(p.top_p, block_sum_u64(tid < kBins ? s_tot[tid] : 0ull, s_wave));
+    // thread t owns bin (kBins - 1 - t): descending key order
+    const int bin = kBins - 1 - tid;
+    scan_select(tid < kBins ? s_tot[bin] : 0ull, (prefix << kRadixBits) | (uint32_t)bin, s_wave, s_sel, target);
+}
+
+// The upper 16 key bits in one sweep, for rows whose cut lies within kWindowBytes values of the
+// key's top byte below the row max (eight binades for four bytes): a histogram over the 16-bit
+// key prefixes of that window, one range per thread, and the row's total mass summed per lane
+// beside it.  Entries below the window go to a histogram over their key's top byte, so that a
+// row whose cut lies there has its first byte-wide level done by the same sweep.
+constexpr int kWindowBytes = 4;
+constexpr int kWindowBins = kWindowBytes * 256;
+constexpr int kWindowCopies = 4;
+constexpr int kWindowSlots = kWindowBins * kWindowCopies;
+constexpr int kHistSlots = kWindowSlots + kBins * kCopies;  // the window, then the top-byte bins
+static_assert(kWindowBins == kThreads, "one window range per thread");
+static_assert(kWindowSlots >= kBins * kCopies, "the byte-wide levels reuse the window's slots");
+
+struct WindowHistogram {
+    float k2, nk;
+    uint32_t top16;            // highest 16-bit prefix of the window
+    unsigned long long* hist;  // [kWindowBins][kWindowCopies], then [kBins][kCopies]
+    uint32_t lane;
+    template <int N> __device__ __forceinline__ void run(int32_t, const float (&x)[N], bool) {
 #pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const unsigned long long v = shfl_up_u64(incl, d);
-            if (lane >= d) incl += v;
+        for (int j = 0; j < N; ++j) {
+            const uint32_t key = order_key(x[j]);
+            const uint32_t idx = top16 - (key >> 16);  // no key of the row lies above top16
+            const unsigned long long fx = to_fixed40(__builtin_amdgcn_exp2f(fmaf(x[j], k2, nk)));
+            const uint32_t fine = idx * kWindowCopies + (lane & (kWindowCopies - 1));
+            const uint32_t coarse = kWindowSlots + (key >> 24) * kCopies + (lane & (kCopies - 1));
+            atomicAdd(&hist[idx < (uint32_t)kWindowBins ? fine : coarse], fx);
         }
-        if (lane == 63) s_wave[wave] = incl;
-        __syncthreads();
-        unsigned long long total = 0;
-        for (int w = 0; w < kWavesPerBlock; ++w) total += s_wave[w];
-        target = (unsigned long long)ceil((double)p.top_p * (double)total);
-        if (target < 1) target = 1;
-        if (target > total) target = total;
-        __syncthreads();
     }
-    scan_select(s_tot, s_wave, s_sel, target);
+};
+
+// Leaves the upper 16 key bits of the cut in s_sel.  Returns false (the same for every thread)
+// when the row has no mass at all.
+template <typename T>
+__device__ bool window_level(const T* __restrict__ row, const SampleParams& p, float xmax, float nk,
+                             unsigned long long* s_hist, unsigned long long* s_tot,
+                             unsigned long long* s_wave, Select* s_sel, unsigned long long& target) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = tid; i < kHistSlots; i += kThreads) s_hist[i] = 0ull;
+    __syncthreads();
+    const uint32_t top16 = (order_key(xmax) >> 16) | 0xFFu;
+    WindowHistogram h{p.k2, nk, top16, s_hist, (uint32_t)lane};
+    sweep<T>(row, p.V, h);  // -inf entries and inactive lanes add 0 to some bin
+    __syncthreads();
+    unsigned long long mine = 0, below = 0;  // my window range; the top-byte bin of my number
+#pragma unroll
+    for (int c = 0; c < kWindowCopies; ++c) mine += s_hist[tid * kWindowCopies + ((c + tid) & (kWindowCopies - 1))];
+    if (tid < kBins) {
+#pragma unroll
+        for (int c = 0; c < kCopies; ++c) below += s_hist[kWindowSlots + tid * kCopies + ((c + tid) & (kCopies - 1))];
+    }
+    const unsigned long long total = block_sum_u64(mine + below, s_wave);
+    if (total == 0) return false;
+    target = top_p_target(p.top_p, total);
+    scan_select(mine, top16 - (uint32_t)tid, s_wave, s_sel, target);
+    if (s_sel->found) return true;
+    // The cut lies below the window.  Top-byte totals: the window's bytes from its ranges (256
+    // threads, four waves, each), the others from the top-byte bins; then that byte's level.
+    unsigned long long wave_mass = mine;
+#pragma unroll
+    for (int mask = 1; mask < 64; mask <<= 1) wave_mass += shfl_xor_u64(wave_mass, mask);
+    if (lane == 0) s_wave[wave] = wave_mass;
+    __syncthreads();
+    if (tid < kBins) {
+        unsigned long long t = below;
+        const uint32_t below_top = (top16 >> 8) - (uint32_t)tid;  // 0 for the window's highest byte
+        if (below_top < (uint32_t)kWindowBytes)
+            for (int w = 0; w < 4; ++w) t += s_wave[below_top * 4 + w];
+        s_tot[tid] = t;
+    }
+    __syncthreads();
+    const int bin = kBins - 1 - tid;
+    scan_select(tid < kBins ? s_tot[bin] : 0ull, (uint32_t)bin, s_wave, s_sel, target);
+    radix_level<T, 16, false>(row, p, nk, s_hist, s_tot, s_wave, s_sel, target);
+    return true;
 }
 
 // RAW: also accumulate sum exp(x - max) at temperature 1 for raw_logprob_out (needed only when
@@ -427,7 +603,7 @@ __global__ __launch_bounds__(kThreads) void sample_rows(const T* __restrict__ lo
                                                          int32_t* __restrict__ tokens_out,
                                                          float* __restrict__ logprob_out,
                                                          float* __restrict__ raw_logprob_out, SampleParams p) {
-    __shared__ unsigned long long s_hist[TOPP ? kBins * kCopies : 1];
+    __shared__ __align__(16) unsigned long long s_hist[TOPP ? kHistSlots : 1];
     __shared__ unsigned long long s_tot[TOPP ? kBins : 1];
     __shared__ unsigned long long s_wave[kWavesPerBlock];
     __shared__ Select s_sel;
@@ -493,33 +669,39 @@ __global__ __launch_bounds__(kThreads) void sample_rows(const T* __restrict__ lo
     Race<false, false, true> race_kept{p, row_id, -INFINITY, 0.f};
     if (TOPP) {
         const float xM = s_m[0];
+        const float nkM = ref_offset(xM, p.k2);
         constexpr int kKeyBits = Elem<T>::kKeyBits;
         unsigned long long target = 0;
-        // Levels from the most significant digit down; the last level may be narrower.
-        radix_level<T, 24, true>(row, p, xM, s_hist, s_tot, s_wave, &s_sel, target);
-        radix_level<T, 16, false>(row, p, xM, s_hist, s_tot, s_wave, &s_sel, target);
+        // The upper 16 key bits from the window sweep, or, when the cut lies below the window,
+        // byte by byte from the most significant one; then the lower 16 of an fp32 key.
+        if (!window_level<T>(row, p, xM, nkM, s_hist, s_tot, s_wave, &s_sel, target)) {
+            radix_level<T, 24, true>(row, p, nkM, s_hist, s_tot, s_wave, &s_sel, target);
+            radix_level<T, 16, false>(row, p, nkM, s_hist, s_tot, s_wave, &s_sel, target);
+        }
         if (kKeyBits == 32) {
-            radix_level<T, 8, false>(row, p, xM, s_hist, s_tot, s_wave, &s_sel, target);
-            radix_level<T, 0, false>(row, p, xM, s_hist, s_tot, s_wave, &s_sel, target);
+            radix_level<T, 8, false>(row, p, nkM, s_hist, s_tot, s_wave, &s_sel, target);
+            radix_level<T, 0, false>(row, p, nkM, s_hist, s_tot, s_wave, &s_sel, target);
         }
         if (tid == 0) {
             // s_sel.prefix is now the key of the cut value (its upper 16 bits for bf16, whose
             // lower key bits are all ones for negative values and zero otherwise).  The kept
-            // mass is everything above the cut plus the cut value's own class, which is the
-            // selected bin of the last level.
+            // mass is everything above the cut plus the cut value's own class.
             const uint32_t key = (s_sel.prefix << (32 - kKeyBits)) |
                                  (kKeyBits == 16 ? ((s_sel.prefix >> 15) ? 0u : 0xFFFFu) : 0u);
             s_xcut = key_to_float(key);
-            const uint32_t digit = s_sel.prefix & (kBins - 1u);
-            const unsigned long long kept = s_sel.above + s_tot[digit];
-            s_lse = (double)xM / p.temperature + log((double)kept * 0x1p-40);
+            s_lse = (log2((double)s_sel.kept * 0x1p-40) - (double)nkM) / kLog2ed;
         }
         __syncthreads();
         race_kept.block_thr_key = &s_thr_key;  // still -inf: no race has run in this launch
         race_kept.x_cut = s_xcut;
         race_kept.set_ref(xM);
         race_kept.refresh_c();
-        sweep<T>(row, p.V, race_kept);
+        static_assert(kWavesPerBlock * kQueueBytesPerWave <= kHistSlots * 8, "the queues reuse the histogram");
+        CompactRace<Race<false, false, true>> gathered{
+            race_kept, (float*)s_hist + wave * (kQueueCap * 4),
+            (uint32_t*)s_hist + kWavesPerBlock * (kQueueCap * 4) + wave * kQueueCap};
+        sweep<T>(row, p.V, gathered);
+        gathered.finish();
     }
 
     // Block arg-max of the exact perturbed values (lowest index on ties).
@@ -545,8 +727,7 @@ __global__ __launch_bounds__(kThreads) void sample_rows(const T* __restrict__ lo
             } else {
                 tokens_out[r] = bi;
                 const double x = (double)Elem<T>::widen(row[bi]);
-                const double z = TOPP ? x / p.temperature : x * (double)p.k2 / kLog2ed;
-                const float lp = (float)(z - s_lse);
+                const float lp = (float)(x * (double)p.k2 / kLog2ed - s_lse);
                 logprob_out[r] = lp;
                 // without an extra sum the sampled distribution is the raw one (T = 1, top_p = 1)
                 if (raw_logprob_out) raw_logprob_out[r] = RAW ? (float)(x - s_raw_lse) : lp;

@@ -107,3 +107,33 @@ def test_policy_version_tag_is_recorded_beside_the_logprob():
         t, lp = run_sample(logits, 1.0, 1.0, 9, step)
         assert np.array_equal(t, toks[step].cpu().numpy())
         assert np.array_equal(lp, lps[step].double().cpu().numpy())
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_top_p_cut_at_every_depth_of_the_row(dtype):
+    # Rows built so that the cut value falls (0) within the same binade as the max, (1) a few
+    # binades below it, (2) at tiny positive values, (3) at negative values, (4) in a row whose
+    # max is zero with both signed zeros present, (5) in a row of one repeated value, (6) in a
+    # sorted row (descending, then (7) ascending), (8) in a row with a single finite entry.
+    g = torch.Generator().manual_seed(77)
+    V = 6000
+    rows = []
+    base = torch.randn((V,), generator=g)
+    rows.append(8.0 + 0.5 * base)                                   # 0: everything in [4, 16)
+    rows.append(torch.where(torch.arange(V) < 40, 6.0 + base, 0.05 * base.abs() + 0.02))   # 1
+    rows.append(torch.where(torch.arange(V) < 3, 1.0 + 0 * base, 1e-4 * (1 + base.abs())))  # 2
+    rows.append(base * 3.0 - 4.0)                                    # 3: mostly negative
+    z = -base.abs() * 2.0
+    z[::7] = 0.0
+    z[3::7] = -0.0
+    rows.append(z)                                                   # 4
+    rows.append(torch.full((V,), -1.25))                             # 5
+    rows.append(torch.sort(base * 2.0, descending=True).values)      # 6
+    rows.append(torch.sort(base * 2.0).values)                       # 7
+    one = torch.full((V,), float("-inf"))
+    one[4321] = -3.0
+    rows.append(one)                                                 # 8
+    lg = torch.stack(rows).to(dtype).contiguous()
+    for T, p in [(1.0, 0.9), (0.6, 0.5), (1.7, 0.999), (1.0, 0.02)]:
+        for step in range(3):
+            compare_sampling(lg, T, p, seed=1234, step=step)
