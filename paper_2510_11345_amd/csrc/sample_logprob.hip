@@ -260,9 +260,9 @@ struct Race {
         }
         (void)active;  // an inactive lane's logits are -inf: they add nothing and cannot pass
         const float (&xa)[N] = x;
+        float vmax = xa[0];
         if (LSE) {  // move the reference to the running max when some lane's max grew (rare after
                     // the first vectors; the sums are rescaled only then)
-            float vmax = xa[0];
 #pragma unroll
             for (int j = 1; j < N; ++j) vmax = fmaxf(vmax, xa[j]);
             if (__any(vmax > xref)) {
@@ -293,14 +293,27 @@ struct Race {
             refresh_c();
             seeded = true;
         }
-        bool pass[N];
-        bool any_pass = false;
+        float e[N];
 #pragma unroll
         for (int j = 0; j < N; ++j) {
             // The exponent keeps full relative accuracy near the reference: the product is not
             // rounded before nk is added.  -inf entries give 0.
-            const float e = __builtin_amdgcn_exp2f(fmaf(xa[j], p.k2, nk));
-            if (LSE) s += e;
+            e[j] = __builtin_amdgcn_exp2f(fmaf(xa[j], p.k2, nk));
+            if (LSE) s += e[j];
+        }
+        if (LSE && N > 1) {
+            // The vector's largest word against its largest exponential: no entry can pass the
+            // test below unless this pair does.
+            uint32_t wmax = words[0];
+#pragma unroll
+            for (int j = 1; j < N; ++j) wmax = wmax > words[j] ? wmax : words[j];
+            const float emax = __builtin_amdgcn_exp2f(fmaf(vmax, p.k2, nk));
+            if (!__any((float)wmax >= fmaf(-emax, c, 8388606.5f * 512.f))) return;
+        }
+        bool pass[N];
+        bool any_pass = false;
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
             // With k = word >> 9, 1 - u = (2^23 - 1 - k + 0.5) 2^-23, so 1 - u <= e exp2(..) reads
             // k >= 2^23 - 0.5 - e exp2(..) 2^23.  Both sides are taken times 2^9: the whole word
             // converted to fp32 (rounded to nearest) is at least k 2^9, and the right side is
@@ -308,7 +321,7 @@ struct Race {
             // quarter unit), so the test can only let an extra entry through, never hold a winner
             // back.  e = 0 (an entry more than 126 binary orders below a logit of the same row,
             // which the 28 orders a draw can add never make up) with c = inf gives NaN: no pass.
-            pass[j] = (float)words[j] >= fmaf(-e, c, 8388606.5f * 512.f) && (!CUT || x[j] >= x_cut);
+            pass[j] = (float)words[j] >= fmaf(-e[j], c, 8388606.5f * 512.f) && (!CUT || x[j] >= x_cut);
             if (j == 0) pass[j] = pass[j] && !seeded;
             any_pass = any_pass || pass[j];
         }
