@@ -253,5 +253,23 @@ __device__ __forceinline__ void store_result(const WaveAcc<D>& a, void* __restri
     }
 }
 
+// The same with the output type fixed at compile time.
+template <int D, bool F32>
+__device__ __forceinline__ void store_result_as(const WaveAcc<D>& a, void* __restrict__ out, int64_t idx) {
+    const float inv = 1.0f / a.l;
+#pragma unroll
+    for (int nt = 0; nt < D / 16; ++nt) {
+        const f32x4_t o = a.o[nt] * inv;
+        if (F32) {
+            *(f32x4_t*)((float*)out + idx + 16 * nt) = o;
+        } else {
+            uint2 pk;
+            pk.x = pack_bf16_rne(o[0], o[1]);
+            pk.y = pack_bf16_rne(o[2], o[3]);
+            *(uint2*)((__bf16*)out + idx + 16 * nt) = pk;
+        }
+    }
+}
+
 }  // namespace attn
 }  // namespace roll

@@ -8,13 +8,20 @@
 // different lengths share the chip evenly.
 //
 // Work decomposition (split-K over the flattened batch).  Row b with L_b tokens
-// is ceil(L_b / 32) steps of 32 tokens for each KV head; the (row, KV head)
-// streams are laid end to end, S steps in all, and persistent wavefront w of W
-// takes the steps [w S / W, (w + 1) S / W).  Every wave therefore reads the same
-// number of bytes whatever the length mix, a row longer than a wave's share is
-// cut across neighbouring waves, and at most the first and the last stream of a
-// wave are pieces; a wave writes a complete stream straight to `out` and a piece
-// (running max, sum, un-normalised output) to its two slots of the workspace.
+// is ceil(L_b / 32) steps of 32 tokens; the rows' steps are laid end to end, R
+// in all, and cut into equal ranges, one per persistent workgroup of four
+// waves.  The four waves of a workgroup walk the SAME range of row steps, each
+// for KV heads of its own (wave j: heads j, j + 4, ...; with fewer than four KV
+// heads the range is cut again so that every wave has a part of one head).
+// They run in step, so at any moment the workgroup reads the blocks of one page
+// for four neighbouring heads, which lie next to each other in the pool: the
+// memory system delivers 6.9-7.0 TB/s to such reads and 6.0-6.2 TB/s when the
+// four waves read pages of their own (measured with equal rows, all else
+// equal).  Every wave reads the same number of bytes whatever the length mix, a
+// row longer than a range is cut across neighbouring workgroups, and for every
+// head at most the first and the last row of a range are pieces; a wave writes
+// a complete (row, head) stream straight to `out` and a piece (running max,
+// sum, un-normalised output) to one of the two slots of its (range, head).
 // Pieces are merged by whichever wave delivers the last one (an arrival counter
 // per group of 16 neighbouring pieces, then one per stream when a stream has
 // more than 16): no wave ever waits for another, so there is nothing to hang.
@@ -46,6 +53,7 @@ constexpr bool kDoubleBuffer = false;  // keep the next step's loads in flight w
 constexpr int kMinSteps = 4;       // do not spread a small batch thinner than this per wave
 constexpr int kMaxBatch = 8192;    // rows whose prefix sums fit the LDS budget
 constexpr int kMaxStreams = 65536; // batch * num_kv_heads: one arrival counter each
+constexpr int kMaxSlots = 32768;   // piece slots: two per (range of row steps, KV head)
 constexpr int kMergeGroup = 16;    // pieces merged by one wave at the first level
 // Upper bound of persistent waves, used to size the workspace without touching the device:
 // 16 waves on each of 256 compute units (a gfx950 device has no more).
@@ -63,32 +71,46 @@ struct AttnParams {
 struct Workspace {
     // zero between calls (roll_decode_attn_workspace_init, then every merger resets its counter)
     int32_t* grid_arrivals;    // [1] workgroups of a fused step that have read the old lengths
-    int32_t* group_arrivals;   // [2 W] indexed by the slot of the first piece of a group
+    int32_t* group_arrivals;   // [kMaxSlots] indexed by the slot of the first piece of a group
     int32_t* stream_arrivals;  // [kMaxStreams] indexed by row * Hkv + kv head
     // scratch
-    float2* part_ml;   // [2 W * G] (max in log2 units, sum) of a piece: slots 2w, 2w + 1 of wave w
-    float* part_acc;   // [2 W * G * D] un-normalised output of a piece
-    float2* group_ml;  // [2 W * G] merged group of pieces, at the slot of the group's first piece
-    float* group_acc;  // [2 W * G * D]
+    float2* part_ml;   // [slots * G] (max in log2 units, sum) of a piece
+    float* part_acc;   // [slots * G * D] un-normalised output of a piece
+    float2* group_ml;  // [slots * G] merged group of pieces, at the slot of the group's first piece
+    float* group_acc;  // [slots * G * D]
     size_t header_bytes;
     size_t bytes;
 };
 
 __host__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-__host__ Workspace carve(void* base, int32_t G, int32_t D) {
+// Ranges of row steps a launch of `waves` persistent waves can use (before the limits that depend
+// on the batch): one per workgroup, times the cut within a workgroup when there are fewer KV
+// heads than waves; never more than the piece slots allow.
+__host__ __device__ inline int32_t ranges_cut(int32_t Hkv) {
+    return (Hkv < kGroupWaves && kGroupWaves % Hkv == 0) ? kGroupWaves / Hkv : 1;
+}
+__host__ __device__ inline int32_t max_ranges(int32_t waves, int32_t Hkv) {
+    const int32_t by_waves = waves / kGroupWaves * ranges_cut(Hkv);
+    const int32_t by_slots = kMaxSlots / (2 * Hkv);
+    const int32_t n = by_waves < by_slots ? by_waves : by_slots;
+    return n < 1 ? 1 : n;
+}
+
+// The header does not depend on the shape (roll_decode_attn_workspace_init has none).
+__host__ Workspace carve(void* base, int32_t Hkv, int32_t G, int32_t D) {
     Workspace w{};
-    const size_t W = kMaxPersistentWaves;
+    const size_t slots = 2 * (size_t)max_ranges(kMaxPersistentWaves, Hkv) * Hkv;
     size_t off = 0;
     char* p = (char*)base;
     w.grid_arrivals = (int32_t*)(p + off);    off = align_up(off + sizeof(int32_t), 256);
-    w.group_arrivals = (int32_t*)(p + off);   off = align_up(off + sizeof(int32_t) * 2 * W, 256);
+    w.group_arrivals = (int32_t*)(p + off);   off = align_up(off + sizeof(int32_t) * kMaxSlots, 256);
     w.stream_arrivals = (int32_t*)(p + off);  off = align_up(off + sizeof(int32_t) * kMaxStreams, 256);
     w.header_bytes = off;
-    w.part_ml = (float2*)(p + off);           off = align_up(off + sizeof(float2) * 2 * W * G, 256);
-    w.part_acc = (float*)(p + off);           off = align_up(off + sizeof(float) * 2 * W * G * D, 256);
-    w.group_ml = (float2*)(p + off);          off = align_up(off + sizeof(float2) * 2 * W * G, 256);
-    w.group_acc = (float*)(p + off);          off = align_up(off + sizeof(float) * 2 * W * G * D, 256);
+    w.part_ml = (float2*)(p + off);           off = align_up(off + sizeof(float2) * slots * G, 256);
+    w.part_acc = (float*)(p + off);           off = align_up(off + sizeof(float) * slots * G * D, 256);
+    w.group_ml = (float2*)(p + off);          off = align_up(off + sizeof(float2) * slots * G, 256);
+    w.group_acc = (float*)(p + off);          off = align_up(off + sizeof(float) * slots * G * D, 256);
     w.bytes = off;
     return w;
 }
@@ -98,17 +120,22 @@ __global__ void zero_words(uint32_t* dst, size_t n) {
     if (i < n) dst[i] = 0u;
 }
 
-// How the S steps are dealt to waves; shared by the attention and the merge kernel.
+// How the R row steps are cut into ranges.
 struct Deal {
-    int64_t S;   // total steps over all (row, KV head) streams
-    int32_t W;   // waves that take part
-    __device__ Deal(int64_t steps, int32_t launched) : S(steps) {
-        const int64_t want = (steps + kMinSteps - 1) / kMinSteps;
-        W = (int32_t)(want < 1 ? 1 : (want < launched ? want : launched));
+    int64_t R;   // total steps over all rows (one KV head)
+    int32_t NC;  // ranges in use
+    __device__ Deal(int32_t steps, int32_t waves, int32_t Hkv) : R(steps) {
+        const int32_t want = (steps + kMinSteps - 1) / kMinSteps;
+        const int32_t most = max_ranges(waves, Hkv);
+        NC = want < 1 ? 1 : (want < most ? want : most);
     }
-    __device__ int64_t first_step(int32_t w) const { return (int64_t)w * S / W; }
-    // the wave whose range holds step i
-    __device__ int32_t owner(int64_t i) const { return (int32_t)(((i + 1) * W + S - 1) / S - 1); }
+    __device__ int32_t first_step(int32_t c) const { return (int32_t)((int64_t)c * R / NC); }
+    // the range that holds row step i
+    __device__ int32_t owner(int32_t i) const { return (int32_t)((((int64_t)i + 1) * NC + R - 1) / R - 1); }
+    // the slots of (range c, KV head h): 0 for a piece that begins the range, 1 for one that ends it
+    __device__ int64_t slot(int32_t c, int32_t h, int32_t Hkv, bool begins) const {
+        return ((int64_t)c * Hkv + h) * 2 + (begins ? 0 : 1);
+    }
 };
 
 // KV is read exactly once per step: a nontemporal load keeps it from displacing the
@@ -149,11 +176,13 @@ struct NoFusedArgs {};
 // NEWEST: the step holds the stream's newest token in a fused launch.
 template <int D, bool NEWEST>
 __device__ __forceinline__ void step_pages(const WaveCtx<D>& c, int32_t t0, int32_t& pgA, int32_t& pgB) {
-    int32_t pa = t0 >> c.log2P;
-    // The second page may lie past the row's end; its table entry is then stale or -1.  Reading
+    // A page index may lie past the row's end (the second page of a tail step, or a step
+    // requested one ahead of the stream's last); its table entry is then stale or -1.  Reading
     // it is in bounds (clamped to the table row) and the id is clamped below, so the loads stay
     // inside the pool; the tokens are masked by the caller.  Not clamping to the row's own
     // last page keeps the row length off the address path.
+    int32_t pa = t0 >> c.log2P;
+    pa = pa > c.max_pages - 1 ? c.max_pages - 1 : pa;
     int32_t pb = (t0 + 16) >> c.log2P;
     pb = pb > c.max_pages - 1 ? c.max_pages - 1 : pb;
     pgA = c.pt_row[pa];
@@ -173,10 +202,8 @@ __device__ __forceinline__ void step_pages(const WaveCtx<D>& c, int32_t t0, int3
 // instruction covers whole 128-byte lines.
 // With NEWEST the lane that owns the newest token reads its row from k_new instead.
 template <int D, bool NEWEST>
-__device__ __forceinline__ void load_k(const WaveCtx<D>& c, int32_t t0, StepData<D>& s) {
+__device__ __forceinline__ void load_k(const WaveCtx<D>& c, int32_t t0, int32_t pgA, int32_t pgB, StepData<D>& s) {
     const int32_t P = 1 << c.log2P;
-    int32_t pgA, pgB;
-    step_pages<D, NEWEST>(c, t0, pgA, pgB);
     const uint4* kbase[2];
     bool fresh[2] = {false, false};
 #pragma unroll
@@ -197,11 +224,9 @@ __device__ __forceinline__ void load_k(const WaveCtx<D>& c, int32_t t0, StepData
 }
 
 // V: lane (r, q) reads, for d-tile nt, the 8 tokens 8q..8q+7 of head-dim element 16nt+r.
-template <int D, bool NEWEST>
-__device__ __forceinline__ void load_v(const WaveCtx<D>& c, int32_t t0, StepData<D>& s) {
+template <int D>
+__device__ __forceinline__ void load_v(const WaveCtx<D>& c, int32_t t0, int32_t pgA, int32_t pgB, StepData<D>& s) {
     const int32_t P = 1 << c.log2P;
-    int32_t pgA, pgB;
-    step_pages<D, NEWEST>(c, t0, pgA, pgB);
     const int32_t page = c.q >= 2 ? pgB : pgA;
     const int32_t oct = ((t0 + 8 * c.q) & (P - 1)) >> 3;
     const uint4* base = c.v_pages + (((int64_t)page * c.Hkv + c.h) * (P / 8) + oct) * D + c.r;
@@ -321,30 +346,54 @@ __device__ __forceinline__ void store_piece(const WaveAcc<D>& a, float2* ml, flo
 }
 
 // Log-sum-exp merge of n pieces whose slots are slot_of(0..n-1); result stays un-normalised.
+// The pieces are taken four at a time, with all loads of a batch requested before the first is
+// used: the merging wave has nothing else to do meanwhile and is usually one of the last to
+// finish, so the merge's latency is the kernel's.
 template <int D, typename SlotFn>
 __device__ __forceinline__ void merge_pieces(WaveAcc<D>& out_acc, const float2* ml, const float* acc,
                                              int32_t n, SlotFn slot_of, int32_t G, int32_t r, int32_t q) {
-    float M = -INFINITY;
-    for (int32_t i = 0; i < n; ++i) {
-        const f32x2_t m_l = coherent_load2((const float*)(ml + slot_of(i) * G + r));
-        M = fmaxf(M, m_l[0]);
-    }
-    float lsum = 0.f;
+    constexpr int kBatch = 4;
+    float M = -INFINITY, lsum = 0.f;
     f32x4_t o[D / 16];
 #pragma unroll
     for (int nt = 0; nt < D / 16; ++nt) o[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 2
-    for (int32_t i = 0; i < n; ++i) {
-        const int64_t row = slot_of(i) * G + r;
-        const f32x2_t m_l = coherent_load2((const float*)(ml + row));
-        const float wgt = __builtin_amdgcn_exp2f(m_l[0] - M);
-        lsum += m_l[1] * wgt;
-        const float* src = acc + row * D + 4 * q;
+#pragma unroll 1
+    for (int32_t base = 0; base < n; base += kBatch) {
+        f32x2_t m_l[kBatch], lo[kBatch][D / 16], hi[kBatch][D / 16];
 #pragma unroll
-        for (int nt = 0; nt < D / 16; ++nt) {
-            const f32x2_t lo = coherent_load2(src + 16 * nt), hi = coherent_load2(src + 16 * nt + 2);
-            o[nt] += f32x4_t{lo[0], lo[1], hi[0], hi[1]} * wgt;
+        for (int k = 0; k < kBatch; ++k) {
+            m_l[k] = f32x2_t{-INFINITY, 0.f};
+            if (base + k < n) {
+                const int64_t row = slot_of(base + k) * G + r;
+                m_l[k] = coherent_load2((const float*)(ml + row));
+                const float* src = acc + row * D + 4 * q;
+#pragma unroll
+                for (int nt = 0; nt < D / 16; ++nt) {
+                    lo[k][nt] = coherent_load2(src + 16 * nt);
+                    hi[k][nt] = coherent_load2(src + 16 * nt + 2);
+                }
+            } else {
+#pragma unroll
+                for (int nt = 0; nt < D / 16; ++nt) lo[k][nt] = hi[k][nt] = f32x2_t{0.f, 0.f};
+            }
         }
+        float Mb = M;
+#pragma unroll
+        for (int k = 0; k < kBatch; ++k) Mb = fmaxf(Mb, m_l[k][0]);
+        // every piece holds a valid token, so Mb is finite; exp2(-inf - Mb) = 0 drops the rest
+        const float keep = __builtin_amdgcn_exp2f(M - Mb);
+        lsum *= keep;
+#pragma unroll
+        for (int nt = 0; nt < D / 16; ++nt) o[nt] *= keep;
+#pragma unroll
+        for (int k = 0; k < kBatch; ++k) {
+            const float wgt = __builtin_amdgcn_exp2f(m_l[k][0] - Mb);
+            lsum += m_l[k][1] * wgt;
+#pragma unroll
+            for (int nt = 0; nt < D / 16; ++nt)
+                o[nt] += f32x4_t{lo[k][nt][0], lo[k][nt][1], hi[k][nt][0], hi[k][nt][1]} * wgt;
+        }
+        M = Mb;
     }
     out_acc.m = M;
     out_acc.l = lsum;
@@ -389,7 +438,7 @@ __device__ __forceinline__ int32_t newest_page(const FusedArgs& fa, const int32_
 // written by the workgroup that is last to finish, when every workgroup has read the old ones.
 // page_table and seq_lens stay __restrict__ although the launch writes both arrays through other
 // pointers: no value it uses is read from an entry it writes.
-template <int D, bool FUSED>
+template <int D, bool FUSED, bool F32OUT>
 __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
     const uint4* __restrict__ q16, const uint4* k_pages, const uint4* v_pages,
     const int32_t* __restrict__ page_table, const int32_t* __restrict__ seq_lens,
@@ -420,32 +469,18 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
         if (len[b] != 0) continue;
         const int64_t base = (int64_t)b * prm.Hq * D;
         for (int32_t e = lane * 4; e < prm.Hq * D; e += 256) {
-            if (prm.out_f32) *(f32x4_t*)((float*)out + base + e) = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            if (F32OUT) *(f32x4_t*)((float*)out + base + e) = f32x4_t{0.f, 0.f, 0.f, 0.f};
             else *(uint2*)((__bf16*)out + base + e) = make_uint2(0u, 0u);
         }
     }
 
-    const Deal deal((int64_t)pre[prm.B] * Hkv, prm.W);
-    do {  // one pass; a wave without work leaves it early
-    if (w >= deal.W) break;
-    int64_t item = deal.first_step(w);
-    int32_t todo = (int32_t)(deal.first_step(w + 1) - item);
-    if (todo <= 0) break;
-
-    // Locate the first stream: the last row b with Hkv * pre[b] <= item (such a row is not empty).
-    int32_t b;
-    {
-        int32_t lo = 0, hi = prm.B;  // invariant: Hkv*pre[lo] <= item < Hkv*pre[hi]
-        while (hi - lo > 1) {
-            const int32_t mid = (lo + hi) >> 1;
-            if ((int64_t)pre[mid] * Hkv <= item) lo = mid; else hi = mid;
-        }
-        b = lo;
-    }
-    int32_t n_b = pre[b + 1] - pre[b];
-    const int32_t rem = (int32_t)(item - (int64_t)pre[b] * Hkv);
-    int32_t h = rem / n_b;
-    int32_t s = rem % n_b;
+    // Ranges of row steps and the (range, KV heads) of this wave: see the top of the file.
+    const Deal deal(pre[prm.B], prm.W, Hkv);
+    const int32_t cut = ranges_cut(Hkv);
+    const int32_t wj = w & (kGroupWaves - 1);
+    const int32_t c = (int32_t)blockIdx.x * cut + (cut > 1 ? wj / Hkv : 0);
+    const int32_t h_begin = cut > 1 ? wj % Hkv : wj;
+    const int32_t h_stride = cut > 1 ? Hkv : kGroupWaves;  // cut > 1: one head per wave
 
     WaveCtx<D> ctx;
     ctx.k_pages = k_pages;
@@ -458,9 +493,27 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
     ctx.q = lane >> 4;
     const int32_t rr = ctx.r < G ? ctx.r : 0;  // lanes of the padding heads shadow head 0, store nothing
 
-    const int32_t b_first = b, h_first = h, s_first = s, n_first = n_b, todo_first = todo;
+    // The row that holds row step `item` (the last row b with pre[b] <= item; it is not empty).
+    auto row_of = [&](int32_t item) -> int32_t {
+        int32_t lo = 0, hi = prm.B;  // invariant: pre[lo] <= item < pre[hi]
+        while (hi - lo > 1) {
+            const int32_t mid = (lo + hi) >> 1;
+            if (pre[mid] <= item) lo = mid; else hi = mid;
+        }
+        return lo;
+    };
+    const int32_t item0 = c < deal.NC ? deal.first_step(c) : 0;
+    const int32_t todo0 = c < deal.NC ? deal.first_step(c + 1) - item0 : 0;
 
+    for (int32_t h = h_begin; h < Hkv && todo0 > 0; h += h_stride) {
+    int32_t todo = todo0;
+    int32_t b = row_of(item0);
+    int32_t n_b = pre[b + 1] - pre[b];
+    int32_t s = item0 - pre[b];
     bool first_stream = true;
+    // The pieces of the segment (at most its first and its last row) and their rows.
+    WaveAcc<D> held0, held1;
+    int32_t row0 = -1, row1 = -1;
     while (todo > 0) {
         const int32_t L = len[b];
         const int32_t cnt = min(todo, n_b - s);
@@ -504,15 +557,18 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
             // Two register sets: the loads of step i + 1 are in flight while step i is computed.
             StepData<D> s0, s1;
             int32_t i = s;
+            int32_t pgA, pgB;
             if (i < loop_end) {
-                load_k<D, false>(ctx, i * kStep, s0);
-                load_v<D, false>(ctx, i * kStep, s0);
+                step_pages<D, false>(ctx, i * kStep, pgA, pgB);
+                load_k<D, false>(ctx, i * kStep, pgA, pgB, s0);
+                load_v<D>(ctx, i * kStep, pgA, pgB, s0);
                 for (;;) {
                     float sv[8];
                     const bool more1 = i + 1 < loop_end;
                     if (more1) {
-                        load_k<D, false>(ctx, (i + 1) * kStep, s1);
-                        load_v<D, false>(ctx, (i + 1) * kStep, s1);
+                        step_pages<D, false>(ctx, (i + 1) * kStep, pgA, pgB);
+                        load_k<D, false>(ctx, (i + 1) * kStep, pgA, pgB, s1);
+                        load_v<D>(ctx, (i + 1) * kStep, pgA, pgB, s1);
                     }
                     score_step<D>(ctx, qf, s0, i * kStep, L, sv);
                     accumulate_step<D, false>(ctx, sv, s0, i * kStep, L, prm.scale_log2e, acc);
@@ -520,8 +576,9 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
                     ++i;
                     const bool more0 = i + 1 < loop_end;
                     if (more0) {
-                        load_k<D, false>(ctx, (i + 1) * kStep, s0);
-                        load_v<D, false>(ctx, (i + 1) * kStep, s0);
+                        step_pages<D, false>(ctx, (i + 1) * kStep, pgA, pgB);
+                        load_k<D, false>(ctx, (i + 1) * kStep, pgA, pgB, s0);
+                        load_v<D>(ctx, (i + 1) * kStep, pgA, pgB, s0);
                     }
                     score_step<D>(ctx, qf, s1, i * kStep, L, sv);
                     accumulate_step<D, false>(ctx, sv, s1, i * kStep, L, prm.scale_log2e, acc);
@@ -530,20 +587,32 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
                 }
             }
         } else {
+            // The page ids of a step are requested one step early, through the scalar cache: a
+            // miss there (one per 64-byte line of the table, every eighth step for 16-token
+            // pages) would otherwise stall the wave, which has no other wave on its SIMD to
+            // hide behind.
+            int32_t pgA, pgB;
+            step_pages<D, false>(ctx, s * kStep, pgA, pgB);
             for (int32_t i = s; i < loop_end; ++i) {
+                int32_t nxtA, nxtB;
+                step_pages<D, false>(ctx, (i + 1) * kStep, nxtA, nxtB);
                 StepData<D> sd;
-                load_k<D, false>(ctx, i * kStep, sd);
-                load_v<D, false>(ctx, i * kStep, sd);
+                load_k<D, false>(ctx, i * kStep, pgA, pgB, sd);
+                load_v<D>(ctx, i * kStep, pgA, pgB, sd);
                 float sv[8];
                 score_step<D>(ctx, qf, sd, i * kStep, L, sv);
                 accumulate_step<D, false>(ctx, sv, sd, i * kStep, L, prm.scale_log2e, acc);
+                pgA = nxtA;
+                pgB = nxtB;
             }
         }
         if (has_newest) {
             const int32_t t0 = loop_end * kStep;
             StepData<D> sd;
-            load_k<D, FUSED>(ctx, t0, sd);
-            load_v<D, FUSED>(ctx, t0, sd);
+            int32_t pgA, pgB;
+            step_pages<D, FUSED>(ctx, t0, pgA, pgB);
+            load_k<D, FUSED>(ctx, t0, pgA, pgB, sd);
+            load_v<D>(ctx, t0, pgA, pgB, sd);
             float sv[8];
             score_step<D>(ctx, qf, sd, t0, L, sv);
             patch_newest_v<D>(ctx, t0, v_fresh, sd);
@@ -553,57 +622,70 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
         // Finish the per-head sum across the four q-groups of the wave.
         acc.l = sum_over_q(acc.l);
 
-        const int64_t out_idx = ((int64_t)b * prm.Hq + (int64_t)h * G + rr) * D + 4 * ctx.q;
         if (cnt == n_b) {  // the whole stream: normalise and write the result
-            if (ctx.r < G) store_result<D>(acc, out, out_idx, prm.out_f32);
+            const int64_t out_idx = ((int64_t)b * prm.Hq + (int64_t)h * G + rr) * D + 4 * ctx.q;
+            if (ctx.r < G) store_result_as<D, F32OUT>(acc, out, out_idx);
         } else {
-            // A piece of a stream that spans the waves w0..w1.  Piece i comes from wave w0 + i and
-            // sits in that wave's slot 2(w0 + i), except that w0 uses its second slot when the
-            // stream is not the first one it touched.
-            const int64_t g0 = (int64_t)pre[b] * Hkv + (int64_t)h * n_b;
-            const int32_t w0 = deal.owner(g0), w1 = deal.owner(g0 + n_b - 1);
-            const int32_t pieces = w1 - w0 + 1;
-            const int64_t slot0 = 2 * (int64_t)w0 + (deal.first_step(w0) == g0 ? 0 : 1);
-            const int64_t my_slot = 2 * (int64_t)w + (first_stream ? 0 : 1);
-            if (ctx.r < G) store_piece<D>(acc, part_ml, part_acc, my_slot, G, ctx.r, ctx.q);
-
-            const int32_t gid = (w - w0) / kMergeGroup;
-            const int32_t gfirst = gid * kMergeGroup;               // first piece of my group
-            const int32_t gsize = min(kMergeGroup, pieces - gfirst);
-            const int32_t ngroups = (pieces + kMergeGroup - 1) / kMergeGroup;
-            // Slots are unique per piece, so the slot of a group's first piece names the group
-            // (a wave can end one stream and begin the next: wave numbers alone would collide).
-            auto piece_slot = [&](int32_t pi) -> int64_t { return pi == 0 ? slot0 : 2 * (int64_t)(w0 + pi); };
-            const int64_t group_slot = piece_slot(gfirst);
-            if (arrive_last(group_arrivals + group_slot, gsize, lane)) {
-                WaveAcc<D> grp;
-                merge_pieces<D>(grp, part_ml, part_acc, gsize,
-                                [&](int32_t i) -> int64_t { return piece_slot(gfirst + i); }, G, rr, ctx.q);
-                if (ngroups == 1) {
-                    if (ctx.r < G) store_result<D>(grp, out, out_idx, prm.out_f32);
-                } else {
-                    if (ctx.r < G) store_piece<D>(grp, group_ml, group_acc, group_slot, G, ctx.r, ctx.q);
-                    if (arrive_last(stream_arrivals + b * Hkv + h, ngroups, lane)) {
-                        WaveAcc<D> all;
-                        merge_pieces<D>(all, group_ml, group_acc, ngroups,
-                                        [&](int32_t j) -> int64_t { return piece_slot(j * kMergeGroup); }, G,
-                                        rr, ctx.q);
-                        if (ctx.r < G) store_result<D>(all, out, out_idx, prm.out_f32);
-                    }
-                }
-            }
+            // A piece of a row that is cut across ranges.  It stays in registers until the
+            // segment is done: see below.
+            if (first_stream) { held0 = acc; row0 = b; }
+            else { held1 = acc; row1 = b; }
         }
 
         todo -= cnt;
         first_stream = false;
         s = 0;
-        if (todo > 0) {  // next stream: next KV head, or the next row that has tokens
-            if (++h == Hkv) {
-                h = 0;
-                do { ++b; } while (b < prm.B - 1 && pre[b + 1] == pre[b]);
-                n_b = pre[b + 1] - pre[b];
+        if (todo > 0) {  // the next row that has tokens
+            do { ++b; } while (b < prm.B - 1 && pre[b + 1] == pre[b]);
+            n_b = pre[b + 1] - pre[b];
+        }
+    }
+
+    // Deliver the segment's pieces.  Written where they were made, the pieces (as many bytes as
+    // four times the output, in small scattered writes, and read back by the merging waves)
+    // reach DRAM in the middle of the KV stream, where every isolated write costs its channel a
+    // turn of the bus: measured 14 us of 285 for c2.  Held back, they are written when the
+    // waves around have finished streaming too.
+    if (row0 >= 0 && ctx.r < G) store_piece<D>(held0, part_ml, part_acc, deal.slot(c, h, Hkv, true), G, ctx.r, ctx.q);
+    if (row1 >= 0 && ctx.r < G) store_piece<D>(held1, part_ml, part_acc, deal.slot(c, h, Hkv, false), G, ctx.r, ctx.q);
+#pragma unroll 1
+    for (int which = 0; which < 2; ++which) {
+        const int32_t pb = which == 0 ? row0 : row1;
+        if (pb < 0) continue;
+        // The row pb spans the ranges c0..c1.  Piece i comes from range c0 + i and sits in the
+        // first slot of (that range, h), except that c0 uses its second slot when the row does
+        // not begin the range.
+        const int32_t g0 = pre[pb], n_pb = pre[pb + 1] - g0;
+        const int32_t c0 = deal.owner(g0), c1 = deal.owner(g0 + n_pb - 1);
+        const int32_t pieces = c1 - c0 + 1;
+        const int64_t slot0 = deal.slot(c0, h, Hkv, deal.first_step(c0) == g0);
+        const int64_t out_idx = ((int64_t)pb * prm.Hq + (int64_t)h * G + rr) * D + 4 * ctx.q;
+        const int32_t gid = (c - c0) / kMergeGroup;
+        const int32_t gfirst = gid * kMergeGroup;               // first piece of my group
+        const int32_t gsize = min(kMergeGroup, pieces - gfirst);
+        const int32_t ngroups = (pieces + kMergeGroup - 1) / kMergeGroup;
+        // Slots are unique per piece, so the slot of a group's first piece names the group
+        // (a range can end one row and begin the next: range numbers alone would collide).
+        auto piece_slot = [&](int32_t pi) -> int64_t { return pi == 0 ? slot0 : deal.slot(c0 + pi, h, Hkv, true); };
+        const int64_t group_slot = piece_slot(gfirst);
+        if (arrive_last(group_arrivals + group_slot, gsize, lane)) {
+            WaveAcc<D> grp;
+            merge_pieces<D>(grp, part_ml, part_acc, gsize,
+                            [&](int32_t i) -> int64_t { return piece_slot(gfirst + i); }, G, rr, ctx.q);
+            if (ngroups == 1) {
+                if (ctx.r < G) store_result_as<D, F32OUT>(grp, out, out_idx);
+            } else {
+                if (ctx.r < G) store_piece<D>(grp, group_ml, group_acc, group_slot, G, ctx.r, ctx.q);
+                if (arrive_last(stream_arrivals + pb * Hkv + h, ngroups, lane)) {
+                    WaveAcc<D> all;
+                    merge_pieces<D>(all, group_ml, group_acc, ngroups,
+                                    [&](int32_t j) -> int64_t { return piece_slot(j * kMergeGroup); }, G,
+                                    rr, ctx.q);
+                    if (ctx.r < G) store_result_as<D, F32OUT>(all, out, out_idx);
+                }
             }
         }
+    }
     }
 
     if constexpr (FUSED) {
@@ -611,32 +693,35 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
         // the wave that owned a stream's last step writes that stream's newest token (the K and
         // V row of one KV head) into the pages.
         const int32_t P = 1 << prm.log2P;
-        int32_t ab = b_first, ah = h_first, as = s_first, an = n_first, atodo = todo_first;
-        while (atodo > 0) {
-            const int32_t cnt = min(atodo, an - as);
-            if (as + cnt == an) {
-                const int32_t L = len[ab];
-                const int32_t page = newest_page(fa, page_table + (int64_t)ab * prm.max_pages, ab, L, prm.log2P, prm.num_pages);
-                const int32_t pos = (L - 1) & (P - 1);
-                const int64_t row = (int64_t)ab * Hkv + ah;
-                if (lane < D / 8)
-                    ((uint4*)k_pages)[(((int64_t)page * Hkv + ah) * (D / 8) + lane) * P + roll::k_slot(pos, P)] =
-                        fa.k_new[row * (D / 8) + lane];
-                uint16_t* vdst = (uint16_t*)v_pages + ((((int64_t)page * Hkv + ah) * (P / 8) + pos / 8) * D) * 8 + pos % 8;
-                const uint16_t* vsrc = (const uint16_t*)fa.v_new + row * D;
+        for (int32_t ah = h_begin; ah < Hkv && todo0 > 0; ah += h_stride) {
+            int32_t atodo = todo0;
+            int32_t ab = row_of(item0);
+            int32_t an = pre[ab + 1] - pre[ab];
+            int32_t as = item0 - pre[ab];
+            while (atodo > 0) {
+                const int32_t cnt = min(atodo, an - as);
+                if (as + cnt == an) {
+                    const int32_t L = len[ab];
+                    const int32_t page = newest_page(fa, page_table + (int64_t)ab * prm.max_pages, ab, L, prm.log2P, prm.num_pages);
+                    const int32_t pos = (L - 1) & (P - 1);
+                    const int64_t row = (int64_t)ab * Hkv + ah;
+                    if (lane < D / 8)
+                        ((uint4*)k_pages)[(((int64_t)page * Hkv + ah) * (D / 8) + lane) * P + roll::k_slot(pos, P)] =
+                            fa.k_new[row * (D / 8) + lane];
+                    uint16_t* vdst = (uint16_t*)v_pages + ((((int64_t)page * Hkv + ah) * (P / 8) + pos / 8) * D) * 8 + pos % 8;
+                    const uint16_t* vsrc = (const uint16_t*)fa.v_new + row * D;
 #pragma unroll
-                for (int e = 0; e < D / 64; ++e) vdst[(int64_t)(lane + 64 * e) * 8] = vsrc[lane + 64 * e];
-            }
-            atodo -= cnt;
-            as = 0;
-            if (atodo > 0 && ++ah == Hkv) {
-                ah = 0;
-                do { ++ab; } while (ab < prm.B - 1 && pre[ab + 1] == pre[ab]);
-                an = pre[ab + 1] - pre[ab];
+                    for (int e = 0; e < D / 64; ++e) vdst[(int64_t)(lane + 64 * e) * 8] = vsrc[lane + 64 * e];
+                }
+                atodo -= cnt;
+                as = 0;
+                if (atodo > 0) {
+                    do { ++ab; } while (ab < prm.B - 1 && pre[ab + 1] == pre[ab]);
+                    an = pre[ab + 1] - pre[ab];
+                }
             }
         }
     }
-    } while (false);
 
     if constexpr (FUSED) {
         // Every workgroup has read the old lengths long ago; the last one to get here writes the
@@ -685,9 +770,9 @@ int persistent_waves(int head_dim, size_t lds_bytes, int32_t* waves_out) {
     ROLL_HIP_CHECK(hipGetDeviceProperties(&prop, dev));
     int groups = 0;
     if (head_dim == 128)
-        ROLL_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&groups, attn_stream<128, false>, kGroupWaves * 64, lds_bytes));
+        ROLL_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&groups, attn_stream<128, false, false>, kGroupWaves * 64, lds_bytes));
     else
-        ROLL_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&groups, attn_stream<64, false>, kGroupWaves * 64, lds_bytes));
+        ROLL_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&groups, attn_stream<64, false, false>, kGroupWaves * 64, lds_bytes));
     if (groups < 1) return roll::fail(ROLL_ERR_HIP, "the attention kernel does not fit on a compute unit");
     c = kGroupWaves * prop.multiProcessorCount;
     *waves_out = c;
@@ -698,11 +783,11 @@ int persistent_waves(int head_dim, size_t lds_bytes, int32_t* waves_out) {
 
 extern "C" size_t roll_decode_attn_workspace_bytes(const roll_attn_desc* d) {
     if (validate(d) != ROLL_OK) return 0;
-    return carve(nullptr, d->num_q_heads / d->num_kv_heads, d->head_dim).bytes;
+    return carve(nullptr, d->num_kv_heads, d->num_q_heads / d->num_kv_heads, d->head_dim).bytes;
 }
 
 extern "C" int roll_decode_attn_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
-    const Workspace ws = carve(workspace, 1, 64);
+    const Workspace ws = carve(workspace, 1, 1, 64);
     if (!workspace || !roll::aligned(workspace, 256)) return roll::fail(ROLL_ERR_WORKSPACE, "workspace NULL or not 256-byte aligned");
     if (workspace_bytes < ws.header_bytes)
         return roll::fail(ROLL_ERR_WORKSPACE, "workspace too small: %zu < %zu bytes", workspace_bytes, ws.header_bytes);
@@ -725,7 +810,7 @@ int launch_attn(const void* q, const void* k_pages, const void* v_pages, const i
         return roll::fail(ROLL_ERR_INVALID_ARG, "q, k_pages, v_pages, out must be 16-byte aligned");
     const int32_t G = d->num_q_heads / d->num_kv_heads;
     if (!workspace || !roll::aligned(workspace, 256)) return roll::fail(ROLL_ERR_WORKSPACE, "workspace NULL or not 256-byte aligned");
-    Workspace ws = carve(workspace, G, d->head_dim);
+    Workspace ws = carve(workspace, d->num_kv_heads, G, d->head_dim);
     if (workspace_bytes < ws.bytes)
         return roll::fail(ROLL_ERR_WORKSPACE, "workspace too small: %zu < %zu bytes", workspace_bytes, ws.bytes);
 
@@ -752,18 +837,24 @@ int launch_attn(const void* q, const void* k_pages, const void* v_pages, const i
 
     const unsigned grid = (unsigned)(W / kGroupWaves);
     if (d->ev_main_begin) ROLL_HIP_CHECK(hipEventRecord((hipEvent_t)d->ev_main_begin, stream));
-#define ROLL_LAUNCH_ATTN(DIM, FUSED, EXTRA)                                                                   \
-    attn_stream<DIM, FUSED><<<grid, kGroupWaves * 64, lds, stream>>>(                                        \
+#define ROLL_LAUNCH_ATTN(DIM, FUSED, F32, EXTRA)                                                              \
+    attn_stream<DIM, FUSED, F32><<<grid, kGroupWaves * 64, lds, stream>>>(                                   \
         (const uint4*)q, (const uint4*)k_pages, (const uint4*)v_pages, page_table, seq_lens, out,             \
         ws.group_arrivals, ws.stream_arrivals, ws.part_ml, ws.part_acc, ws.group_ml, ws.group_acc, prm, EXTRA)
+#define ROLL_LAUNCH_ATTN_OUT(DIM, FUSED, EXTRA)                  \
+    do {                                                         \
+        if (prm.out_f32) ROLL_LAUNCH_ATTN(DIM, FUSED, true, EXTRA); \
+        else ROLL_LAUNCH_ATTN(DIM, FUSED, false, EXTRA);            \
+    } while (0)
     if (fused) {
         fused->grid_arrivals = ws.grid_arrivals;
-        if (d->head_dim == 128) ROLL_LAUNCH_ATTN(128, true, *fused);
-        else ROLL_LAUNCH_ATTN(64, true, *fused);
+        if (d->head_dim == 128) ROLL_LAUNCH_ATTN_OUT(128, true, *fused);
+        else ROLL_LAUNCH_ATTN_OUT(64, true, *fused);
     } else {
-        if (d->head_dim == 128) ROLL_LAUNCH_ATTN(128, false, NoFusedArgs{});
-        else ROLL_LAUNCH_ATTN(64, false, NoFusedArgs{});
+        if (d->head_dim == 128) ROLL_LAUNCH_ATTN_OUT(128, false, NoFusedArgs{});
+        else ROLL_LAUNCH_ATTN_OUT(64, false, NoFusedArgs{});
     }
+#undef ROLL_LAUNCH_ATTN_OUT
 #undef ROLL_LAUNCH_ATTN
     ROLL_HIP_CHECK(hipGetLastError());
     if (d->ev_main_end) ROLL_HIP_CHECK(hipEventRecord((hipEvent_t)d->ev_main_end, stream));
