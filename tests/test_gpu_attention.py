@@ -71,8 +71,12 @@ def test_32b_shape_page32():
     check(cfg, L, seed=3)
 
 
-@pytest.mark.parametrize("Hq,Hkv,D,P", [(4, 4, 64, 64), (16, 1, 64, 16), (16, 1, 128, 64), (6, 2, 128, 32)])
+@pytest.mark.parametrize("Hq,Hkv,D,P", [(4, 4, 64, 64), (16, 1, 64, 16), (16, 1, 128, 64), (6, 2, 128, 32),
+                                        (6, 3, 128, 16), (12, 6, 64, 16), (20, 5, 128, 32), (24, 12, 64, 16)])
 def test_other_head_and_page_shapes(Hq, Hkv, D, P):
+    # KV head counts of every kind for the dealing of heads to a workgroup's four waves: fewer than
+    # four (1, 2: the range is cut again; 3: a wave stays idle), more than four and not a multiple
+    # of four (5, 6: the waves get unequal numbers of heads), multiples of four (4, 12)
     cfg = dataclasses.replace(wl.CONFIGS["c1"], name=f"h{Hq}_{Hkv}_d{D}_p{P}", num_q_heads=Hq,
                               num_kv_heads=Hkv, head_dim=D, page_size=P)
     check(cfg, [1, 7, 63, 64, 65, 200, 513, 700, 129], seed=4)

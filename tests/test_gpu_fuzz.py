@@ -14,7 +14,7 @@ from gpu_helpers import compare_sampling, oracle_attn, run_attn, say
 
 pytestmark = pytest.mark.gpu
 
-HEADS = [(1, 1), (4, 1), (7, 1), (8, 2), (12, 4), (16, 16), (28, 4), (32, 2), (64, 8)]
+HEADS = [(1, 1), (4, 1), (7, 1), (8, 2), (12, 4), (16, 16), (28, 4), (32, 2), (64, 8), (6, 3), (12, 6), (20, 5)]
 
 
 def _draw_lengths(rng, B, cap):
