@@ -348,10 +348,13 @@ __device__ __forceinline__ void store_piece(const WaveAcc<D>& a, float2* ml, flo
 // Log-sum-exp merge of n pieces whose slots are slot_of(0..n-1); result stays un-normalised.
 // The pieces are taken four at a time, with all loads of a batch requested before the first is
 // used: the merging wave has nothing else to do meanwhile and is usually one of the last to
-// finish, so the merge's latency is the kernel's.
+// finish, so the merge's latency is the kernel's.  Piece number own_idx (none if negative) is
+// taken from `own` (registers) instead of memory; the arithmetic is the same either way, so the
+// result does not depend on which wave merges.
 template <int D, typename SlotFn>
 __device__ __forceinline__ void merge_pieces(WaveAcc<D>& out_acc, const float2* ml, const float* acc,
-                                             int32_t n, SlotFn slot_of, int32_t G, int32_t r, int32_t q) {
+                                             int32_t n, SlotFn slot_of, int32_t G, int32_t r, int32_t q,
+                                             const WaveAcc<D>* own = nullptr, int32_t own_idx = -1) {
     constexpr int kBatch = 4;
     float M = -INFINITY, lsum = 0.f;
     f32x4_t o[D / 16];
@@ -363,7 +366,14 @@ __device__ __forceinline__ void merge_pieces(WaveAcc<D>& out_acc, const float2* 
 #pragma unroll
         for (int k = 0; k < kBatch; ++k) {
             m_l[k] = f32x2_t{-INFINITY, 0.f};
-            if (base + k < n) {
+            if (base + k == own_idx) {
+                m_l[k] = f32x2_t{own->m, own->l};
+#pragma unroll
+                for (int nt = 0; nt < D / 16; ++nt) {
+                    lo[k][nt] = f32x2_t{own->o[nt][0], own->o[nt][1]};
+                    hi[k][nt] = f32x2_t{own->o[nt][2], own->o[nt][3]};
+                }
+            } else if (base + k < n) {
                 const int64_t row = slot_of(base + k) * G + r;
                 m_l[k] = coherent_load2((const float*)(ml + row));
                 const float* src = acc + row * D + 4 * q;
@@ -511,9 +521,64 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
     int32_t n_b = pre[b + 1] - pre[b];
     int32_t s = item0 - pre[b];
     bool first_stream = true;
-    // The pieces of the segment (at most its first and its last row) and their rows.
-    WaveAcc<D> held0, held1;
-    int32_t row0 = -1, row1 = -1;
+    // Delivers this wave's piece `mine` of row pb (the row spans the ranges c0..c1; piece i comes
+    // from range c0 + i and sits in the first slot of (that range, h), except that c0 uses its
+    // second slot when the row does not begin the range).  If every other piece of the group
+    // has arrived already, this wave is the one that merges and its own piece never goes through
+    // memory; that is the usual case for the piece that ends a range, whose partner began the
+    // next range long ago.  Writes are what a ragged batch costs this kernel, and pieces are
+    // most of them.
+    auto deliver = [&](const WaveAcc<D>& mine, int32_t pb, bool begins) {
+        const int32_t g0 = pre[pb], n_pb = pre[pb + 1] - g0;
+        const int32_t c0 = deal.owner(g0), c1 = deal.owner(g0 + n_pb - 1);
+        const int32_t pieces = c1 - c0 + 1;
+        const int64_t slot0 = deal.slot(c0, h, Hkv, deal.first_step(c0) == g0);
+        const int64_t out_idx = ((int64_t)pb * prm.Hq + (int64_t)h * G + rr) * D + 4 * ctx.q;
+        const int32_t my_pi = c - c0;
+        const int32_t gid = my_pi / kMergeGroup;
+        const int32_t gfirst = gid * kMergeGroup;               // first piece of my group
+        const int32_t gsize = min(kMergeGroup, pieces - gfirst);
+        const int32_t ngroups = (pieces + kMergeGroup - 1) / kMergeGroup;
+        // Slots are unique per piece, so the slot of a group's first piece names the group
+        // (a range can end one row and begin the next: range numbers alone would collide).
+        auto piece_slot = [&](int32_t pi) -> int64_t { return pi == 0 ? slot0 : deal.slot(c0 + pi, h, Hkv, true); };
+        const int64_t group_slot = piece_slot(gfirst);
+        int32_t* counter = group_arrivals + group_slot;
+
+        WaveAcc<D> grp;
+        bool merged = false;
+        int32_t seen = 0;
+        if (lane == 0) seen = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        seen = __builtin_amdgcn_readfirstlane(seen);
+        if (seen == gsize - 1) {
+            // Everybody else is here (an arrival follows the completion of the piece's stores),
+            // and nobody touches the counter any more: reset it as a last arriver does.
+            merge_pieces<D>(grp, part_ml, part_acc, gsize,
+                            [&](int32_t i) -> int64_t { return piece_slot(gfirst + i); }, G, rr, ctx.q, &mine,
+                            my_pi - gfirst);
+            if (lane == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            merged = true;
+        } else {
+            if (ctx.r < G) store_piece<D>(mine, part_ml, part_acc, deal.slot(c, h, Hkv, begins), G, ctx.r, ctx.q);
+            if (arrive_last(counter, gsize, lane)) {
+                merge_pieces<D>(grp, part_ml, part_acc, gsize,
+                                [&](int32_t i) -> int64_t { return piece_slot(gfirst + i); }, G, rr, ctx.q);
+                merged = true;
+            }
+        }
+        if (!merged) return;
+        if (ngroups == 1) {
+            if (ctx.r < G) store_result_as<D, F32OUT>(grp, out, out_idx);
+        } else {
+            if (ctx.r < G) store_piece<D>(grp, group_ml, group_acc, group_slot, G, ctx.r, ctx.q);
+            if (arrive_last(stream_arrivals + pb * Hkv + h, ngroups, lane)) {
+                WaveAcc<D> all;
+                merge_pieces<D>(all, group_ml, group_acc, ngroups,
+                                [&](int32_t j) -> int64_t { return piece_slot(j * kMergeGroup); }, G, rr, ctx.q);
+                if (ctx.r < G) store_result_as<D, F32OUT>(all, out, out_idx);
+            }
+        }
+    };
     while (todo > 0) {
         const int32_t L = len[b];
         const int32_t cnt = min(todo, n_b - s);
@@ -626,10 +691,8 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
             const int64_t out_idx = ((int64_t)b * prm.Hq + (int64_t)h * G + rr) * D + 4 * ctx.q;
             if (ctx.r < G) store_result_as<D, F32OUT>(acc, out, out_idx);
         } else {
-            // A piece of a row that is cut across ranges.  It stays in registers until the
-            // segment is done: see below.
-            if (first_stream) { held0 = acc; row0 = b; }
-            else { held1 = acc; row1 = b; }
+            // A piece of a row that is cut across ranges: see deliver().
+            deliver(acc, b, first_stream);
         }
 
         todo -= cnt;
@@ -641,51 +704,6 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
         }
     }
 
-    // Deliver the segment's pieces.  Written where they were made, the pieces (as many bytes as
-    // four times the output, in small scattered writes, and read back by the merging waves)
-    // reach DRAM in the middle of the KV stream, where every isolated write costs its channel a
-    // turn of the bus: measured 14 us of 285 for c2.  Held back, they are written when the
-    // waves around have finished streaming too.
-    if (row0 >= 0 && ctx.r < G) store_piece<D>(held0, part_ml, part_acc, deal.slot(c, h, Hkv, true), G, ctx.r, ctx.q);
-    if (row1 >= 0 && ctx.r < G) store_piece<D>(held1, part_ml, part_acc, deal.slot(c, h, Hkv, false), G, ctx.r, ctx.q);
-#pragma unroll 1
-    for (int which = 0; which < 2; ++which) {
-        const int32_t pb = which == 0 ? row0 : row1;
-        if (pb < 0) continue;
-        // The row pb spans the ranges c0..c1.  Piece i comes from range c0 + i and sits in the
-        // first slot of (that range, h), except that c0 uses its second slot when the row does
-        // not begin the range.
-        const int32_t g0 = pre[pb], n_pb = pre[pb + 1] - g0;
-        const int32_t c0 = deal.owner(g0), c1 = deal.owner(g0 + n_pb - 1);
-        const int32_t pieces = c1 - c0 + 1;
-        const int64_t slot0 = deal.slot(c0, h, Hkv, deal.first_step(c0) == g0);
-        const int64_t out_idx = ((int64_t)pb * prm.Hq + (int64_t)h * G + rr) * D + 4 * ctx.q;
-        const int32_t gid = (c - c0) / kMergeGroup;
-        const int32_t gfirst = gid * kMergeGroup;               // first piece of my group
-        const int32_t gsize = min(kMergeGroup, pieces - gfirst);
-        const int32_t ngroups = (pieces + kMergeGroup - 1) / kMergeGroup;
-        // Slots are unique per piece, so the slot of a group's first piece names the group
-        // (a range can end one row and begin the next: range numbers alone would collide).
-        auto piece_slot = [&](int32_t pi) -> int64_t { return pi == 0 ? slot0 : deal.slot(c0 + pi, h, Hkv, true); };
-        const int64_t group_slot = piece_slot(gfirst);
-        if (arrive_last(group_arrivals + group_slot, gsize, lane)) {
-            WaveAcc<D> grp;
-            merge_pieces<D>(grp, part_ml, part_acc, gsize,
-                            [&](int32_t i) -> int64_t { return piece_slot(gfirst + i); }, G, rr, ctx.q);
-            if (ngroups == 1) {
-                if (ctx.r < G) store_result_as<D, F32OUT>(grp, out, out_idx);
-            } else {
-                if (ctx.r < G) store_piece<D>(grp, group_ml, group_acc, group_slot, G, ctx.r, ctx.q);
-                if (arrive_last(stream_arrivals + pb * Hkv + h, ngroups, lane)) {
-                    WaveAcc<D> all;
-                    merge_pieces<D>(all, group_ml, group_acc, ngroups,
-                                    [&](int32_t j) -> int64_t { return piece_slot(j * kMergeGroup); }, G,
-                                    rr, ctx.q);
-                    if (ctx.r < G) store_result_as<D, F32OUT>(all, out, out_idx);
-                }
-            }
-        }
-    }
     }
 
     if constexpr (FUSED) {
