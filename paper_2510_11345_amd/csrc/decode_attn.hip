@@ -49,7 +49,6 @@ namespace {
 using namespace roll::attn;
 
 constexpr int kGroupWaves = 4;     // wavefronts per workgroup (they only share the LDS prefix)
-constexpr bool kDoubleBuffer = false;  // keep the next step's loads in flight while computing
 constexpr int kMinSteps = 4;       // do not spread a small batch thinner than this per wave
 constexpr int kMaxBatch = 8192;    // rows whose prefix sums fit the LDS budget
 constexpr int kMaxStreams = 65536; // batch * num_kv_heads: one arrival counter each
@@ -618,44 +617,11 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
         // own after the loop, so that the loop is the same as in a plain launch.
         const bool has_newest = FUSED && s + cnt == n_b;
         const int32_t loop_end = s + cnt - (has_newest ? 1 : 0);
-        if (kDoubleBuffer) {
-            // Two register sets: the loads of step i + 1 are in flight while step i is computed.
-            StepData<D> s0, s1;
-            int32_t i = s;
-            int32_t pgA, pgB;
-            if (i < loop_end) {
-                step_pages<D, false>(ctx, i * kStep, pgA, pgB);
-                load_k<D, false>(ctx, i * kStep, pgA, pgB, s0);
-                load_v<D>(ctx, i * kStep, pgA, pgB, s0);
-                for (;;) {
-                    float sv[8];
-                    const bool more1 = i + 1 < loop_end;
-                    if (more1) {
-                        step_pages<D, false>(ctx, (i + 1) * kStep, pgA, pgB);
-                        load_k<D, false>(ctx, (i + 1) * kStep, pgA, pgB, s1);
-                        load_v<D>(ctx, (i + 1) * kStep, pgA, pgB, s1);
-                    }
-                    score_step<D>(ctx, qf, s0, i * kStep, L, sv);
-                    accumulate_step<D, false>(ctx, sv, s0, i * kStep, L, prm.scale_log2e, acc);
-                    if (!more1) break;
-                    ++i;
-                    const bool more0 = i + 1 < loop_end;
-                    if (more0) {
-                        step_pages<D, false>(ctx, (i + 1) * kStep, pgA, pgB);
-                        load_k<D, false>(ctx, (i + 1) * kStep, pgA, pgB, s0);
-                        load_v<D>(ctx, (i + 1) * kStep, pgA, pgB, s0);
-                    }
-                    score_step<D>(ctx, qf, s1, i * kStep, L, sv);
-                    accumulate_step<D, false>(ctx, sv, s1, i * kStep, L, prm.scale_log2e, acc);
-                    if (!more0) break;
-                    ++i;
-                }
-            }
-        } else {
-            // The page ids of a step are requested one step early, through the scalar cache: a
-            // miss there (one per 64-byte line of the table, every eighth step for 16-token
-            // pages) would otherwise stall the wave, which has no other wave on its SIMD to
-            // hide behind.
+        {
+            // The page ids of a step are requested one step early, through the scalar cache, so
+            // that a miss there (one per 64-byte line of the table, every eighth step for
+            // 16-token pages) does not sit between a step's arithmetic and the next loads; the
+            // wave has no other wave on its SIMD to hide behind.  (Within the noise on c2.)
             int32_t pgA, pgB;
             step_pages<D, false>(ctx, s * kStep, pgA, pgB);
             for (int32_t i = s; i < loop_end; ++i) {
