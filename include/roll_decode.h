@@ -237,7 +237,7 @@ int roll_decode_attn_workspace_init(void* workspace, size_t workspace_bytes, voi
  *   workspace   DEVICE, 256-byte aligned, >= roll_decode_attn_workspace_bytes,
  *               prepared with roll_decode_attn_workspace_init
  * All pointers 16-byte aligned.  Enqueues one kernel on stream: the persistent
- * stream-K attention kernel, which also merges the rows it cut across waves.
+ * stream-K attention kernel, which also merges the rows it cut across workgroups.
  * The workspace size does not depend on the sequence lengths.  Two calls that
  * share a workspace must be ordered on one stream.
  */

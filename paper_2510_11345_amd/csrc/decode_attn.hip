@@ -49,7 +49,7 @@ namespace {
 using namespace roll::attn;
 
 constexpr int kGroupWaves = 4;     // wavefronts per workgroup (they only share the LDS prefix)
-constexpr int kMinSteps = 4;       // do not spread a small batch thinner than this per wave
+constexpr int kMinSteps = 4;       // do not cut a small batch into ranges shorter than this
 constexpr int kMaxBatch = 8192;    // rows whose prefix sums fit the LDS budget
 constexpr int kMaxStreams = 65536; // batch * num_kv_heads: one arrival counter each
 constexpr int kMaxSlots = 32768;   // piece slots: two per (range of row steps, KV head)
