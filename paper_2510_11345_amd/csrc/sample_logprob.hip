@@ -221,10 +221,12 @@ struct Race {
         for (int mask = 1; mask < 64; mask <<= 1) b = fmax(b, shfl_xor_f64(b, mask));
         float t = (float)(b * kLog2ed);
         if ((double)t > b * kLog2ed) t = nextafterf(t, -INFINITY);
-        t = nextafterf(t, -INFINITY);
-        // publish it and take what the other waves have published: any wave's best bounds the
-        // row's best from below.  Which threshold a wave happens to see only decides how many
-        // entries it evaluates exactly, never the result.
+        publish(nextafterf(t, -INFINITY));
+    }
+    // t (wave-uniform) bounds the row's best perturbed logit from below, in log2 units: publish
+    // it and take what the other waves have published.  Which threshold a wave happens to see
+    // only decides how many entries it evaluates exactly, never the result.
+    __device__ __forceinline__ void publish(float t) {
         uint32_t k = order_key(t);
         uint32_t seen = 0;
         if ((threadIdx.x & 63) == 0) seen = atomicMax(block_thr_key, k);
@@ -282,16 +284,28 @@ struct Race {
             thr2 = key_to_float(block_key);
             refresh_c();
         }
-        bool seeded = false;
-        const bool seed0 = x[0] > -INFINITY && (!CUT || x[0] >= x_cut);
-        if (__any(thr2 == -INFINITY && seed0)) {
-            // Nothing bounds the best yet, so every kept entry would pass: evaluate the first
-            // entry of every lane that keeps it, and filter the rest of the vector against the
-            // best of those.
-            if (seed0) exact(i0, x[0], words[0]);
-            share();
+        if (__any(thr2 == -INFINITY)) {
+            // Nothing bounds the best yet, so every kept entry would pass and be evaluated
+            // exactly.  A bound from below in fp32 comes first: -ln u <= (1 - u) / u, so the
+            // perturbed logit in log2 units is at least x k2 - log2(1 - u) + log2(u), and both
+            // u = (k + 0.5) 2^-23 and 1 - u = (2^23 - 1 - k + 0.5) 2^-23 are exact in fp32 (the
+            // 2^-23 cancel).  The margin covers the two hardware logs (1 ulp of a value below 24)
+            // and the rounding of k2 and of the product.  The bound is within (1 - u) / 2 of the
+            // value itself, so what then passes the test below is little more than the winner.
+            float lb = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < N; ++j) {
+                const float u_num = (float)(words[j] >> 9) + 0.5f;
+                const float one_minus_u_num = (float)((~words[j]) >> 9) + 0.5f;
+                const float z2 = x[j] * p.k2;
+                const float v = z2 - __builtin_amdgcn_logf(one_minus_u_num) + __builtin_amdgcn_logf(u_num) -
+                                (0x1p-16f + fabsf(z2) * 0x1p-21f);
+                if (x[j] > -INFINITY && (!CUT || x[j] >= x_cut)) lb = fmaxf(lb, v);
+            }
+#pragma unroll
+            for (int mask = 1; mask < 64; mask <<= 1) lb = fmaxf(lb, __shfl_xor(lb, mask));
+            publish(lb);
             refresh_c();
-            seeded = true;
         }
         float e[N];
 #pragma unroll
@@ -322,7 +336,6 @@ struct Race {
             // back.  e = 0 (an entry more than 126 binary orders below a logit of the same row,
             // which the 28 orders a draw can add never make up) with c = inf gives NaN: no pass.
             pass[j] = (float)words[j] >= fmaf(-e[j], c, 8388606.5f * 512.f) && (!CUT || x[j] >= x_cut);
-            if (j == 0) pass[j] = pass[j] && !seeded;
             any_pass = any_pass || pass[j];
         }
         if (__any(any_pass)) {
