@@ -9,23 +9,30 @@
 // One workgroup of 1024 threads per row.
 //   top_p == 1: ONE sweep over the row computes the online (max, sum-exp) for
 //     the log-sum-exp and runs the Gumbel-max race.
-//   top_p <  1: sweep 1 finds max z; a radix select over the order-preserving
-//     integer key of the logit (one byte per level: 2 levels for bf16, 4 for
-//     fp32) finds the cut value x_cut, each level being one sweep that adds
-//     exp(z - max) in 2^-40 fixed point (integer adds commute, so the cut does
-//     not depend on thread timing) into an LDS histogram (16 copies per bin so
-//     that hot bins do not serialise the wave) followed by a block-wide suffix
-//     scan; the last sweep runs the race over logits >= x_cut.
+//   top_p <  1: sweep 1 finds max z.  Sweep 2 finds the upper 16 bits of the
+//     order-preserving integer key of the cut value x_cut: a histogram in LDS
+//     over the 16-bit key prefixes of a window of four top-byte values at and
+//     below the row max's, entries below the window going to bins by top byte;
+//     every entry adds exp(z - max) in 2^-40 fixed point (integer adds commute,
+//     so the cut does not depend on thread timing), and a block-wide scan in
+//     descending key order picks the range at which the running mass reaches
+//     ceil(top_p * total).  A cut below the window takes one more sweep (the
+//     second key byte), fp32 logits two more (the lower 16 key bits).  The last
+//     sweep runs the race over logits >= x_cut, drawing random numbers only
+//     for the Philox blocks that hold a kept entry (gathered by wave in LDS).
 //
 // The Gumbel-max race is exact and cheap.  With g(u) = -log(-log u) and
 // -log u >= 1 - u, an entry can only win if  1 - u <= exp(z - best), best being
-// the largest exact perturbed logit seen so far by its wave.  exp(z - ref) is
-// needed for the log-sum-exp anyway, so the test costs one multiply and one
-// compare per entry on top of the Philox draw; the few entries that pass are
-// evaluated in fp64 (division by the temperature and both logs), the arithmetic
-// the definition is stated in.  The running best is shared across the wave
-// whenever it moves.  The integer multiplies of Philox are the bulk of the
-// arithmetic: each round is two 32x32->64 products (v_mad_u64_u32).
+// any lower bound of the row's best perturbed logit.  exp(z - ref) is needed
+// for the log-sum-exp anyway, so the test costs a convert, a fused multiply-add
+// and a compare per entry on top of the Philox draw (and most vectors are
+// dismissed by one test of their largest word against their largest
+// exponential); the few entries that pass are evaluated in fp64 (division by
+// the temperature and both logs), the arithmetic the definition is stated in.
+// The first bound comes from an fp32 lower bound of the first vector's
+// entries; a bound that moves is shared by the row's 16 waves through LDS.
+// The integer multiplies of Philox are the bulk of the arithmetic: each round
+// is two 32x32->64 products (v_mad_u64_u32) and two three-input xors.
 #include <cfloat>
 #include <cmath>
 
