@@ -42,6 +42,16 @@ def profiled_traffic(workload: str, algorithmic_bytes: float):
     return None
 
 
+def profiled_valu_per_logit(workload: str):
+    """Vector instructions per logit of the sampling kernel from the rocprofv3 --pmc summary under
+    profiles/ (`sample_rows_<workload>_valu_counters.txt`); None if there is none."""
+    path = os.path.join(ROOT, "profiles", f"sample_rows_{workload}_valu_counters.txt")
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"=\s*([0-9.]+) per logit", open(path).read())
+    return float(m.group(1)) if m else None
+
+
 def policy_loss_bench(args, torch, rb, wl):
     """Tokens/s of roll_policy_loss on a rollout-sized ragged batch (512 responses, lognormal lengths),
     one launch pair per objective; HBM roofline on the bytes a token moves."""
@@ -265,6 +275,28 @@ def main():
                      "traffic": profiled_traffic(cfg.name, avg_kv_bytes),
                      "algorithmic_bytes_per_launch": avg_kv_bytes, "avg_launch_ms": avg_kern_ms},
     }
+
+    # The sampling launch alone (after the timed region): its bound is the vector ALU, not HBM, so
+    # it is reported as logits per second and vector instructions per logit.
+    n_s = 20
+    s0, s1 = rb.ProfEvent(), rb.ProfEvent()
+    sdesc = rb.sample_desc(logits)
+    s0.record()
+    for i in range(n_s):
+        rb.roll_sample_logprob(logits, cfg.temperature, cfg.top_p, args.seed, step_index + i, batch.tokens,
+                               batch.logprob, sdesc, None)
+    s1.record()
+    torch.cuda.synchronize()
+    samp_ms = s0.elapsed_ms(s1) / n_s
+    result["sampling"] = {"kernel": "sample_rows", "bound": "alu", "avg_launch_ms": samp_ms,
+                          "Gelem_per_s": cfg.batch * cfg.vocab / (samp_ms * 1e-3) / 1e9,
+                          "vector_instructions_per_logit": profiled_valu_per_logit(cfg.name),
+                          "peak_lane_ops_per_s": 256 * 4 * 16 * 2.4e9,
+                          "compulsory_bytes": cfg.batch * cfg.vocab * (2 if cfg.logits_dtype == "bf16" else 4)}
+    # the step that parity is checked on must be the last one the batch ran
+    rb.roll_sample_logprob(logits, cfg.temperature, cfg.top_p, args.seed, step_index - 1, batch.tokens,
+                           batch.logprob, sdesc, None)
+    torch.cuda.synchronize()
 
     if not args.no_cpu_baseline:
         import oracle
