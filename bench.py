@@ -293,6 +293,12 @@ def main():
                           "vector_instructions_per_logit": profiled_valu_per_logit(cfg.name),
                           "peak_lane_ops_per_s": 256 * 4 * 16 * 2.4e9,
                           "compulsory_bytes": cfg.batch * cfg.vocab * (2 if cfg.logits_dtype == "bf16" else 4)}
+    n_layers = 64 if cfg.name == "c5" else 28
+    result["extrapolation"] = {
+        "what": "tokens/s if every step ran n_layers such attention launches and one sampling launch "
+                "(the attention and sampling times measured above; nothing else of a model counted)",
+        "n_layers": n_layers,
+        "tokens_per_s": cfg.batch / ((n_layers * avg_kern_ms + samp_ms) * 1e-3)}
     # the step that parity is checked on must be the last one the batch ran
     rb.roll_sample_logprob(logits, cfg.temperature, cfg.top_p, args.seed, step_index - 1, batch.tokens,
                            batch.logprob, sdesc, None)
