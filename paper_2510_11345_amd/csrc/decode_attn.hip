@@ -515,161 +515,160 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
     const int32_t todo0 = c < deal.NC ? deal.first_step(c + 1) - item0 : 0;
 
     for (int32_t h = h_begin; h < Hkv && todo0 > 0; h += h_stride) {
-    int32_t todo = todo0;
-    int32_t b = row_of(item0);
-    int32_t n_b = pre[b + 1] - pre[b];
-    int32_t s = item0 - pre[b];
-    bool first_stream = true;
-    // Delivers this wave's piece `mine` of row pb (the row spans the ranges c0..c1; piece i comes
-    // from range c0 + i and sits in the first slot of (that range, h), except that c0 uses its
-    // second slot when the row does not begin the range).  If every other piece of the group
-    // has arrived already, this wave is the one that merges and its own piece never goes through
-    // memory; that is the usual case for the piece that ends a range, whose partner began the
-    // next range long ago.  Writes are what a ragged batch costs this kernel, and pieces are
-    // most of them.
-    auto deliver = [&](const WaveAcc<D>& mine, int32_t pb, bool begins) {
-        const int32_t g0 = pre[pb], n_pb = pre[pb + 1] - g0;
-        const int32_t c0 = deal.owner(g0), c1 = deal.owner(g0 + n_pb - 1);
-        const int32_t pieces = c1 - c0 + 1;
-        const int64_t slot0 = deal.slot(c0, h, Hkv, deal.first_step(c0) == g0);
-        const int64_t out_idx = ((int64_t)pb * prm.Hq + (int64_t)h * G + rr) * D + 4 * ctx.q;
-        const int32_t my_pi = c - c0;
-        const int32_t gid = my_pi / kMergeGroup;
-        const int32_t gfirst = gid * kMergeGroup;               // first piece of my group
-        const int32_t gsize = min(kMergeGroup, pieces - gfirst);
-        const int32_t ngroups = (pieces + kMergeGroup - 1) / kMergeGroup;
-        // Slots are unique per piece, so the slot of a group's first piece names the group
-        // (a range can end one row and begin the next: range numbers alone would collide).
-        auto piece_slot = [&](int32_t pi) -> int64_t { return pi == 0 ? slot0 : deal.slot(c0 + pi, h, Hkv, true); };
-        const int64_t group_slot = piece_slot(gfirst);
-        int32_t* counter = group_arrivals + group_slot;
+        int32_t todo = todo0;
+        int32_t b = row_of(item0);
+        int32_t n_b = pre[b + 1] - pre[b];
+        int32_t s = item0 - pre[b];
+        bool first_stream = true;
+        // Delivers this wave's piece `mine` of row pb (the row spans the ranges c0..c1; piece i comes
+        // from range c0 + i and sits in the first slot of (that range, h), except that c0 uses its
+        // second slot when the row does not begin the range).  If every other piece of the group
+        // has arrived already, this wave is the one that merges and its own piece never goes through
+        // memory; that is the usual case for the piece that ends a range, whose partner began the
+        // next range long ago.  Writes are what a ragged batch costs this kernel, and pieces are
+        // most of them.
+        auto deliver = [&](const WaveAcc<D>& mine, int32_t pb, bool begins) {
+            const int32_t g0 = pre[pb], n_pb = pre[pb + 1] - g0;
+            const int32_t c0 = deal.owner(g0), c1 = deal.owner(g0 + n_pb - 1);
+            const int32_t pieces = c1 - c0 + 1;
+            const int64_t slot0 = deal.slot(c0, h, Hkv, deal.first_step(c0) == g0);
+            const int64_t out_idx = ((int64_t)pb * prm.Hq + (int64_t)h * G + rr) * D + 4 * ctx.q;
+            const int32_t my_pi = c - c0;
+            const int32_t gid = my_pi / kMergeGroup;
+            const int32_t gfirst = gid * kMergeGroup;               // first piece of my group
+            const int32_t gsize = min(kMergeGroup, pieces - gfirst);
+            const int32_t ngroups = (pieces + kMergeGroup - 1) / kMergeGroup;
+            // Slots are unique per piece, so the slot of a group's first piece names the group
+            // (a range can end one row and begin the next: range numbers alone would collide).
+            auto piece_slot = [&](int32_t pi) -> int64_t { return pi == 0 ? slot0 : deal.slot(c0 + pi, h, Hkv, true); };
+            const int64_t group_slot = piece_slot(gfirst);
+            int32_t* counter = group_arrivals + group_slot;
 
-        WaveAcc<D> grp;
-        bool merged = false;
-        int32_t seen = 0;
-        if (lane == 0) seen = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        seen = __builtin_amdgcn_readfirstlane(seen);
-        if (seen == gsize - 1) {
-            // Everybody else is here (an arrival follows the completion of the piece's stores),
-            // and nobody touches the counter any more: reset it as a last arriver does.
-            merge_pieces<D>(grp, part_ml, part_acc, gsize,
-                            [&](int32_t i) -> int64_t { return piece_slot(gfirst + i); }, G, rr, ctx.q, &mine,
-                            my_pi - gfirst);
-            if (lane == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            merged = true;
-        } else {
-            if (ctx.r < G) store_piece<D>(mine, part_ml, part_acc, deal.slot(c, h, Hkv, begins), G, ctx.r, ctx.q);
-            if (arrive_last(counter, gsize, lane)) {
+            WaveAcc<D> grp;
+            bool merged = false;
+            int32_t seen = 0;
+            if (lane == 0) seen = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            seen = __builtin_amdgcn_readfirstlane(seen);
+            if (seen == gsize - 1) {
+                // Everybody else is here (an arrival follows the completion of the piece's stores),
+                // and nobody touches the counter any more: reset it as a last arriver does.
                 merge_pieces<D>(grp, part_ml, part_acc, gsize,
-                                [&](int32_t i) -> int64_t { return piece_slot(gfirst + i); }, G, rr, ctx.q);
+                                [&](int32_t i) -> int64_t { return piece_slot(gfirst + i); }, G, rr, ctx.q, &mine,
+                                my_pi - gfirst);
+                if (lane == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 merged = true;
+            } else {
+                if (ctx.r < G) store_piece<D>(mine, part_ml, part_acc, deal.slot(c, h, Hkv, begins), G, ctx.r, ctx.q);
+                if (arrive_last(counter, gsize, lane)) {
+                    merge_pieces<D>(grp, part_ml, part_acc, gsize,
+                                    [&](int32_t i) -> int64_t { return piece_slot(gfirst + i); }, G, rr, ctx.q);
+                    merged = true;
+                }
             }
-        }
-        if (!merged) return;
-        if (ngroups == 1) {
-            if (ctx.r < G) store_result_as<D, F32OUT>(grp, out, out_idx);
-        } else {
-            if (ctx.r < G) store_piece<D>(grp, group_ml, group_acc, group_slot, G, ctx.r, ctx.q);
-            if (arrive_last(stream_arrivals + pb * Hkv + h, ngroups, lane)) {
-                WaveAcc<D> all;
-                merge_pieces<D>(all, group_ml, group_acc, ngroups,
-                                [&](int32_t j) -> int64_t { return piece_slot(j * kMergeGroup); }, G, rr, ctx.q);
-                if (ctx.r < G) store_result_as<D, F32OUT>(all, out, out_idx);
+            if (!merged) return;
+            if (ngroups == 1) {
+                if (ctx.r < G) store_result_as<D, F32OUT>(grp, out, out_idx);
+            } else {
+                if (ctx.r < G) store_piece<D>(grp, group_ml, group_acc, group_slot, G, ctx.r, ctx.q);
+                if (arrive_last(stream_arrivals + pb * Hkv + h, ngroups, lane)) {
+                    WaveAcc<D> all;
+                    merge_pieces<D>(all, group_ml, group_acc, ngroups,
+                                    [&](int32_t j) -> int64_t { return piece_slot(j * kMergeGroup); }, G, rr, ctx.q);
+                    if (ctx.r < G) store_result_as<D, F32OUT>(all, out, out_idx);
+                }
             }
-        }
-    };
-    while (todo > 0) {
-        const int32_t L = len[b];
-        const int32_t cnt = min(todo, n_b - s);
-        ctx.pt_row = page_table + (int64_t)b * prm.max_pages;
-        ctx.h = h;
-        if constexpr (FUSED) {
-            ctx.k_new_row = fa.k_new + ((int64_t)b * Hkv + h) * (D / 8);
-            ctx.v_new_row = (const uint16_t*)fa.v_new + ((int64_t)b * Hkv + h) * D;
-            ctx.new_tok = L - 1;
-            ctx.new_pi = (L - 1) >> prm.log2P;
-            ctx.new_page = s + cnt == n_b ? newest_page(fa, ctx.pt_row, b, L, prm.log2P, prm.num_pages) : 0;
-        }
-        // The newest token's V elements this lane may need, fetched ahead of the stream's loads.
-        uint32_t v_fresh[D / 16];
-        if constexpr (FUSED) {
-            if (s + cnt == n_b) {
+        };
+        while (todo > 0) {
+            const int32_t L = len[b];
+            const int32_t cnt = min(todo, n_b - s);
+            ctx.pt_row = page_table + (int64_t)b * prm.max_pages;
+            ctx.h = h;
+            if constexpr (FUSED) {
+                ctx.k_new_row = fa.k_new + ((int64_t)b * Hkv + h) * (D / 8);
+                ctx.v_new_row = (const uint16_t*)fa.v_new + ((int64_t)b * Hkv + h) * D;
+                ctx.new_tok = L - 1;
+                ctx.new_pi = (L - 1) >> prm.log2P;
+                ctx.new_page = s + cnt == n_b ? newest_page(fa, ctx.pt_row, b, L, prm.log2P, prm.num_pages) : 0;
+            }
+            // The newest token's V elements this lane may need, fetched ahead of the stream's loads.
+            uint32_t v_fresh[D / 16];
+            if constexpr (FUSED) {
+                if (s + cnt == n_b) {
 #pragma unroll
-                for (int nt = 0; nt < D / 16; ++nt) v_fresh[nt] = ctx.v_new_row[16 * nt + ctx.r];
+                    for (int nt = 0; nt < D / 16; ++nt) v_fresh[nt] = ctx.v_new_row[16 * nt + ctx.r];
+                }
             }
-        }
 
-        // Q as the B operand: lane (r, q) holds head r, head-dim 32kk + 8q .. + 7; zero for r >= G.
-        bf16x8_t qf[D / 32];
-        {
-            const uint4 zero = make_uint4(0, 0, 0, 0);
-            const uint4* qrow = q16 + ((int64_t)b * prm.Hq + (int64_t)h * G + ctx.r) * (D / 8) + ctx.q;
+            // Q as the B operand: lane (r, q) holds head r, head-dim 32kk + 8q .. + 7; zero for r >= G.
+            bf16x8_t qf[D / 32];
+            {
+                const uint4 zero = make_uint4(0, 0, 0, 0);
+                const uint4* qrow = q16 + ((int64_t)b * prm.Hq + (int64_t)h * G + ctx.r) * (D / 8) + ctx.q;
 #pragma unroll
-            for (int kk = 0; kk < D / 32; ++kk) qf[kk] = as_bf16x8(ctx.r < G ? qrow[kk * 4] : zero);
-        }
-        WaveAcc<D> acc;
+                for (int kk = 0; kk < D / 32; ++kk) qf[kk] = as_bf16x8(ctx.r < G ? qrow[kk * 4] : zero);
+            }
+            WaveAcc<D> acc;
 #pragma unroll
-        for (int nt = 0; nt < D / 16; ++nt) acc.o[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-        acc.m = -INFINITY;
-        acc.l = 0.f;
+            for (int nt = 0; nt < D / 16; ++nt) acc.o[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            acc.m = -INFINITY;
+            acc.l = 0.f;
 
-        // In a fused launch the step that holds the stream's newest token runs as code of its
-        // own after the loop, so that the loop is the same as in a plain launch.
-        const bool has_newest = FUSED && s + cnt == n_b;
-        const int32_t loop_end = s + cnt - (has_newest ? 1 : 0);
-        {
-            // The page ids of a step are requested one step early, through the scalar cache, so
-            // that a miss there (one per 64-byte line of the table, every eighth step for
-            // 16-token pages) does not sit between a step's arithmetic and the next loads; the
-            // wave has no other wave on its SIMD to hide behind.  (Within the noise on c2.)
-            int32_t pgA, pgB;
-            step_pages<D, false>(ctx, s * kStep, pgA, pgB);
-            for (int32_t i = s; i < loop_end; ++i) {
-                int32_t nxtA, nxtB;
-                step_pages<D, false>(ctx, (i + 1) * kStep, nxtA, nxtB);
+            // In a fused launch the step that holds the stream's newest token runs as code of its
+            // own after the loop, so that the loop is the same as in a plain launch.
+            const bool has_newest = FUSED && s + cnt == n_b;
+            const int32_t loop_end = s + cnt - (has_newest ? 1 : 0);
+            {
+                // The page ids of a step are requested one step early, through the scalar cache, so
+                // that a miss there (one per 64-byte line of the table, every eighth step for
+                // 16-token pages) does not sit between a step's arithmetic and the next loads; the
+                // wave has no other wave on its SIMD to hide behind.  (Within the noise on c2.)
+                int32_t pgA, pgB;
+                step_pages<D, false>(ctx, s * kStep, pgA, pgB);
+                for (int32_t i = s; i < loop_end; ++i) {
+                    int32_t nxtA, nxtB;
+                    step_pages<D, false>(ctx, (i + 1) * kStep, nxtA, nxtB);
+                    StepData<D> sd;
+                    load_k<D, false>(ctx, i * kStep, pgA, pgB, sd);
+                    load_v<D>(ctx, i * kStep, pgA, pgB, sd);
+                    float sv[8];
+                    score_step<D>(ctx, qf, sd, i * kStep, L, sv);
+                    accumulate_step<D, false>(ctx, sv, sd, i * kStep, L, prm.scale_log2e, acc);
+                    pgA = nxtA;
+                    pgB = nxtB;
+                }
+            }
+            if (has_newest) {
+                const int32_t t0 = loop_end * kStep;
                 StepData<D> sd;
-                load_k<D, false>(ctx, i * kStep, pgA, pgB, sd);
-                load_v<D>(ctx, i * kStep, pgA, pgB, sd);
+                int32_t pgA, pgB;
+                step_pages<D, FUSED>(ctx, t0, pgA, pgB);
+                load_k<D, FUSED>(ctx, t0, pgA, pgB, sd);
+                load_v<D>(ctx, t0, pgA, pgB, sd);
                 float sv[8];
-                score_step<D>(ctx, qf, sd, i * kStep, L, sv);
-                accumulate_step<D, false>(ctx, sv, sd, i * kStep, L, prm.scale_log2e, acc);
-                pgA = nxtA;
-                pgB = nxtB;
+                score_step<D>(ctx, qf, sd, t0, L, sv);
+                patch_newest_v<D>(ctx, t0, v_fresh, sd);
+                accumulate_step<D, FUSED>(ctx, sv, sd, t0, L, prm.scale_log2e, acc);
+            }
+
+            // Finish the per-head sum across the four q-groups of the wave.
+            acc.l = sum_over_q(acc.l);
+
+            if (cnt == n_b) {  // the whole stream: normalise and write the result
+                const int64_t out_idx = ((int64_t)b * prm.Hq + (int64_t)h * G + rr) * D + 4 * ctx.q;
+                if (ctx.r < G) store_result_as<D, F32OUT>(acc, out, out_idx);
+            } else {
+                // A piece of a row that is cut across ranges: see deliver().
+                deliver(acc, b, first_stream);
+            }
+
+            todo -= cnt;
+            first_stream = false;
+            s = 0;
+            if (todo > 0) {  // the next row that has tokens
+                do { ++b; } while (b < prm.B - 1 && pre[b + 1] == pre[b]);
+                n_b = pre[b + 1] - pre[b];
             }
         }
-        if (has_newest) {
-            const int32_t t0 = loop_end * kStep;
-            StepData<D> sd;
-            int32_t pgA, pgB;
-            step_pages<D, FUSED>(ctx, t0, pgA, pgB);
-            load_k<D, FUSED>(ctx, t0, pgA, pgB, sd);
-            load_v<D>(ctx, t0, pgA, pgB, sd);
-            float sv[8];
-            score_step<D>(ctx, qf, sd, t0, L, sv);
-            patch_newest_v<D>(ctx, t0, v_fresh, sd);
-            accumulate_step<D, FUSED>(ctx, sv, sd, t0, L, prm.scale_log2e, acc);
-        }
-
-        // Finish the per-head sum across the four q-groups of the wave.
-        acc.l = sum_over_q(acc.l);
-
-        if (cnt == n_b) {  // the whole stream: normalise and write the result
-            const int64_t out_idx = ((int64_t)b * prm.Hq + (int64_t)h * G + rr) * D + 4 * ctx.q;
-            if (ctx.r < G) store_result_as<D, F32OUT>(acc, out, out_idx);
-        } else {
-            // A piece of a row that is cut across ranges: see deliver().
-            deliver(acc, b, first_stream);
-        }
-
-        todo -= cnt;
-        first_stream = false;
-        s = 0;
-        if (todo > 0) {  // the next row that has tokens
-            do { ++b; } while (b < prm.B - 1 && pre[b + 1] == pre[b]);
-            n_b = pre[b + 1] - pre[b];
-        }
-    }
-
     }
 
     if constexpr (FUSED) {
