@@ -188,7 +188,8 @@ class RefillLoop:
         if refilled:
             rb.roll_kv_commit(b.pool)   # the prompt writer looks its pages up on the device
             parts = [self._prompt(req, n) for _, req, n in refilled]
-            q, k, v = (torch.cat([p[i] for p in parts]) for i in range(3))
+            # one prompt (the usual tick): its slices of the bank as they are, no copy
+            q, k, v = parts[0] if len(parts) == 1 else (torch.cat([p[i] for p in parts]) for i in range(3))
             lens = [n for _, _, n in refilled]
             first = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
             if self.prefill:
