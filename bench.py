@@ -52,6 +52,48 @@ def profiled_valu_per_logit(workload: str):
     return float(m.group(1)) if m else None
 
 
+def equal_rows_bench(args, torch, rb, wl, DecodeBatch):
+    """The plain attention launch (roll_decode_attn) on the config's batch with every row at the same
+    length: the mean of the config's lengths rounded to the number of steps that gives every
+    workgroup whole rows.  (The ragged batch is what the default run measures; a second batch in one
+    process lands elsewhere in memory and times ~10 us slower, so it is not repeated here.)"""
+    cfg = wl.CONFIGS[args.config]
+    ragged = wl.draw_lengths(cfg.lengths, cfg.batch, args.seed, cfg.max_len).astype(np.int64)
+    steps = max(1, int(round(ragged.mean() / 32.0)))
+    out = {}
+    for name, lengths in (("equal_rows", np.full(cfg.batch, 32 * steps, np.int64)),):
+        batch = DecodeBatch(cfg, args.seed, lengths, headroom_tokens=8)
+        torch.cuda.synchronize()
+        desc, n = batch.desc, max(args.steps, 5)
+        evs = [(rb.ProfEvent(), rb.ProfEvent()) for _ in range(n)]
+        for _ in range(max(args.warmup, 1)):
+            rb.roll_decode_attn(batch.q, batch.k_pages, batch.v_pages, batch.page_table, batch.seq_lens, batch.out,
+                                desc, batch._ws)
+        torch.cuda.synchronize()
+        for a, b in evs:
+            desc.ev_main_begin, desc.ev_main_end = a.handle.value, b.handle.value
+            rb.roll_decode_attn(batch.q, batch.k_pages, batch.v_pages, batch.page_table, batch.seq_lens, batch.out,
+                                desc, batch._ws)
+        torch.cuda.synchronize()
+        desc.ev_main_begin, desc.ev_main_end = None, None
+        ms = float(np.mean([a.elapsed_ms(b) for a, b in evs]))
+        kv_bytes = cfg.kv_bytes_per_token * batch.total_tokens()
+        out[name] = {"sum_seq_lens": int(batch.total_tokens()), "avg_launch_ms": ms,
+                     "GBps": kv_bytes / (ms * 1e-3) / 1e9, "frac_of_peak": kv_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        batch.close()
+        del batch
+        torch.cuda.empty_cache()
+    print(json.dumps({"metric": "KV-read GB/s of the plain attention launch on equal rows",
+                      "unit": "GB/s", "n_gpus": 1, "steps": max(args.steps, 5), "warmup": max(args.warmup, 1),
+                      "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": f"{cfg.name}: B={cfg.batch} Hq={cfg.num_q_heads} Hkv={cfg.num_kv_heads} "
+                                             f"D={cfg.head_dim} P={cfg.page_size}, rows of {32 * steps} tokens"},
+                      "roofline": {"bound": "hbm", "kernel": "attn_stream", "achieved": out["equal_rows"]["GBps"],
+                                   "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": out["equal_rows"]["frac_of_peak"],
+                                   "traffic": None},
+                      **out}))
+
+
 def policy_loss_bench(args, torch, rb, wl):
     """Tokens/s of roll_policy_loss on a rollout-sized ragged batch (512 responses, lognormal lengths),
     one launch pair per objective; HBM roofline on the bytes a token moves."""
@@ -173,6 +215,9 @@ def main():
                     help="measure roll_policy_loss (the consumer of logprob_out) instead of the decode step")
     ap.add_argument("--prefill", action="store_true",
                     help="measure roll_prefill_attn (chunked prefill into pages) instead of the decode step")
+    ap.add_argument("--equal-rows", action="store_true",
+                    help="measure the plain attention launch on a batch of equal rows of the config's mean "
+                         "length (no row is cut, little is written): what the kernel reads when nothing is ragged")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="only run one plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -199,6 +244,9 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"pmc_calibration": "one device copy", "bytes_read": src.numel() * 4,
                           "bytes_written": dst.numel() * 4}))
+        return
+    if args.equal_rows:
+        equal_rows_bench(args, torch, rb, wl, DecodeBatch)
         return
     if args.policy_loss:
         policy_loss_bench(args, torch, rb, wl)
