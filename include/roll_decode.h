@@ -363,6 +363,8 @@ size_t roll_sample_logprob_workspace_bytes(const roll_sample_desc* desc);
  *   top_p        in (0, 1]
  *   tokens_out   DEVICE int32 [B]
  *   logprob_out  DEVICE fp32 [B]
+ * Entries of -inf are masked tokens (probability 0).  A row without any finite entry has no
+ * distribution to draw from: its token is -1 and its log-probs are NaN.
  */
 int roll_sample_logprob(const void* logits, float temperature, float top_p,
                         uint64_t philox_seed, uint64_t step,

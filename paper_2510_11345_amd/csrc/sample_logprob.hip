@@ -526,7 +526,7 @@ __device__ __forceinline__ unsigned long long top_p_target(float top_p, unsigned
 
 // One radix level: histogram of the digit at SHIFT (BITS wide) over the entries whose higher
 // key bits equal the prefix chosen so far, then the suffix scan that picks the next digit.
-template <typename T, int SHIFT, bool FIRST>
+template <typename T, int SHIFT>
 __device__ void radix_level(const T* __restrict__ row, const SampleParams& p, float nk,
                             unsigned long long* s_hist, unsigned long long* s_tot,
                             unsigned long long* s_wave, Select* s_sel, unsigned long long& target) {
@@ -544,8 +544,6 @@ __device__ void radix_level(const T* __restrict__ row, const SampleParams& p, fl
         s_tot[tid] = t;
     }
     __syncthreads();
-    if (FIRST)  // total mass -> target = ceil(top_p * total)
-        target = top_p_target(p.top_p, block_sum_u64(tid < kBins ? s_tot[tid] : 0ull, s_wave));
     // thread t owns bin (kBins - 1 - t): descending key order
     const int bin = kBins - 1 - tid;
     scan_select(tid < kBins ? s_tot[bin] : 0ull, (prefix << kRadixBits) | (uint32_t)bin, s_wave, s_sel, target);
@@ -624,7 +622,7 @@ __device__ bool window_level(const T* __restrict__ row, const SampleParams& p, f
     __syncthreads();
     const int bin = kBins - 1 - tid;
     scan_select(tid < kBins ? s_tot[bin] : 0ull, (uint32_t)bin, s_wave, s_sel, target);
-    radix_level<T, 16, false>(row, p, nk, s_hist, s_tot, s_wave, s_sel, target);
+    radix_level<T, 16>(row, p, nk, s_hist, s_tot, s_wave, s_sel, target);
     return true;
 }
 
@@ -705,36 +703,36 @@ __global__ __launch_bounds__(kThreads) void sample_rows(const T* __restrict__ lo
         const float nkM = ref_offset(xM, p.k2);
         constexpr int kKeyBits = Elem<T>::kKeyBits;
         unsigned long long target = 0;
-        // The upper 16 key bits from the window sweep, or, when the cut lies below the window,
-        // byte by byte from the most significant one; then the lower 16 of an fp32 key.
-        if (!window_level<T>(row, p, xM, nkM, s_hist, s_tot, s_wave, &s_sel, target)) {
-            radix_level<T, 24, true>(row, p, nkM, s_hist, s_tot, s_wave, &s_sel, target);
-            radix_level<T, 16, false>(row, p, nkM, s_hist, s_tot, s_wave, &s_sel, target);
+        // The upper 16 key bits from the window sweep (and a sweep for the second byte when the cut
+        // lies below the window), then the lower 16 of an fp32 key.  A row without mass (no finite
+        // entry) has no cut and no race: the result below is then "no token".
+        const bool has_mass = window_level<T>(row, p, xM, nkM, s_hist, s_tot, s_wave, &s_sel, target);
+        if (has_mass) {
+            if (kKeyBits == 32) {
+                radix_level<T, 8>(row, p, nkM, s_hist, s_tot, s_wave, &s_sel, target);
+                radix_level<T, 0>(row, p, nkM, s_hist, s_tot, s_wave, &s_sel, target);
+            }
+            if (tid == 0) {
+                // s_sel.prefix is now the key of the cut value (its upper 16 bits for bf16, whose
+                // lower key bits are all ones for negative values and zero otherwise).  The kept
+                // mass is everything above the cut plus the cut value's own class.
+                const uint32_t key = (s_sel.prefix << (32 - kKeyBits)) |
+                                     (kKeyBits == 16 ? ((s_sel.prefix >> 15) ? 0u : 0xFFFFu) : 0u);
+                s_xcut = key_to_float(key);
+                s_lse = (log2((double)s_sel.kept * 0x1p-40) - (double)nkM) / kLog2ed;
+            }
+            __syncthreads();
+            race_kept.block_thr_key = &s_thr_key;  // still -inf: no race has run in this launch
+            race_kept.x_cut = s_xcut;
+            race_kept.set_ref(xM);
+            race_kept.refresh_c();
+            static_assert(kWavesPerBlock * kQueueBytesPerWave <= kHistSlots * 8, "the queues reuse the histogram");
+            CompactRace<Race<false, false, true>> gathered{
+                race_kept, (float*)s_hist + wave * (kQueueCap * 4),
+                (uint32_t*)s_hist + kWavesPerBlock * (kQueueCap * 4) + wave * kQueueCap};
+            sweep<T>(row, p.V, gathered);
+            gathered.finish();
         }
-        if (kKeyBits == 32) {
-            radix_level<T, 8, false>(row, p, nkM, s_hist, s_tot, s_wave, &s_sel, target);
-            radix_level<T, 0, false>(row, p, nkM, s_hist, s_tot, s_wave, &s_sel, target);
-        }
-        if (tid == 0) {
-            // s_sel.prefix is now the key of the cut value (its upper 16 bits for bf16, whose
-            // lower key bits are all ones for negative values and zero otherwise).  The kept
-            // mass is everything above the cut plus the cut value's own class.
-            const uint32_t key = (s_sel.prefix << (32 - kKeyBits)) |
-                                 (kKeyBits == 16 ? ((s_sel.prefix >> 15) ? 0u : 0xFFFFu) : 0u);
-            s_xcut = key_to_float(key);
-            s_lse = (log2((double)s_sel.kept * 0x1p-40) - (double)nkM) / kLog2ed;
-        }
-        __syncthreads();
-        race_kept.block_thr_key = &s_thr_key;  // still -inf: no race has run in this launch
-        race_kept.x_cut = s_xcut;
-        race_kept.set_ref(xM);
-        race_kept.refresh_c();
-        static_assert(kWavesPerBlock * kQueueBytesPerWave <= kHistSlots * 8, "the queues reuse the histogram");
-        CompactRace<Race<false, false, true>> gathered{
-            race_kept, (float*)s_hist + wave * (kQueueCap * 4),
-            (uint32_t*)s_hist + kWavesPerBlock * (kQueueCap * 4) + wave * kQueueCap};
-        sweep<T>(row, p.V, gathered);
-        gathered.finish();
     }
 
     // Block arg-max of the exact perturbed values (lowest index on ties).
@@ -754,7 +752,7 @@ __global__ __launch_bounds__(kThreads) void sample_rows(const T* __restrict__ lo
                 if (s_best[w] > b || (s_best[w] == b && s_besti[w] < bi)) { b = s_best[w]; bi = s_besti[w]; }
             if (p.policy_version_out) p.policy_version_out[r] = p.policy_version;
             if ((uint32_t)bi >= (uint32_t)p.V) {  // no finite entry in the row
-                tokens_out[r] = 0;
+                tokens_out[r] = -1;
                 logprob_out[r] = NAN;
                 if (raw_logprob_out) raw_logprob_out[r] = NAN;
             } else {

@@ -137,3 +137,23 @@ def test_top_p_cut_at_every_depth_of_the_row(dtype):
     for T, p in [(1.0, 0.9), (0.6, 0.5), (1.7, 0.999), (1.0, 0.02)]:
         for step in range(3):
             compare_sampling(lg, T, p, seed=1234, step=step)
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_row_without_a_finite_entry_gives_no_token(dtype):
+    # row 1 is masked entirely: token -1 and NaN log-probs, as the oracle says; its neighbours are
+    # untouched by it, with and without top-p
+    cfg = dataclasses.replace(wl.CONFIGS["c1"], batch=3, vocab=3001)
+    lg = wl.make_logits(cfg, 12).to(dtype)
+    full = torch.zeros((3, 3008), dtype=dtype, device="cuda")    # rows dense, stride a multiple of 8
+    full[:, :3001] = lg.cuda()
+    full[1, :] = float("-inf")
+    lg = full[:, :3001]
+    import oracle
+    for T, p in [(1.0, 1.0), (0.8, 0.9)]:
+        tok, lp, raw = run_sample(lg, T, p, 5, 1, want_raw=True)
+        ref = oracle.sample_logprob(wl.logits_numpy(lg), T, p, 5, 1)
+        assert tok[1] == -1 and ref["tokens"][1] == -1
+        assert np.isnan(lp[1]) and np.isnan(raw[1])
+        for r in (0, 2):
+            assert tok[r] == ref["tokens"][r] and abs(lp[r] - ref["logprob"][r]) <= 1e-3
