@@ -157,3 +157,18 @@ def test_row_without_a_finite_entry_gives_no_token(dtype):
         assert np.isnan(lp[1]) and np.isnan(raw[1])
         for r in (0, 2):
             assert tok[r] == ref["tokens"][r] and abs(lp[r] - ref["logprob"][r]) <= 1e-3
+
+
+@pytest.mark.parametrize("T", [0.01, 0.05, 10.0, 100.0])
+def test_extreme_temperatures_and_tiny_vocabularies(T):
+    # T = 0.01 multiplies the logits by 100 (nearly greedy, exponents hundreds of binary orders
+    # apart), T = 100 flattens them; vocabularies of one and two entries have nothing to sweep
+    for dtype in ("bf16", "f32"):
+        for V in (1, 2, 9, 4097):
+            cfg = dataclasses.replace(wl.CONFIGS["c1"], batch=6, vocab=V, logits_dtype=dtype, logits="normal2")
+            stride = (V + 7) // 8 * 8
+            full = torch.zeros((6, stride), dtype=torch.bfloat16 if dtype == "bf16" else torch.float32,
+                               device="cuda")
+            full[:, :V] = wl.make_logits(cfg, 77 + V, "cuda")
+            for p in (1.0, 0.5, 0.999):
+                compare_sampling(full[:, :V], T, p, 9, 3)
