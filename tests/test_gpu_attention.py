@@ -140,3 +140,18 @@ def test_repeat_calls_are_bit_identical():
     a = run_attn(inp, cfg, torch.float32)
     b = run_attn(inp, cfg, torch.float32)
     assert np.array_equal(a, b)
+
+
+def test_maximum_batch_of_short_and_empty_rows():
+    # 8192 rows (the limit of the row prefix in LDS), most of a few tokens, many empty, some longer
+    B = 8192
+    rng = np.random.default_rng(B)
+    lengths = rng.integers(0, 40, size=B).astype(np.int32)
+    lengths[::97] = 300
+    cfg = dataclasses.replace(wl.CONFIGS["c1"], batch=B, num_q_heads=4, num_kv_heads=2, head_dim=64, page_size=16)
+    inp = wl.make_attn_inputs(cfg, 31, "cpu", lengths=np.maximum(lengths, 1))
+    inp["seq_lens"] = lengths
+    got = run_attn(inp, cfg, out_dtype=torch.float32)
+    want = oracle_attn(inp, cfg)
+    assert np.abs(got - want).max() <= 1e-4
+    assert not got[lengths == 0].any()
