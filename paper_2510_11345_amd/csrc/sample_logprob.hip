@@ -202,7 +202,8 @@ struct Race {
     float s_raw = 0.f;       // the same at temperature 1 (LSE and RAW only)
     double best = -INFINITY; // best exact perturbed logit of this lane, natural-log units
     int32_t best_i = 0x7FFFFFFF;
-    uint32_t* block_thr_key; // LDS: order_key of the largest threshold any wave of the workgroup published
+    uint32_t* block_thr_key = nullptr;  // LDS: order_key of the largest threshold any wave of the
+                                        // workgroup published (set before the first run)
     float thr2 = -INFINITY;  // lower bound of the row's best perturbed logit, log2 units: the largest
                              // exact value this wave has seen, or one another wave published
     uint32_t thr_key = order_key(-INFINITY);
