@@ -528,7 +528,7 @@ __device__ __forceinline__ unsigned long long top_p_target(float top_p, unsigned
 // One radix level: histogram of the digit at SHIFT (BITS wide) over the entries whose higher
 // key bits equal the prefix chosen so far, then the suffix scan that picks the next digit.
 template <typename T, int SHIFT>
-__device__ void radix_level(const T* __restrict__ row, const SampleParams& p, float nk,
+__device__ void radix_level(const T* __restrict__ row, int32_t n, const SampleParams& p, float nk,
                             unsigned long long* s_hist, unsigned long long* s_tot,
                             unsigned long long* s_wave, Select* s_sel, unsigned long long& target) {
     const int tid = threadIdx.x, lane = tid & 63;
@@ -536,7 +536,7 @@ __device__ void radix_level(const T* __restrict__ row, const SampleParams& p, fl
     __syncthreads();
     const uint32_t prefix = s_sel->prefix;
     Histogram<SHIFT> h{p.k2, nk, prefix, s_hist, (uint32_t)(lane & (kCopies - 1))};
-    sweep<T>(row, p.V, h);
+    sweep<T>(row, n, h);
     __syncthreads();
     if (tid < kBins) {  // fold the copies of my bin
         unsigned long long t = 0;
@@ -549,6 +549,30 @@ __device__ void radix_level(const T* __restrict__ row, const SampleParams& p, fl
     const int bin = kBins - 1 - tid;
     scan_select(tid < kBins ? s_tot[bin] : 0ull, (prefix << kRadixBits) | (uint32_t)bin, s_wave, s_sel, target);
 }
+
+// The entries whose upper 16 key bits equal `prefix`, copied to a list in LDS (in no particular
+// order: what is done with them does not depend on it).  *count ends as the number of such
+// entries, also when they do not all fit.
+struct GatherPrefix {
+    uint32_t prefix;
+    float* list;
+    int32_t* count;
+    int32_t capacity;
+    template <int N> __device__ __forceinline__ void run(int32_t, const float (&x)[N], bool) {
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            const bool match = (order_key(x[j]) >> 16) == prefix;
+            const unsigned long long mask = __ballot(match);
+            if (mask == 0) continue;
+            int32_t base = 0;
+            if ((threadIdx.x & 63) == 0) base = atomicAdd(count, (int32_t)__popcll(mask));
+            base = __builtin_amdgcn_readfirstlane(base);
+            const int32_t pos = base + (int32_t)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                                          __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+            if (match && pos < capacity) list[pos] = x[j];
+        }
+    }
+};
 
 // The upper 16 key bits in one sweep, for rows whose cut lies within kWindowBytes values of the
 // key's top byte below the row max (eight binades for four bytes): a histogram over the 16-bit
@@ -623,7 +647,7 @@ __device__ bool window_level(const T* __restrict__ row, const SampleParams& p, f
     __syncthreads();
     const int bin = kBins - 1 - tid;
     scan_select(tid < kBins ? s_tot[bin] : 0ull, (uint32_t)bin, s_wave, s_sel, target);
-    radix_level<T, 16>(row, p, nk, s_hist, s_tot, s_wave, s_sel, target);
+    radix_level<T, 16>(row, p.V, p, nk, s_hist, s_tot, s_wave, s_sel, target);
     return true;
 }
 
@@ -648,6 +672,7 @@ __global__ __launch_bounds__(kThreads) void sample_rows(const T* __restrict__ lo
     __shared__ double s_sraw[kWavesPerBlock];
     __shared__ double s_raw_lse;
     __shared__ uint32_t s_thr_key;
+    __shared__ int32_t s_count;
 
     const int32_t r = blockIdx.x;
     const T* __restrict__ row = logits + (int64_t)r * p.row_stride;
@@ -709,9 +734,23 @@ __global__ __launch_bounds__(kThreads) void sample_rows(const T* __restrict__ lo
         // entry) has no cut and no race: the result below is then "no token".
         const bool has_mass = window_level<T>(row, p, xM, nkM, s_hist, s_tot, s_wave, &s_sel, target);
         if (has_mass) {
-            if (kKeyBits == 32) {
-                radix_level<T, 8>(row, p, nkM, s_hist, s_tot, s_wave, &s_sel, target);
-                radix_level<T, 0>(row, p, nkM, s_hist, s_tot, s_wave, &s_sel, target);
+            if constexpr (kKeyBits == 32) {
+                // The lower 16 key bits concern only the entries that share the upper 16 with the
+                // cut, usually a few hundred: they are gathered into LDS in one sweep and the two
+                // byte-wide levels run over that list.  Rows with more such entries than the list
+                // holds (many equal logits) take the levels over the whole row.
+                constexpr int32_t kListCap = (kHistSlots - kBins * kCopies) * 2;  // floats behind the level's bins
+                float* list = (float*)(s_hist + kBins * kCopies);
+                if (tid == 0) s_count = 0;
+                __syncthreads();
+                GatherPrefix g{s_sel.prefix, list, &s_count, kListCap};
+                sweep<T>(row, p.V, g);
+                __syncthreads();
+                const int32_t n_list = s_count;
+                const T* src = n_list <= kListCap ? (const T*)list : row;
+                const int32_t n_src = n_list <= kListCap ? n_list : p.V;
+                radix_level<T, 8>(src, n_src, p, nkM, s_hist, s_tot, s_wave, &s_sel, target);
+                radix_level<T, 0>(src, n_src, p, nkM, s_hist, s_tot, s_wave, &s_sel, target);
             }
             if (tid == 0) {
                 // s_sel.prefix is now the key of the cut value (its upper 16 bits for bf16, whose

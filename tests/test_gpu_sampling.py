@@ -139,6 +139,30 @@ def test_top_p_cut_at_every_depth_of_the_row(dtype):
             compare_sampling(lg, T, p, seed=1234, step=step)
 
 
+def test_fp32_top_p_with_crowded_cut_bucket():
+    # fp32 rows whose cut value shares its upper 16 key bits with few, 8192, 8193 and all of the
+    # row's entries (equal values and distinct ones): the lower key bits are resolved over those
+    # entries alone when they fit on chip and over the whole row otherwise, with one result.
+    g = torch.Generator().manual_seed(91)
+    V = 20000
+    fine = 2.0 + torch.randint(0, 1 << 16, (V,), generator=g).float() * 2.0 ** -22   # one bucket: [2, 2 + 2^-6)
+    rows = []
+    for crowd in (300, 8192, 8193, V):
+        r = -3.0 + 0.5 * torch.randn((V,), generator=g)
+        idx = torch.randperm(V, generator=g)[:crowd]
+        r[idx] = fine[idx]
+        rows.append(r)
+    rows.append(torch.full((V,), 0.75))
+    eq = -3.0 + 0.5 * torch.randn((V,), generator=g)
+    eq[torch.randperm(V, generator=g)[:9000]] = 2.0
+    rows.append(eq)
+    lg = torch.stack(rows).contiguous()
+    assert lg.dtype == torch.float32
+    for T, p in [(1.0, 0.9), (0.5, 0.4), (1.0, 0.999), (2.0, 0.05)]:
+        for step in range(2):
+            compare_sampling(lg, T, p, seed=4321, step=step)
+
+
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
 def test_row_without_a_finite_entry_gives_no_token(dtype):
     # row 1 is masked entirely: token -1 and NaN log-probs, as the oracle says; its neighbours are
