@@ -119,18 +119,28 @@ __global__ void zero_words(uint32_t* dst, size_t n) {
     if (i < n) dst[i] = 0u;
 }
 
-// How the R row steps are cut into ranges.
+// How the row steps are cut into ranges.  A wave runs alone on its SIMD, so what a stream costs
+// beyond its steps (the merge or the result store of the one before, its Q, its first page ids and
+// first K/V bytes, each a round trip to memory with nothing to hide behind) is time in which the
+// wave streams nothing: about one step, measured.  Ranges are therefore equal in
+// cost, not in steps: on a line where every row that holds tokens takes kRowCost units followed
+// by kStepCost units for each of its steps, range c begins at position floor(c T / NC) of the T
+// units in all, and owns the steps that begin at or after that position and before the next
+// range's.  A range with many short rows gets fewer steps.
+constexpr int32_t kStepCost = 2;
+constexpr int32_t kRowCost = 2;
 struct Deal {
-    int64_t R;   // total steps over all rows (one KV head)
+    int64_t T;   // total cost units over all rows (one KV head)
     int32_t NC;  // ranges in use
-    __device__ Deal(int32_t steps, int32_t waves, int32_t Hkv) : R(steps) {
+    __device__ Deal(int32_t steps, int32_t rows, int32_t waves, int32_t Hkv)
+        : T((int64_t)steps * kStepCost + (int64_t)rows * kRowCost) {
         const int32_t want = (steps + kMinSteps - 1) / kMinSteps;
         const int32_t most = max_ranges(waves, Hkv);
         NC = want < 1 ? 1 : (want < most ? want : most);
     }
-    __device__ int32_t first_step(int32_t c) const { return (int32_t)((int64_t)c * R / NC); }
-    // the range that holds row step i
-    __device__ int32_t owner(int32_t i) const { return (int32_t)((((int64_t)i + 1) * NC + R - 1) / R - 1); }
+    __device__ int64_t boundary(int32_t c) const { return (int64_t)c * T / NC; }
+    // the range that owns a step whose first cost unit is x: the last c with boundary(c) <= x
+    __device__ int32_t owner(int64_t x) const { return (int32_t)(((x + 1) * NC + T - 1) / T - 1); }
     // the slots of (range c, KV head h): 0 for a piece that begins the range, 1 for one that ends it
     __device__ int64_t slot(int32_t c, int32_t h, int32_t Hkv, bool begins) const {
         return ((int64_t)c * Hkv + h) * 2 + (begins ? 0 : 1);
@@ -277,15 +287,15 @@ __device__ __forceinline__ void accumulate_step(const WaveCtx<D>& c, const float
     softmax_pv<D>(sv, s, scale_log2e, a);
 }
 
-// Steps per row into LDS as an exclusive prefix, clamped lengths beside it.
-// pre has B + 1 entries, len has B.  All threads of the workgroup take part.
-// With grow, every row that holds tokens counts one more than the stored length (the token
-// appended by the same launch).
+// Steps per row into LDS as an exclusive prefix, clamped lengths beside it, and the number of
+// rows with tokens before each row.  pre and live have B + 1 entries, len has B.  All threads of
+// the workgroup take part.  With grow, every row that holds tokens counts one more than the
+// stored length (the token appended by the same launch).
 __device__ void build_row_prefix(const int32_t* seq_lens, int32_t B, int32_t max_len, bool grow,
-                                 int32_t* pre, int32_t* len, int32_t* s_wave_tot) {
+                                 int32_t* pre, int32_t* len, uint16_t* live, int32_t* s_wave_tot) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nthreads = blockDim.x, nwaves = nthreads >> 6;
-    int32_t carry = 0;
+    int32_t carry = 0, carry_live = 0;
     for (int32_t base = 0; base < B; base += nthreads) {
         const int32_t b = base + tid;
         int32_t L = 0;
@@ -302,17 +312,33 @@ __device__ void build_row_prefix(const int32_t* seq_lens, int32_t B, int32_t max
             const int32_t v = __shfl_up(incl, d);
             if (lane >= d) incl += v;
         }
-        if (lane == 63) s_wave_tot[wave] = incl;
+        const unsigned long long live_mask = __ballot(n > 0);
+        const int32_t live_before = (int32_t)__builtin_amdgcn_mbcnt_hi((uint32_t)(live_mask >> 32),
+                                                                      __builtin_amdgcn_mbcnt_lo((uint32_t)live_mask, 0u));
+        if (lane == 63) {
+            s_wave_tot[wave] = incl;
+            s_wave_tot[kGroupWaves + wave] = (int32_t)__popcll(live_mask);
+        }
         __syncthreads();
-        int32_t before = carry;
-        for (int w = 0; w < wave; ++w) before += s_wave_tot[w];
-        int32_t tile_total = 0;
-        for (int w = 0; w < nwaves; ++w) tile_total += s_wave_tot[w];
-        if (b < B) pre[b] = before + incl - n;
-        carry += tile_total;
+        int32_t before = carry, before_live = carry_live;
+        for (int w = 0; w < wave; ++w) {
+            before += s_wave_tot[w];
+            before_live += s_wave_tot[kGroupWaves + w];
+        }
+        for (int w = 0; w < nwaves; ++w) {
+            carry += s_wave_tot[w];
+            carry_live += s_wave_tot[kGroupWaves + w];
+        }
+        if (b < B) {
+            pre[b] = before + incl - n;
+            live[b] = (uint16_t)(before_live + live_before);
+        }
         __syncthreads();
     }
-    if (tid == 0) pre[B] = carry;
+    if (tid == 0) {
+        pre[B] = carry;
+        live[B] = (uint16_t)carry_live;
+    }
     __syncthreads();
 }
 
@@ -457,8 +483,9 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
     extern __shared__ int32_t lds[];
     int32_t* pre = lds;                  // [B + 1]
     int32_t* len = lds + prm.B + 1;      // [B]
-    __shared__ int32_t s_wave_tot[kGroupWaves];
-    build_row_prefix(seq_lens, prm.B, prm.max_len, FUSED, pre, len, s_wave_tot);
+    uint16_t* live = (uint16_t*)(lds + 2 * prm.B + 1);  // [B + 1] rows with tokens before row b
+    __shared__ int32_t s_wave_tot[2 * kGroupWaves];
+    build_row_prefix(seq_lens, prm.B, prm.max_len, FUSED, pre, len, live, s_wave_tot);
 
     const int32_t lane = threadIdx.x & 63;
     const int32_t w = blockIdx.x * kGroupWaves + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -484,7 +511,7 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
     }
 
     // Ranges of row steps and the (range, KV heads) of this wave: see the top of the file.
-    const Deal deal(pre[prm.B], prm.W, Hkv);
+    const Deal deal(pre[prm.B], live[prm.B], prm.W, Hkv);
     const int32_t cut = ranges_cut(Hkv);
     const int32_t wj = w & (kGroupWaves - 1);
     const int32_t c = (int32_t)blockIdx.x * cut + (cut > 1 ? wj / Hkv : 0);
@@ -511,8 +538,23 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
         }
         return lo;
     };
-    const int32_t item0 = c < deal.NC ? deal.first_step(c) : 0;
-    const int32_t todo0 = c < deal.NC ? deal.first_step(c + 1) - item0 : 0;
+    // Position of row b on the cost line, and the first step a range owns (see Deal).
+    auto cost_pre = [&](int32_t b) -> int64_t { return (int64_t)pre[b] * kStepCost + (int64_t)live[b] * kRowCost; };
+    auto first_step = [&](int32_t range) -> int32_t {
+        if (range >= deal.NC) return pre[prm.B];
+        const int64_t x = deal.boundary(range);
+        int32_t lo = 0, hi = prm.B;  // invariant: cost_pre(lo) <= x < cost_pre(hi); row lo ends up with tokens
+        while (hi - lo > 1) {
+            const int32_t mid = (lo + hi) >> 1;
+            if (cost_pre(mid) <= x) lo = mid; else hi = mid;
+        }
+        const int64_t local = x - cost_pre(lo);
+        const int32_t n = pre[lo + 1] - pre[lo];
+        const int64_t k = local <= kRowCost ? 0 : (local - kRowCost + kStepCost - 1) / kStepCost;
+        return pre[lo] + (int32_t)(k < n ? k : n);
+    };
+    const int32_t item0 = c < deal.NC ? first_step(c) : 0;
+    const int32_t todo0 = c < deal.NC ? first_step(c + 1) - item0 : 0;
 
     for (int32_t h = h_begin; h < Hkv && todo0 > 0; h += h_stride) {
         int32_t todo = todo0;
@@ -529,9 +571,12 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
         // most of them.
         auto deliver = [&](const WaveAcc<D>& mine, int32_t pb, bool begins) {
             const int32_t g0 = pre[pb], n_pb = pre[pb + 1] - g0;
-            const int32_t c0 = deal.owner(g0), c1 = deal.owner(g0 + n_pb - 1);
+            const int64_t x0 = cost_pre(pb) + kRowCost;  // the row's first step on the cost line
+            const int32_t c0 = deal.owner(x0), c1 = deal.owner(x0 + (int64_t)(n_pb - 1) * kStepCost);
             const int32_t pieces = c1 - c0 + 1;
-            const int64_t slot0 = deal.slot(c0, h, Hkv, deal.first_step(c0) == g0);
+            // c0 begins with this row if it owns nothing of the row before: its boundary lies past
+            // the first unit of that row's last step
+            const int64_t slot0 = deal.slot(c0, h, Hkv, deal.boundary(c0) + kStepCost > cost_pre(pb));
             const int64_t out_idx = ((int64_t)pb * prm.Hq + (int64_t)h * G + rr) * D + 4 * ctx.q;
             const int32_t my_pi = c - c0;
             const int32_t gid = my_pi / kMergeGroup;
@@ -797,7 +842,7 @@ int launch_attn(const void* q, const void* k_pages, const void* v_pages, const i
     if (workspace_bytes < ws.bytes)
         return roll::fail(ROLL_ERR_WORKSPACE, "workspace too small: %zu < %zu bytes", workspace_bytes, ws.bytes);
 
-    const size_t lds = sizeof(int32_t) * (2 * (size_t)d->batch + 1);
+    const size_t lds = sizeof(int32_t) * (2 * (size_t)d->batch + 1) + sizeof(uint16_t) * ((size_t)d->batch + 2);
     int32_t W = 0;
     int rc = persistent_waves(d->head_dim, lds, &W);
     if (rc != ROLL_OK) return rc;

@@ -59,6 +59,25 @@ def test_rows_cut_across_many_waves_and_tiny_batches(lengths):
     assert np.isfinite(got).all() and err <= TOL_F32
 
 
+@pytest.mark.parametrize("Hq,Hkv", [(28, 4), (16, 2), (24, 8), (12, 6)])
+def test_short_rows_clustered_beside_long_ones(Hq, Hkv):
+    # Ranges are equal in cost, a row costing about a step beyond its steps: a range of one-step
+    # rows holds fewer steps than one inside a long row, and range ends fall at every place of a
+    # row (its first step, its last, the gap between two rows, empty rows between).
+    rng = np.random.default_rng(Hq * 100 + Hkv)
+    short = rng.integers(0, 70, size=700)
+    short[rng.integers(0, 700, size=60)] = 0
+    lens = np.concatenate([short[:350], rng.integers(1500, 6000, size=12), short[350:], [9000, 1, 0, 33, 32, 31]]).astype(np.int32)
+    cfg = dataclasses.replace(wl.CONFIGS["c2"], batch=len(lens), num_q_heads=Hq, num_kv_heads=Hkv)
+    inp = wl.make_attn_inputs(cfg, 17, "cpu", lengths=np.maximum(lens, 1))
+    ref = oracle_attn(inp, cfg, seq_lens=lens)
+    got = run_attn(inp, cfg, torch.float32, seq_lens=lens)
+    err = np.abs(got - ref).max()
+    say(f"  attn clustered short rows Hq={Hq} Hkv={Hkv} B={len(lens)} sumL={int(lens.sum())}: max abs err {err:.3e}")
+    assert np.isfinite(got).all() and err <= TOL_F32
+    assert not got[lens == 0].any()
+
+
 def test_7b_shape_lognormal_lengths():
     cfg = wl.CONFIGS["c2"]
     L = np.minimum(wl.draw_lengths(cfg.lengths, 24, 2), 6000)
