@@ -8,16 +8,16 @@
 // different lengths share the chip evenly.
 //
 // Work decomposition (split-K over the flattened batch).  Row b with L_b tokens
-// is ceil(L_b / 32) steps of 32 tokens; the rows' steps are laid end to end, R
-// in all, and cut into equal ranges, one per persistent workgroup of four
-// waves.  The four waves of a workgroup walk the SAME range of row steps, each
+// is ceil(L_b / 32) steps of 32 tokens; the rows' steps are laid end to end
+// and cut into ranges of equal cost (a row's steps plus one for starting it:
+// see Deal), one per persistent workgroup of four waves.  The four waves of a workgroup walk the SAME range of row steps, each
 // for KV heads of its own (wave j: heads j, j + 4, ...; with fewer than four KV
 // heads the range is cut again so that every wave has a part of one head).
 // They run in step, so at any moment the workgroup reads the blocks of one page
 // for four neighbouring heads, which lie next to each other in the pool: the
 // memory system delivers 6.9-7.0 TB/s to such reads and 6.0-6.2 TB/s when the
 // four waves read pages of their own (measured with equal rows, all else
-// equal).  Every wave reads the same number of bytes whatever the length mix, a
+// equal).  Every wave has the same share of the work whatever the length mix, a
 // row longer than a range is cut across neighbouring workgroups, and for every
 // head at most the first and the last row of a range are pieces; a wave writes
 // a complete (row, head) stream straight to `out` and a piece (running max,
