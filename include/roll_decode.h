@@ -217,6 +217,23 @@ typedef struct roll_attn_desc {
 size_t roll_decode_attn_workspace_bytes(const roll_attn_desc* desc);
 
 /*
+ * HOST, introspection for tests and schedulers: how roll_decode_attn would
+ * cut a batch with these lengths across `workgroups` persistent workgroups
+ * (a launch uses one per compute unit).  The rows' 32-token steps, laid end
+ * to end, are cut into ranges that are equal in cost, a row counting one step
+ * more than it has (what starting a row costs a wave); range c owns the steps
+ * first_step_out[c] .. first_step_out[c + 1] - 1.  Arithmetic shared with the
+ * kernel.  Long-tailed lengths: Section 1 of the paper.
+ *   seq_lens_host   HOST int32 [B], clamped as the kernel clamps them
+ *   first_step_out  HOST int32 [capacity]; num_ranges + 1 entries are written
+ *   num_ranges_out  HOST; written also when capacity is too small (then the
+ *                   call returns ROLL_ERR_INVALID_ARG and writes nothing else)
+ * Touches no device.
+ */
+int roll_decode_attn_ranges(const roll_attn_desc* desc, const int32_t* seq_lens_host, int32_t workgroups,
+                            int32_t* first_step_out, int32_t capacity, int32_t* num_ranges_out);
+
+/*
  * Prepare a workspace: enqueues a kernel on stream that zeroes the arrival
  * counters at its start.  Call once after allocating the buffer (and again if
  * anything else has written to it, or after a call that failed on the

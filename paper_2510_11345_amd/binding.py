@@ -26,6 +26,7 @@ EXPORTS = [
     "roll_kv_fused_steps",
     "roll_kv_append_tokens",
     "roll_decode_attn_workspace_bytes", "roll_decode_attn_workspace_init", "roll_decode_attn",
+    "roll_decode_attn_ranges",
     "roll_decode_step_attn", "roll_prefill_attn",
     "roll_sample_logprob_workspace_bytes", "roll_sample_logprob", "roll_policy_loss",
     "roll_sample_buffer_create", "roll_sample_buffer_destroy", "roll_sample_buffer_begin",
@@ -110,6 +111,8 @@ def lib():
         L.roll_kv_append_tokens.argtypes = [C.c_void_p] * 5 + [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p] + \
             [C.c_int32] * 5 + [C.c_void_p]
         L.roll_decode_attn_workspace_init.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
+        L.roll_decode_attn_ranges.argtypes = [C.POINTER(AttnDesc), C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
+                                              C.POINTER(C.c_int32)]
         L.roll_decode_attn.argtypes = [C.c_void_p] * 6 + [C.POINTER(AttnDesc), C.c_void_p, C.c_size_t, C.c_void_p]
         L.roll_decode_step_attn.argtypes = [C.c_void_p] * 7 + [C.POINTER(AttnDesc), C.c_void_p, C.c_size_t, C.c_void_p]
         L.roll_prefill_attn.argtypes = [C.c_void_p] * 10 + [C.POINTER(PrefillDesc), C.c_void_p]
@@ -271,6 +274,21 @@ def roll_decode_attn_workspace_bytes(desc: AttnDesc) -> int:
     if n == 0:
         raise RollError(-1, lib().roll_last_error().decode())
     return n
+
+
+def roll_decode_attn_ranges(desc: AttnDesc, seq_lens, workgroups: int = 256):
+    """First step of every range roll_decode_attn would cut this batch into (host arithmetic only),
+    as an int32 array of num_ranges + 1 entries."""
+    import numpy as np
+    lens = np.ascontiguousarray(seq_lens, dtype=np.int32)
+    if lens.shape != (desc.batch,):
+        raise ValueError("seq_lens must hold one length per row")
+    n = C.c_int32(0)
+    cap = 4 * 256 * 4 + 2
+    out = np.zeros(cap, dtype=np.int32)
+    _check(lib().roll_decode_attn_ranges(C.byref(desc), lens.ctypes.data, workgroups, out.ctypes.data, cap,
+                                         C.byref(n)))
+    return out[:n.value + 1].copy()
 
 
 def roll_decode_attn_workspace_init(workspace: torch.Tensor) -> None:

@@ -35,11 +35,14 @@
 // shared with the prefill kernel and described where it is defined.
 #include <cfloat>
 #include <cmath>
+#include <climits>
 #include <mutex>
+#include <vector>
 
 #include <type_traits>
 
 #include "attn_core.h"
+#include "attn_deal.h"
 #include "common.h"
 #include "kv_layout.h"
 #include "kv_pool_internal.h"
@@ -47,12 +50,10 @@
 namespace {
 
 using namespace roll::attn;
+static_assert(kDealStep == kStep, "the dealing and the kernel must agree on the step");
 
-constexpr int kGroupWaves = 4;     // wavefronts per workgroup (they only share the LDS prefix)
-constexpr int kMinSteps = 4;       // do not cut a small batch into ranges shorter than this
 constexpr int kMaxBatch = 8192;    // rows whose prefix sums fit the LDS budget
 constexpr int kMaxStreams = 65536; // batch * num_kv_heads: one arrival counter each
-constexpr int kMaxSlots = 32768;   // piece slots: two per (range of row steps, KV head)
 constexpr int kMergeGroup = 16;    // pieces merged by one wave at the first level
 // Upper bound of persistent waves, used to size the workspace without touching the device:
 // 16 waves on each of 256 compute units (a gfx950 device has no more).
@@ -83,19 +84,6 @@ struct Workspace {
 
 __host__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// Ranges of row steps a launch of `waves` persistent waves can use (before the limits that depend
-// on the batch): one per workgroup, times the cut within a workgroup when there are fewer KV
-// heads than waves; never more than the piece slots allow.
-__host__ __device__ inline int32_t ranges_cut(int32_t Hkv) {
-    return (Hkv < kGroupWaves && kGroupWaves % Hkv == 0) ? kGroupWaves / Hkv : 1;
-}
-__host__ __device__ inline int32_t max_ranges(int32_t waves, int32_t Hkv) {
-    const int32_t by_waves = waves / kGroupWaves * ranges_cut(Hkv);
-    const int32_t by_slots = kMaxSlots / (2 * Hkv);
-    const int32_t n = by_waves < by_slots ? by_waves : by_slots;
-    return n < 1 ? 1 : n;
-}
-
 // The header does not depend on the shape (roll_decode_attn_workspace_init has none).
 __host__ Workspace carve(void* base, int32_t Hkv, int32_t G, int32_t D) {
     Workspace w{};
@@ -118,34 +106,6 @@ __global__ void zero_words(uint32_t* dst, size_t n) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) dst[i] = 0u;
 }
-
-// How the row steps are cut into ranges.  A wave runs alone on its SIMD, so what a stream costs
-// beyond its steps (the merge or the result store of the one before, its Q, its first page ids and
-// first K/V bytes, each a round trip to memory with nothing to hide behind) is time in which the
-// wave streams nothing: about one step, measured.  Ranges are therefore equal in
-// cost, not in steps: on a line where every row that holds tokens takes kRowCost units followed
-// by kStepCost units for each of its steps, range c begins at position floor(c T / NC) of the T
-// units in all, and owns the steps that begin at or after that position and before the next
-// range's.  A range with many short rows gets fewer steps.
-constexpr int32_t kStepCost = 2;
-constexpr int32_t kRowCost = 2;
-struct Deal {
-    int64_t T;   // total cost units over all rows (one KV head)
-    int32_t NC;  // ranges in use
-    __device__ Deal(int32_t steps, int32_t rows, int32_t waves, int32_t Hkv)
-        : T((int64_t)steps * kStepCost + (int64_t)rows * kRowCost) {
-        const int32_t want = (steps + kMinSteps - 1) / kMinSteps;
-        const int32_t most = max_ranges(waves, Hkv);
-        NC = want < 1 ? 1 : (want < most ? want : most);
-    }
-    __device__ int64_t boundary(int32_t c) const { return (int64_t)c * T / NC; }
-    // the range that owns a step whose first cost unit is x: the last c with boundary(c) <= x
-    __device__ int32_t owner(int64_t x) const { return (int32_t)(((x + 1) * NC + T - 1) / T - 1); }
-    // the slots of (range c, KV head h): 0 for a piece that begins the range, 1 for one that ends it
-    __device__ int64_t slot(int32_t c, int32_t h, int32_t Hkv, bool begins) const {
-        return ((int64_t)c * Hkv + h) * 2 + (begins ? 0 : 1);
-    }
-};
 
 // KV is read exactly once per step: a nontemporal load keeps it from displacing the
 // page table, Q and the pieces in L2 (measured: +10 % on a plain streaming read).
@@ -538,21 +498,8 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
         }
         return lo;
     };
-    // Position of row b on the cost line, and the first step a range owns (see Deal).
-    auto cost_pre = [&](int32_t b) -> int64_t { return (int64_t)pre[b] * kStepCost + (int64_t)live[b] * kRowCost; };
-    auto first_step = [&](int32_t range) -> int32_t {
-        if (range >= deal.NC) return pre[prm.B];
-        const int64_t x = deal.boundary(range);
-        int32_t lo = 0, hi = prm.B;  // invariant: cost_pre(lo) <= x < cost_pre(hi); row lo ends up with tokens
-        while (hi - lo > 1) {
-            const int32_t mid = (lo + hi) >> 1;
-            if (cost_pre(mid) <= x) lo = mid; else hi = mid;
-        }
-        const int64_t local = x - cost_pre(lo);
-        const int32_t n = pre[lo + 1] - pre[lo];
-        const int64_t k = local <= kRowCost ? 0 : (local - kRowCost + kStepCost - 1) / kStepCost;
-        return pre[lo] + (int32_t)(k < n ? k : n);
-    };
+    auto cost_pre = [&](int32_t b) -> int64_t { return roll::attn::cost_pre(pre, live, b); };
+    auto first_step = [&](int32_t range) -> int32_t { return roll::attn::first_step(deal, range, prm.B, pre, live); };
     const int32_t item0 = c < deal.NC ? first_step(c) : 0;
     const int32_t todo0 = c < deal.NC ? first_step(c + 1) - item0 : 0;
 
@@ -822,6 +769,39 @@ extern "C" int roll_decode_attn_workspace_init(void* workspace, size_t workspace
     const size_t words = ws.header_bytes / 4;
     zero_words<<<(unsigned)((words + 255) / 256), 256, 0, (hipStream_t)stream>>>((uint32_t*)workspace, words);
     ROLL_HIP_CHECK(hipGetLastError());
+    return ROLL_OK;
+}
+
+extern "C" int roll_decode_attn_ranges(const roll_attn_desc* d, const int32_t* seq_lens_host, int32_t workgroups,
+                                       int32_t* first_step_out, int32_t capacity, int32_t* num_ranges_out) {
+    int rc = validate(d);
+    if (rc != ROLL_OK) return rc;
+    if (!seq_lens_host || !first_step_out || !num_ranges_out) return roll::fail(ROLL_ERR_INVALID_ARG, "NULL pointer argument");
+    if (workgroups <= 0) return roll::fail(ROLL_ERR_INVALID_ARG, "workgroups must be > 0");
+    const int32_t B = d->batch;
+    const int64_t max_len = (int64_t)d->max_pages_per_seq * d->page_size;
+    std::vector<int32_t> pre((size_t)B + 1);
+    std::vector<uint16_t> live((size_t)B + 1);
+    int64_t steps = 0;
+    int32_t rows = 0;
+    for (int32_t b = 0; b < B; ++b) {
+        int64_t L = seq_lens_host[b];
+        L = L < 0 ? 0 : (L > max_len ? max_len : L);
+        pre[(size_t)b] = (int32_t)steps;
+        live[(size_t)b] = (uint16_t)rows;
+        steps += (L + kStep - 1) / kStep;
+        rows += L > 0;
+        if (steps > INT32_MAX) return roll::fail(ROLL_ERR_SEQ_TOO_LONG, "more than 2^31 steps of %d tokens in the batch", kStep);
+    }
+    pre[(size_t)B] = (int32_t)steps;
+    live[(size_t)B] = (uint16_t)rows;
+    int64_t waves = (int64_t)workgroups * kGroupWaves;
+    if (waves > kMaxPersistentWaves) waves = kMaxPersistentWaves;
+    const Deal deal((int32_t)steps, rows, (int32_t)waves, d->num_kv_heads);
+    *num_ranges_out = deal.NC;
+    if (capacity < deal.NC + 1)
+        return roll::fail(ROLL_ERR_INVALID_ARG, "first_step_out holds %d entries, %d needed", capacity, deal.NC + 1);
+    for (int32_t c = 0; c <= deal.NC; ++c) first_step_out[c] = first_step(deal, c, B, pre.data(), live.data());
     return ROLL_OK;
 }
 
