@@ -74,9 +74,9 @@ struct Workspace {
     int32_t* group_arrivals;   // [kMaxSlots] indexed by the slot of the first piece of a group
     int32_t* stream_arrivals;  // [kMaxStreams] indexed by row * Hkv + kv head
     // scratch
-    float2* part_ml;   // [slots * G] (max in log2 units, sum) of a piece
+    float2* part_ml;   // [slots * 16] (max in log2 units, sum) of a piece's heads: one 128-byte line per slot
     float* part_acc;   // [slots * G * D] un-normalised output of a piece
-    float2* group_ml;  // [slots * G] merged group of pieces, at the slot of the group's first piece
+    float2* group_ml;  // [slots * 16] merged group of pieces, at the slot of the group's first piece
     float* group_acc;  // [slots * G * D]
     size_t header_bytes;
     size_t bytes;
@@ -94,9 +94,9 @@ __host__ Workspace carve(void* base, int32_t Hkv, int32_t G, int32_t D) {
     w.group_arrivals = (int32_t*)(p + off);   off = align_up(off + sizeof(int32_t) * kMaxSlots, 256);
     w.stream_arrivals = (int32_t*)(p + off);  off = align_up(off + sizeof(int32_t) * kMaxStreams, 256);
     w.header_bytes = off;
-    w.part_ml = (float2*)(p + off);           off = align_up(off + sizeof(float2) * slots * G, 256);
+    w.part_ml = (float2*)(p + off);           off = align_up(off + sizeof(float2) * slots * 16, 256);
     w.part_acc = (float*)(p + off);           off = align_up(off + sizeof(float) * slots * G * D, 256);
-    w.group_ml = (float2*)(p + off);          off = align_up(off + sizeof(float2) * slots * G, 256);
+    w.group_ml = (float2*)(p + off);          off = align_up(off + sizeof(float2) * slots * 16, 256);
     w.group_acc = (float*)(p + off);          off = align_up(off + sizeof(float) * slots * G * D, 256);
     w.bytes = off;
     return w;
@@ -316,17 +316,29 @@ __device__ __forceinline__ f32x2_t coherent_load2(const float* p) {
     return f32x2_t{__uint_as_float((uint32_t)bits), __uint_as_float((uint32_t)(bits >> 32))};
 }
 
+// A piece's un-normalised output in the workspace: G * D floats per slot, laid out for the wave
+// that writes it, not by head: the 8-byte unit that lane (r, q) stores with its k-th instruction
+// (k = 2 nt + half) sits at unit (4 k + q) G + r, so that one store instruction of the wave covers
+// 32 G contiguous bytes, whole 32-byte sectors.  (By head, every instruction wrote half of each
+// sector it touched, and these stores go through to memory one by one.)
+__device__ __forceinline__ int64_t piece_unit(int64_t slot, int32_t G, int32_t D, int32_t r, int32_t q) {
+    return slot * ((int64_t)G * D) + 2 * ((int64_t)q * G + r);
+}
+
 // Store a piece (un-normalised) at `slot` of a piece array; lane (r, q) owns head r, quads 4q.
+// Called by the whole wave: the (max, sum) pairs of all sixteen tile rows go out as one 128-byte
+// line (the rows past G hold nothing that is read back), the output units only for r < G.
 template <int D>
 __device__ __forceinline__ void store_piece(const WaveAcc<D>& a, float2* ml, float* acc, int64_t slot,
                                             int32_t G, int32_t r, int32_t q) {
-    const int64_t row = slot * G + r;
-    if (q == 0) coherent_store2((float*)(ml + row), a.m, a.l);
-    float* dst = acc + row * D + 4 * q;
+    if (q == 0) coherent_store2((float*)(ml + slot * 16 + r), a.m, a.l);
+    if (r >= G) return;
+    float* dst = acc + piece_unit(slot, G, D, r, q);
+    const int32_t stride = 8 * G;  // floats between a lane's consecutive units
 #pragma unroll
     for (int nt = 0; nt < D / 16; ++nt) {
-        coherent_store2(dst + 16 * nt, a.o[nt][0], a.o[nt][1]);
-        coherent_store2(dst + 16 * nt + 2, a.o[nt][2], a.o[nt][3]);
+        coherent_store2(dst + (2 * nt) * stride, a.o[nt][0], a.o[nt][1]);
+        coherent_store2(dst + (2 * nt + 1) * stride, a.o[nt][2], a.o[nt][3]);
     }
 }
 
@@ -359,13 +371,14 @@ __device__ __forceinline__ void merge_pieces(WaveAcc<D>& out_acc, const float2* 
                     hi[k][nt] = f32x2_t{own->o[nt][2], own->o[nt][3]};
                 }
             } else if (base + k < n) {
-                const int64_t row = slot_of(base + k) * G + r;
-                m_l[k] = coherent_load2((const float*)(ml + row));
-                const float* src = acc + row * D + 4 * q;
+                const int64_t slot = slot_of(base + k);
+                m_l[k] = coherent_load2((const float*)(ml + slot * 16 + r));
+                const float* src = acc + piece_unit(slot, G, D, r, q);
+                const int32_t stride = 8 * G;
 #pragma unroll
                 for (int nt = 0; nt < D / 16; ++nt) {
-                    lo[k][nt] = coherent_load2(src + 16 * nt);
-                    hi[k][nt] = coherent_load2(src + 16 * nt + 2);
+                    lo[k][nt] = coherent_load2(src + (2 * nt) * stride);
+                    hi[k][nt] = coherent_load2(src + (2 * nt + 1) * stride);
                 }
             } else {
 #pragma unroll
@@ -550,7 +563,7 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
                 if (lane == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 merged = true;
             } else {
-                if (ctx.r < G) store_piece<D>(mine, part_ml, part_acc, deal.slot(c, h, Hkv, begins), G, ctx.r, ctx.q);
+                store_piece<D>(mine, part_ml, part_acc, deal.slot(c, h, Hkv, begins), G, ctx.r, ctx.q);
                 if (arrive_last(counter, gsize, lane)) {
                     merge_pieces<D>(grp, part_ml, part_acc, gsize,
                                     [&](int32_t i) -> int64_t { return piece_slot(gfirst + i); }, G, rr, ctx.q);
@@ -561,7 +574,7 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
             if (ngroups == 1) {
                 if (ctx.r < G) store_result_as<D, F32OUT>(grp, out, out_idx);
             } else {
-                if (ctx.r < G) store_piece<D>(grp, group_ml, group_acc, group_slot, G, ctx.r, ctx.q);
+                store_piece<D>(grp, group_ml, group_acc, group_slot, G, ctx.r, ctx.q);
                 if (arrive_last(stream_arrivals + pb * Hkv + h, ngroups, lane)) {
                     WaveAcc<D> all;
                     merge_pieces<D>(all, group_ml, group_acc, ngroups,
