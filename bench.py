@@ -154,8 +154,7 @@ def prefill_bench(args, torch, rb, wl):
         for s_, n in enumerate(lens):
             rb.roll_kv_alloc(pool, s_, int(n))
         rb.roll_kv_commit(pool)
-        k_pages = torch.zeros((num_pages, Hkv, D // 8, P, 8), dtype=torch.bfloat16, device="cuda")
-        v_pages = torch.zeros((num_pages, Hkv, P // 8, D, 8), dtype=torch.bfloat16, device="cuda")
+        k_pages, v_pages = rb.new_kv_pools(num_pages, Hkv, D, P, fill=0)
         # calls: one per chunk round; every call holds one chunk per prompt that still has tokens
         calls = []
         step = int(lens.max()) if chunk is None else chunk

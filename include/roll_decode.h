@@ -44,6 +44,17 @@
  * the block and the last four to the second half.  (The score tile of the
  * attention kernel hands each lane four consecutive tokens of either half;
  * with this order the K rows of one tile are contiguous in memory.)
+ *
+ * Page stride.  A page of a pool is Hkv * P * D elements; consecutive pages
+ * are page_stride elements apart, the same for both pools (0 = dense, the
+ * page size itself; otherwise a multiple of P * D that is >= Hkv * P * D).
+ * The stride lets K and V share ONE allocation with the two blocks of a page
+ * side by side, which is the layout to prefer:
+ *   kv[page][0 = K, 1 = V][...],  k_pages = kv,  v_pages = kv + Hkv * P * D,
+ *   page_stride = 2 * Hkv * P * D.
+ * A decode step then reads one contiguous 2 * Hkv * P * D * 2 bytes per page
+ * instead of two regions in different allocations, and DRAM serves fewer,
+ * longer runs: measured 4-5 % more KV bandwidth on the 7B-class shapes.
  */
 #ifndef ROLL_DECODE_H
 #define ROLL_DECODE_H
@@ -89,6 +100,8 @@ typedef struct roll_kv_config {
     int32_t page_size;          /* tokens per page: 16, 32 or 64 */
     int32_t num_slots;          /* rows of the running batch (B) */
     int32_t max_pages_per_seq;  /* row length of page_table */
+    int32_t run_pages;          /* pages handed out together: 0 or 1 = single pages; 2, 4 or 8 = aligned
+                                   runs of that many physically consecutive pages (see roll_kv_pool_create) */
 } roll_kv_config;
 
 /*
@@ -102,6 +115,16 @@ typedef struct roll_kv_config {
  * schedulers, tests) and roll_kv_commit is an error.
  * Free pages are handed out as a LIFO stack whose initial pop order is
  * 0, 1, 2, ...; no result of the decode step depends on that order.
+ * With run_pages = R > 1 the stack holds runs of R consecutive pages
+ * (R k .. R k + R - 1; num_pages is used up to a multiple of R): a slot
+ * takes a run when it needs page number 0, R, 2R, ... of its sequence and
+ * the following R - 1 pages come from the same run, so that R consecutive
+ * logical pages are physically adjacent however fragmented the pool has
+ * become; at most R - 1 pages per slot are held unused.  With 16-token pages
+ * R = 2 makes every 32-token step of the attention kernel one contiguous
+ * region (with K and V side by side: 2 * Hkv * 32 * D * 2 bytes), which DRAM
+ * serves 3-4 % faster than two scattered pages.  roll_kv_free_pages counts
+ * the pages of the free runs.
  */
 int roll_kv_pool_create(roll_kv_pool** pool, const roll_kv_config* cfg,
                         int32_t* page_table_dev, int32_t* seq_lens_dev);
@@ -148,10 +171,11 @@ int roll_kv_commit(roll_kv_pool* pool, void* stream);
  * write does not depend on the device tables being published first.
  *   k_new, v_new    DEVICE bf16 [num_slots, num_kv_heads, head_dim], row-major
  *   k_pages,v_pages DEVICE bf16 pools of cfg.num_pages pages
+ *   page_stride     elements between pages (0 = dense), see the top of this header
  */
 int roll_kv_commit_append(roll_kv_pool* pool, const void* k_new, const void* v_new,
                           void* k_pages, void* v_pages, int32_t num_kv_heads,
-                          int32_t head_dim, void* stream);
+                          int32_t head_dim, int64_t page_stride, void* stream);
 
 /* HOST introspection. */
 int roll_kv_free_pages(const roll_kv_pool* pool);               /* count, or < 0 */
@@ -179,6 +203,7 @@ int64_t roll_kv_fused_steps(const roll_kv_pool* pool);
  *   seq_lens       DEVICE int32 [num_slots]; read only when positions is NULL
  *   k_pages,v_pages DEVICE bf16 pools
  *   page_table     DEVICE int32 [num_slots, max_pages_per_seq]
+ *   page_stride    elements between pages (0 = dense), see the top of this header
  */
 int roll_kv_append_tokens(const void* k_new, const void* v_new,
                           const int32_t* slots, const int32_t* positions,
@@ -186,7 +211,7 @@ int roll_kv_append_tokens(const void* k_new, const void* v_new,
                           int32_t n_tokens, void* k_pages, void* v_pages,
                           const int32_t* page_table, int32_t max_pages_per_seq,
                           int32_t num_pages, int32_t page_size,
-                          int32_t num_kv_heads, int32_t head_dim, void* stream);
+                          int32_t num_kv_heads, int32_t head_dim, int64_t page_stride, void* stream);
 
 /* ------------------------------------------------------------------ */
 /* Paged GQA decode attention (the bandwidth-bound part of the step,   */
@@ -208,7 +233,7 @@ typedef struct roll_attn_desc {
     int32_t num_pages;          /* pages in each pool (bounds the page ids) */
     int32_t out_dtype;          /* ROLL_BF16 or ROLL_F32 */
     float softmax_scale;        /* 0 => 1 / sqrt(D) */
-    int32_t reserved;           /* must be 0 */
+    int32_t page_stride;        /* elements between pages of a pool; 0 = dense (Hkv * P * D) */
     void* ev_main_begin;        /* optional hipEvent_t recorded before / after the    */
     void* ev_main_end;          /* stream-K attention kernel (profiling); NULL = none */
 } roll_attn_desc;
@@ -309,7 +334,7 @@ typedef struct roll_prefill_desc {
     int32_t num_slots;          /* rows of page_table                     */
     int32_t out_dtype;          /* ROLL_BF16 or ROLL_F32                  */
     float   softmax_scale;      /* 0 = 1/sqrt(head_dim)                   */
-    int32_t reserved;           /* must be 0                              */
+    int32_t page_stride;        /* elements between pages; 0 = dense      */
 } roll_prefill_desc;
 
 /*

@@ -46,14 +46,14 @@ class RollError(RuntimeError):
 
 class KvConfig(C.Structure):
     _fields_ = [("num_pages", C.c_int32), ("page_size", C.c_int32), ("num_slots", C.c_int32),
-                ("max_pages_per_seq", C.c_int32)]
+                ("max_pages_per_seq", C.c_int32), ("run_pages", C.c_int32)]
 
 
 class AttnDesc(C.Structure):
     _fields_ = [("batch", C.c_int32), ("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("page_size", C.c_int32), ("max_pages_per_seq", C.c_int32),
                 ("num_pages", C.c_int32), ("out_dtype", C.c_int32), ("softmax_scale", C.c_float),
-                ("reserved", C.c_int32),
+                ("page_stride", C.c_int32),
                 ("ev_main_begin", C.c_void_p), ("ev_main_end", C.c_void_p)]
 
 
@@ -69,7 +69,7 @@ class PrefillDesc(C.Structure):
     _fields_ = [("num_chunks", C.c_int32), ("num_tokens", C.c_int32), ("num_q_heads", C.c_int32),
                 ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("page_size", C.c_int32),
                 ("max_pages_per_seq", C.c_int32), ("num_pages", C.c_int32), ("num_slots", C.c_int32),
-                ("out_dtype", C.c_int32), ("softmax_scale", C.c_float), ("reserved", C.c_int32)]
+                ("out_dtype", C.c_int32), ("softmax_scale", C.c_float), ("page_stride", C.c_int32)]
 
 
 class SampleDesc(C.Structure):
@@ -102,14 +102,14 @@ def lib():
         L.roll_kv_alloc_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]
         L.roll_kv_release.argtypes = [C.c_void_p, C.c_int32]
         L.roll_kv_commit.argtypes = [C.c_void_p, C.c_void_p]
-        L.roll_kv_commit_append.argtypes = [C.c_void_p] * 5 + [C.c_int32, C.c_int32, C.c_void_p]
+        L.roll_kv_commit_append.argtypes = [C.c_void_p] * 5 + [C.c_int32, C.c_int32, C.c_int64, C.c_void_p]
         L.roll_kv_free_pages.argtypes = [C.c_void_p]
         L.roll_kv_fused_steps.argtypes = [C.c_void_p]
         L.roll_kv_fused_steps.restype = C.c_int64
         L.roll_kv_seq_len.argtypes = [C.c_void_p, C.c_int32]
         L.roll_kv_slot_pages.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_int32]
         L.roll_kv_append_tokens.argtypes = [C.c_void_p] * 5 + [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p] + \
-            [C.c_int32] * 5 + [C.c_void_p]
+            [C.c_int32] * 5 + [C.c_int64, C.c_void_p]
         L.roll_decode_attn_workspace_init.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
         L.roll_decode_attn_ranges.argtypes = [C.POINTER(AttnDesc), C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
                                               C.POINTER(C.c_int32)]
@@ -163,6 +163,35 @@ def _dev(t: Optional[torch.Tensor], dtype=None) -> Optional[int]:
     return t.data_ptr()
 
 
+def _pool(t: torch.Tensor) -> int:
+    """Device pointer of a KV pool: bf16, pages dense inside, any stride between pages."""
+    if not t.is_cuda or t.dtype != torch.bfloat16:
+        raise ValueError("expected a bf16 CUDA (ROCm) tensor")
+    if not t[0].is_contiguous():
+        raise ValueError("the pages of a pool must be dense")
+    return t.data_ptr()
+
+
+def page_stride(k_pages: torch.Tensor, v_pages: torch.Tensor) -> int:
+    """Elements between consecutive pages of the two pools: 0 for dense pools, the common stride
+    for K and V views of one allocation (see `new_kv_pools`)."""
+    sk, sv = k_pages.stride(0), v_pages.stride(0)
+    if sk != sv:
+        raise ValueError("k_pages and v_pages must have the same page stride")
+    return 0 if sk == k_pages[0].numel() else sk
+
+
+def new_kv_pools(num_pages: int, num_kv_heads: int, head_dim: int, page_size: int, device="cuda", fill=None):
+    """K and V pools as two views of ONE allocation in which the K block and the V block of a page
+    sit side by side (the layout the header recommends).  fill: None (uninitialised) or 0."""
+    Hkv, D, P = num_kv_heads, head_dim, page_size
+    make = torch.zeros if fill == 0 else torch.empty
+    both = make((num_pages, 2, Hkv * P * D), dtype=torch.bfloat16, device=device)
+    k = both[:, 0].view(num_pages, Hkv, D // 8, P, 8)
+    v = both[:, 1].view(num_pages, Hkv, P // 8, D, 8)
+    return k, v
+
+
 def roll_version() -> str:
     return lib().roll_version().decode()
 
@@ -175,8 +204,9 @@ class KvPool:
     (or both None for a host-only pool)."""
 
     def __init__(self, num_pages: int, page_size: int, num_slots: int, max_pages_per_seq: int,
-                 page_table: Optional[torch.Tensor] = None, seq_lens: Optional[torch.Tensor] = None):
-        self.cfg = KvConfig(num_pages, page_size, num_slots, max_pages_per_seq)
+                 page_table: Optional[torch.Tensor] = None, seq_lens: Optional[torch.Tensor] = None,
+                 run_pages: int = 1):
+        self.cfg = KvConfig(num_pages, page_size, num_slots, max_pages_per_seq, run_pages)
         self.page_table, self.seq_lens = page_table, seq_lens
         if page_table is not None:
             assert tuple(page_table.shape) == (num_slots, max_pages_per_seq)
@@ -223,7 +253,7 @@ def roll_kv_commit_append(pool: KvPool, k_new, v_new, k_pages, v_pages) -> None:
     n, Hkv, D = k_new.shape
     assert n == pool.cfg.num_slots and tuple(v_new.shape) == (n, Hkv, D)
     _check(lib().roll_kv_commit_append(pool._h, _dev(k_new, torch.bfloat16), _dev(v_new, torch.bfloat16),
-                                       _dev(k_pages, torch.bfloat16), _dev(v_pages, torch.bfloat16), Hkv, D,
+                                       _pool(k_pages), _pool(v_pages), Hkv, D, page_stride(k_pages, v_pages),
                                        _stream()))
 
 
@@ -253,9 +283,9 @@ def roll_kv_append_tokens(k_new, v_new, slots, positions, seq_lens, k_pages, v_p
     _check(lib().roll_kv_append_tokens(
         _dev(k_new, torch.bfloat16), _dev(v_new, torch.bfloat16), _dev(slots, torch.int32),
         _dev(positions, torch.int32), _dev(seq_lens, torch.int32), n,
-        _dev(k_pages, torch.bfloat16), _dev(v_pages, torch.bfloat16),
+        _pool(k_pages), _pool(v_pages),
         _dev(page_table, torch.int32), page_table.shape[1], k_pages.shape[0], page_size, Hkv, D,
-        _stream()))
+        page_stride(k_pages, v_pages), _stream()))
 
 
 # ----------------------------------------------------------------------------
@@ -263,10 +293,12 @@ def roll_kv_append_tokens(k_new, v_new, slots, positions, seq_lens, k_pages, v_p
 # ----------------------------------------------------------------------------
 def attn_desc(q, k_pages, page_table, page_size, out_dtype=torch.bfloat16, softmax_scale=0.0,
               ev_begin=None, ev_end=None) -> AttnDesc:
+    """The page stride is taken from k_pages (the calls check that v_pages has the same)."""
     B, Hq, D = q.shape
+    stride = k_pages.stride(0)
     return AttnDesc(B, Hq, k_pages.shape[1], D, page_size, page_table.shape[1], k_pages.shape[0],
                     ROLL_F32 if out_dtype == torch.float32 else ROLL_BF16, softmax_scale,
-                    0, ev_begin, ev_end)
+                    0 if stride == k_pages[0].numel() else stride, ev_begin, ev_end)
 
 
 def roll_decode_attn_workspace_bytes(desc: AttnDesc) -> int:
@@ -305,17 +337,21 @@ def new_attn_workspace(desc: AttnDesc, device="cuda") -> torch.Tensor:
 
 def roll_decode_attn(q, k_pages, v_pages, page_table, seq_lens, out, desc: AttnDesc,
                      workspace: torch.Tensor) -> None:
+    if page_stride(k_pages, v_pages) != desc.page_stride:
+        raise ValueError("the pools' page stride differs from the desc's")
     _check(lib().roll_decode_attn(
-        _dev(q, torch.bfloat16), _dev(k_pages, torch.bfloat16), _dev(v_pages, torch.bfloat16),
+        _dev(q, torch.bfloat16), _pool(k_pages), _pool(v_pages),
         _dev(page_table, torch.int32), _dev(seq_lens, torch.int32), _dev(out), C.byref(desc),
         _dev(workspace), workspace.numel() * workspace.element_size(), _stream()))
 
 
 def roll_decode_step_attn(pool: "KvPool", k_new, v_new, q, k_pages, v_pages, out, desc: AttnDesc,
                           workspace: torch.Tensor) -> None:
+    if page_stride(k_pages, v_pages) != desc.page_stride:
+        raise ValueError("the pools' page stride differs from the desc's")
     _check(lib().roll_decode_step_attn(
         pool._h, _dev(k_new, torch.bfloat16), _dev(v_new, torch.bfloat16), _dev(q, torch.bfloat16),
-        _dev(k_pages, torch.bfloat16), _dev(v_pages, torch.bfloat16), _dev(out), C.byref(desc),
+        _pool(k_pages), _pool(v_pages), _dev(out), C.byref(desc),
         _dev(workspace), workspace.numel() * workspace.element_size(), _stream()))
 
 
@@ -332,11 +368,11 @@ def roll_prefill_attn(q, k_new, v_new, chunk_slot, chunk_start, chunk_offset, k_
         raise TypeError("out must be bfloat16 or float32")
     desc = PrefillDesc(n_chunks, T, Hq, Hkv, D, page_size, page_table.shape[1], k_pages.shape[0],
                        page_table.shape[0], ROLL_BF16 if out.dtype == torch.bfloat16 else ROLL_F32,
-                       softmax_scale, 0)
+                       softmax_scale, page_stride(k_pages, v_pages))
     _check(lib().roll_prefill_attn(
         _dev(q, torch.bfloat16), _dev(k_new, torch.bfloat16), _dev(v_new, torch.bfloat16),
         _dev(chunk_slot, torch.int32), _dev(chunk_start, torch.int32), _dev(chunk_offset, torch.int32),
-        _dev(k_pages, torch.bfloat16), _dev(v_pages, torch.bfloat16), _dev(page_table, torch.int32),
+        _pool(k_pages), _pool(v_pages), _dev(page_table, torch.int32),
         _dev(out), C.byref(desc), _stream()))
 
 

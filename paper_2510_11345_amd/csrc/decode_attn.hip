@@ -61,6 +61,7 @@ constexpr int32_t kMaxPersistentWaves = 16 * 256;
 
 struct AttnParams {
     int32_t B, Hq, Hkv, G;
+    int32_t Hs;       // page stride of the pools in head blocks (Hkv when dense)
     int32_t log2P, max_pages, num_pages;
     int32_t max_len;
     int32_t W;        // persistent waves launched
@@ -120,7 +121,7 @@ struct WaveCtx {
     const uint4* __restrict__ k_pages;
     const uint4* __restrict__ v_pages;
     const int32_t* __restrict__ pt_row;
-    int32_t h, Hkv, log2P, num_pages, max_pages, r, q;
+    int32_t h, Hkv, Hs, log2P, num_pages, max_pages, r, q;
     // Fused step only: the stream's newest token is not in the pages yet; its K row, V row,
     // position, page index and physical page.
     const uint4* __restrict__ k_new_row;
@@ -179,7 +180,7 @@ __device__ __forceinline__ void load_k(const WaveCtx<D>& c, int32_t t0, int32_t 
     for (int tt = 0; tt < 2; ++tt) {
         const int32_t page = (P == 16 && c.r >= 8) ? pgB : pgA;
         const int32_t slot = P == 16 ? (c.r & 7) + 8 * tt : (t0 & (P - 1)) + c.r + 16 * tt;
-        kbase[tt] = c.k_pages + (((int64_t)page * c.Hkv + c.h) * (D / 8) + c.q) * P + slot;
+        kbase[tt] = c.k_pages + (((int64_t)page * c.Hs + c.h) * (D / 8) + c.q) * P + slot;
         if (NEWEST) fresh[tt] = t0 + 8 * (c.r >> 2) + 4 * tt + (c.r & 3) == c.new_tok;
     }
 #pragma unroll
@@ -198,7 +199,7 @@ __device__ __forceinline__ void load_v(const WaveCtx<D>& c, int32_t t0, int32_t 
     const int32_t P = 1 << c.log2P;
     const int32_t page = c.q >= 2 ? pgB : pgA;
     const int32_t oct = ((t0 + 8 * c.q) & (P - 1)) >> 3;
-    const uint4* base = c.v_pages + (((int64_t)page * c.Hkv + c.h) * (P / 8) + oct) * D + c.r;
+    const uint4* base = c.v_pages + (((int64_t)page * c.Hs + c.h) * (P / 8) + oct) * D + c.r;
 #pragma unroll
     for (int nt = 0; nt < D / 16; ++nt) s.v[nt] = load_stream(base + nt * 16);
 }
@@ -495,6 +496,7 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
     ctx.k_pages = k_pages;
     ctx.v_pages = v_pages;
     ctx.Hkv = Hkv;
+    ctx.Hs = prm.Hs;
     ctx.log2P = prm.log2P;
     ctx.num_pages = prm.num_pages;
     ctx.max_pages = prm.max_pages;
@@ -694,9 +696,9 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
                     const int32_t pos = (L - 1) & (P - 1);
                     const int64_t row = (int64_t)ab * Hkv + ah;
                     if (lane < D / 8)
-                        ((uint4*)k_pages)[(((int64_t)page * Hkv + ah) * (D / 8) + lane) * P + roll::k_slot(pos, P)] =
+                        ((uint4*)k_pages)[(((int64_t)page * prm.Hs + ah) * (D / 8) + lane) * P + roll::k_slot(pos, P)] =
                             fa.k_new[row * (D / 8) + lane];
-                    uint16_t* vdst = (uint16_t*)v_pages + ((((int64_t)page * Hkv + ah) * (P / 8) + pos / 8) * D) * 8 + pos % 8;
+                    uint16_t* vdst = (uint16_t*)v_pages + ((((int64_t)page * prm.Hs + ah) * (P / 8) + pos / 8) * D) * 8 + pos % 8;
                     const uint16_t* vsrc = (const uint16_t*)fa.v_new + row * D;
 #pragma unroll
                     for (int e = 0; e < D / 64; ++e) vdst[(int64_t)(lane + 64 * e) * 8] = vsrc[lane + 64 * e];
@@ -736,6 +738,8 @@ int validate(const roll_attn_desc* d) {
         return roll::fail(ROLL_ERR_INVALID_ARG, "max_pages_per_seq * page_size above 2^24 tokens");
     if (d->out_dtype != ROLL_BF16 && d->out_dtype != ROLL_F32) return roll::fail(ROLL_ERR_INVALID_ARG, "out_dtype must be ROLL_BF16 or ROLL_F32");
     if (!(d->softmax_scale >= 0.f) || std::isinf(d->softmax_scale)) return roll::fail(ROLL_ERR_INVALID_ARG, "softmax_scale must be finite and >= 0");
+    if (roll::page_stride_heads(d->page_stride, d->num_kv_heads, d->page_size, d->head_dim) == 0)
+        return roll::fail(ROLL_ERR_INVALID_ARG, "page_stride must be 0 or a multiple of page_size * head_dim that holds all KV heads");
     return ROLL_OK;
 }
 
@@ -847,6 +851,7 @@ int launch_attn(const void* q, const void* k_pages, const void* v_pages, const i
     prm.Hq = d->num_q_heads;
     prm.Hkv = d->num_kv_heads;
     prm.G = G;
+    prm.Hs = roll::page_stride_heads(d->page_stride, d->num_kv_heads, d->page_size, d->head_dim);
     prm.log2P = d->page_size == 16 ? 4 : (d->page_size == 32 ? 5 : 6);
     prm.max_pages = d->max_pages_per_seq;
     prm.num_pages = d->num_pages;
@@ -913,7 +918,8 @@ extern "C" int roll_decode_step_attn(roll_kv_pool* pool, const void* k_new, cons
     if (!plan.fusable) {
         // Not a plain decode step since the last commit (refills, first use, many new pages):
         // publish through the allocator's own kernel, then attend.
-        rc = roll_kv_commit_append(pool, k_new, v_new, k_pages, v_pages, d->num_kv_heads, d->head_dim, stream_v);
+        rc = roll_kv_commit_append(pool, k_new, v_new, k_pages, v_pages, d->num_kv_heads, d->head_dim, d->page_stride,
+                                   stream_v);
         if (rc != ROLL_OK) return rc;
         return launch_attn(q, k_pages, v_pages, plan.page_table_dev, plan.seq_lens_dev, out, d, workspace,
                            workspace_bytes, stream, nullptr);

@@ -18,11 +18,12 @@ __device__ __forceinline__ int32_t k_slot(int32_t t, int32_t P) {
 }
 
 // Store 8 consecutive head-dim elements (slice c) of one token's K and V for head h.
+// Hs: page stride in head blocks (the number of KV heads for dense pools).
 __device__ __forceinline__ void store_kv_slice(uint4 kv, uint4 vv, uint4* __restrict__ k_pages,
                                                uint16_t* __restrict__ v_pages, int32_t page, int32_t t,
-                                               int32_t h, int32_t c, int32_t P, int32_t Hkv, int32_t D) {
-    k_pages[(((int64_t)page * Hkv + h) * (D / 8) + c) * P + k_slot(t, P)] = kv;
-    uint16_t* vdst = v_pages + ((((int64_t)page * Hkv + h) * (P / 8) + t / 8) * D + c * 8) * 8 + t % 8;
+                                               int32_t h, int32_t c, int32_t P, int32_t Hs, int32_t D) {
+    k_pages[(((int64_t)page * Hs + h) * (D / 8) + c) * P + k_slot(t, P)] = kv;
+    uint16_t* vdst = v_pages + ((((int64_t)page * Hs + h) * (P / 8) + t / 8) * D + c * 8) * 8 + t % 8;
     const uint32_t w[4] = {vv.x, vv.y, vv.z, vv.w};
 #pragma unroll
     for (int j = 0; j < 4; ++j) {

@@ -48,7 +48,7 @@ __global__ void apply_updates(const int32_t* __restrict__ stage, int32_t* __rest
                               int32_t n_delta, int64_t table_elems, const uint4* __restrict__ k_new,
                               const uint4* __restrict__ v_new, uint4* __restrict__ k_pages,
                               uint16_t* __restrict__ v_pages, int32_t num_pages, int32_t P, int32_t Hkv,
-                              int32_t D) {
+                              int32_t D, int32_t Hs) {
     const int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (copy_lens && i < num_slots) seq_lens[i] = stage[i];
     if (i < n_delta) {
@@ -63,7 +63,7 @@ __global__ void apply_updates(const int32_t* __restrict__ stage, int32_t* __rest
             const int32_t c = i % d8n, h = (i / d8n) % Hkv, slot = i / (d8n * Hkv);
             const int32_t target = stage[num_slots + slot];
             if (target >= 0 && target / P < num_pages)
-                roll::store_kv_slice(k_new[i], v_new[i], k_pages, v_pages, target / P, target % P, h, c, P, Hkv, D);
+                roll::store_kv_slice(k_new[i], v_new[i], k_pages, v_pages, target / P, target % P, h, c, P, Hs, D);
         }
     }
 }
@@ -74,7 +74,7 @@ __global__ void append_tokens(const uint4* __restrict__ k_new, const uint4* __re
                               const int32_t* __restrict__ seq_lens, int64_t n_items,
                               uint4* __restrict__ k_pages, uint16_t* __restrict__ v_pages,
                               const int32_t* __restrict__ page_table, int32_t max_pages,
-                              int32_t num_pages, int32_t P, int32_t Hkv, int32_t D) {
+                              int32_t num_pages, int32_t P, int32_t Hkv, int32_t D, int32_t Hs) {
     const int64_t item = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (item >= n_items) return;
     const int32_t d8n = D / 8;
@@ -89,14 +89,15 @@ __global__ void append_tokens(const uint4* __restrict__ k_new, const uint4* __re
     if (pidx >= max_pages) return;
     const int32_t page = page_table[(int64_t)slot * max_pages + pidx];
     if (page < 0 || page >= num_pages) return;
-    roll::store_kv_slice(k_new[item], v_new[item], k_pages, v_pages, page, pos % P, h, c, P, Hkv, D);
+    roll::store_kv_slice(k_new[item], v_new[item], k_pages, v_pages, page, pos % P, h, c, P, Hs, D);
 }
 
 }  // namespace
 
 struct roll_kv_pool {
     roll_kv_config cfg{};
-    std::vector<int32_t> free_stack;  // back() is the next page handed out
+    std::vector<int32_t> free_stack;  // free runs of `run` consecutive pages; back() is handed out next
+    int32_t run = 1;                  // pages per run
     std::vector<int32_t> slot_pages;  // [num_slots * max_pages_per_seq]
     std::vector<int32_t> slot_npages;
     std::vector<int32_t> slot_len;
@@ -126,11 +127,16 @@ extern "C" int roll_kv_pool_create(roll_kv_pool** pool, const roll_kv_config* cf
         return roll::fail(ROLL_ERR_INVALID_ARG, "page_table_dev and seq_lens_dev must both be set or both NULL");
     if ((int64_t)cfg->num_slots * cfg->max_pages_per_seq > INT32_MAX)
         return roll::fail(ROLL_ERR_INVALID_ARG, "page table larger than 2^31 entries");
+    const int32_t run = cfg->run_pages == 0 ? 1 : cfg->run_pages;
+    if (run != 1 && run != 2 && run != 4 && run != 8)
+        return roll::fail(ROLL_ERR_INVALID_ARG, "run_pages must be 0, 1, 2, 4 or 8 (got %d)", cfg->run_pages);
     roll_kv_pool* p = new (std::nothrow) roll_kv_pool();
     if (!p) return roll::fail(ROLL_ERR_INVALID_ARG, "out of host memory");
     p->cfg = *cfg;
-    p->free_stack.resize(cfg->num_pages);
-    for (int32_t i = 0; i < cfg->num_pages; ++i) p->free_stack[i] = cfg->num_pages - 1 - i;
+    p->run = run;
+    const int32_t num_runs = cfg->num_pages / run;
+    p->free_stack.resize(num_runs);
+    for (int32_t i = 0; i < num_runs; ++i) p->free_stack[i] = num_runs - 1 - i;
     p->slot_pages.assign((size_t)cfg->num_slots * cfg->max_pages_per_seq, -1);
     p->slot_npages.assign(cfg->num_slots, 0);
     p->slot_len.assign(cfg->num_slots, 0);
@@ -165,13 +171,20 @@ extern "C" int roll_kv_alloc(roll_kv_pool* pool, int32_t slot, int32_t n_tokens)
     if (need > c.max_pages_per_seq)
         return roll::fail(ROLL_ERR_SEQ_TOO_LONG, "slot %d would need %lld pages (max %d)", slot, (long long)need, c.max_pages_per_seq);
     const int32_t have = pool->slot_npages[slot];
-    const int64_t extra = need - have;
-    if (extra > (int64_t)pool->free_stack.size())
-        return roll::fail(ROLL_ERR_NO_PAGES, "slot %d needs %lld more pages, %zu free", slot, (long long)extra, pool->free_stack.size());
-    for (int64_t i = 0; i < extra; ++i) {
-        const int32_t page = pool->free_stack.back();
-        pool->free_stack.pop_back();
-        const int32_t idx = slot * c.max_pages_per_seq + have + (int32_t)i;
+    const int32_t R = pool->run;
+    const int64_t extra_runs = (need + R - 1) / R - (have + R - 1) / R;
+    if (extra_runs > (int64_t)pool->free_stack.size())
+        return roll::fail(ROLL_ERR_NO_PAGES, "slot %d needs %lld more runs of %d pages, %zu free", slot, (long long)extra_runs, R,
+                          pool->free_stack.size());
+    for (int32_t n = have; n < need; ++n) {
+        const int32_t idx = slot * c.max_pages_per_seq + n;
+        int32_t page;
+        if (n % R == 0) {  // a new run
+            page = pool->free_stack.back() * R;
+            pool->free_stack.pop_back();
+        } else {           // the next page of the slot's last run
+            page = pool->slot_pages[idx - 1] + 1;
+        }
         pool->slot_pages[idx] = page;
         pool->pending.push_back(idx);
         pool->pending.push_back(page);
@@ -200,10 +213,11 @@ extern "C" int roll_kv_alloc_batch(roll_kv_pool* pool, const int32_t* slots, con
         const int64_t need = ((int64_t)pool->slot_len[slot] + n_tokens[i] + c.page_size - 1) / c.page_size;
         if (need > c.max_pages_per_seq)
             return roll::fail(ROLL_ERR_SEQ_TOO_LONG, "slot %d would need %lld pages (max %d)", slot, (long long)need, c.max_pages_per_seq);
-        extra_total += need - pool->slot_npages[slot];
+        extra_total += (need + pool->run - 1) / pool->run - (pool->slot_npages[slot] + pool->run - 1) / pool->run;
     }
     if (extra_total > (int64_t)pool->free_stack.size())
-        return roll::fail(ROLL_ERR_NO_PAGES, "batch needs %lld more pages, %zu free", (long long)extra_total, pool->free_stack.size());
+        return roll::fail(ROLL_ERR_NO_PAGES, "batch needs %lld more runs of %d pages, %zu free", (long long)extra_total, pool->run,
+                          pool->free_stack.size());
     for (int32_t i = 0; i < count; ++i) {
         const int rc = roll_kv_alloc(pool, slots[i], n_tokens[i]);
         if (rc != ROLL_OK) return rc;  // unreachable after pass 1
@@ -220,7 +234,7 @@ extern "C" int roll_kv_release(roll_kv_pool* pool, int32_t slot) {
     // Push in reverse so that an immediate re-alloc gets the pages back in the same order.
     for (int32_t i = n - 1; i >= 0; --i) {
         const int32_t idx = slot * c.max_pages_per_seq + i;
-        pool->free_stack.push_back(pool->slot_pages[idx]);
+        if (i % pool->run == 0) pool->free_stack.push_back(pool->slot_pages[idx] / pool->run);
         pool->slot_pages[idx] = -1;
     }
     pool->slot_npages[slot] = 0;
@@ -230,7 +244,7 @@ extern "C" int roll_kv_release(roll_kv_pool* pool, int32_t slot) {
 
 extern "C" int roll_kv_free_pages(const roll_kv_pool* pool) {
     if (!pool) return roll::fail(ROLL_ERR_INVALID_ARG, "pool is NULL");
-    return (int)pool->free_stack.size();
+    return (int)pool->free_stack.size() * pool->run;
 }
 
 extern "C" int roll_kv_seq_len(const roll_kv_pool* pool, int32_t slot) {
@@ -272,6 +286,7 @@ struct AppendArgs {
     uint4* k_pages = nullptr;
     uint16_t* v_pages = nullptr;
     int32_t Hkv = 0, D = 0;
+    int32_t Hs = 0;  // page stride in head blocks
 };
 
 // Where the newest token of each live slot goes: page * P + position in page, -1 for an empty slot.
@@ -348,7 +363,7 @@ static int commit_impl(roll_kv_pool* pool, void* stream_v, const AppendArgs& ap)
         apply_updates<<<(n + threads - 1) / threads, threads, 0, stream>>>(
             s->dev, pool->page_table_dev, pool->seq_lens_dev, c.num_slots, last ? 1 : 0, batch, table_elems,
             append ? ap.k_new : nullptr, ap.v_new, ap.k_pages, ap.v_pages, c.num_pages, c.page_size, ap.Hkv,
-            ap.D);
+            ap.D, ap.Hs);
         ROLL_HIP_CHECK(hipGetLastError());
         ROLL_HIP_CHECK(hipEventRecord(s->consumed, stream));
         s->in_flight = true;
@@ -406,7 +421,8 @@ extern "C" int64_t roll_kv_fused_steps(const roll_kv_pool* pool) {
 }
 
 extern "C" int roll_kv_commit_append(roll_kv_pool* pool, const void* k_new, const void* v_new, void* k_pages,
-                                     void* v_pages, int32_t num_kv_heads, int32_t head_dim, void* stream) {
+                                     void* v_pages, int32_t num_kv_heads, int32_t head_dim, int64_t page_stride,
+                                     void* stream) {
     if (!k_new || !v_new || !k_pages || !v_pages) return roll::fail(ROLL_ERR_INVALID_ARG, "NULL pointer argument");
     if (!roll::aligned(k_new, 16) || !roll::aligned(v_new, 16) || !roll::aligned(k_pages, 16) || !roll::aligned(v_pages, 16))
         return roll::fail(ROLL_ERR_INVALID_ARG, "k_new, v_new, k_pages, v_pages must be 16-byte aligned");
@@ -420,6 +436,9 @@ extern "C" int roll_kv_commit_append(roll_kv_pool* pool, const void* k_new, cons
     ap.v_pages = (uint16_t*)v_pages;
     ap.Hkv = num_kv_heads;
     ap.D = head_dim;
+    ap.Hs = pool ? roll::page_stride_heads(page_stride, num_kv_heads, pool->cfg.page_size, head_dim) : num_kv_heads;
+    if (ap.Hs == 0)
+        return roll::fail(ROLL_ERR_INVALID_ARG, "page_stride must be 0 or a multiple of page_size * head_dim that holds all KV heads");
     return commit_impl(pool, stream, ap);
 }
 
@@ -428,7 +447,7 @@ extern "C" int roll_kv_append_tokens(const void* k_new, const void* v_new, const
                                      int32_t n_tokens, void* k_pages,
                                      void* v_pages, const int32_t* page_table, int32_t max_pages_per_seq,
                                      int32_t num_pages, int32_t page_size, int32_t num_kv_heads,
-                                     int32_t head_dim, void* stream) {
+                                     int32_t head_dim, int64_t page_stride, void* stream) {
     if (n_tokens < 0) return roll::fail(ROLL_ERR_INVALID_ARG, "n_tokens < 0");
     if (n_tokens == 0) return ROLL_OK;
     if (!k_new || !v_new || !k_pages || !v_pages || !page_table)
@@ -441,11 +460,14 @@ extern "C" int roll_kv_append_tokens(const void* k_new, const void* v_new, const
         return roll::fail(ROLL_ERR_INVALID_ARG, "page_size must be 16, 32 or 64");
     if (head_dim <= 0 || head_dim % 8 != 0 || num_kv_heads <= 0 || max_pages_per_seq <= 0 || num_pages <= 0)
         return roll::fail(ROLL_ERR_INVALID_ARG, "bad shape");
+    const int32_t Hs = roll::page_stride_heads(page_stride, num_kv_heads, page_size, head_dim);
+    if (Hs == 0)
+        return roll::fail(ROLL_ERR_INVALID_ARG, "page_stride must be 0 or a multiple of page_size * head_dim that holds all KV heads");
     const int64_t items = (int64_t)n_tokens * num_kv_heads * (head_dim / 8);
     const int threads = 256;
     append_tokens<<<(unsigned)((items + threads - 1) / threads), threads, 0, (hipStream_t)stream>>>(
         (const uint4*)k_new, (const uint4*)v_new, slots, positions, seq_lens, items, (uint4*)k_pages,
-        (uint16_t*)v_pages, page_table, max_pages_per_seq, num_pages, page_size, num_kv_heads, head_dim);
+        (uint16_t*)v_pages, page_table, max_pages_per_seq, num_pages, page_size, num_kv_heads, head_dim, Hs);
     ROLL_HIP_CHECK(hipGetLastError());
     return ROLL_OK;
 }

@@ -37,6 +37,7 @@ constexpr int kAhead = kTiles - 1;
 
 struct PrefillParams {
     int32_t C, T, Hq, Hkv, G;
+    int32_t Hs;  // page stride of the pools in head blocks (Hkv when dense)
     int32_t log2P, max_pages, num_pages, num_slots;
     int32_t out_f32;
     float scale_log2e;
@@ -75,7 +76,7 @@ __global__ __launch_bounds__(256) void append_chunks(
         if (slot < 0 || slot >= prm.num_slots || pos < 0 || (pos >> prm.log2P) >= prm.max_pages) return;
         const int32_t page = page_table[(int64_t)slot * prm.max_pages + (pos >> prm.log2P)];
         if (page < 0 || page >= prm.num_pages) return;
-        k_pages[(((int64_t)page * prm.Hkv + rem / d8n) * d8n + rem % d8n) * P + roll::k_slot(pos & (P - 1), P)] = k_new[item];
+        k_pages[(((int64_t)page * prm.Hs + rem / d8n) * d8n + rem % d8n) * P + roll::k_slot(pos & (P - 1), P)] = k_new[item];
         return;
     }
     // V: which (chunk, octet of it) is this wave's?  Octets are numbered chunk after chunk; the
@@ -122,7 +123,7 @@ __global__ __launch_bounds__(256) void append_chunks(
         const int32_t j = pos - pos0;
         w[j >> 1] |= val << ((j & 1) * 16);
     }
-    uint4* dst = v_pages + (((int64_t)page * prm.Hkv + h) * (P / 8) + ((pos0 & (P - 1)) >> 3)) * D + d;
+    uint4* dst = v_pages + (((int64_t)page * prm.Hs + h) * (P / 8) + ((pos0 & (P - 1)) >> 3)) * D + d;
     if (hi - lo == 8) {
         *dst = make_uint4(w[0], w[1], w[2], w[3]);
     } else {
@@ -166,7 +167,7 @@ __device__ __forceinline__ StepPages step_page_ids(const int32_t* __restrict__ p
 template <int D>
 __device__ __forceinline__ void copy_step(uint4* tile, const uint4* __restrict__ k_pages,
                                           const uint4* __restrict__ v_pages, StepPages pg, int32_t h, int32_t t0,
-                                          int32_t log2P, int32_t Hkv) {
+                                          int32_t log2P, int32_t Hs) {
     const int32_t P = 1 << log2P;
     const int32_t pgA = pg.a, pgB = pg.b;
     if (threadIdx.x >= kCopyThreads) return;
@@ -184,12 +185,12 @@ __device__ __forceinline__ void copy_step(uint4* tile, const uint4* __restrict__
             const int32_t s32 = P == 16 ? 16 * ((pos >> 3) & 1) + (pos & 7) + 8 * (pos >> 4) : pos;
             const int32_t page = (P == 16 && s32 >= 16) ? pgB : pgA;
             const int32_t slot = P == 16 ? (s32 & 15) : (t0 & (P - 1)) + s32;
-            src = k_pages + (((int64_t)page * Hkv + h) * (D / 8) + d8) * P + slot;
+            src = k_pages + (((int64_t)page * Hs + h) * (D / 8) + d8) * P + slot;
         } else {
             const int32_t j = idx - (D / 8) * 32, oct = j / D, d = j - oct * D;
             const int32_t page = (P == 16 && oct >= 2) ? pgB : pgA;
             const int32_t oct_in_page = ((t0 + 8 * oct) & (P - 1)) >> 3;
-            src = v_pages + (((int64_t)page * Hkv + h) * (P / 8) + oct_in_page) * D + d;
+            src = v_pages + (((int64_t)page * Hs + h) * (P / 8) + oct_in_page) * D + d;
         }
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                          (__attribute__((address_space(3))) void*)(tile + i * kCopyThreads + wave_base),
@@ -317,7 +318,7 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
         return step_page_ids(pt_row, min(t0, last_t0), prm.log2P, prm.max_pages, prm.num_pages);
     };
     auto copy_to = [&](auto I, int32_t t0, StepPages pg) {
-        copy_step<D>(tile(I), k_pages, v_pages, pg, h, min(t0, last_t0), prm.log2P, prm.Hkv);
+        copy_step<D>(tile(I), k_pages, v_pages, pg, h, min(t0, last_t0), prm.log2P, prm.Hs);
     };
     StepPages pg_next;   // page ids of the next copy, fetched one step early: the copy never waits for them
     StepData<D> sd;   // K of the step about to be computed is read one step early (see below)
@@ -441,6 +442,9 @@ extern "C" int roll_prefill_attn(const void* q, const void* k_new, const void* v
     prm.T = d->num_tokens;
     prm.Hq = d->num_q_heads;
     prm.Hkv = d->num_kv_heads;
+    prm.Hs = roll::page_stride_heads(d->page_stride, d->num_kv_heads, d->page_size, d->head_dim);
+    if (prm.Hs == 0)
+        return roll::fail(ROLL_ERR_INVALID_ARG, "page_stride must be 0 or a multiple of page_size * head_dim that holds all KV heads");
     prm.G = d->num_q_heads / d->num_kv_heads;
     prm.log2P = d->page_size == 16 ? 4 : (d->page_size == 32 ? 5 : 6);
     prm.max_pages = d->max_pages_per_seq;

@@ -25,7 +25,8 @@ class DecodeBatch:
     def __init__(self, cfg: wl.DecodeConfig, seed: int, lengths: np.ndarray, headroom_tokens: int = 0,
                  out_dtype=torch.bfloat16, device: str = "cuda",
                  spare_pages: int = 64, max_len: int | None = None, fill_pools: bool = True,
-                 profile_events: bool = False, num_pages: int | None = None, fused: bool = True):
+                 profile_events: bool = False, num_pages: int | None = None, fused: bool = True,
+                 side_by_side: bool = True, run_pages: int | None = None):
         self.cfg, self.seed, self.device = cfg, seed, device
         B, P = cfg.batch, cfg.page_size
         Hq, Hkv, D = cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim
@@ -33,12 +34,21 @@ class DecodeBatch:
         assert len(lengths) == B
         cap = int(max(int(lengths.max()) + headroom_tokens, 1)) if max_len is None else int(max_len)
         self.max_pages = (cap + P - 1) // P
-        need = int(((np.minimum(lengths + headroom_tokens, cap) + P - 1) // P).sum())
-        self.num_pages = need + spare_pages if num_pages is None else int(num_pages)
+        # pages are handed out in aligned runs that cover one 32-token step of the attention kernel
+        self.run_pages = max(1, 32 // P) if run_pages is None else int(run_pages)
+        R = self.run_pages
+        need = int((((np.minimum(lengths + headroom_tokens, cap) + P - 1) // P + R - 1) // R * R).sum())
+        self.num_pages = (need + spare_pages + R - 1) // R * R if num_pages is None else int(num_pages)
         self.page_table = torch.empty((B, self.max_pages), dtype=torch.int32, device=device)
         self.seq_lens = torch.zeros((B,), dtype=torch.int32, device=device)
-        self.pool = rb.KvPool(self.num_pages, P, B, self.max_pages, self.page_table, self.seq_lens)
-        if fill_pools:
+        self.pool = rb.KvPool(self.num_pages, P, B, self.max_pages, self.page_table, self.seq_lens, run_pages=R)
+        if side_by_side:
+            # one allocation, the K block and the V block of a page next to each other
+            both = (wl.randn_bf16((self.num_pages, 2, Hkv * P * D), seed, 2, device) if fill_pools else
+                    torch.zeros((self.num_pages, 2, Hkv * P * D), dtype=torch.bfloat16, device=device))
+            self.k_pages = both[:, 0].view(self.num_pages, Hkv, D // 8, P, 8)
+            self.v_pages = both[:, 1].view(self.num_pages, Hkv, P // 8, D, 8)
+        elif fill_pools:
             self.k_pages = wl.randn_bf16((self.num_pages, Hkv, D // 8, P, 8), seed, 2, device)
             self.v_pages = wl.randn_bf16((self.num_pages, Hkv, P // 8, D, 8), seed, 3, device)
         else:
@@ -109,6 +119,11 @@ class DecodeBatch:
                                cfg.top_p if top_p is None else top_p, self.seed, step_index,
                                self.tokens, self.logprob, sdesc, None)
 
+    def pages_held(self) -> int:
+        """Pages that the slots hold, counting the unused rest of every slot's last run."""
+        R = self.run_pages
+        return sum((len(rb.roll_kv_slot_pages(self.pool, s)) + R - 1) // R * R for s in range(self.cfg.batch))
+
     # -- host copies for the oracle --------------------------------------------
     def gather_rows(self, rows):
         """Host copy of the listed rows: compact pools holding only their pages and a remapped
@@ -158,7 +173,8 @@ class RefillLoop:
         self.next_request = B
         start_len = plan.prompt_len[:B].astype(np.int64) + self.generated
         # the pool can hold every slot at max_len, so a refill never runs out of pages
-        total_pages = B * ((max_len + cfg.page_size - 1) // cfg.page_size)
+        R = max(1, 32 // cfg.page_size)   # DecodeBatch's run length
+        total_pages = B * (((max_len + cfg.page_size - 1) // cfg.page_size + R - 1) // R * R)
         self.batch = DecodeBatch(cfg, seed, start_len, out_dtype=out_dtype, device=device,
                                  max_len=max_len, fill_pools=True, num_pages=total_pages)
         self.refills = 0

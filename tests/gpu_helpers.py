@@ -11,12 +11,28 @@ def say(msg):
     print(msg, flush=True)
 
 
-def run_attn(inp, cfg, out_dtype=torch.float32, softmax_scale=0.0, seq_lens=None):
-    """inp: dict from workloads.make_attn_inputs (cpu or cuda tensors). Returns out on host (float64)."""
+def side_by_side(k_pages, v_pages, extra_heads=0):
+    """The two pools copied into ONE allocation with the K and the V block of a page next to each
+    other (plus extra_heads unused head blocks per page, filled with NaN): strided views of it."""
+    N, Hkv, d8, P, _ = k_pages.shape
+    D = d8 * 8
+    blk = Hkv * P * D
+    both = torch.full((N, 2 * blk + extra_heads * P * D), float("nan"), dtype=torch.bfloat16, device=k_pages.device)
+    both[:, :blk] = k_pages.reshape(N, blk)
+    both[:, blk:2 * blk] = v_pages.reshape(N, blk)
+    return both[:, :blk].view(N, Hkv, d8, P, 8), both[:, blk:2 * blk].view(N, Hkv, P // 8, D, 8)
+
+
+def run_attn(inp, cfg, out_dtype=torch.float32, softmax_scale=0.0, seq_lens=None, layout="dense"):
+    """inp: dict from workloads.make_attn_inputs (cpu or cuda tensors). Returns out on host (float64).
+    layout: "dense" (two allocations), "side_by_side" (one, K and V of a page adjacent), or
+    "padded" (the same with three unused head blocks per page)."""
     dev = "cuda"
     q = inp["q"].to(dev)
     k_pages = inp["k_pages"].to(dev)
     v_pages = inp["v_pages"].to(dev)
+    if layout != "dense":
+        k_pages, v_pages = side_by_side(k_pages, v_pages, 3 if layout == "padded" else 0)
     table = torch.from_numpy(np.ascontiguousarray(inp["page_table"])).to(dev)
     lens = torch.from_numpy(np.ascontiguousarray(inp["seq_lens"] if seq_lens is None else seq_lens)).to(dev)
     B, Hq, D = q.shape

@@ -165,3 +165,78 @@ def test_alloc_batch_is_all_or_nothing():
         assert (owned(pool, 4), rb.roll_kv_free_pages(pool)) == snap
     rb.roll_kv_alloc_batch(pool, np.array([], np.int32), np.array([], np.int32))
     check_conservation(pool, 4, 10)
+
+
+@pytest.mark.parametrize("R", [2, 4, 8])
+def test_runs_of_pages_are_aligned_adjacent_and_conserved(R):
+    # pages handed out in aligned runs of R: logical pages R j .. R j + R - 1 of a slot are the
+    # physical pages R k .. R k + R - 1 of one run, however the pool has been churned
+    rng = np.random.default_rng(R)
+    slots, num_pages, max_pages = 12, 40 * R + 3, 24     # the 3 pages past the last whole run are never used
+    pool = rb.KvPool(num_pages, 16, slots, max_pages, run_pages=R)
+    usable = num_pages // R * R
+    assert rb.roll_kv_free_pages(pool) == usable
+    lens = [0] * slots
+    for it in range(4000):
+        s = int(rng.integers(slots))
+        if lens[s] and rng.random() < 0.2:
+            rb.roll_kv_release(pool, s); lens[s] = 0
+        else:
+            n = int(rng.integers(1, 60))
+            free_before, pages_before = rb.roll_kv_free_pages(pool), rb.roll_kv_slot_pages(pool, s)
+            try:
+                rb.roll_kv_alloc(pool, s, n); lens[s] += n
+            except rb.RollError as e:
+                assert e.status in (-2, -5)
+                assert rb.roll_kv_free_pages(pool) == free_before and rb.roll_kv_slot_pages(pool, s) == pages_before
+        if it % 50 == 0 or it == 3999:
+            held, seen = 0, set()
+            for t in range(slots):
+                pages = rb.roll_kv_slot_pages(pool, t)
+                assert len(pages) == (lens[t] + 15) // 16
+                for j, p in enumerate(pages):
+                    assert 0 <= p < usable and p not in seen
+                    seen.add(p)
+                    if j % R == 0:
+                        assert p % R == 0                    # a run starts at a multiple of R
+                    else:
+                        assert p == pages[j - 1] + 1          # and continues page by page
+                held += (len(pages) + R - 1) // R * R
+            assert held + rb.roll_kv_free_pages(pool) == usable
+    # release + re-alloc hands the same pages back in the same order
+    s = max(range(slots), key=lambda t: lens[t])
+    before = rb.roll_kv_slot_pages(pool, s)
+    rb.roll_kv_release(pool, s)
+    rb.roll_kv_alloc(pool, s, lens[s])
+    assert rb.roll_kv_slot_pages(pool, s) == before
+
+
+def test_runs_batch_alloc_is_all_or_nothing_and_bad_run_lengths_are_rejected():
+    pool = rb.KvPool(8, 16, 4, 8, run_pages=2)           # 4 runs of 2 pages
+    rb.roll_kv_alloc_batch(pool, np.array([0, 1, 2], np.int32), np.array([1, 17, 33], np.int32))   # 1 + 1 + 2 runs
+    assert rb.roll_kv_free_pages(pool) == 0
+    snap = [rb.roll_kv_slot_pages(pool, s) for s in range(4)]
+    with pytest.raises(rb.RollError) as e:
+        rb.roll_kv_alloc_batch(pool, np.array([0, 3], np.int32), np.array([15, 1], np.int32))  # slot 0 fits its run, slot 3 needs one
+    assert e.value.status == -2
+    assert [rb.roll_kv_slot_pages(pool, s) for s in range(4)] == snap and rb.roll_kv_seq_len(pool, 0) == 1
+    rb.roll_kv_alloc(pool, 0, 31)                        # the second page of slot 0's run: no new run needed
+    assert rb.roll_kv_slot_pages(pool, 0) == [snap[0][0], snap[0][0] + 1]
+    for R in (3, 5, 16, -1):
+        with pytest.raises(rb.RollError):
+            rb.KvPool(64, 16, 4, 8, run_pages=R)
+
+
+def test_page_stride_must_be_whole_head_blocks_that_hold_all_heads():
+    L = rb.lib()
+    base = dict(batch=4, Hq=8, Hkv=2, D=64, P=16)
+    block = base["P"] * base["D"]
+
+    def desc(stride):
+        return rb.AttnDesc(base["batch"], base["Hq"], base["Hkv"], base["D"], base["P"], 8, 32, rb.ROLL_BF16, 0.0,
+                           stride, None, None)
+    for ok in (0, 2 * block, 4 * block, 7 * block):      # dense; exactly the heads; K and V side by side; padded
+        assert L.roll_decode_attn_workspace_bytes(C.byref(desc(ok))) > 0
+    for bad in (block, 2 * block + 8, -2 * block, 2 * block - 1):
+        assert L.roll_decode_attn_workspace_bytes(C.byref(desc(bad))) == 0
+        assert L.roll_decode_attn(16, 16, 16, 16, 16, 16, C.byref(desc(bad)), 256, 1 << 30, None) == -1

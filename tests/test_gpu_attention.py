@@ -18,17 +18,17 @@ EDGE_LENGTHS = [1, 2, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 511, 51
                 1025, 1537, 2048, 2049]
 
 
-def check(cfg, lengths, seed, bf16_too=True, scale=0.0):
+def check(cfg, lengths, seed, bf16_too=True, scale=0.0, layout="dense"):
     say(f"  attn case {cfg.name} B={len(lengths)} Hq={cfg.num_q_heads} Hkv={cfg.num_kv_heads} "
         f"D={cfg.head_dim} P={cfg.page_size} seed={seed} maxL={max(lengths)}")
     inp = wl.make_attn_inputs(cfg, seed, "cpu", lengths=np.asarray(lengths, np.int32))
     ref = oracle_attn(inp, cfg, scale=scale if scale else None)
-    got = run_attn(inp, cfg, torch.float32, softmax_scale=scale)
+    got = run_attn(inp, cfg, torch.float32, softmax_scale=scale, layout=layout)
     err = np.abs(got - ref).max()
-    say(f"    fp32 out: max abs err {err:.3e}")
+    say(f"    fp32 out ({layout} pools): max abs err {err:.3e}")
     assert np.isfinite(got).all() and err <= TOL_F32
     if bf16_too:
-        got16 = run_attn(inp, cfg, torch.bfloat16, softmax_scale=scale)
+        got16 = run_attn(inp, cfg, torch.bfloat16, softmax_scale=scale, layout=layout)
         err16 = np.abs(got16 - ref).max()
         say(f"    bf16 out: max abs err {err16:.3e}")
         assert np.isfinite(got16).all() and err16 <= TOL_BF16
@@ -78,27 +78,30 @@ def test_short_rows_clustered_beside_long_ones(Hq, Hkv):
     assert not got[lens == 0].any()
 
 
-def test_7b_shape_lognormal_lengths():
+@pytest.mark.parametrize("layout", ["dense", "side_by_side"])
+def test_7b_shape_lognormal_lengths(layout):
     cfg = wl.CONFIGS["c2"]
     L = np.minimum(wl.draw_lengths(cfg.lengths, 24, 2), 6000)
-    check(cfg, L, seed=2)
+    check(cfg, L, seed=2, layout=layout)
 
 
-def test_32b_shape_page32():
+@pytest.mark.parametrize("layout", ["dense", "side_by_side", "padded"])
+def test_32b_shape_page32(layout):
     cfg = wl.CONFIGS["c5"]
     L = [64, 65, 95, 96, 97, 1000, 2047, 2048, 3000, 31, 1, 33]
-    check(cfg, L, seed=3)
+    check(cfg, L, seed=3, layout=layout)
 
 
 @pytest.mark.parametrize("Hq,Hkv,D,P", [(4, 4, 64, 64), (16, 1, 64, 16), (16, 1, 128, 64), (6, 2, 128, 32),
                                         (6, 3, 128, 16), (12, 6, 64, 16), (20, 5, 128, 32), (24, 12, 64, 16)])
-def test_other_head_and_page_shapes(Hq, Hkv, D, P):
+@pytest.mark.parametrize("layout", ["dense", "side_by_side"])
+def test_other_head_and_page_shapes(Hq, Hkv, D, P, layout):
     # KV head counts of every kind for the dealing of heads to a workgroup's four waves: fewer than
     # four (1, 2: the range is cut again; 3: a wave stays idle), more than four and not a multiple
     # of four (5, 6: the waves get unequal numbers of heads), multiples of four (4, 12)
     cfg = dataclasses.replace(wl.CONFIGS["c1"], name=f"h{Hq}_{Hkv}_d{D}_p{P}", num_q_heads=Hq,
                               num_kv_heads=Hkv, head_dim=D, page_size=P)
-    check(cfg, [1, 7, 63, 64, 65, 200, 513, 700, 129], seed=4)
+    check(cfg, [1, 7, 63, 64, 65, 200, 513, 700, 129], seed=4, layout=layout)
 
 
 def test_custom_softmax_scale():

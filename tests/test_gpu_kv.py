@@ -59,9 +59,17 @@ def test_many_deltas_span_several_staging_blocks():
     pool.close()
 
 
+def zero_pools(num_pages, Hkv, D, P, side_by_side):
+    if side_by_side:
+        return rb.new_kv_pools(num_pages, Hkv, D, P, fill=0)
+    return (torch.zeros((num_pages, Hkv, D // 8, P, 8), dtype=torch.bfloat16, device="cuda"),
+            torch.zeros((num_pages, Hkv, P // 8, D, 8), dtype=torch.bfloat16, device="cuda"))
+
+
+@pytest.mark.parametrize("side_by_side", [False, True])
 @pytest.mark.parametrize("Hkv,D,P", [(4, 128, 16), (8, 128, 32), (2, 64, 64)])
-def test_append_tokens_writes_the_documented_layouts(Hkv, D, P):
-    say(f"  append case Hkv={Hkv} D={D} P={P}")
+def test_append_tokens_writes_the_documented_layouts(Hkv, D, P, side_by_side):
+    say(f"  append case Hkv={Hkv} D={D} P={P} side_by_side={side_by_side}")
     slots, max_pages = 3, 6
     num_pages = slots * max_pages
     pool, table, lens = make_pool(num_pages, P, slots, max_pages)
@@ -74,8 +82,7 @@ def test_append_tokens_writes_the_documented_layouts(Hkv, D, P):
     n = len(pos)
     k_new = wl.randn_bf16((n, Hkv, D), 1, 50)
     v_new = wl.randn_bf16((n, Hkv, D), 1, 51)
-    k_pages = torch.zeros((num_pages, Hkv, D // 8, P, 8), dtype=torch.bfloat16, device="cuda")
-    v_pages = torch.zeros((num_pages, Hkv, P // 8, D, 8), dtype=torch.bfloat16, device="cuda")
+    k_pages, v_pages = zero_pools(num_pages, Hkv, D, P, side_by_side)
     rb.roll_kv_append_tokens(k_new.cuda(), v_new.cuda(), torch.from_numpy(slot_ids).cuda(),
                              torch.from_numpy(pos).cuda(), None, k_pages, v_pages, table, P)
     torch.cuda.synchronize()
@@ -91,14 +98,14 @@ def test_append_tokens_writes_the_documented_layouts(Hkv, D, P):
     pool.close()
 
 
+@pytest.mark.parametrize("side_by_side", [False, True])
 @pytest.mark.parametrize("Hkv,D,P", [(4, 128, 16), (8, 128, 32)])
-def test_commit_append_publishes_and_writes_in_one_launch(Hkv, D, P):
-    say(f"  commit_append case Hkv={Hkv} D={D} P={P}")
+def test_commit_append_publishes_and_writes_in_one_launch(Hkv, D, P, side_by_side):
+    say(f"  commit_append case Hkv={Hkv} D={D} P={P} side_by_side={side_by_side}")
     slots, max_pages = 6, 5
     num_pages = slots * max_pages
     pool, table, lens = make_pool(num_pages, P, slots, max_pages)
-    k_pages = torch.zeros((num_pages, Hkv, D // 8, P, 8), dtype=torch.bfloat16, device="cuda")
-    v_pages = torch.zeros((num_pages, Hkv, P // 8, D, 8), dtype=torch.bfloat16, device="cuda")
+    k_pages, v_pages = zero_pools(num_pages, Hkv, D, P, side_by_side)
     ek = np.zeros(num_pages * Hkv * D * P, np.uint16)
     ev = np.zeros_like(ek)
     L = [P - 1, 0, 2 * P, 5, 0, 3 * P + 7]           # slots 1 and 4 stay empty

@@ -7,7 +7,7 @@ import torch
 import oracle
 from paper_2510_11345_amd import binding as rb
 from paper_2510_11345_amd import workloads as wl
-from gpu_helpers import say
+from gpu_helpers import say, side_by_side
 
 pytestmark = pytest.mark.gpu
 
@@ -24,6 +24,8 @@ class Pool:
         self.pool = rb.KvPool(self.num_pages, P, num_slots, self.max_pages, self.page_table, self.seq_lens)
         self.k_pages = wl.randn_bf16((self.num_pages, Hkv, D // 8, P, 8), seed, 2, "cuda")
         self.v_pages = wl.randn_bf16((self.num_pages, Hkv, P // 8, D, 8), seed, 3, "cuda")
+        if seed % 2 == 1:   # odd seeds: K and V of a page side by side in one allocation
+            self.k_pages, self.v_pages = side_by_side(self.k_pages, self.v_pages)
 
     def host_table(self, num_slots):
         t = np.full((num_slots, self.max_pages), -1, np.int32)

@@ -32,8 +32,7 @@ def test_refill_loop_reduced():
         refilled = loop.step(logits, step)
         torch.cuda.synchronize()
         # allocator invariants after every tick
-        owned = sum(len(rb.roll_kv_slot_pages(b.pool, s)) for s in range(cfg.batch))
-        assert owned + rb.roll_kv_free_pages(b.pool) == total_pages
+        assert b.pages_held() + rb.roll_kv_free_pages(b.pool) == total_pages
         assert np.array_equal(b.seq_lens.cpu().numpy(), b.lengths.astype(np.int32))
         # sampling parity every step (row id = slot, step = decode step)
         ref = oracle.sample_logprob(wl.logits_numpy(logits), cfg.temperature, cfg.top_p, 3, step)
@@ -150,8 +149,7 @@ def test_random_release_refill_schedule():
         for slot in range(B):
             pages = rb.roll_kv_slot_pages(b.pool, slot)
             assert list(table[slot, :len(pages)]) == pages, (step, slot)
-        owned = sum(len(rb.roll_kv_slot_pages(b.pool, s)) for s in range(B))
-        assert owned + rb.roll_kv_free_pages(b.pool) == b.num_pages
+        assert b.pages_held() + rb.roll_kv_free_pages(b.pool) == b.num_pages
         if step % 6 == 0 or step == steps - 1 or chunks:
             q, k, v, tb, lens = b.gather_rows(list(range(B)))
             want = oracle.decode_attn(q, k, v, tb, lens, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, P)
