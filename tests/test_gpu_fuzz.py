@@ -48,7 +48,8 @@ def test_decode_attention_random_cases():
         inp["seq_lens"] = lengths                      # rows drawn empty keep their one page
         scale = 0.0 if rng.random() < 0.7 else float(rng.uniform(0.02, 0.3))
         out_dtype = torch.float32 if rng.random() < 0.5 else torch.bfloat16
-        got = run_attn(inp, cfg, out_dtype=out_dtype, softmax_scale=scale)
+        layout = ["dense", "side_by_side", "padded"][case % 3]
+        got = run_attn(inp, cfg, out_dtype=out_dtype, softmax_scale=scale, layout=layout)
         want = oracle_attn(inp, cfg, scale=None if scale == 0.0 else scale)
         err = float(np.abs(got - want).max())
         assert np.isfinite(got).all()
@@ -71,7 +72,11 @@ def test_fused_steps_random_cases():
         start = np.maximum(_draw_lengths(rng, B, 400), 1) - 1       # zero = the slot starts its sequence
         cfg = dataclasses.replace(wl.CONFIGS["c1"], batch=B, num_q_heads=Hq, num_kv_heads=Hkv, head_dim=D,
                                   page_size=P, vocab=512)
-        b = DecodeBatch(cfg, 300 + case, start, headroom_tokens=8, out_dtype=torch.float32)
+        # pools side by side with runs of pages (the default), side by side with single pages, or
+        # two dense allocations with runs of four
+        kind = case % 3
+        b = DecodeBatch(cfg, 300 + case, start, headroom_tokens=8, out_dtype=torch.float32,
+                        side_by_side=kind != 2, run_pages=[None, 1, 4][kind])
         logits = wl.make_logits(cfg, 300 + case, "cuda")
         for step in range(5):
             b.k_new.copy_(wl.randn_bf16(tuple(b.k_new.shape), 300 + case, 50 + step, "cuda"))
