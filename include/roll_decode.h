@@ -269,8 +269,8 @@ int roll_decode_attn_workspace_init(void* workspace, size_t workspace_bytes, voi
 
 /*
  *   q           DEVICE bf16 [B, Hq, D]
- *   k_pages     DEVICE bf16 [num_pages, Hkv, D/8, P, 8]
- *   v_pages     DEVICE bf16 [num_pages, Hkv, P/8, D, 8]
+ *   k_pages     DEVICE bf16 [num_pages, Hkv, D/8, P, 8], pages desc->page_stride apart
+ *   v_pages     DEVICE bf16 [num_pages, Hkv, P/8, D, 8], likewise
  *   page_table  DEVICE int32 [B, max_pages_per_seq]; entries past a row's
  *               last page are never read
  *   seq_lens    DEVICE int32 [B]; values outside [0, max_pages*P] are
