@@ -217,6 +217,9 @@ def main():
     ap.add_argument("--equal-rows", action="store_true",
                     help="measure the plain attention launch on a batch of equal rows of the config's mean "
                          "length (no row is cut, little is written): what the kernel reads when nothing is ragged")
+    ap.add_argument("--dense-pools", action="store_true",
+                    help="K and V in two dense allocations and pages handed out one by one, instead of one "
+                         "allocation with the K and V block of a page side by side and pages in runs of 32 / P")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="only run one plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -256,17 +259,18 @@ def main():
     cfg = wl.CONFIGS[args.config]
     K, W = args.steps, args.warmup
     extra = {}
+    pool_kw = dict(side_by_side=False, run_pages=1) if args.dense_pools else {}
     if cfg.name == "c4":
         # continuous refill: slots finish by pre-drawn length and are refilled from the prompt queue
         from paper_2510_11345_amd.harness import RefillLoop
         plan = wl.draw_refill_plan(cfg.batch, cfg.batch + 4 * (K + W) + 64, args.seed)
-        loop = RefillLoop(cfg, plan, args.seed, max_len=cfg.max_len + K + W + 2)
+        loop = RefillLoop(cfg, plan, args.seed, max_len=cfg.max_len + K + W + 2, **pool_kw)
         batch = loop.batch
         step_fn = loop.step
     else:
         lengths = wl.draw_lengths(cfg.lengths, cfg.batch, args.seed, cfg.max_len).astype(np.int64)
         # seq_lens count the token being decoded: start one short, every step appends one token
-        batch = DecodeBatch(cfg, args.seed, lengths - 1, headroom_tokens=K + W + 2, profile_events=False)
+        batch = DecodeBatch(cfg, args.seed, lengths - 1, headroom_tokens=K + W + 2, profile_events=False, **pool_kw)
         step_fn = batch.step
     logits = wl.make_logits(cfg, args.seed, "cuda")
     torch.cuda.synchronize()
@@ -314,7 +318,10 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": workload, "seed": args.seed, "sum_seq_lens": int(batch.total_tokens()), **extra},
+        "config": {"workload": workload, "seed": args.seed, "sum_seq_lens": int(batch.total_tokens()),
+                   "kv_pools": ("two dense allocations, single pages" if args.dense_pools else
+                                f"one allocation, K and V of a page side by side, pages in runs of {batch.run_pages}"),
+                   **extra},
         "kv_read_GBps": achieved,
         "kv_read_frac_of_peak": achieved / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "kernel": "attn_stream", "achieved": achieved, "peak": HBM_PEAK_GBS,

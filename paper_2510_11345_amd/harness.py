@@ -153,7 +153,8 @@ class RefillLoop:
     then every slot decodes one token.  Prompt Q/K/V are slices of a seeded random bank."""
 
     def __init__(self, cfg: wl.DecodeConfig, plan: wl.RefillPlan, seed: int, max_len: int,
-                 out_dtype=torch.bfloat16, device: str = "cuda", prefill: bool = True):
+                 out_dtype=torch.bfloat16, device: str = "cuda", prefill: bool = True,
+                 side_by_side: bool = True, run_pages: int | None = None):
         self.cfg, self.plan, self.seed, self.device = cfg, plan, seed, device
         self.prefill = prefill
         self.bank_tokens = int(plan.prompt_len.max()) + 4096
@@ -173,10 +174,11 @@ class RefillLoop:
         self.next_request = B
         start_len = plan.prompt_len[:B].astype(np.int64) + self.generated
         # the pool can hold every slot at max_len, so a refill never runs out of pages
-        R = max(1, 32 // cfg.page_size)   # DecodeBatch's run length
+        R = max(1, 32 // cfg.page_size) if run_pages is None else int(run_pages)   # DecodeBatch's run length
         total_pages = B * (((max_len + cfg.page_size - 1) // cfg.page_size + R - 1) // R * R)
         self.batch = DecodeBatch(cfg, seed, start_len, out_dtype=out_dtype, device=device,
-                                 max_len=max_len, fill_pools=True, num_pages=total_pages)
+                                 max_len=max_len, fill_pools=True, num_pages=total_pages,
+                                 side_by_side=side_by_side, run_pages=run_pages)
         self.refills = 0
         self.refill_log = []  # (step, slot, request)
         self._load_torch_kernels()
