@@ -15,7 +15,11 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "roll_oracle.c")
-_LIB = os.path.join(_HERE, "libroll_oracle.so")
+# ROLL_ORACLE_SANITIZE=1 (set by tests/test_sanitizers.py for a child process that preloads the
+# sanitizer runtime) selects a second build of the same source with AddressSanitizer and
+# UndefinedBehaviorSanitizer, so that the pins also prove the oracle reads and writes in bounds.
+SANITIZE = os.environ.get("ROLL_ORACLE_SANITIZE", "") == "1"
+_LIB = os.path.join(_HERE, "libroll_oracle_san.so" if SANITIZE else "libroll_oracle.so")
 
 BF16, F32 = 0, 1
 _lib = None
@@ -24,7 +28,9 @@ _lib = None
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (OpenMP over independent rows / heads only)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+        opt = (["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+                "-fno-sanitize-recover=all"] if SANITIZE else ["-O2"])
+        cmd = ["gcc", *opt, "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
                "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB

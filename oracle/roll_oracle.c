@@ -328,17 +328,20 @@ static int cmp_desc(const void* a, const void* b)
  * p = softmax(z).  Going down the DISTINCT values of x, add the mass of
  * all entries equal to the value; x_cut is the first value at which the
  * running mass is >= top_p, and the kept set is { i : x_i >= x_cut }.
- * top_p >= 1 keeps everything (x_cut = -inf).
+ * top_p >= 1 keeps everything (x_cut = -inf).  Entries of -inf are masked
+ * tokens (probability 0); a row without any finite entry has no softmax and
+ * therefore no cut: NaN.
  * Readings: truncation applies to the tempered distribution; the token
  * that crosses top_p is kept; entries tied with the cut value are kept,
  * so the set does not depend on any sort order.
  */
 double oracle_top_p_cut(const double* x, int V, double T, double top_p)
 {
-    if (top_p >= 1.0) return -INFINITY;
     double m = -INFINITY;
     for (int i = 0; i < V; ++i)
         if (x[i] / T > m) m = x[i] / T;
+    if (!(m > -INFINITY)) return NAN; /* no finite entry: no distribution, so no cut */
+    if (top_p >= 1.0) return -INFINITY;
     double Z = 0.0;
     for (int i = 0; i < V; ++i) Z += exp(x[i] / T - m);
     double* sorted = (double*)malloc(sizeof(double) * (size_t)V);
@@ -369,6 +372,11 @@ double oracle_top_p_cut(const double* x, int V, double T, double top_p)
  * Extra outputs for the parity report: gap = best minus second-best
  * perturbed logit (+inf if one entry is kept), kept count, x_cut, and the
  * cuts for top_p - band and top_p + band (the boundary band).
+ * Reading (the paper says nothing of masked vocabularies): -inf entries are
+ * masked tokens; a row in which every entry is masked defines no distribution,
+ * so nothing is drawn from it: token = -1, logprob = raw_logprob = NaN (the
+ * importance weight of Appendix A.1 has no denominator), kept = 0,
+ * gap = +inf, the three cuts NaN.
  */
 static void sample_row(const void* row, int dtype, int V, double T, double top_p,
                        uint64_t seed, uint64_t step, uint32_t row_id, double band,
@@ -376,7 +384,23 @@ static void sample_row(const void* row, int dtype, int V, double T, double top_p
                        double* x_cut, double* x_cut_minus, double* x_cut_plus, double* raw_logprob)
 {
     double* x = (double*)malloc(sizeof(double) * (size_t)V);
-    for (int i = 0; i < V; ++i) x[i] = logit_to_double(row, dtype, i);
+    int finite_entries = 0;
+    for (int i = 0; i < V; ++i) {
+        x[i] = logit_to_double(row, dtype, i);
+        if (x[i] > -INFINITY) ++finite_entries;
+    }
+    if (finite_entries == 0) { /* every token masked: no distribution, no token */
+        *token = -1;
+        *logprob = NAN;
+        if (raw_logprob) *raw_logprob = NAN;
+        if (gap) *gap = INFINITY;
+        if (kept_count) *kept_count = 0;
+        if (x_cut) *x_cut = NAN;
+        if (x_cut_minus) *x_cut_minus = NAN;
+        if (x_cut_plus) *x_cut_plus = NAN;
+        free(x);
+        return;
+    }
     double cut = oracle_top_p_cut(x, V, T, top_p);
     if (x_cut) *x_cut = cut;
     if (x_cut_minus) {
@@ -490,7 +514,7 @@ void oracle_sample_counts(const void* row, int dtype, int V, double T, double to
         double lp;
         sample_row(row, dtype, V, T, top_p, seed, step0 + (uint64_t)s, row_id, 0.0,
                    &tok, &lp, NULL, NULL, NULL, NULL, NULL, NULL);
-        counts[tok] += 1;
+        if (tok >= 0) counts[tok] += 1; /* a row without a finite entry draws nothing */
     }
 }
 

@@ -189,3 +189,45 @@ def test_sampled_frequencies_match_distribution(T, p, V):
     chi2 = ((counts[kept] - n * prob[kept]) ** 2 / (n * prob[kept])).sum()
     dof = kept.sum() - 1
     assert chi2 < scipy.stats.chi2.ppf(1 - 1e-6, dof)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("T,top_p", [(1.0, 1.0), (0.7, 0.95), (1.0, 0.5)])
+def test_row_with_every_token_masked_draws_nothing(dtype, T, top_p):
+    # -inf entries are masked tokens; a row in which every entry is masked defines no distribution:
+    # token -1, log-probs NaN (nothing for the importance weight of Appendix A.1 to divide by),
+    # nothing kept.  The neighbouring rows are untouched by it.
+    rng = np.random.default_rng(5)
+    x = (rng.standard_normal((3, 41)) * 2).astype(np.float32)
+    x[1, :] = -np.inf
+    x[2, 5:] = -np.inf          # a row with SOME masked entries is an ordinary row
+    xin = to_bf16_bits(x) if dtype == "bf16" else x
+    r = oracle.sample_logprob(xin, T, top_p, seed=9, step=4)
+    assert r["tokens"][1] == -1
+    assert np.isnan(r["logprob"][1]) and np.isnan(r["raw_logprob"][1])
+    assert r["kept"][1] == 0 and np.isposinf(r["gap"][1])
+    assert np.isnan(r["x_cut"][1]) and np.isnan(r["x_cut_minus"][1]) and np.isnan(r["x_cut_plus"][1])
+    # the other rows: same result as when sampled alone under their own row ids
+    for b in (0, 2):
+        alone = oracle.sample_logprob(xin[b:b + 1], T, top_p, seed=9, step=4, row_ids=[b])
+        assert alone["tokens"][0] == r["tokens"][b] and alone["logprob"][0] == r["logprob"][b]
+        assert 0 <= r["tokens"][b] < 41 and np.isfinite(r["logprob"][b])
+    # masked entries can never be drawn; under a cut they are not in the kept set either (at
+    # top_p = 1 the cut is -inf and the count is the whole row, masked entries carrying no mass)
+    assert r["tokens"][2] < 5 and (1 <= r["kept"][2] <= 5 if top_p < 1 else r["kept"][2] == 41)
+    # the helpers agree: no cut, nothing kept, nothing counted
+    row = xin[1]
+    assert np.isnan(oracle.top_p_cut(np.full(41, -np.inf), T, top_p))
+    _, kept = oracle.row_detail(row, T, top_p, seed=9, step=4, row_id=1)
+    assert not kept.any()
+    assert oracle.sample_counts(row, T, top_p, seed=9, step0=0, n_draws=50).sum() == 0
+
+
+def test_single_finite_entry_among_masked_ones_is_drawn_with_logprob_zero():
+    # the smallest distribution there is: one unmasked token has probability 1 whatever T and top_p
+    x = np.full((1, 33), -np.inf, dtype=np.float32)
+    x[0, 17] = -3.5
+    for T, p in [(1.0, 1.0), (0.7, 0.95), (2.0, 1e-6)]:
+        r = oracle.sample_logprob(x, T, p, seed=1, step=2)
+        assert r["tokens"][0] == 17 and r["logprob"][0] == 0.0 and r["raw_logprob"][0] == 0.0
+        assert np.isposinf(r["gap"][0]) and r["kept"][0] == (1 if p < 1 else 33)
