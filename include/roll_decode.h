@@ -233,9 +233,7 @@ typedef struct roll_attn_desc {
     int32_t num_pages;          /* pages in each pool (bounds the page ids) */
     int32_t out_dtype;          /* ROLL_BF16 or ROLL_F32 */
     float softmax_scale;        /* 0 => 1 / sqrt(D) */
-    int32_t page_stride;        /* elements between pages of a pool; 0 = dense (Hkv * P * D) */
-    void* ev_main_begin;        /* optional hipEvent_t recorded before / after the    */
-    void* ev_main_end;          /* stream-K attention kernel (profiling); NULL = none */
+    int64_t page_stride;        /* elements between pages of a pool; 0 = dense (Hkv * P * D) */
 } roll_attn_desc;
 
 /* HOST. Bytes of DEVICE workspace roll_decode_attn needs for this desc. */
@@ -260,12 +258,27 @@ int roll_decode_attn_ranges(const roll_attn_desc* desc, const int32_t* seq_lens_
 
 /*
  * Prepare a workspace: enqueues a kernel on stream that zeroes the arrival
- * counters at its start.  Call once after allocating the buffer (and again if
- * anything else has written to it, or after a call that failed on the
- * device); every roll_decode_attn leaves the counters zero again.  A
- * workspace prepared once serves any later desc it is large enough for.
+ * counters at its start and writes a tag word that marks the buffer as
+ * prepared.  Call once after allocating the buffer (and again if anything else
+ * has written to it, or after a call that failed on the device); every
+ * roll_decode_attn leaves the counters zero again.  A workspace prepared once
+ * serves any later desc it is large enough for.
+ * The attention kernel reads the tag before it writes anything: on a buffer
+ * that was never prepared it leaves `out`, the pools and the tables untouched
+ * and records the refusal in the workspace, where roll_decode_attn_workspace_check
+ * finds it.
  */
 int roll_decode_attn_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Diagnostic, SYNCHRONISES: waits for stream, then inspects the workspace header.
+ * ROLL_OK if the buffer is prepared, no launch has refused it and every arrival
+ * counter is zero (as between any two calls); ROLL_ERR_WORKSPACE otherwise, the
+ * message saying which: never prepared, refused by a launch (whose results were
+ * therefore not written), or counters left over from a launch that did not
+ * finish.  Prepare the buffer again after any of these.
+ */
+int roll_decode_attn_workspace_check(const void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  *   q           DEVICE bf16 [B, Hq, D]
@@ -334,7 +347,7 @@ typedef struct roll_prefill_desc {
     int32_t num_slots;          /* rows of page_table                     */
     int32_t out_dtype;          /* ROLL_BF16 or ROLL_F32                  */
     float   softmax_scale;      /* 0 = 1/sqrt(head_dim)                   */
-    int32_t page_stride;        /* elements between pages; 0 = dense      */
+    int64_t page_stride;        /* elements between pages; 0 = dense      */
 } roll_prefill_desc;
 
 /*
@@ -494,8 +507,27 @@ int64_t roll_sample_buffer_outstanding(const roll_sample_buffer* buffer);
 int64_t roll_sample_buffer_capacity(const roll_sample_buffer* buffer);
 
 /* ------------------------------------------------------------------ */
-/* Profiling helpers: HIP events the benchmark hands to roll_attn_desc. */
+/* Profiling helpers: HIP events around the attention kernel.          */
 /* ------------------------------------------------------------------ */
+/* HOST, per calling thread: the next roll_decode_attn / roll_decode_step_attn
+ * launches made by this thread record `begin` right before and `end` right
+ * after the stream-K attention kernel, on the launch's stream (hipEvent_t
+ * handles from roll_prof_event_create).  NULL, NULL switches it off again. */
+int roll_prof_attn_events(void* begin, void* end);
+/*
+ * Bandwidth ceiling of the decode step's access pattern (Section 1: decoding is
+ * memory-bandwidth bound): enqueues ONE kernel that reads, through page_table,
+ * the K block and the V block (all KV heads) of every page that holds tokens of
+ * a row (ceil(seq_lens[b] / page_size) pages of row b), with streaming 16-byte
+ * loads and no arithmetic.  Arguments as for roll_decode_attn (desc: batch,
+ * num_kv_heads, head_dim, page_size, max_pages_per_seq, num_pages, page_stride).
+ *   sink            DEVICE, >= 2048 * 256 * 4 bytes; receives one meaningless word per thread
+ *   bytes_per_page  HOST, optional: bytes the kernel reads per page (K + V block)
+ * The caller times the launch; bytes read = bytes_per_page * sum_b ceil(L_b / P).
+ */
+int roll_prof_kv_read_probe(const void* k_pages, const void* v_pages, const int32_t* page_table,
+                            const int32_t* seq_lens, const roll_attn_desc* desc, void* sink,
+                            size_t sink_bytes, int64_t* bytes_per_page, void* stream);
 int roll_prof_event_create(void** event);
 int roll_prof_event_destroy(void* event);
 int roll_prof_event_record(void* event, void* stream);

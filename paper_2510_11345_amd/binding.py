@@ -15,7 +15,9 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libroll_decode.so")
+# ROLL_DECODE_LIB names another build of the same sources (the CPU test suite points it at a build
+# whose host code is instrumented with sanitizers).
+LIB_PATH = os.environ.get("ROLL_DECODE_LIB") or os.path.join(_HERE, "libroll_decode.so")
 
 ROLL_BF16, ROLL_F32 = 0, 1
 
@@ -25,15 +27,15 @@ EXPORTS = [
     "roll_kv_commit", "roll_kv_commit_append", "roll_kv_free_pages", "roll_kv_seq_len", "roll_kv_slot_pages",
     "roll_kv_fused_steps",
     "roll_kv_append_tokens",
-    "roll_decode_attn_workspace_bytes", "roll_decode_attn_workspace_init", "roll_decode_attn",
-    "roll_decode_attn_ranges",
+    "roll_decode_attn_workspace_bytes", "roll_decode_attn_workspace_init", "roll_decode_attn_workspace_check",
+    "roll_decode_attn", "roll_decode_attn_ranges",
     "roll_decode_step_attn", "roll_prefill_attn",
     "roll_sample_logprob_workspace_bytes", "roll_sample_logprob", "roll_policy_loss",
     "roll_sample_buffer_create", "roll_sample_buffer_destroy", "roll_sample_buffer_begin",
     "roll_sample_buffer_complete", "roll_sample_buffer_abort", "roll_sample_buffer_resume",
     "roll_sample_buffer_take_batch", "roll_sample_buffer_advance_version", "roll_sample_buffer_version",
     "roll_sample_buffer_outstanding", "roll_sample_buffer_capacity",
-    "roll_prof_event_create", "roll_prof_event_destroy", "roll_prof_event_record",
+    "roll_prof_attn_events", "roll_prof_kv_read_probe", "roll_prof_event_create", "roll_prof_event_destroy", "roll_prof_event_record",
     "roll_prof_event_elapsed_ms",
 ]
 
@@ -53,8 +55,7 @@ class AttnDesc(C.Structure):
     _fields_ = [("batch", C.c_int32), ("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("page_size", C.c_int32), ("max_pages_per_seq", C.c_int32),
                 ("num_pages", C.c_int32), ("out_dtype", C.c_int32), ("softmax_scale", C.c_float),
-                ("page_stride", C.c_int32),
-                ("ev_main_begin", C.c_void_p), ("ev_main_end", C.c_void_p)]
+                ("page_stride", C.c_int64)]
 
 
 class LossDesc(C.Structure):
@@ -69,7 +70,7 @@ class PrefillDesc(C.Structure):
     _fields_ = [("num_chunks", C.c_int32), ("num_tokens", C.c_int32), ("num_q_heads", C.c_int32),
                 ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("page_size", C.c_int32),
                 ("max_pages_per_seq", C.c_int32), ("num_pages", C.c_int32), ("num_slots", C.c_int32),
-                ("out_dtype", C.c_int32), ("softmax_scale", C.c_float), ("page_stride", C.c_int32)]
+                ("out_dtype", C.c_int32), ("softmax_scale", C.c_float), ("page_stride", C.c_int64)]
 
 
 class SampleDesc(C.Structure):
@@ -111,6 +112,10 @@ def lib():
         L.roll_kv_append_tokens.argtypes = [C.c_void_p] * 5 + [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p] + \
             [C.c_int32] * 5 + [C.c_int64, C.c_void_p]
         L.roll_decode_attn_workspace_init.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
+        L.roll_decode_attn_workspace_check.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
+        L.roll_prof_attn_events.argtypes = [C.c_void_p, C.c_void_p]
+        L.roll_prof_kv_read_probe.argtypes = [C.c_void_p] * 4 + [C.POINTER(AttnDesc), C.c_void_p, C.c_size_t,
+                                              C.POINTER(C.c_int64), C.c_void_p]
         L.roll_decode_attn_ranges.argtypes = [C.POINTER(AttnDesc), C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
                                               C.POINTER(C.c_int32)]
         L.roll_decode_attn.argtypes = [C.c_void_p] * 6 + [C.POINTER(AttnDesc), C.c_void_p, C.c_size_t, C.c_void_p]
@@ -291,14 +296,13 @@ def roll_kv_append_tokens(k_new, v_new, slots, positions, seq_lens, k_pages, v_p
 # ----------------------------------------------------------------------------
 # attention
 # ----------------------------------------------------------------------------
-def attn_desc(q, k_pages, page_table, page_size, out_dtype=torch.bfloat16, softmax_scale=0.0,
-              ev_begin=None, ev_end=None) -> AttnDesc:
+def attn_desc(q, k_pages, page_table, page_size, out_dtype=torch.bfloat16, softmax_scale=0.0) -> AttnDesc:
     """The page stride is taken from k_pages (the calls check that v_pages has the same)."""
     B, Hq, D = q.shape
     stride = k_pages.stride(0)
     return AttnDesc(B, Hq, k_pages.shape[1], D, page_size, page_table.shape[1], k_pages.shape[0],
                     ROLL_F32 if out_dtype == torch.float32 else ROLL_BF16, softmax_scale,
-                    0 if stride == k_pages[0].numel() else stride, ev_begin, ev_end)
+                    0 if stride == k_pages[0].numel() else stride)
 
 
 def roll_decode_attn_workspace_bytes(desc: AttnDesc) -> int:
@@ -343,6 +347,13 @@ def roll_decode_attn(q, k_pages, v_pages, page_table, seq_lens, out, desc: AttnD
         _dev(q, torch.bfloat16), _pool(k_pages), _pool(v_pages),
         _dev(page_table, torch.int32), _dev(seq_lens, torch.int32), _dev(out), C.byref(desc),
         _dev(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def roll_decode_attn_workspace_check(workspace: torch.Tensor) -> None:
+    """Diagnostic (synchronises): raises RollError unless the workspace is prepared, was refused by no
+    launch and holds no counters left over from an unfinished one."""
+    _check(lib().roll_decode_attn_workspace_check(_dev(workspace), workspace.numel() * workspace.element_size(),
+                                                  _stream()))
 
 
 def roll_decode_step_attn(pool: "KvPool", k_new, v_new, q, k_pages, v_pages, out, desc: AttnDesc,
@@ -482,6 +493,21 @@ class SampleBuffer:
 # ----------------------------------------------------------------------------
 # profiling events
 # ----------------------------------------------------------------------------
+def roll_prof_attn_events(begin: Optional["ProfEvent"], end: Optional["ProfEvent"]) -> None:
+    """The calling thread's next attention launches record these two events around the kernel;
+    (None, None) switches that off."""
+    _check(lib().roll_prof_attn_events(None if begin is None else begin.handle, None if end is None else end.handle))
+
+
+def roll_prof_kv_read_probe(k_pages, v_pages, page_table, seq_lens, desc: AttnDesc, sink: torch.Tensor) -> int:
+    """Enqueue the plain read of the batch's paged KV bytes; returns the bytes it reads per page."""
+    per_page = C.c_int64()
+    _check(lib().roll_prof_kv_read_probe(_pool(k_pages), _pool(v_pages), _dev(page_table, torch.int32),
+                                         _dev(seq_lens, torch.int32), C.byref(desc), _dev(sink),
+                                         sink.numel() * sink.element_size(), C.byref(per_page), _stream()))
+    return per_page.value
+
+
 class ProfEvent:
     def __init__(self):
         self._h = C.c_void_p()

@@ -10,15 +10,25 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libroll_decode.so")
 SOURCES = ["api.hip", "kv_pool.hip", "decode_attn.hip", "prefill_attn.hip", "sample_logprob.hip", "policy_loss.hip",
-           "sample_buffer.hip"]
+           "sample_buffer.hip", "prof_probe.hip"]
 
 
-def build(verbose: bool = False) -> str:
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+def hipcc_path() -> str:
+    return os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+
+
+def build(verbose: bool = False, out: str = LIB, sanitize_host: bool = False) -> str:
+    """Compile the library to `out`.  sanitize_host instruments the HOST pass only with
+    AddressSanitizer and UndefinedBehaviorSanitizer (allocator, SampleBuffer, dealing arithmetic,
+    argument checks); the CPU test suite runs its host-only tests through such a build."""
+    cmd = [hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wall", "-Wno-unused-function",
-           "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", LIB]
+           "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", out]
+    if sanitize_host:
+        cmd += ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                "-Xarch_host", "-fno-sanitize-recover=all", "-Xarch_host", "-fno-omit-frame-pointer",
+                "-shared-libsan", "-g"]
     cmd += [os.path.join(CSRC, s) for s in SOURCES]
     if verbose:
         print(" ".join(cmd), flush=True)
@@ -29,7 +39,7 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if err.strip() and verbose:
         print(err, file=sys.stderr)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

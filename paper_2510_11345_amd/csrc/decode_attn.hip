@@ -36,6 +36,8 @@
 #include <cfloat>
 #include <cmath>
 #include <climits>
+#include <cstddef>
+#include <cstring>
 #include <mutex>
 #include <vector>
 
@@ -56,8 +58,11 @@ constexpr int kMaxBatch = 8192;    // rows whose prefix sums fit the LDS budget
 constexpr int kMaxStreams = 65536; // batch * num_kv_heads: one arrival counter each
 constexpr int kMergeGroup = 16;    // pieces merged by one wave at the first level
 // Upper bound of persistent waves, used to size the workspace without touching the device:
-// 16 waves on each of 256 compute units (a gfx950 device has no more).
-constexpr int32_t kMaxPersistentWaves = 16 * 256;
+// one workgroup on each of 256 compute units (a gfx950 device has no more).
+constexpr int32_t kMaxPersistentWaves = kGroupWaves * 256;
+// Tag that roll_decode_attn_workspace_init leaves in a workspace's header; the kernel refuses a
+// buffer without it.
+constexpr uint32_t kWorkspaceTag = 0x524F4C57u;
 
 struct AttnParams {
     int32_t B, Hq, Hkv, G;
@@ -69,9 +74,16 @@ struct AttnParams {
     float scale_log2e;
 };
 
+// First words of a workspace.
+struct WorkspaceHeader {
+    int32_t grid_arrivals;  // workgroups of a fused step that have read the old lengths (zero between calls)
+    uint32_t tag;           // kWorkspaceTag once prepared
+    uint32_t refused;       // launches that found no tag and did nothing
+};
+
 struct Workspace {
+    WorkspaceHeader* header;
     // zero between calls (roll_decode_attn_workspace_init, then every merger resets its counter)
-    int32_t* grid_arrivals;    // [1] workgroups of a fused step that have read the old lengths
     int32_t* group_arrivals;   // [kMaxSlots] indexed by the slot of the first piece of a group
     int32_t* stream_arrivals;  // [kMaxStreams] indexed by row * Hkv + kv head
     // scratch
@@ -85,27 +97,34 @@ struct Workspace {
 
 __host__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// The header does not depend on the shape (roll_decode_attn_workspace_init has none).
-__host__ Workspace carve(void* base, int32_t Hkv, int32_t G, int32_t D) {
+// Lays a workspace out for launches of up to `waves` persistent waves; with base == nullptr only
+// the sizes are filled in.  The header does not depend on the shape
+// (roll_decode_attn_workspace_init has none).
+__host__ Workspace carve(void* base, int32_t Hkv, int32_t G, int32_t D, int32_t waves = kMaxPersistentWaves) {
     Workspace w{};
-    const size_t slots = 2 * (size_t)max_ranges(kMaxPersistentWaves, Hkv) * Hkv;
+    const size_t slots = 2 * (size_t)max_ranges(waves, Hkv) * Hkv;
     size_t off = 0;
-    char* p = (char*)base;
-    w.grid_arrivals = (int32_t*)(p + off);    off = align_up(off + sizeof(int32_t), 256);
-    w.group_arrivals = (int32_t*)(p + off);   off = align_up(off + sizeof(int32_t) * kMaxSlots, 256);
-    w.stream_arrivals = (int32_t*)(p + off);  off = align_up(off + sizeof(int32_t) * kMaxStreams, 256);
+    auto take = [&](size_t bytes) -> char* {
+        char* at = base ? (char*)base + off : nullptr;
+        off = align_up(off + bytes, 256);
+        return at;
+    };
+    w.header = (WorkspaceHeader*)take(sizeof(WorkspaceHeader));
+    w.group_arrivals = (int32_t*)take(sizeof(int32_t) * kMaxSlots);
+    w.stream_arrivals = (int32_t*)take(sizeof(int32_t) * kMaxStreams);
     w.header_bytes = off;
-    w.part_ml = (float2*)(p + off);           off = align_up(off + sizeof(float2) * slots * 16, 256);
-    w.part_acc = (float*)(p + off);           off = align_up(off + sizeof(float) * slots * G * D, 256);
-    w.group_ml = (float2*)(p + off);          off = align_up(off + sizeof(float2) * slots * 16, 256);
-    w.group_acc = (float*)(p + off);          off = align_up(off + sizeof(float) * slots * G * D, 256);
+    w.part_ml = (float2*)take(sizeof(float2) * slots * 16);
+    w.part_acc = (float*)take(sizeof(float) * slots * G * D);
+    w.group_ml = (float2*)take(sizeof(float2) * slots * 16);
+    w.group_acc = (float*)take(sizeof(float) * slots * G * D);
     w.bytes = off;
     return w;
 }
 
-__global__ void zero_words(uint32_t* dst, size_t n) {
+// Zeroes the header's words (counters included) and leaves the tag.
+__global__ void prepare_header(uint32_t* dst, size_t n) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) dst[i] = 0u;
+    if (i < n) dst[i] = i == offsetof(WorkspaceHeader, tag) / 4 ? kWorkspaceTag : 0u;
 }
 
 // KV is read exactly once per step: a nontemporal load keeps it from displacing the
@@ -138,7 +157,6 @@ struct FusedArgs {
     const uint4* v_new;
     int32_t* page_table_w;
     int32_t* seq_lens_w;
-    int32_t* grid_arrivals;
 };
 struct NoFusedArgs {};
 
@@ -451,15 +469,24 @@ template <int D, bool FUSED, bool F32OUT>
 __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
     const uint4* __restrict__ q16, const uint4* k_pages, const uint4* v_pages,
     const int32_t* __restrict__ page_table, const int32_t* __restrict__ seq_lens,
-    void* __restrict__ out, int32_t* group_arrivals, int32_t* stream_arrivals, float2* part_ml,
-    float* part_acc, float2* group_ml, float* group_acc, AttnParams prm,
+    void* __restrict__ out, WorkspaceHeader* header, int32_t* group_arrivals, int32_t* stream_arrivals,
+    float2* part_ml, float* part_acc, float2* group_ml, float* group_acc, AttnParams prm,
     const typename std::conditional<FUSED, FusedArgs, NoFusedArgs>::type fa) {
     extern __shared__ int32_t lds[];
     int32_t* pre = lds;                  // [B + 1]
     int32_t* len = lds + prm.B + 1;      // [B]
     uint16_t* live = (uint16_t*)(lds + 2 * prm.B + 1);  // [B + 1] rows with tokens before row b
     __shared__ int32_t s_wave_tot[2 * kGroupWaves];
+    // The workspace's tag, requested beside the lengths.  A buffer that was never prepared holds
+    // arbitrary counters, with which cut rows would be merged too early or never: such a launch
+    // writes nothing at all and leaves a mark for roll_decode_attn_workspace_check.
+    const uint32_t tag = __hip_atomic_load(&header->tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     build_row_prefix(seq_lens, prm.B, prm.max_len, FUSED, pre, len, live, s_wave_tot);
+    if (tag != kWorkspaceTag) {
+        if (blockIdx.x == 0 && threadIdx.x == 0)
+            __hip_atomic_fetch_add(&header->refused, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return;
+    }
 
     const int32_t lane = threadIdx.x & 63;
     const int32_t w = blockIdx.x * kGroupWaves + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -716,7 +743,7 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
     if constexpr (FUSED) {
         // Every workgroup has read the old lengths long ago; the last one to get here writes the
         // new ones.  At the end of the wave's work the atomic's round trip delays nothing.
-        if (threadIdx.x < 64 && arrive_last(fa.grid_arrivals, (int32_t)gridDim.x, lane))
+        if (threadIdx.x < 64 && arrive_last(&header->grid_arrivals, (int32_t)gridDim.x, lane))
             for (int32_t i = lane; i < prm.B; i += 64) fa.seq_lens_w[i] = len[i];
     }
 }
@@ -736,6 +763,9 @@ int validate(const roll_attn_desc* d) {
     if (d->max_pages_per_seq <= 0 || d->num_pages <= 0) return roll::fail(ROLL_ERR_INVALID_ARG, "max_pages_per_seq and num_pages must be > 0");
     if ((int64_t)d->max_pages_per_seq * d->page_size > (1 << 24))
         return roll::fail(ROLL_ERR_INVALID_ARG, "max_pages_per_seq * page_size above 2^24 tokens");
+    // the kernel keeps the rows' step counts as 32-bit prefix sums
+    if ((int64_t)d->batch * (((int64_t)d->max_pages_per_seq * d->page_size + kStep - 1) / kStep) > INT32_MAX)
+        return roll::fail(ROLL_ERR_SEQ_TOO_LONG, "batch * ceil(max_pages_per_seq * page_size / %d) above 2^31 - 1 steps", kStep);
     if (d->out_dtype != ROLL_BF16 && d->out_dtype != ROLL_F32) return roll::fail(ROLL_ERR_INVALID_ARG, "out_dtype must be ROLL_BF16 or ROLL_F32");
     if (!(d->softmax_scale >= 0.f) || std::isinf(d->softmax_scale)) return roll::fail(ROLL_ERR_INVALID_ARG, "softmax_scale must be finite and >= 0");
     if (roll::page_stride_heads(d->page_stride, d->num_kv_heads, d->page_size, d->head_dim) == 0)
@@ -744,32 +774,33 @@ int validate(const roll_attn_desc* d) {
 }
 
 // Persistent waves to launch: one workgroup (kGroupWaves waves, one per SIMD) on every compute
-// unit.  Measured on c2 / c3 / c5: 3 to 4 waves per CU with 16 KiB in flight each already sit on
-// the memory system's plateau; 8 per CU are 1-2 % slower and 2 per CU need double buffering
-// to get there.  Fewer waves also mean fewer cut rows to merge.
-int persistent_waves(int head_dim, size_t lds_bytes, int32_t* waves_out) {
+// unit of the current device.  Measured on c2 / c3 / c5: 3 to 4 waves per CU with 16 KiB in flight
+// each already sit on the memory system's plateau; 8 per CU are 1-2 % slower and 2 per CU need
+// double buffering to get there.  Fewer waves also mean fewer cut rows to merge.  No wave waits
+// for another, so nothing depends on the workgroups being resident together: a workgroup that
+// does not fit (LDS for the batch's prefix sums) fails the launch itself.
+constexpr int kMaxDevices = 64;
+int persistent_waves(int32_t* waves_out, int* device_out = nullptr) {
     static std::mutex mu;
-    static int cached[2] = {0, 0};
-    std::lock_guard<std::mutex> lock(mu);
-    int& c = cached[head_dim == 128];
-    if (c > 0) {
-        *waves_out = c;
-        return ROLL_OK;
-    }
+    static int cu_count[kMaxDevices] = {0};
     int dev = 0;
     ROLL_HIP_CHECK(hipGetDevice(&dev));
-    hipDeviceProp_t prop;
-    ROLL_HIP_CHECK(hipGetDeviceProperties(&prop, dev));
-    int groups = 0;
-    if (head_dim == 128)
-        ROLL_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&groups, attn_stream<128, false, false>, kGroupWaves * 64, lds_bytes));
-    else
-        ROLL_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&groups, attn_stream<64, false, false>, kGroupWaves * 64, lds_bytes));
-    if (groups < 1) return roll::fail(ROLL_ERR_HIP, "the attention kernel does not fit on a compute unit");
-    c = kGroupWaves * prop.multiProcessorCount;
-    *waves_out = c;
+    if (dev < 0 || dev >= kMaxDevices) return roll::fail(ROLL_ERR_HIP, "device index %d out of range", dev);
+    std::lock_guard<std::mutex> lock(mu);
+    if (cu_count[dev] == 0) {
+        int n = 0;
+        ROLL_HIP_CHECK(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev));
+        if (n < 1) return roll::fail(ROLL_ERR_HIP, "device %d reports no compute units", dev);
+        cu_count[dev] = n;
+    }
+    int32_t W = kGroupWaves * cu_count[dev];
+    *waves_out = W > kMaxPersistentWaves ? kMaxPersistentWaves : W;
+    if (device_out) *device_out = dev;
     return ROLL_OK;
 }
+
+// Profiling events of the calling thread (roll_prof_attn_events).
+thread_local hipEvent_t t_ev_begin = nullptr, t_ev_end = nullptr;
 
 }  // namespace
 
@@ -779,13 +810,41 @@ extern "C" size_t roll_decode_attn_workspace_bytes(const roll_attn_desc* d) {
 }
 
 extern "C" int roll_decode_attn_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
-    const Workspace ws = carve(workspace, 1, 1, 64);
     if (!workspace || !roll::aligned(workspace, 256)) return roll::fail(ROLL_ERR_WORKSPACE, "workspace NULL or not 256-byte aligned");
+    const Workspace ws = carve(workspace, 1, 1, 64);
     if (workspace_bytes < ws.header_bytes)
         return roll::fail(ROLL_ERR_WORKSPACE, "workspace too small: %zu < %zu bytes", workspace_bytes, ws.header_bytes);
     const size_t words = ws.header_bytes / 4;
-    zero_words<<<(unsigned)((words + 255) / 256), 256, 0, (hipStream_t)stream>>>((uint32_t*)workspace, words);
+    prepare_header<<<(unsigned)((words + 255) / 256), 256, 0, (hipStream_t)stream>>>((uint32_t*)workspace, words);
     ROLL_HIP_CHECK(hipGetLastError());
+    return ROLL_OK;
+}
+
+extern "C" int roll_decode_attn_workspace_check(const void* workspace, size_t workspace_bytes, void* stream) {
+    if (!workspace || !roll::aligned(workspace, 256)) return roll::fail(ROLL_ERR_WORKSPACE, "workspace NULL or not 256-byte aligned");
+    const Workspace ws = carve(nullptr, 1, 1, 64);
+    if (workspace_bytes < ws.header_bytes)
+        return roll::fail(ROLL_ERR_WORKSPACE, "workspace too small: %zu < %zu bytes", workspace_bytes, ws.header_bytes);
+    ROLL_HIP_CHECK(hipStreamSynchronize((hipStream_t)stream));
+    std::vector<uint32_t> host(ws.header_bytes / 4);
+    ROLL_HIP_CHECK(hipMemcpy(host.data(), workspace, ws.header_bytes, hipMemcpyDeviceToHost));
+    WorkspaceHeader h;
+    memcpy(&h, host.data(), sizeof h);
+    if (h.tag != kWorkspaceTag)
+        return roll::fail(ROLL_ERR_WORKSPACE, "workspace was never prepared (roll_decode_attn_workspace_init)");
+    if (h.refused != 0)
+        return roll::fail(ROLL_ERR_WORKSPACE, "%u launch(es) found the workspace unprepared and wrote no results", h.refused);
+    size_t dirty = h.grid_arrivals != 0;
+    for (size_t i = align_up(sizeof(WorkspaceHeader), 256) / 4; i < host.size(); ++i) dirty += host[i] != 0u;
+    if (dirty != 0)
+        return roll::fail(ROLL_ERR_WORKSPACE, "%zu arrival counter(s) are not zero: a launch on this workspace did not finish", dirty);
+    return ROLL_OK;
+}
+
+extern "C" int roll_prof_attn_events(void* begin, void* end) {
+    if ((begin == nullptr) != (end == nullptr)) return roll::fail(ROLL_ERR_INVALID_ARG, "begin and end must both be set or both NULL");
+    t_ev_begin = (hipEvent_t)begin;
+    t_ev_end = (hipEvent_t)end;
     return ROLL_OK;
 }
 
@@ -824,28 +883,25 @@ extern "C" int roll_decode_attn_ranges(const roll_attn_desc* d, const int32_t* s
 
 namespace {
 
-// Argument checks and the launch shared by the plain and the fused entry point.
+// Argument checks and the launch shared by the entry points.  ws_of(W) hands over the laid-out
+// scratch for a launch of W persistent waves, or fails.
+template <typename WsFn>
 int launch_attn(const void* q, const void* k_pages, const void* v_pages, const int32_t* page_table,
-                const int32_t* seq_lens, void* out, const roll_attn_desc* d, void* workspace,
-                size_t workspace_bytes, hipStream_t stream, FusedArgs* fused) {
+                const int32_t* seq_lens, void* out, const roll_attn_desc* d, WsFn ws_of, hipStream_t stream,
+                FusedArgs* fused) {
     if (!q || !k_pages || !v_pages || !page_table || !seq_lens || !out)
         return roll::fail(ROLL_ERR_INVALID_ARG, "NULL pointer argument");
     if (!roll::aligned(q, 16) || !roll::aligned(k_pages, 16) || !roll::aligned(v_pages, 16) || !roll::aligned(out, 16) ||
         !roll::aligned(page_table, 4) || !roll::aligned(seq_lens, 4))
         return roll::fail(ROLL_ERR_INVALID_ARG, "q, k_pages, v_pages, out must be 16-byte aligned");
     const int32_t G = d->num_q_heads / d->num_kv_heads;
-    if (!workspace || !roll::aligned(workspace, 256)) return roll::fail(ROLL_ERR_WORKSPACE, "workspace NULL or not 256-byte aligned");
-    Workspace ws = carve(workspace, d->num_kv_heads, G, d->head_dim);
-    if (workspace_bytes < ws.bytes)
-        return roll::fail(ROLL_ERR_WORKSPACE, "workspace too small: %zu < %zu bytes", workspace_bytes, ws.bytes);
-
-    const size_t lds = sizeof(int32_t) * (2 * (size_t)d->batch + 1) + sizeof(uint16_t) * ((size_t)d->batch + 2);
     int32_t W = 0;
-    int rc = persistent_waves(d->head_dim, lds, &W);
+    Workspace ws{};
+    int rc = ws_of(&W, &ws);
     if (rc != ROLL_OK) return rc;
-    if (W > kMaxPersistentWaves) W = kMaxPersistentWaves;
     W = W / kGroupWaves * kGroupWaves;
 
+    const size_t lds = sizeof(int32_t) * (2 * (size_t)d->batch + 1) + sizeof(uint16_t) * ((size_t)d->batch + 2);
     AttnParams prm{};
     prm.B = d->batch;
     prm.Hq = d->num_q_heads;
@@ -862,10 +918,10 @@ int launch_attn(const void* q, const void* k_pages, const void* v_pages, const i
     prm.scale_log2e = scale * 1.44269504088896340736f;
 
     const unsigned grid = (unsigned)(W / kGroupWaves);
-    if (d->ev_main_begin) ROLL_HIP_CHECK(hipEventRecord((hipEvent_t)d->ev_main_begin, stream));
+    if (t_ev_begin) ROLL_HIP_CHECK(hipEventRecord(t_ev_begin, stream));
 #define ROLL_LAUNCH_ATTN(DIM, FUSED, F32, EXTRA)                                                              \
     attn_stream<DIM, FUSED, F32><<<grid, kGroupWaves * 64, lds, stream>>>(                                   \
-        (const uint4*)q, (const uint4*)k_pages, (const uint4*)v_pages, page_table, seq_lens, out,             \
+        (const uint4*)q, (const uint4*)k_pages, (const uint4*)v_pages, page_table, seq_lens, out, ws.header,  \
         ws.group_arrivals, ws.stream_arrivals, ws.part_ml, ws.part_acc, ws.group_ml, ws.group_acc, prm, EXTRA)
 #define ROLL_LAUNCH_ATTN_OUT(DIM, FUSED, EXTRA)                  \
     do {                                                         \
@@ -873,7 +929,6 @@ int launch_attn(const void* q, const void* k_pages, const void* v_pages, const i
         else ROLL_LAUNCH_ATTN(DIM, FUSED, false, EXTRA);            \
     } while (0)
     if (fused) {
-        fused->grid_arrivals = ws.grid_arrivals;
         if (d->head_dim == 128) ROLL_LAUNCH_ATTN_OUT(128, true, *fused);
         else ROLL_LAUNCH_ATTN_OUT(64, true, *fused);
     } else {
@@ -883,9 +938,23 @@ int launch_attn(const void* q, const void* k_pages, const void* v_pages, const i
 #undef ROLL_LAUNCH_ATTN_OUT
 #undef ROLL_LAUNCH_ATTN
     ROLL_HIP_CHECK(hipGetLastError());
-    if (d->ev_main_end) ROLL_HIP_CHECK(hipEventRecord((hipEvent_t)d->ev_main_end, stream));
+    if (t_ev_end) ROLL_HIP_CHECK(hipEventRecord(t_ev_end, stream));
     return ROLL_OK;
 }
+
+// The scratch of a launch from a caller's workspace (sized for any launch, see carve).
+struct CallerWorkspace {
+    const roll_attn_desc* d;
+    void* workspace;
+    size_t workspace_bytes;
+    int operator()(int32_t* W, Workspace* ws) const {
+        if (!workspace || !roll::aligned(workspace, 256)) return roll::fail(ROLL_ERR_WORKSPACE, "workspace NULL or not 256-byte aligned");
+        *ws = carve(workspace, d->num_kv_heads, d->num_q_heads / d->num_kv_heads, d->head_dim);
+        if (workspace_bytes < ws->bytes)
+            return roll::fail(ROLL_ERR_WORKSPACE, "workspace too small: %zu < %zu bytes", workspace_bytes, ws->bytes);
+        return persistent_waves(W);
+    }
+};
 
 }  // namespace
 
@@ -895,7 +964,7 @@ extern "C" int roll_decode_attn(const void* q, const void* k_pages, const void* 
                                 void* stream_v) {
     int rc = validate(d);
     if (rc != ROLL_OK) return rc;
-    return launch_attn(q, k_pages, v_pages, page_table, seq_lens, out, d, workspace, workspace_bytes,
+    return launch_attn(q, k_pages, v_pages, page_table, seq_lens, out, d, CallerWorkspace{d, workspace, workspace_bytes},
                        (hipStream_t)stream_v, nullptr);
 }
 
@@ -904,9 +973,19 @@ extern "C" int roll_decode_step_attn(roll_kv_pool* pool, const void* k_new, cons
                                      void* workspace, size_t workspace_bytes, void* stream_v) {
     int rc = validate(d);
     if (rc != ROLL_OK) return rc;
-    if (!pool || !k_new || !v_new) return roll::fail(ROLL_ERR_INVALID_ARG, "NULL pointer argument");
-    if (!roll::aligned(k_new, 16) || !roll::aligned(v_new, 16))
-        return roll::fail(ROLL_ERR_INVALID_ARG, "k_new, v_new must be 16-byte aligned");
+    if (!pool || !k_new || !v_new || !q || !k_pages || !v_pages || !out)
+        return roll::fail(ROLL_ERR_INVALID_ARG, "NULL pointer argument");
+    if (!roll::aligned(k_new, 16) || !roll::aligned(v_new, 16) || !roll::aligned(q, 16) || !roll::aligned(k_pages, 16) ||
+        !roll::aligned(v_pages, 16) || !roll::aligned(out, 16))
+        return roll::fail(ROLL_ERR_INVALID_ARG, "k_new, v_new, q, k_pages, v_pages, out must be 16-byte aligned");
+    // the workspace is checked before the allocator's pending changes are touched, so that a
+    // refused call leaves them pending
+    {
+        int32_t W;
+        Workspace ws;
+        rc = CallerWorkspace{d, workspace, workspace_bytes}(&W, &ws);
+        if (rc != ROLL_OK) return rc;
+    }
     hipStream_t stream = (hipStream_t)stream_v;
     roll::FusedPlan plan;
     rc = roll::plan_fused_step(pool, stream, &plan);
@@ -915,14 +994,15 @@ extern "C" int roll_decode_step_attn(roll_kv_pool* pool, const void* k_new, cons
         plan.num_pages != d->num_pages)
         return roll::fail(ROLL_ERR_INVALID_ARG, "desc does not match the pool (slots %d, page size %d, max pages %d, pages %d)",
                           plan.num_slots, plan.page_size, plan.max_pages, plan.num_pages);
+    const CallerWorkspace caller_ws{d, workspace, workspace_bytes};
     if (!plan.fusable) {
         // Not a plain decode step since the last commit (refills, first use, many new pages):
         // publish through the allocator's own kernel, then attend.
         rc = roll_kv_commit_append(pool, k_new, v_new, k_pages, v_pages, d->num_kv_heads, d->head_dim, d->page_stride,
                                    stream_v);
         if (rc != ROLL_OK) return rc;
-        return launch_attn(q, k_pages, v_pages, plan.page_table_dev, plan.seq_lens_dev, out, d, workspace,
-                           workspace_bytes, stream, nullptr);
+        return launch_attn(q, k_pages, v_pages, plan.page_table_dev, plan.seq_lens_dev, out, d, caller_ws, stream,
+                           nullptr);
     }
     FusedArgs fa{};
     fa.n_delta = plan.n_delta;
@@ -934,9 +1014,7 @@ extern "C" int roll_decode_step_attn(roll_kv_pool* pool, const void* k_new, cons
     fa.v_new = (const uint4*)v_new;
     fa.page_table_w = plan.page_table_dev;
     fa.seq_lens_w = plan.seq_lens_dev;
-    fa.grid_arrivals = nullptr;
-    rc = launch_attn(q, k_pages, v_pages, plan.page_table_dev, plan.seq_lens_dev, out, d, workspace,
-                     workspace_bytes, stream, &fa);
+    rc = launch_attn(q, k_pages, v_pages, plan.page_table_dev, plan.seq_lens_dev, out, d, caller_ws, stream, &fa);
     if (rc != ROLL_OK) return rc;
     roll::finish_fused_step(pool);
     return ROLL_OK;

@@ -104,7 +104,7 @@ class DecodeBatch:
         desc = self.desc
         if self.profile_events:
             e0, e1 = self.ev_spare.pop() if self.ev_spare else (rb.ProfEvent(), rb.ProfEvent())
-            desc.ev_main_begin, desc.ev_main_end = e0.handle.value, e1.handle.value
+            rb.roll_prof_attn_events(e0, e1)
             self.ev_pairs.append((e0, e1, self.total_tokens()))
         if fused:
             rb.roll_decode_step_attn(self.pool, self.k_new, self.v_new, self.q, self.k_pages, self.v_pages,
@@ -113,7 +113,7 @@ class DecodeBatch:
             rb.roll_decode_attn(self.q, self.k_pages, self.v_pages, self.page_table, self.seq_lens, self.out,
                                 desc, self._ws)
         if self.profile_events:
-            desc.ev_main_begin, desc.ev_main_end = None, None
+            rb.roll_prof_attn_events(None, None)
         sdesc = rb.sample_desc(logits)
         rb.roll_sample_logprob(logits, cfg.temperature if temperature is None else temperature,
                                cfg.top_p if top_p is None else top_p, self.seed, step_index,

@@ -123,11 +123,11 @@ def test_bad_pool_config_is_rejected():
 
 def test_attention_and_sampling_reject_bad_descriptors_on_the_host():
     L = rb.lib()
-    good = rb.AttnDesc(4, 8, 2, 64, 16, 8, 32, rb.ROLL_BF16, 0.0, 0, None, None)
+    good = rb.AttnDesc(4, 8, 2, 64, 16, 8, 32, rb.ROLL_BF16, 0.0, 0)
     assert L.roll_decode_attn_workspace_bytes(C.byref(good)) > 0
     for field, val in [("head_dim", 96), ("num_kv_heads", 3), ("page_size", 8), ("batch", 8193),
                        ("batch", 0), ("out_dtype", 7), ("num_q_heads", 64)]:
-        d = rb.AttnDesc(4, 8, 2, 64, 16, 8, 32, rb.ROLL_BF16, 0.0, 0, None, None)
+        d = rb.AttnDesc(4, 8, 2, 64, 16, 8, 32, rb.ROLL_BF16, 0.0, 0)
         if field == "num_q_heads":
             d.num_kv_heads = 2  # group of 32 > 16
         setattr(d, field, val)
@@ -234,9 +234,37 @@ def test_page_stride_must_be_whole_head_blocks_that_hold_all_heads():
 
     def desc(stride):
         return rb.AttnDesc(base["batch"], base["Hq"], base["Hkv"], base["D"], base["P"], 8, 32, rb.ROLL_BF16, 0.0,
-                           stride, None, None)
+                           stride)
     for ok in (0, 2 * block, 4 * block, 7 * block):      # dense; exactly the heads; K and V side by side; padded
         assert L.roll_decode_attn_workspace_bytes(C.byref(desc(ok))) > 0
     for bad in (block, 2 * block + 8, -2 * block, 2 * block - 1):
         assert L.roll_decode_attn_workspace_bytes(C.byref(desc(bad))) == 0
         assert L.roll_decode_attn(16, 16, 16, 16, 16, 16, C.byref(desc(bad)), 256, 1 << 30, None) == -1
+
+
+def test_step_count_of_a_batch_must_fit_32_bits():
+    # the kernel keeps the rows' step counts as 32-bit prefix sums: a desc that could exceed them is
+    # refused on the host
+    L = rb.lib()
+    ok = rb.AttnDesc(8192, 8, 2, 64, 64, (1 << 24) // 64 // 4, 32, rb.ROLL_BF16, 0.0, 0)
+    assert L.roll_decode_attn_workspace_bytes(C.byref(ok)) > 0
+    big = rb.AttnDesc(8192, 8, 2, 64, 64, (1 << 24) // 64, 32, rb.ROLL_BF16, 0.0, 0)
+    assert L.roll_decode_attn_workspace_bytes(C.byref(big)) == 0
+    assert L.roll_decode_attn(16, 16, 16, 16, 16, 16, C.byref(big), 256, 1 << 30, None) == -5
+
+
+def test_workspace_check_and_decode_step_reject_bad_arguments_on_the_host():
+    L = rb.lib()
+    good = rb.AttnDesc(4, 8, 2, 64, 16, 8, 32, rb.ROLL_BF16, 0.0, 0)
+    assert L.roll_decode_attn_workspace_check(None, 1 << 30, None) == -6
+    assert L.roll_decode_attn_workspace_check(128, 1 << 30, None) == -6
+    assert L.roll_decode_attn_workspace_check(256, 8, None) == -6
+    assert L.roll_decode_attn_workspace_init(256, 8, None) == -6
+    assert L.roll_prof_attn_events(16, None) == -1
+    assert L.roll_prof_attn_events(None, None) == 0
+    # the decode step checks its pointers and workspace before it touches the allocator's pending changes
+    pool = host_pool()
+    rb.roll_kv_alloc(pool, 0, 3)
+    assert L.roll_decode_step_attn(pool._h, 16, 16, None, 16, 16, 16, C.byref(good), 256, 1 << 30, None) == -1
+    assert L.roll_decode_step_attn(pool._h, 16, 16, 16, 16, 16, 16, C.byref(good), 256, 8, None) == -6
+    assert rb.roll_kv_seq_len(pool, 0) == 3

@@ -12,7 +12,7 @@ STEP, STEP_COST, ROW_COST = 32, 2, 2
 
 
 def desc(B, Hq=28, Hkv=4, D=128, P=16, max_pages=2048):
-    return rb.AttnDesc(B, Hq, Hkv, D, P, max_pages, 1 << 20, rb.ROLL_BF16, 0.0, 0, None, None)
+    return rb.AttnDesc(B, Hq, Hkv, D, P, max_pages, 1 << 20, rb.ROLL_BF16, 0.0, 0)
 
 
 def by_definition(lens, num_ranges):

@@ -177,3 +177,40 @@ def test_maximum_batch_of_short_and_empty_rows():
     want = oracle_attn(inp, cfg)
     assert np.abs(got - want).max() <= 1e-4
     assert not got[lengths == 0].any()
+
+
+def test_unprepared_workspace_is_refused_by_the_kernel_and_found_by_the_check():
+    # A workspace that roll_decode_attn_workspace_init never saw holds arbitrary arrival counters,
+    # with which cut rows would merge too early or never.  The kernel refuses it: nothing is
+    # written, and the diagnostic call says why.
+    from paper_2510_11345_amd import binding as rb
+    cfg = wl.CONFIGS["c2"]
+    lens = np.asarray([5000, 3, 700, 0, 64], np.int32)
+    inp = wl.make_attn_inputs(cfg, 5, "cuda", lengths=np.maximum(lens, 1))
+    q, k, v = inp["q"], inp["k_pages"], inp["v_pages"]
+    table = torch.from_numpy(inp["page_table"]).cuda()
+    sl = torch.from_numpy(lens).cuda()
+    out = torch.full(q.shape, 3.0, dtype=torch.float32, device="cuda")
+    desc = rb.attn_desc(q, k, table, cfg.page_size, torch.float32)
+    ws = torch.full((rb.roll_decode_attn_workspace_bytes(desc),), 0xA5, dtype=torch.uint8, device="cuda")
+    rb.roll_decode_attn(q, k, v, table, sl, out, desc, ws)
+    torch.cuda.synchronize()
+    assert bool((out == 3.0).all())
+    with pytest.raises(rb.RollError) as e:
+        rb.roll_decode_attn_workspace_check(ws)
+    assert e.value.status == -6 and "never prepared" in str(e.value)
+    # a tag without a clean header (here: a counter left over) is found too
+    rb.roll_decode_attn_workspace_init(ws)
+    rb.roll_decode_attn_workspace_check(ws)
+    ws[4096:4100] = 1
+    with pytest.raises(rb.RollError) as e:
+        rb.roll_decode_attn_workspace_check(ws)
+    assert "not zero" in str(e.value)
+    # prepared: the same call now computes, and leaves the header clean
+    rb.roll_decode_attn_workspace_init(ws)
+    rb.roll_decode_attn(q, k, v, table, sl, out, desc, ws)
+    torch.cuda.synchronize()
+    rb.roll_decode_attn_workspace_check(ws)
+    ref = oracle.decode_attn(wl.bits(q), wl.bits(k).reshape(-1), wl.bits(v).reshape(-1), inp["page_table"], lens,
+                             cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.page_size)
+    assert np.abs(out.double().cpu().numpy() - ref).max() <= TOL_F32
