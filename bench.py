@@ -2,10 +2,14 @@
 """Benchmark of the rollout decode step on one MI355X.
 
 One step = the whole hot path over one batch: allocator (+1 token per row, one commit),
-K/V append, paged GQA decode attention (work list, split-K partial, merge) and
+K/V append, paged GQA decode attention (work dealing, split-K partial, merge) and
 temperature / top-p sampling with log-prob recording.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c2]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c2|c3|c4|c5]
+
+Without --config the line's own fields are those of c5 (the largest configuration that fits one
+GPU), and `per_config` holds the same fields for c3, c2 and c4 (its 200-step refill loop), every
+configuration with its roofline, its CPU-oracle baseline and the parity of all its rows.
 """
 from __future__ import annotations
 
@@ -71,11 +75,11 @@ def equal_rows_bench(args, torch, rb, wl, DecodeBatch):
                                 desc, batch._ws)
         torch.cuda.synchronize()
         for a, b in evs:
-            desc.ev_main_begin, desc.ev_main_end = a.handle.value, b.handle.value
+            rb.roll_prof_attn_events(a, b)
             rb.roll_decode_attn(batch.q, batch.k_pages, batch.v_pages, batch.page_table, batch.seq_lens, batch.out,
                                 desc, batch._ws)
         torch.cuda.synchronize()
-        desc.ev_main_begin, desc.ev_main_end = None, None
+        rb.roll_prof_attn_events(None, None)
         ms = float(np.mean([a.elapsed_ms(b) for a, b in evs]))
         kv_bytes = cfg.kv_bytes_per_token * batch.total_tokens()
         out[name] = {"sum_seq_lens": int(batch.total_tokens()), "avg_launch_ms": ms,
@@ -200,13 +204,200 @@ def prefill_bench(args, torch, rb, wl):
                       "per_workload": res}), flush=True)
 
 
+def spread(xs):
+    """mean, median, 10th and 90th percentile of a list of milliseconds."""
+    a = np.asarray(xs, dtype=np.float64)
+    return {"mean": float(a.mean()), "median": float(np.median(a)), "p10": float(np.percentile(a, 10)),
+            "p90": float(np.percentile(a, 90)), "n": int(a.size)}
+
+
+def ceiling_probe(torch, rb, batch, n=12):
+    """GB/s of a plain streaming read of the batch's paged KV bytes through its page table
+    (roll_prof_kv_read_probe): what this machine's memory system gives to the access pattern of the
+    step, with no arithmetic and nothing written.  Median of n launches."""
+    sink = torch.empty(2048 * 256, dtype=torch.int32, device="cuda")
+    per_page = 0
+    for _ in range(3):
+        per_page = rb.roll_prof_kv_read_probe(batch.k_pages, batch.v_pages, batch.page_table, batch.seq_lens,
+                                              batch.desc, sink)
+    evs = [(rb.ProfEvent(), rb.ProfEvent()) for _ in range(n)]
+    torch.cuda.synchronize()
+    for a, b in evs:
+        a.record()
+        rb.roll_prof_kv_read_probe(batch.k_pages, batch.v_pages, batch.page_table, batch.seq_lens, batch.desc, sink)
+        b.record()
+    torch.cuda.synchronize()
+    P = batch.cfg.page_size
+    pages = int(((batch.lengths + P - 1) // P).sum())
+    ms = float(np.median([a.elapsed_ms(b) for a, b in evs]))
+    return {"GBps": per_page * pages / (ms * 1e-3) / 1e9, "bytes": per_page * pages, "median_launch_ms": ms}
+
+
+def run_config(name, K, W, args, torch, rb, wl):
+    """W warm-up steps, then K timed steps of the whole path on config `name`; the attention launch
+    timed by HIP events on its stream; the sampling launch alone; the bandwidth ceiling; the CPU
+    oracle on every row with the parity of the last step.  Returns the fields of one result."""
+    from paper_2510_11345_amd.harness import DecodeBatch
+    cfg = wl.CONFIGS[name]
+    extra = {}
+    pool_kw = dict(side_by_side=False, run_pages=1) if args.dense_pools else {}
+    loop = None
+    if cfg.name == "c4":
+        # continuous refill: slots finish by pre-drawn length and are refilled from the prompt queue
+        from paper_2510_11345_amd.harness import RefillLoop
+        plan = wl.draw_refill_plan(cfg.batch, cfg.batch + 4 * (K + W) + 64, args.seed)
+        loop = RefillLoop(cfg, plan, args.seed, max_len=cfg.max_len + K + W + 2, **pool_kw)
+        batch = loop.batch
+        step_fn = loop.step
+    else:
+        lengths = wl.draw_lengths(cfg.lengths, cfg.batch, args.seed, cfg.max_len).astype(np.int64)
+        # seq_lens count the token being decoded: start one short, every step appends one token
+        batch = DecodeBatch(cfg, args.seed, lengths - 1, headroom_tokens=K + W + 2, profile_events=False, **pool_kw)
+        step_fn = batch.step
+    logits = wl.make_logits(cfg, args.seed, "cuda")
+    torch.cuda.synchronize()
+
+    step_index = 0
+    for _ in range(W):
+        step_fn(logits, step_index)
+        step_index += 1
+    torch.cuda.synchronize()
+    batch.ev_spare = [(rb.ProfEvent(), rb.ProfEvent()) for _ in range(K)]
+    batch.profile_events = True
+    refills_before = loop.refills if loop else 0
+    t0 = time.perf_counter()
+    for _ in range(K):
+        step_fn(logits, step_index)
+        step_index += 1
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    batch.profile_events = False
+    if loop:
+        extra = {"refills_in_timed_steps": loop.refills - refills_before,
+                 "free_pages_at_end": rb.roll_kv_free_pages(batch.pool),
+                 "note": "refill (release, alloc, chunked prefill of the new prompts into pages) is inside the timed steps"}
+
+    ms_per_step = (t1 - t0) * 1e3 / K
+    beta = cfg.kv_bytes_per_token
+    kern_ms = [a.elapsed_ms(b) for a, b, _ in batch.ev_pairs]
+    kv_bytes = [beta * tot for _, _, tot in batch.ev_pairs]
+    # one step on the GPU's clock: from the start of an attention launch to the start of the next
+    step_gpu_ms = [batch.ev_pairs[i][0].elapsed_ms(batch.ev_pairs[i + 1][0]) for i in range(len(batch.ev_pairs) - 1)]
+    avg_kern_ms = float(np.mean(kern_ms))
+    avg_kv_bytes = float(np.mean(kv_bytes))
+    achieved = avg_kv_bytes / (avg_kern_ms * 1e-3) / 1e9
+    workload = (f"{cfg.name}: B={cfg.batch} Hq={cfg.num_q_heads} Hkv={cfg.num_kv_heads} D={cfg.head_dim} "
+                f"P={cfg.page_size} lengths={cfg.lengths} V={cfg.vocab} T={cfg.temperature} top_p={cfg.top_p}")
+    ceiling = ceiling_probe(torch, rb, batch)
+
+    result = {
+        "value": cfg.batch / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": ms_per_step,
+        "config": {"workload": workload, "seed": args.seed, "sum_seq_lens": int(batch.total_tokens()),
+                   "kv_pools": ("two dense allocations, single pages" if args.dense_pools else
+                                f"one allocation, K and V of a page side by side, pages in runs of {batch.run_pages}"),
+                   **extra},
+        "kv_read_GBps": achieved,
+        "kv_read_frac_of_peak": achieved / HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "attn_stream", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": profiled_traffic(cfg.name, avg_kv_bytes),
+                     "algorithmic_bytes_per_launch": avg_kv_bytes, "avg_launch_ms": avg_kern_ms,
+                     "launch_ms": spread(kern_ms),
+                     "ceiling_GBps": ceiling["GBps"], "frac_of_ceiling": achieved / ceiling["GBps"],
+                     "ceiling": "median of 12 launches of roll_prof_kv_read_probe: a plain streaming read of the "
+                                "same pages through the same page table, no arithmetic, nothing written"},
+    }
+    if step_gpu_ms:
+        result["step_ms_on_gpu_clock"] = spread(step_gpu_ms)
+
+    # The sampling launch alone (after the timed region): its bound is the vector ALU, not HBM, so
+    # it is reported as logits per second and vector instructions per logit.
+    n_s = 20
+    s0, s1 = rb.ProfEvent(), rb.ProfEvent()
+    sdesc = rb.sample_desc(logits)
+    s0.record()
+    for i in range(n_s):
+        rb.roll_sample_logprob(logits, cfg.temperature, cfg.top_p, args.seed, step_index + i, batch.tokens,
+                               batch.logprob, sdesc, None)
+    s1.record()
+    torch.cuda.synchronize()
+    samp_ms = s0.elapsed_ms(s1) / n_s
+    result["sampling"] = {"kernel": "sample_rows", "bound": "alu", "avg_launch_ms": samp_ms,
+                          "Gelem_per_s": cfg.batch * cfg.vocab / (samp_ms * 1e-3) / 1e9,
+                          "vector_instructions_per_logit": profiled_valu_per_logit(cfg.name),
+                          "peak_lane_ops_per_s": 256 * 4 * 16 * 2.4e9,
+                          "compulsory_bytes": cfg.batch * cfg.vocab * (2 if cfg.logits_dtype == "bf16" else 4)}
+    result["gpu_busy_frac"] = (avg_kern_ms + samp_ms) / ms_per_step
+    n_layers = 64 if cfg.name == "c5" else 28
+    result["extrapolation"] = {
+        "what": "tokens/s if every step ran n_layers such attention launches and one sampling launch "
+                "(the attention and sampling times measured above; nothing else of a model counted)",
+        "n_layers": n_layers,
+        "tokens_per_s": cfg.batch / ((n_layers * avg_kern_ms + samp_ms) * 1e-3)}
+    # the step that parity is checked on must be the last one the batch ran
+    rb.roll_sample_logprob(logits, cfg.temperature, cfg.top_p, args.seed, step_index - 1, batch.tokens,
+                           batch.logprob, sdesc, None)
+    torch.cuda.synchronize()
+
+    if not args.no_cpu_baseline:
+        import oracle
+        n = cfg.batch if args.oracle_rows <= 0 else min(args.oracle_rows, cfg.batch)
+        rows = [int(r) for r in np.linspace(0, cfg.batch - 1, n).round().astype(int)]
+        rows = sorted(set(rows))
+        q, k, v, table, lens = batch.gather_rows(rows)
+        last_step = step_index - 1
+        gpu_out = batch.out[torch.tensor(rows, device="cuda")].double().cpu().numpy()
+        gpu_tok = batch.tokens.cpu().numpy()[rows]
+        gpu_lp = batch.logprob.double().cpu().numpy()[rows]
+        lg_host = wl.logits_numpy(logits[torch.tensor(rows, device="cuda")])
+        c0 = time.perf_counter()
+        ref_out, threads = oracle.decode_attn(q, k, v, table, lens, cfg.num_q_heads, cfg.num_kv_heads,
+                                              cfg.head_dim, cfg.page_size, return_threads=True)
+        c1 = time.perf_counter()
+        ref = oracle.sample_logprob(lg_host, cfg.temperature, cfg.top_p, args.seed, last_step, row_ids=rows)
+        c2 = time.perf_counter()
+        differ = gpu_tok != ref["tokens"]
+        x = logits[torch.tensor(rows, device="cuda")].float().cpu().numpy()
+        # rows whose tokens differ and one of the two lies between the cuts for top_p -+ 1e-5
+        in_band = sum(any(ref["x_cut_plus"][i] <= x[i, t] < ref["x_cut_minus"][i]
+                          for t in (gpu_tok[i], ref["tokens"][i]) if 0 <= t < cfg.vocab)
+                      for i in np.flatnonzero(differ))
+        near_tie = int((differ & (ref["gap"] < 1e-5)).sum())
+        result["cpu_baseline"] = {
+            "value": len(rows) / (c2 - c0), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{len(rows)} of {cfg.batch} rows" + (" (all)" if len(rows) == cfg.batch else " (evenly spaced)") +
+                      f", {int(lens.sum())} KV tokens: attention {c1 - c0:.2f} s + sampling {c2 - c1:.2f} s",
+        }
+        result["parity_on_sample"] = {
+            "rows_compared": len(rows),
+            "attn_max_abs_err_bf16_out": float(np.abs(gpu_out - ref_out).max()),
+            "logprob_max_abs_err": float(np.abs(gpu_lp - ref["logprob"])[~differ].max()) if not differ.all() else None,
+            "token_mismatches": int(differ.sum()),
+            "token_mismatches_at_near_ties_below_1e-5": near_tie,
+            "token_mismatches_in_top_p_boundary_band": int(in_band),
+            "near_ties_below_1e-5": int((ref["gap"] < 1e-5).sum()),
+        }
+    batch.close()
+    del batch, loop, logits
+    torch.cuda.empty_cache()
+    return result
+
+
+C4_STEPS = 200  # the refill workload is defined over 200 decode steps
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="c2", choices=["c2", "c3", "c4", "c5"],
-                    help="c2 (default) is the configuration the metric is quoted on; c4 is the 200-step refill loop")
+    ap.add_argument("--config", default=None, choices=["c2", "c3", "c4", "c5"],
+                    help="one configuration only.  Default: the headline is c5, the largest single-GPU "
+                         "configuration, and c2, c3 and c4 (the 200-step refill loop) follow under per_config")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--oracle-rows", type=int, default=0, help="rows timed on the CPU oracle (0 = the whole batch)")
@@ -248,6 +439,7 @@ def main():
                           "bytes_written": dst.numel() * 4}))
         return
     if args.equal_rows:
+        args.config = args.config or "c2"
         equal_rows_bench(args, torch, rb, wl, DecodeBatch)
         return
     if args.policy_loss:
@@ -256,139 +448,34 @@ def main():
     if args.prefill:
         prefill_bench(args, torch, rb, wl)
         return
-    cfg = wl.CONFIGS[args.config]
+
     K, W = args.steps, args.warmup
-    extra = {}
-    pool_kw = dict(side_by_side=False, run_pages=1) if args.dense_pools else {}
-    if cfg.name == "c4":
-        # continuous refill: slots finish by pre-drawn length and are refilled from the prompt queue
-        from paper_2510_11345_amd.harness import RefillLoop
-        plan = wl.draw_refill_plan(cfg.batch, cfg.batch + 4 * (K + W) + 64, args.seed)
-        loop = RefillLoop(cfg, plan, args.seed, max_len=cfg.max_len + K + W + 2, **pool_kw)
-        batch = loop.batch
-        step_fn = loop.step
-    else:
-        lengths = wl.draw_lengths(cfg.lengths, cfg.batch, args.seed, cfg.max_len).astype(np.int64)
-        # seq_lens count the token being decoded: start one short, every step appends one token
-        batch = DecodeBatch(cfg, args.seed, lengths - 1, headroom_tokens=K + W + 2, profile_events=False, **pool_kw)
-        step_fn = batch.step
-    logits = wl.make_logits(cfg, args.seed, "cuda")
-    torch.cuda.synchronize()
-
-    step_index = 0
-    for _ in range(W):
-        step_fn(logits, step_index)
-        step_index += 1
-    torch.cuda.synchronize()
-    batch.ev_spare = [(rb.ProfEvent(), rb.ProfEvent()) for _ in range(K)]
-    batch.profile_events = True
-    refills_before = loop.refills if cfg.name == "c4" else 0
-    t0 = time.perf_counter()
-    for _ in range(K):
-        step_fn(logits, step_index)
-        step_index += 1
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    batch.profile_events = False
-    if cfg.name == "c4":
-        extra = {"refills_in_timed_steps": loop.refills - refills_before,
-                 "free_pages_at_end": rb.roll_kv_free_pages(batch.pool),
-                 "note": "refill (release, alloc, chunked prefill of the new prompts into pages) is inside the timed steps"}
-
-    ms_per_step = (t1 - t0) * 1e3 / K
-    beta = cfg.kv_bytes_per_token
-    kern_ms = [a.elapsed_ms(b) for a, b, _ in batch.ev_pairs]
-    kv_bytes = [beta * tot for _, _, tot in batch.ev_pairs]
-    avg_kern_ms = float(np.mean(kern_ms))
-    avg_kv_bytes = float(np.mean(kv_bytes))
-    achieved = avg_kv_bytes / (avg_kern_ms * 1e-3) / 1e9
-    workload = (f"{cfg.name}: B={cfg.batch} Hq={cfg.num_q_heads} Hkv={cfg.num_kv_heads} D={cfg.head_dim} "
-                f"P={cfg.page_size} lengths={cfg.lengths} V={cfg.vocab} T={cfg.temperature} top_p={cfg.top_p}")
-
+    head_name = args.config or "c5"
+    say = lambda m: print(m, file=sys.stderr, flush=True)
+    say(f"bench: {head_name}, {K} steps")
+    head = run_config(head_name, K, W, args, torch, rb, wl)
     result = {
         "metric": "decode tokens/s (one attention layer + sampling per step)",
-        "value": cfg.batch / (ms_per_step * 1e-3),
-        "unit": "tokens/s",
+        "value": head.pop("value"),
+        "unit": head.pop("unit"),
         "n_gpus": 1,
-        "steps": K,
-        "warmup": W,
-        "ms_per_step": ms_per_step,
+        "steps": head.pop("steps"),
+        "warmup": head.pop("warmup"),
+        "ms_per_step": head.pop("ms_per_step"),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": workload, "seed": args.seed, "sum_seq_lens": int(batch.total_tokens()),
-                   "kv_pools": ("two dense allocations, single pages" if args.dense_pools else
-                                f"one allocation, K and V of a page side by side, pages in runs of {batch.run_pages}"),
-                   **extra},
-        "kv_read_GBps": achieved,
-        "kv_read_frac_of_peak": achieved / HBM_PEAK_GBS,
-        "roofline": {"bound": "hbm", "kernel": "attn_stream", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": profiled_traffic(cfg.name, avg_kv_bytes),
-                     "algorithmic_bytes_per_launch": avg_kv_bytes, "avg_launch_ms": avg_kern_ms},
+        **head,
     }
-
-    # The sampling launch alone (after the timed region): its bound is the vector ALU, not HBM, so
-    # it is reported as logits per second and vector instructions per logit.
-    n_s = 20
-    s0, s1 = rb.ProfEvent(), rb.ProfEvent()
-    sdesc = rb.sample_desc(logits)
-    s0.record()
-    for i in range(n_s):
-        rb.roll_sample_logprob(logits, cfg.temperature, cfg.top_p, args.seed, step_index + i, batch.tokens,
-                               batch.logprob, sdesc, None)
-    s1.record()
-    torch.cuda.synchronize()
-    samp_ms = s0.elapsed_ms(s1) / n_s
-    result["sampling"] = {"kernel": "sample_rows", "bound": "alu", "avg_launch_ms": samp_ms,
-                          "Gelem_per_s": cfg.batch * cfg.vocab / (samp_ms * 1e-3) / 1e9,
-                          "vector_instructions_per_logit": profiled_valu_per_logit(cfg.name),
-                          "peak_lane_ops_per_s": 256 * 4 * 16 * 2.4e9,
-                          "compulsory_bytes": cfg.batch * cfg.vocab * (2 if cfg.logits_dtype == "bf16" else 4)}
-    n_layers = 64 if cfg.name == "c5" else 28
-    result["extrapolation"] = {
-        "what": "tokens/s if every step ran n_layers such attention launches and one sampling launch "
-                "(the attention and sampling times measured above; nothing else of a model counted)",
-        "n_layers": n_layers,
-        "tokens_per_s": cfg.batch / ((n_layers * avg_kern_ms + samp_ms) * 1e-3)}
-    # the step that parity is checked on must be the last one the batch ran
-    rb.roll_sample_logprob(logits, cfg.temperature, cfg.top_p, args.seed, step_index - 1, batch.tokens,
-                           batch.logprob, sdesc, None)
-    torch.cuda.synchronize()
-
-    if not args.no_cpu_baseline:
-        import oracle
-        n = cfg.batch if args.oracle_rows <= 0 else min(args.oracle_rows, cfg.batch)
-        rows = [int(r) for r in np.linspace(0, cfg.batch - 1, n).round().astype(int)]
-        rows = sorted(set(rows))
-        q, k, v, table, lens = batch.gather_rows(rows)
-        last_step = step_index - 1
-        gpu_out = batch.out[torch.tensor(rows, device="cuda")].double().cpu().numpy()
-        gpu_tok = batch.tokens.cpu().numpy()[rows]
-        gpu_lp = batch.logprob.double().cpu().numpy()[rows]
-        lg_host = wl.logits_numpy(logits[torch.tensor(rows, device="cuda")])
-        c0 = time.perf_counter()
-        ref_out, threads = oracle.decode_attn(q, k, v, table, lens, cfg.num_q_heads, cfg.num_kv_heads,
-                                              cfg.head_dim, cfg.page_size, return_threads=True)
-        c1 = time.perf_counter()
-        ref = oracle.sample_logprob(lg_host, cfg.temperature, cfg.top_p, args.seed, last_step, row_ids=rows)
-        c2 = time.perf_counter()
-        mism = int((gpu_tok != ref["tokens"]).sum())
-        result["cpu_baseline"] = {
-            "value": len(rows) / (c2 - c0), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{len(rows)} of {cfg.batch} rows (evenly spaced), {int(lens.sum())} KV tokens: "
-                      f"attention {c1 - c0:.2f} s + sampling {c2 - c1:.2f} s",
-        }
-        result["parity_on_sample"] = {
-            "attn_max_abs_err_bf16_out": float(np.abs(gpu_out - ref_out).max()),
-            "logprob_max_abs_err": float(np.abs(gpu_lp - ref["logprob"])[gpu_tok == ref["tokens"]].max())
-            if mism < len(rows) else None,
-            "token_mismatches": mism,
-            "near_ties_below_1e-5": int((ref["gap"] < 1e-5).sum()),
-        }
-    batch.close()
+    if args.config is None:
+        # the other single-GPU configurations, each a whole run of its own (same fields)
+        result["per_config"] = {}
+        for name in ("c3", "c2", "c4"):
+            k = C4_STEPS if name == "c4" else K
+            say(f"bench: {name}, {k} steps")
+            result["per_config"][name] = run_config(name, k, W, args, torch, rb, wl)
     print(json.dumps(result), flush=True)
 
 
