@@ -1,60 +1,123 @@
-"""Parity at the full sizes of the benchmark configurations, in the launch configuration bench.py times (needs an
-MI355X): one decode step of c2, c3 and c5 through the harness; attention on sampled rows (the
-shortest, the longest, and rows spread over the batch), sampling on sampled rows."""
+"""Parity at the full sizes of the benchmark configurations, in the launch configuration bench.py
+times (needs an MI355X): one decode step of c2, c3 and c5 through the harness with EVERY row's
+attention output, token and log-prob compared with the oracle, and config 4 (256 slots, 200 steps
+of continuous refill) with sampling parity at every step and attention parity on a schedule."""
 import numpy as np
 import pytest
 import torch
 
 import oracle
+from paper_2510_11345_amd import binding as rb
 from paper_2510_11345_amd import workloads as wl
-from paper_2510_11345_amd.harness import DecodeBatch
+from paper_2510_11345_amd.harness import DecodeBatch, RefillLoop
 from gpu_helpers import say
 
 pytestmark = pytest.mark.gpu
 
 
+def check_sampling(tok, lp, ref, logits_rows, vocab, where=""):
+    """The bar on tokens and log-probs for the rows of `ref`: identical tokens unless the oracle's
+    top-two gap is below 1e-5 or a token lies in the top-p boundary band; log-probs within 1e-3
+    wherever the tokens agree.  Returns (near-tie mismatches, boundary-band mismatches)."""
+    same = tok == ref["tokens"]
+    assert ((tok >= 0) & (tok < vocab)).all(), where
+    if same.any():
+        assert np.abs(lp - ref["logprob"])[same].max() <= 1e-3, where
+    ties = band = 0
+    for i in np.flatnonzero(~same):
+        x = logits_rows(int(i))
+        in_band = lambda t: ref["x_cut_plus"][i] <= x[t] < ref["x_cut_minus"][i]
+        if ref["gap"][i] < 1e-5:
+            ties += 1
+        else:
+            assert in_band(tok[i]) or in_band(ref["tokens"][i]), (where, int(i), int(tok[i]), int(ref["tokens"][i]))
+            band += 1
+    return ties, band
+
+
+@pytest.mark.timeout(600)
 @pytest.mark.parametrize("name", ["c2", "c3", "c5"])
-def test_full_size_step_matches_oracle_on_sampled_rows(name):
+def test_full_size_step_matches_oracle_on_every_row(name, capsys):
     cfg = wl.CONFIGS[name]
     lengths = wl.draw_lengths(cfg.lengths, cfg.batch, 0, cfg.max_len).astype(np.int64)
-    say(f"  full-size case {name}: B={cfg.batch} sum L={int(lengths.sum())} max L={int(lengths.max())}")
+    with capsys.disabled():
+        say(f"\n  full-size case {name}: B={cfg.batch} sum L={int(lengths.sum())} max L={int(lengths.max())}")
     batch = DecodeBatch(cfg, 0, lengths - 1, headroom_tokens=4)
     logits = wl.make_logits(cfg, 0, "cuda")
     batch.step(logits, 0)
     torch.cuda.synchronize()
     assert np.array_equal(batch.lengths, lengths)
-    order = np.argsort(lengths)
-    rows = sorted(set([int(order[0]), int(order[1]), int(order[-1]), int(order[-2]), int(order[len(order) // 2])] +
-                      [int(r) for r in np.linspace(0, cfg.batch - 1, 7).round()]))
-    q, k, v, table, lens = batch.gather_rows(rows)
-    want = oracle.decode_attn(q, k, v, table, lens, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim,
-                              cfg.page_size)
-    got = batch.out[torch.tensor(rows, device="cuda")].double().cpu().numpy()
-    err = np.abs(got - want).max()
-    say(f"    attention on {len(rows)} rows (lengths {sorted(int(x) for x in lens)[:3]}..{int(lens.max())}): "
-        f"max abs err {err:.3e} (bf16 out)")
-    assert np.isfinite(got).all() and err <= 2e-2
-    # every finite-length row must have produced output (no row silently skipped by the dealing)
-    assert bool((batch.out.float().abs().sum(dim=(1, 2)) > 0).all())
-
-    srows = rows[:8]
-    ref = oracle.sample_logprob(wl.logits_numpy(logits[torch.tensor(srows, device="cuda")]), cfg.temperature,
-                                cfg.top_p, 0, 0, row_ids=srows)
-    tok = batch.tokens.cpu().numpy()[srows]
-    lp = batch.logprob.double().cpu().numpy()[srows]
-    x = logits[torch.tensor(srows, device="cuda")].float().cpu().numpy()
-    ties = band = 0
-    for i in range(len(srows)):
-        if tok[i] == ref["tokens"][i]:
-            assert abs(lp[i] - ref["logprob"][i]) <= 1e-3
-        elif ref["gap"][i] < 1e-5:
-            ties += 1
-        else:
-            in_band = lambda t: ref["x_cut_plus"][i] <= x[i, t] < ref["x_cut_minus"][i]
-            assert in_band(tok[i]) or in_band(ref["tokens"][i]), (srows[i], tok[i], ref["tokens"][i])
-            band += 1
-    say(f"    sampling on {len(srows)} rows: near-tie mismatches {ties}, boundary-band mismatches {band}")
-    # all tokens in range for the whole batch
-    all_tok = batch.tokens.cpu().numpy()
-    assert ((all_tok >= 0) & (all_tok < cfg.vocab)).all()
+    rb.roll_decode_attn_workspace_check(batch._ws)
+    got = batch.out.double().cpu().numpy()
+    assert np.isfinite(got).all()
+    # attention, every row, in slices so that the host copy of the pages stays small
+    worst = 0.0
+    for first in range(0, cfg.batch, 32):
+        rows = list(range(first, min(first + 32, cfg.batch)))
+        q, k, v, table, lens = batch.gather_rows(rows)
+        want = oracle.decode_attn(q, k, v, table, lens, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim,
+                                  cfg.page_size)
+        err = float(np.abs(got[rows] - want).max())
+        worst = max(worst, err)
+        assert err <= 2e-2, (name, first, err)
+        with capsys.disabled():
+            say(f"    attention rows {first}..{rows[-1]}: max abs err {err:.3e} (bf16 out)")
+    # sampling, every row
+    ref = oracle.sample_logprob(wl.logits_numpy(logits), cfg.temperature, cfg.top_p, 0, 0)
+    tok = batch.tokens.cpu().numpy()
+    lp = batch.logprob.double().cpu().numpy()
+    ties, band = check_sampling(tok, lp, ref, lambda i: logits[i].float().cpu().numpy(), cfg.vocab, name)
+    with capsys.disabled():
+        say(f"    {name}: attention on all {cfg.batch} rows max abs err {worst:.3e}; sampling on all rows: "
+            f"near-tie mismatches {ties}, boundary-band mismatches {band}")
     batch.close()
+
+
+@pytest.mark.timeout(900)
+def test_config4_full_size_refill_loop(capsys):
+    # 256 slots, 200 decode steps, finish by pre-drawn target length, release + refill from the prompt
+    # queue with chunked prefill; fresh logits every step.  Every step: sampling parity on all rows,
+    # allocator conservation, device lengths.  Attention parity on all rows at steps 0, 199 and
+    # every 20th; right after a refill on the refilled rows and 15 rows spread over the batch.
+    cfg = wl.CONFIGS["c4"]
+    steps, seed = 200, 0
+    plan = wl.draw_refill_plan(cfg.batch, cfg.batch + 4 * steps + 64, seed)
+    loop = RefillLoop(cfg, plan, seed, max_len=cfg.max_len + steps + 2)
+    b = loop.batch
+    total_pages = b.num_pages
+    spread = [int(r) for r in np.linspace(0, cfg.batch - 1, 15).round()]
+    checked_all = checked_some = ties = band = 0
+    worst = 0.0
+    for step in range(steps):
+        logits = wl.make_logits(cfg, seed, "cuda", salt=1000 + step)
+        refilled = loop.step(logits, step)
+        torch.cuda.synchronize()
+        assert b.pages_held() + rb.roll_kv_free_pages(b.pool) == total_pages, step
+        assert np.array_equal(b.seq_lens.cpu().numpy(), b.lengths.astype(np.int32)), step
+        ref = oracle.sample_logprob(wl.logits_numpy(logits), cfg.temperature, cfg.top_p, seed, step)
+        t, bd = check_sampling(b.tokens.cpu().numpy(), b.logprob.double().cpu().numpy(), ref,
+                               lambda i: logits[i].float().cpu().numpy(), cfg.vocab, f"step {step}")
+        ties, band = ties + t, band + bd
+        everything = step in (0, steps - 1) or step % 20 == 0
+        rows = list(range(cfg.batch)) if everything else (sorted(set(refilled + spread)) if refilled else [])
+        for first in range(0, len(rows), 64):
+            part = rows[first:first + 64]
+            q, k, v, table, lens = b.gather_rows(part)
+            want = oracle.decode_attn(q, k, v, table, lens, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim,
+                                      cfg.page_size)
+            err = float(np.abs(b.out[torch.tensor(part, device="cuda")].double().cpu().numpy() - want).max())
+            worst = max(worst, err)
+            assert err <= 2e-2, (step, first, err)
+        checked_all += everything
+        checked_some += bool(rows) and not everything
+        if step % 10 == 0 or step == steps - 1:
+            with capsys.disabled():
+                say(f"    c4 step {step}: refills so far {loop.refills}, sum L {b.total_tokens()}, "
+                    f"attention max abs err so far {worst:.3e}")
+    rb.roll_decode_attn_workspace_check(b._ws)
+    with capsys.disabled():
+        say(f"  c4 full size: {steps} steps, {loop.refills} refills, attention checked on all rows at {checked_all} "
+            f"steps and on the refilled + 15 spread rows at {checked_some}, near-tie mismatches {ties}, "
+            f"boundary-band mismatches {band}, {rb.roll_kv_fused_steps(b.pool)} steps in one launch")
+    assert loop.refills >= 20 and checked_some >= 10
+    loop.close()
