@@ -302,6 +302,25 @@ int roll_decode_attn(const void* q, const void* k_pages, const void* v_pages,
                      void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * roll_decode_attn for callers that cannot allocate device memory or bring a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, results and kernel as roll_decode_attn; the
+ * scratch for the pieces of cut rows is a buffer inside the library's device
+ * image (48 MiB, held on every GPU the library runs on until the process ends).
+ * The call allocates nothing and frees nothing.  A shape whose scratch does not
+ * fit (it grows with num_kv_heads * num_q_heads / num_kv_heads * head_dim; the
+ * 7B- and 32B-class shapes of this header's benchmarks need 15 and 34 MiB) is
+ * refused with ROLL_ERR_WORKSPACE before anything is launched.  The first call
+ * on a device also enqueues, on stream and ahead of the attention kernel, the
+ * small kernel that prepares the buffer.  All calls on one GPU share that
+ * GPU's buffer: calls that overlap on one GPU race, so order them (one stream,
+ * or events between streams).
+ */
+int roll_decode_attn_static(const void* q, const void* k_pages, const void* v_pages,
+                            const int32_t* page_table, const int32_t* seq_lens,
+                            void* out, const roll_attn_desc* desc, void* stream);
+
+/*
  * One launch for the memory-side of a decode step (Section 4.2, the engine's
  * step over the whole running batch): what roll_kv_commit_append followed by
  * roll_decode_attn on the pool's own device tables would do.  Publishes the

@@ -28,7 +28,7 @@ EXPORTS = [
     "roll_kv_fused_steps",
     "roll_kv_append_tokens",
     "roll_decode_attn_workspace_bytes", "roll_decode_attn_workspace_init", "roll_decode_attn_workspace_check",
-    "roll_decode_attn", "roll_decode_attn_ranges",
+    "roll_decode_attn", "roll_decode_attn_static", "roll_decode_attn_ranges",
     "roll_decode_step_attn", "roll_prefill_attn",
     "roll_sample_logprob_workspace_bytes", "roll_sample_logprob", "roll_policy_loss",
     "roll_sample_buffer_create", "roll_sample_buffer_destroy", "roll_sample_buffer_begin",
@@ -113,6 +113,7 @@ def lib():
             [C.c_int32] * 5 + [C.c_int64, C.c_void_p]
         L.roll_decode_attn_workspace_init.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
         L.roll_decode_attn_workspace_check.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
+        L.roll_decode_attn_static.argtypes = [C.c_void_p] * 6 + [C.POINTER(AttnDesc), C.c_void_p]
         L.roll_prof_attn_events.argtypes = [C.c_void_p, C.c_void_p]
         L.roll_prof_kv_read_probe.argtypes = [C.c_void_p] * 4 + [C.POINTER(AttnDesc), C.c_void_p, C.c_size_t,
                                               C.POINTER(C.c_int64), C.c_void_p]
@@ -354,6 +355,15 @@ def roll_decode_attn_workspace_check(workspace: torch.Tensor) -> None:
     launch and holds no counters left over from an unfinished one."""
     _check(lib().roll_decode_attn_workspace_check(_dev(workspace), workspace.numel() * workspace.element_size(),
                                                   _stream()))
+
+
+def roll_decode_attn_static(q, k_pages, v_pages, page_table, seq_lens, out, desc: AttnDesc) -> None:
+    """roll_decode_attn on the library's own static scratch (allocates nothing)."""
+    if page_stride(k_pages, v_pages) != desc.page_stride:
+        raise ValueError("the pools' page stride differs from the desc's")
+    _check(lib().roll_decode_attn_static(
+        _dev(q, torch.bfloat16), _pool(k_pages), _pool(v_pages),
+        _dev(page_table, torch.int32), _dev(seq_lens, torch.int32), _dev(out), C.byref(desc), _stream()))
 
 
 def roll_decode_step_attn(pool: "KvPool", k_new, v_new, q, k_pages, v_pages, out, desc: AttnDesc,

@@ -1019,3 +1019,67 @@ extern "C" int roll_decode_step_attn(roll_kv_pool* pool, const void* k_new, cons
     roll::finish_fused_step(pool);
     return ROLL_OK;
 }
+
+// ---------------------------------------------------------------------------------------------
+// roll_decode_attn_static: the plain attention launch on scratch that is part of the library's
+// own device image, for callers that cannot allocate (HIP graph capture, serving loops and
+// harnesses that forbid hipMalloc).  Each GPU the library runs on holds its own copy of the array
+// until the process ends.  In host code the array's name is only a stand-in: its address on the
+// current device comes from hipGetSymbolAddress, once per device, and only that pointer is ever
+// handed to a kernel.
+// ---------------------------------------------------------------------------------------------
+constexpr size_t kStaticScratchBytes = (size_t)48 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+
+struct StaticScratch {
+    void* ptr = nullptr;    // address of `scratch` on this device
+    bool prepared = false;  // its header has been zeroed and tagged by a kernel enqueued earlier
+};
+StaticScratch g_static[kMaxDevices];
+std::mutex g_static_mu;
+
+// The scratch of a launch from the static array, laid out for exactly the waves the launch uses.
+struct StaticWorkspace {
+    const roll_attn_desc* d;
+    hipStream_t stream;
+    int operator()(int32_t* W, Workspace* ws) const {
+        int dev = 0;
+        int rc = persistent_waves(W, &dev);
+        if (rc != ROLL_OK) return rc;
+        const Workspace need = carve(nullptr, d->num_kv_heads, d->num_q_heads / d->num_kv_heads, d->head_dim, *W);
+        if (need.bytes > kStaticScratchBytes)
+            return roll::fail(ROLL_ERR_WORKSPACE,
+                              "this shape needs %zu bytes of scratch, the static buffer holds %zu: use roll_decode_attn "
+                              "with a workspace of the caller's", need.bytes, kStaticScratchBytes);
+        std::lock_guard<std::mutex> lock(g_static_mu);
+        StaticScratch& st = g_static[dev];
+        if (!st.ptr) {
+            void* p = nullptr;
+            ROLL_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+            if (!p || !roll::aligned(p, 256)) return roll::fail(ROLL_ERR_HIP, "static scratch has no usable device address");
+            st.ptr = p;
+        }
+        if (!st.prepared) {
+            // a fill kernel, not hipMemsetAsync: the call may be recorded into a graph
+            const size_t words = need.header_bytes / 4;
+            prepare_header<<<(unsigned)((words + 255) / 256), 256, 0, stream>>>((uint32_t*)st.ptr, words);
+            ROLL_HIP_CHECK(hipGetLastError());
+            st.prepared = true;
+        }
+        *ws = carve(st.ptr, d->num_kv_heads, d->num_q_heads / d->num_kv_heads, d->head_dim, *W);
+        return ROLL_OK;
+    }
+};
+
+}  // namespace
+
+extern "C" int roll_decode_attn_static(const void* q, const void* k_pages, const void* v_pages,
+                                       const int32_t* page_table, const int32_t* seq_lens, void* out,
+                                       const roll_attn_desc* d, void* stream_v) {
+    int rc = validate(d);
+    if (rc != ROLL_OK) return rc;
+    return launch_attn(q, k_pages, v_pages, page_table, seq_lens, out, d, StaticWorkspace{d, (hipStream_t)stream_v},
+                       (hipStream_t)stream_v, nullptr);
+}

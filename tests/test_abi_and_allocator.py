@@ -253,9 +253,13 @@ def test_step_count_of_a_batch_must_fit_32_bits():
     assert L.roll_decode_attn(16, 16, 16, 16, 16, 16, C.byref(big), 256, 1 << 30, None) == -5
 
 
-def test_workspace_check_and_decode_step_reject_bad_arguments_on_the_host():
+def test_static_entry_point_and_workspace_check_reject_bad_arguments_on_the_host():
     L = rb.lib()
     good = rb.AttnDesc(4, 8, 2, 64, 16, 8, 32, rb.ROLL_BF16, 0.0, 0)
+    bad = rb.AttnDesc(4, 8, 2, 96, 16, 8, 32, rb.ROLL_BF16, 0.0, 0)
+    assert L.roll_decode_attn_static(16, 16, 16, 16, 16, 16, C.byref(bad), None) == -1
+    assert L.roll_decode_attn_static(None, 16, 16, 16, 16, 16, C.byref(good), None) == -1
+    assert L.roll_decode_attn_static(8, 16, 16, 16, 16, 16, C.byref(good), None) == -1
     assert L.roll_decode_attn_workspace_check(None, 1 << 30, None) == -6
     assert L.roll_decode_attn_workspace_check(128, 1 << 30, None) == -6
     assert L.roll_decode_attn_workspace_check(256, 8, None) == -6
