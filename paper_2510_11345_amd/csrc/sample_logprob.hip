@@ -35,6 +35,7 @@
 // is two 32x32->64 products (v_mad_u64_u32) and two three-input xors.
 #include <cfloat>
 #include <cmath>
+#include <type_traits>
 
 #include "common.h"
 
@@ -651,6 +652,223 @@ __device__ bool window_level(const T* __restrict__ row, const SampleParams& p, f
     return true;
 }
 
+// ---- bf16 rows: the cut from a count of every value -----------------------------------------
+// A bf16 logit is one of 65536 bit patterns, and all entries of one value have one weight, so
+// the cut needs no masses while the row streams by: ONE sweep counts the entries of every value
+// (two 16-bit counters per LDS word, 128 KiB), and needs neither the row max nor an exponential
+// per entry.  The max is then the highest value with a count, a value's mass is
+// count * fixed40(exp(z - max)) (the very integers the histogram route adds up entry by entry, so
+// both routes find the same cut), and the values are walked in descending order until the
+// running mass reaches ceil(top_p * total): by chunks of 128 values, then inside the chunk that
+// crosses.  Chunks without entries (most of the 512) cost a load and a vote.
+// A 16-bit counter that overflows (65536 equal entries) is noticed, because the counts no longer
+// add up to the number of entries counted, and the row takes the histogram route instead.
+// Entries of -inf are not counted (a heavily masked row would overflow their counter).
+constexpr int kCountWords = 32768;
+constexpr int kCountChunks = kCountWords / 64;  // 512 chunks of 64 words = 128 values
+static_assert(kCountChunks <= kThreads && kCountChunks % kWavesPerBlock == 0, "one thread per chunk in the scan");
+
+// The value with 16-bit order key k (the key of order_key() without its lower 16 bits).
+__device__ __forceinline__ float key16_value(uint32_t k) {
+    const uint32_t b = (k & 0x8000u) ? (k ^ 0x8000u) : (~k & 0xFFFFu);
+    return __uint_as_float(b << 16);
+}
+
+__device__ __forceinline__ void count_value(uint32_t* cnt, uint32_t f, uint32_t& counted) {
+    if (f == 0xFF800000u) return;                                   // -inf: no mass, not counted
+    const uint32_t key = f ^ ((uint32_t)((int32_t)f >> 31) | 0x80000000u);   // order key, upper 16 bits used
+    atomicAdd(&cnt[key >> 17], 1u + ((key >> 16) & 1u) * 0xFFFFu);   // low or high 16-bit counter
+    ++counted;
+}
+
+struct CountCut {
+    enum { kNoMass = 0, kFound = 1, kOverflow = 2 };
+};
+
+// Returns CountCut::kFound with *xmax_out, *xcut_out, *kept_out (the kept set's mass relative to
+// the max, 2^-40 fixed point; and *raw_lse_out with RAW) set,
+// kNoMass for a row without a finite entry, kOverflow if a counter overflowed (nothing set).
+// The same value in every thread.  s_u64: kWavesPerBlock + 2 words; s_u32: 2 * kWavesPerBlock + 2;
+// s_f64: kWavesPerBlock; s_chunk: kCountChunks.
+template <bool RAW>
+__device__ int count_cut_bf16(const uint16_t* __restrict__ row, const SampleParams& p, uint32_t* cnt,
+                              unsigned long long* s_u64, uint32_t* s_u32, double* s_f64,
+                              unsigned long long* s_chunk, Select* s_sel, float* xmax_out,
+                              float* xcut_out, unsigned long long* kept_out, double* raw_lse_out) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    {
+        uint4* z = (uint4*)cnt;
+        for (int i = tid; i < kCountWords / 4; i += kThreads) z[i] = make_uint4(0u, 0u, 0u, 0u);
+    }
+    __syncthreads();
+    // ---- the sweep: one LDS atomic per entry
+    uint32_t counted = 0;
+    {
+        const int32_t nvec = p.V / 8;
+        const uint4* __restrict__ row16 = (const uint4*)row;
+        const uint4 none = make_uint4(0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u);
+        int32_t vi = tid;
+        uint4 cur = vi < nvec ? row16[vi] : none;
+        for (int32_t base = 0; base < nvec; base += kThreads) {
+            const int32_t vn = vi + kThreads;
+            const uint4 nxt = vn < nvec ? row16[vn] : none;
+            const uint32_t w[4] = {cur.x, cur.y, cur.z, cur.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                count_value(cnt, w[j] << 16, counted);
+                count_value(cnt, w[j] & 0xFFFF0000u, counted);
+            }
+            cur = nxt;
+            vi = vn;
+        }
+        const int32_t i = nvec * 8 + tid;
+        if (i < p.V) count_value(cnt, (uint32_t)row[i] << 16, counted);
+    }
+    __syncthreads();
+    // The 65536 values in descending order are 512 chunks of 128 (64 words, the high half of a
+    // word before its low half; lane l of the wave that handles chunk c holds word
+    // kCountWords - 1 - 64 c - l).  Chunk c is handled by wave c % 16: the few chunks that hold
+    // entries lie next to each other, and this way every wave gets some of them.
+    constexpr int kIters = kCountChunks / kWavesPerBlock;
+    // ---- pass 0: entries counted, which of the wave's chunks hold entries at all (a bit per
+    // iteration, the same in every lane) and, from the highest of those, the highest value that
+    // has any
+    uint32_t busy = 0;
+    {
+        uint32_t in_bins = 0;
+#pragma unroll
+        for (int i = 0; i < kIters; ++i) {
+            const uint32_t c = cnt[kCountWords - 1 - 64 * (kWavesPerBlock * i + wave) - lane];
+            in_bins = __builtin_amdgcn_sad_u16(c, 0u, in_bins);  // + low half + high half
+            busy |= __any(c != 0u) ? 1u << i : 0u;
+        }
+        busy = __builtin_amdgcn_readfirstlane(busy);
+        uint32_t top = 0;
+        if (busy != 0) {
+            const uint32_t word = kCountWords - 1 - 64 * (kWavesPerBlock * __builtin_ctz(busy) + wave) - lane;
+            const uint32_t c = cnt[word];
+            top = c >> 16 ? 2u * word + 1u : (c ? 2u * word : 0u);
+        }
+#pragma unroll
+        for (int mask = 1; mask < 64; mask <<= 1) {
+            in_bins += __shfl_xor(in_bins, mask);
+            counted += __shfl_xor(counted, mask);
+            const uint32_t o = __shfl_xor(top, mask);
+            top = top > o ? top : o;
+        }
+        if (lane == 0) {
+            s_u32[wave] = in_bins;
+            s_u32[kWavesPerBlock + wave] = top;
+            s_u64[wave] = counted;
+        }
+        if (tid < kCountChunks) s_chunk[tid] = 0ull;
+    }
+    __syncthreads();
+    uint32_t in_bins = 0, top = 0;
+    unsigned long long counted_all = 0;
+    for (int w = 0; w < kWavesPerBlock; ++w) {
+        in_bins += s_u32[w];
+        top = top > s_u32[kWavesPerBlock + w] ? top : s_u32[kWavesPerBlock + w];
+        counted_all += s_u64[w];
+    }
+    __syncthreads();
+    if ((unsigned long long)in_bins != counted_all) return CountCut::kOverflow;
+    if (counted_all == 0) return CountCut::kNoMass;
+    const float xmax = key16_value(top);
+    const float nk = ref_offset(xmax, p.k2);
+    // mass of one value: count * fixed40(exp(z - max))
+    auto mass_of = [&](uint32_t count, uint32_t key) -> unsigned long long {
+        return count ? count * to_fixed40(__builtin_amdgcn_exp2f(fmaf(key16_value(key), p.k2, nk))) : 0ull;
+    };
+    // ---- pass A: the mass of every chunk that holds entries
+    {
+        double raw = 0.0;
+#pragma unroll 1
+        for (uint32_t left = busy; left != 0; left &= left - 1) {
+            const int32_t chunk = kWavesPerBlock * (__builtin_ctz(left)) + wave;
+            const uint32_t word = kCountWords - 1 - 64 * chunk - lane;
+            const uint32_t c = cnt[word];
+            unsigned long long mine = mass_of(c >> 16, 2u * word + 1u) + mass_of(c & 0xFFFFu, 2u * word);
+#pragma unroll
+            for (int mask = 1; mask < 64; mask <<= 1) mine += shfl_xor_u64(mine, mask);
+            if (RAW) {
+                const uint32_t c_hi = c >> 16, c_lo = c & 0xFFFFu;
+                raw += (c_hi ? (double)c_hi * (double)__builtin_amdgcn_exp2f((key16_value(2u * word + 1u) - xmax) * kLog2e) : 0.0) +
+                       (c_lo ? (double)c_lo * (double)__builtin_amdgcn_exp2f((key16_value(2u * word) - xmax) * kLog2e) : 0.0);
+            }
+            if (lane == 0) s_chunk[chunk] = mine;
+        }
+        if (RAW) {
+#pragma unroll
+            for (int mask = 1; mask < 64; mask <<= 1) raw += shfl_xor_f64(raw, mask);
+            if (lane == 0) s_f64[wave] = raw;
+        }
+    }
+    __syncthreads();
+    // ---- the chunk at which the running mass reaches the target: the first eight waves scan
+    // one chunk per thread
+    constexpr int kScanWaves = kCountChunks / 64;
+    unsigned long long incl = tid < kCountChunks ? s_chunk[tid] : 0ull;
+    const unsigned long long chunk_mass = incl;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const unsigned long long v = shfl_up_u64(incl, d);
+        if (lane >= d) incl += v;
+    }
+    if (lane == 63 && wave < kScanWaves) s_u64[wave] = incl;
+    __syncthreads();
+    unsigned long long total = 0, base = 0;
+    for (int w = 0; w < kScanWaves; ++w) {
+        if (w == wave) base = total;
+        total += s_u64[w];
+    }
+    const unsigned long long target = top_p_target(p.top_p, total);
+    if (wave < kScanWaves && base + incl - chunk_mass < target && base + incl >= target) {
+        s_sel->prefix = (uint32_t)tid;                // the chunk
+        s_sel->above = base + incl - chunk_mass;      // mass of all chunks above it
+    }
+    __syncthreads();
+    // ---- pass B: the wave of that chunk finds the value inside it
+    const int32_t cross = (int32_t)s_sel->prefix;
+    if (wave == (cross & (kWavesPerBlock - 1))) {
+        const uint32_t word = kCountWords - 1 - 64 * cross - lane;
+        const uint32_t c = cnt[word];
+        const unsigned long long hi = mass_of(c >> 16, 2u * word + 1u), lo = mass_of(c & 0xFFFFu, 2u * word);
+        const unsigned long long m = hi + lo;
+        unsigned long long run = m;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const unsigned long long v = shfl_up_u64(run, d);
+            if (lane >= d) run += v;
+        }
+        run += s_sel->above;                             // mass of this lane's values and all higher ones
+        const unsigned long long before = run - m;
+        if (before < target && run >= target) {
+            const bool in_hi = before + hi >= target;    // hi > 0 then, since before < target
+            const uint32_t kcut = in_hi ? 2u * word + 1u : 2u * word;
+            unsigned long long kept = in_hi ? before + hi : run;
+            // -0 and +0 are one value with two bit patterns, -0 (key 0x7FFF) right below +0 (key
+            // 0x8000): a cut at +0 keeps the entries of -0 too.  (A cut at -0 keeps +0 anyway.)
+            if (kcut == 0x8000u) kept += mass_of(cnt[0x3FFF] >> 16, 0x7FFFu);
+            s_u32[0] = kcut;
+            s_u64[kWavesPerBlock] = kept;
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        *xmax_out = xmax;
+        *xcut_out = key16_value(s_u32[0]);
+        *kept_out = s_u64[kWavesPerBlock];
+        if (RAW) {
+            double sr = 0.0;
+            for (int w = 0; w < kWavesPerBlock; ++w) sr += s_f64[w];
+            *raw_lse_out = (double)xmax + log(sr);
+        }
+    }
+    __syncthreads();
+    return CountCut::kFound;
+}
+
 // RAW: also accumulate sum exp(x - max) at temperature 1 for raw_logprob_out (needed only when
 // the sampled distribution differs from the raw one).
 template <typename T, bool TOPP, bool RAW>
@@ -659,15 +877,22 @@ __global__ __launch_bounds__(kThreads) void sample_rows(const T* __restrict__ lo
                                                          int32_t* __restrict__ tokens_out,
                                                          float* __restrict__ logprob_out,
                                                          float* __restrict__ raw_logprob_out, SampleParams p) {
-    __shared__ __align__(16) unsigned long long s_hist[TOPP ? kHistSlots : 1];
+    // bf16 rows with top-p count every value first (count_cut_bf16): 128 KiB of counters, which
+    // the histogram route and the race's queues then reuse.
+    constexpr bool kCounts = TOPP && std::is_same<T, uint16_t>::value;
+    constexpr int kBigWords = kCounts ? kCountWords / 2 : (TOPP ? kHistSlots : 1);
+    __shared__ __align__(16) unsigned long long s_hist[kBigWords];
     __shared__ unsigned long long s_tot[TOPP ? kBins : 1];
-    __shared__ unsigned long long s_wave[kWavesPerBlock];
+    __shared__ unsigned long long s_wave[kWavesPerBlock + 2];
+    __shared__ uint32_t s_u32[2 * kWavesPerBlock + 2];
+    __shared__ unsigned long long s_chunk[kCounts ? kCountChunks : 1];
     __shared__ Select s_sel;
     __shared__ float s_m[kWavesPerBlock];
     __shared__ double s_s[kWavesPerBlock];
     __shared__ double s_best[kWavesPerBlock];
     __shared__ int32_t s_besti[kWavesPerBlock];
     __shared__ float s_xcut;
+    __shared__ unsigned long long s_kept;  // top-p: mass of the kept set relative to the row max, 2^-40 fixed point
     __shared__ double s_lse;
     __shared__ double s_sraw[kWavesPerBlock];
     __shared__ double s_raw_lse;
@@ -681,24 +906,18 @@ __global__ __launch_bounds__(kThreads) void sample_rows(const T* __restrict__ lo
 
     if (threadIdx.x == 0) s_thr_key = order_key(-INFINITY);
     __syncthreads();
-    Race<true, RAW, false> race{p, row_id, -INFINITY, -FLT_MAX};
-    race.block_thr_key = &s_thr_key;
-    race.set_ref(-FLT_MAX);
-    MaxOnly<RAW> mo;
-    if (!TOPP) sweep<T>(row, p.V, race);  // one sweep: online log-sum-exp and the race together
-    else sweep<T>(row, p.V, mo);
 
-    // Block max of the raw logits and, for top_p == 1, the log-sum-exp in log2 units of the
-    // logits times k2: a lane's sum is relative to 2^(-nk) of its own reference, the block's to
-    // that of the row max, and the sampled token's log-prob is taken with the same k2, so the
-    // rounding of k2 and of nk cancels (a row with all its mass on one entry gives 0).
-    {
-        const float mine = TOPP ? mo.xm : race.xref;
+    // Block max of the raw logits from the threads' maxima and, for top_p == 1, the log-sum-exp in
+    // log2 units of the logits times k2: a lane's sum is relative to 2^(-nk) of its own reference,
+    // the block's to that of the row max, and the sampled token's log-prob is taken with the same
+    // k2, so the rounding of k2 and of nk cancels (a row with all its mass on one entry gives 0).
+    // Leaves the max in s_m[0], the log-sum-exp in s_lse and the raw one in s_raw_lse.
+    auto reduce_max_and_sums = [&](float mine, float s_thread, float nk_thread, float s_raw_thread) {
         float m = mine;
 #pragma unroll
         for (int mask = 1; mask < 64; mask <<= 1) m = fmaxf(m, __shfl_xor(m, mask));
-        double s = TOPP ? 0.0 : (double)race.s * (double)__builtin_amdgcn_exp2f(ref_offset(m, p.k2) - race.nk);
-        double sr = (double)(TOPP ? mo.s_raw : race.s_raw) * (double)__builtin_amdgcn_exp2f((mine - m) * kLog2e);
+        double s = TOPP ? 0.0 : (double)s_thread * (double)__builtin_amdgcn_exp2f(ref_offset(m, p.k2) - nk_thread);
+        double sr = (double)s_raw_thread * (double)__builtin_amdgcn_exp2f((mine - m) * kLog2e);
 #pragma unroll
         for (int mask = 1; mask < 64; mask <<= 1) {
             s += shfl_xor_f64(s, mask);
@@ -721,52 +940,75 @@ __global__ __launch_bounds__(kThreads) void sample_rows(const T* __restrict__ lo
             s_sel.above = 0;
         }
         __syncthreads();
-    }
+    };
 
+    Race<true, RAW, false> race{p, row_id, -INFINITY, -FLT_MAX};
     Race<false, false, true> race_kept{p, row_id, -INFINITY, 0.f};
-    if (TOPP) {
-        const float xM = s_m[0];
-        const float nkM = ref_offset(xM, p.k2);
-        constexpr int kKeyBits = Elem<T>::kKeyBits;
-        unsigned long long target = 0;
-        // The upper 16 key bits from the window sweep (and a sweep for the second byte when the cut
-        // lies below the window), then the lower 16 of an fp32 key.  A row without mass (no finite
-        // entry) has no cut and no race: the result below is then "no token".
-        const bool has_mass = window_level<T>(row, p, xM, nkM, s_hist, s_tot, s_wave, &s_sel, target);
+    if constexpr (!TOPP) {
+        race.block_thr_key = &s_thr_key;
+        race.set_ref(-FLT_MAX);
+        sweep<T>(row, p.V, race);  // one sweep: online log-sum-exp and the race together
+        reduce_max_and_sums(race.xref, race.s, race.nk, race.s_raw);
+    } else {
+        // The cut: s_m[0] = row max, s_xcut, s_kept (the kept set's mass; its logarithm is taken at
+        // the end, beside the load of the winner's logit) and s_raw_lse.
+        bool has_mass = false, have_cut = false;
+        if constexpr (kCounts) {
+            const int st = count_cut_bf16<RAW>(row, p, (uint32_t*)s_hist, s_wave, s_u32, s_s, s_chunk, &s_sel, &s_m[0],
+                                               &s_xcut, &s_kept, &s_raw_lse);
+            have_cut = st != CountCut::kOverflow;
+            has_mass = st == CountCut::kFound;
+        }
+        if (!have_cut) {
+            // The histogram route: a sweep for the row max, the upper 16 key bits from the window
+            // sweep (and a sweep for the second byte when the cut lies below the window), then the
+            // lower 16 of an fp32 key.  A row without mass (no finite entry) has no cut and no race:
+            // the result below is then "no token".
+            MaxOnly<RAW> mo;
+            sweep<T>(row, p.V, mo);
+            reduce_max_and_sums(mo.xm, 0.f, 0.f, mo.s_raw);
+            const float xM = s_m[0];
+            const float nkM = ref_offset(xM, p.k2);
+            constexpr int kKeyBits = Elem<T>::kKeyBits;
+            unsigned long long target = 0;
+            has_mass = window_level<T>(row, p, xM, nkM, s_hist, s_tot, s_wave, &s_sel, target);
+            if (has_mass) {
+                if constexpr (kKeyBits == 32) {
+                    // The lower 16 key bits concern only the entries that share the upper 16 with the
+                    // cut, usually a few hundred: they are gathered into LDS in one sweep and the two
+                    // byte-wide levels run over that list.  Rows with more such entries than the list
+                    // holds (many equal logits) take the levels over the whole row.
+                    constexpr int32_t kListCap = (kHistSlots - kBins * kCopies) * 2;  // floats behind the level's bins
+                    float* list = (float*)(s_hist + kBins * kCopies);
+                    if (tid == 0) s_count = 0;
+                    __syncthreads();
+                    GatherPrefix g{s_sel.prefix, list, &s_count, kListCap};
+                    sweep<T>(row, p.V, g);
+                    __syncthreads();
+                    const int32_t n_list = s_count;
+                    const T* src = n_list <= kListCap ? (const T*)list : row;
+                    const int32_t n_src = n_list <= kListCap ? n_list : p.V;
+                    radix_level<T, 8>(src, n_src, p, nkM, s_hist, s_tot, s_wave, &s_sel, target);
+                    radix_level<T, 0>(src, n_src, p, nkM, s_hist, s_tot, s_wave, &s_sel, target);
+                }
+                if (tid == 0) {
+                    // s_sel.prefix is now the key of the cut value (its upper 16 bits for bf16, whose
+                    // lower key bits are all ones for negative values and zero otherwise).  The kept
+                    // mass is everything above the cut plus the cut value's own class.
+                    const uint32_t key = (s_sel.prefix << (32 - kKeyBits)) |
+                                         (kKeyBits == 16 ? ((s_sel.prefix >> 15) ? 0u : 0xFFFFu) : 0u);
+                    s_xcut = key_to_float(key);
+                    s_kept = s_sel.kept;
+                }
+                __syncthreads();
+            }
+        }
         if (has_mass) {
-            if constexpr (kKeyBits == 32) {
-                // The lower 16 key bits concern only the entries that share the upper 16 with the
-                // cut, usually a few hundred: they are gathered into LDS in one sweep and the two
-                // byte-wide levels run over that list.  Rows with more such entries than the list
-                // holds (many equal logits) take the levels over the whole row.
-                constexpr int32_t kListCap = (kHistSlots - kBins * kCopies) * 2;  // floats behind the level's bins
-                float* list = (float*)(s_hist + kBins * kCopies);
-                if (tid == 0) s_count = 0;
-                __syncthreads();
-                GatherPrefix g{s_sel.prefix, list, &s_count, kListCap};
-                sweep<T>(row, p.V, g);
-                __syncthreads();
-                const int32_t n_list = s_count;
-                const T* src = n_list <= kListCap ? (const T*)list : row;
-                const int32_t n_src = n_list <= kListCap ? n_list : p.V;
-                radix_level<T, 8>(src, n_src, p, nkM, s_hist, s_tot, s_wave, &s_sel, target);
-                radix_level<T, 0>(src, n_src, p, nkM, s_hist, s_tot, s_wave, &s_sel, target);
-            }
-            if (tid == 0) {
-                // s_sel.prefix is now the key of the cut value (its upper 16 bits for bf16, whose
-                // lower key bits are all ones for negative values and zero otherwise).  The kept
-                // mass is everything above the cut plus the cut value's own class.
-                const uint32_t key = (s_sel.prefix << (32 - kKeyBits)) |
-                                     (kKeyBits == 16 ? ((s_sel.prefix >> 15) ? 0u : 0xFFFFu) : 0u);
-                s_xcut = key_to_float(key);
-                s_lse = (log2((double)s_sel.kept * 0x1p-40) - (double)nkM) / kLog2ed;
-            }
-            __syncthreads();
             race_kept.block_thr_key = &s_thr_key;  // still -inf: no race has run in this launch
             race_kept.x_cut = s_xcut;
-            race_kept.set_ref(xM);
+            race_kept.set_ref(s_m[0]);
             race_kept.refresh_c();
-            static_assert(kWavesPerBlock * kQueueBytesPerWave <= kHistSlots * 8, "the queues reuse the histogram");
+            static_assert(kWavesPerBlock * kQueueBytesPerWave <= kBigWords * 8, "the queues reuse the histogram");
             CompactRace<Race<false, false, true>> gathered{
                 race_kept, (float*)s_hist + wave * (kQueueCap * 4),
                 (uint32_t*)s_hist + kWavesPerBlock * (kQueueCap * 4) + wave * kQueueCap};
@@ -797,8 +1039,10 @@ __global__ __launch_bounds__(kThreads) void sample_rows(const T* __restrict__ lo
                 if (raw_logprob_out) raw_logprob_out[r] = NAN;
             } else {
                 tokens_out[r] = bi;
-                const double x = (double)Elem<T>::widen(row[bi]);
-                const float lp = (float)(x * (double)p.k2 / kLog2ed - s_lse);
+                const T x_bits = row[bi];
+                const double lse = TOPP ? (log2((double)s_kept * 0x1p-40) - (double)ref_offset(s_m[0], p.k2)) / kLog2ed : s_lse;
+                const double x = (double)Elem<T>::widen(x_bits);
+                const float lp = (float)(x * (double)p.k2 / kLog2ed - lse);
                 logprob_out[r] = lp;
                 // without an extra sum the sampled distribution is the raw one (T = 1, top_p = 1)
                 if (raw_logprob_out) raw_logprob_out[r] = RAW ? (float)(x - s_raw_lse) : lp;

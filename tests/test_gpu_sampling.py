@@ -196,3 +196,34 @@ def test_extreme_temperatures_and_tiny_vocabularies(T):
             full[:, :V] = wl.make_logits(cfg, 77 + V, "cuda")
             for p in (1.0, 0.5, 0.999):
                 compare_sampling(full[:, :V], T, p, 9, 3)
+
+
+def test_bf16_top_p_rows_that_overflow_the_value_counters():
+    # bf16 rows with top-p count the entries of every value in 16-bit counters; a row with 65536
+    # or more equal entries overflows one, is noticed and takes the histogram route, with the same
+    # result.  Rows: one repeated value; 70 000 equal entries among Gaussian ones (as the row max,
+    # as a low value); 40 000 entries of +0 and 40 000 of -0 (one value, two bit patterns); exactly
+    # 65 535 and 65 536 equal entries; a row masked but for 300 entries (-inf is not counted).
+    g = torch.Generator().manual_seed(5)
+    V = 152064
+    base = torch.randn((V,), generator=g) * 2.0
+    perm = torch.randperm(V, generator=g)
+    rows = [torch.full((V,), 0.375)]
+    for value in (9.5, -3.0):
+        r = base.clone()
+        r[perm[:70000]] = value
+        rows.append(r)
+    z = -base.abs() - 0.5
+    z[perm[:40000]] = 0.0
+    z[perm[40000:80000]] = -0.0
+    rows.append(z)
+    for n in (65535, 65536):
+        r = base.clone()
+        r[perm[:n]] = 1.25
+        rows.append(r)
+    masked = torch.full((V,), float("-inf"))
+    masked[perm[:300]] = base[perm[:300]]
+    rows.append(masked)
+    lg = torch.stack(rows).to(torch.bfloat16).contiguous()
+    for T, p in [(1.0, 0.9), (0.7, 0.95), (1.3, 0.3)]:
+        compare_sampling(lg, T, p, seed=77, step=2)
