@@ -473,20 +473,29 @@ typedef struct roll_loss_desc {
     float c;           /* truncation threshold (TIS, TOPR, is_weight_out) */
 } roll_loss_desc;
 
+/* HOST. Bytes of DEVICE workspace roll_policy_loss needs (partial sums of the responses that are
+ * spread over several waves); 0 for a bad desc. */
+size_t roll_policy_loss_workspace_bytes(const roll_loss_desc* desc);
+
 /*
  * All pointers DEVICE.  Tokens of response s are seq_offsets[s] .. seq_offsets[s+1]-1.
  *   logp_theta, logp_old, signal  fp32 [T]; logp_prox fp32 [T] (Decoupled PPO only, else NULL)
- *   seq_offsets    int64 [num_seqs + 1], non-decreasing
+ *   seq_offsets    int64 [num_seqs + 1], non-decreasing, seq_offsets[0] = 0
  *   value_out      fp32 [T] or NULL: the objective per token
  *   grad_out       fp32 [T] or NULL: its derivative with respect to log pi_theta
  *   is_weight_out  fp32 [T] or NULL: min(pi_theta / pi_old, c)
  *   seq_mean_out   fp32 [num_seqs]: (1/|o|) sum_t value (0 for an empty response)
  *   batch_mean_out fp32 [1]: mean of seq_mean_out over the non-empty responses
+ *   workspace      8-byte aligned, >= roll_policy_loss_workspace_bytes; needs no preparation;
+ *                  two calls that share it must be ordered on one stream
+ * Enqueues two kernels on stream.  The batch's tokens are dealt to the waves in equal shares
+ * whatever the lengths of the responses, so a long-tailed batch runs as fast as an even one.
  */
 int roll_policy_loss(const float* logp_theta, const float* logp_old, const float* logp_prox,
                      const float* signal, const int64_t* seq_offsets, float* value_out,
                      float* grad_out, float* is_weight_out, float* seq_mean_out,
-                     float* batch_mean_out, const roll_loss_desc* desc, void* stream);
+                     float* batch_mean_out, const roll_loss_desc* desc,
+                     void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------ */
 /* SampleBuffer with the asynchronous ratio (Section 4.3), HOST only.  */

@@ -31,6 +31,7 @@ EXPORTS = [
     "roll_decode_attn", "roll_decode_attn_static", "roll_decode_attn_ranges",
     "roll_decode_step_attn", "roll_prefill_attn",
     "roll_sample_logprob_workspace_bytes", "roll_sample_logprob", "roll_policy_loss",
+    "roll_policy_loss_workspace_bytes",
     "roll_sample_buffer_create", "roll_sample_buffer_destroy", "roll_sample_buffer_begin",
     "roll_sample_buffer_complete", "roll_sample_buffer_abort", "roll_sample_buffer_resume",
     "roll_sample_buffer_take_batch", "roll_sample_buffer_advance_version", "roll_sample_buffer_version",
@@ -125,7 +126,9 @@ def lib():
         L.roll_sample_logprob.argtypes = [C.c_void_p, C.c_float, C.c_float, C.c_uint64, C.c_uint64,
                                           C.c_void_p, C.c_void_p, C.POINTER(SampleDesc), C.c_void_p,
                                           C.c_size_t, C.c_void_p]
-        L.roll_policy_loss.argtypes = [C.c_void_p] * 10 + [C.POINTER(LossDesc), C.c_void_p]
+        L.roll_policy_loss.argtypes = [C.c_void_p] * 10 + [C.POINTER(LossDesc), C.c_void_p, C.c_size_t, C.c_void_p]
+        L.roll_policy_loss_workspace_bytes.restype = C.c_size_t
+        L.roll_policy_loss_workspace_bytes.argtypes = [C.POINTER(LossDesc)]
         L.roll_sample_buffer_create.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.c_double]
         L.roll_sample_buffer_destroy.argtypes = [C.c_void_p]
         L.roll_sample_buffer_begin.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
@@ -432,14 +435,32 @@ def roll_sample_logprob(logits, temperature, top_p, philox_seed, step, tokens_ou
 # ----------------------------------------------------------------------------
 # consumer of the log-probs
 # ----------------------------------------------------------------------------
+_loss_workspaces = {}
+
+
+def roll_policy_loss_workspace_bytes(num_seqs: int) -> int:
+    desc = LossDesc(0, num_seqs, 0.2, 0.2, 5.0)
+    return lib().roll_policy_loss_workspace_bytes(C.byref(desc))
+
+
 def roll_policy_loss(kind, logp_theta, logp_old, logp_prox, signal, seq_offsets, value_out, grad_out,
-                     is_weight_out, seq_mean_out, batch_mean_out, eps_low=0.2, eps_high=0.2, c=5.0) -> None:
+                     is_weight_out, seq_mean_out, batch_mean_out, eps_low=0.2, eps_high=0.2, c=5.0,
+                     workspace: Optional[torch.Tensor] = None) -> None:
+    """workspace None: one buffer per device is kept and reused (calls are then ordered on the
+    current stream by the caller, as any two calls that share a workspace must be)."""
     desc = LossDesc(LOSS_KINDS[kind], seq_offsets.numel() - 1, eps_low, eps_high, c)
+    if workspace is None:
+        key = logp_theta.device.index
+        if key not in _loss_workspaces:
+            _loss_workspaces[key] = torch.empty(lib().roll_policy_loss_workspace_bytes(C.byref(desc)),
+                                                dtype=torch.uint8, device=logp_theta.device)
+        workspace = _loss_workspaces[key]
     _check(lib().roll_policy_loss(
         _dev(logp_theta, torch.float32), _dev(logp_old, torch.float32), _dev(logp_prox, torch.float32),
         _dev(signal, torch.float32), _dev(seq_offsets, torch.int64), _dev(value_out, torch.float32),
         _dev(grad_out, torch.float32), _dev(is_weight_out, torch.float32), _dev(seq_mean_out, torch.float32),
-        _dev(batch_mean_out, torch.float32), C.byref(desc), _stream()))
+        _dev(batch_mean_out, torch.float32), C.byref(desc), _dev(workspace),
+        workspace.numel() * workspace.element_size(), _stream()))
 
 
 # ----------------------------------------------------------------------------

@@ -181,6 +181,7 @@ class RefillLoop:
                                  side_by_side=side_by_side, run_pages=run_pages)
         self.refills = 0
         self.refill_log = []  # (step, slot, request)
+        self.prefill_events = []  # (begin, end) around the prefill launches of a tick, while the batch profiles
         self._load_torch_kernels()
 
     def _load_torch_kernels(self):
@@ -237,8 +238,14 @@ class RefillLoop:
                 slot_["host"][2, :n_ch + 1] = torch.from_numpy(first)
                 meta = slot_["dev"]
                 meta.copy_(slot_["host"], non_blocking=True)
+                if b.profile_events:
+                    e0, e1 = rb.ProfEvent(), rb.ProfEvent()
+                    e0.record()
                 rb.roll_prefill_attn(q, k, v, meta[0, :n_ch], meta[1, :n_ch], meta[2, :n_ch + 1], b.k_pages,
                                      b.v_pages, b.page_table, out, cfg.page_size)
+                if b.profile_events:
+                    e1.record()
+                    self.prefill_events.append((e0, e1))
                 slot_["ev"] = torch.cuda.Event()
                 slot_["ev"].record()
                 self.last_prefill = (q, out, [(r[0], r[2], int(f)) for r, f in zip(refilled, first)])

@@ -71,3 +71,43 @@ def test_bad_arguments():
     with pytest.raises(rb.RollError):
         rb.roll_policy_loss("tis", b["logp_theta"], b["logp_old"], None, b["signal"], b["offsets"],
                             None, None, None, sm, bm, c=0.0)
+
+
+@pytest.mark.parametrize("shape", ["one_long", "many_tiny", "mixed", "fewer_tokens_than_waves", "many_responses"])
+def test_token_shares_and_partial_sums_at_every_kind_of_boundary(shape):
+    # The batch's tokens are dealt to the waves in equal shares whatever the responses' lengths: one
+    # response spread over every wave, thousands of one- and two-token responses (dozens per
+    # share), responses that begin or end exactly at share boundaries with empty ones between,
+    # fewer tokens than waves (most shares empty), and more responses than the on-chip offset
+    # table holds.
+    rng = np.random.default_rng(["one_long", "many_tiny", "mixed", "fewer_tokens_than_waves", "many_responses"].index(shape))
+    if shape == "one_long":
+        lens = np.array([0, 300000, 0, 5])
+    elif shape == "many_tiny":
+        lens = rng.integers(0, 3, size=6000)
+    elif shape == "mixed":
+        lens = np.concatenate([[4096 * 7, 0, 0, 4096, 1, 4095, 0], rng.integers(0, 9000, size=40), [0]])
+    elif shape == "fewer_tokens_than_waves":
+        lens = np.array([3, 0, 700, 1, 0, 0, 2])
+    else:
+        lens = rng.integers(0, 40, size=9000)
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    T = int(offsets[-1])
+    g = torch.Generator().manual_seed(T)
+    lo = -(torch.randn(T, generator=g).abs() * 1.5 + 0.01)
+    b = dict(logp_old=lo, logp_theta=lo + torch.randn(T, generator=g) * 0.3, logp_prox=lo + torch.randn(T, generator=g) * 0.1,
+             signal=torch.randn(T, generator=g), offsets=torch.from_numpy(offsets))
+    say(f"  policy loss shares {shape}: {len(lens)} responses, {T} tokens")
+    for kind in ("ppo", "decoupled_ppo", "topr"):
+        ref = oracle.policy_loss(kind, b["logp_theta"].numpy(), b["logp_old"].numpy(),
+                                 b["logp_prox"].numpy() if kind == "decoupled_ppo" else None,
+                                 b["signal"].numpy(), offsets, np.float32(0.2), np.float32(0.28), np.float32(5.0))
+        value, grad, w, seq_mean, batch_mean = run_gpu(kind, b, 0.2, 0.28, 5.0)
+        tol = lambda x: 1e-6 * (1 + np.abs(x))
+        assert (np.abs(value - ref["value"]) <= tol(ref["value"])).all()
+        assert (np.abs(grad - ref["grad"]) <= tol(ref["grad"])).all()
+        assert (np.abs(w - ref["is_weight"]) <= tol(ref["is_weight"])).all()
+        assert (np.abs(seq_mean - ref["seq_mean"]) <= tol(ref["seq_mean"])).all()
+        assert abs(batch_mean - ref["batch_mean"]) <= 1e-6 * (1 + abs(ref["batch_mean"]))
+        again = run_gpu(kind, b, 0.2, 0.28, 5.0)
+        assert np.array_equal(seq_mean, again[3]) and batch_mean == again[4]     # reproducible
