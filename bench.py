@@ -147,6 +147,79 @@ def policy_loss_bench(args, torch, rb, wl):
                       "batches": out}), flush=True)
 
 
+def attn_timeline_bench(args, torch, rb, wl):
+    """Where the attention launch spends its time, wave by wave: needs the library built with
+    `python -m paper_2510_11345_amd.build --timeline`, whose kernel stamps the 100 MHz clock at five
+    places per wave.  Runs the configuration's decode loop and reports, over the timed launches
+    that took the single fused launch: the launch's span, how long a wave takes to its first
+    finished step, the steady step time, when the waves run out of work (by XCD too) and how many
+    microseconds the average wave idles at the end.  Steps are synchronised one by one, so the
+    step rate of this run means nothing."""
+    from paper_2510_11345_amd.harness import DecodeBatch, RefillLoop
+    cfg = wl.CONFIGS[args.config]
+    K, W = args.steps, args.warmup
+    loop = None
+    if cfg.name == "c4":
+        plan = wl.draw_refill_plan(cfg.batch, cfg.batch + 4 * (K + W) + 64, args.seed)
+        loop = RefillLoop(cfg, plan, args.seed, max_len=cfg.max_len + K + W + 2)
+        batch, step_fn = loop.batch, loop.step
+    else:
+        lengths = wl.draw_lengths(cfg.lengths, cfg.batch, args.seed, cfg.max_len).astype(np.int64)
+        batch = DecodeBatch(cfg, args.seed, lengths - 1, headroom_tokens=K + W + 2)
+        step_fn = batch.step
+    logits = wl.make_logits(cfg, args.seed, "cuda")
+    for i in range(W):
+        step_fn(logits, i)
+    torch.cuda.synchronize()
+    buf = torch.zeros((1024, 8), dtype=torch.int64, device="cuda")
+    rb.roll_prof_attn_timeline(buf)
+    per_launch = []
+    for i in range(K):
+        buf.zero_()
+        fused_before = rb.roll_kv_fused_steps(batch.pool)
+        step_fn(logits, W + i)
+        torch.cuda.synchronize()
+        if rb.roll_kv_fused_steps(batch.pool) == fused_before:
+            continue                      # a refill tick: two launches, not the one profiled here
+        t = buf.cpu().numpy().astype(np.float64)
+        t = t[t[:, 0] > 0]
+        ticks = 0.01                      # microseconds per tick of the 100 MHz clock
+        t0 = t[:, 0].min()
+        entry, prefix, first, last, exit_ = ((t[:, k] - t0) * ticks for k in range(5))
+        steps, xcd = t[:, 5], t[:, 6].astype(int)
+        span = exit_.max()
+        work = steps > 1
+        step_us = float(np.median((last[work] - first[work]) / (steps[work] - 1)))
+        kv_bytes = cfg.kv_bytes_per_token * batch.total_tokens()
+        per_launch.append({
+            "span_us": float(span), "GBps_over_span": kv_bytes / span / 1e3,
+            "entry_skew_us": float(entry.max()), "prefix_build_us": float(np.median(prefix - entry)),
+            "first_step_done_us": float(np.median(first[steps > 0])),
+            "step_us": step_us,
+            "last_step_p10_p50_p90_max_us": [float(np.percentile(last, q)) for q in (10, 50, 90)] + [float(last.max())],
+            "exit_p10_p50_p90_max_us": [float(np.percentile(exit_, q)) for q in (10, 50, 90)] + [float(exit_.max())],
+            "mean_idle_at_end_us": float((span - exit_).mean()),
+            "mean_start_over_one_step_us": float(np.mean(first[steps > 0] - step_us)),
+            "after_last_step_us": float(np.median(exit_ - last)),
+            "last_step_mean_by_xcd_us": [float(last[xcd == x].mean()) if (xcd == x).any() else None for x in range(8)],
+            "steps_per_wave_min_max": [int(steps.min()), int(steps.max())], "waves": int(len(t)),
+        })
+    rb.roll_prof_attn_timeline(None)
+    keys = [k for k in per_launch[0] if not isinstance(per_launch[0][k], list)]
+    mean = {k: float(np.mean([p[k] for p in per_launch])) for k in keys}
+    for k in per_launch[0]:
+        if isinstance(per_launch[0][k], list) and k != "steps_per_wave_min_max":
+            mean[k] = [float(np.mean([p[k][i] for p in per_launch])) for i in range(len(per_launch[0][k]))]
+    print(json.dumps({"metric": "per-wave timeline of the attention launch (attn_stream, fused decode step)",
+                      "unit": "us", "n_gpus": 1, "steps": K, "warmup": W, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": f"{cfg.name}: B={cfg.batch} Hq={cfg.num_q_heads} Hkv={cfg.num_kv_heads} "
+                                             f"D={cfg.head_dim} P={cfg.page_size} lengths={cfg.lengths}",
+                                 "sum_seq_lens": int(batch.total_tokens())},
+                      "launches_profiled": len(per_launch), "mean_over_launches": mean,
+                      "first_launch": per_launch[0]}), flush=True)
+    batch.close()
+
+
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix-core peak
 
 
@@ -429,6 +502,9 @@ def main():
     ap.add_argument("--dense-pools", action="store_true",
                     help="K and V in two dense allocations and pages handed out one by one, instead of one "
                          "allocation with the K and V block of a page side by side and pages in runs of 32 / P")
+    ap.add_argument("--attn-timeline", action="store_true",
+                    help="per-wave timestamps of the attention launch on --config (default c4): needs the "
+                         "library built with `python -m paper_2510_11345_amd.build --timeline`")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="only run one plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -442,6 +518,13 @@ def main():
     from paper_2510_11345_amd import binding as rb
     from paper_2510_11345_amd import workloads as wl
     from paper_2510_11345_amd.harness import DecodeBatch
+    if args.attn_timeline:
+        from paper_2510_11345_amd import build as hip_build
+        if not os.path.exists(hip_build.TIMELINE_LIB):
+            print("bench.py --attn-timeline: build the instrumented library first: "
+                  "python -m paper_2510_11345_amd.build --timeline", file=sys.stderr)
+            sys.exit(1)
+        rb.LIB_PATH = hip_build.TIMELINE_LIB
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -455,6 +538,10 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"pmc_calibration": "one device copy", "bytes_read": src.numel() * 4,
                           "bytes_written": dst.numel() * 4}))
+        return
+    if args.attn_timeline:
+        args.config = args.config or "c4"
+        attn_timeline_bench(args, torch, rb, wl)
         return
     if args.equal_rows:
         args.config = args.config or "c2"

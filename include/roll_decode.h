@@ -543,6 +543,16 @@ int64_t roll_sample_buffer_capacity(const roll_sample_buffer* buffer);
  * handles from roll_prof_event_create).  NULL, NULL switches it off again. */
 int roll_prof_attn_events(void* begin, void* end);
 /*
+ * Per-wave timestamps of the attention kernel, for a library built with
+ * -DROLL_ATTN_TIMELINE only (the product build returns ROLL_ERR_INVALID_ARG).
+ * buffer: DEVICE, 8-byte aligned, >= 1024 waves * 8 * 8 bytes, or NULL to switch
+ * it off.  Every wave of the following attention launches writes 8 words:
+ * the 100 MHz clock at entry, after the row prefix, after its first step,
+ * after its last step, at exit; the steps it ran; its XCD; its streams.
+ * SYNCHRONISES (a copy to a device symbol).
+ */
+int roll_prof_attn_timeline(void* buffer, size_t buffer_bytes);
+/*
  * Bandwidth ceiling of the decode step's access pattern (Section 1: decoding is
  * memory-bandwidth bound): enqueues ONE kernel that reads, through page_table,
  * the K block and the V block (all KV heads) of every page that holds tokens of

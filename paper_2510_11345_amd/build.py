@@ -17,7 +17,10 @@ def hipcc_path() -> str:
     return os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 
-def build(verbose: bool = False, out: str = LIB, sanitize_host: bool = False) -> str:
+TIMELINE_LIB = os.path.join(HERE, "libroll_decode_timeline.so")
+
+
+def build(verbose: bool = False, out: str = LIB, sanitize_host: bool = False, timeline: bool = False) -> str:
     """Compile the library to `out`.  sanitize_host instruments the HOST pass only with
     AddressSanitizer and UndefinedBehaviorSanitizer (allocator, SampleBuffer, dealing arithmetic,
     argument checks); the CPU test suite runs its host-only tests through such a build."""
@@ -25,6 +28,8 @@ def build(verbose: bool = False, out: str = LIB, sanitize_host: bool = False) ->
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wall", "-Wno-unused-function",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", out]
+    if timeline:  # per-wave timestamps in the attention kernel (bench.py --attn-timeline)
+        cmd += ["-DROLL_ATTN_TIMELINE"]
     if sanitize_host:
         cmd += ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
                 "-Xarch_host", "-fno-sanitize-recover=all", "-Xarch_host", "-fno-omit-frame-pointer",
@@ -43,4 +48,7 @@ def build(verbose: bool = False, out: str = LIB, sanitize_host: bool = False) ->
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    if "--timeline" in sys.argv[1:]:
+        print(build(verbose=True, out=TIMELINE_LIB, timeline=True))
+    else:
+        print(build(verbose=True))

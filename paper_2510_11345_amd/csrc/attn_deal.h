@@ -65,6 +65,15 @@ __host__ __device__ inline int64_t cost_pre(const int32_t* pre, const uint16_t* 
     return (int64_t)pre[b] * kStepCost + (int64_t)live[b] * kRowCost;
 }
 
+// The first step of the range whose boundary is position x of the cost line, given the row `lo`
+// that holds x: the last row with cost_pre(lo) <= x (it has tokens).
+__host__ __device__ inline int32_t first_step_in_row(int64_t x, int32_t lo, const int32_t* pre, const uint16_t* live) {
+    const int64_t local = x - cost_pre(pre, live, lo);
+    const int32_t n = pre[lo + 1] - pre[lo];
+    const int64_t k = local <= kRowCost ? 0 : (local - kRowCost + kStepCost - 1) / kStepCost;
+    return pre[lo] + (int32_t)(k < n ? k : n);
+}
+
 // The first step range `range` owns (the total number of steps for range >= NC).
 __host__ __device__ inline int32_t first_step(const Deal& deal, int32_t range, int32_t B, const int32_t* pre,
                                               const uint16_t* live) {
@@ -75,10 +84,7 @@ __host__ __device__ inline int32_t first_step(const Deal& deal, int32_t range, i
         const int32_t mid = (lo + hi) >> 1;
         if (cost_pre(pre, live, mid) <= x) lo = mid; else hi = mid;
     }
-    const int64_t local = x - cost_pre(pre, live, lo);
-    const int32_t n = pre[lo + 1] - pre[lo];
-    const int64_t k = local <= kRowCost ? 0 : (local - kRowCost + kStepCost - 1) / kStepCost;
-    return pre[lo] + (int32_t)(k < n ? k : n);
+    return first_step_in_row(x, lo, pre, live);
 }
 
 }  // namespace attn

@@ -127,6 +127,21 @@ __global__ void prepare_header(uint32_t* dst, size_t n) {
     if (i < n) dst[i] = i == offsetof(WorkspaceHeader, tag) / 4 ? kWorkspaceTag : 0u;
 }
 
+// Built with -DROLL_ATTN_TIMELINE (paper_2510_11345_amd.build --timeline, a library of its own), every
+// wave of attn_stream leaves eight 64-bit words in the buffer handed to roll_prof_attn_timeline:
+// the constant 100 MHz clock at entry, after the row prefix is built, after its first step, after
+// its last step, at exit; the steps it ran; its XCD; the streams it started.  The product build
+// has none of this.
+#ifdef ROLL_ATTN_TIMELINE
+__device__ uint64_t* g_timeline = nullptr;
+#define ROLL_TIMELINE(slot, value)                                                    \
+    do {                                                                              \
+        if (tl && lane == 0) tl[(size_t)w * 8 + (slot)] = (uint64_t)(value);          \
+    } while (0)
+#else
+#define ROLL_TIMELINE(slot, value) do { } while (0)
+#endif
+
 // KV is read exactly once per step: a nontemporal load keeps it from displacing the
 // page table, Q and the pieces in L2 (measured: +10 % on a plain streaming read).
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
@@ -321,6 +336,24 @@ __device__ void build_row_prefix(const int32_t* seq_lens, int32_t B, int32_t max
     __syncthreads();
 }
 
+// The last b in [0, n) with key(b) <= x, for a non-decreasing key with key(0) <= x < key(n): the
+// interval is cut into (up to) 64 parts per round, lane l probing the start of part l + 1; the
+// probes that hold are the first ones, so their count names the part to go on with.  The same
+// result in every lane.
+template <typename KeyFn>
+__device__ __forceinline__ int32_t wave_last_row(int32_t n, int64_t x, KeyFn key, int32_t lane) {
+    int32_t lo = 0, hi = n;
+    while (hi - lo > 1) {
+        const int32_t stride = (hi - lo + 63) >> 6;
+        const int32_t probe = lo + (lane + 1) * stride;
+        const bool holds = probe < hi && key(probe) <= x;
+        const int32_t t = (int32_t)__popcll(__ballot(holds));
+        lo += t * stride;
+        hi = lo + stride < hi ? lo + stride : hi;
+    }
+    return lo;
+}
+
 // Pieces travel between waves on different XCDs (each with its own L2) inside one kernel.
 // They are written and read with relaxed device-scope atomic 8-byte accesses, which are
 // coherent across the XCDs by themselves; the handshake is a device-scope atomic counter.
@@ -481,6 +514,11 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
     // arbitrary counters, with which cut rows would be merged too early or never: such a launch
     // writes nothing at all and leaves a mark for roll_decode_attn_workspace_check.
     const uint32_t tag = __hip_atomic_load(&header->tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#ifdef ROLL_ATTN_TIMELINE
+    uint64_t* const tl = g_timeline;
+    const uint64_t tl_entry = wall_clock64();
+    uint64_t tl_first = 0, tl_steps = 0, tl_streams = 0;
+#endif
     build_row_prefix(seq_lens, prm.B, prm.max_len, FUSED, pre, len, live, s_wave_tot);
     if (tag != kWorkspaceTag) {
         if (blockIdx.x == 0 && threadIdx.x == 0)
@@ -491,6 +529,8 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
     const int32_t lane = threadIdx.x & 63;
     const int32_t w = blockIdx.x * kGroupWaves + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int32_t G = prm.G, Hkv = prm.Hkv;
+    ROLL_TIMELINE(0, tl_entry);
+    ROLL_TIMELINE(1, wall_clock64());
 
     if constexpr (FUSED) {
         if (blockIdx.x == 0)
@@ -531,17 +571,19 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
     ctx.q = lane >> 4;
     const int32_t rr = ctx.r < G ? ctx.r : 0;  // lanes of the padding heads shadow head 0, store nothing
 
+    // The searches over the rows are done by the whole wave, 64 probes of LDS at a time (two or
+    // three round trips instead of the eight to thirteen of a binary search): they stand between
+    // the launch's start and the wave's first K/V byte.
     // The row that holds row step `item` (the last row b with pre[b] <= item; it is not empty).
     auto row_of = [&](int32_t item) -> int32_t {
-        int32_t lo = 0, hi = prm.B;  // invariant: pre[lo] <= item < pre[hi]
-        while (hi - lo > 1) {
-            const int32_t mid = (lo + hi) >> 1;
-            if (pre[mid] <= item) lo = mid; else hi = mid;
-        }
-        return lo;
+        return wave_last_row(prm.B, (int64_t)item, [&](int32_t b) -> int64_t { return pre[b]; }, lane);
     };
     auto cost_pre = [&](int32_t b) -> int64_t { return roll::attn::cost_pre(pre, live, b); };
-    auto first_step = [&](int32_t range) -> int32_t { return roll::attn::first_step(deal, range, prm.B, pre, live); };
+    auto first_step = [&](int32_t range) -> int32_t {
+        if (range >= deal.NC) return pre[prm.B];
+        const int64_t x = deal.boundary(range);
+        return first_step_in_row(x, wave_last_row(prm.B, x, cost_pre, lane), pre, live);
+    };
     const int32_t item0 = c < deal.NC ? first_step(c) : 0;
     const int32_t todo0 = c < deal.NC ? first_step(c + 1) - item0 : 0;
 
@@ -667,6 +709,9 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
                     float sv[8];
                     score_step<D>(ctx, qf, sd, i * kStep, L, sv);
                     accumulate_step<D, false>(ctx, sv, sd, i * kStep, L, prm.scale_log2e, acc);
+#ifdef ROLL_ATTN_TIMELINE
+                    if (tl_first == 0) tl_first = wall_clock64();
+#endif
                     pgA = nxtA;
                     pgB = nxtB;
                 }
@@ -684,6 +729,10 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
                 accumulate_step<D, FUSED>(ctx, sv, sd, t0, L, prm.scale_log2e, acc);
             }
 
+#ifdef ROLL_ATTN_TIMELINE
+            tl_steps += (uint64_t)cnt;
+            tl_streams += 1;
+#endif
             // Finish the per-head sum across the four q-groups of the wave.
             acc.l = sum_over_q(acc.l);
 
@@ -705,6 +754,17 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
         }
     }
 
+#ifdef ROLL_ATTN_TIMELINE
+    ROLL_TIMELINE(2, tl_first);
+    ROLL_TIMELINE(3, wall_clock64());
+    ROLL_TIMELINE(5, tl_steps);
+    ROLL_TIMELINE(7, tl_streams);
+    {
+        uint32_t xcc;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+        ROLL_TIMELINE(6, xcc & 0xF);
+    }
+#endif
     if constexpr (FUSED) {
         // Append pass, after the wave's attention work so that nothing waits for these stores:
         // the wave that owned a stream's last step writes that stream's newest token (the K and
@@ -746,6 +806,7 @@ __global__ __launch_bounds__(kGroupWaves * 64) void attn_stream(
         if (threadIdx.x < 64 && arrive_last(&header->grid_arrivals, (int32_t)gridDim.x, lane))
             for (int32_t i = lane; i < prm.B; i += 64) fa.seq_lens_w[i] = len[i];
     }
+    ROLL_TIMELINE(4, wall_clock64());
 }
 
 int validate(const roll_attn_desc* d) {
@@ -839,6 +900,22 @@ extern "C" int roll_decode_attn_workspace_check(const void* workspace, size_t wo
     if (dirty != 0)
         return roll::fail(ROLL_ERR_WORKSPACE, "%zu arrival counter(s) are not zero: a launch on this workspace did not finish", dirty);
     return ROLL_OK;
+}
+
+extern "C" int roll_prof_attn_timeline(void* buffer, size_t buffer_bytes) {
+#ifdef ROLL_ATTN_TIMELINE
+    if (buffer && buffer_bytes < (size_t)kMaxPersistentWaves * 8 * sizeof(uint64_t))
+        return roll::fail(ROLL_ERR_WORKSPACE, "timeline buffer too small: %zu < %zu bytes", buffer_bytes,
+                          (size_t)kMaxPersistentWaves * 8 * sizeof(uint64_t));
+    uint64_t* p = (uint64_t*)buffer;
+    ROLL_HIP_CHECK(hipMemcpyToSymbol(HIP_SYMBOL(g_timeline), &p, sizeof p));
+    return ROLL_OK;
+#else
+    (void)buffer;
+    (void)buffer_bytes;
+    return roll::fail(ROLL_ERR_INVALID_ARG, "this library was built without ROLL_ATTN_TIMELINE "
+                                            "(python -m paper_2510_11345_amd.build --timeline builds one with it)");
+#endif
 }
 
 extern "C" int roll_prof_attn_events(void* begin, void* end) {
