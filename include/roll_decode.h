@@ -22,7 +22,9 @@
  *   - Every pointer is tagged HOST or DEVICE.  DEVICE pointers belong to
  *     the one visible GPU; the caller owns them and the stream.
  *   - Calls that take a stream enqueue work on it (a hipStream_t passed as
- *     void*, NULL = the default stream) and return without waiting for it.
+ *     void*, NULL = the default stream) and return without waiting for it; the
+ *     exceptions say so (roll_kv_commit when the host runs 8 commits ahead,
+ *     the diagnostic and profiling calls marked SYNCHRONISES).
  *   - Return value: ROLL_OK (0) or a negative roll_status.  On error no
  *     output buffer has been written and no allocator state has changed.
  *     roll_last_error() returns a thread-local description.
@@ -84,7 +86,7 @@ typedef enum roll_dtype { ROLL_BF16 = 0, ROLL_F32 = 1 } roll_dtype;
 /* HOST. Thread-local text of the last error on this thread ("" if none). */
 const char* roll_last_error(void);
 
-/* HOST. Library version, e.g. "0.1". */
+/* HOST. Library version, e.g. "0.2". */
 const char* roll_version(void);
 
 /* ------------------------------------------------------------------ */
@@ -157,9 +159,12 @@ int roll_kv_release(roll_kv_pool* pool, int32_t slot);
 
 /*
  * Publish every change made since the last commit to page_table_dev and
- * seq_lens_dev, as one small host-to-device copy plus one scatter kernel
- * enqueued on stream.  Does not wait for the stream.  Work enqueued on the
- * same stream afterwards sees the new tables.
+ * seq_lens_dev, as one small block of pinned host memory that one scatter
+ * kernel, enqueued on stream, reads.  Work enqueued on the same stream
+ * afterwards sees the new tables.  The call does not wait for the stream, with
+ * one exception: the pool owns a ring of 8 such blocks, and a host that is 8
+ * commits ahead of the GPU waits (hipEventSynchronize) for the oldest block to
+ * have been consumed before it reuses it.
  */
 int roll_kv_commit(roll_kv_pool* pool, void* stream);
 
