@@ -164,18 +164,25 @@ __device__ __forceinline__ StepPages step_page_ids(const int32_t* __restrict__ p
     return StepPages{pgA, pgB};
 }
 
+// What a copying thread keeps for the pieces it moves every step: the address of each piece in
+// page 0 at step offset 0 (pool, KV head, place inside the page's head block), whether the piece
+// lies in the step's second page (16-token pages), and how far a token of step offset inside a
+// larger page moves it (uint4 units: 1 for a K piece, D/8 for a V piece).
 template <int D>
-__device__ __forceinline__ void copy_step(uint4* tile, const uint4* __restrict__ k_pages,
-                                          const uint4* __restrict__ v_pages, StepPages pg, int32_t h, int32_t t0,
-                                          int32_t log2P, int32_t Hs) {
+struct CopySrc {
+    const uint4* base[CopyPlan<D>::kPerThread];
+    uint32_t per_token[CopyPlan<D>::kPerThread];
+    bool second[CopyPlan<D>::kPerThread];
+};
+
+template <int D>
+__device__ __forceinline__ CopySrc<D> copy_sources(const uint4* __restrict__ k_pages, const uint4* __restrict__ v_pages,
+                                                   int32_t h, int32_t log2P) {
     const int32_t P = 1 << log2P;
-    const int32_t pgA = pg.a, pgB = pg.b;
-    if (threadIdx.x >= kCopyThreads) return;
-    const int32_t wave_base = (int32_t)(threadIdx.x & ~63u);
+    CopySrc<D> cs;
 #pragma unroll
     for (int i = 0; i < CopyPlan<D>::kPerThread; ++i) {
-        const int32_t idx = threadIdx.x + i * kCopyThreads;
-        const uint4* src;
+        const int32_t idx = (threadIdx.x & (kCopyThreads - 1)) + i * kCopyThreads;
         if (idx < (D / 8) * 32) {
             // LDS order of the 32 token slots of a K row: the 16 slots that the lanes r = 0..15 of
             // MFMA tile tt read sit next to each other at 16 tt + r (256 contiguous bytes, all 64
@@ -183,15 +190,36 @@ __device__ __forceinline__ void copy_step(uint4* tile, const uint4* __restrict__
             // first page and of its second page; with larger pages the page order is that order.
             const int32_t d8 = idx >> 5, pos = idx & 31;
             const int32_t s32 = P == 16 ? 16 * ((pos >> 3) & 1) + (pos & 7) + 8 * (pos >> 4) : pos;
-            const int32_t page = (P == 16 && s32 >= 16) ? pgB : pgA;
-            const int32_t slot = P == 16 ? (s32 & 15) : (t0 & (P - 1)) + s32;
-            src = k_pages + (((int64_t)page * Hs + h) * (D / 8) + d8) * P + slot;
+            cs.second[i] = P == 16 && s32 >= 16;
+            cs.base[i] = k_pages + ((int64_t)h * (D / 8) + d8) * P + (P == 16 ? (s32 & 15) : s32);
+            cs.per_token[i] = 1u;
         } else {
             const int32_t j = idx - (D / 8) * 32, oct = j / D, d = j - oct * D;
-            const int32_t page = (P == 16 && oct >= 2) ? pgB : pgA;
-            const int32_t oct_in_page = ((t0 + 8 * oct) & (P - 1)) >> 3;
-            src = v_pages + (((int64_t)page * Hs + h) * (P / 8) + oct_in_page) * D + d;
+            cs.second[i] = P == 16 && oct >= 2;
+            cs.base[i] = v_pages + ((int64_t)h * (P / 8) + (P == 16 ? (oct & 1) : oct)) * D + d;
+            cs.per_token[i] = (uint32_t)(D / 8);
         }
+    }
+    return cs;
+}
+
+// Copies one step's K and V from the pages into an LDS tile with global_load_lds_dwordx4.  Called
+// by all threads; the first kCopyThreads do the work.  page_stride: uint4 units between pages
+// (the same for K and V blocks).
+template <int D>
+__device__ __forceinline__ void copy_step(uint4* tile, const CopySrc<D>& cs, StepPages pg, int32_t t0, int32_t log2P,
+                                          int64_t page_stride) {
+    if (threadIdx.x >= kCopyThreads) return;
+    const int32_t wave_base = (int32_t)(threadIdx.x & ~63u);
+    const uint32_t in_page = (uint32_t)t0 & ((1u << log2P) - 1u);   // 0 with 16-token pages
+    // The two page offsets are wave-uniform (scalar multiplies); a lane only picks one of them.
+    const uint64_t offA = (uint64_t)(uint32_t)pg.a * (uint64_t)page_stride, offB = (uint64_t)(uint32_t)pg.b * (uint64_t)page_stride;
+    const uint32_t a_lo = __builtin_amdgcn_readfirstlane((uint32_t)offA), a_hi = __builtin_amdgcn_readfirstlane((uint32_t)(offA >> 32));
+    const uint32_t b_lo = __builtin_amdgcn_readfirstlane((uint32_t)offB), b_hi = __builtin_amdgcn_readfirstlane((uint32_t)(offB >> 32));
+#pragma unroll
+    for (int i = 0; i < CopyPlan<D>::kPerThread; ++i) {
+        const uint32_t lo = cs.second[i] ? b_lo : a_lo, hi = cs.second[i] ? b_hi : a_hi;
+        const uint4* src = cs.base[i] + (int64_t)(((uint64_t)hi << 32) | lo) + in_page * cs.per_token[i];
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                          (__attribute__((address_space(3))) void*)(tile + i * kCopyThreads + wave_base),
                                          16, 0, 0);
@@ -317,8 +345,10 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     auto pages_of = [&](int32_t t0) {
         return step_page_ids(pt_row, min(t0, last_t0), prm.log2P, prm.max_pages, prm.num_pages);
     };
+    const CopySrc<D> cs = copy_sources<D>(k_pages, v_pages, h, prm.log2P);
+    const int64_t page_stride = ((int64_t)prm.Hs * D) << (prm.log2P - 3);
     auto copy_to = [&](auto I, int32_t t0, StepPages pg) {
-        copy_step<D>(tile(I), k_pages, v_pages, pg, h, min(t0, last_t0), prm.log2P, prm.Hs);
+        copy_step<D>(tile(I), cs, pg, min(t0, last_t0), prm.log2P, page_stride);
     };
     StepPages pg_next;   // page ids of the next copy, fetched one step early: the copy never waits for them
     StepData<D> sd;   // K of the step about to be computed is read one step early (see below)
@@ -375,18 +405,226 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
         __builtin_amdgcn_s_barrier();
     };
 
-    copy_to(std::integral_constant<int, 0>{}, 0, pages_of(0));
-    copy_to(std::integral_constant<int, 1>{}, kStep, pages_of(kStep));
-    copy_to(std::integral_constant<int, 2>{}, 2 * kStep, pages_of(2 * kStep));
-    pg_next = pages_of(kAhead * kStep);
-    copies_landed_but<D, kAhead - 2>();
+    // The same work as a three-stage pipeline (workgroups of 8 waves, which have the registers for
+    // it).  A wave issues an instruction every five or six cycles at best, a matrix instruction
+    // keeps the matrix core busy for sixteen or more, and vector instructions that do not depend
+    // on it run in its shadow: so the step's three parts must not follow each other (scores,
+    // then softmax, then PV: the matrix cores idle during the softmax and the vector units
+    // during the products) but run side by side on different steps.  Iteration s holds, in one
+    // stretch of straight-line code with no dependencies between the three: the PV products of
+    // step s - 1 (probabilities and V from the previous iteration), the exponentials, sums and
+    // packing of step s (its scores came out of the previous iteration), and the score products
+    // of step s + 1 (K read at the start of the iteration).  Iteration 0 multiplies zero
+    // probabilities, the last one scores the ring's clamped copy of the last step and drops them.
+    // What has to branch comes before that stretch: the causal mask of the steps on the diagonal
+    // and the (rare) move of the softmax reference, which first completes the pending PV products
+    // because their probabilities are relative to the old reference.
+    StepProbs pr[QT];
+    float sv[QT][8], t[QT][8];
+    // The part that branches: causal mask and exponents of step s (scores in sv), reference moved
+    // if some score is far above it.
+    auto exponents = [&](int32_t s) {
+        const int32_t t0 = s * kStep;
+        if (t0 + kStep - 1 > pos0) {
+            const int32_t first = t0 + 8 * q;
+#pragma unroll
+            for (int c = 0; c < QT; ++c)
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (first + j > pq[c]) sv[c][j] = -INFINITY;
+        }
+        float top = -INFINITY;
+#pragma unroll
+        for (int c = 0; c < QT; ++c)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                t[c][j] = fmaf(sv[c][j], prm.scale_log2e, -acc[c].m);
+                top = fmaxf(top, t[c][j]);
+            }
+        if (__any(!(top <= kLazyBits))) {
+#pragma unroll
+            for (int c = 0; c < QT; ++c) {
+                pv_accumulate<D, F32OUT>(sd, pr[c], acc[c]);
+                pr[c].hi = as_bf16x8(make_uint4(0u, 0u, 0u, 0u));
+                pr[c].lo = pr[c].hi;
+                move_reference<D>(sv[c], prm.scale_log2e, acc[c]);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) t[c][j] = fmaf(sv[c][j], prm.scale_log2e, -acc[c].m);
+            }
+        }
+    };
+    // The straight-line stretch of iteration s: K of step s + 1 from LDS, PV of step s - 1,
+    // probabilities of step s from its exponents, V of step s from LDS, scores of step s + 1.
+    auto products = [&](auto I) {
+        constexpr int kI = decltype(I)::value;
+        StepData<D> nx;
+        const uint4* kt = tile(std::integral_constant<int, (kI + 1) % kTiles>{});
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+            for (int kk = 0; kk < D / 32; ++kk) nx.k[tt][kk] = kt[(4 * kk + q) * 32 + 16 * tt + r];
+        StepProbs now[QT];
+#pragma unroll
+        for (int c = 0; c < QT; ++c) pv_accumulate<D, F32OUT>(sd, pr[c], acc[c]);
+#pragma unroll
+        for (int c = 0; c < QT; ++c) now[c] = probs_of_exponents<D, F32OUT>(t[c], acc[c]);
+        const uint4* vt = tile(I) + (D / 8) * 32;
+#pragma unroll
+        for (int nt = 0; nt < D / 16; ++nt) nx.v[nt] = vt[q * D + 16 * nt + r];
+#pragma unroll
+        for (int c = 0; c < QT; ++c) qk_scores<D>(qf[c], nx, sv[c]);
+#pragma unroll
+        for (int c = 0; c < QT; ++c) pr[c] = now[c];
+        sd = nx;
+    };
+    auto feed = [&](auto I, int32_t s) {   // the copy of step s + kAhead, the page ids of the one after
+        constexpr int kI = decltype(I)::value;
+        copy_to(std::integral_constant<int, (kI + kAhead) % kTiles>{}, (s + kAhead) * kStep, pg_next);
+        pg_next = pages_of((s + kAhead + 1) * kStep);
+    };
+    // Who copies.  A wave issues an instruction every eight cycles or so whatever its kind, and two
+    // waves per SIMD do not fill the SIMD's issue port: what a computing wave does not have to
+    // issue is time won.  With fewer than 8 query heads per KV head the workgroup has waves
+    // that compute nothing; the last 1, 2 or 4 of them then do all the copying (16, 8 or 4
+    // pieces per lane and step for head_dim 128) and fetch the page ids, and the computing waves
+    // issue nothing but their products, the softmax and their LDS reads.  With 8 heads all
+    // waves copy, two pieces per lane.
+    const int32_t n_cp = MAXW != 8 ? 0 : prm.G <= 4 ? 4 : prm.G <= 6 ? 2 : prm.G == 7 ? 1 : 0;
+    const int32_t first_cp = 8 - n_cp;
+
+    if constexpr (MAXW == 8) {
+        if (n_cp > 0 && wave >= first_cp) {
+            // ---- a copying wave
+            constexpr int kMaxPieces = CopyPlan<D>::kPieces / 64;   // per lane, with one copying wave
+            const int32_t n_pc = kMaxPieces / n_cp;
+            const int32_t stride_cp = 64 * n_cp, cw = wave - first_cp;
+            const int32_t P = 1 << prm.log2P;
+            const uint4* base[kMaxPieces];
+            uint32_t per_token[kMaxPieces];
+            bool second[kMaxPieces];
+#pragma unroll
+            for (int i = 0; i < kMaxPieces; ++i) {
+                const int32_t idx = cw * 64 + lane + i * stride_cp;
+                base[i] = k_pages;
+                per_token[i] = 0;
+                second[i] = false;
+                if (i < n_pc) {
+                    if (idx < (D / 8) * 32) {   // the LDS order of a K row's 32 token slots: see copy_sources
+                        const int32_t d8 = idx >> 5, pos = idx & 31;
+                        const int32_t s32 = P == 16 ? 16 * ((pos >> 3) & 1) + (pos & 7) + 8 * (pos >> 4) : pos;
+                        second[i] = P == 16 && s32 >= 16;
+                        base[i] = k_pages + ((int64_t)h * (D / 8) + d8) * P + (P == 16 ? (s32 & 15) : s32);
+                        per_token[i] = 1u;
+                    } else {
+                        const int32_t j = idx - (D / 8) * 32, oct = j / D, d = j - oct * D;
+                        second[i] = P == 16 && oct >= 2;
+                        base[i] = v_pages + ((int64_t)h * (P / 8) + (P == 16 ? (oct & 1) : oct)) * D + d;
+                        per_token[i] = (uint32_t)(D / 8);
+                    }
+                }
+            }
+            auto copy_all = [&](auto I, int32_t t0_raw, StepPages pg) {
+                const int32_t t0 = min(t0_raw, last_t0);
+                uint4* dst = tile(I) + cw * 64;
+                const uint32_t in_page = (uint32_t)t0 & ((1u << prm.log2P) - 1u);
+                const uint64_t offA = (uint64_t)(uint32_t)pg.a * (uint64_t)page_stride;
+                const uint64_t offB = (uint64_t)(uint32_t)pg.b * (uint64_t)page_stride;
+                const uint32_t a_lo = __builtin_amdgcn_readfirstlane((uint32_t)offA), a_hi = __builtin_amdgcn_readfirstlane((uint32_t)(offA >> 32));
+                const uint32_t b_lo = __builtin_amdgcn_readfirstlane((uint32_t)offB), b_hi = __builtin_amdgcn_readfirstlane((uint32_t)(offB >> 32));
+#pragma unroll
+                for (int i = 0; i < kMaxPieces; ++i) {
+                    if (i < n_pc) {
+                        const uint32_t lo = second[i] ? b_lo : a_lo, hi = second[i] ? b_hi : a_hi;
+                        const uint4* src = base[i] + (int64_t)(((uint64_t)hi << 32) | lo) + in_page * per_token[i];
+                        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                                         (__attribute__((address_space(3))) void*)(dst + i * stride_cp), 16, 0, 0);
+                    }
+                }
+            };
+            // All of this wave's copies but those of the youngest step have landed.
+            auto landed_but_one = [&]() {
+                if (n_pc == 16) __builtin_amdgcn_s_waitcnt((16 & 0xF) | ((16 >> 4) << 14) | (7 << 4));
+                else if (n_pc == 8) __builtin_amdgcn_s_waitcnt(8 | (7 << 4));
+                else if (n_pc == 4) __builtin_amdgcn_s_waitcnt(4 | (7 << 4));
+                else __builtin_amdgcn_s_waitcnt(2 | (7 << 4));
+            };
+            static_assert(kMaxPieces == 16 || kMaxPieces == 8, "wait counts above are written for 16 or 8 pieces per lane");
+            copy_all(std::integral_constant<int, 0>{}, 0, pages_of(0));
+            copy_all(std::integral_constant<int, 1>{}, kStep, pages_of(kStep));
+            copy_all(std::integral_constant<int, 2>{}, 2 * kStep, pages_of(2 * kStep));
+            pg_next = pages_of(kAhead * kStep);
+            landed_but_one();
+            __builtin_amdgcn_s_barrier();
+            auto feed_all = [&](auto I, int32_t s) {
+                constexpr int kI = decltype(I)::value;
+                copy_all(std::integral_constant<int, (kI + kAhead) % kTiles>{}, (s + kAhead) * kStep, pg_next);
+                pg_next = pages_of((s + kAhead + 1) * kStep);
+                landed_but_one();
+                __builtin_amdgcn_s_barrier();
+            };
+            for (int32_t s = 0; s < n_steps; s += kTiles) {
+                feed_all(std::integral_constant<int, 0>{}, s);
+                if (s + 1 < n_steps) feed_all(std::integral_constant<int, 1>{}, s + 1);
+                if (s + 2 < n_steps) feed_all(std::integral_constant<int, 2>{}, s + 2);
+                if (s + 3 < n_steps) feed_all(std::integral_constant<int, 3>{}, s + 3);
+            }
+            return;
+        }
+        if (n_cp > 0 && !computes) {   // a wave with nothing to do keeps the barriers company
+            for (int32_t s = 0; s <= n_steps; ++s) __builtin_amdgcn_s_barrier();
+            return;
+        }
+    }
+
+    const bool shared_copy = n_cp == 0;
+    auto iter = [&](auto I, int32_t s) {
+        if (computes) exponents(s);
+        if (shared_copy) feed(I, s);
+        if (computes) products(I);
+        if (shared_copy) copies_landed_but<D, kAhead - 2>();
+        else __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (0xF) | (3 << 14));   // LDS reads returned (vmcnt untouched)
+        __builtin_amdgcn_s_barrier();
+    };
+
+    if (shared_copy) {
+        copy_to(std::integral_constant<int, 0>{}, 0, pages_of(0));
+        copy_to(std::integral_constant<int, 1>{}, kStep, pages_of(kStep));
+        copy_to(std::integral_constant<int, 2>{}, 2 * kStep, pages_of(2 * kStep));
+        pg_next = pages_of(kAhead * kStep);
+        copies_landed_but<D, kAhead - 2>();
+    }
     __builtin_amdgcn_s_barrier();
-    if (computes) read_k(std::integral_constant<int, 0>{});
-    for (int32_t s = 0; s < n_steps; s += kTiles) {   // n_steps is the same for the whole workgroup
-        step(std::integral_constant<int, 0>{}, s);
-        if (s + 1 < n_steps) step(std::integral_constant<int, 1>{}, s + 1);
-        if (s + 2 < n_steps) step(std::integral_constant<int, 2>{}, s + 2);
-        if (s + 3 < n_steps) step(std::integral_constant<int, 3>{}, s + 3);
+    if constexpr (MAXW == 8) {
+        if (computes) {
+            read_k(std::integral_constant<int, 0>{});
+#pragma unroll
+            for (int c = 0; c < QT; ++c) {
+                qk_scores<D>(qf[c], sd, sv[c]);
+                pr[c].hi = as_bf16x8(make_uint4(0u, 0u, 0u, 0u));
+                pr[c].lo = pr[c].hi;
+            }
+#pragma unroll
+            for (int nt = 0; nt < D / 16; ++nt) sd.v[nt] = make_uint4(0u, 0u, 0u, 0u);
+        }
+        for (int32_t s = 0; s < n_steps; s += kTiles) {   // n_steps is the same for the whole workgroup
+            iter(std::integral_constant<int, 0>{}, s);
+            if (s + 1 < n_steps) iter(std::integral_constant<int, 1>{}, s + 1);
+            if (s + 2 < n_steps) iter(std::integral_constant<int, 2>{}, s + 2);
+            if (s + 3 < n_steps) iter(std::integral_constant<int, 3>{}, s + 3);
+        }
+        if (computes) {   // the PV products of the last step, whose tokens past the end count for nothing
+            if (n_steps * kStep > kv_end) mask_v_tail<D>(sd, kv_end - ((n_steps - 1) * kStep + 8 * q));
+#pragma unroll
+            for (int c = 0; c < QT; ++c) pv_accumulate<D, F32OUT>(sd, pr[c], acc[c]);
+        }
+    } else {
+        if (computes) read_k(std::integral_constant<int, 0>{});
+        for (int32_t s = 0; s < n_steps; s += kTiles) {
+            step(std::integral_constant<int, 0>{}, s);
+            if (s + 1 < n_steps) step(std::integral_constant<int, 1>{}, s + 1);
+            if (s + 2 < n_steps) step(std::integral_constant<int, 2>{}, s + 2);
+            if (s + 3 < n_steps) step(std::integral_constant<int, 3>{}, s + 3);
+        }
     }
 
     if (!computes) return;
