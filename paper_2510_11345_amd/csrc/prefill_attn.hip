@@ -494,50 +494,54 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
 
     if constexpr (MAXW == 8) {
         if (n_cp > 0 && wave >= first_cp) {
-            // ---- a copying wave
+            // ---- a copying wave.  Lane cl of the copying lanes moves the pieces cl, cl + stride_cp,
+            // cl + 2 stride_cp, .. of the step's LDS tile (K pieces first, then V pieces).  What
+            // depends on the lane is kept from before the loop; what depends on the piece is the
+            // same for the whole wave and comes from the scalar unit.
+            constexpr int kKPieces = (D / 8) * 32, kVPieces = 4 * D;
             constexpr int kMaxPieces = CopyPlan<D>::kPieces / 64;   // per lane, with one copying wave
             const int32_t n_pc = kMaxPieces / n_cp;
-            const int32_t stride_cp = 64 * n_cp, cw = wave - first_cp;
+            const int32_t stride_cp = 64 * n_cp, cw = wave - first_cp, cl = cw * 64 + lane;
             const int32_t P = 1 << prm.log2P;
-            const uint4* base[kMaxPieces];
-            uint32_t per_token[kMaxPieces];
-            bool second[kMaxPieces];
-#pragma unroll
-            for (int i = 0; i < kMaxPieces; ++i) {
-                const int32_t idx = cw * 64 + lane + i * stride_cp;
-                base[i] = k_pages;
-                per_token[i] = 0;
-                second[i] = false;
-                if (i < n_pc) {
-                    if (idx < (D / 8) * 32) {   // the LDS order of a K row's 32 token slots: see copy_sources
-                        const int32_t d8 = idx >> 5, pos = idx & 31;
-                        const int32_t s32 = P == 16 ? 16 * ((pos >> 3) & 1) + (pos & 7) + 8 * (pos >> 4) : pos;
-                        second[i] = P == 16 && s32 >= 16;
-                        base[i] = k_pages + ((int64_t)h * (D / 8) + d8) * P + (P == 16 ? (s32 & 15) : s32);
-                        per_token[i] = 1u;
-                    } else {
-                        const int32_t j = idx - (D / 8) * 32, oct = j / D, d = j - oct * D;
-                        second[i] = P == 16 && oct >= 2;
-                        base[i] = v_pages + ((int64_t)h * (P / 8) + (P == 16 ? (oct & 1) : oct)) * D + d;
-                        per_token[i] = (uint32_t)(D / 8);
-                    }
-                }
-            }
+            const int32_t nk = kKPieces / stride_cp, nv = kVPieces / stride_cp;
+            // K piece ik: head-dim octet (cl >> 5) + ik (stride_cp >> 5), token slot by the LDS order
+            // of a K row (see copy_sources); the slot, and with 16-token pages the page, are the lane's.
+            const int32_t pos = cl & 31;
+            const int32_t s32 = P == 16 ? 16 * ((pos >> 3) & 1) + (pos & 7) + 8 * (pos >> 4) : pos;
+            const bool k_second = P == 16 && s32 >= 16;
+            const uint4* k_lane = k_pages + ((int64_t)h * (D / 8) + (cl >> 5)) * P + (P == 16 ? (s32 & 15) : s32);
+            const int64_t k_piece_step = (int64_t)(stride_cp >> 5) * P;
+            // V piece iv: linear index j = cl + iv stride_cp, octet j / D of the step (the same for
+            // the whole wave), head-dim element j mod D.
+            const uint32_t v_lane = (uint32_t)(cl & (D - 1));
+            const int32_t v_oct_of_wave = __builtin_amdgcn_readfirstlane(cl / D);
             auto copy_all = [&](auto I, int32_t t0_raw, StepPages pg) {
                 const int32_t t0 = min(t0_raw, last_t0);
                 uint4* dst = tile(I) + cw * 64;
-                const uint32_t in_page = (uint32_t)t0 & ((1u << prm.log2P) - 1u);
+                const uint32_t in_page = (uint32_t)t0 & ((1u << prm.log2P) - 1u);   // 0 with 16-token pages
                 const uint64_t offA = (uint64_t)(uint32_t)pg.a * (uint64_t)page_stride;
                 const uint64_t offB = (uint64_t)(uint32_t)pg.b * (uint64_t)page_stride;
                 const uint32_t a_lo = __builtin_amdgcn_readfirstlane((uint32_t)offA), a_hi = __builtin_amdgcn_readfirstlane((uint32_t)(offA >> 32));
                 const uint32_t b_lo = __builtin_amdgcn_readfirstlane((uint32_t)offB), b_hi = __builtin_amdgcn_readfirstlane((uint32_t)(offB >> 32));
+                const uint32_t lo = k_second ? b_lo : a_lo, hi = k_second ? b_hi : a_hi;
+                const uint4* k_src = k_lane + (int64_t)(((uint64_t)hi << 32) | lo) + in_page;
 #pragma unroll
-                for (int i = 0; i < kMaxPieces; ++i) {
-                    if (i < n_pc) {
-                        const uint32_t lo = second[i] ? b_lo : a_lo, hi = second[i] ? b_hi : a_hi;
-                        const uint4* src = base[i] + (int64_t)(((uint64_t)hi << 32) | lo) + in_page * per_token[i];
-                        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                                         (__attribute__((address_space(3))) void*)(dst + i * stride_cp), 16, 0, 0);
+                for (int ik = 0; ik < kKPieces / 64; ++ik) {
+                    if (ik < nk)
+                        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(k_src + ik * k_piece_step),
+                                                         (__attribute__((address_space(3))) void*)(dst + ik * stride_cp), 16, 0, 0);
+                }
+#pragma unroll
+                for (int iv = 0; iv < kVPieces / 64; ++iv) {
+                    if (iv < nv) {
+                        const int32_t oct = (iv * stride_cp) / D + v_oct_of_wave;
+                        const int32_t d_extra = (iv * stride_cp) & (D - 1);
+                        const bool second = P == 16 && oct >= 2;
+                        const int32_t oct_in_page = P == 16 ? (oct & 1) : oct + (int32_t)(in_page >> 3);
+                        const uint64_t off = second ? offB : offA;
+                        const uint4* v_base = v_pages + (int64_t)off + ((int64_t)h * (P / 8) + oct_in_page) * D + d_extra;
+                        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(v_base + v_lane),
+                                                         (__attribute__((address_space(3))) void*)(dst + kKPieces + iv * stride_cp), 16, 0, 0);
                     }
                 }
             };
