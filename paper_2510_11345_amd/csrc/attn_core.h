@@ -225,6 +225,28 @@ __device__ __forceinline__ void move_reference(const float (&sv)[8], float scale
 #pragma unroll
     for (int nt = 0; nt < D / 16; ++nt) a.o[nt] *= alpha;
 }
+// Probabilities as PV operands: rounded to bf16 once, or (SPLIT) as a bf16 high part plus a bf16
+// remainder.
+template <bool SPLIT>
+__device__ __forceinline__ StepProbs pack_probs(const float (&p)[8]) {
+    StepProbs out;
+    uint32_t hi[4], lo[4];
+#pragma unroll
+    for (int k2 = 0; k2 < 4; ++k2) {
+        hi[k2] = pack_bf16_rne(p[2 * k2], p[2 * k2 + 1]);
+        if (SPLIT) {
+            const float r0 = p[2 * k2] - __uint_as_float(hi[k2] << 16);
+            const float r1 = p[2 * k2 + 1] - __uint_as_float(hi[k2] & 0xFFFF0000u);
+            lo[k2] = pack_bf16_rne(r0, r1);
+        } else {
+            lo[k2] = 0u;
+        }
+    }
+    out.hi = as_bf16x8(make_uint4(hi[0], hi[1], hi[2], hi[3]));
+    out.lo = as_bf16x8(make_uint4(lo[0], lo[1], lo[2], lo[3]));
+    out.alpha = 1.0f;
+    return out;
+}
 template <int D, bool SPLIT>
 __device__ __forceinline__ StepProbs probs_of_exponents(const float (&t)[8], WaveAcc<D>& a) {
     float p[8];

@@ -236,6 +236,75 @@ __device__ __forceinline__ void copies_landed_but() {
     __builtin_amdgcn_s_waitcnt((n & 0xF) | ((n >> 4) << 14) | (7 << 4));
 }
 
+// The loop of a copying wave (workgroups with spare waves: the last NCP waves copy, wave cw of them
+// here).  Lane cl = 64 cw + lane of the copying lanes moves the pieces cl, cl + 64 NCP, .. of a
+// step's LDS tile, K pieces first, then V pieces.  What depends on the lane (the token slot of a K
+// piece and, with 16-token pages, its page; the head-dim element of a V piece) is kept from before
+// the loop; what depends on the piece is the same for the whole wave and, with the page size
+// and NCP known to the compiler, an immediate.  One barrier after the first three steps' copies,
+// then one per step, as in the computing waves.
+template <int D, int LOG2P, int NCP>
+__device__ __forceinline__ void copier_loop(uint4* tile0, uint4* tile1, uint4* tile2, uint4* tile3,
+                                            const uint4* __restrict__ k_pages, const uint4* __restrict__ v_pages,
+                                            const int32_t* __restrict__ pt_row, int32_t h, int32_t cw, int32_t lane,
+                                            int32_t n_steps, int64_t page_stride, int32_t max_pages, int32_t num_pages) {
+    constexpr int P = 1 << LOG2P;
+    constexpr int kKPieces = (D / 8) * 32, kVPieces = 4 * D, kStride = 64 * NCP;
+    constexpr int nk = kKPieces / kStride, nv = kVPieces / kStride;
+    static_assert(nk >= 1 && nv >= 1 && (nk + nv) < 64, "pieces per lane");
+    const int32_t cl = cw * 64 + lane;
+    const int32_t pos = cl & 31;
+    const int32_t s32 = P == 16 ? 16 * ((pos >> 3) & 1) + (pos & 7) + 8 * (pos >> 4) : pos;   // LDS order of a K row: see copy_sources
+    const bool k_second = P == 16 && s32 >= 16;
+    const uint4* k_lane = k_pages + ((int64_t)h * (D / 8) + (cl >> 5)) * P + (P == 16 ? (s32 & 15) : s32);
+    const uint32_t v_lane = (uint32_t)(cl & (D - 1));
+    const int32_t v_oct_of_wave = __builtin_amdgcn_readfirstlane(cl / D);
+    const uint4* v_head = v_pages + (int64_t)h * (P / 8) * D;
+    const int32_t last_t0 = (n_steps - 1) * kStep;
+    auto copy_all = [&](int32_t step) {
+        const int32_t t0 = min(step * kStep, last_t0);
+        const StepPages pg = step_page_ids(pt_row, t0, LOG2P, max_pages, num_pages);
+        uint4* tl = (step & 3) == 0 ? tile0 : (step & 3) == 1 ? tile1 : (step & 3) == 2 ? tile2 : tile3;
+        uint4* dst = tl + cw * 64;
+        const uint32_t in_page = (uint32_t)t0 & (uint32_t)(P - 1);   // 0 with 16-token pages
+        const uint64_t offA = (uint64_t)(uint32_t)pg.a * (uint64_t)page_stride;
+        const uint64_t offB = (uint64_t)(uint32_t)pg.b * (uint64_t)page_stride;
+        const uint32_t a_lo = __builtin_amdgcn_readfirstlane((uint32_t)offA), a_hi = __builtin_amdgcn_readfirstlane((uint32_t)(offA >> 32));
+        const uint32_t b_lo = __builtin_amdgcn_readfirstlane((uint32_t)offB), b_hi = __builtin_amdgcn_readfirstlane((uint32_t)(offB >> 32));
+        const uint32_t lo = k_second ? b_lo : a_lo, hi = k_second ? b_hi : a_hi;
+        const uint4* k_src = k_lane + (int64_t)(((uint64_t)hi << 32) | lo) + in_page;
+#pragma unroll
+        for (int ik = 0; ik < nk; ++ik)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(k_src + ik * (kStride >> 5) * P),
+                                             (__attribute__((address_space(3))) void*)(dst + ik * kStride), 16, 0, 0);
+#pragma unroll
+        for (int iv = 0; iv < nv; ++iv) {
+            const int32_t oct = (iv * kStride) / D + v_oct_of_wave;
+            const int32_t d_extra = (iv * kStride) & (D - 1);
+            const bool second = P == 16 && oct >= 2;
+            const int32_t oct_in_page = P == 16 ? (oct & 1) : oct + (int32_t)(in_page >> 3);
+            const uint4* v_base = v_head + (int64_t)(second ? offB : offA) + oct_in_page * D + d_extra;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(v_base + v_lane),
+                                             (__attribute__((address_space(3))) void*)(dst + kKPieces + iv * kStride), 16, 0, 0);
+        }
+    };
+    // All of this wave's copies but those of the youngest step have landed.
+    auto landed_but_one = [&]() {
+        constexpr int n = nk + nv;
+        __builtin_amdgcn_s_waitcnt((n & 0xF) | ((n >> 4) << 14) | (7 << 4) | (0xF << 8));
+    };
+    copy_all(0);
+    copy_all(1);
+    copy_all(2);
+    landed_but_one();
+    __builtin_amdgcn_s_barrier();
+    for (int32_t s = 0; s < n_steps; ++s) {
+        copy_all(s + kAhead);
+        landed_but_one();
+        __builtin_amdgcn_s_barrier();
+    }
+}
+
 // MAXW: most waves a workgroup of this instance may have (the register budget follows from it).
 // QT: column tiles (16 query tokens each) per wave; every K/V piece read from LDS is used for all
 // of them.  F32OUT: fp32 result, P split in two bf16 parts; else bf16 result, P rounded once.
@@ -455,27 +524,61 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     };
     // The straight-line stretch of iteration s: K of step s + 1 from LDS, PV of step s - 1,
     // probabilities of step s from its exponents, V of step s from LDS, scores of step s + 1.
-    auto products = [&](auto I) {
+    // K of step s + 1 is asked for before the branching part, so that it is on its way from LDS
+    // while that part runs.  The stretch itself is fenced into three parts so that the LDS reads
+    // stay where their latency is covered: PV products with the exponentials and the packing,
+    // then the reads of V (into the registers the PV products have just read), then the score
+    // products with the sums; V then arrives during the score products, before the barrier's wait.
+    uint4 k_next[2][D / 32];
+    auto ask_k = [&](auto I) {
         constexpr int kI = decltype(I)::value;
-        StepData<D> nx;
         const uint4* kt = tile(std::integral_constant<int, (kI + 1) % kTiles>{});
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-            for (int kk = 0; kk < D / 32; ++kk) nx.k[tt][kk] = kt[(4 * kk + q) * 32 + 16 * tt + r];
+            for (int kk = 0; kk < D / 32; ++kk) k_next[tt][kk] = kt[(4 * kk + q) * 32 + 16 * tt + r];
+    };
+    auto products = [&](auto I) {
+        float p[QT][8];
         StepProbs now[QT];
 #pragma unroll
         for (int c = 0; c < QT; ++c) pv_accumulate<D, F32OUT>(sd, pr[c], acc[c]);
 #pragma unroll
-        for (int c = 0; c < QT; ++c) now[c] = probs_of_exponents<D, F32OUT>(t[c], acc[c]);
+        for (int c = 0; c < QT; ++c) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) p[c][j] = __builtin_amdgcn_exp2f(t[c][j]);
+            now[c] = pack_probs<F32OUT>(p[c]);
+        }
+        // one product, one exponential, .. (the exponential runs while the matrix core works)
+#pragma unroll
+        for (int i = 0; i < QT * 8; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // K has had the whole branching part and the PV products to arrive: saying so here keeps
+        // the wait for it from also covering the reads of V that follow.
+        __builtin_amdgcn_s_waitcnt((7 << 4) | 0xF | (3 << 14));
         const uint4* vt = tile(I) + (D / 8) * 32;
 #pragma unroll
-        for (int nt = 0; nt < D / 16; ++nt) nx.v[nt] = vt[q * D + 16 * nt + r];
+        for (int nt = 0; nt < D / 16; ++nt) sd.v[nt] = vt[q * D + 16 * nt + r];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int c = 0; c < QT; ++c) qk_scores<D>(qf[c], nx, sv[c]);
+        for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-        for (int c = 0; c < QT; ++c) pr[c] = now[c];
-        sd = nx;
+            for (int kk = 0; kk < D / 32; ++kk) sd.k[tt][kk] = k_next[tt][kk];
+#pragma unroll
+        for (int c = 0; c < QT; ++c) qk_scores<D>(qf[c], sd, sv[c]);
+#pragma unroll
+        for (int c = 0; c < QT; ++c) {
+            acc[c].l += ((p[c][0] + p[c][1]) + (p[c][2] + p[c][3])) + ((p[c][4] + p[c][5]) + (p[c][6] + p[c][7]));
+            pr[c] = now[c];
+        }
+#pragma unroll
+        for (int i = 0; i < QT * 8; ++i) {   // one product, one addition, ..
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+            __builtin_amdgcn_sched_group_barrier(0x002, 1, 1);
+        }
     };
     auto feed = [&](auto I, int32_t s) {   // the copy of step s + kAhead, the page ids of the one after
         constexpr int kI = decltype(I)::value;
@@ -494,84 +597,20 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
 
     if constexpr (MAXW == 8) {
         if (n_cp > 0 && wave >= first_cp) {
-            // ---- a copying wave.  Lane cl of the copying lanes moves the pieces cl, cl + stride_cp,
-            // cl + 2 stride_cp, .. of the step's LDS tile (K pieces first, then V pieces).  What
-            // depends on the lane is kept from before the loop; what depends on the piece is the
-            // same for the whole wave and comes from the scalar unit.
-            constexpr int kKPieces = (D / 8) * 32, kVPieces = 4 * D;
-            constexpr int kMaxPieces = CopyPlan<D>::kPieces / 64;   // per lane, with one copying wave
-            const int32_t n_pc = kMaxPieces / n_cp;
-            const int32_t stride_cp = 64 * n_cp, cw = wave - first_cp, cl = cw * 64 + lane;
-            const int32_t P = 1 << prm.log2P;
-            const int32_t nk = kKPieces / stride_cp, nv = kVPieces / stride_cp;
-            // K piece ik: head-dim octet (cl >> 5) + ik (stride_cp >> 5), token slot by the LDS order
-            // of a K row (see copy_sources); the slot, and with 16-token pages the page, are the lane's.
-            const int32_t pos = cl & 31;
-            const int32_t s32 = P == 16 ? 16 * ((pos >> 3) & 1) + (pos & 7) + 8 * (pos >> 4) : pos;
-            const bool k_second = P == 16 && s32 >= 16;
-            const uint4* k_lane = k_pages + ((int64_t)h * (D / 8) + (cl >> 5)) * P + (P == 16 ? (s32 & 15) : s32);
-            const int64_t k_piece_step = (int64_t)(stride_cp >> 5) * P;
-            // V piece iv: linear index j = cl + iv stride_cp, octet j / D of the step (the same for
-            // the whole wave), head-dim element j mod D.
-            const uint32_t v_lane = (uint32_t)(cl & (D - 1));
-            const int32_t v_oct_of_wave = __builtin_amdgcn_readfirstlane(cl / D);
-            auto copy_all = [&](auto I, int32_t t0_raw, StepPages pg) {
-                const int32_t t0 = min(t0_raw, last_t0);
-                uint4* dst = tile(I) + cw * 64;
-                const uint32_t in_page = (uint32_t)t0 & ((1u << prm.log2P) - 1u);   // 0 with 16-token pages
-                const uint64_t offA = (uint64_t)(uint32_t)pg.a * (uint64_t)page_stride;
-                const uint64_t offB = (uint64_t)(uint32_t)pg.b * (uint64_t)page_stride;
-                const uint32_t a_lo = __builtin_amdgcn_readfirstlane((uint32_t)offA), a_hi = __builtin_amdgcn_readfirstlane((uint32_t)(offA >> 32));
-                const uint32_t b_lo = __builtin_amdgcn_readfirstlane((uint32_t)offB), b_hi = __builtin_amdgcn_readfirstlane((uint32_t)(offB >> 32));
-                const uint32_t lo = k_second ? b_lo : a_lo, hi = k_second ? b_hi : a_hi;
-                const uint4* k_src = k_lane + (int64_t)(((uint64_t)hi << 32) | lo) + in_page;
-#pragma unroll
-                for (int ik = 0; ik < kKPieces / 64; ++ik) {
-                    if (ik < nk)
-                        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(k_src + ik * k_piece_step),
-                                                         (__attribute__((address_space(3))) void*)(dst + ik * stride_cp), 16, 0, 0);
-                }
-#pragma unroll
-                for (int iv = 0; iv < kVPieces / 64; ++iv) {
-                    if (iv < nv) {
-                        const int32_t oct = (iv * stride_cp) / D + v_oct_of_wave;
-                        const int32_t d_extra = (iv * stride_cp) & (D - 1);
-                        const bool second = P == 16 && oct >= 2;
-                        const int32_t oct_in_page = P == 16 ? (oct & 1) : oct + (int32_t)(in_page >> 3);
-                        const uint64_t off = second ? offB : offA;
-                        const uint4* v_base = v_pages + (int64_t)off + ((int64_t)h * (P / 8) + oct_in_page) * D + d_extra;
-                        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(v_base + v_lane),
-                                                         (__attribute__((address_space(3))) void*)(dst + kKPieces + iv * stride_cp), 16, 0, 0);
-                    }
-                }
-            };
-            // All of this wave's copies but those of the youngest step have landed.
-            auto landed_but_one = [&]() {
-                if (n_pc == 16) __builtin_amdgcn_s_waitcnt((16 & 0xF) | ((16 >> 4) << 14) | (7 << 4));
-                else if (n_pc == 8) __builtin_amdgcn_s_waitcnt(8 | (7 << 4));
-                else if (n_pc == 4) __builtin_amdgcn_s_waitcnt(4 | (7 << 4));
-                else __builtin_amdgcn_s_waitcnt(2 | (7 << 4));
-            };
-            static_assert(kMaxPieces == 16 || kMaxPieces == 8, "wait counts above are written for 16 or 8 pieces per lane");
-            copy_all(std::integral_constant<int, 0>{}, 0, pages_of(0));
-            copy_all(std::integral_constant<int, 1>{}, kStep, pages_of(kStep));
-            copy_all(std::integral_constant<int, 2>{}, 2 * kStep, pages_of(2 * kStep));
-            pg_next = pages_of(kAhead * kStep);
-            landed_but_one();
-            __builtin_amdgcn_s_barrier();
-            auto feed_all = [&](auto I, int32_t s) {
-                constexpr int kI = decltype(I)::value;
-                copy_all(std::integral_constant<int, (kI + kAhead) % kTiles>{}, (s + kAhead) * kStep, pg_next);
-                pg_next = pages_of((s + kAhead + 1) * kStep);
-                landed_but_one();
-                __builtin_amdgcn_s_barrier();
-            };
-            for (int32_t s = 0; s < n_steps; s += kTiles) {
-                feed_all(std::integral_constant<int, 0>{}, s);
-                if (s + 1 < n_steps) feed_all(std::integral_constant<int, 1>{}, s + 1);
-                if (s + 2 < n_steps) feed_all(std::integral_constant<int, 2>{}, s + 2);
-                if (s + 3 < n_steps) feed_all(std::integral_constant<int, 3>{}, s + 3);
+            // ---- a copying wave (page size and number of copying waves as compile-time constants,
+            // so that everything about a piece but its page is an immediate)
+            const int32_t cw = wave - first_cp;
+#define ROLL_COPIER(LOG2P, NCP)                                                                                     \
+    copier_loop<D, LOG2P, NCP>(tile0, tile1, tile2, tile3, k_pages, v_pages, pt_row, h, cw, lane, n_steps, page_stride, \
+                               prm.max_pages, prm.num_pages)
+            if (prm.log2P == 4) {
+                if (n_cp == 1) ROLL_COPIER(4, 1); else if (n_cp == 2) ROLL_COPIER(4, 2); else ROLL_COPIER(4, 4);
+            } else if (prm.log2P == 5) {
+                if (n_cp == 1) ROLL_COPIER(5, 1); else if (n_cp == 2) ROLL_COPIER(5, 2); else ROLL_COPIER(5, 4);
+            } else {
+                if (n_cp == 1) ROLL_COPIER(6, 1); else if (n_cp == 2) ROLL_COPIER(6, 2); else ROLL_COPIER(6, 4);
             }
+#undef ROLL_COPIER
             return;
         }
         if (n_cp > 0 && !computes) {   // a wave with nothing to do keeps the barriers company
@@ -582,6 +621,7 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
 
     const bool shared_copy = n_cp == 0;
     auto iter = [&](auto I, int32_t s) {
+        if (computes) ask_k(I);
         if (computes) exponents(s);
         if (shared_copy) feed(I, s);
         if (computes) products(I);
