@@ -76,20 +76,24 @@ __device__ __forceinline__ float sum_over_q(float v) {
 // Raw scores q . k of the step's 32 tokens for column r; the 8 a lane owns are the step's
 // tokens 8q + j.  No scaling, no masking.
 template <int D>
-__device__ __forceinline__ void qk_scores(const bf16x8_t (&qf)[D / 32], const StepData<D>& s, float (&sv)[8]) {
+__device__ __forceinline__ void qk_scores_of(const bf16x8_t (&qf)[D / 32], const uint4 (&k)[2][D / 32], float (&sv)[8]) {
     f32x4_t sc[2];
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
         f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kk = 0; kk < D / 32; ++kk)
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(s.k[tt][kk]), qf[kk], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(k[tt][kk]), qf[kk], acc, 0, 0, 0);
         sc[tt] = acc;
     }
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
         for (int i = 0; i < 4; ++i) sv[4 * tt + i] = sc[tt][i];
+}
+template <int D>
+__device__ __forceinline__ void qk_scores(const bf16x8_t (&qf)[D / 32], const StepData<D>& s, float (&sv)[8]) {
+    qk_scores_of<D>(qf, s.k, sv);
 }
 
 // Zero the V elements of this lane's tokens nvalid, nvalid + 1, .. 7 (tokens that do not exist

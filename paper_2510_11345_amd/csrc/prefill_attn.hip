@@ -34,6 +34,10 @@ constexpr int kCopyWaves = 8;     // the first 8 waves of a workgroup copy K/V (
 constexpr int kCopyThreads = 64 * kCopyWaves;
 constexpr int kTiles = 4;         // LDS ring: the step in use and three steps of copies in flight
 constexpr int kAhead = kTiles - 1;
+// A row sum at or above this after the loop that never moves the softmax reference (or a NaN)
+// sends the workgroup through the exact loop: probabilities up to 2^40 times those of the
+// reference are harmless, beyond that products with V could overflow.
+constexpr float kSumLimit = 1.0995116e12f;   // 2^40
 
 struct PrefillParams {
     int32_t C, T, Hq, Hkv, G;
@@ -261,9 +265,11 @@ __device__ __forceinline__ void copier_loop(uint4* tile0, uint4* tile1, uint4* t
     const int32_t v_oct_of_wave = __builtin_amdgcn_readfirstlane(cl / D);
     const uint4* v_head = v_pages + (int64_t)h * (P / 8) * D;
     const int32_t last_t0 = (n_steps - 1) * kStep;
+    StepPages pg_ahead = step_page_ids(pt_row, 0, LOG2P, max_pages, num_pages);   // page ids come one step early
     auto copy_all = [&](int32_t step) {
         const int32_t t0 = min(step * kStep, last_t0);
-        const StepPages pg = step_page_ids(pt_row, t0, LOG2P, max_pages, num_pages);
+        const StepPages pg = pg_ahead;
+        pg_ahead = step_page_ids(pt_row, min((step + 1) * kStep, last_t0), LOG2P, max_pages, num_pages);
         uint4* tl = (step & 3) == 0 ? tile0 : (step & 3) == 1 ? tile1 : (step & 3) == 2 ? tile2 : tile3;
         uint4* dst = tl + cw * 64;
         const uint32_t in_page = (uint32_t)t0 & (uint32_t)(P - 1);   // 0 with 16-token pages
@@ -317,7 +323,7 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     static_assert(kTiles == 4 && kAhead == 3, "the step loop is written out for four tiles");
     __shared__ uint4 tile0[CopyPlan<D>::kPieces], tile1[CopyPlan<D>::kPieces], tile2[CopyPlan<D>::kPieces],
         tile3[CopyPlan<D>::kPieces];
-    __shared__ int32_t s_chunk, s_qb, s_found;
+    __shared__ int32_t s_chunk, s_qb, s_found, s_redo;
 
     // Which (chunk, query block) is this workgroup's?  Blocks are numbered chunk after chunk;
     // the workgroups take them from the last one down, so that within a prompt the blocks
@@ -340,7 +346,7 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
             total += __shfl(incl, 63);
         }
         const int32_t wanted = total - 1 - wanted_from_end;
-        if (lane == 0) s_found = 0;
+        if (lane == 0) { s_found = 0; s_redo = 0; }
         int32_t carry = 0;
         for (int32_t base = 0; base < prm.C && wanted >= 0; base += 64) {
             const int32_t c = base + lane;
@@ -414,7 +420,7 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     auto pages_of = [&](int32_t t0) {
         return step_page_ids(pt_row, min(t0, last_t0), prm.log2P, prm.max_pages, prm.num_pages);
     };
-    const CopySrc<D> cs = copy_sources<D>(k_pages, v_pages, h, prm.log2P);
+    CopySrc<D> cs;   // set where a loop in which all waves copy begins (not kept through the other loops)
     const int64_t page_stride = ((int64_t)prm.Hs * D) << (prm.log2P - 3);
     auto copy_to = [&](auto I, int32_t t0, StepPages pg) {
         copy_step<D>(tile(I), cs, pg, min(t0, last_t0), prm.log2P, page_stride);
@@ -490,45 +496,11 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     // because their probabilities are relative to the old reference.
     StepProbs pr[QT];
     float sv[QT][8], t[QT][8];
-    // The part that branches: causal mask and exponents of step s (scores in sv), reference moved
-    // if some score is far above it.
-    auto exponents = [&](int32_t s) {
-        const int32_t t0 = s * kStep;
-        if (t0 + kStep - 1 > pos0) {
-            const int32_t first = t0 + 8 * q;
-#pragma unroll
-            for (int c = 0; c < QT; ++c)
-#pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    if (first + j > pq[c]) sv[c][j] = -INFINITY;
-        }
-        float top = -INFINITY;
-#pragma unroll
-        for (int c = 0; c < QT; ++c)
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                t[c][j] = fmaf(sv[c][j], prm.scale_log2e, -acc[c].m);
-                top = fmaxf(top, t[c][j]);
-            }
-        if (__any(!(top <= kLazyBits))) {
-#pragma unroll
-            for (int c = 0; c < QT; ++c) {
-                pv_accumulate<D, F32OUT>(sd, pr[c], acc[c]);
-                pr[c].hi = as_bf16x8(make_uint4(0u, 0u, 0u, 0u));
-                pr[c].lo = pr[c].hi;
-                move_reference<D>(sv[c], prm.scale_log2e, acc[c]);
-#pragma unroll
-                for (int j = 0; j < 8; ++j) t[c][j] = fmaf(sv[c][j], prm.scale_log2e, -acc[c].m);
-            }
-        }
-    };
-    // The straight-line stretch of iteration s: K of step s + 1 from LDS, PV of step s - 1,
-    // probabilities of step s from its exponents, V of step s from LDS, scores of step s + 1.
-    // K of step s + 1 is asked for before the branching part, so that it is on its way from LDS
-    // while that part runs.  The stretch itself is fenced into three parts so that the LDS reads
-    // stay where their latency is covered: PV products with the exponentials and the packing,
-    // then the reads of V (into the registers the PV products have just read), then the score
-    // products with the sums; V then arrives during the score products, before the barrier's wait.
+    // K of step s + 1 is asked for at the start of the iteration; the stretch itself is fenced into
+    // three parts so that the LDS reads stay where their latency is covered: PV products with the
+    // exponents, exponentials, packing and sums, then the reads of V (into the registers the PV
+    // products have just read), then the score products; V arrives during the score products,
+    // before the barrier's wait.
     uint4 k_next[2][D / 32];
     auto ask_k = [&](auto I) {
         constexpr int kI = decltype(I)::value;
@@ -538,46 +510,82 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
 #pragma unroll
             for (int kk = 0; kk < D / 32; ++kk) k_next[tt][kk] = kt[(4 * kk + q) * 32 + 16 * tt + r];
     };
-    auto products = [&](auto I) {
-        float p[QT][8];
+    // Sum of a step's probabilities of one column in this lane.  For a bf16 result it is the sum
+    // of the ROUNDED probabilities, the ones the PV products use (numerator and denominator of
+    // the softmax then carry the same rounding), taken two at a time by the bf16 dot product.
+    auto step_sum = [&](const float (&p)[8], const StepProbs& now) -> float {
+        if constexpr (F32OUT) {
+            return ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+        } else {
+            const uint4 w = __builtin_bit_cast(uint4, now.hi);
+            const bf16x2_t ones = __builtin_bit_cast(bf16x2_t, 0x3F803F80u);
+            float acc2 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.x), ones, 0.f, false);
+            acc2 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.y), ones, acc2, false);
+            acc2 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.z), ones, acc2, false);
+            return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.w), ones, acc2, false);
+        }
+    };
+    // The reference of a column is NOT moved in this loop.  It is the exact maximum of the column's
+    // scores in step 0; a later score above it only makes probabilities larger than 1, which
+    // neither bf16 (a relative rounding) nor the fp32 sums mind, and the final division makes
+    // the result the same.  Moving it would take a test of the step's scores and a branch in
+    // every step, and a branch on a vector result waits until the wave's matrix instructions in
+    // flight have finished: a quarter of the step's time.  What can go wrong without it is
+    // overflow when scores rise by tens of powers of two above those of the first 32 tokens;
+    // that shows in the row sums, which are tested once after the loop (kSumLimit), and such a
+    // workgroup runs its block again through the exact loop below.
+    auto products = [&](auto I, int32_t s) {
+        const int32_t t0 = s * kStep;
+        if (t0 + kStep - 1 > pos0) {   // the step reaches past the first query's position: causal mask
+            const int32_t first = t0 + 8 * q;
+#pragma unroll
+            for (int c = 0; c < QT; ++c)
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (first + j > pq[c]) sv[c][j] = -INFINITY;
+        }
+        float t[QT][8], p[QT][8], sum[QT];
         StepProbs now[QT];
 #pragma unroll
         for (int c = 0; c < QT; ++c) pv_accumulate<D, F32OUT>(sd, pr[c], acc[c]);
 #pragma unroll
         for (int c = 0; c < QT; ++c) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) p[c][j] = __builtin_amdgcn_exp2f(t[c][j]);
-            now[c] = pack_probs<F32OUT>(p[c]);
+            for (int j = 0; j < 8; ++j) {
+                t[c][j] = fmaf(sv[c][j], prm.scale_log2e, -acc[c].m);
+                p[c][j] = __builtin_amdgcn_exp2f(t[c][j]);
+            }
         }
-        // one product, one exponential, .. (the exponential runs while the matrix core works)
 #pragma unroll
-        for (int i = 0; i < QT * 8; ++i) {
+        for (int i = 0; i < QT * 8; ++i) {   // one product, one exponent, one exponential, ..
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
-        // K has had the whole branching part and the PV products to arrive: saying so here keeps
-        // the wait for it from also covering the reads of V that follow.
+        // K has had the PV products to arrive: saying so here keeps the wait for it from also
+        // covering the reads of V that follow.
         __builtin_amdgcn_s_waitcnt((7 << 4) | 0xF | (3 << 14));
         const uint4* vt = tile(I) + (D / 8) * 32;
 #pragma unroll
         for (int nt = 0; nt < D / 16; ++nt) sd.v[nt] = vt[q * D + 16 * nt + r];
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt)
+        for (int c = 0; c < QT; ++c) qk_scores_of<D>(qf[c], k_next, sv[c]);
 #pragma unroll
-            for (int kk = 0; kk < D / 32; ++kk) sd.k[tt][kk] = k_next[tt][kk];
-#pragma unroll
-        for (int c = 0; c < QT; ++c) qk_scores<D>(qf[c], sd, sv[c]);
-#pragma unroll
-        for (int c = 0; c < QT; ++c) {
-            acc[c].l += ((p[c][0] + p[c][1]) + (p[c][2] + p[c][3])) + ((p[c][4] + p[c][5]) + (p[c][6] + p[c][7]));
-            pr[c] = now[c];
+        for (int c = 0; c < QT; ++c) {   // packing and sums in the shadow of the score products
+            now[c] = pack_probs<F32OUT>(p[c]);
+            sum[c] = step_sum(p[c], now[c]);
         }
 #pragma unroll
-        for (int i = 0; i < QT * 8; ++i) {   // one product, one addition, ..
+        for (int i = 0; i < QT * 8; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
             __builtin_amdgcn_sched_group_barrier(0x002, 1, 1);
+        }
+#pragma unroll
+        for (int c = 0; c < QT; ++c) {
+            acc[c].l += sum[c];
+            pr[c] = now[c];
         }
     };
     auto feed = [&](auto I, int32_t s) {   // the copy of step s + kAhead, the page ids of the one after
@@ -595,6 +603,19 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     const int32_t n_cp = MAXW != 8 ? 0 : prm.G <= 4 ? 4 : prm.G <= 6 ? 2 : prm.G == 7 ? 1 : 0;
     const int32_t first_cp = 8 - n_cp;
 
+    const bool shared_copy = n_cp == 0;
+    auto iter = [&](auto I, int32_t s) {
+        // (nothing is outstanding here; said explicitly, it keeps the first wait of the stretch,
+        // the one for V of the previous step, from covering the reads of K asked for now)
+        __builtin_amdgcn_s_waitcnt((7 << 4) | 0xF | (3 << 14));
+        if (computes) ask_k(I);
+        if (shared_copy) feed(I, s);
+        if (computes) products(I, s);
+        if (shared_copy) copies_landed_but<D, kAhead - 2>();
+        else __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (0xF) | (3 << 14));   // LDS reads returned (vmcnt untouched)
+        __builtin_amdgcn_s_barrier();
+    };
+
     if constexpr (MAXW == 8) {
         if (n_cp > 0 && wave >= first_cp) {
             // ---- a copying wave (page size and number of copying waves as compile-time constants,
@@ -611,64 +632,94 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
                 if (n_cp == 1) ROLL_COPIER(6, 1); else if (n_cp == 2) ROLL_COPIER(6, 2); else ROLL_COPIER(6, 4);
             }
 #undef ROLL_COPIER
-            return;
-        }
-        if (n_cp > 0 && !computes) {   // a wave with nothing to do keeps the barriers company
+        } else if (n_cp > 0 && !computes) {   // a wave with nothing to do keeps the barriers company
             for (int32_t s = 0; s <= n_steps; ++s) __builtin_amdgcn_s_barrier();
-            return;
+        } else {
+            if (shared_copy) {
+                cs = copy_sources<D>(k_pages, v_pages, h, prm.log2P);
+                copy_to(std::integral_constant<int, 0>{}, 0, pages_of(0));
+                copy_to(std::integral_constant<int, 1>{}, kStep, pages_of(kStep));
+                copy_to(std::integral_constant<int, 2>{}, 2 * kStep, pages_of(2 * kStep));
+                pg_next = pages_of(kAhead * kStep);
+                copies_landed_but<D, kAhead - 2>();
+            }
+            __builtin_amdgcn_s_barrier();
+            if (computes) {
+                read_k(std::integral_constant<int, 0>{});
+#pragma unroll
+                for (int c = 0; c < QT; ++c) {
+                    qk_scores<D>(qf[c], sd, sv[c]);
+                    pr[c].hi = as_bf16x8(make_uint4(0u, 0u, 0u, 0u));
+                    pr[c].lo = pr[c].hi;
+                }
+#pragma unroll
+                for (int nt = 0; nt < D / 16; ++nt) sd.v[nt] = make_uint4(0u, 0u, 0u, 0u);
+                // The reference of a column: the exact maximum of its scores in step 0 (token 0 is
+                // visible to every column, so it is finite).
+                float s0[QT][8];
+#pragma unroll
+                for (int c = 0; c < QT; ++c)
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) s0[c][j] = 8 * q + j > pq[c] ? -INFINITY : sv[c][j];
+#pragma unroll
+                for (int c = 0; c < QT; ++c) move_reference<D>(s0[c], prm.scale_log2e, acc[c]);
+            }
+            for (int32_t s = 0; s < n_steps; s += kTiles) {   // n_steps is the same for the whole workgroup
+                iter(std::integral_constant<int, 0>{}, s);
+                if (s + 1 < n_steps) iter(std::integral_constant<int, 1>{}, s + 1);
+                if (s + 2 < n_steps) iter(std::integral_constant<int, 2>{}, s + 2);
+                if (s + 3 < n_steps) iter(std::integral_constant<int, 3>{}, s + 3);
+            }
+            if (computes) {   // the PV products of the last step, whose tokens past the end count for nothing
+                if (n_steps * kStep > kv_end) mask_v_tail<D>(sd, kv_end - ((n_steps - 1) * kStep + 8 * q));
+                bool suspect = false;
+#pragma unroll
+                for (int c = 0; c < QT; ++c) {
+                    pv_accumulate<D, F32OUT>(sd, pr[c], acc[c]);
+                    suspect |= !(acc[c].l < kSumLimit);
+                }
+                if (suspect) s_redo = 1;
+            }
         }
-    }
-
-    const bool shared_copy = n_cp == 0;
-    auto iter = [&](auto I, int32_t s) {
-        if (computes) ask_k(I);
-        if (computes) exponents(s);
-        if (shared_copy) feed(I, s);
-        if (computes) products(I);
-        if (shared_copy) copies_landed_but<D, kAhead - 2>();
-        else __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (0xF) | (3 << 14));   // LDS reads returned (vmcnt untouched)
-        __builtin_amdgcn_s_barrier();
-    };
-
-    if (shared_copy) {
-        copy_to(std::integral_constant<int, 0>{}, 0, pages_of(0));
-        copy_to(std::integral_constant<int, 1>{}, kStep, pages_of(kStep));
-        copy_to(std::integral_constant<int, 2>{}, 2 * kStep, pages_of(2 * kStep));
-        pg_next = pages_of(kAhead * kStep);
-        copies_landed_but<D, kAhead - 2>();
-    }
-    __builtin_amdgcn_s_barrier();
-    if constexpr (MAXW == 8) {
-        if (computes) {
-            read_k(std::integral_constant<int, 0>{});
+        // Every copy of the loop above must have landed before the tiles may be used again.
+        __builtin_amdgcn_s_waitcnt((7 << 4) | (0xF << 8));
+        __syncthreads();
+        if (s_redo == 0) {
+            if (!computes) return;
 #pragma unroll
             for (int c = 0; c < QT; ++c) {
-                qk_scores<D>(qf[c], sd, sv[c]);
-                pr[c].hi = as_bf16x8(make_uint4(0u, 0u, 0u, 0u));
-                pr[c].lo = pr[c].hi;
+                acc[c].l = sum_over_q(acc[c].l);
+                if (kTile * c + r < nq) {
+                    const int64_t idx = ((int64_t)(tq0 + kTile * c + r) * prm.Hq + (int64_t)h * prm.G + wave) * D + 4 * q;
+                    store_result<D>(acc[c], out, idx, F32OUT);
+                }
             }
+            return;
+        }
 #pragma unroll
-            for (int nt = 0; nt < D / 16; ++nt) sd.v[nt] = make_uint4(0u, 0u, 0u, 0u);
-        }
-        for (int32_t s = 0; s < n_steps; s += kTiles) {   // n_steps is the same for the whole workgroup
-            iter(std::integral_constant<int, 0>{}, s);
-            if (s + 1 < n_steps) iter(std::integral_constant<int, 1>{}, s + 1);
-            if (s + 2 < n_steps) iter(std::integral_constant<int, 2>{}, s + 2);
-            if (s + 3 < n_steps) iter(std::integral_constant<int, 3>{}, s + 3);
-        }
-        if (computes) {   // the PV products of the last step, whose tokens past the end count for nothing
-            if (n_steps * kStep > kv_end) mask_v_tail<D>(sd, kv_end - ((n_steps - 1) * kStep + 8 * q));
+        for (int c = 0; c < QT; ++c) {
 #pragma unroll
-            for (int c = 0; c < QT; ++c) pv_accumulate<D, F32OUT>(sd, pr[c], acc[c]);
+            for (int nt = 0; nt < D / 16; ++nt) acc[c].o[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            acc[c].m = -INFINITY;
+            acc[c].l = 0.f;
         }
-    } else {
-        if (computes) read_k(std::integral_constant<int, 0>{});
-        for (int32_t s = 0; s < n_steps; s += kTiles) {
-            step(std::integral_constant<int, 0>{}, s);
-            if (s + 1 < n_steps) step(std::integral_constant<int, 1>{}, s + 1);
-            if (s + 2 < n_steps) step(std::integral_constant<int, 2>{}, s + 2);
-            if (s + 3 < n_steps) step(std::integral_constant<int, 3>{}, s + 3);
-        }
+    }
+
+    // ---- the exact loop: all of the first 8 waves copy, the reference moves whenever a step's
+    // scores rise above it.
+    cs = copy_sources<D>(k_pages, v_pages, h, prm.log2P);
+    copy_to(std::integral_constant<int, 0>{}, 0, pages_of(0));
+    copy_to(std::integral_constant<int, 1>{}, kStep, pages_of(kStep));
+    copy_to(std::integral_constant<int, 2>{}, 2 * kStep, pages_of(2 * kStep));
+    pg_next = pages_of(kAhead * kStep);
+    copies_landed_but<D, kAhead - 2>();
+    __builtin_amdgcn_s_barrier();
+    if (computes) read_k(std::integral_constant<int, 0>{});
+    for (int32_t s = 0; s < n_steps; s += kTiles) {
+        step(std::integral_constant<int, 0>{}, s);
+        if (s + 1 < n_steps) step(std::integral_constant<int, 1>{}, s + 1);
+        if (s + 2 < n_steps) step(std::integral_constant<int, 2>{}, s + 2);
+        if (s + 3 < n_steps) step(std::integral_constant<int, 3>{}, s + 3);
     }
 
     if (!computes) return;

@@ -112,6 +112,23 @@ def test_prefill_bf16_out_custom_scale_and_long_prefix():
     assert err <= 2e-2
 
 
+@pytest.mark.parametrize("Hq,Hkv", [(28, 4), (16, 2), (10, 2), (4, 1)])
+@pytest.mark.parametrize("scale", [1.0, 8.0])
+def test_prefill_scores_that_rise_far_above_those_of_the_first_tokens(Hq, Hkv, scale):
+    # The fast loop of the kernel keeps the softmax reference of a column at the maximum over the
+    # first 32 tokens and runs the block again through the exact loop when the row sums show that
+    # later scores rose too far above it.  With unit-variance q and k the logits have a standard
+    # deviation of 11 * scale nats: scale 1 gives probabilities of thousands relative to the
+    # reference (kept by the fast loop), scale 8 overflows it (the exact loop must take over).
+    # Head counts: one, two and four copying waves, and all waves copying (8 heads per KV head).
+    chunks = [(0, 0, 300), (1, 40, 130), (2, 0, 33)]
+    err = _run_case(Hq, Hkv, 128, 16, chunks, seed=31, scale=scale)
+    say(f"  prefill Hq={Hq} Hkv={Hkv} scale={scale}: max abs err {err:.2e}")
+    assert err <= 1e-4
+    err = _run_case(Hq, Hkv, 128, 16, chunks, seed=32, out_dtype=torch.bfloat16, scale=scale)
+    assert err <= 2e-2
+
+
 def test_prefill_no_tokens_is_a_no_op_and_bad_desc_is_rejected():
     Hq, Hkv, D, P = 8, 2, 64, 16
     pool = Pool(2, 64, Hkv, D, P, 1)
