@@ -213,11 +213,9 @@ __device__ __forceinline__ StepProbs softmax_probs_lazy(const float (&sv)[8], fl
     return out;
 }
 
-// The two halves of the lazy update on their own, for a kernel that overlaps them with other
-// work.  move_reference: the reference of the columns goes to the exact running maximum
-// including this step's scores, sums and O^T are rescaled.  probs_of_exponents: t holds the
-// scores' exponents relative to the reference (log2 units); the probabilities of the step as PV
-// operands, their sum added to the running sum.
+// Parts of the update on their own, for a kernel that overlaps them with other work.
+// move_reference: the reference of the columns goes to the exact running maximum including this
+// step's scores, sums and O^T are rescaled.
 template <int D>
 __device__ __forceinline__ void move_reference(const float (&sv)[8], float scale_log2e, WaveAcc<D>& a) {
     float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
@@ -251,35 +249,6 @@ __device__ __forceinline__ StepProbs pack_probs(const float (&p)[8]) {
     out.alpha = 1.0f;
     return out;
 }
-template <int D, bool SPLIT>
-__device__ __forceinline__ StepProbs probs_of_exponents(const float (&t)[8], WaveAcc<D>& a) {
-    float p[8];
-    float psum = 0.f;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        p[j] = __builtin_amdgcn_exp2f(t[j]);
-        psum += p[j];
-    }
-    a.l += psum;
-    StepProbs out;
-    uint32_t hi[4], lo[4];
-#pragma unroll
-    for (int k2 = 0; k2 < 4; ++k2) {
-        hi[k2] = pack_bf16_rne(p[2 * k2], p[2 * k2 + 1]);
-        if (SPLIT) {
-            const float r0 = p[2 * k2] - __uint_as_float(hi[k2] << 16);
-            const float r1 = p[2 * k2 + 1] - __uint_as_float(hi[k2] & 0xFFFF0000u);
-            lo[k2] = pack_bf16_rne(r0, r1);
-        } else {
-            lo[k2] = 0u;
-        }
-    }
-    out.hi = as_bf16x8(make_uint4(hi[0], hi[1], hi[2], hi[3]));
-    out.lo = as_bf16x8(make_uint4(lo[0], lo[1], lo[2], lo[3]));
-    out.alpha = 1.0f;
-    return out;
-}
-
 // Second half: O^T = alpha O^T (skipped by the caller's test when no lane needs it) + V^T P^T.
 template <int D>
 __device__ __forceinline__ void rescale(WaveAcc<D>& a, float alpha) {
