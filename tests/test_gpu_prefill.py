@@ -129,6 +129,19 @@ def test_prefill_scores_that_rise_far_above_those_of_the_first_tokens(Hq, Hkv, s
     assert err <= 2e-2
 
 
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("P", [16, 32, 64])
+@pytest.mark.parametrize("G", [7, 5, 3])
+def test_prefill_every_page_size_with_one_two_and_four_copying_waves(D, P, G):
+    # 7, 5 and 3 query heads per KV head leave 1, 2 and 4 waves of the workgroup to do the copying;
+    # their addresses are written out per head_dim, page size and number of copying waves.
+    # Chunks that start inside a page and inside a 32-token step, on top of cached tokens.
+    chunks = [(0, 0, 150), (1, 21, 90), (2, 70, 37), (0, 150, 40)]
+    err = _run_case(2 * G, 2, D, P, chunks, seed=40 + G, num_slots=3)
+    say(f"  prefill G={G} D={D} P={P}: max abs err {err:.2e}")
+    assert err <= 1e-4
+
+
 def test_prefill_no_tokens_is_a_no_op_and_bad_desc_is_rejected():
     Hq, Hkv, D, P = 8, 2, 64, 16
     pool = Pool(2, 64, Hkv, D, P, 1)
