@@ -23,12 +23,12 @@
 // SIMD's vector issue port for about two thirds of the time the matrix core needs for it, a vector
 // instruction of another kind fits in the rest only in part, a wave issues at most one
 // instruction every eight cycles or so, and a branch on a vector result waits for the wave's
-// matrix instructions in flight.  Workgroups of 8 waves (up to 8 query heads per KV head)
-// therefore run a loop built around that: spare waves do all the copying, the computing waves
+// matrix instructions in flight.  Workgroups of 8 waves (up to 8 query heads per KV head) with a
+// bf16 result therefore run a loop built around that: spare waves do all the copying, the computing waves
 // run the three parts of a step (scores, softmax, PV) of three consecutive steps side by side in
 // one straight-line stretch, and the softmax reference is fixed after the first step and verified
 // once at the end (a workgroup that fails the check repeats its block in the exact loop, which
-// is also the loop of workgroups of 16 waves).
+// is also the loop of workgroups of 16 waves and of fp32 results).
 #include <cmath>
 #include <type_traits>
 
@@ -614,7 +614,10 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     // pieces per lane and step for head_dim 128) and fetch the page ids, and the computing waves
     // issue nothing but their products, the softmax and their LDS reads.  With 8 heads all
     // waves copy, two pieces per lane.
-    const int32_t n_cp = MAXW != 8 ? 0 : prm.G <= 4 ? 4 : prm.G <= 6 ? 2 : prm.G == 7 ? 1 : 0;
+    // (An fp32 result splits every probability into two bf16 parts: half again as many PV products
+    // and not enough registers for three steps side by side; it keeps the exact loop below.)
+    constexpr bool kPipelined = MAXW == 8 && !F32OUT;
+    const int32_t n_cp = !kPipelined ? 0 : prm.G <= 4 ? 4 : prm.G <= 6 ? 2 : prm.G == 7 ? 1 : 0;
     const int32_t first_cp = 8 - n_cp;
 
     const bool shared_copy = n_cp == 0;
@@ -630,7 +633,7 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
         __builtin_amdgcn_s_barrier();
     };
 
-    if constexpr (MAXW == 8) {
+    if constexpr (kPipelined) {
         if (n_cp > 0 && wave >= first_cp) {
             // ---- a copying wave (page size and number of copying waves as compile-time constants,
             // so that everything about a piece but its page is an immediate)
