@@ -261,22 +261,34 @@ def prefill_bench(args, torch, rb, wl):
                 off=torch.from_numpy(off).cuda(),
                 out=torch.empty((T, Hq, D), dtype=torch.bfloat16, device="cuda"),
                 pairs=sum(n * st + n * (n + 1) // 2 for _, st, n in ch), T=T))
-        run = lambda: [rb.roll_prefill_attn(c["q"], c["k"], c["v"], c["slot"], c["start"], c["off"], k_pages, v_pages,
-                                            page_table, c["out"], P) for c in calls]
+        kernel_events = []   # one pair per attention launch of the timed steps
+
+        def run(timed=False):
+            for c in calls:
+                if timed:
+                    kernel_events.append((rb.ProfEvent(), rb.ProfEvent()))
+                    rb.roll_prof_prefill_events(*kernel_events[-1])
+                rb.roll_prefill_attn(c["q"], c["k"], c["v"], c["slot"], c["start"], c["off"], k_pages, v_pages,
+                                     page_table, c["out"], P)
         for _ in range(args.warmup):
             run()
         e0, e1 = rb.ProfEvent(), rb.ProfEvent()
         torch.cuda.synchronize()
         e0.record()
         for _ in range(args.steps):
-            run()
+            run(timed=True)
         e1.record()
         torch.cuda.synchronize()
+        rb.roll_prof_prefill_events(None, None)
         ms = e0.elapsed_ms(e1) / args.steps
+        launch_ms = [a.elapsed_ms(b) for a, b in kernel_events]
+        attn_ms = sum(launch_ms) / args.steps     # the attention launches of one pass over the prompts
         tokens, pairs = sum(c["T"] for c in calls), sum(c["pairs"] for c in calls)
         flops = 4.0 * D * Hq * pairs
         res[name] = {"ms": ms, "tokens": tokens, "launch_pairs": len(calls), "tokens_per_s": tokens / (ms * 1e-3),
-                     "TFLOPs": flops / (ms * 1e-3) / 1e12}
+                     "TFLOPs_of_the_call": flops / (ms * 1e-3) / 1e12,
+                     "attn_launch_ms": spread(launch_ms), "attn_ms_per_pass": attn_ms,
+                     "TFLOPs": flops / (attn_ms * 1e-3) / 1e12}
         pool.close()
     head = res["long_prompts_8x8192_chunks_of_2048"]
     print(json.dumps({"metric": "prefill tokens/s (one attention layer, K/V written into pages)",
@@ -286,7 +298,11 @@ def prefill_bench(args, torch, rb, wl):
                       "config": {"workload": f"8 prompts x 8192 tokens in chunks of 2048, Hq={Hq} Hkv={Hkv} D={D} P={P}"},
                       "roofline": {"bound": "mfma", "kernel": "prefill_attn", "achieved": head["TFLOPs"],
                                    "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                                   "frac": head["TFLOPs"] / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+                                   "frac": head["TFLOPs"] / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                                   "launch_ms": head["attn_launch_ms"],
+                                   "note": "algorithmic flops of a pass / the attention launches' own time (events "
+                                           "around the kernel); with the K/V writer and the gaps between launches: "
+                                           f"{head['TFLOPs_of_the_call']:.0f} TFLOP/s"},
                       "per_workload": res}), flush=True)
 
 

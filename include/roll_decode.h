@@ -547,6 +547,9 @@ int64_t roll_sample_buffer_capacity(const roll_sample_buffer* buffer);
  * after the stream-K attention kernel, on the launch's stream (hipEvent_t
  * handles from roll_prof_event_create).  NULL, NULL switches it off again. */
 int roll_prof_attn_events(void* begin, void* end);
+/* The same for roll_prefill_attn: the events bracket its attention kernel (the
+ * launch after the K/V writer). */
+int roll_prof_prefill_events(void* begin, void* end);
 /*
  * Per-wave timestamps of the attention kernel, for a library built with
  * -DROLL_ATTN_TIMELINE only (the product build returns ROLL_ERR_INVALID_ARG).

@@ -36,7 +36,7 @@ EXPORTS = [
     "roll_sample_buffer_complete", "roll_sample_buffer_abort", "roll_sample_buffer_resume",
     "roll_sample_buffer_take_batch", "roll_sample_buffer_advance_version", "roll_sample_buffer_version",
     "roll_sample_buffer_outstanding", "roll_sample_buffer_capacity",
-    "roll_prof_attn_events", "roll_prof_attn_timeline", "roll_prof_kv_read_probe", "roll_prof_event_create", "roll_prof_event_destroy", "roll_prof_event_record",
+    "roll_prof_attn_events", "roll_prof_prefill_events", "roll_prof_attn_timeline", "roll_prof_kv_read_probe", "roll_prof_event_create", "roll_prof_event_destroy", "roll_prof_event_record",
     "roll_prof_event_elapsed_ms",
 ]
 
@@ -116,6 +116,7 @@ def lib():
         L.roll_decode_attn_workspace_check.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
         L.roll_decode_attn_static.argtypes = [C.c_void_p] * 6 + [C.POINTER(AttnDesc), C.c_void_p]
         L.roll_prof_attn_events.argtypes = [C.c_void_p, C.c_void_p]
+        L.roll_prof_prefill_events.argtypes = [C.c_void_p, C.c_void_p]
         L.roll_prof_attn_timeline.argtypes = [C.c_void_p, C.c_size_t]
         L.roll_prof_kv_read_probe.argtypes = [C.c_void_p] * 4 + [C.POINTER(AttnDesc), C.c_void_p, C.c_size_t,
                                               C.POINTER(C.c_int64), C.c_void_p]
@@ -529,6 +530,11 @@ def roll_prof_attn_events(begin: Optional["ProfEvent"], end: Optional["ProfEvent
     """The calling thread's next attention launches record these two events around the kernel;
     (None, None) switches that off."""
     _check(lib().roll_prof_attn_events(None if begin is None else begin.handle, None if end is None else end.handle))
+
+
+def roll_prof_prefill_events(begin: Optional["ProfEvent"], end: Optional["ProfEvent"]) -> None:
+    """The same for roll_prefill_attn: the events bracket its attention kernel."""
+    _check(lib().roll_prof_prefill_events(None if begin is None else begin.handle, None if end is None else end.handle))
 
 
 def roll_prof_attn_timeline(buffer: Optional[torch.Tensor]) -> None:

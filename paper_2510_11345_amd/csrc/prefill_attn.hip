@@ -750,6 +750,9 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     }
 }
 
+// Profiling events of the calling thread (roll_prof_prefill_events).
+thread_local hipEvent_t t_ev_begin = nullptr, t_ev_end = nullptr;
+
 int validate(const roll_prefill_desc* d) {
     if (!d) return roll::fail(ROLL_ERR_INVALID_ARG, "desc is NULL");
     if (d->num_chunks < 0 || d->num_tokens < 0) return roll::fail(ROLL_ERR_INVALID_ARG, "num_chunks and num_tokens must be >= 0");
@@ -825,6 +828,7 @@ extern "C" int roll_prefill_attn(const void* q, const void* k_new, const void* v
     const int64_t grid = blocks_bound * prm.Hkv;
     if (grid > INT32_MAX) return roll::fail(ROLL_ERR_INVALID_ARG, "too many query blocks");
     const int threads = 64 * (prm.G > kCopyWaves ? prm.G : kCopyWaves);
+    if (t_ev_begin) ROLL_HIP_CHECK(hipEventRecord(t_ev_begin, stream));
 #define ROLL_LAUNCH_PREFILL(DIM, MAXW, QT, F32)                                                                \
     prefill_attn<DIM, MAXW, QT, F32><<<(unsigned)grid, threads, 0, stream>>>( \
         (const uint4*)q, (const uint4*)k_pages, (const uint4*)v_pages, page_table, chunk_slot, chunk_start,    \
@@ -844,5 +848,13 @@ extern "C" int roll_prefill_attn(const void* q, const void* k_new, const void* v
 #undef ROLL_LAUNCH_PREFILL_DIM
 #undef ROLL_LAUNCH_PREFILL
     ROLL_HIP_CHECK(hipGetLastError());
+    if (t_ev_end) ROLL_HIP_CHECK(hipEventRecord(t_ev_end, stream));
+    return ROLL_OK;
+}
+
+extern "C" int roll_prof_prefill_events(void* begin, void* end) {
+    if ((begin == nullptr) != (end == nullptr)) return roll::fail(ROLL_ERR_INVALID_ARG, "begin and end must both be set or both NULL");
+    t_ev_begin = (hipEvent_t)begin;
+    t_ev_end = (hipEvent_t)end;
     return ROLL_OK;
 }
