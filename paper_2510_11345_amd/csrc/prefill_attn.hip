@@ -276,11 +276,11 @@ __device__ __forceinline__ void copier_loop(uint4* tile0, uint4* tile1, uint4* t
     const int32_t v_oct_of_wave = __builtin_amdgcn_readfirstlane(cl / D);
     const uint4* v_head = v_pages + (int64_t)h * (P / 8) * D;
     const int32_t last_t0 = (n_steps - 1) * kStep;
-    StepPages pg_ahead = step_page_ids(pt_row, 0, LOG2P, max_pages, num_pages);   // page ids come one step early
-    auto copy_all = [&](int32_t step) {
+    auto ids_of = [&](int32_t step) {
+        return step_page_ids(pt_row, min(step * kStep, last_t0), LOG2P, max_pages, num_pages);
+    };
+    auto copy_all = [&](int32_t step, StepPages pg) {
         const int32_t t0 = min(step * kStep, last_t0);
-        const StepPages pg = pg_ahead;
-        pg_ahead = step_page_ids(pt_row, min((step + 1) * kStep, last_t0), LOG2P, max_pages, num_pages);
         uint4* tl = (step & 3) == 0 ? tile0 : (step & 3) == 1 ? tile1 : (step & 3) == 2 ? tile2 : tile3;
         uint4* dst = tl + cw * 64;
         const uint32_t in_page = (uint32_t)t0 & (uint32_t)(P - 1);   // 0 with 16-token pages
@@ -313,13 +313,19 @@ __device__ __forceinline__ void copier_loop(uint4* tile0, uint4* tile1, uint4* t
     // The copying wave shares its SIMD with a computing wave that started before it and would
     // otherwise win every issue slot; its few instructions per step go first.
     __builtin_amdgcn_s_setprio(3);
-    copy_all(0);
-    copy_all(1);
-    copy_all(2);
+    // The page ids of the first four steps in one round trip, then the copies back to back; in the
+    // loop the ids come one step early.
+    const StepPages pg0 = ids_of(0), pg1 = ids_of(1), pg2 = ids_of(2);
+    StepPages pg_ahead = ids_of(kAhead);
+    copy_all(0, pg0);
+    copy_all(1, pg1);
+    copy_all(2, pg2);
     landed_but_one();
     __builtin_amdgcn_s_barrier();
     for (int32_t s = 0; s < n_steps; ++s) {
-        copy_all(s + kAhead);
+        const StepPages pg = pg_ahead;
+        pg_ahead = ids_of(s + kAhead + 1);
+        copy_all(s + kAhead, pg);
         landed_but_one();
         __builtin_amdgcn_s_barrier();
     }
@@ -337,7 +343,7 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     static_assert(kTiles == 4 && kAhead == 3, "the step loop is written out for four tiles");
     __shared__ uint4 tile0[CopyPlan<D>::kPieces], tile1[CopyPlan<D>::kPieces], tile2[CopyPlan<D>::kPieces],
         tile3[CopyPlan<D>::kPieces];
-    __shared__ int32_t s_chunk, s_qb, s_found, s_redo;
+    __shared__ int32_t s_meta[8], s_found, s_redo;
 
     // Which (chunk, query block) is this workgroup's?  Blocks are numbered chunk after chunk;
     // the workgroups take them from the last one down, so that within a prompt the blocks
@@ -346,50 +352,80 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     const int32_t h = blockIdx.x % prm.Hkv;
     const int32_t wanted_from_end = blockIdx.x / prm.Hkv;
     const int32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // (What the search finds goes to the other waves through LDS together with the chunk's slot,
+    // start and offset, read in the same round trip as the lengths: every dependent trip to memory
+    // before the first product is time in which the compute unit does nothing, about a
+    // microsecond each.)
     if (wave == 0) {
-        int32_t total = 0;
-        for (int32_t base = 0; base < prm.C; base += 64) {
-            const int32_t c = base + lane;
-            const int32_t n = c < prm.C ? chunk_offset[c + 1] - chunk_offset[c] : 0;
-            int32_t incl = (n + kQBlock - 1) / kQBlock;
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                const int32_t v = __shfl_up(incl, d);
-                if (lane >= d) incl += v;
-            }
-            total += __shfl(incl, 63);
-        }
-        const int32_t wanted = total - 1 - wanted_from_end;
         if (lane == 0) { s_found = 0; s_redo = 0; }
-        int32_t carry = 0;
-        for (int32_t base = 0; base < prm.C && wanted >= 0; base += 64) {
-            const int32_t c = base + lane;
-            const int32_t n = c < prm.C ? chunk_offset[c + 1] - chunk_offset[c] : 0;
-            const int32_t nb = (n + kQBlock - 1) / kQBlock;
+        if (prm.C <= 64) {   // one round of 64 lanes holds all chunks: their arrays are read once
+            const bool in = lane < prm.C;
+            const int32_t o0 = in ? chunk_offset[lane] : 0, o1 = in ? chunk_offset[lane + 1] : 0;
+            const int32_t sl = in ? chunk_slot[lane] : 0, st = in ? chunk_start[lane] : 0;
+            const int32_t n = o1 - o0, nb = (n + kQBlock - 1) / kQBlock;
             int32_t incl = nb;
 #pragma unroll
             for (int d = 1; d < 64; d <<= 1) {
                 const int32_t v = __shfl_up(incl, d);
                 if (lane >= d) incl += v;
             }
-            const int32_t first = carry + incl - nb;
+            const int32_t wanted = __shfl(incl, 63) - 1 - wanted_from_end, first = incl - nb;
             if (wanted >= first && wanted < first + nb) {
-                s_chunk = c;
-                s_qb = wanted - first;
+                s_meta[0] = sl;
+                s_meta[1] = st;
+                s_meta[2] = o0;
+                s_meta[3] = n;
+                s_meta[4] = wanted - first;
                 s_found = 1;
             }
-            carry += __shfl(incl, 63);
+        } else {
+            int32_t total = 0;
+            for (int32_t base = 0; base < prm.C; base += 64) {
+                const int32_t c = base + lane;
+                const int32_t n = c < prm.C ? chunk_offset[c + 1] - chunk_offset[c] : 0;
+                int32_t incl = (n + kQBlock - 1) / kQBlock;
+#pragma unroll
+                for (int d = 1; d < 64; d <<= 1) {
+                    const int32_t v = __shfl_up(incl, d);
+                    if (lane >= d) incl += v;
+                }
+                total += __shfl(incl, 63);
+            }
+            const int32_t wanted = total - 1 - wanted_from_end;
+            int32_t carry = 0;
+            for (int32_t base = 0; base < prm.C && wanted >= 0; base += 64) {
+                const int32_t c = base + lane;
+                const int32_t o0 = c < prm.C ? chunk_offset[c] : 0, o1 = c < prm.C ? chunk_offset[c + 1] : 0;
+                const int32_t n = o1 - o0, nb = (n + kQBlock - 1) / kQBlock;
+                int32_t incl = nb;
+#pragma unroll
+                for (int d = 1; d < 64; d <<= 1) {
+                    const int32_t v = __shfl_up(incl, d);
+                    if (lane >= d) incl += v;
+                }
+                const int32_t first = carry + incl - nb;
+                if (wanted >= first && wanted < first + nb) {
+                    s_meta[0] = chunk_slot[c];
+                    s_meta[1] = chunk_start[c];
+                    s_meta[2] = o0;
+                    s_meta[3] = n;
+                    s_meta[4] = wanted - first;
+                    s_found = 1;
+                }
+                carry += __shfl(incl, 63);
+            }
         }
     }
     __syncthreads();
     if (!s_found) return;
     // (wave-uniform by construction; saying so keeps everything derived from them in scalar registers)
-    const int32_t c = __builtin_amdgcn_readfirstlane(s_chunk), qb = __builtin_amdgcn_readfirstlane(s_qb);
-
-    const int32_t slot = chunk_slot[c];
-    const int32_t n_c = chunk_offset[c + 1] - chunk_offset[c];
-    const int32_t tq0 = chunk_offset[c] + kQBlock * qb;       // first query token of the block
-    const int32_t pos0 = chunk_start[c] + kQBlock * qb;       // its position in the slot
+    const int32_t slot = __builtin_amdgcn_readfirstlane(s_meta[0]);
+    const int32_t chunk_first = __builtin_amdgcn_readfirstlane(s_meta[1]);
+    const int32_t chunk_off = __builtin_amdgcn_readfirstlane(s_meta[2]);
+    const int32_t n_c = __builtin_amdgcn_readfirstlane(s_meta[3]);
+    const int32_t qb = __builtin_amdgcn_readfirstlane(s_meta[4]);
+    const int32_t tq0 = chunk_off + kQBlock * qb;             // first query token of the block
+    const int32_t pos0 = chunk_first + kQBlock * qb;          // its position in the slot
     const int32_t nq = min(kQBlock, n_c - kQBlock * qb);      // query tokens in the block
     if (slot < 0 || slot >= prm.num_slots || pos0 < 0) return;
     int32_t kv_end = pos0 + nq;                               // tokens the last query sees
