@@ -134,7 +134,7 @@ def policy_loss_bench(args, torch, rb, wl):
         torch.cuda.empty_cache()
     big = out["4096_responses"]
     best = big["per_objective"]["ppo"]
-    print(json.dumps({"metric": "policy-loss tokens/s (value, derivative, IS weight, ragged means)",
+    return ({"metric": "policy-loss tokens/s (value, derivative, IS weight, ragged means)",
                       "value": best["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
                       "warmup": args.warmup, "ms_per_step": best["ms"], "higher_is_better": True,
                       "dtype": "f64 arithmetic on f32 data", "data": "synthetic",
@@ -144,7 +144,7 @@ def policy_loss_bench(args, torch, rb, wl):
                       "roofline": {"bound": "hbm", "kernel": "policy_loss_tokens", "achieved": best["GBps"],
                                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": best["GBps"] / HBM_PEAK_GBS,
                                    "traffic": None},
-                      "batches": out}), flush=True)
+                      "batches": out})
 
 
 def attn_timeline_bench(args, torch, rb, wl):
@@ -291,7 +291,7 @@ def prefill_bench(args, torch, rb, wl):
                      "TFLOPs": flops / (attn_ms * 1e-3) / 1e12}
         pool.close()
     head = res["long_prompts_8x8192_chunks_of_2048"]
-    print(json.dumps({"metric": "prefill tokens/s (one attention layer, K/V written into pages)",
+    return ({"metric": "prefill tokens/s (one attention layer, K/V written into pages)",
                       "value": head["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
                       "warmup": args.warmup, "ms_per_step": head["ms"], "higher_is_better": True,
                       "dtype": "bf16", "data": "synthetic",
@@ -303,7 +303,7 @@ def prefill_bench(args, torch, rb, wl):
                                    "note": "algorithmic flops of a pass / the attention launches' own time (events "
                                            "around the kernel); with the K/V writer and the gaps between launches: "
                                            f"{head['TFLOPs_of_the_call']:.0f} TFLOP/s"},
-                      "per_workload": res}), flush=True)
+                      "per_workload": res})
 
 
 def spread(xs):
@@ -564,10 +564,10 @@ def main():
         equal_rows_bench(args, torch, rb, wl, DecodeBatch)
         return
     if args.policy_loss:
-        policy_loss_bench(args, torch, rb, wl)
+        print(json.dumps(policy_loss_bench(args, torch, rb, wl)), flush=True)
         return
     if args.prefill:
-        prefill_bench(args, torch, rb, wl)
+        print(json.dumps(prefill_bench(args, torch, rb, wl)), flush=True)
         return
 
     K, W = args.steps, args.warmup
@@ -597,6 +597,20 @@ def main():
             k = C4_STEPS if name == "c4" else K
             say(f"bench: {name}, {k} steps")
             result["per_config"][name] = run_config(name, k, W, args, torch, rb, wl)
+        # the kernels beside the decode step (prefill of refilled prompts, the consumer of the recorded
+        # log-probs), a short run of each with its own roofline block; a failure here is reported in
+        # place of the figures and does not take the decode figures with it
+        result["other_kernels"] = {}
+        for name, fn, k, w in (("prefill_attn", prefill_bench, 10, 3), ("policy_loss", policy_loss_bench, 20, 3)):
+            say(f"bench: {name}, {k} steps")
+            sub = argparse.Namespace(**{**vars(args), "steps": k, "warmup": w})
+            try:
+                r = fn(sub, torch, rb, wl)
+                result["other_kernels"][name] = {key: r[key] for key in ("metric", "value", "unit", "steps", "warmup",
+                                                                         "ms_per_step", "dtype", "config", "roofline")}
+            except Exception as e:   # noqa: BLE001
+                result["other_kernels"][name] = {"error": f"{type(e).__name__}: {e}"}
+            torch.cuda.empty_cache()
     print(json.dumps(result), flush=True)
 
 
