@@ -151,6 +151,30 @@ def test_prefill_every_page_size_with_one_two_and_four_copying_waves(D, P, G):
     assert err <= 1e-4
 
 
+@pytest.mark.parametrize("case", range(8))
+def test_prefill_random_shapes_and_chunkings(case):
+    # Seeded draws of head counts (1 to 16 query heads per KV head), head_dim, page size, and of
+    # chunks with arbitrary starts and lengths (several chunks of one slot in a call follow each
+    # other), both result types.
+    rng = np.random.default_rng([77, case])
+    G = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8, 12, 16]))
+    Hkv = int(rng.choice([1, 2, 4]))
+    D = int(rng.choice([64, 128]))
+    P = int(rng.choice([16, 32, 64]))
+    chunks = []
+    for slot in range(int(rng.integers(2, 6))):
+        pos = int(rng.integers(0, 90))
+        for _ in range(int(rng.integers(1, 4))):
+            n = int(rng.integers(1, 120))
+            chunks.append((slot, pos, n))
+            pos += n
+    num_slots = max(c[0] for c in chunks) + 1
+    for dtype, tol in ((torch.bfloat16, 2e-2), (torch.float32, 1e-4)):
+        err = _run_case(G * Hkv, Hkv, D, P, chunks, seed=50 + case, out_dtype=dtype, num_slots=num_slots)
+        say(f"  prefill case {case}: G={G} Hkv={Hkv} D={D} P={P}, {len(chunks)} chunks, {dtype}: max abs err {err:.2e}")
+        assert err <= tol
+
+
 def test_prefill_no_tokens_is_a_no_op_and_bad_desc_is_rejected():
     Hq, Hkv, D, P = 8, 2, 64, 16
     pool = Pool(2, 64, Hkv, D, P, 1)
