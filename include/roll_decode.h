@@ -86,7 +86,7 @@ typedef enum roll_dtype { ROLL_BF16 = 0, ROLL_F32 = 1 } roll_dtype;
 /* HOST. Thread-local text of the last error on this thread ("" if none). */
 const char* roll_last_error(void);
 
-/* HOST. Library version, e.g. "0.2". */
+/* HOST. Library version, e.g. "0.3". */
 const char* roll_version(void);
 
 /* ------------------------------------------------------------------ */
