@@ -121,3 +121,58 @@ def test_config4_full_size_refill_loop(capsys):
             f"boundary-band mismatches {band}, {rb.roll_kv_fused_steps(b.pool)} steps in one launch")
     assert loop.refills >= 20 and checked_some >= 10
     loop.close()
+
+
+@pytest.mark.timeout(600)
+def test_prefill_full_size_sampled_tokens(capsys):
+    """bench.py --prefill's long-prompt workload in its launch configuration (8 prompts x 8192 tokens
+    in chunks of 2048, 7B-class heads, 16-token pages, side-by-side pools, bf16 result: blocks of up
+    to 256 steps in the pipelined loop).  The oracle cannot afford all 65536 tokens; it computes
+    sampled ones one by one, as decode steps over the slot's first pos + 1 tokens read from the
+    pools the library wrote: the first tokens, both sides of every chunk and step boundary, the
+    last token, of three slots."""
+    Hq, Hkv, D, P = 28, 4, 128, 16
+    n_slots, n, chunk = 8, 8192, 2048
+    max_pages = n // P
+    num_pages = n_slots * max_pages + 8
+    page_table = torch.empty((n_slots, max_pages), dtype=torch.int32, device="cuda")
+    seq_lens = torch.zeros((n_slots,), dtype=torch.int32, device="cuda")
+    pool = rb.KvPool(num_pages, P, n_slots, max_pages, page_table, seq_lens)
+    for s in range(n_slots):
+        rb.roll_kv_alloc(pool, s, n)
+    rb.roll_kv_commit(pool)
+    k_pages, v_pages = rb.new_kv_pools(num_pages, Hkv, D, P, fill=0)
+    T = n_slots * chunk
+    slot = torch.arange(n_slots, dtype=torch.int32, device="cuda")
+    off = torch.arange(n_slots + 1, dtype=torch.int32, device="cuda") * chunk
+    qs, outs = [], []
+    for ci, start in enumerate(range(0, n, chunk)):
+        q = wl.randn_bf16((T, Hq, D), 3, 40 + ci, "cuda")
+        k = wl.randn_bf16((T, Hkv, D), 3, 50 + ci, "cuda")
+        v = wl.randn_bf16((T, Hkv, D), 3, 60 + ci, "cuda")
+        out = torch.full((T, Hq, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+        rb.roll_prefill_attn(q, k, v, slot, torch.full((n_slots,), start, dtype=torch.int32, device="cuda"), off,
+                             k_pages, v_pages, page_table, out, P)
+        qs.append(q)
+        outs.append(out)
+        del k, v
+    torch.cuda.synchronize()
+    with capsys.disabled():
+        say("  prefill full size: 4 calls of 8 x 2048 tokens done, comparing sampled tokens with the oracle")
+    positions = [0, 1, 15, 16, 31, 32, 33, 2047, 2048, 2049, 2079, 2080, 4095, 4096, 5555, 6143, 6144, 8190, 8191]
+    samples = [(s, p) for s in (0, 3, 7) for p in positions]
+    table = np.full((n_slots, max_pages), -1, np.int32)
+    for s in range(n_slots):
+        pr = rb.roll_kv_slot_pages(pool, s)
+        table[s, :len(pr)] = pr
+    kb, vb = wl.bits(k_pages).reshape(-1), wl.bits(v_pages).reshape(-1)
+    q_rows = np.stack([wl.bits(qs[p // chunk][s * chunk + p % chunk]) for s, p in samples])
+    got = np.stack([outs[p // chunk][s * chunk + p % chunk].double().cpu().numpy() for s, p in samples])
+    want = oracle.decode_attn(np.ascontiguousarray(q_rows), kb, vb, np.ascontiguousarray(table[[s for s, _ in samples]]),
+                              np.array([p + 1 for _, p in samples], np.int32), Hq, Hkv, D, P)
+    assert not np.isnan(got).any()
+    err = np.abs(got - want).max(axis=(1, 2))
+    with capsys.disabled():
+        say(f"  prefill full size: {len(samples)} sampled tokens, max abs err {err.max():.2e} (bf16 result)")
+    assert err.max() <= 2e-2, [(samples[i], float(err[i])) for i in np.flatnonzero(err > 2e-2)]
+    pool.close()
