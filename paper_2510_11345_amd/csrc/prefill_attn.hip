@@ -545,7 +545,7 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     // and the (rare) move of the softmax reference, which first completes the pending PV products
     // because their probabilities are relative to the old reference.
     StepProbs pr[QT];
-    float sv[QT][8], t[QT][8];
+    float sv[QT][8];
     // K of step s + 1 is asked for at the start of the iteration; the stretch itself is fenced into
     // three parts so that the LDS reads stay where their latency is covered: PV products with the
     // exponents, exponentials, packing and sums, then the reads of V (into the registers the PV
