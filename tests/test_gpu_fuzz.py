@@ -1,6 +1,9 @@
 """Seeded random shapes and parameters for every GPU entry point against the oracle (needs an
-MI355X).  The fixed-case files pick their edge cases by hand; this one draws many small ones."""
+MI355X).  The fixed-case files pick their edge cases by hand; this one draws many small ones.
+ROLL_FUZZ_SEED=<n> draws another sweep and ROLL_FUZZ_ROUNDS=<k> makes it k times as long (give pytest
+a longer --timeout with it); without them the sweep is the same on every run."""
 import dataclasses
+import os
 
 import numpy as np
 import pytest
@@ -13,6 +16,9 @@ from paper_2510_11345_amd.harness import DecodeBatch
 from gpu_helpers import compare_sampling, oracle_attn, run_attn, say
 
 pytestmark = pytest.mark.gpu
+
+SEED = 1000 * int(os.environ.get("ROLL_FUZZ_SEED", "0"))
+ROUNDS = max(1, int(os.environ.get("ROLL_FUZZ_ROUNDS", "1")))
 
 HEADS = [(1, 1), (4, 1), (7, 1), (8, 2), (12, 4), (16, 16), (28, 4), (32, 2), (64, 8), (6, 3), (12, 6), (20, 5)]
 
@@ -31,9 +37,9 @@ def _draw_lengths(rng, B, cap):
 
 
 def test_decode_attention_random_cases():
-    rng = np.random.default_rng(101)
+    rng = np.random.default_rng(101 + SEED)
     worst32 = worst16 = 0.0
-    for case in range(24):
+    for case in range(24 * ROUNDS):
         Hq, Hkv = HEADS[rng.integers(0, len(HEADS))]
         D = int(rng.choice([64, 128]))
         P = int(rng.choice([16, 32, 64]))
@@ -59,12 +65,12 @@ def test_decode_attention_random_cases():
         else:
             worst16 = max(worst16, err)
             assert err <= 2e-2, (case, Hq, Hkv, D, P, B, cap, err)
-    say(f"  decode attention, 24 random cases: worst abs err {worst32:.2e} (fp32 out), {worst16:.2e} (bf16 out)")
+    say(f"  decode attention, {24 * ROUNDS} random cases: worst abs err {worst32:.2e} (fp32 out), {worst16:.2e} (bf16 out)")
 
 
 def test_fused_steps_random_cases():
-    rng = np.random.default_rng(202)
-    for case in range(8):
+    rng = np.random.default_rng(202 + SEED)
+    for case in range(8 * ROUNDS):
         Hq, Hkv = HEADS[rng.integers(0, len(HEADS))]
         D = int(rng.choice([64, 128]))
         P = int(rng.choice([16, 32, 64]))
@@ -93,9 +99,9 @@ def test_fused_steps_random_cases():
 
 
 def test_prefill_random_cases():
-    rng = np.random.default_rng(303)
+    rng = np.random.default_rng(303 + SEED)
     worst = 0.0
-    for case in range(12):
+    for case in range(12 * ROUNDS):
         Hq, Hkv = HEADS[rng.integers(0, len(HEADS))]
         D = int(rng.choice([64, 128]))
         P = int(rng.choice([16, 32, 64]))
@@ -104,7 +110,7 @@ def test_prefill_random_cases():
         for slot in range(n_slots):
             pos = int(rng.integers(0, 60)) if rng.random() < 0.5 else 0
             for _ in range(int(rng.integers(0, 3))):                 # up to two chunks of a slot, in order
-                n = int(rng.choice([0, 1, 7, 8, 9, 16, 31, 32, 33, 50, 120]))
+                n = int(rng.choice([0, 1, 7, 8, 9, 16, 31, 32, 33, 50, 120, 257, 400]))
                 chunks.append((slot, pos, n))
                 pos += n
             need[slot] = pos
@@ -152,12 +158,12 @@ def test_prefill_random_cases():
         assert np.array_equal(wl.bits(k_pages).reshape(-1), kp_host), case
         assert np.array_equal(wl.bits(v_pages).reshape(-1), vp_host), case
         pool.close()
-    say(f"  prefill, 12 random cases: worst abs err {worst:.2e} (fp32 out)")
+    say(f"  prefill, {12 * ROUNDS} random cases: worst abs err {worst:.2e} (fp32 out)")
 
 
 def test_sampling_random_cases():
-    rng = np.random.default_rng(404)
-    for case in range(16):
+    rng = np.random.default_rng(404 + SEED)
+    for case in range(16 * ROUNDS):
         B = int(rng.integers(1, 12))
         V = int(rng.choice([3, 17, 256, 1000, 4099, 32003]))
         dtype = "bf16" if rng.random() < 0.6 else "f32"
