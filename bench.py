@@ -306,6 +306,88 @@ def prefill_bench(args, torch, rb, wl):
                       "per_workload": res})
 
 
+def prefill_timeline_bench(args, torch, rb, wl):
+    """A prefill workgroup's life: needs the library built with
+    `python -m paper_2510_11345_amd.build --timeline`, whose kernel stamps the 100 MHz clock per
+    workgroup at entry, with its block found, before and after its step loop and after its stores,
+    with the compute unit it ran on.  For three prompt shapes (7B-class heads, bf16 result) the
+    last call of a pass is profiled: what a block costs beyond its steps (before the loop, after
+    it, and the time between the end of one workgroup and the first instruction of the next on
+    the same compute unit), the step time inside the loop, and how the launch's span divides."""
+    cfg = wl.CONFIGS["c2"]
+    Hq, Hkv, D, P = cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.page_size
+    out = {}
+    for n_slots, n, chunk in ((8, 8192, 2048), (8, 4096, 4096), (8, 2048, 2048)):
+        max_pages = n // P
+        num_pages = n_slots * max_pages + 8
+        page_table = torch.empty((n_slots, max_pages), dtype=torch.int32, device="cuda")
+        seq_lens = torch.zeros((n_slots,), dtype=torch.int32, device="cuda")
+        pool = rb.KvPool(num_pages, P, n_slots, max_pages, page_table, seq_lens)
+        for s_ in range(n_slots):
+            rb.roll_kv_alloc(pool, s_, n)
+        rb.roll_kv_commit(pool)
+        k_pages, v_pages = rb.new_kv_pools(num_pages, Hkv, D, P, fill=0)
+        T = n_slots * chunk
+        q = wl.randn_bf16((T, Hq, D), args.seed, 40, "cuda")
+        k = wl.randn_bf16((T, Hkv, D), args.seed, 41, "cuda")
+        v = wl.randn_bf16((T, Hkv, D), args.seed, 42, "cuda")
+        slot = torch.arange(n_slots, dtype=torch.int32, device="cuda")
+        starts = [torch.full((n_slots,), s0, dtype=torch.int32, device="cuda") for s0 in range(0, n, chunk)]
+        off = torch.arange(n_slots + 1, dtype=torch.int32, device="cuda") * chunk
+        res = torch.empty((T, Hq, D), dtype=torch.bfloat16, device="cuda")
+
+        def call(st):
+            rb.roll_prefill_attn(q, k, v, slot, st, off, k_pages, v_pages, page_table, res, P)
+        for _ in range(args.warmup):
+            for st in starts:
+                call(st)
+        torch.cuda.synchronize()
+        n_wg = (T // 32 + n_slots) * Hkv
+        buf = torch.zeros((n_wg, 8), dtype=torch.int64, device="cuda")
+        rb.roll_prof_prefill_timeline(buf)
+        call(starts[-1])
+        torch.cuda.synchronize()
+        rb.roll_prof_prefill_timeline(None)
+        t = buf.cpu().numpy()
+        t = t[t[:, 7] == 1]
+        ts = (t[:, :5] - t[:, 0].min()) * 0.01                     # microseconds
+        steps = t[:, 6].astype(np.float64)
+        hw, xcc = t[:, 5] & 0xFFFFFFFF, t[:, 5] >> 32
+        cu = xcc * 4096 + ((hw >> 13) & 7) * 512 + ((hw >> 12) & 1) * 256 + ((hw >> 8) & 15)   # XCC, SE, SH, CU
+        units = np.unique(cu)
+        loop = ts[:, 3] - ts[:, 2]
+        gaps, in_wg, idle_end = [], [], []
+        for c in units:
+            m = np.flatnonzero(cu == c)
+            o = m[np.argsort(ts[m, 0])]
+            gaps.extend((ts[o[1:], 0] - ts[o[:-1], 4]).tolist())
+            in_wg.append(float((ts[o, 4] - ts[o, 0]).sum()))
+            idle_end.append(float(ts[:, 4].max() - ts[o[-1], 4]))
+        span = float(ts[:, 4].max())
+        pairs = n_slots * (chunk * (n - chunk) + chunk * (chunk + 1) // 2)
+        pct = lambda a: [float(np.percentile(a, p_)) for p_ in (10, 50, 90)]
+        out[f"{n_slots}x{n}_last_chunk_of_{chunk}"] = {
+            "workgroups": int(len(t)), "compute_units": int(len(units)), "steps_min_max": [int(steps.min()), int(steps.max())],
+            "span_us": span, "TFLOPs_over_span": 4.0 * D * Hq * pairs / span / 1e6,
+            "entry_to_block_found_us_p10_p50_p90": pct(ts[:, 1] - ts[:, 0]),
+            "entry_to_loop_us_p10_p50_p90": pct(ts[:, 2] - ts[:, 0]),
+            "loop_end_to_stores_done_us_p10_p50_p90": pct(ts[:, 4] - ts[:, 3]),
+            "between_workgroups_on_a_unit_us_p10_p50_p90": pct(gaps) if gaps else None,
+            "between_workgroups_min_us": float(np.min(gaps)) if gaps else None,
+            "loop_us_per_step_mean": float(loop.sum() / steps.sum()),
+            # a step is 32 queries x 32 keys per query head of the group; all units in their loops at once
+            "TFLOPs_inside_the_loops": 4.0 * D * (Hq // Hkv) * 32 * 32 * steps.sum() / loop.sum() * len(units) / 1e6,
+            "share_of_span_in_workgroups": float(np.mean(in_wg) / span),
+            "share_of_span_in_loops": float(loop.sum() / len(units) / span),
+            "idle_at_the_end_us_mean_max": [float(np.mean(idle_end)), float(np.max(idle_end))],
+        }
+        pool.close()
+    print(json.dumps({"metric": "per-workgroup timeline of the prefill attention launch (prefill_attn)", "unit": "us",
+                      "n_gpus": 1, "steps": 1, "warmup": args.warmup, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": f"prompts of 7B-class heads, Hq={Hq} Hkv={Hkv} D={D} P={P}, bf16 result"},
+                      "per_workload": out}), flush=True)
+
+
 def spread(xs):
     """mean, median, 10th and 90th percentile of a list of milliseconds."""
     a = np.asarray(xs, dtype=np.float64)
@@ -518,6 +600,9 @@ def main():
     ap.add_argument("--dense-pools", action="store_true",
                     help="K and V in two dense allocations and pages handed out one by one, instead of one "
                          "allocation with the K and V block of a page side by side and pages in runs of 32 / P")
+    ap.add_argument("--prefill-timeline", action="store_true",
+                    help="per-workgroup timestamps of the prefill attention launch on three prompt shapes; needs "
+                         "the library built with `python -m paper_2510_11345_amd.build --timeline`")
     ap.add_argument("--attn-timeline", action="store_true",
                     help="per-wave timestamps of the attention launch on --config (default c4): needs the "
                          "library built with `python -m paper_2510_11345_amd.build --timeline`")
@@ -534,10 +619,10 @@ def main():
     from paper_2510_11345_amd import binding as rb
     from paper_2510_11345_amd import workloads as wl
     from paper_2510_11345_amd.harness import DecodeBatch
-    if args.attn_timeline:
+    if args.attn_timeline or args.prefill_timeline:
         from paper_2510_11345_amd import build as hip_build
         if not os.path.exists(hip_build.TIMELINE_LIB):
-            print("bench.py --attn-timeline: build the instrumented library first: "
+            print("bench.py --attn-timeline / --prefill-timeline: build the instrumented library first: "
                   "python -m paper_2510_11345_amd.build --timeline", file=sys.stderr)
             sys.exit(1)
         rb.LIB_PATH = hip_build.TIMELINE_LIB
@@ -554,6 +639,9 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"pmc_calibration": "one device copy", "bytes_read": src.numel() * 4,
                           "bytes_written": dst.numel() * 4}))
+        return
+    if args.prefill_timeline:
+        prefill_timeline_bench(args, torch, rb, wl)
         return
     if args.attn_timeline:
         args.config = args.config or "c4"

@@ -86,7 +86,7 @@ typedef enum roll_dtype { ROLL_BF16 = 0, ROLL_F32 = 1 } roll_dtype;
 /* HOST. Thread-local text of the last error on this thread ("" if none). */
 const char* roll_last_error(void);
 
-/* HOST. Library version, e.g. "0.3". */
+/* HOST. Library version, e.g. "0.4". */
 const char* roll_version(void);
 
 /* ------------------------------------------------------------------ */
@@ -560,6 +560,18 @@ int roll_prof_prefill_events(void* begin, void* end);
  * SYNCHRONISES (a copy to a device symbol).
  */
 int roll_prof_attn_timeline(void* buffer, size_t buffer_bytes);
+/*
+ * Per-workgroup timestamps of the prefill attention kernel, for a library built
+ * with -DROLL_ATTN_TIMELINE only (the product build returns ROLL_ERR_INVALID_ARG).
+ * buffer: DEVICE, 8-byte aligned, 64 bytes per workgroup to record (workgroups
+ * numbered at or above buffer_bytes / 64 record nothing), or NULL to switch it
+ * off.  Wave 0 of every workgroup of the following roll_prefill_attn launches
+ * that takes the pipelined loop (bf16 result, up to 8 query heads per KV head)
+ * writes 8 words: the 100 MHz clock at entry, with its block found, before its
+ * first and after its last loop iteration, after its stores; XCC_ID << 32 |
+ * HW_ID; its steps; 1.  SYNCHRONISES (copies to device symbols).
+ */
+int roll_prof_prefill_timeline(void* buffer, size_t buffer_bytes);
 /*
  * Bandwidth ceiling of the decode step's access pattern (Section 1: decoding is
  * memory-bandwidth bound): enqueues ONE kernel that reads, through page_table,

@@ -50,6 +50,19 @@ constexpr int kAhead = kTiles - 1;
 // reference are harmless, beyond that products with V could overflow.
 constexpr float kSumLimit = 1.0995116e12f;   // 2^40
 
+// Built with -DROLL_ATTN_TIMELINE (paper_2510_11345_amd.build --timeline, a library of its own), wave 0
+// of every workgroup of prefill_attn that stores a result leaves eight 64-bit words in the buffer
+// handed to roll_prof_prefill_timeline: the constant 100 MHz clock at entry, when its block is
+// found, before the first and after the last iteration of the step loop, after its stores; the
+// hardware id (XCC_ID << 32 | HW_ID); its steps; 1.  The product build has none of this.
+#ifdef ROLL_ATTN_TIMELINE
+__device__ uint64_t* g_pf_timeline = nullptr;
+__device__ uint32_t g_pf_timeline_blocks = 0;
+#define ROLL_PF_STAMP(var) var = wall_clock64()
+#else
+#define ROLL_PF_STAMP(var) do { } while (0)
+#endif
+
 struct PrefillParams {
     int32_t C, T, Hq, Hkv, G;
     int32_t Hs;  // page stride of the pools in head blocks (Hkv when dense)
@@ -352,6 +365,10 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     const int32_t h = blockIdx.x % prm.Hkv;
     const int32_t wanted_from_end = blockIdx.x / prm.Hkv;
     const int32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#ifdef ROLL_ATTN_TIMELINE
+    uint64_t tl_entry, tl_found, tl_loop = 0, tl_done = 0;
+#endif
+    ROLL_PF_STAMP(tl_entry);
     // (What the search finds goes to the other waves through LDS together with the chunk's slot,
     // start and offset, read in the same round trip as the lengths: every dependent trip to memory
     // before the first product is time in which the compute unit does nothing, about a
@@ -418,6 +435,7 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     }
     __syncthreads();
     if (!s_found) return;
+    ROLL_PF_STAMP(tl_found);
     // (wave-uniform by construction; saying so keeps everything derived from them in scalar registers)
     const int32_t slot = __builtin_amdgcn_readfirstlane(s_meta[0]);
     const int32_t chunk_first = __builtin_amdgcn_readfirstlane(s_meta[1]);
@@ -717,12 +735,14 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
 #pragma unroll
                 for (int c = 0; c < QT; ++c) move_reference<D>(s0[c], prm.scale_log2e, acc[c]);
             }
+            ROLL_PF_STAMP(tl_loop);
             for (int32_t s = 0; s < n_steps; s += kTiles) {   // n_steps is the same for the whole workgroup
                 iter(std::integral_constant<int, 0>{}, s);
                 if (s + 1 < n_steps) iter(std::integral_constant<int, 1>{}, s + 1);
                 if (s + 2 < n_steps) iter(std::integral_constant<int, 2>{}, s + 2);
                 if (s + 3 < n_steps) iter(std::integral_constant<int, 3>{}, s + 3);
             }
+            ROLL_PF_STAMP(tl_done);
             if (computes) {   // the PV products of the last step, whose tokens past the end count for nothing
                 if (n_steps * kStep > kv_end) mask_v_tail<D>(sd, kv_end - ((n_steps - 1) * kStep + 8 * q));
                 bool suspect = false;
@@ -747,6 +767,22 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
                     store_result<D>(acc[c], out, idx, F32OUT);
                 }
             }
+#ifdef ROLL_ATTN_TIMELINE
+            if (wave == 0 && lane == 0 && g_pf_timeline != nullptr && blockIdx.x < g_pf_timeline_blocks) {
+                uint32_t hw, xcc;
+                asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
+                asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+                uint64_t* o = g_pf_timeline + 8 * (size_t)blockIdx.x;
+                o[0] = tl_entry;
+                o[1] = tl_found;
+                o[2] = tl_loop;
+                o[3] = tl_done;
+                o[4] = wall_clock64();
+                o[5] = ((uint64_t)(xcc & 0xF) << 32) | hw;
+                o[6] = (uint64_t)n_steps;
+                o[7] = 1;
+            }
+#endif
             return;
         }
 #pragma unroll
@@ -886,6 +922,23 @@ extern "C" int roll_prefill_attn(const void* q, const void* k_new, const void* v
     ROLL_HIP_CHECK(hipGetLastError());
     if (t_ev_end) ROLL_HIP_CHECK(hipEventRecord(t_ev_end, stream));
     return ROLL_OK;
+}
+
+extern "C" int roll_prof_prefill_timeline(void* buffer, size_t buffer_bytes) {
+#ifdef ROLL_ATTN_TIMELINE
+    uint64_t* p = (uint64_t*)buffer;
+    const size_t blocks = buffer ? buffer_bytes / (8 * sizeof(uint64_t)) : 0;
+    const uint32_t n = blocks > UINT32_MAX ? UINT32_MAX : (uint32_t)blocks;
+    if (buffer && !roll::aligned(buffer, 8)) return roll::fail(ROLL_ERR_INVALID_ARG, "timeline buffer must be 8-byte aligned");
+    ROLL_HIP_CHECK(hipMemcpyToSymbol(HIP_SYMBOL(g_pf_timeline_blocks), &n, sizeof n));
+    ROLL_HIP_CHECK(hipMemcpyToSymbol(HIP_SYMBOL(g_pf_timeline), &p, sizeof p));
+    return ROLL_OK;
+#else
+    (void)buffer;
+    (void)buffer_bytes;
+    return roll::fail(ROLL_ERR_INVALID_ARG, "this library was built without ROLL_ATTN_TIMELINE "
+                                            "(python -m paper_2510_11345_amd.build --timeline builds one with it)");
+#endif
 }
 
 extern "C" int roll_prof_prefill_events(void* begin, void* end) {

@@ -268,6 +268,9 @@ def test_static_entry_point_and_workspace_check_reject_bad_arguments_on_the_host
     assert L.roll_prof_attn_events(None, None) == 0
     assert L.roll_prof_prefill_events(None, 16) == -1
     assert L.roll_prof_prefill_events(None, None) == 0
+    # the product library has no timestamps in its kernels and says so
+    assert L.roll_prof_attn_timeline(None, 0) == -1
+    assert L.roll_prof_prefill_timeline(None, 0) == -1
     # the decode step checks its pointers and workspace before it touches the allocator's pending changes
     pool = host_pool()
     rb.roll_kv_alloc(pool, 0, 3)
