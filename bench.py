@@ -226,15 +226,19 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix-core peak
 def prefill_bench(args, torch, rb, wl):
     """Tokens/s of roll_prefill_attn on prompts with the 7B-class head shape of c2 / c4.  Two
     workloads: the refill queue's prompt lengths (128..1024, 64 prompts in one call) and long
-    prompts (8 x 8192, prefilled in chunks of 2048).  Matrix-core roofline on the algorithmic
-    flops of causal attention: 4 D Hq per (query, visible key) pair."""
+    prompts (8 x 8192, prefilled in chunks of 2048); the long prompts once more with 32 query
+    heads on 8 KV heads (4 per KV head: workgroups of two spans of query tokens).  Matrix-core
+    roofline on the algorithmic flops of causal attention: 4 D Hq per (query, visible key) pair."""
     import numpy as np
     cfg = wl.CONFIGS["c2"]
-    Hq, Hkv, D, P = cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.page_size
+    D, P = cfg.head_dim, cfg.page_size
     rng = np.random.default_rng([args.seed, 0x505245])
     res = {}
-    for name, lens, chunk in [("refill_prompts_64x128..1024", rng.integers(128, 1025, size=64), None),
-                              ("long_prompts_8x8192_chunks_of_2048", np.full(8, 8192), 2048)]:
+    for name, lens, chunk, heads in [
+            ("refill_prompts_64x128..1024", rng.integers(128, 1025, size=64), None, (cfg.num_q_heads, cfg.num_kv_heads)),
+            ("long_prompts_8x8192_chunks_of_2048", np.full(8, 8192), 2048, (cfg.num_q_heads, cfg.num_kv_heads)),
+            ("long_prompts_8x8192_chunks_of_2048_Hq32_Hkv8", np.full(8, 8192), 2048, (32, 8))]:
+        Hq, Hkv = heads
         n_slots, cap = len(lens), int(lens.max())
         max_pages = (cap + P - 1) // P
         num_pages = n_slots * max_pages + 8
@@ -285,12 +289,13 @@ def prefill_bench(args, torch, rb, wl):
         attn_ms = sum(launch_ms) / args.steps     # the attention launches of one pass over the prompts
         tokens, pairs = sum(c["T"] for c in calls), sum(c["pairs"] for c in calls)
         flops = 4.0 * D * Hq * pairs
-        res[name] = {"ms": ms, "tokens": tokens, "launch_pairs": len(calls), "tokens_per_s": tokens / (ms * 1e-3),
+        res[name] = {"Hq": Hq, "Hkv": Hkv, "ms": ms, "tokens": tokens, "launch_pairs": len(calls), "tokens_per_s": tokens / (ms * 1e-3),
                      "TFLOPs_of_the_call": flops / (ms * 1e-3) / 1e12,
                      "attn_launch_ms": spread(launch_ms), "attn_ms_per_pass": attn_ms,
                      "TFLOPs": flops / (attn_ms * 1e-3) / 1e12}
         pool.close()
     head = res["long_prompts_8x8192_chunks_of_2048"]
+    Hq, Hkv = cfg.num_q_heads, cfg.num_kv_heads
     return ({"metric": "prefill tokens/s (one attention layer, K/V written into pages)",
                       "value": head["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
                       "warmup": args.warmup, "ms_per_step": head["ms"], "higher_is_better": True,

@@ -551,6 +551,16 @@ int roll_prof_attn_events(void* begin, void* end);
  * launch after the K/V writer). */
 int roll_prof_prefill_events(void* begin, void* end);
 /*
+ * With up to 4 query heads per KV head a prefill workgroup takes up to 8 / G spans
+ * of 32 query tokens (2 for G = 3) instead of one, so that more of its waves
+ * compute; how many is chosen from the size of the launch (a small launch keeps
+ * more, lighter workgroups).  This sets the rule for the calling thread's
+ * roll_prefill_attn calls: 0 = by launch size (the default), 1 = always the most,
+ * -1 = always one (for tests and measurements; results are the same to rounding
+ * order).  HOST; ROLL_ERR_INVALID_ARG for any other value.
+ */
+int roll_prof_prefill_spans(int32_t policy);
+/*
  * Per-wave timestamps of the attention kernel, for a library built with
  * -DROLL_ATTN_TIMELINE only (the product build returns ROLL_ERR_INVALID_ARG).
  * buffer: DEVICE, 8-byte aligned, >= 1024 waves * 8 * 8 bytes, or NULL to switch

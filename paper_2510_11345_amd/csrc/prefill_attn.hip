@@ -10,7 +10,9 @@
 // Unlike decoding this is a dense contraction: the query tokens of one head share every K/V
 // byte, and the G query heads of a KV head share it again.  One workgroup therefore takes
 // (chunk, block of 32 query tokens, KV head); wave g of it owns query head g of the group and
-// holds the query tokens as the columns of two MFMA tiles.  Each 32-token step of K and V is
+// holds the query tokens as the columns of two MFMA tiles.  (With up to 4 heads per KV head the
+// block is several spans of 32 tokens, one wave per head and span, so that the waves of the
+// workgroup all have work.)  Each 32-token step of K and V is
 // copied once per workgroup from the pages into LDS in 16-byte pieces with global_load_lds (the
 // page layouts are already the A-operand layouts; the pieces are ordered so that consecutive
 // lanes read consecutive pieces and the LDS reads are conflict free), into a ring of tiles with
@@ -43,6 +45,7 @@ using namespace roll::attn;
 constexpr int kTile = 16;         // query tokens per MFMA column tile
 constexpr int kCopyWaves = 8;     // the first 8 waves of a workgroup copy K/V (workgroups have at least 8)
 constexpr int kCopyThreads = 64 * kCopyWaves;
+constexpr int kComputeUnits = 256;   // of an MI355X (only how many query tokens a workgroup takes depends on it)
 constexpr int kTiles = 4;         // LDS ring: the step in use and three steps of copies in flight
 constexpr int kAhead = kTiles - 1;
 // A row sum at or above this after the loop that never moves the softmax reference (or a NaN)
@@ -65,6 +68,7 @@ __device__ uint32_t g_pf_timeline_blocks = 0;
 
 struct PrefillParams {
     int32_t C, T, Hq, Hkv, G;
+    int32_t S;   // spans of query tokens per workgroup: wave w computes head w % G of span w / G
     int32_t Hs;  // page stride of the pools in head blocks (Hkv when dense)
     int32_t log2P, max_pages, num_pages, num_slots;
     int32_t out_f32;
@@ -361,7 +365,8 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     // Which (chunk, query block) is this workgroup's?  Blocks are numbered chunk after chunk;
     // the workgroups take them from the last one down, so that within a prompt the blocks
     // with the longest prefixes start first.  Wave 0 counts the blocks of 64 chunks at a time.
-    constexpr int kQBlock = kTile * QT;   // query tokens per workgroup
+    constexpr int kSpan = kTile * QT;          // query tokens per wave
+    const int32_t kQBlock = kSpan * prm.S;      // query tokens per workgroup
     const int32_t h = blockIdx.x % prm.Hkv;
     const int32_t wanted_from_end = blockIdx.x / prm.Hkv;
     const int32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -452,17 +457,24 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     const int32_t n_steps = (kv_end + kStep - 1) / kStep;
     const int32_t* pt_row = page_table + (int64_t)slot * prm.max_pages;
 
+    // With few query heads per KV head a workgroup takes several spans of query tokens, so that
+    // its waves (and both issue slots of every SIMD) have work: wave w computes head w % G of span
+    // w / G.  All spans run the block's steps; the steps past a span's own last token are masked
+    // like the diagonal.
+    const int32_t span = __builtin_amdgcn_readfirstlane(wave / prm.G), head = __builtin_amdgcn_readfirstlane(wave % prm.G);
+    const int32_t tq0_w = tq0 + kSpan * span, pos0_w = pos0 + kSpan * span;   // the wave's first query token, its position
+    const int32_t nq_w = min(kSpan, nq - kSpan * span);                         // the wave's query tokens
     const int32_t r = lane & 15, q = lane >> 4;
-    const bool computes = wave < prm.G;                       // the other waves only copy
+    const bool computes = span < prm.S && nq_w > 0;           // the other waves only copy (or wait)
     int32_t pq[QT];                                           // newest position column r of tile c sees
     bf16x8_t qf[QT][D / 32];
     WaveAcc<D> acc[QT];
 #pragma unroll
     for (int c = 0; c < QT; ++c) {
-        const int32_t col = kTile * c + r < nq ? kTile * c + r : nq - 1;   // padding columns shadow the last query
-        pq[c] = pos0 + col;
+        const int32_t col = kTile * c + r < nq_w ? kTile * c + r : nq_w - 1;   // padding columns shadow the last query
+        pq[c] = pos0_w + col;
         if (computes) {
-            const uint4* qrow = q16 + ((int64_t)(tq0 + col) * prm.Hq + (int64_t)h * prm.G + wave) * (D / 8) + q;
+            const uint4* qrow = q16 + ((int64_t)(tq0_w + col) * prm.Hq + (int64_t)h * prm.G + head) * (D / 8) + q;
 #pragma unroll
             for (int kk = 0; kk < D / 32; ++kk) qf[c][kk] = as_bf16x8(qrow[kk * 4]);
         }
@@ -527,7 +539,7 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
 #pragma unroll
             for (int c = 0; c < QT; ++c) qk_scores<D>(qf[c], sd, sv[c]);
             read_k(std::integral_constant<int, (kI + 1) % kTiles>{});
-            if (t0 + kStep - 1 > pos0) {   // the step reaches past the first query's position: causal mask
+            if (t0 + kStep - 1 > pos0_w) {   // the step reaches past the first query's position: causal mask
                 const int32_t first = t0 + 8 * q;
 #pragma unroll
                 for (int c = 0; c < QT; ++c)
@@ -604,7 +616,7 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     // workgroup runs its block again through the exact loop below.
     auto products = [&](auto I, int32_t s) {
         const int32_t t0 = s * kStep;
-        if (t0 + kStep - 1 > pos0) {   // the step reaches past the first query's position: causal mask
+        if (t0 + kStep - 1 > pos0_w) {   // the step reaches past the first query's position: causal mask
             const int32_t first = t0 + 8 * q;
 #pragma unroll
             for (int c = 0; c < QT; ++c)
@@ -671,7 +683,8 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     // (An fp32 result splits every probability into two bf16 parts: half again as many PV products
     // and not enough registers for three steps side by side; it keeps the exact loop below.)
     constexpr bool kPipelined = MAXW == 8 && !F32OUT;
-    const int32_t n_cp = !kPipelined ? 0 : prm.G <= 4 ? 4 : prm.G <= 6 ? 2 : prm.G == 7 ? 1 : 0;
+    const int32_t n_busy = prm.G * prm.S;   // waves with a head and a span
+    const int32_t n_cp = !kPipelined ? 0 : n_busy <= 4 ? 4 : n_busy <= 6 ? 2 : n_busy == 7 ? 1 : 0;
     const int32_t first_cp = 8 - n_cp;
 
     const bool shared_copy = n_cp == 0;
@@ -762,8 +775,8 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
 #pragma unroll
             for (int c = 0; c < QT; ++c) {
                 acc[c].l = sum_over_q(acc[c].l);
-                if (kTile * c + r < nq) {
-                    const int64_t idx = ((int64_t)(tq0 + kTile * c + r) * prm.Hq + (int64_t)h * prm.G + wave) * D + 4 * q;
+                if (kTile * c + r < nq_w) {
+                    const int64_t idx = ((int64_t)(tq0_w + kTile * c + r) * prm.Hq + (int64_t)h * prm.G + head) * D + 4 * q;
                     store_result<D>(acc[c], out, idx, F32OUT);
                 }
             }
@@ -815,8 +828,8 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
 #pragma unroll
     for (int c = 0; c < QT; ++c) {
         acc[c].l = sum_over_q(acc[c].l);
-        if (kTile * c + r < nq) {
-            const int64_t idx = ((int64_t)(tq0 + kTile * c + r) * prm.Hq + (int64_t)h * prm.G + wave) * D + 4 * q;
+        if (kTile * c + r < nq_w) {
+            const int64_t idx = ((int64_t)(tq0_w + kTile * c + r) * prm.Hq + (int64_t)h * prm.G + head) * D + 4 * q;
             store_result<D>(acc[c], out, idx, F32OUT);
         }
     }
@@ -824,6 +837,8 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
 
 // Profiling events of the calling thread (roll_prof_prefill_events).
 thread_local hipEvent_t t_ev_begin = nullptr, t_ev_end = nullptr;
+// How the calling thread's launches choose the spans per workgroup (roll_prof_prefill_spans).
+thread_local int32_t t_span_policy = 0;
 
 int validate(const roll_prefill_desc* d) {
     if (!d) return roll::fail(ROLL_ERR_INVALID_ARG, "desc is NULL");
@@ -894,7 +909,28 @@ extern "C" int roll_prefill_attn(const void* q, const void* k_new, const void* v
     // Groups of up to 8 query heads keep two column tiles (32 query tokens) per wave; larger
     // groups have half the register budget per wave and keep one.
     const int qt = prm.G <= 8 ? 2 : 1;
-    const int q_block = kTile * qt;
+    // Up to 4 query heads per KV head: up to 8 / G spans of query tokens per workgroup (2 for
+    // G = 3), so that more of the workgroup's 8 waves compute.  A compute unit holds one workgroup;
+    // what it gets done grows with the waves that compute, one for one up to a wave per SIMD and
+    // by about a sixth from there to two per SIMD (measured, 8 x 4096 tokens: 4 -> 8 waves
+    // +14..23 %, 2 -> 8 +52 %, 1 -> 8 x 2.5).  The spans are the power of two for which
+    // (workgroups, at most one per compute unit) x (that yield) is largest: a small launch is
+    // better off with more, lighter workgroups.
+    prm.S = 1;
+    if (prm.G <= 4 && t_span_policy >= 0) {
+        const int most = prm.G == 3 ? 2 : 8 / prm.G;
+        auto yield = [](int waves) { return waves <= 4 ? (double)waves : 4.0 + 0.15 * (waves - 4); };
+        double best = 0.0;
+        for (int spans = 1; spans <= most; spans *= 2) {
+            const int64_t wgs = (((int64_t)prm.T + kTile * qt * spans - 1) / (kTile * qt * spans) + prm.C) * prm.Hkv;
+            const double score = (double)(wgs < kComputeUnits ? wgs : kComputeUnits) * yield(prm.G * spans);
+            if (score > best || (t_span_policy > 0 && spans == most)) {
+                best = score;
+                prm.S = spans;
+            }
+        }
+    }
+    const int q_block = kTile * qt * prm.S;
     // At most ceil(T / q_block) + C query blocks (each chunk ends with at most one partial block).
     const int64_t blocks_bound = ((int64_t)prm.T + q_block - 1) / q_block + prm.C;
     const int64_t grid = blocks_bound * prm.Hkv;
@@ -939,6 +975,12 @@ extern "C" int roll_prof_prefill_timeline(void* buffer, size_t buffer_bytes) {
     return roll::fail(ROLL_ERR_INVALID_ARG, "this library was built without ROLL_ATTN_TIMELINE "
                                             "(python -m paper_2510_11345_amd.build --timeline builds one with it)");
 #endif
+}
+
+extern "C" int roll_prof_prefill_spans(int32_t policy) {
+    if (policy < -1 || policy > 1) return roll::fail(ROLL_ERR_INVALID_ARG, "policy must be -1, 0 or 1");
+    t_span_policy = policy;
+    return ROLL_OK;
 }
 
 extern "C" int roll_prof_prefill_events(void* begin, void* end) {

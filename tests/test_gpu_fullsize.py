@@ -124,14 +124,16 @@ def test_config4_full_size_refill_loop(capsys):
 
 
 @pytest.mark.timeout(600)
-def test_prefill_full_size_sampled_tokens(capsys):
-    """bench.py --prefill's long-prompt workload in its launch configuration (8 prompts x 8192 tokens
-    in chunks of 2048, 7B-class heads, 16-token pages, side-by-side pools, bf16 result: blocks of up
-    to 256 steps in the pipelined loop).  The oracle cannot afford all 65536 tokens; it computes
-    sampled ones one by one, as decode steps over the slot's first pos + 1 tokens read from the
-    pools the library wrote: the first tokens, both sides of every chunk and step boundary, the
-    last token, of three slots."""
-    Hq, Hkv, D, P = 28, 4, 128, 16
+@pytest.mark.parametrize("Hq,Hkv", [(28, 4), (32, 8)])
+def test_prefill_full_size_sampled_tokens(capsys, Hq, Hkv):
+    """bench.py --prefill's long-prompt workloads in their launch configuration (8 prompts x 8192
+    tokens in chunks of 2048, 16-token pages, side-by-side pools, bf16 result: blocks of up to 256
+    steps in the pipelined loop; 7B-class heads, and 32 heads on 8, whose workgroups take two spans
+    of query tokens in a launch of this size).  The oracle cannot afford all 65536 tokens; it
+    computes sampled ones one by one, as decode steps over the slot's first pos + 1 tokens read
+    from the pools the library wrote: the first tokens, both sides of every chunk, span and step
+    boundary, the last token, of three slots."""
+    D, P = 128, 16
     n_slots, n, chunk = 8, 8192, 2048
     max_pages = n // P
     num_pages = n_slots * max_pages + 8
@@ -159,7 +161,8 @@ def test_prefill_full_size_sampled_tokens(capsys):
     torch.cuda.synchronize()
     with capsys.disabled():
         say("  prefill full size: 4 calls of 8 x 2048 tokens done, comparing sampled tokens with the oracle")
-    positions = [0, 1, 15, 16, 31, 32, 33, 2047, 2048, 2049, 2079, 2080, 4095, 4096, 5555, 6143, 6144, 8190, 8191]
+    positions = [0, 1, 15, 16, 31, 32, 33, 63, 64, 2047, 2048, 2049, 2079, 2080, 2111, 2112, 4095, 4096, 5555, 6143,
+                 6144, 8190, 8191]
     samples = [(s, p) for s in (0, 3, 7) for p in positions]
     table = np.full((n_slots, max_pages), -1, np.int32)
     for s in range(n_slots):
