@@ -227,7 +227,7 @@ def prefill_bench(args, torch, rb, wl):
     """Tokens/s of roll_prefill_attn on prompts with the 7B-class head shape of c2 / c4.  Two
     workloads: the refill queue's prompt lengths (128..1024, 64 prompts in one call) and long
     prompts (8 x 8192, prefilled in chunks of 2048); the long prompts once more with 32 query
-    heads on 8 KV heads (4 per KV head: workgroups of two spans of query tokens).  Matrix-core
+    heads on 8 KV heads (4 per KV head: a workgroup's seven computing waves span two or three spans of query tokens).  Matrix-core
     roofline on the algorithmic flops of causal attention: 4 D Hq per (query, visible key) pair."""
     import numpy as np
     cfg = wl.CONFIGS["c2"]
@@ -350,8 +350,10 @@ def prefill_timeline_bench(args, torch, rb, wl):
         n_wg = (T // 32 + n_slots) * Hkv
         buf = torch.zeros((n_wg, 8), dtype=torch.int64, device="cuda")
         rb.roll_prof_prefill_timeline(buf)
+        rb.roll_prof_prefill_units(Hq // Hkv)     # a span with all its heads per workgroup (what a launch of this size gets anyway)
         call(starts[-1])
         torch.cuda.synchronize()
+        rb.roll_prof_prefill_units(0)
         rb.roll_prof_prefill_timeline(None)
         t = buf.cpu().numpy()
         t = t[t[:, 7] == 1]

@@ -86,7 +86,7 @@ typedef enum roll_dtype { ROLL_BF16 = 0, ROLL_F32 = 1 } roll_dtype;
 /* HOST. Thread-local text of the last error on this thread ("" if none). */
 const char* roll_last_error(void);
 
-/* HOST. Library version, e.g. "0.4". */
+/* HOST. Library version, e.g. "0.5". */
 const char* roll_version(void);
 
 /* ------------------------------------------------------------------ */
@@ -551,15 +551,17 @@ int roll_prof_attn_events(void* begin, void* end);
  * launch after the K/V writer). */
 int roll_prof_prefill_events(void* begin, void* end);
 /*
- * With up to 4 query heads per KV head a prefill workgroup takes up to 8 / G spans
- * of 32 query tokens (2 for G = 3) instead of one, so that more of its waves
- * compute; how many is chosen from the size of the launch (a small launch keeps
- * more, lighter workgroups).  This sets the rule for the calling thread's
- * roll_prefill_attn calls: 0 = by launch size (the default), 1 = always the most,
- * -1 = always one (for tests and measurements; results are the same to rounding
- * order).  HOST; ROLL_ERR_INVALID_ARG for any other value.
+ * A prefill workgroup computes U units, one per wave, where a unit is (span of 32
+ * query tokens of a chunk, query head of the KV head's group) and a chunk's units
+ * are dealt out span after span.  For groups of up to 8 heads U is chosen per
+ * launch from its size (7 computing waves and a copying one for a large launch
+ * with a bf16 result, fewer for a small one); this fixes it for the calling
+ * thread's roll_prefill_attn calls: units = 1 .. 8, or 0 for the choice per launch
+ * (for tests and measurements; results are the same to rounding order).  Groups
+ * above 8 heads always take one span with all its heads.  HOST;
+ * ROLL_ERR_INVALID_ARG for any other value.
  */
-int roll_prof_prefill_spans(int32_t policy);
+int roll_prof_prefill_units(int32_t units);
 /*
  * Per-wave timestamps of the attention kernel, for a library built with
  * -DROLL_ATTN_TIMELINE only (the product build returns ROLL_ERR_INVALID_ARG).

@@ -36,7 +36,7 @@ EXPORTS = [
     "roll_sample_buffer_complete", "roll_sample_buffer_abort", "roll_sample_buffer_resume",
     "roll_sample_buffer_take_batch", "roll_sample_buffer_advance_version", "roll_sample_buffer_version",
     "roll_sample_buffer_outstanding", "roll_sample_buffer_capacity",
-    "roll_prof_attn_events", "roll_prof_prefill_events", "roll_prof_attn_timeline", "roll_prof_prefill_timeline", "roll_prof_prefill_spans", "roll_prof_kv_read_probe", "roll_prof_event_create", "roll_prof_event_destroy", "roll_prof_event_record",
+    "roll_prof_attn_events", "roll_prof_prefill_events", "roll_prof_attn_timeline", "roll_prof_prefill_timeline", "roll_prof_prefill_units", "roll_prof_kv_read_probe", "roll_prof_event_create", "roll_prof_event_destroy", "roll_prof_event_record",
     "roll_prof_event_elapsed_ms",
 ]
 
@@ -119,7 +119,7 @@ def lib():
         L.roll_prof_prefill_events.argtypes = [C.c_void_p, C.c_void_p]
         L.roll_prof_attn_timeline.argtypes = [C.c_void_p, C.c_size_t]
         L.roll_prof_prefill_timeline.argtypes = [C.c_void_p, C.c_size_t]
-        L.roll_prof_prefill_spans.argtypes = [C.c_int32]
+        L.roll_prof_prefill_units.argtypes = [C.c_int32]
         L.roll_prof_kv_read_probe.argtypes = [C.c_void_p] * 4 + [C.POINTER(AttnDesc), C.c_void_p, C.c_size_t,
                                               C.POINTER(C.c_int64), C.c_void_p]
         L.roll_decode_attn_ranges.argtypes = [C.POINTER(AttnDesc), C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
@@ -545,10 +545,10 @@ def roll_prof_attn_timeline(buffer: Optional[torch.Tensor]) -> None:
     _check(lib().roll_prof_attn_timeline(_dev(buffer), 0 if buffer is None else buffer.numel() * buffer.element_size()))
 
 
-def roll_prof_prefill_spans(policy: int) -> None:
-    """Spans of query tokens per prefill workgroup for head groups of up to 4: 0 = by launch size
-    (the default), 1 = always several, -1 = always one.  Applies to the calling thread."""
-    _check(lib().roll_prof_prefill_spans(policy))
+def roll_prof_prefill_units(units: int) -> None:
+    """Units (span of query tokens x query head) per prefill workgroup for head groups of up to 8:
+    1 .. 8, or 0 for the choice per launch (the default).  Applies to the calling thread."""
+    _check(lib().roll_prof_prefill_units(units))
 
 
 def roll_prof_prefill_timeline(buffer: Optional[torch.Tensor]) -> None:

@@ -9,7 +9,7 @@ char* error_buffer() {
 }  // namespace roll
 
 extern "C" const char* roll_last_error(void) { return roll::error_buffer(); }
-extern "C" const char* roll_version(void) { return "0.4"; }
+extern "C" const char* roll_version(void) { return "0.5"; }
 
 extern "C" int roll_prof_event_create(void** event) {
     if (!event) return roll::fail(ROLL_ERR_INVALID_ARG, "event is NULL");

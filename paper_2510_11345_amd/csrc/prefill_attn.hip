@@ -8,11 +8,11 @@
 // two layouts the decode kernel streams.
 //
 // Unlike decoding this is a dense contraction: the query tokens of one head share every K/V
-// byte, and the G query heads of a KV head share it again.  One workgroup therefore takes
-// (chunk, block of 32 query tokens, KV head); wave g of it owns query head g of the group and
-// holds the query tokens as the columns of two MFMA tiles.  (With up to 4 heads per KV head the
-// block is several spans of 32 tokens, one wave per head and span, so that the waves of the
-// workgroup all have work.)  Each 32-token step of K and V is
+// byte, and the G query heads of a KV head share it again.  A wave's work is a unit: a span of
+// 32 query tokens of a chunk for one query head, the tokens held as the columns of two MFMA
+// tiles.  A chunk's units of one KV head, span after span and head after head, are dealt out U to
+// a workgroup (7 computing waves and one that copies for a large launch, whatever G is: a
+// workgroup's units may lie in several spans).  Each 32-token step of K and V is
 // copied once per workgroup from the pages into LDS in 16-byte pieces with global_load_lds (the
 // page layouts are already the A-operand layouts; the pieces are ordered so that consecutive
 // lanes read consecutive pieces and the LDS reads are conflict free), into a ring of tiles with
@@ -68,7 +68,7 @@ __device__ uint32_t g_pf_timeline_blocks = 0;
 
 struct PrefillParams {
     int32_t C, T, Hq, Hkv, G;
-    int32_t S;   // spans of query tokens per workgroup: wave w computes head w % G of span w / G
+    int32_t U;   // units per workgroup: a unit is (span of 32 or 16 query tokens, query head of the group)
     int32_t Hs;  // page stride of the pools in head blocks (Hkv when dense)
     int32_t log2P, max_pages, num_pages, num_slots;
     int32_t out_f32;
@@ -366,7 +366,9 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     // the workgroups take them from the last one down, so that within a prompt the blocks
     // with the longest prefixes start first.  Wave 0 counts the blocks of 64 chunks at a time.
     constexpr int kSpan = kTile * QT;          // query tokens per wave
-    const int32_t kQBlock = kSpan * prm.S;      // query tokens per workgroup
+    // A chunk's units, span after span and head after head within a span, are dealt out U to a
+    // workgroup; a chunk of n tokens has this many workgroups:
+    auto blocks_of = [&](int32_t n) { return (((n + kSpan - 1) / kSpan) * prm.G + prm.U - 1) / prm.U; };
     const int32_t h = blockIdx.x % prm.Hkv;
     const int32_t wanted_from_end = blockIdx.x / prm.Hkv;
     const int32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -384,7 +386,7 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
             const bool in = lane < prm.C;
             const int32_t o0 = in ? chunk_offset[lane] : 0, o1 = in ? chunk_offset[lane + 1] : 0;
             const int32_t sl = in ? chunk_slot[lane] : 0, st = in ? chunk_start[lane] : 0;
-            const int32_t n = o1 - o0, nb = (n + kQBlock - 1) / kQBlock;
+            const int32_t n = o1 - o0, nb = blocks_of(n);
             int32_t incl = nb;
 #pragma unroll
             for (int d = 1; d < 64; d <<= 1) {
@@ -405,7 +407,7 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
             for (int32_t base = 0; base < prm.C; base += 64) {
                 const int32_t c = base + lane;
                 const int32_t n = c < prm.C ? chunk_offset[c + 1] - chunk_offset[c] : 0;
-                int32_t incl = (n + kQBlock - 1) / kQBlock;
+                int32_t incl = blocks_of(n);
 #pragma unroll
                 for (int d = 1; d < 64; d <<= 1) {
                     const int32_t v = __shfl_up(incl, d);
@@ -418,7 +420,7 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
             for (int32_t base = 0; base < prm.C && wanted >= 0; base += 64) {
                 const int32_t c = base + lane;
                 const int32_t o0 = c < prm.C ? chunk_offset[c] : 0, o1 = c < prm.C ? chunk_offset[c + 1] : 0;
-                const int32_t n = o1 - o0, nb = (n + kQBlock - 1) / kQBlock;
+                const int32_t n = o1 - o0, nb = blocks_of(n);
                 int32_t incl = nb;
 #pragma unroll
                 for (int d = 1; d < 64; d <<= 1) {
@@ -447,25 +449,27 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     const int32_t chunk_off = __builtin_amdgcn_readfirstlane(s_meta[2]);
     const int32_t n_c = __builtin_amdgcn_readfirstlane(s_meta[3]);
     const int32_t qb = __builtin_amdgcn_readfirstlane(s_meta[4]);
-    const int32_t tq0 = chunk_off + kQBlock * qb;             // first query token of the block
-    const int32_t pos0 = chunk_first + kQBlock * qb;          // its position in the slot
-    const int32_t nq = min(kQBlock, n_c - kQBlock * qb);      // query tokens in the block
-    if (slot < 0 || slot >= prm.num_slots || pos0 < 0) return;
-    int32_t kv_end = pos0 + nq;                               // tokens the last query sees
+    // The workgroup's units u0 .. u0 + U - 1 lie in the spans u0 / G .. (u0 + U - 1) / G of the chunk
+    // (the last workgroup of a chunk may run out of units before it runs out of waves).
+    const int32_t u0 = prm.U * qb, spans_c = (n_c + kSpan - 1) / kSpan;
+    const int32_t span_last = min((u0 + prm.U - 1) / prm.G, spans_c - 1);
+    if (slot < 0 || slot >= prm.num_slots || chunk_first < 0) return;
+    int32_t kv_end = chunk_first + min(n_c, kSpan * (span_last + 1));   // tokens the last query sees
     const int32_t cap = prm.max_pages << prm.log2P;
     kv_end = kv_end > cap ? cap : kv_end;
     const int32_t n_steps = (kv_end + kStep - 1) / kStep;
     const int32_t* pt_row = page_table + (int64_t)slot * prm.max_pages;
 
-    // With few query heads per KV head a workgroup takes several spans of query tokens, so that
-    // its waves (and both issue slots of every SIMD) have work: wave w computes head w % G of span
-    // w / G.  All spans run the block's steps; the steps past a span's own last token are masked
-    // like the diagonal.
-    const int32_t span = __builtin_amdgcn_readfirstlane(wave / prm.G), head = __builtin_amdgcn_readfirstlane(wave % prm.G);
-    const int32_t tq0_w = tq0 + kSpan * span, pos0_w = pos0 + kSpan * span;   // the wave's first query token, its position
-    const int32_t nq_w = min(kSpan, nq - kSpan * span);                         // the wave's query tokens
+    // Wave w computes unit u0 + w: whatever the number of query heads per KV head, U waves of the
+    // workgroup (and both issue slots of the SIMDs they sit on) have work.  The workgroup's units
+    // may lie in different spans; all of them run the steps of the last span, those past a
+    // span's own last token masked like the diagonal.
+    const int32_t wave_s = __builtin_amdgcn_readfirstlane(wave);
+    const int32_t span = (u0 + wave_s) / prm.G, head = (u0 + wave_s) - span * prm.G;
+    const int32_t tq0_w = chunk_off + kSpan * span, pos0_w = chunk_first + kSpan * span;   // the wave's first query token, its position
+    const int32_t nq_w = min(kSpan, n_c - kSpan * span);                                    // the wave's query tokens
     const int32_t r = lane & 15, q = lane >> 4;
-    const bool computes = span < prm.S && nq_w > 0;           // the other waves only copy (or wait)
+    const bool computes = wave_s < prm.U && span < spans_c;   // the other waves only copy (or wait)
     int32_t pq[QT];                                           // newest position column r of tile c sees
     bf16x8_t qf[QT][D / 32];
     WaveAcc<D> acc[QT];
@@ -683,8 +687,7 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     // (An fp32 result splits every probability into two bf16 parts: half again as many PV products
     // and not enough registers for three steps side by side; it keeps the exact loop below.)
     constexpr bool kPipelined = MAXW == 8 && !F32OUT;
-    const int32_t n_busy = prm.G * prm.S;   // waves with a head and a span
-    const int32_t n_cp = !kPipelined ? 0 : n_busy <= 4 ? 4 : n_busy <= 6 ? 2 : n_busy == 7 ? 1 : 0;
+    const int32_t n_cp = !kPipelined ? 0 : prm.U <= 4 ? 4 : prm.U <= 6 ? 2 : prm.U == 7 ? 1 : 0;
     const int32_t first_cp = 8 - n_cp;
 
     const bool shared_copy = n_cp == 0;
@@ -837,8 +840,8 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
 
 // Profiling events of the calling thread (roll_prof_prefill_events).
 thread_local hipEvent_t t_ev_begin = nullptr, t_ev_end = nullptr;
-// How the calling thread's launches choose the spans per workgroup (roll_prof_prefill_spans).
-thread_local int32_t t_span_policy = 0;
+// Units per workgroup of the calling thread's launches, 0 = chosen per launch (roll_prof_prefill_units).
+thread_local int32_t t_units = 0;
 
 int validate(const roll_prefill_desc* d) {
     if (!d) return roll::fail(ROLL_ERR_INVALID_ARG, "desc is NULL");
@@ -909,31 +912,36 @@ extern "C" int roll_prefill_attn(const void* q, const void* k_new, const void* v
     // Groups of up to 8 query heads keep two column tiles (32 query tokens) per wave; larger
     // groups have half the register budget per wave and keep one.
     const int qt = prm.G <= 8 ? 2 : 1;
-    // Up to 4 query heads per KV head: up to 8 / G spans of query tokens per workgroup (2 for
-    // G = 3), so that more of the workgroup's 8 waves compute.  A compute unit holds one workgroup;
-    // what it gets done grows with the waves that compute, one for one up to a wave per SIMD and
-    // by about a sixth from there to two per SIMD (measured, 8 x 4096 tokens: 4 -> 8 waves
-    // +14..23 %, 2 -> 8 +52 %, 1 -> 8 x 2.5).  The spans are the power of two for which
-    // (workgroups, at most one per compute unit) x (that yield) is largest: a small launch is
-    // better off with more, lighter workgroups.
-    prm.S = 1;
-    if (prm.G <= 4 && t_span_policy >= 0) {
-        const int most = prm.G == 3 ? 2 : 8 / prm.G;
-        auto yield = [](int waves) { return waves <= 4 ? (double)waves : 4.0 + 0.15 * (waves - 4); };
-        double best = 0.0;
-        for (int spans = 1; spans <= most; spans *= 2) {
-            const int64_t wgs = (((int64_t)prm.T + kTile * qt * spans - 1) / (kTile * qt * spans) + prm.C) * prm.Hkv;
-            const double score = (double)(wgs < kComputeUnits ? wgs : kComputeUnits) * yield(prm.G * spans);
-            if (score > best || (t_span_policy > 0 && spans == most)) {
-                best = score;
-                prm.S = spans;
+    // How many units (span of query tokens x query head) a workgroup takes, one per computing wave.
+    // A compute unit holds one workgroup of 8 waves; what it gets done depends on how many of
+    // them compute (measured on 8 x 4096 tokens with 1 .. 8 query heads per KV head and one span
+    // per workgroup, relative to one wave; 7 waves and a copying one beat 8 that share the
+    // copying).  The number is the one for which (workgroups, at most one per compute unit) x
+    // (that yield) is largest: a small launch is better off with more, lighter workgroups.
+    // Groups above 8 heads run workgroups of G waves, one span each.
+    const int span = kTile * qt;
+    const int64_t spans_bound = ((int64_t)prm.T + span - 1) / span + prm.C;   // each chunk ends with at most one partial span
+    auto workgroups = [&](int units) { return ((spans_bound * prm.G + units - 1) / units + prm.C) * prm.Hkv; };
+    prm.U = prm.G;
+    if (prm.G <= 8) {
+        static const double kYieldPipelined[9] = {0.0, 1.0, 2.0, 2.63, 3.4, 3.54, 4.18, 4.6, 4.44};
+        if (t_units >= 1) {
+            prm.U = t_units;
+        } else {
+            double best = 0.0;
+            for (int units = 1; units <= 8; ++units) {
+                const int64_t wgs = workgroups(units);
+                const double yield = prm.out_f32 ? (units <= 4 ? (double)units : 4.0 + 0.15 * (units - 4)) : kYieldPipelined[units];
+                const double score = (double)(wgs < kComputeUnits ? wgs : kComputeUnits) * yield;
+                if (score > best) {
+                    best = score;
+                    prm.U = units;
+                }
             }
         }
     }
-    const int q_block = kTile * qt * prm.S;
-    // At most ceil(T / q_block) + C query blocks (each chunk ends with at most one partial block).
-    const int64_t blocks_bound = ((int64_t)prm.T + q_block - 1) / q_block + prm.C;
-    const int64_t grid = blocks_bound * prm.Hkv;
+    // At most this many workgroups: every chunk's last one may be partly empty.
+    const int64_t grid = workgroups(prm.U);
     if (grid > INT32_MAX) return roll::fail(ROLL_ERR_INVALID_ARG, "too many query blocks");
     const int threads = 64 * (prm.G > kCopyWaves ? prm.G : kCopyWaves);
     if (t_ev_begin) ROLL_HIP_CHECK(hipEventRecord(t_ev_begin, stream));
@@ -977,9 +985,9 @@ extern "C" int roll_prof_prefill_timeline(void* buffer, size_t buffer_bytes) {
 #endif
 }
 
-extern "C" int roll_prof_prefill_spans(int32_t policy) {
-    if (policy < -1 || policy > 1) return roll::fail(ROLL_ERR_INVALID_ARG, "policy must be -1, 0 or 1");
-    t_span_policy = policy;
+extern "C" int roll_prof_prefill_units(int32_t units) {
+    if (units < 0 || units > 8) return roll::fail(ROLL_ERR_INVALID_ARG, "units must be 0 (chosen per launch) or 1 .. 8");
+    t_units = units;
     return ROLL_OK;
 }
 

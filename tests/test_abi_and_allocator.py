@@ -271,8 +271,8 @@ def test_static_entry_point_and_workspace_check_reject_bad_arguments_on_the_host
     # the product library has no timestamps in its kernels and says so
     assert L.roll_prof_attn_timeline(None, 0) == -1
     assert L.roll_prof_prefill_timeline(None, 0) == -1
-    assert L.roll_prof_prefill_spans(2) == -1
-    assert L.roll_prof_prefill_spans(-1) == 0 and L.roll_prof_prefill_spans(0) == 0
+    assert L.roll_prof_prefill_units(9) == -1 and L.roll_prof_prefill_units(-1) == -1
+    assert L.roll_prof_prefill_units(8) == 0 and L.roll_prof_prefill_units(0) == 0
     # the decode step checks its pointers and workspace before it touches the allocator's pending changes
     pool = host_pool()
     rb.roll_kv_alloc(pool, 0, 3)

@@ -128,8 +128,8 @@ def test_config4_full_size_refill_loop(capsys):
 def test_prefill_full_size_sampled_tokens(capsys, Hq, Hkv):
     """bench.py --prefill's long-prompt workloads in their launch configuration (8 prompts x 8192
     tokens in chunks of 2048, 16-token pages, side-by-side pools, bf16 result: blocks of up to 256
-    steps in the pipelined loop; 7B-class heads, and 32 heads on 8, whose workgroups take two spans
-    of query tokens in a launch of this size).  The oracle cannot afford all 65536 tokens; it
+    steps in the pipelined loop; 7B-class heads, and 32 heads on 8, whose workgroups of seven
+    computing waves reach over two or three spans of query tokens in a launch of this size).  The oracle cannot afford all 65536 tokens; it
     computes sampled ones one by one, as decode steps over the slot's first pos + 1 tokens read
     from the pools the library wrote: the first tokens, both sides of every chunk, span and step
     boundary, the last token, of three slots."""

@@ -141,11 +141,11 @@ def test_prefill_random_cases():
         kp_host, vp_host = wl.bits(k_pages).reshape(-1).copy(), wl.bits(v_pages).reshape(-1).copy()
         out_dtype = torch.float32 if rng.random() < 0.5 else torch.bfloat16
         out = torch.full((T, Hq, D), float("nan"), dtype=out_dtype, device="cuda")
-        # several spans of query tokens per workgroup (head groups of up to 4), one, or by launch size
-        rb.roll_prof_prefill_spans(int(rng.choice([1, 1, -1, 0])))
+        # units (span of query tokens x query head) per workgroup: fixed at 1 .. 8, or chosen by the launch
+        rb.roll_prof_prefill_units(int(rng.integers(0, 9)))
         rb.roll_prefill_attn(q, k_new, v_new, torch.from_numpy(cs).cuda(), torch.from_numpy(st).cuda(),
                              torch.from_numpy(off).cuda(), k_pages, v_pages, page_table, out, P)
-        rb.roll_prof_prefill_spans(0)
+        rb.roll_prof_prefill_units(0)
         torch.cuda.synchronize()
         table = np.full((n_slots, max_pages), -1, np.int32)
         for slot in range(n_slots):

@@ -175,40 +175,36 @@ def test_prefill_random_shapes_and_chunkings(case):
         assert err <= tol
 
 
-@pytest.fixture
-def several_spans():
-    """Workgroups of several spans of query tokens whatever the size of the launch (by default only
-    launches of 512 workgroups and more take them)."""
-    rb.roll_prof_prefill_spans(1)
-    yield
-    rb.roll_prof_prefill_spans(0)
+@pytest.mark.parametrize("units", [1, 2, 3, 5, 7, 8])
+@pytest.mark.parametrize("Hq,Hkv,D,P", [(4, 4, 128, 16), (2, 1, 64, 32), (6, 2, 128, 64), (8, 2, 128, 16), (5, 1, 64, 16),
+                                        (12, 2, 128, 32), (7, 1, 128, 16), (16, 2, 64, 64)])
+def test_prefill_units_per_workgroup(Hq, Hkv, D, P, units):
+    """A workgroup computes `units` consecutive (span of 32 query tokens, query head) units of a
+    chunk, one per wave, whatever the number of heads per KV head: its waves may sit in different
+    spans, a span's heads in different workgroups, and the last workgroup of a chunk may have
+    waves left over.  Prompts that end inside the first span, at a span's end, one token into the
+    next one; chunks on a cache at positions that are no multiples of anything; a prompt of one
+    token.  Both result types (the pipelined loop and the exact one) against the oracle, pools
+    bit for bit."""
+    rb.roll_prof_prefill_units(units)
+    try:
+        chunks = [(0, 0, 113), (1, 0, 64), (2, 0, 65), (3, 0, 255), (4, 0, 1), (5, 0, 96)]
+        for out_dtype, tol in ((torch.bfloat16, 2e-2), (torch.float32, 1e-4)):
+            err = _run_case(Hq, Hkv, D, P, chunks, 70 + Hq, out_dtype=out_dtype)
+            assert err <= tol, (out_dtype, err)
+        chunks = [(0, 0, 45), (1, 0, 130), (0, 45, 104), (1, 130, 33), (2, 0, 7)]
+        for out_dtype, tol in ((torch.bfloat16, 2e-2), (torch.float32, 1e-4)):
+            err = _run_case(Hq, Hkv, D, P, chunks, 71 + Hq, out_dtype=out_dtype)
+            assert err <= tol, (out_dtype, err)
+    finally:
+        rb.roll_prof_prefill_units(0)
 
 
-@pytest.mark.parametrize("D,P", [(128, 16), (64, 32), (128, 64)])
-@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (2, 1), (8, 4), (6, 2), (4, 1), (16, 4)])
-def test_prefill_workgroups_of_several_spans(several_spans, Hq, Hkv, D, P):
-    """Up to 4 query heads per KV head: a workgroup takes 8, 4, 2 or 2 spans of 32 query tokens, one
-    per wave and head.  Prompts that end inside the first span of a block, at a span's end, one
-    token into the next one and inside the last one; chunks on a cache at positions that are no
-    multiples of anything; a prompt of one token.  Both result types (the pipelined loop and the
-    exact one) against the oracle, pools bit for bit."""
-    block = 32 * (8 // (Hq // Hkv))
-    chunks = [(0, 0, block + 17), (1, 0, 64), (2, 0, 65), (3, 0, 2 * block - 1), (4, 0, 1), (5, 0, 3 * block)]
-    for out_dtype, tol in ((torch.bfloat16, 2e-2), (torch.float32, 1e-4)):
-        err = _run_case(Hq, Hkv, D, P, chunks, 70 + Hq, out_dtype=out_dtype)
-        assert err <= tol, (out_dtype, err)
-    chunks = [(0, 0, 45), (1, 0, 130), (0, 45, block + 40), (1, 130, 33), (2, 0, 7)]
-    for out_dtype, tol in ((torch.bfloat16, 2e-2), (torch.float32, 1e-4)):
-        err = _run_case(Hq, Hkv, D, P, chunks, 71 + Hq, out_dtype=out_dtype)
-        assert err <= tol, (out_dtype, err)
-
-
-def test_prefill_spans_rule_is_checked():
+def test_prefill_units_are_checked():
     with pytest.raises(rb.RollError):
-        rb.roll_prof_prefill_spans(2)
-    rb.roll_prof_prefill_spans(-1)
-    assert _run_case(4, 1, 128, 16, [(0, 0, 100)], 5) <= 1e-4
-    rb.roll_prof_prefill_spans(0)
+        rb.roll_prof_prefill_units(9)
+    with pytest.raises(rb.RollError):
+        rb.roll_prof_prefill_units(-1)
 
 
 def test_prefill_no_tokens_is_a_no_op_and_bad_desc_is_rejected():
