@@ -362,7 +362,7 @@ int roll_decode_step_attn(roll_kv_pool* pool, const void* k_new, const void* v_n
 typedef struct roll_prefill_desc {
     int32_t num_chunks;         /* C >= 0                                 */
     int32_t num_tokens;         /* T = chunk_offset[C] >= 0               */
-    int32_t num_q_heads;        /* Hq, multiple of num_kv_heads, G <= 16  */
+    int32_t num_q_heads;        /* Hq, a multiple of num_kv_heads         */
     int32_t num_kv_heads;       /* Hkv                                    */
     int32_t head_dim;           /* D: 64 or 128                           */
     int32_t page_size;          /* P: 16, 32 or 64                        */
@@ -553,12 +553,11 @@ int roll_prof_prefill_events(void* begin, void* end);
 /*
  * A prefill workgroup computes U units, one per wave, where a unit is (span of 32
  * query tokens of a chunk, query head of the KV head's group) and a chunk's units
- * are dealt out span after span.  For groups of up to 8 heads U is chosen per
- * launch from its size (7 computing waves and a copying one for a large launch
- * with a bf16 result, fewer for a small one); this fixes it for the calling
- * thread's roll_prefill_attn calls: units = 1 .. 8, or 0 for the choice per launch
- * (for tests and measurements; results are the same to rounding order).  Groups
- * above 8 heads always take one span with all its heads.  HOST;
+ * are dealt out span after span.  U is chosen per launch from its size (7
+ * computing waves and a copying one for a large launch with a bf16 result, fewer
+ * for a small one); this fixes it for the calling thread's roll_prefill_attn
+ * calls: units = 1 .. 8, or 0 for the choice per launch (for tests and
+ * measurements; results are the same to rounding order).  HOST;
  * ROLL_ERR_INVALID_ARG for any other value.
  */
 int roll_prof_prefill_units(int32_t units);

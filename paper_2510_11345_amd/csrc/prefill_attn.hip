@@ -30,7 +30,7 @@
 // run the three parts of a step (scores, softmax, PV) of three consecutive steps side by side in
 // one straight-line stretch, and the softmax reference is fixed after the first step and verified
 // once at the end (a workgroup that fails the check repeats its block in the exact loop, which
-// is also the loop of workgroups of 16 waves and of fp32 results).
+// is also the loop of fp32 results).
 #include <cmath>
 #include <type_traits>
 
@@ -43,7 +43,7 @@ namespace {
 using namespace roll::attn;
 
 constexpr int kTile = 16;         // query tokens per MFMA column tile
-constexpr int kCopyWaves = 8;     // the first 8 waves of a workgroup copy K/V (workgroups have at least 8)
+constexpr int kCopyWaves = 8;     // waves of a workgroup; where no wave is set aside for it, all of them copy K/V
 constexpr int kCopyThreads = 64 * kCopyWaves;
 constexpr int kComputeUnits = 256;   // of an MI355X (only how many query tokens a workgroup takes depends on it)
 constexpr int kTiles = 4;         // LDS ring: the step in use and three steps of copies in flight
@@ -348,11 +348,11 @@ __device__ __forceinline__ void copier_loop(uint4* tile0, uint4* tile1, uint4* t
     }
 }
 
-// MAXW: most waves a workgroup of this instance may have (the register budget follows from it).
-// QT: column tiles (16 query tokens each) per wave; every K/V piece read from LDS is used for all
-// of them.  F32OUT: fp32 result, P split in two bf16 parts; else bf16 result, P rounded once.
-template <int D, int MAXW, int QT, bool F32OUT>
-__global__ __launch_bounds__(64 * MAXW) void prefill_attn(
+// Workgroups of 8 waves (the register budget follows from it).  QT: column tiles (16 query tokens
+// each) per wave; every K/V piece read from LDS is used for all of them.  F32OUT: fp32 result, P
+// split in two bf16 parts; else bf16 result, P rounded once.
+template <int D, int QT, bool F32OUT>
+__global__ __launch_bounds__(kCopyThreads) void prefill_attn(
     const uint4* __restrict__ q16, const uint4* __restrict__ k_pages, const uint4* __restrict__ v_pages,
     const int32_t* __restrict__ page_table, const int32_t* __restrict__ chunk_slot,
     const int32_t* __restrict__ chunk_start, const int32_t* __restrict__ chunk_offset,
@@ -679,14 +679,14 @@ __global__ __launch_bounds__(64 * MAXW) void prefill_attn(
     };
     // Who copies.  A wave issues an instruction every eight cycles or so whatever its kind, and two
     // waves per SIMD do not fill the SIMD's issue port: what a computing wave does not have to
-    // issue is time won.  With fewer than 8 query heads per KV head the workgroup has waves
-    // that compute nothing; the last 1, 2 or 4 of them then do all the copying (16, 8 or 4
-    // pieces per lane and step for head_dim 128) and fetch the page ids, and the computing waves
-    // issue nothing but their products, the softmax and their LDS reads.  With 8 heads all
-    // waves copy, two pieces per lane.
+    // issue is time won.  With fewer than 8 units the workgroup has waves that compute nothing;
+    // the last 1, 2 or 4 of them then do all the copying (16, 8 or 4 pieces per lane and step
+    // for head_dim 128) and fetch the page ids, and the computing waves issue nothing but their
+    // products, the softmax and their LDS reads.  With 8 units all waves copy, two pieces per
+    // lane.
     // (An fp32 result splits every probability into two bf16 parts: half again as many PV products
     // and not enough registers for three steps side by side; it keeps the exact loop below.)
-    constexpr bool kPipelined = MAXW == 8 && !F32OUT;
+    constexpr bool kPipelined = !F32OUT;
     const int32_t n_cp = !kPipelined ? 0 : prm.U <= 4 ? 4 : prm.U <= 6 ? 2 : prm.U == 7 ? 1 : 0;
     const int32_t first_cp = 8 - n_cp;
 
@@ -848,8 +848,6 @@ int validate(const roll_prefill_desc* d) {
     if (d->num_chunks < 0 || d->num_tokens < 0) return roll::fail(ROLL_ERR_INVALID_ARG, "num_chunks and num_tokens must be >= 0");
     if (d->num_q_heads <= 0 || d->num_kv_heads <= 0 || d->num_q_heads % d->num_kv_heads != 0)
         return roll::fail(ROLL_ERR_INVALID_ARG, "num_q_heads must be a positive multiple of num_kv_heads");
-    if (d->num_q_heads / d->num_kv_heads > 16)
-        return roll::fail(ROLL_ERR_INVALID_ARG, "GQA group size above 16 is not supported");
     if (d->head_dim != 64 && d->head_dim != 128) return roll::fail(ROLL_ERR_INVALID_ARG, "head_dim must be 64 or 128");
     if (d->page_size != 16 && d->page_size != 32 && d->page_size != 64)
         return roll::fail(ROLL_ERR_INVALID_ARG, "page_size must be 16, 32 or 64");
@@ -909,59 +907,46 @@ extern "C" int roll_prefill_attn(const void* q, const void* k_new, const void* v
         (uint4*)v_pages, page_table, prm, d->head_dim, (int32_t)k_blocks);
     ROLL_HIP_CHECK(hipGetLastError());
 
-    // Groups of up to 8 query heads keep two column tiles (32 query tokens) per wave; larger
-    // groups have half the register budget per wave and keep one.
-    const int qt = prm.G <= 8 ? 2 : 1;
+    constexpr int qt = 2;   // column tiles (16 query tokens) per wave
     // How many units (span of query tokens x query head) a workgroup takes, one per computing wave.
     // A compute unit holds one workgroup of 8 waves; what it gets done depends on how many of
     // them compute (measured on 8 x 4096 tokens with 1 .. 8 query heads per KV head and one span
     // per workgroup, relative to one wave; 7 waves and a copying one beat 8 that share the
     // copying).  The number is the one for which (workgroups, at most one per compute unit) x
     // (that yield) is largest: a small launch is better off with more, lighter workgroups.
-    // Groups above 8 heads run workgroups of G waves, one span each.
     const int span = kTile * qt;
     const int64_t spans_bound = ((int64_t)prm.T + span - 1) / span + prm.C;   // each chunk ends with at most one partial span
     auto workgroups = [&](int units) { return ((spans_bound * prm.G + units - 1) / units + prm.C) * prm.Hkv; };
-    prm.U = prm.G;
-    if (prm.G <= 8) {
-        static const double kYieldPipelined[9] = {0.0, 1.0, 2.0, 2.63, 3.4, 3.54, 4.18, 4.6, 4.44};
-        if (t_units >= 1) {
-            prm.U = t_units;
-        } else {
-            double best = 0.0;
-            for (int units = 1; units <= 8; ++units) {
-                const int64_t wgs = workgroups(units);
-                const double yield = prm.out_f32 ? (units <= 4 ? (double)units : 4.0 + 0.15 * (units - 4)) : kYieldPipelined[units];
-                const double score = (double)(wgs < kComputeUnits ? wgs : kComputeUnits) * yield;
-                if (score > best) {
-                    best = score;
-                    prm.U = units;
-                }
+    static const double kYieldPipelined[9] = {0.0, 1.0, 2.0, 2.63, 3.4, 3.54, 4.18, 4.6, 4.44};
+    prm.U = 1;
+    if (t_units >= 1) {
+        prm.U = t_units;
+    } else {
+        double best = 0.0;
+        for (int units = 1; units <= kCopyWaves; ++units) {
+            const int64_t wgs = workgroups(units);
+            const double yield = prm.out_f32 ? (units <= 4 ? (double)units : 4.0 + 0.15 * (units - 4)) : kYieldPipelined[units];
+            const double score = (double)(wgs < kComputeUnits ? wgs : kComputeUnits) * yield;
+            if (score > best) {
+                best = score;
+                prm.U = units;
             }
         }
     }
     // At most this many workgroups: every chunk's last one may be partly empty.
     const int64_t grid = workgroups(prm.U);
     if (grid > INT32_MAX) return roll::fail(ROLL_ERR_INVALID_ARG, "too many query blocks");
-    const int threads = 64 * (prm.G > kCopyWaves ? prm.G : kCopyWaves);
+    const int threads = kCopyThreads;   // 8 waves
     if (t_ev_begin) ROLL_HIP_CHECK(hipEventRecord(t_ev_begin, stream));
-#define ROLL_LAUNCH_PREFILL(DIM, MAXW, QT, F32)                                                                \
-    prefill_attn<DIM, MAXW, QT, F32><<<(unsigned)grid, threads, 0, stream>>>( \
+#define ROLL_LAUNCH_PREFILL(DIM, F32)                                                                         \
+    prefill_attn<DIM, qt, F32><<<(unsigned)grid, threads, 0, stream>>>(                                       \
         (const uint4*)q, (const uint4*)k_pages, (const uint4*)v_pages, page_table, chunk_slot, chunk_start,    \
         chunk_offset, out, prm)
-#define ROLL_LAUNCH_PREFILL_DIM(DIM)                                   \
-    do {                                                               \
-        if (prm.G <= 8) {                                              \
-            if (prm.out_f32) ROLL_LAUNCH_PREFILL(DIM, 8, 2, true);     \
-            else ROLL_LAUNCH_PREFILL(DIM, 8, 2, false);                \
-        } else {                                                       \
-            if (prm.out_f32) ROLL_LAUNCH_PREFILL(DIM, 16, 1, true);    \
-            else ROLL_LAUNCH_PREFILL(DIM, 16, 1, false);               \
-        }                                                              \
-    } while (0)
-    if (d->head_dim == 128) ROLL_LAUNCH_PREFILL_DIM(128);
-    else ROLL_LAUNCH_PREFILL_DIM(64);
-#undef ROLL_LAUNCH_PREFILL_DIM
+    if (d->head_dim == 128) {
+        if (prm.out_f32) ROLL_LAUNCH_PREFILL(128, true); else ROLL_LAUNCH_PREFILL(128, false);
+    } else {
+        if (prm.out_f32) ROLL_LAUNCH_PREFILL(64, true); else ROLL_LAUNCH_PREFILL(64, false);
+    }
 #undef ROLL_LAUNCH_PREFILL
     ROLL_HIP_CHECK(hipGetLastError());
     if (t_ev_end) ROLL_HIP_CHECK(hipEventRecord(t_ev_end, stream));

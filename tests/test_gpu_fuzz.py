@@ -102,7 +102,7 @@ def test_prefill_random_cases():
     rng = np.random.default_rng(303 + SEED)
     worst = 0.0
     for case in range(12 * ROUNDS):
-        Hq, Hkv = HEADS[rng.integers(0, len(HEADS))]
+        Hq, Hkv = (HEADS + [(24, 1), (40, 2), (9, 1)])[rng.integers(0, len(HEADS) + 3)]   # prefill takes any group size
         D = int(rng.choice([64, 128]))
         P = int(rng.choice([16, 32, 64]))
         n_slots = int(rng.integers(1, 7))

@@ -200,6 +200,22 @@ def test_prefill_units_per_workgroup(Hq, Hkv, D, P, units):
         rb.roll_prof_prefill_units(0)
 
 
+@pytest.mark.parametrize("Hq,Hkv,D,P", [(12, 1, 128, 16), (32, 2, 64, 32), (32, 1, 128, 64), (64, 1, 64, 16), (18, 2, 128, 16)])
+def test_prefill_large_head_groups(Hq, Hkv, D, P):
+    """More query heads per KV head than a workgroup has waves (9, 12, 16, 32, 64): the heads of a
+    span are spread over several workgroups.  Whole prompts and chunks on a cache, both result
+    types; the number of units per workgroup as the launch chooses it and fixed at 7 and 8."""
+    chunks = [(0, 0, 70), (1, 0, 33), (2, 9, 40), (0, 70, 31)]
+    for units in (0, 7, 8):
+        rb.roll_prof_prefill_units(units)
+        try:
+            for out_dtype, tol in ((torch.bfloat16, 2e-2), (torch.float32, 1e-4)):
+                err = _run_case(Hq, Hkv, D, P, chunks, 90 + Hq, out_dtype=out_dtype, num_slots=3)
+                assert err <= tol, (units, out_dtype, err)
+        finally:
+            rb.roll_prof_prefill_units(0)
+
+
 def test_prefill_units_are_checked():
     with pytest.raises(rb.RollError):
         rb.roll_prof_prefill_units(9)
