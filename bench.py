@@ -311,6 +311,61 @@ def prefill_bench(args, torch, rb, wl):
                       "per_workload": res})
 
 
+def prefill_groups_bench(args, torch, rb, wl):
+    """roll_prefill_attn across numbers of query heads per KV head (4 KV heads, head_dim 128, 16-token
+    pages, bf16 result, 8 prompts in one call): TFLOP/s with the units per workgroup as the launch
+    chooses them, and with one span and all its heads per workgroup (up to 8 heads per KV head)."""
+    D, P, Hkv, n_slots = 128, 16, 4, 8
+    out = {}
+    for n in (4096, 512):
+        max_pages = n // P
+        num_pages = n_slots * max_pages + 8
+        page_table = torch.empty((n_slots, max_pages), dtype=torch.int32, device="cuda")
+        seq_lens = torch.zeros((n_slots,), dtype=torch.int32, device="cuda")
+        pool = rb.KvPool(num_pages, P, n_slots, max_pages, page_table, seq_lens)
+        for s_ in range(n_slots):
+            rb.roll_kv_alloc(pool, s_, n)
+        rb.roll_kv_commit(pool)
+        k_pages, v_pages = rb.new_kv_pools(num_pages, Hkv, D, P, fill=0)
+        T = n_slots * n
+        k = wl.randn_bf16((T, Hkv, D), args.seed, 41, "cuda")
+        v = wl.randn_bf16((T, Hkv, D), args.seed, 42, "cuda")
+        slot = torch.arange(n_slots, dtype=torch.int32, device="cuda")
+        start = torch.zeros(n_slots, dtype=torch.int32, device="cuda")
+        off = torch.arange(n_slots + 1, dtype=torch.int32, device="cuda") * n
+        pairs = n_slots * n * (n + 1) // 2
+        rows = {}
+        for G in (7, 1, 2, 3, 4, 5, 6, 7, 8, 9, 12, 16):      # (the first one warms the clocks and is measured again)
+            Hq = G * Hkv
+            q = wl.randn_bf16((T, Hq, D), args.seed, 40, "cuda")
+            res = torch.empty((T, Hq, D), dtype=torch.bfloat16, device="cuda")
+            row = {}
+            for label, units in (("one_span_per_workgroup", G if G <= 8 else None), ("chosen_by_the_launch", 0)):
+                if units is None:
+                    continue
+                rb.roll_prof_prefill_units(units)
+                for _ in range(args.warmup):
+                    rb.roll_prefill_attn(q, k, v, slot, start, off, k_pages, v_pages, page_table, res, P)
+                e0, e1 = rb.ProfEvent(), rb.ProfEvent()
+                torch.cuda.synchronize()
+                e0.record()
+                for _ in range(args.steps):
+                    rb.roll_prefill_attn(q, k, v, slot, start, off, k_pages, v_pages, page_table, res, P)
+                e1.record()
+                torch.cuda.synchronize()
+                rb.roll_prof_prefill_units(0)
+                ms = e0.elapsed_ms(e1) / args.steps
+                row[label] = {"ms": ms, "TFLOPs": 4.0 * D * Hq * pairs / (ms * 1e-3) / 1e12}
+            rows[f"G={G}"] = row
+            del q, res
+        out[f"8x{n}"] = rows
+        pool.close()
+    print(json.dumps({"metric": "prefill TFLOP/s by query heads per KV head (K/V writer included)", "unit": "TFLOP/s",
+                      "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": f"8 prompts in one call, Hkv={Hkv} D={D} P={P}, Hq = G x Hkv"},
+                      "per_workload": out}), flush=True)
+
+
 def prefill_timeline_bench(args, torch, rb, wl):
     """A prefill workgroup's life: needs the library built with
     `python -m paper_2510_11345_amd.build --timeline`, whose kernel stamps the 100 MHz clock per
@@ -607,6 +662,9 @@ def main():
     ap.add_argument("--dense-pools", action="store_true",
                     help="K and V in two dense allocations and pages handed out one by one, instead of one "
                          "allocation with the K and V block of a page side by side and pages in runs of 32 / P")
+    ap.add_argument("--prefill-groups", action="store_true",
+                    help="prefill attention across numbers of query heads per KV head, units per workgroup chosen "
+                         "by the launch against one span per workgroup")
     ap.add_argument("--prefill-timeline", action="store_true",
                     help="per-workgroup timestamps of the prefill attention launch on three prompt shapes; needs "
                          "the library built with `python -m paper_2510_11345_amd.build --timeline`")
@@ -649,6 +707,9 @@ def main():
         return
     if args.prefill_timeline:
         prefill_timeline_bench(args, torch, rb, wl)
+        return
+    if args.prefill_groups:
+        prefill_groups_bench(args, torch, rb, wl)
         return
     if args.attn_timeline:
         args.config = args.config or "c4"
