@@ -87,7 +87,7 @@ __device__ __forceinline__ int32_t chunk_of_token(const int32_t* __restrict__ ch
 
 // Writes the chunk tokens' K and V into the pages.  Tokens whose slot, position or page is out
 // of range are skipped.  The first k_blocks workgroups write K: one thread per (token, KV head,
-// 8 head-dim elements), a 16-byte store each.  The others write V, whose layout keeps 8
+// 8 head-dim elements), a 16-byte store each, a wave taking 16 tokens x 4 pieces.  The others write V, whose layout keeps 8
 // consecutive positions of one head-dim element together: one wave per (octet of positions of
 // a chunk, KV head) gathers the (up to) 8 tokens' elements row by row and stores 16 bytes per
 // head-dim element; an octet that the chunk covers only in part is written element by element
@@ -99,16 +99,23 @@ __global__ __launch_bounds__(256) void append_chunks(
     int32_t k_blocks) {
     const int32_t P = 1 << prm.log2P;
     if ((int32_t)blockIdx.x < k_blocks) {
-        const int32_t d8n = D / 8, per_tok = prm.Hkv * d8n;
-        const int64_t item = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-        if (item >= (int64_t)prm.T * per_tok) return;
-        const int32_t t = (int32_t)(item / per_tok), rem = (int32_t)(item - (int64_t)t * per_tok);
+        // A wave takes 16 consecutive tokens x 4 consecutive pieces of a head: its loads are 16 runs of
+        // 64 bytes, its stores (a page keeps the tokens of a piece side by side) 4 runs of 256 bytes
+        // where the tokens share a page, instead of 64 pieces of 16 bytes in 64 different lines.
+        const int32_t d8n = D / 8, per_tok = prm.Hkv * d8n, per_tok4 = per_tok >> 2;
+        const int64_t group = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+        const int32_t lane = threadIdx.x & 63;
+        const int64_t t16 = group / per_tok4;
+        const int32_t t = (int32_t)(t16 * 16 + (lane >> 2)), rem = (int32_t)(group - t16 * per_tok4) * 4 + (lane & 3);
+        if (t >= prm.T) return;
+        const int64_t item = (int64_t)t * per_tok + rem;
+        const uint4 piece = k_new[item];   // asked for before the lookups below, not after them
         const int32_t c = chunk_of_token(chunk_offset, prm.C, t);
         const int32_t slot = chunk_slot[c], pos = chunk_start[c] + (t - chunk_offset[c]);
         if (slot < 0 || slot >= prm.num_slots || pos < 0 || (pos >> prm.log2P) >= prm.max_pages) return;
         const int32_t page = page_table[(int64_t)slot * prm.max_pages + (pos >> prm.log2P)];
         if (page < 0 || page >= prm.num_pages) return;
-        k_pages[(((int64_t)page * prm.Hs + rem / d8n) * d8n + rem % d8n) * P + roll::k_slot(pos & (P - 1), P)] = k_new[item];
+        k_pages[(((int64_t)page * prm.Hs + rem / d8n) * d8n + rem % d8n) * P + roll::k_slot(pos & (P - 1), P)] = piece;
         return;
     }
     // V: which (chunk, octet of it) is this wave's?  Octets are numbered chunk after chunk; the
@@ -148,17 +155,22 @@ __global__ __launch_bounds__(256) void append_chunks(
     if (slot < 0 || slot >= prm.num_slots || (pos0 >> prm.log2P) >= prm.max_pages) return;
     const int32_t page = page_table[(int64_t)slot * prm.max_pages + (pos0 >> prm.log2P)];
     if (page < 0 || page >= prm.num_pages) return;
-    uint32_t w[4] = {0u, 0u, 0u, 0u};
-    for (int32_t pos = lo; pos < hi; ++pos) {
-        const int64_t t = (int64_t)chunk_offset[c] + (pos - start);
-        const uint32_t val = v_new[(t * prm.Hkv + h) * D + d];
-        const int32_t j = pos - pos0;
-        w[j >> 1] |= val << ((j & 1) * 16);
-    }
     uint4* dst = v_pages + (((int64_t)page * prm.Hs + h) * (P / 8) + ((pos0 & (P - 1)) >> 3)) * D + d;
-    if (hi - lo == 8) {
-        *dst = make_uint4(w[0], w[1], w[2], w[3]);
+    const int64_t t_lo = (int64_t)chunk_offset[c] + (lo - start);   // the token at position lo
+    if (hi - lo == 8) {   // a whole octet: the eight loads go out together
+        const uint16_t* src = v_new + (t_lo * prm.Hkv + h) * D + d;
+        const int64_t per_token = (int64_t)prm.Hkv * D;
+        uint32_t val[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) val[j] = src[j * per_token];
+        *dst = make_uint4(val[0] | (val[1] << 16), val[2] | (val[3] << 16), val[4] | (val[5] << 16), val[6] | (val[7] << 16));
     } else {
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+        for (int32_t pos = lo; pos < hi; ++pos) {
+            const uint32_t val = v_new[((t_lo + (pos - lo)) * prm.Hkv + h) * D + d];
+            const int32_t j = pos - pos0;
+            w[j >> 1] |= val << ((j & 1) * 16);
+        }
         uint16_t* dst16 = (uint16_t*)dst;
         for (int32_t pos = lo; pos < hi; ++pos) {
             const int32_t j = pos - pos0;
@@ -895,7 +907,7 @@ extern "C" int roll_prefill_attn(const void* q, const void* k_new, const void* v
     const float scale = d->softmax_scale > 0.f ? d->softmax_scale : 1.0f / sqrtf((float)d->head_dim);
     prm.scale_log2e = scale * 1.44269504088896340736f;
 
-    const int64_t k_items = (int64_t)prm.T * prm.Hkv * (d->head_dim / 8);
+    const int64_t k_items = (((int64_t)prm.T + 15) / 16 * 16) * prm.Hkv * (d->head_dim / 8);   // tokens in sixteens
     const int64_t k_blocks = (k_items + 255) / 256;
     // at most T / 8 + 2 C octets of positions (a chunk may begin and end inside one); one wave per
     // octet, KV head and 64 head-dim elements, four waves per workgroup
